@@ -1,0 +1,139 @@
+"""fp64 CPU oracle for the FFT-convolution path -- TEST INFRASTRUCTURE ONLY.
+
+Thin numpy front end of ``conv_oracle.c`` (plain C, term-by-term sums in
+double precision; see that file's header for the definitions it follows:
+paper Section 2.1 for the convolution, Eq. 1 for its circular form, Section
+3.3 / Appendix A.4 for partial and frequency-sparse filters).
+
+Nothing in the product package may import this module; it shares no code with
+the HIP library.  Allowed callers: ``tests/``, ``__graft_entry__.smoke()`` and
+the ``cpu_baseline`` leg of ``bench.py``.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "conv_oracle.c")
+_SO = os.path.join(_HERE, "libconv_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile conv_oracle.c with gcc into libconv_oracle.so next to it."""
+    if force or not os.path.exists(_SO) or os.path.getmtime(_SO) < os.path.getmtime(_SRC):
+        tmp = _SO + ".tmp%d" % os.getpid()
+        subprocess.check_call(
+            ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-Wall", "-o", tmp, _SRC, "-lm"]
+        )
+        os.replace(tmp, _SO)
+    return _SO
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        p = ctypes.c_void_p
+        i64 = ctypes.c_int64
+        lib.oracle_fftconv.argtypes = [p, p, p, i64, i64, i64, i64]
+        lib.oracle_fftconv.restype = ctypes.c_int
+        lib.oracle_fftconv_at.argtypes = [p, p, p, p, i64, i64, i64, i64]
+        lib.oracle_fftconv_at.restype = ctypes.c_int
+        lib.oracle_mask_filter.argtypes = [p, p, p, i64, i64]
+        lib.oracle_mask_filter.restype = ctypes.c_int
+        lib.oracle_num_threads.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def _f64(a):
+    return np.ascontiguousarray(np.asarray(a, dtype=np.float64))
+
+
+def extend_filter(k, M: int) -> np.ndarray:
+    """Lay a filter k of shape (H, Nk), Nk <= M, out on M taps (zeros after Nk)."""
+    k = _f64(k)
+    if k.ndim != 2 or k.shape[1] > M:
+        raise ValueError("k must be (H, Nk) with Nk <= M")
+    out = np.zeros((k.shape[0], M), dtype=np.float64)
+    out[:, : k.shape[1]] = k
+    return out
+
+
+def fftconv(u, kext, M: int | None = None) -> np.ndarray:
+    """y[b,h,i] = sum_j u[b,h,j] * kext[h,(i-j) mod M] for 0 <= i < N.
+
+    u: (B,H,N); kext: (H,M) -- or (H,Nk) with M given, zero-extended here.
+    """
+    u = _f64(u)
+    kext = _f64(kext)
+    if M is not None and kext.shape[1] != M:
+        kext = extend_filter(kext, M)
+    B, H, N = u.shape
+    if kext.shape[0] != H:
+        raise ValueError("filter rows must equal H")
+    M = kext.shape[1]
+    y = np.empty_like(u)
+    rc = _load().oracle_fftconv(u.ctypes.data, kext.ctypes.data, y.ctypes.data, B, H, N, M)
+    if rc != 0:
+        raise ValueError("oracle_fftconv rejected sizes B=%d H=%d N=%d M=%d" % (B, H, N, M))
+    return y
+
+
+def fftconv_at(u_rows, kext_rows, idx) -> np.ndarray:
+    """The same sum at chosen output positions.
+
+    u_rows: (S,N) sequences; kext_rows: (S,M) the filter row of each sequence;
+    idx: (S,P) int positions in [0,N).  Returns (S,P).
+    """
+    u_rows = _f64(u_rows)
+    kext_rows = _f64(kext_rows)
+    idx = np.ascontiguousarray(np.asarray(idx, dtype=np.int64))
+    S, N = u_rows.shape
+    if kext_rows.shape[0] != S or idx.shape[0] != S:
+        raise ValueError("row counts differ")
+    M = kext_rows.shape[1]
+    P = idx.shape[1]
+    out = np.empty((S, P), dtype=np.float64)
+    rc = _load().oracle_fftconv_at(
+        u_rows.ctypes.data, kext_rows.ctypes.data, idx.ctypes.data, out.ctypes.data, S, N, M, P
+    )
+    if rc != 0:
+        raise ValueError("oracle_fftconv_at rejected its arguments")
+    return out
+
+
+def mask_filter(kext, keep) -> np.ndarray:
+    """Time-domain filter of the spectrum DFT_M(kext) with bins keep[f]==0 zeroed.
+
+    kext: (H,M) real; keep: (M,) of 0/1 indexed by natural frequency f.
+    Returns Re(IDFT(keep * DFT(kext))), shape (H,M), by naive O(M^2) sums.
+    """
+    kext = _f64(kext)
+    keep = np.ascontiguousarray(np.asarray(keep, dtype=np.uint8))
+    H, M = kext.shape
+    if keep.shape != (M,):
+        raise ValueError("keep must have one entry per frequency bin")
+    out = np.empty_like(kext)
+    rc = _load().oracle_mask_filter(kext.ctypes.data, keep.ctypes.data, out.ctypes.data, H, M)
+    if rc != 0:
+        raise RuntimeError("oracle_mask_filter failed (%d)" % rc)
+    return out
+
+
+def num_threads() -> int:
+    return int(_load().oracle_num_threads())
+
+
+def rel_l2_per_sequence(y, y_ref) -> np.ndarray:
+    """||y - y_ref||_2 / ||y_ref||_2 over the last axis (the parity metric)."""
+    y = np.asarray(y, dtype=np.float64)
+    y_ref = np.asarray(y_ref, dtype=np.float64)
+    num = np.sqrt(((y - y_ref) ** 2).sum(axis=-1))
+    den = np.sqrt((y_ref ** 2).sum(axis=-1))
+    return num / np.where(den > 0, den, 1.0)

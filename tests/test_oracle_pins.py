@@ -1,0 +1,215 @@
+"""Pins of the CPU oracle against things it shares no code with.
+
+The paper prints no worked numeric example of a convolution, so the pins are:
+Eq. 1 evaluated with dense DFT matrices on tiny inputs, closed forms, exact
+integer polynomial products, invariants and library routines (numpy.convolve,
+numpy.fft), chosen so that a dropped term, a wrong sign or index, a wrong
+stride or a transposed operand fails at least one of them.
+"""
+import numpy as np
+import pytest
+
+import oracle
+
+RNG = np.random.default_rng(12345)
+
+
+def dft_matrix(M, sign=-1):
+    j = np.arange(M)
+    return np.exp(sign * 2j * np.pi * np.outer(j, j) / M)
+
+
+def eq1_dense(u, kext):
+    """Eq. 1 literally: F^-1 (F u_pad . F k) with dense M x M DFT matrices."""
+    B, H, N = u.shape
+    M = kext.shape[1]
+    F = dft_matrix(M, -1)
+    Fi = dft_matrix(M, +1) / M
+    up = np.zeros((B, H, M))
+    up[..., :N] = u
+    Uf = up @ F.T
+    Kf = kext @ F.T
+    y = (Uf * Kf[None]) @ Fi.T
+    assert np.abs(y.imag).max() < 1e-9
+    return y.real[..., :N]
+
+
+@pytest.mark.parametrize("N,M", [(1, 1), (5, 5), (8, 8), (8, 16), (7, 16), (16, 32), (32, 64), (24, 37), (64, 64)])
+def test_matches_eq1_with_dense_dft(N, M):
+    B, H = 3, 2
+    u = RNG.standard_normal((B, H, N))
+    kext = RNG.standard_normal((H, M))          # full-length filter: exercises the wrap-around taps
+    y = oracle.fftconv(u, kext)
+    assert np.allclose(y, eq1_dense(u, kext), rtol=0, atol=1e-11)
+
+
+@pytest.mark.parametrize("N", [1, 2, 17, 64, 300])
+def test_causal_equals_numpy_convolve(N):
+    B, H = 2, 3
+    u = RNG.standard_normal((B, H, N))
+    k = RNG.standard_normal((H, N))
+    y = oracle.fftconv(u, k, M=2 * N)
+    for b in range(B):
+        for h in range(H):
+            assert np.allclose(y[b, h], np.convolve(u[b, h], k[h])[:N], rtol=0, atol=1e-12)
+
+
+def test_integer_inputs_give_exact_polynomial_product():
+    B, H, N = 2, 2, 50
+    u = RNG.integers(-9, 10, size=(B, H, N))
+    k = RNG.integers(-9, 10, size=(H, N))
+    y = oracle.fftconv(u.astype(float), k.astype(float), M=2 * N)
+    for b in range(B):
+        for h in range(H):
+            prod = np.polymul(u[b, h][::-1], k[h][::-1])[::-1]      # exact int64 coefficients
+            assert np.array_equal(y[b, h], prod[:N].astype(float))
+
+
+def test_delta_and_shifted_delta():
+    N, M = 40, 80
+    u = RNG.standard_normal((2, 1, N))
+    k = np.zeros((1, N))
+    k[0, 0] = 1.0
+    assert np.array_equal(oracle.fftconv(u, k, M=M), u)
+    for s in (1, 7, 39):
+        k = np.zeros((1, N))
+        k[0, s] = 1.0
+        y = oracle.fftconv(u, k, M=M)
+        assert np.array_equal(y[..., :s], np.zeros_like(y[..., :s]))
+        assert np.array_equal(y[..., s:], u[..., : N - s])
+
+
+def test_circular_wraps_when_fft_size_equals_n():
+    N = 16
+    u = RNG.standard_normal((1, 1, N))
+    for s in (1, 5, 15):
+        k = np.zeros((1, N))
+        k[0, s] = 1.0
+        y = oracle.fftconv(u, k)                      # M = N: circular
+        assert np.array_equal(y[0, 0], np.roll(u[0, 0], s))
+
+
+def test_closed_forms():
+    N = 64
+    ones = np.ones((1, 1, N))
+    y = oracle.fftconv(ones, np.ones((1, N)), M=2 * N)
+    assert np.array_equal(y[0, 0], np.arange(1, N + 1, dtype=float))
+    r = 0.9
+    k = r ** np.arange(N)
+    y = oracle.fftconv(ones, k[None], M=2 * N)
+    assert np.allclose(y[0, 0], (1 - r ** np.arange(1, N + 1)) / (1 - r), rtol=1e-13)
+
+
+def test_linearity_and_shift_equivariance():
+    B, H, N = 2, 2, 33
+    u1, u2 = RNG.standard_normal((2, B, H, N))
+    k1, k2 = RNG.standard_normal((2, H, N))
+    a, c = 1.7, -0.3
+    f = lambda u, k: oracle.fftconv(u, k, M=2 * N)
+    assert np.allclose(f(a * u1 + c * u2, k1), a * f(u1, k1) + c * f(u2, k1), atol=1e-12)
+    assert np.allclose(f(u1, a * k1 + c * k2), a * f(u1, k1) + c * f(u1, k2), atol=1e-12)
+    s = 5
+    us = np.zeros_like(u1)
+    us[..., s:] = u1[..., : N - s]
+    ys = f(us, k1)
+    assert np.allclose(ys[..., s:], f(u1, k1)[..., : N - s], atol=1e-12)
+    assert np.array_equal(ys[..., :s], np.zeros_like(ys[..., :s]))
+
+
+def test_filter_row_belongs_to_channel_not_batch():
+    # B != H and distinct filters: a swapped (b,h) stride or a filter indexed by b fails here.
+    B, H, N = 3, 5, 12
+    u = RNG.standard_normal((B, H, N))
+    k = RNG.standard_normal((H, N))
+    y = oracle.fftconv(u, k, M=32)
+    for b in range(B):
+        for h in range(H):
+            assert np.allclose(y[b, h], np.convolve(u[b, h], k[h])[:N], atol=1e-12)
+
+
+def test_partial_filter_is_a_sliding_window():
+    # Section 3.3: a filter whose later taps are zero only sees the last Nk inputs.
+    N, Nk = 96, 8
+    u = RNG.standard_normal((1, 1, N))
+    k = np.zeros((1, N))
+    k[0, :Nk] = RNG.standard_normal(Nk)
+    y = oracle.fftconv(u, k, M=2 * N)
+    y_short = oracle.fftconv(u, k[:, :Nk], M=2 * N)
+    assert np.array_equal(y, y_short)
+    u2 = u.copy()
+    u2[..., :40] += 100.0
+    y2 = oracle.fftconv(u2, k, M=2 * N)
+    assert np.array_equal(y2[..., 40 + Nk - 1:], y[..., 40 + Nk - 1:])
+    # overlap-add with blocks of length Nk reproduces it
+    acc = np.zeros(N + 2 * Nk)
+    for c in range(N // Nk):
+        blk = u[0, 0, c * Nk:(c + 1) * Nk]
+        acc[c * Nk:c * Nk + 2 * Nk - 1] += np.convolve(blk, k[0, :Nk])
+    assert np.allclose(acc[:N], y[0, 0], atol=1e-12)
+
+
+def test_sampled_positions_equal_full_and_direct_dot():
+    S, N, M = 3, 200, 512
+    u = RNG.standard_normal((S, N))
+    kext = np.zeros((S, M))
+    kext[:, :N] = RNG.standard_normal((S, N))
+    idx = np.stack([RNG.integers(0, N, size=9) for _ in range(S)])
+    idx[0, 0], idx[0, 1] = 0, N - 1
+    out = oracle.fftconv_at(u, kext, idx)
+    for s in range(S):
+        full = oracle.fftconv(u[s][None, None], kext[s][None])[0, 0]
+        assert np.array_equal(out[s], full[idx[s]])
+        for p, i in enumerate(idx[s]):
+            assert np.isclose(out[s, p], np.dot(u[s, : i + 1], kext[s, i::-1][: i + 1]), atol=1e-12)
+    with pytest.raises(ValueError):
+        oracle.fftconv_at(u, kext, np.full((S, 1), N))
+
+
+def test_mask_filter_identity_and_library_crosscheck():
+    H, M = 2, 64
+    kext = RNG.standard_normal((H, M))
+    assert np.allclose(oracle.mask_filter(kext, np.ones(M)), kext, atol=1e-12)
+    assert np.allclose(oracle.mask_filter(kext, np.zeros(M)), 0.0, atol=0)
+    keep = (RNG.random(M) < 0.4).astype(np.uint8)             # not Hermitian-symmetric on purpose
+    ref = np.fft.ifft(np.fft.fft(kext, axis=1) * keep[None], axis=1).real
+    assert np.allclose(oracle.mask_filter(kext, keep), ref, atol=1e-12)
+
+
+def test_mask_filter_closed_forms_fix_signs_and_scale():
+    M, f0 = 32, 3
+    t = np.arange(M)
+    delta0 = np.zeros((1, M))
+    delta0[0, 0] = 1.0
+    keep = np.zeros(M)
+    keep[[f0, M - f0]] = 1
+    assert np.allclose(oracle.mask_filter(delta0, keep)[0], 2.0 / M * np.cos(2 * np.pi * f0 * t / M), atol=1e-14)
+    # one non-symmetric bin of a delta at t=1: forward sign -, inverse sign +  =>  cos(2 pi f0 (t-1)/M)/M
+    delta1 = np.zeros((1, M))
+    delta1[0, 1] = 1.0
+    keep = np.zeros(M)
+    keep[f0] = 1
+    assert np.allclose(oracle.mask_filter(delta1, keep)[0], np.cos(2 * np.pi * f0 * (t - 1) / M) / M, atol=1e-14)
+
+
+def test_mask_filter_parseval_for_symmetric_mask():
+    M = 128
+    kext = RNG.standard_normal((1, M))
+    keep = np.zeros(M, dtype=np.uint8)
+    keep[:20] = 1
+    keep[M - 19:] = 1                                           # f and M-f kept together
+    kt = oracle.mask_filter(kext, keep)
+    K = dft_matrix(M) @ kext[0]
+    assert np.isclose((kt ** 2).sum(), (np.abs(K) ** 2 * keep).sum() / M, rtol=1e-12)
+
+
+def test_bad_sizes_are_rejected():
+    with pytest.raises(ValueError):
+        oracle.fftconv(np.zeros((1, 1, 8)), np.zeros((1, 4)))        # M < N
+    with pytest.raises(ValueError):
+        oracle.fftconv(np.zeros((1, 2, 8)), np.zeros((3, 16)))       # filter rows != H
+
+
+def test_rel_l2_metric():
+    y = np.array([[3.0, 4.0], [0.0, 0.0]])
+    r = np.array([[3.0, 0.0], [0.0, 0.0]])
+    assert np.allclose(oracle.rel_l2_per_sequence(y, r), [4.0 / 3.0, 0.0])
