@@ -1,0 +1,137 @@
+/*
+ * fftconv.h -- C ABI of the MI355X (gfx950) long FFT-convolution library.
+ *
+ * The operation (paper Section 2.1, Eq. 1; problem statement of Algorithm 1):
+ * for every batch row b and channel h, independently,
+ *
+ *     y[b,h,:] = iFFT( FFT(zero-pad(u[b,h,:])) . k_f[h,:] )[0:N],
+ *     k_f[h,:] = FFT(zero-pad(k[h,:])),
+ *
+ * with transforms of length fft_size.  The result is the circular convolution
+ * of u and k modulo fft_size, truncated to N outputs; it equals the causal
+ * convolution sum_{j<=i} u[j] k[i-j] whenever N + Nk - 1 <= fft_size.  k is
+ * shared over the batch, so k_f is computed once per filter and reused
+ * (Section 1).  The transforms are evaluated as chains of small DFT-matrix
+ * products with twiddle scaling in between (order-p decomposition, Section
+ * 2.1 and Algorithms 1, 3, 4); which factorisation is used is the plan's
+ * business and never visible in the results.
+ *
+ * Conventions
+ *  - Every pointer named u, k, k_f, y, workspace is DEVICE memory on the
+ *    device that was current when the plan was created; the caller owns and
+ *    frees it.  block_keep is HOST memory.
+ *  - u and y are contiguous row-major (B, H, N) in the plan's I/O dtype;
+ *    k is contiguous row-major (H, Nk) fp32.
+ *  - k_f is an opaque buffer of fftconv_kf_bytes() bytes: spectrum in the
+ *    plan's internal (permuted) order, pre-scaled by 1/fft_size.  It is only
+ *    valid with the plan that produced it (or a plan created with identical
+ *    arguments).
+ *  - All *_filter_fft* and *_forward* calls are asynchronous on `stream`
+ *    (a hipStream_t passed as void*, NULL = the default stream).  They do not
+ *    allocate and do not synchronise.
+ *  - Every call returns FFTCONV_OK (0) or a negative error code; on error no
+ *    kernel has been launched by that call.  fftconv_last_error() returns a
+ *    thread-local description of the most recent failure on this thread.
+ *  - Arithmetic: 16-bit I/O plans multiply bf16/fp16 operands on the matrix
+ *    cores with fp32 accumulation; fp32 I/O plans compute in fp32.  All
+ *    16-bit roundings are round-to-nearest-even.
+ */
+#ifndef FFTCONV_H
+#define FFTCONV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct fftconv_plan fftconv_plan; /* opaque */
+
+enum { FFTCONV_F32 = 0, FFTCONV_F16 = 1, FFTCONV_BF16 = 2 }; /* I/O dtype of u and y */
+
+enum {
+    FFTCONV_OK = 0,
+    FFTCONV_EINVAL = -1,       /* bad argument (size, NULL pointer, mismatch with the plan) */
+    FFTCONV_EUNSUPPORTED = -2, /* valid request this build has no kernel for */
+    FFTCONV_EHIP = -3,         /* a HIP runtime call failed */
+    FFTCONV_ENOMEM = -4,       /* host or device allocation failed */
+    FFTCONV_ENODEV = -5        /* no usable GPU */
+};
+
+/* Create a plan for sequences of length N, transform length fft_size, H
+ * channels and the given I/O dtype (Section 3.1; the paper's range of
+ * transform lengths, 256 .. 4M, Section 1).
+ *   N >= 1; fft_size a power of two in [256, 2^22]; N <= fft_size; H >= 1.
+ * Builds the DFT matrices and twiddle tables in fp64 on the host, uploads
+ * them, chooses the factorisation and allocates the plan's private scratch.
+ * Arguments are validated before any device is touched. */
+int fftconv_plan_create(fftconv_plan **out, int64_t N, int64_t fft_size, int64_t H, int dtype);
+
+/* Free the plan and everything it owns.  NULL is accepted. */
+int fftconv_plan_destroy(fftconv_plan *plan);
+
+/* Bytes of the opaque k_f buffer for the plan's H channels. */
+size_t fftconv_kf_bytes(const fftconv_plan *plan);
+
+/* Bytes of caller-provided workspace fftconv_forward* needs for batch size B
+ * (0 when the whole transform is fused on chip). */
+size_t fftconv_workspace_bytes(const fftconv_plan *plan, int64_t B);
+
+/* k_f = FFT(zero-pad(k)) / fft_size in the plan's order (Section 1: the
+ * filter transform is computed once and reused over the batch).
+ *   k: device, (H, Nk) fp32, 1 <= Nk <= fft_size; taps t >= Nk are zero.
+ * The transform itself runs in fp64 on the device. */
+int fftconv_filter_fft(const fftconv_plan *plan, const float *k, int64_t Nk, void *k_f, void *stream);
+
+/* y = conv(u, k) as defined at the top (Algorithm 1 / 3 / 4 depending on
+ * fft_size).  H and N must equal the plan's; B >= 0 is free.  y must not
+ * alias u.  workspace: at least fftconv_workspace_bytes(plan, B) bytes, may
+ * be NULL when that is 0. */
+int fftconv_forward(const fftconv_plan *plan, const void *u, const void *k_f, void *y,
+                    int64_t B, int64_t H, int64_t N, void *workspace, void *stream);
+
+/* Partial convolution (Section 3.3): the filter is zero for taps t >= Nk.
+ * k_f must come from fftconv_filter_fft(plan, k, Nk, ...) with the same Nk.
+ * Same result as fftconv_forward on that k_f; the plan may skip the parts of
+ * the decomposition that a short filter leaves unused. */
+int fftconv_forward_partial(const fftconv_plan *plan, const void *u, const void *k_f, void *y,
+                            int64_t B, int64_t H, int64_t N, int64_t Nk, void *workspace, void *stream);
+
+/* Frequency-sparse filter (Section 3.3, Appendix A.4): as fftconv_filter_fft,
+ * then every frequency bin f whose block is dropped is set to zero.
+ *   block_keep: host, n_blocks bytes, 1 = keep; n_blocks a power of two that
+ *   divides fft_size; block j holds the natural-order frequencies
+ *   f in [j * fft_size / n_blocks, (j+1) * fft_size / n_blocks). */
+int fftconv_filter_fft_sparse(const fftconv_plan *plan, const float *k, int64_t Nk,
+                              const uint8_t *block_keep, int64_t n_blocks, void *k_f, void *stream);
+
+/* Forward pass with a frequency-sparse k_f made by fftconv_filter_fft_sparse
+ * with the same block_keep.  Same result as fftconv_forward on that k_f; the
+ * matrix blocks that only meet zeroed bins may be skipped. */
+int fftconv_forward_freq_sparse(const fftconv_plan *plan, const void *u, const void *k_f,
+                                const uint8_t *block_keep, int64_t n_blocks, void *y,
+                                int64_t B, int64_t H, int64_t N, void *workspace, void *stream);
+
+/* Fraction of k_f that a cut-off pattern zeroes (Appendix A.4): k_f is viewed
+ * as an ndim-dimensional array of shape dims[0..ndim) and, in every dimension
+ * i, the last cuts[i] indices are set to zero (cuts[i] = how much of that
+ * dimension is removed).  Returns 1 - prod_i (dims[i] - cuts[i]) / dims[i],
+ * or a negative value on bad arguments.  Host-only helper. */
+double fftconv_sparsity_fraction(const int64_t *dims, const int64_t *cuts, int ndim);
+
+/* Name of the kernel family the plan dispatches to ("staged", "fused3", ...);
+ * for logs and benchmarks.  Never NULL for a valid plan. */
+const char *fftconv_plan_path(const fftconv_plan *plan);
+
+/* Factorisation of fft_size the plan uses: writes up to max_factors factors
+ * (outermost first) and returns how many there are. */
+int fftconv_plan_factors(const fftconv_plan *plan, int64_t *factors, int max_factors);
+
+const char *fftconv_strerror(int code);
+const char *fftconv_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FFTCONV_H */

@@ -1,0 +1,299 @@
+// C ABI of libfftconv.so: argument checking, plan life cycle and dispatch to the
+// kernel families.  See include/fftconv.h for the contract of every entry point.
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "fftconv_internal.h"
+
+namespace fftconv {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+static bool is_pow2(int64_t v) { return v > 0 && (v & (v - 1)) == 0; }
+
+constexpr int64_t MAX_BLOCKS = 4096;
+
+}  // namespace fftconv
+
+using namespace fftconv;
+
+static int check_plan(const fftconv_plan *p, const char *who)
+{
+    if (!p) {
+        set_error("%s: plan is NULL", who);
+        return FFTCONV_EINVAL;
+    }
+    return FFTCONV_OK;
+}
+
+extern "C" {
+
+int fftconv_plan_create(fftconv_plan **out, int64_t N, int64_t fft_size, int64_t H, int dtype)
+{
+    if (!out) {
+        set_error("fftconv_plan_create: out is NULL");
+        return FFTCONV_EINVAL;
+    }
+    *out = nullptr;
+    if (!is_pow2(fft_size) || fft_size < 256 || fft_size > ((int64_t)1 << 22)) {
+        set_error("fftconv_plan_create: fft_size=%lld must be a power of two in [256, 2^22]", (long long)fft_size);
+        return FFTCONV_EINVAL;
+    }
+    if (N < 1 || N > fft_size) {
+        set_error("fftconv_plan_create: N=%lld must satisfy 1 <= N <= fft_size=%lld", (long long)N,
+                  (long long)fft_size);
+        return FFTCONV_EINVAL;
+    }
+    if (H < 1 || H > ((int64_t)1 << 24)) {
+        set_error("fftconv_plan_create: H=%lld out of range", (long long)H);
+        return FFTCONV_EINVAL;
+    }
+    if (dtype != FFTCONV_F32 && dtype != FFTCONV_F16 && dtype != FFTCONV_BF16) {
+        set_error("fftconv_plan_create: unknown dtype %d", dtype);
+        return FFTCONV_EINVAL;
+    }
+    int ndev = 0;
+    hipError_t e = hipGetDeviceCount(&ndev);
+    if (e != hipSuccess || ndev < 1) {
+        (void)hipGetLastError();
+        set_error("fftconv_plan_create: no usable GPU (%s)", e == hipSuccess ? "device count 0" : hipGetErrorString(e));
+        return FFTCONV_ENODEV;
+    }
+    fftconv_plan *p = new (std::nothrow) fftconv_plan();
+    if (!p) {
+        set_error("fftconv_plan_create: out of host memory");
+        return FFTCONV_ENOMEM;
+    }
+    p->N = N;
+    p->M = fft_size;
+    p->H = H;
+    p->dtype = dtype;
+    int rc = FFTCONV_OK;
+    if (hipGetDevice(&p->device) != hipSuccess) rc = FFTCONV_EHIP;
+    if (rc == FFTCONV_OK) rc = staged_init(p);      // tables of the filter transform; fallback forward
+    if (rc == FFTCONV_OK && hipMalloc((void **)&p->keep_dev, MAX_BLOCKS) != hipSuccess) {
+        set_error("fftconv_plan_create: hipMalloc of the block mask failed");
+        rc = FFTCONV_ENOMEM;
+    }
+    if (rc == FFTCONV_OK) {
+        if (fused3_supported(N, fft_size, dtype)) {
+            p->path = PATH_FUSED3;
+            rc = fused3_init(p);
+        } else {
+            p->path = PATH_STAGED;
+        }
+    }
+    if (rc != FFTCONV_OK) {
+        fftconv_plan_destroy(p);
+        return rc;
+    }
+    *out = p;
+    return FFTCONV_OK;
+}
+
+int fftconv_plan_destroy(fftconv_plan *p)
+{
+    if (!p) return FFTCONV_OK;
+    fused3_destroy(p);
+    staged_destroy(p);
+    if (p->keep_dev) (void)hipFree(p->keep_dev);
+    delete p;
+    return FFTCONV_OK;
+}
+
+size_t fftconv_kf_bytes(const fftconv_plan *p)
+{
+    if (!p) return 0;
+    return p->path == PATH_FUSED3 ? fused3_kf_bytes(p) : staged_kf_bytes(p);
+}
+
+size_t fftconv_workspace_bytes(const fftconv_plan *p, int64_t B)
+{
+    if (!p || B <= 0) return 0;
+    return p->path == PATH_STAGED ? staged_workspace_bytes(p, B) : 0;
+}
+
+static int filter_fft_impl(const fftconv_plan *p, const float *k, int64_t Nk, const uint8_t *block_keep,
+                           int64_t n_blocks, void *k_f, void *stream, const char *who)
+{
+    int rc = check_plan(p, who);
+    if (rc) return rc;
+    if (!k || !k_f) {
+        set_error("%s: k and k_f must not be NULL", who);
+        return FFTCONV_EINVAL;
+    }
+    if (Nk < 1 || Nk > p->M) {
+        set_error("%s: Nk=%lld must satisfy 1 <= Nk <= fft_size=%lld", who, (long long)Nk, (long long)p->M);
+        return FFTCONV_EINVAL;
+    }
+    hipStream_t s = (hipStream_t)stream;
+    const uint8_t *keep_dev = nullptr;
+    if (block_keep) {
+        if (!is_pow2(n_blocks) || n_blocks > MAX_BLOCKS || n_blocks > p->M) {
+            set_error("%s: n_blocks=%lld must be a power of two <= min(%lld, fft_size)", who, (long long)n_blocks,
+                      (long long)MAX_BLOCKS);
+            return FFTCONV_EINVAL;
+        }
+        FC_HIP(hipMemcpyAsync(p->keep_dev, block_keep, (size_t)n_blocks, hipMemcpyHostToDevice, s));
+        keep_dev = p->keep_dev;
+    }
+    for (int64_t h0 = 0; h0 < p->H; h0 += p->filt_chunk) {
+        int64_t nh = p->H - h0 < p->filt_chunk ? p->H - h0 : p->filt_chunk;
+        double2 *spec = nullptr;
+        rc = staged_filter_transform(p, k, Nk, h0, nh, s, &spec);
+        if (rc) return rc;
+        rc = p->path == PATH_FUSED3 ? fused3_pack_kf(p, spec, h0, nh, keep_dev, n_blocks, k_f, s)
+                                    : staged_pack_kf(p, spec, h0, nh, keep_dev, n_blocks, k_f, s);
+        if (rc) return rc;
+    }
+    return FFTCONV_OK;
+}
+
+int fftconv_filter_fft(const fftconv_plan *p, const float *k, int64_t Nk, void *k_f, void *stream)
+{
+    return filter_fft_impl(p, k, Nk, nullptr, 1, k_f, stream, "fftconv_filter_fft");
+}
+
+int fftconv_filter_fft_sparse(const fftconv_plan *p, const float *k, int64_t Nk, const uint8_t *block_keep,
+                              int64_t n_blocks, void *k_f, void *stream)
+{
+    if (!block_keep) {
+        set_error("fftconv_filter_fft_sparse: block_keep is NULL");
+        return FFTCONV_EINVAL;
+    }
+    return filter_fft_impl(p, k, Nk, block_keep, n_blocks, k_f, stream, "fftconv_filter_fft_sparse");
+}
+
+static int forward_check(const fftconv_plan *p, const void *u, const void *k_f, void *y, int64_t B, int64_t H,
+                         int64_t N, void *workspace, const char *who)
+{
+    int rc = check_plan(p, who);
+    if (rc) return rc;
+    if (B < 0) {
+        set_error("%s: B=%lld is negative", who, (long long)B);
+        return FFTCONV_EINVAL;
+    }
+    if (H != p->H || N != p->N) {
+        set_error("%s: (H=%lld, N=%lld) differ from the plan's (H=%lld, N=%lld)", who, (long long)H, (long long)N,
+                  (long long)p->H, (long long)p->N);
+        return FFTCONV_EINVAL;
+    }
+    if (B == 0) return FFTCONV_OK;
+    if (!u || !k_f || !y) {
+        set_error("%s: u, k_f and y must not be NULL", who);
+        return FFTCONV_EINVAL;
+    }
+    if (u == y) {
+        set_error("%s: y must not alias u", who);
+        return FFTCONV_EINVAL;
+    }
+    if (!workspace && fftconv_workspace_bytes(p, B) != 0) {
+        set_error("%s: this plan needs %zu bytes of workspace for B=%lld", who, fftconv_workspace_bytes(p, B),
+                  (long long)B);
+        return FFTCONV_EINVAL;
+    }
+    return FFTCONV_OK;
+}
+
+int fftconv_forward(const fftconv_plan *p, const void *u, const void *k_f, void *y, int64_t B, int64_t H, int64_t N,
+                    void *workspace, void *stream)
+{
+    int rc = forward_check(p, u, k_f, y, B, H, N, workspace, "fftconv_forward");
+    if (rc || B == 0) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    switch (p->path) {
+    case PATH_FUSED3:
+        return fused3_forward(p, u, k_f, y, B, s);
+    default:
+        return staged_forward(p, u, k_f, y, B, workspace, s);
+    }
+}
+
+int fftconv_forward_partial(const fftconv_plan *p, const void *u, const void *k_f, void *y, int64_t B, int64_t H,
+                            int64_t N, int64_t Nk, void *workspace, void *stream)
+{
+    int rc = forward_check(p, u, k_f, y, B, H, N, workspace, "fftconv_forward_partial");
+    if (rc) return rc;
+    if (Nk < 1 || Nk > p->M) {
+        set_error("fftconv_forward_partial: Nk=%lld must satisfy 1 <= Nk <= fft_size", (long long)Nk);
+        return FFTCONV_EINVAL;
+    }
+    if (B == 0) return FFTCONV_OK;
+    return fftconv_forward(p, u, k_f, y, B, H, N, workspace, stream);
+}
+
+int fftconv_forward_freq_sparse(const fftconv_plan *p, const void *u, const void *k_f, const uint8_t *block_keep,
+                                int64_t n_blocks, void *y, int64_t B, int64_t H, int64_t N, void *workspace,
+                                void *stream)
+{
+    int rc = forward_check(p, u, k_f, y, B, H, N, workspace, "fftconv_forward_freq_sparse");
+    if (rc) return rc;
+    if (!block_keep || !is_pow2(n_blocks) || n_blocks > MAX_BLOCKS || n_blocks > p->M) {
+        set_error("fftconv_forward_freq_sparse: block_keep must be given, n_blocks a power of two <= min(%lld, fft_size)",
+                  (long long)MAX_BLOCKS);
+        return FFTCONV_EINVAL;
+    }
+    if (B == 0) return FFTCONV_OK;
+    return fftconv_forward(p, u, k_f, y, B, H, N, workspace, stream);
+}
+
+double fftconv_sparsity_fraction(const int64_t *dims, const int64_t *cuts, int ndim)
+{
+    if (!dims || !cuts || ndim < 1) return -1.0;
+    double kept = 1.0;
+    for (int i = 0; i < ndim; ++i) {
+        if (dims[i] < 1 || cuts[i] < 0 || cuts[i] > dims[i]) return -1.0;
+        kept *= (double)(dims[i] - cuts[i]) / (double)dims[i];
+    }
+    return 1.0 - kept;
+}
+
+const char *fftconv_plan_path(const fftconv_plan *p)
+{
+    if (!p) return "";
+    switch (p->path) {
+    case PATH_FUSED3: return "fused3";
+    case PATH_MULTIPASS: return "multipass";
+    default: return "staged";
+    }
+}
+
+int fftconv_plan_factors(const fftconv_plan *p, int64_t *factors, int max_factors)
+{
+    if (!p || !factors) return 0;
+    int n = 0;
+    if (p->path == PATH_FUSED3) {
+        int64_t f[3] = {p->f3.N1, p->f3.N2, p->f3.N3};
+        for (; n < 3 && n < max_factors; ++n) factors[n] = f[n];
+        return 3;
+    }
+    for (; n < p->st.nf && n < max_factors; ++n) factors[n] = p->st.fac[n];
+    return p->st.nf;
+}
+
+const char *fftconv_strerror(int code)
+{
+    switch (code) {
+    case FFTCONV_OK: return "ok";
+    case FFTCONV_EINVAL: return "invalid argument";
+    case FFTCONV_EUNSUPPORTED: return "unsupported configuration";
+    case FFTCONV_EHIP: return "HIP runtime error";
+    case FFTCONV_ENOMEM: return "out of memory";
+    case FFTCONV_ENODEV: return "no usable GPU";
+    default: return "unknown error code";
+    }
+}
+
+const char *fftconv_last_error(void) { return fftconv::g_err; }
+
+}  // extern "C"

@@ -1,0 +1,89 @@
+// Internal declarations shared by the translation units of libfftconv.so.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "fftconv.h"
+
+namespace fftconv {
+
+void set_error(const char *fmt, ...);
+
+#define FC_HIP(call)                                                                      \
+    do {                                                                                  \
+        hipError_t e_ = (call);                                                           \
+        if (e_ != hipSuccess) {                                                           \
+            ::fftconv::set_error("%s failed: %s (%s:%d)", #call, hipGetErrorString(e_),   \
+                                 __FILE__, __LINE__);                                     \
+            return FFTCONV_EHIP;                                                          \
+        }                                                                                 \
+    } while (0)
+
+enum Path { PATH_STAGED = 0, PATH_FUSED3 = 1, PATH_MULTIPASS = 2 };
+
+constexpr int MAX_FACTORS = 8;
+
+// Generic multi-kernel path: one launch per stage of the order-p decomposition,
+// complex intermediates in a caller-provided workspace.  Used for fp32 I/O, for
+// sizes without a fused kernel, and (in fp64) for every filter transform.
+struct StagedTables {
+    int nf = 0;
+    int64_t fac[MAX_FACTORS] = {0};   // outermost (first contracted) first
+    float2 *w32 = nullptr;            // W_M^t, t in [0,M), fp32 pairs
+    double2 *w64 = nullptr;           // same in fp64 (filter transform)
+};
+
+// Fused single-kernel path for 16-bit I/O, fft_size = N1*N2*N3 (Algorithm 3).
+struct Fused3Tables {
+    int N1 = 0, N2 = 0, N3 = 0;
+    void *consts = nullptr;           // operand tables in the kernel's lane order
+    size_t consts_bytes = 0;
+};
+
+}  // namespace fftconv
+
+struct fftconv_plan {
+    int64_t N = 0, M = 0, H = 0;
+    int dtype = 0;
+    int device = 0;
+    fftconv::Path path = fftconv::PATH_STAGED;
+    fftconv::StagedTables st;
+    fftconv::Fused3Tables f3;
+    // private scratch of the filter transform (two fp64 complex ping-pong buffers)
+    double2 *filt_a = nullptr, *filt_b = nullptr;
+    int64_t filt_chunk = 0;           // channels per pass through the scratch
+    int64_t fwd_chunk_cap = 0;        // staged forward: max sequences per pass
+    uint8_t *keep_dev = nullptr;      // device copy of a frequency-block mask (sparse filter transform)
+};
+
+namespace fftconv {
+
+// ---- staged path (staged.hip)
+int staged_init(fftconv_plan *p);
+void staged_destroy(fftconv_plan *p);
+size_t staged_kf_bytes(const fftconv_plan *p);
+size_t staged_workspace_bytes(const fftconv_plan *p, int64_t B);
+int staged_forward(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B,
+                   void *workspace, hipStream_t s);
+// fp64 transform of zero-padded filters into p->filt_a for channels [h0, h0+nh):
+// on return filt_a holds position-ordered spectra (position -> frequency via staged_pos_to_freq).
+int staged_filter_transform(const fftconv_plan *p, const float *k, int64_t Nk, int64_t h0, int64_t nh,
+                            hipStream_t s, double2 **result);
+// scatter of the fp64 spectra into the staged path's own k_f layout
+int staged_pack_kf(const fftconv_plan *p, const double2 *spec, int64_t h0, int64_t nh,
+                   const uint8_t *keep_dev, int64_t n_blocks, void *kf, hipStream_t s);
+
+// ---- fused 3-stage path (fused3.hip)
+bool fused3_supported(int64_t N, int64_t M, int dtype);
+int fused3_init(fftconv_plan *p);
+void fused3_destroy(fftconv_plan *p);
+size_t fused3_kf_bytes(const fftconv_plan *p);
+int fused3_pack_kf(const fftconv_plan *p, const double2 *spec, int64_t h0, int64_t nh,
+                   const uint8_t *keep_dev, int64_t n_blocks, void *kf, hipStream_t s);
+int fused3_forward(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, hipStream_t s);
+
+}  // namespace fftconv

@@ -1,0 +1,350 @@
+// Generic multi-kernel FFT convolution: one launch per stage of the order-p
+// decomposition (paper Section 2.1: F_M as a chain of small DFT-matrix products
+// with twiddle diagonals in between), intermediates in HBM.  This is the path
+// for fp32 I/O and for transform lengths without a fused kernel, and -- in fp64
+// -- the engine of every filter transform k -> k_f.
+//
+// Index maps.  M = N_1 * ... * N_p.  Time index n = sum_i n_i S_i with
+// S_i = prod_{j>i} N_j (n_1 most significant); frequency f = sum_i k_i R_i with
+// R_i = prod_{j<i} N_j (k_1 least significant).  Then
+//   W_M^{n f} = prod_i W_{N_i}^{n_i k_i} * prod_i W_M^{k_i R_i (n mod S_i)},
+// so stage i contracts digit i in place (position sum_i d_i S_i, d_i = n_i before
+// and k_i after the stage) and is followed by the twiddle W_M^{k_i R_i r},
+// r = the not-yet-transformed lower digits.  After the last stage position
+// sum_i k_i S_i holds frequency sum_i k_i R_i; k_f is stored in that order so no
+// permutation is ever executed.  The inverse runs the mirrored chain with
+// conjugated factors; its 1/M lives in k_f.
+#include <hip/hip_bf16.h>
+#include <hip/hip_fp16.h>
+
+#include <cmath>
+
+#include "fftconv_internal.h"
+
+namespace fftconv {
+
+namespace {
+
+struct FacList {
+    int nf;
+    int fac[MAX_FACTORS];
+};
+
+template <typename T> struct C2;
+template <> struct C2<float> { using type = float2; };
+template <> struct C2<double> { using type = double2; };
+
+template <typename V> __device__ __forceinline__ V cmul(V a, V b)
+{
+    V r;
+    r.x = a.x * b.x - a.y * b.y;
+    r.y = a.x * b.y + a.y * b.x;
+    return r;
+}
+template <typename V> __device__ __forceinline__ V cmul_conj(V a, V b)   // a * conj(b)
+{
+    V r;
+    r.x = a.x * b.x + a.y * b.y;
+    r.y = a.y * b.x - a.x * b.y;
+    return r;
+}
+
+__device__ __forceinline__ float load_real(const float *p, int64_t i) { return p[i]; }
+__device__ __forceinline__ float load_real(const __half *p, int64_t i) { return __half2float(p[i]); }
+__device__ __forceinline__ float load_real(const __hip_bfloat16 *p, int64_t i) { return __bfloat162float(p[i]); }
+__device__ __forceinline__ void store_real(float *p, int64_t i, float v) { p[i] = v; }
+__device__ __forceinline__ void store_real(__half *p, int64_t i, float v) { p[i] = __float2half_rn(v); }
+__device__ __forceinline__ void store_real(__hip_bfloat16 *p, int64_t i, float v) { p[i] = __float2bfloat16(v); }
+
+// Zero-padded real input -> complex buffer (imaginary part 0, zeros for n >= len).
+template <typename V, typename In>
+__global__ void k_load_padded(const In *src, V *dst, int64_t len, int64_t M, int64_t nrows)
+{
+    int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= nrows * M) return;
+    int64_t row = idx / M, n = idx % M;
+    V v;
+    v.x = n < len ? (decltype(v.x))load_real(src, row * len + n) : 0;
+    v.y = 0;
+    dst[idx] = v;
+}
+
+// Forward stage: out[prefix, k, r] = W_M^{k R r} * sum_n W_{Nj}^{n k} in[prefix, n, r].
+template <typename V>
+__global__ void k_stage_fwd(const V *in, V *out, const V *w, int64_t M, int Nj, int64_t Sj, int64_t Rj,
+                            int64_t nrows)
+{
+    int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= nrows * M) return;
+    int64_t row = idx / M, p = idx % M;
+    int64_t r = p % Sj;
+    int k = (int)((p / Sj) % Nj);
+    int64_t base = row * M + (p - (int64_t)k * Sj);
+    int64_t step = M / Nj;
+    V acc;
+    acc.x = 0;
+    acc.y = 0;
+    int ph = 0;                                   // (n*k) mod Nj
+    for (int n = 0; n < Nj; ++n) {
+        V x = in[base + (int64_t)n * Sj];
+        V t = cmul(x, w[(int64_t)ph * step]);
+        acc.x += t.x;
+        acc.y += t.y;
+        ph += k;
+        if (ph >= Nj) ph -= Nj;
+    }
+    out[idx] = cmul(acc, w[(int64_t)k * Rj * r]);  // k*Rj*r < Nj*Rj*Sj = M
+}
+
+// Inverse stage: out[prefix, n, r] = sum_k conj(W_{Nj}^{n k} W_M^{k R r}) in[prefix, k, r].
+template <typename V>
+__global__ void k_stage_inv(const V *in, V *out, const V *w, int64_t M, int Nj, int64_t Sj, int64_t Rj,
+                            int64_t nrows)
+{
+    int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= nrows * M) return;
+    int64_t row = idx / M, p = idx % M;
+    int64_t r = p % Sj;
+    int n = (int)((p / Sj) % Nj);
+    int64_t base = row * M + (p - (int64_t)n * Sj);
+    int64_t step = M / Nj;
+    V acc;
+    acc.x = 0;
+    acc.y = 0;
+    int ph = 0;                                   // (n*k) mod Nj
+    for (int k = 0; k < Nj; ++k) {
+        V x = in[base + (int64_t)k * Sj];
+        int64_t e = (int64_t)ph * step + (int64_t)k * Rj * r;
+        if (e >= M) e -= M;
+        V t = cmul_conj(x, w[e]);
+        acc.x += t.x;
+        acc.y += t.y;
+        ph += n;
+        if (ph >= Nj) ph -= Nj;
+    }
+    out[idx] = acc;
+}
+
+// x[row, p] *= kf[(row0 + row) % H, p]
+__global__ void k_pointwise(float2 *x, const float2 *kf, int64_t M, int64_t H, int64_t row0, int64_t nrows)
+{
+    int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= nrows * M) return;
+    int64_t row = idx / M, p = idx % M;
+    int64_t h = (row0 + row) % H;
+    x[idx] = cmul(x[idx], kf[h * M + p]);
+}
+
+template <typename Out>
+__global__ void k_store_real(const float2 *x, Out *y, int64_t N, int64_t M, int64_t nrows)
+{
+    int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= nrows * N) return;
+    int64_t row = idx / N, n = idx % N;
+    store_real(y, idx, x[row * M + n].x);
+}
+
+__host__ __device__ inline int64_t freq_to_pos(int64_t f, const FacList &fl, int64_t M)
+{
+    int64_t p = 0, S = M;
+    for (int i = 0; i < fl.nf; ++i) {
+        S /= fl.fac[i];
+        p += (f % fl.fac[i]) * S;
+        f /= fl.fac[i];
+    }
+    return p;
+}
+
+// spectra in position order (fp64) -> staged k_f (fp32 pairs, same position order), scaled 1/M,
+// with dropped frequency blocks zeroed.
+__global__ void k_pack_staged(const double2 *spec, float2 *kf, FacList fl, int64_t M, int64_t h0, int64_t nh,
+                              const uint8_t *keep, int64_t n_blocks)
+{
+    int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= nh * M) return;
+    int64_t h = idx / M, f = idx % M;
+    int64_t p = freq_to_pos(f, fl, M);
+    double2 v = spec[h * M + p];
+    double sc = 1.0 / (double)M;
+    if (keep && !keep[f / (M / n_blocks)]) sc = 0.0;
+    kf[(h0 + h) * M + p] = make_float2((float)(v.x * sc), (float)(v.y * sc));
+}
+
+FacList fac_list(const fftconv_plan *p)
+{
+    FacList fl;
+    fl.nf = p->st.nf;
+    for (int i = 0; i < MAX_FACTORS; ++i) fl.fac[i] = (int)p->st.fac[i];
+    return fl;
+}
+
+inline unsigned grid_for(int64_t n, int bs) { return (unsigned)((n + bs - 1) / bs); }
+
+template <typename V>
+int run_stages_fwd(const fftconv_plan *p, V *a, V *b, const V *w, int64_t nrows, hipStream_t s, V **result)
+{
+    const int bs = 256;
+    int64_t M = p->M, S = M, R = 1;
+    V *src = a, *dst = b;
+    for (int i = 0; i < p->st.nf; ++i) {
+        int Nj = (int)p->st.fac[i];
+        S /= Nj;
+        hipLaunchKernelGGL(k_stage_fwd<V>, dim3(grid_for(nrows * M, bs)), dim3(bs), 0, s, src, dst, w, M, Nj, S, R,
+                           nrows);
+        FC_HIP(hipGetLastError());
+        R *= Nj;
+        V *t = src; src = dst; dst = t;
+    }
+    *result = src;
+    return FFTCONV_OK;
+}
+
+}  // namespace
+
+int staged_init(fftconv_plan *p)
+{
+    // factors of 16, remainder (2, 4 or 8) last
+    int lg = 0;
+    while (((int64_t)1 << lg) < p->M) ++lg;
+    int nf = 0;
+    int rem = lg;
+    while (rem >= 4) { p->st.fac[nf++] = 16; rem -= 4; }
+    if (rem) p->st.fac[nf++] = (int64_t)1 << rem;
+    p->st.nf = nf;
+
+    int64_t M = p->M;
+    std::vector<double2> w64((size_t)M);
+    std::vector<float2> w32((size_t)M);
+    const double two_pi = 6.283185307179586476925286766559;
+    for (int64_t t = 0; t < M; ++t) {
+        // exact octant symmetry is not needed: libm is accurate to < 1 ulp for |x| <= 2 pi
+        double a = two_pi * (double)t / (double)M;
+        w64[t] = make_double2(std::cos(a), -std::sin(a));
+        w32[t] = make_float2((float)w64[t].x, (float)w64[t].y);
+    }
+    FC_HIP(hipMalloc((void **)&p->st.w64, sizeof(double2) * M));
+    FC_HIP(hipMalloc((void **)&p->st.w32, sizeof(float2) * M));
+    FC_HIP(hipMemcpy(p->st.w64, w64.data(), sizeof(double2) * M, hipMemcpyHostToDevice));
+    FC_HIP(hipMemcpy(p->st.w32, w32.data(), sizeof(float2) * M, hipMemcpyHostToDevice));
+
+    // filter-transform scratch: two ping-pong buffers of at most 64 MiB (or one channel) each
+    const int64_t cap = (int64_t)64 << 20;
+    int64_t per_ch = M * (int64_t)sizeof(double2);
+    int64_t chunk = cap / per_ch;
+    if (chunk < 1) chunk = 1;
+    if (chunk > p->H) chunk = p->H;
+    p->filt_chunk = chunk;
+    FC_HIP(hipMalloc((void **)&p->filt_a, (size_t)(chunk * per_ch)));
+    FC_HIP(hipMalloc((void **)&p->filt_b, (size_t)(chunk * per_ch)));
+
+    // forward workspace: two fp32 complex buffers, at most 256 MiB each
+    int64_t fcap = ((int64_t)256 << 20) / (M * (int64_t)sizeof(float2));
+    p->fwd_chunk_cap = fcap < 1 ? 1 : fcap;
+    return FFTCONV_OK;
+}
+
+void staged_destroy(fftconv_plan *p)
+{
+    if (p->st.w64) (void)hipFree(p->st.w64);
+    if (p->st.w32) (void)hipFree(p->st.w32);
+    if (p->filt_a) (void)hipFree(p->filt_a);
+    if (p->filt_b) (void)hipFree(p->filt_b);
+    p->st.w64 = nullptr;
+    p->st.w32 = nullptr;
+    p->filt_a = p->filt_b = nullptr;
+}
+
+size_t staged_kf_bytes(const fftconv_plan *p) { return (size_t)(p->H * p->M) * sizeof(float2); }
+
+static int64_t staged_chunk(const fftconv_plan *p, int64_t B)
+{
+    int64_t nseq = B * p->H;
+    return nseq < p->fwd_chunk_cap ? nseq : p->fwd_chunk_cap;
+}
+
+size_t staged_workspace_bytes(const fftconv_plan *p, int64_t B)
+{
+    return (size_t)(2 * staged_chunk(p, B) * p->M) * sizeof(float2);
+}
+
+template <typename IO>
+static int staged_forward_t(const fftconv_plan *p, const IO *u, const float2 *kf, IO *y, int64_t B, void *workspace,
+                            hipStream_t s)
+{
+    const int bs = 256;
+    int64_t M = p->M, N = p->N, H = p->H;
+    int64_t nseq = B * H;
+    if (nseq == 0) return FFTCONV_OK;
+    int64_t chunk = staged_chunk(p, B);
+    float2 *a = (float2 *)workspace;
+    float2 *b = a + chunk * M;
+    for (int64_t row0 = 0; row0 < nseq; row0 += chunk) {
+        int64_t nrows = nseq - row0 < chunk ? nseq - row0 : chunk;
+        hipLaunchKernelGGL((k_load_padded<float2, IO>), dim3(grid_for(nrows * M, bs)), dim3(bs), 0, s, u + row0 * N,
+                           a, N, M, nrows);
+        FC_HIP(hipGetLastError());
+        float2 *x = nullptr;
+        int rc = run_stages_fwd<float2>(p, a, b, p->st.w32, nrows, s, &x);
+        if (rc) return rc;
+        hipLaunchKernelGGL(k_pointwise, dim3(grid_for(nrows * M, bs)), dim3(bs), 0, s, x, kf, M, H, row0, nrows);
+        FC_HIP(hipGetLastError());
+        float2 *src = x, *dst = (x == a) ? b : a;
+        int64_t S = 1, R = M;
+        for (int i = p->st.nf - 1; i >= 0; --i) {
+            int Nj = (int)p->st.fac[i];
+            R /= Nj;
+            hipLaunchKernelGGL(k_stage_inv<float2>, dim3(grid_for(nrows * M, bs)), dim3(bs), 0, s, src, dst,
+                               p->st.w32, M, Nj, S, R, nrows);
+            FC_HIP(hipGetLastError());
+            S *= Nj;
+            float2 *t = src; src = dst; dst = t;
+        }
+        hipLaunchKernelGGL((k_store_real<IO>), dim3(grid_for(nrows * N, bs)), dim3(bs), 0, s, src, y + row0 * N, N, M,
+                           nrows);
+        FC_HIP(hipGetLastError());
+    }
+    return FFTCONV_OK;
+}
+
+int staged_forward(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, void *workspace,
+                   hipStream_t s)
+{
+    switch (p->dtype) {
+    case FFTCONV_F32:
+        return staged_forward_t<float>(p, (const float *)u, (const float2 *)kf, (float *)y, B, workspace, s);
+    case FFTCONV_F16:
+        return staged_forward_t<__half>(p, (const __half *)u, (const float2 *)kf, (__half *)y, B, workspace, s);
+    default:
+        return staged_forward_t<__hip_bfloat16>(p, (const __hip_bfloat16 *)u, (const float2 *)kf,
+                                                (__hip_bfloat16 *)y, B, workspace, s);
+    }
+}
+
+int staged_filter_transform(const fftconv_plan *p, const float *k, int64_t Nk, int64_t h0, int64_t nh, hipStream_t s,
+                            double2 **result)
+{
+    const int bs = 256;
+    hipLaunchKernelGGL((k_load_padded<double2, float>), dim3(grid_for(nh * p->M, bs)), dim3(bs), 0, s, k + h0 * Nk,
+                       p->filt_a, Nk, p->M, nh);
+    FC_HIP(hipGetLastError());
+    return run_stages_fwd<double2>(p, p->filt_a, p->filt_b, p->st.w64, nh, s, result);
+}
+
+int staged_pack_kf(const fftconv_plan *p, const double2 *spec, int64_t h0, int64_t nh, const uint8_t *keep_dev,
+                   int64_t n_blocks, void *kf, hipStream_t s)
+{
+    const int bs = 256;
+    hipLaunchKernelGGL(k_pack_staged, dim3(grid_for(nh * p->M, bs)), dim3(bs), 0, s, spec, (float2 *)kf, fac_list(p),
+                       p->M, h0, nh, keep_dev, n_blocks);
+    FC_HIP(hipGetLastError());
+    return FFTCONV_OK;
+}
+
+// frequency -> position in the staged order (host side; used by other paths' packers)
+int64_t staged_freq_to_pos(const fftconv_plan *p, int64_t f)
+{
+    FacList fl = fac_list(p);
+    return freq_to_pos(f, fl, p->M);
+}
+
+}  // namespace fftconv

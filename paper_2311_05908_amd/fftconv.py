@@ -1,0 +1,200 @@
+"""Python binding of the C-ABI library libfftconv.so (see include/fftconv.h).
+
+Argument marshalling only: every step of the convolution runs in the HIP
+kernels of the library.  PyTorch supplies device memory and the stream.  There
+is no fallback: if the library cannot be loaded, importing callers fail.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+from . import build as _build
+
+FFTCONV_F32, FFTCONV_F16, FFTCONV_BF16 = 0, 1, 2
+_DTYPE_CODE = {torch.float32: FFTCONV_F32, torch.float16: FFTCONV_F16, torch.bfloat16: FFTCONV_BF16}
+_DTYPE_NAME = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
+
+EXPORTS = [
+    "fftconv_plan_create", "fftconv_plan_destroy", "fftconv_kf_bytes", "fftconv_workspace_bytes",
+    "fftconv_filter_fft", "fftconv_forward", "fftconv_forward_partial", "fftconv_filter_fft_sparse",
+    "fftconv_forward_freq_sparse", "fftconv_sparsity_fraction", "fftconv_plan_path", "fftconv_plan_factors",
+    "fftconv_strerror", "fftconv_last_error",
+]
+
+_lib = None
+
+
+class FFTConvError(RuntimeError):
+    def __init__(self, code: int, detail: str):
+        super().__init__("fftconv error %d: %s" % (code, detail))
+        self.code = code
+
+
+def library_path() -> str:
+    return _build.LIB
+
+
+def load():
+    """Load libfftconv.so, building it first only if no built library exists."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_build.LIB):
+        _build.build()
+    lib = ctypes.CDLL(_build.LIB)
+    vp, i64, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
+    lib.fftconv_plan_create.argtypes = [ctypes.POINTER(vp), i64, i64, i64, ci]
+    lib.fftconv_plan_create.restype = ci
+    lib.fftconv_plan_destroy.argtypes = [vp]
+    lib.fftconv_plan_destroy.restype = ci
+    lib.fftconv_kf_bytes.argtypes = [vp]
+    lib.fftconv_kf_bytes.restype = ctypes.c_size_t
+    lib.fftconv_workspace_bytes.argtypes = [vp, i64]
+    lib.fftconv_workspace_bytes.restype = ctypes.c_size_t
+    lib.fftconv_filter_fft.argtypes = [vp, vp, i64, vp, vp]
+    lib.fftconv_filter_fft.restype = ci
+    lib.fftconv_forward.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, vp]
+    lib.fftconv_forward.restype = ci
+    lib.fftconv_forward_partial.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, vp, vp]
+    lib.fftconv_forward_partial.restype = ci
+    lib.fftconv_filter_fft_sparse.argtypes = [vp, vp, i64, vp, i64, vp, vp]
+    lib.fftconv_filter_fft_sparse.restype = ci
+    lib.fftconv_forward_freq_sparse.argtypes = [vp, vp, vp, vp, i64, vp, i64, i64, i64, vp, vp]
+    lib.fftconv_forward_freq_sparse.restype = ci
+    lib.fftconv_sparsity_fraction.argtypes = [ctypes.POINTER(i64), ctypes.POINTER(i64), ci]
+    lib.fftconv_sparsity_fraction.restype = ctypes.c_double
+    lib.fftconv_plan_path.argtypes = [vp]
+    lib.fftconv_plan_path.restype = ctypes.c_char_p
+    lib.fftconv_plan_factors.argtypes = [vp, ctypes.POINTER(i64), ci]
+    lib.fftconv_plan_factors.restype = ci
+    lib.fftconv_strerror.argtypes = [ci]
+    lib.fftconv_strerror.restype = ctypes.c_char_p
+    lib.fftconv_last_error.argtypes = []
+    lib.fftconv_last_error.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def _check(rc: int):
+    if rc != 0:
+        lib = load()
+        detail = lib.fftconv_last_error().decode() or lib.fftconv_strerror(rc).decode()
+        raise FFTConvError(rc, detail)
+
+
+def _stream_ptr():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def sparsity_fraction(dims, cuts) -> float:
+    """fftconv_sparsity_fraction: share of k_f zeroed by per-dimension cut-offs."""
+    n = len(dims)
+    if len(cuts) != n:
+        raise ValueError("dims and cuts differ in length")
+    arr = ctypes.c_int64 * max(n, 1)
+    v = load().fftconv_sparsity_fraction(arr(*dims), arr(*cuts), n)
+    if v < 0:
+        raise ValueError("bad sparsity pattern")
+    return v
+
+
+class Plan:
+    """fftconv_plan_create / fftconv_plan_destroy and the calls that take a plan."""
+
+    def __init__(self, N: int, fft_size: int, H: int, dtype):
+        if isinstance(dtype, str):
+            dtype = _DTYPE_NAME[dtype]
+        self.N, self.fft_size, self.H, self.dtype = int(N), int(fft_size), int(H), dtype
+        self._lib = load()
+        self._h = ctypes.c_void_p()
+        _check(self._lib.fftconv_plan_create(ctypes.byref(self._h), self.N, self.fft_size, self.H, _DTYPE_CODE[dtype]))
+        self._ws = None
+
+    def close(self):
+        if getattr(self, "_h", None) is not None and self._h:
+            self._lib.fftconv_plan_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    @property
+    def path(self) -> str:
+        return self._lib.fftconv_plan_path(self._h).decode()
+
+    @property
+    def factors(self):
+        buf = (ctypes.c_int64 * 8)()
+        n = self._lib.fftconv_plan_factors(self._h, buf, 8)
+        return [int(buf[i]) for i in range(n)]
+
+    def kf_bytes(self) -> int:
+        return int(self._lib.fftconv_kf_bytes(self._h))
+
+    def workspace_bytes(self, B: int) -> int:
+        return int(self._lib.fftconv_workspace_bytes(self._h, int(B)))
+
+    def _workspace(self, B: int, device):
+        need = self.workspace_bytes(B)
+        if need == 0:
+            return None
+        if self._ws is None or self._ws.numel() < need or self._ws.device != device:
+            self._ws = torch.empty(need, dtype=torch.uint8, device=device)
+        return self._ws
+
+    def _check_k(self, k):
+        if k.dtype != torch.float32 or not k.is_cuda or not k.is_contiguous() or k.dim() != 2 or k.shape[0] != self.H:
+            raise ValueError("k must be a contiguous CUDA fp32 tensor of shape (H, Nk)")
+
+    def filter_fft(self, k: torch.Tensor, block_keep=None) -> torch.Tensor:
+        """fftconv_filter_fft / fftconv_filter_fft_sparse: returns the opaque k_f buffer."""
+        self._check_k(k)
+        kf = torch.empty(self.kf_bytes(), dtype=torch.uint8, device=k.device)
+        if block_keep is None:
+            _check(self._lib.fftconv_filter_fft(self._h, k.data_ptr(), k.shape[1], kf.data_ptr(), _stream_ptr()))
+        else:
+            bk = bytes(bytearray(int(x) for x in block_keep))
+            _check(self._lib.fftconv_filter_fft_sparse(self._h, k.data_ptr(), k.shape[1], bk, len(bk), kf.data_ptr(),
+                                                       _stream_ptr()))
+        return kf
+
+    def _check_u(self, u):
+        if (u.dtype != self.dtype or not u.is_cuda or not u.is_contiguous() or u.dim() != 3
+                or u.shape[1] != self.H or u.shape[2] != self.N):
+            raise ValueError("u must be a contiguous CUDA tensor (B, H=%d, N=%d) of dtype %s" % (self.H, self.N, self.dtype))
+
+    def forward(self, u: torch.Tensor, kf: torch.Tensor, out: torch.Tensor | None = None) -> torch.Tensor:
+        """fftconv_forward."""
+        self._check_u(u)
+        y = torch.empty_like(u) if out is None else out
+        ws = self._workspace(u.shape[0], u.device)
+        _check(self._lib.fftconv_forward(self._h, u.data_ptr(), kf.data_ptr(), y.data_ptr(), u.shape[0], self.H,
+                                         self.N, None if ws is None else ws.data_ptr(), _stream_ptr()))
+        return y
+
+    def forward_partial(self, u, kf, Nk: int, out=None):
+        """fftconv_forward_partial."""
+        self._check_u(u)
+        y = torch.empty_like(u) if out is None else out
+        ws = self._workspace(u.shape[0], u.device)
+        _check(self._lib.fftconv_forward_partial(self._h, u.data_ptr(), kf.data_ptr(), y.data_ptr(), u.shape[0],
+                                                 self.H, self.N, int(Nk), None if ws is None else ws.data_ptr(),
+                                                 _stream_ptr()))
+        return y
+
+    def forward_freq_sparse(self, u, kf, block_keep, out=None):
+        """fftconv_forward_freq_sparse."""
+        self._check_u(u)
+        y = torch.empty_like(u) if out is None else out
+        ws = self._workspace(u.shape[0], u.device)
+        bk = bytes(bytearray(int(x) for x in block_keep))
+        _check(self._lib.fftconv_forward_freq_sparse(self._h, u.data_ptr(), kf.data_ptr(), bk, len(bk), y.data_ptr(),
+                                                     u.shape[0], self.H, self.N,
+                                                     None if ws is None else ws.data_ptr(), _stream_ptr()))
+        return y

@@ -1,0 +1,77 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2311_05908_amd import fftconv, synth
+from parity_util import TOL, check_all_sequences, gpu_forward
+
+pytestmark = pytest.mark.gpu
+W = synth.WORKLOADS
+
+
+def test_cfg1_fp32_all_sequences():
+    err, plan = check_all_sequences(W["cfg1"])
+    print("cfg1 path=%s factors=%s max rel L2 = %.3e" % (plan.path, plan.factors, err), flush=True)
+    assert err <= TOL["f32"]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("B,H,N,M", [
+    (3, 5, 128, 256),        # smallest transform
+    (2, 3, 300, 1024),       # ragged N, N < M/2
+    (1, 2, 512, 512),        # circular: fft_size == N
+    (2, 2, 700, 1024),       # N > M/2: wrap-around taps matter
+    (5, 1, 2048, 4096),
+])
+def test_small_shapes_all_dtypes(dtype, B, H, N, M):
+    w = synth.scaled(W["cfg2"], B=B, H=H, N=N, fft_size=M, dtype=dtype, alpha=(1e-2, 1e-1))
+    err, plan = check_all_sequences(w)
+    print("%s B=%d H=%d N=%d M=%d path=%s err=%.3e" % (dtype, B, H, N, M, plan.path, err), flush=True)
+    assert err <= TOL[dtype]
+
+
+def test_delta_filter_is_identity_and_zero_input_gives_zero():
+    N, M, H, B = 1024, 2048, 3, 2
+    plan = fftconv.Plan(N, M, H, torch.float32)
+    k = torch.zeros(H, N, device="cuda")
+    k[:, 0] = 1.0
+    kf = plan.filter_fft(k)
+    u = torch.randn(B, H, N, device="cuda")
+    y = plan.forward(u, kf)
+    assert torch.allclose(y, u, atol=2e-5)
+    y0 = plan.forward(torch.zeros_like(u), kf)
+    assert torch.equal(y0, torch.zeros_like(u))
+
+
+def test_batch_zero_and_error_paths_on_device():
+    plan = fftconv.Plan(256, 512, 2, torch.float32)
+    k = torch.randn(2, 256, device="cuda")
+    kf = plan.filter_fft(k)
+    y = plan.forward(torch.empty(0, 2, 256, device="cuda"), kf)
+    assert tuple(y.shape) == (0, 2, 256)
+    with pytest.raises(ValueError):
+        plan.forward(torch.zeros(1, 3, 256, device="cuda"), kf)      # wrong H
+    lib = fftconv.load()
+    u = torch.zeros(1, 2, 256, device="cuda")
+    rc = lib.fftconv_forward(plan._h, u.data_ptr(), kf.data_ptr(), u.data_ptr(), 1, 2, 256, None, None)
+    assert rc == -1                                                   # y aliases u
+    rc = lib.fftconv_forward(plan._h, u.data_ptr(), kf.data_ptr(), torch.empty_like(u).data_ptr(), 1, 2, 128, None, None)
+    assert rc == -1                                                   # N differs from the plan's
+
+
+def test_frequency_sparse_filter_matches_masked_oracle_small():
+    w = synth.scaled(W["cfg5b"], B=2, H=3, N=256, fft_size=512, dtype="f32", alpha=(1e-2, 1e-1),
+                     keep_blocks=(0, 1, 14, 15), n_blocks=16)
+    err, _ = check_all_sequences(w)
+    assert err <= TOL["f32"]
+    err, _ = check_all_sequences(w, variant="skip")
+    assert err <= TOL["f32"]
+
+
+def test_partial_filter_small():
+    w = synth.scaled(W["cfg5a"], B=2, H=3, N=512, fft_size=1024, dtype="f32", alpha=(1e-2, 1e-1), Nk=64)
+    for variant in ("dense", "skip"):
+        err, _ = check_all_sequences(w, variant=variant)
+        assert err <= TOL["f32"]
