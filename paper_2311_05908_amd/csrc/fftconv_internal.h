@@ -27,6 +27,25 @@ enum Path { PATH_STAGED = 0, PATH_FUSED3 = 1, PATH_MULTIPASS = 2 };
 
 constexpr int MAX_FACTORS = 8;
 
+// Factor list of the staged transform, passed to kernels by value.
+struct FacList {
+    int nf;
+    int fac[MAX_FACTORS];
+};
+
+// Position, in the staged transform's output order, of natural frequency f:
+// f = sum_i k_i R_i (k_1 least significant) sits at sum_i k_i S_i (k_1 most significant).
+__host__ __device__ inline int64_t freq_to_pos(int64_t f, const FacList &fl, int64_t M)
+{
+    int64_t p = 0, S = M;
+    for (int i = 0; i < fl.nf; ++i) {
+        S /= fl.fac[i];
+        p += (f % fl.fac[i]) * S;
+        f /= fl.fac[i];
+    }
+    return p;
+}
+
 // Generic multi-kernel path: one launch per stage of the order-p decomposition,
 // complex intermediates in a caller-provided workspace.  Used for fp32 I/O, for
 // sizes without a fused kernel, and (in fp64) for every filter transform.
@@ -76,6 +95,7 @@ int staged_filter_transform(const fftconv_plan *p, const float *k, int64_t Nk, i
 // scatter of the fp64 spectra into the staged path's own k_f layout
 int staged_pack_kf(const fftconv_plan *p, const double2 *spec, int64_t h0, int64_t nh,
                    const uint8_t *keep_dev, int64_t n_blocks, void *kf, hipStream_t s);
+FacList staged_fac_list(const fftconv_plan *p);
 
 // ---- fused 3-stage path (fused3.hip)
 bool fused3_supported(int64_t N, int64_t M, int dtype);

@@ -1,10 +1,660 @@
-// placeholder until the fused kernel lands
+// Fused causal FFT convolution for 16-bit I/O, fft_size M = N1*N2*N3 with N1 = 32
+// (paper Algorithm 3: order-3 decomposition, whole sequence on chip, one HBM read
+// of u and one HBM write of y).  gfx950 only.
+//
+// What is different from the paper's kernel, and why
+//  * Two batch rows that share a channel are transformed together as one complex
+//    sequence z = u[b] + i*u[b+1].  The filter is real, so
+//    iFFT(FFT(z) . k_f) = conv(u[b],k) + i*conv(u[b+1],k): one complex transform
+//    serves two sequences and no spectrum unpacking is needed.  This plays the role
+//    of the paper's real-FFT trick (Section 3.1 "Domain-Specific Optimizations",
+//    Appendix A.1): it halves the transform work per sequence.
+//  * Implicit zero padding (Section 3.1): only the n1 < N1/2 half of the outermost
+//    DFT matrix is multiplied in the forward transform and only the n1 < N1/2 output
+//    rows (real and imaginary part = the two sequences) are formed in the inverse.
+//  * Every DFT-matrix product is a v_mfma_f32_16x16x32 (bf16 or f16 operands, fp32
+//    accumulate).  A complex Nx16 * 16x16 product is the real product
+//    [Xr Xi] * [[Gr Gi], [-Gi Gr]] with K = 32.
+//  * Stage-to-stage hand-off without a transpose (the paper's accumulator ->
+//    matrix_a reuse, Appendix A.2): an MFMA result leaves each lane with 4
+//    consecutive rows of one column; the next contraction runs over exactly those
+//    rows, and since a contraction does not care about the order of K, the constant
+//    matrix is stored with its K axis permuted to (4 rows) x (re, im) per lane.
+//    Only two exchanges per pair go through LDS (before the innermost forward
+//    stage and before the outermost inverse stage), both as packed 16-bit pairs.
+//  * Twiddles that depend only on (contracted index, output index, tile constant)
+//    are folded into per-tile DFT matrices; the others are fp32 multiplies on the
+//    accumulators.
+//
+// Index maps (time n = (n1*N2 + n2)*N3 + n3, frequency f = k1 + N1*k2 + N1*N2*k3):
+//   forward  A1[k1,n2,n3] = sum_{n1<N1/2} z[n1,n2,n3] W_N1^{n1 k1}
+//            A1 *= W_M^{k1 (N3 n2 + n3)}
+//            A2[k1,k2,n3] = sum_{n2} A1 W_N2^{n2 k2} W_{N2 N3}^{k2 n3}     (folded)
+//            A3[k1,k2,k3] = sum_{n3} A2 W_N3^{n3 k3};   A3 *= k_f[k1,k2,k3]
+//   inverse  B3[k1,k2,n3] = sum_{k3} A3 conj(W_N3^{k3 n3})
+//            B3 *= conj(W_M^{(k1 + N1 k2) n3})
+//            B2[k1,n2,n3] = sum_{k2} B3 conj(W_N2^{k2 n2} W_{N1 N2}^{k1 n2})  (folded)
+//            y[n1,n2,n3]  = sum_{k1} B2 conj(W_N1^{k1 n1}),  n1 < N1/2
+// Work split of a 512-thread workgroup (8 waves) on one pair:
+//   phase A (per n3):  stage 1, twiddle, stage 2      -> LDS[k1,k2,n3]
+//   phase B (per k1):  stage 3, k_f, inverse 3, twiddle, inverse 2 -> LDS in place
+//   phase C (per n3):  inverse stage 1                -> LDS staging -> HBM
+#include <cmath>
+#include <cstring>
+#include <vector>
+
 #include "fftconv_internal.h"
+
 namespace fftconv {
-bool fused3_supported(int64_t, int64_t, int) { return false; }
-int fused3_init(fftconv_plan *) { return FFTCONV_EUNSUPPORTED; }
-void fused3_destroy(fftconv_plan *) {}
-size_t fused3_kf_bytes(const fftconv_plan *) { return 0; }
-int fused3_pack_kf(const fftconv_plan *, const double2 *, int64_t, int64_t, const uint8_t *, int64_t, void *, hipStream_t) { return FFTCONV_EUNSUPPORTED; }
-int fused3_forward(const fftconv_plan *, const void *, const void *, void *, int64_t, hipStream_t) { return FFTCONV_EUNSUPPORTED; }
+
+namespace {
+
+constexpr int N1 = 32;
+constexpr int NT = 512;
+constexpr int NW = NT / 64;
+
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
+
+struct BF16 {
+    static __device__ __forceinline__ f32x4 mfma(uint4 a, uint4 b, f32x4 c)
+    {
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c,
+                                                       0, 0, 0);
+    }
+    static __device__ __forceinline__ uint32_t pack(float lo, float hi)
+    {
+        f32x2 v = {lo, hi};
+        return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+    }
+    static __device__ __forceinline__ uint16_t cvt(float x) { return __builtin_bit_cast(uint16_t, (__bf16)x); }
+};
+struct F16 {
+    static __device__ __forceinline__ f32x4 mfma(uint4 a, uint4 b, f32x4 c)
+    {
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0,
+                                                      0, 0);
+    }
+    static __device__ __forceinline__ uint32_t pack(float lo, float hi)
+    {
+        f32x2 v = {lo, hi};
+        return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));
+    }
+    static __device__ __forceinline__ uint16_t cvt(float x) { return __builtin_bit_cast(uint16_t, (_Float16)x); }
+};
+
+template <int N2, int N3> struct Geo {
+    static constexpr int M = N1 * N2 * N3;
+    static constexpr int R2 = N2 / 16, R3 = N3 / 16;
+    static constexpr int C3 = N3 / NW;           // n3 values per wave (phases A, C)
+    static constexpr int C1 = N1 / NW;           // k1 values per wave (phase B)
+    // exchange buffer, 32-bit words: X(k1,k2,n3) = n3*PN3 + k1*PK1 + k2.
+    // 4*PK1 and 4*PN3 are 16 mod 32, which spreads the 4 lane groups of a wave over the banks.
+    static constexpr int PK1 = N2 + 4;
+    static constexpr int PN3 = N1 * PK1 + 4;
+    static constexpr int XB_WORDS = N3 * PN3;
+    // staging of u / y, 16-bit elements: (s, n1, n2, n3) -> s*SU + n1*PQ1 + n2*PR + n3
+    static constexpr int PR = N3 + 2;
+    static constexpr int PQ1 = N2 * PR + 8;
+    static constexpr int SU = (N1 / 2) * PQ1;
+    static constexpr int UB_ELEMS = 2 * SU;
+    static constexpr size_t LDS_BYTES = (size_t)XB_WORDS * 4 + (size_t)UB_ELEMS * 2 * 2;
+    static constexpr int CHUNKS = M / 8 / NT;    // 16-byte chunks of a pair's input per thread
+    // table sizes (entries)
+    static constexpr int TAB1 = 2 * 2 * 64;                 // [ct][part][lane] uint4
+    static constexpr int TAB2 = N3 * R2 * R2 * 2 * 64;      // [n3][t][ct][part][lane]
+    static constexpr int TAB3 = R3 * R3 * 2 * 64;           // [t][ct][part][lane]
+    static constexpr int TAB2I = N1 * R2 * R2 * 2 * 64;     // [k1][t][ct][part][lane]
+    static constexpr int TAB1I = 2 * 2 * 64;                // [t][part][lane]
+    static constexpr int TWA = N3 * R2 * 2 * 4 * 64;        // [n3][rt][ct][r][lane] float2
+    static constexpr int TWB = N1 * R2 * R3 * 4 * 64;       // [k1][ct2][ct3][r][lane] float2
+    static constexpr int KF_PER_H = N1 * R2 * R3 * 4 * 64;  // == M
+};
+
+struct Consts {
+    const uint4 *tab1, *tab2, *tab3, *tab3i, *tab2i, *tab1i;
+    const float2 *twa, *twb;
+};
+
+__device__ __forceinline__ void cmul_ip(float &re, float &im, float2 w)
+{
+    float r = re * w.x - im * w.y;
+    float i = re * w.y + im * w.x;
+    re = r;
+    im = i;
 }
+
+template <int N2, int N3, typename TT, bool REGC>
+__global__ void __launch_bounds__(NT) k_fused3(const uint16_t *__restrict__ u, uint16_t *__restrict__ y,
+                                              const float2 *__restrict__ kf, Consts cs, int B, int H, int N,
+                                              int pairs_per_wg)
+{
+    using G = Geo<N2, N3>;
+    constexpr int R2 = G::R2, R3 = G::R3, C3 = G::C3, C1 = G::C1;
+    extern __shared__ uint32_t smem[];
+    uint32_t *XB = smem;
+    uint16_t *UB = (uint16_t *)(smem + G::XB_WORDS);
+    uint16_t *YB = UB + G::UB_ELEMS;
+
+    const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, q = l >> 4, c16 = l & 15;
+    const int h = blockIdx.x;
+    const int npairs = (B + 1) / 2;
+    const int pair0 = blockIdx.y * pairs_per_wg;
+    const int pair1 = min(npairs, pair0 + pairs_per_wg);
+    if (pair0 >= pair1) return;
+
+    // ---------------- constants (per-lane operand tables) ----------------
+    uint4 tab1[2][2], tab1i[2][2], tab3[R3][R3][2], tab3i[R3][R3][2];
+    uint4 tab2[C3][R2][R2][2], tab2i[C1][R2][R2][2];
+    float2 twa[C3][R2][2][4], twb[C1][R2][R3][4], kfr[C1][R2][R3][4];
+
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            tab1[a][p] = cs.tab1[(a * 2 + p) * 64 + l];
+            tab1i[a][p] = cs.tab1i[(a * 2 + p) * 64 + l];
+        }
+#pragma unroll
+    for (int t = 0; t < R3; ++t)
+#pragma unroll
+        for (int c = 0; c < R3; ++c)
+#pragma unroll
+            for (int p = 0; p < 2; ++p) {
+                tab3[t][c][p] = cs.tab3[((t * R3 + c) * 2 + p) * 64 + l];
+                tab3i[t][c][p] = cs.tab3i[((t * R3 + c) * 2 + p) * 64 + l];
+            }
+    auto load_A = [&](int i) {
+        const int c = w * C3 + i;
+#pragma unroll
+        for (int t = 0; t < R2; ++t)
+#pragma unroll
+            for (int ct = 0; ct < R2; ++ct)
+#pragma unroll
+                for (int p = 0; p < 2; ++p)
+                    tab2[i][t][ct][p] = cs.tab2[(((c * R2 + t) * R2 + ct) * 2 + p) * 64 + l];
+#pragma unroll
+        for (int rt = 0; rt < R2; ++rt)
+#pragma unroll
+            for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    twa[i][rt][ct][r] = cs.twa[(((c * R2 + rt) * 2 + ct) * 4 + r) * 64 + l];
+    };
+    auto load_B = [&](int i) {
+        const int c = w * C1 + i;
+#pragma unroll
+        for (int t = 0; t < R2; ++t)
+#pragma unroll
+            for (int ct = 0; ct < R2; ++ct)
+#pragma unroll
+                for (int p = 0; p < 2; ++p)
+                    tab2i[i][t][ct][p] = cs.tab2i[(((c * R2 + t) * R2 + ct) * 2 + p) * 64 + l];
+#pragma unroll
+        for (int a = 0; a < R2; ++a)
+#pragma unroll
+            for (int b = 0; b < R3; ++b)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int idx = (((c * R2 + a) * R3 + b) * 4 + r) * 64 + l;
+                    twb[i][a][b][r] = cs.twb[idx];
+                    kfr[i][a][b][r] = kf[(size_t)h * G::KF_PER_H + idx];
+                }
+    };
+    if constexpr (REGC) {
+#pragma unroll
+        for (int i = 0; i < C3; ++i) load_A(i);
+#pragma unroll
+        for (int i = 0; i < C1; ++i) load_B(i);
+    }
+
+    // ---------------- input prefetch (registers) ----------------
+    uint4 pre[G::CHUNKS];
+    auto issue_loads = [&](int pair) {
+#pragma unroll
+        for (int j = 0; j < G::CHUNKS; ++j) {
+            const int ch = tid + NT * j;                 // chunk id within the pair
+            const int s = ch / (G::M / 16);
+            const int n = (ch % (G::M / 16)) * 8;
+            const int b = 2 * pair + s;
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (b < B && n < N) v = *(const uint4 *)(u + ((size_t)b * H + h) * N + n);
+            pre[j] = v;
+        }
+    };
+    issue_loads(pair0);
+
+    for (int pair = pair0; pair < pair1; ++pair) {
+        // ---- P0: prefetched input -> UB
+#pragma unroll
+        for (int j = 0; j < G::CHUNKS; ++j) {
+            const int ch = tid + NT * j;
+            const int s = ch / (G::M / 16);
+            const int n = (ch % (G::M / 16)) * 8;
+            const int n3 = n % N3, n2 = (n / N3) % N2, n1 = n / (N2 * N3);
+            uint32_t *dst = (uint32_t *)(UB + s * G::SU + n1 * G::PQ1 + n2 * G::PR + n3);
+            dst[0] = pre[j].x;
+            dst[1] = pre[j].y;
+            dst[2] = pre[j].z;
+            dst[3] = pre[j].w;
+        }
+        __syncthreads();
+        if (pair + 1 < pair1) issue_loads(pair + 1);
+
+        // ---- phase A: per n3 = c: stage 1, twiddle, stage 2 -> XB
+#pragma unroll
+        for (int i = 0; i < C3; ++i) {
+            const int c = w * C3 + i;
+            if constexpr (!REGC) load_A(i);
+            uint4 x2[2][R2];                              // stage-2 operands [k1 tile][K step = n2 tile]
+#pragma unroll
+            for (int rt = 0; rt < R2; ++rt) {
+                // operand of stage 1: row n2 = 16 rt + c16, slots (2r+s) = u_s[n1 = 4q + r]
+                const uint16_t *p0 = UB + (4 * q) * G::PQ1 + (16 * rt + c16) * G::PR + c;
+                uint32_t d[4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    d[r] = (uint32_t)p0[r * G::PQ1] | ((uint32_t)p0[G::SU + r * G::PQ1] << 16);
+                const uint4 x1 = make_uint4(d[0], d[1], d[2], d[3]);
+#pragma unroll
+                for (int ct = 0; ct < 2; ++ct) {
+                    f32x4 z = {0.f, 0.f, 0.f, 0.f};
+                    f32x4 dre = TT::mfma(x1, tab1[ct][0], z);
+                    f32x4 dim = TT::mfma(x1, tab1[ct][1], z);
+                    uint32_t o[4];
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        float re = dre[r], im = dim[r];
+                        cmul_ip(re, im, twa[i][rt][ct][r]);
+                        o[r] = TT::pack(re, im);
+                    }
+                    x2[ct][rt] = make_uint4(o[0], o[1], o[2], o[3]);
+                }
+            }
+#pragma unroll
+            for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+                for (int ct2 = 0; ct2 < R2; ++ct2) {
+                    f32x4 dre = {0.f, 0.f, 0.f, 0.f}, dim = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int t = 0; t < R2; ++t) {
+                        dre = TT::mfma(x2[ct][t], tab2[i][t][ct2][0], dre);
+                        dim = TT::mfma(x2[ct][t], tab2[i][t][ct2][1], dim);
+                    }
+                    // lane: k2 = 16 ct2 + c16; reg r: k1 = 16 ct + 4q + r
+                    uint32_t *dst = XB + c * G::PN3 + (16 * ct + 4 * q) * G::PK1 + 16 * ct2 + c16;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) dst[r * G::PK1] = TT::pack(dre[r], dim[r]);
+                }
+        }
+        __syncthreads();
+
+        // ---- phase B: per k1 = c: stage 3, k_f, inverse 3, twiddle, inverse 2 -> XB in place
+#pragma unroll
+        for (int i = 0; i < C1; ++i) {
+            const int c = w * C1 + i;
+            if constexpr (!REGC) load_B(i);
+            uint4 x3[R2][R3];
+#pragma unroll
+            for (int ct2 = 0; ct2 < R2; ++ct2)
+#pragma unroll
+                for (int t = 0; t < R3; ++t) {
+                    const uint32_t *src = XB + (16 * t + 4 * q) * G::PN3 + c * G::PK1 + 16 * ct2 + c16;
+                    x3[ct2][t] = make_uint4(src[0], src[G::PN3], src[2 * G::PN3], src[3 * G::PN3]);
+                }
+            uint4 x3i[R2][R3];                            // [k2 tile][K step = k3 tile]
+#pragma unroll
+            for (int ct2 = 0; ct2 < R2; ++ct2)
+#pragma unroll
+                for (int ct3 = 0; ct3 < R3; ++ct3) {
+                    f32x4 dre = {0.f, 0.f, 0.f, 0.f}, dim = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int t = 0; t < R3; ++t) {        // matrix is the A operand: rows k3, data columns k2
+                        dre = TT::mfma(tab3[t][ct3][0], x3[ct2][t], dre);
+                        dim = TT::mfma(tab3[t][ct3][1], x3[ct2][t], dim);
+                    }
+                    uint32_t o[4];
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        float re = dre[r], im = dim[r];
+                        cmul_ip(re, im, kfr[i][ct2][ct3][r]);
+                        o[r] = TT::pack(re, im);
+                    }
+                    x3i[ct2][ct3] = make_uint4(o[0], o[1], o[2], o[3]);
+                }
+            uint4 x2i[R3][R2];                            // [n3 tile][K step = k2 tile]
+#pragma unroll
+            for (int ct2 = 0; ct2 < R2; ++ct2)
+#pragma unroll
+                for (int cn3 = 0; cn3 < R3; ++cn3) {
+                    f32x4 dre = {0.f, 0.f, 0.f, 0.f}, dim = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int t = 0; t < R3; ++t) {
+                        dre = TT::mfma(x3i[ct2][t], tab3i[t][cn3][0], dre);
+                        dim = TT::mfma(x3i[ct2][t], tab3i[t][cn3][1], dim);
+                    }
+                    uint32_t o[4];
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        float re = dre[r], im = dim[r];
+                        cmul_ip(re, im, twb[i][ct2][cn3][r]);
+                        o[r] = TT::pack(re, im);
+                    }
+                    x2i[cn3][ct2] = make_uint4(o[0], o[1], o[2], o[3]);
+                }
+#pragma unroll
+            for (int cn3 = 0; cn3 < R3; ++cn3)
+#pragma unroll
+                for (int cn2 = 0; cn2 < R2; ++cn2) {
+                    f32x4 dre = {0.f, 0.f, 0.f, 0.f}, dim = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int t = 0; t < R2; ++t) {
+                        dre = TT::mfma(x2i[cn3][t], tab2i[i][t][cn2][0], dre);
+                        dim = TT::mfma(x2i[cn3][t], tab2i[i][t][cn2][1], dim);
+                    }
+                    // lane: n2 = 16 cn2 + c16; reg r: n3 = 16 cn3 + 4q + r
+                    uint32_t *dst = XB + (16 * cn3 + 4 * q) * G::PN3 + c * G::PK1 + 16 * cn2 + c16;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) dst[r * G::PN3] = TT::pack(dre[r], dim[r]);
+                }
+        }
+        __syncthreads();
+
+        // ---- phase C: per n3 = c: inverse stage 1 (n1 < 16; re -> row b, im -> row b+1) -> YB
+#pragma unroll
+        for (int i = 0; i < C3; ++i) {
+            const int c = w * C3 + i;
+#pragma unroll
+            for (int cn2 = 0; cn2 < R2; ++cn2) {
+                f32x4 dre = {0.f, 0.f, 0.f, 0.f}, dim = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    const uint32_t *src = XB + c * G::PN3 + (16 * t + 4 * q) * G::PK1 + 16 * cn2 + c16;
+                    const uint4 x = make_uint4(src[0], src[G::PK1], src[2 * G::PK1], src[3 * G::PK1]);
+                    dre = TT::mfma(tab1i[t][0], x, dre);
+                    dim = TT::mfma(tab1i[t][1], x, dim);
+                }
+                // lane: n2 = 16 cn2 + c16; reg r: n1 = 4q + r
+                uint16_t *dst = YB + (4 * q) * G::PQ1 + (16 * cn2 + c16) * G::PR + c;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    dst[r * G::PQ1] = TT::cvt(dre[r]);
+                    dst[G::SU + r * G::PQ1] = TT::cvt(dim[r]);
+                }
+            }
+        }
+        __syncthreads();
+
+        // ---- store: YB -> y, 16 bytes per lane, coalesced
+#pragma unroll
+        for (int j = 0; j < G::CHUNKS; ++j) {
+            const int ch = tid + NT * j;
+            const int s = ch / (G::M / 16);
+            const int n = (ch % (G::M / 16)) * 8;
+            const int b = 2 * pair + s;
+            const int n3 = n % N3, n2 = (n / N3) % N2, n1 = n / (N2 * N3);
+            const uint32_t *src = (const uint32_t *)(YB + s * G::SU + n1 * G::PQ1 + n2 * G::PR + n3);
+            const uint4 v = make_uint4(src[0], src[1], src[2], src[3]);
+            if (b < B && n < N) *(uint4 *)(y + ((size_t)b * H + h) * N + n) = v;
+        }
+    }
+}
+
+// k_f in the fused kernel's per-lane order: [h][k1][k2 tile][k3 tile][r][lane] float2, where the
+// lane holds k2 = 16 tile + lane%16 and k3 = 16 tile + 4 (lane/16) + r.
+template <int N2, int N3>
+__global__ void k_pack_fused3(const double2 *spec, float2 *kf, FacList fl, int64_t h0, int64_t nh,
+                              const uint8_t *keep, int64_t n_blocks)
+{
+    using G = Geo<N2, N3>;
+    constexpr int64_t M = G::M;
+    int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= nh * M) return;
+    int64_t h = idx / M, f = idx % M;
+    int k1 = (int)(f % N1), k2 = (int)((f / N1) % N2), k3 = (int)(f / (N1 * N2));
+    int lane = ((k3 % 16) / 4) * 16 + (k2 % 16), r = k3 % 4;
+    int64_t dst = ((((int64_t)k1 * G::R2 + k2 / 16) * G::R3 + k3 / 16) * 4 + r) * 64 + lane;
+    double2 v = spec[h * M + freq_to_pos(f, fl, M)];
+    double sc = 1.0 / (double)M;
+    if (keep && !keep[f / (M / n_blocks)]) sc = 0.0;
+    kf[(h0 + h) * M + dst] = make_float2((float)(v.x * sc), (float)(v.y * sc));
+}
+
+// ---------------------------------------------------------------- host side
+
+uint16_t to_bf16(double x)
+{
+    float f = (float)x;
+    uint32_t b;
+    std::memcpy(&b, &f, 4);
+    b += 0x7fffu + ((b >> 16) & 1u);       // round to nearest even (finite inputs only)
+    return (uint16_t)(b >> 16);
+}
+uint16_t to_f16(double x)
+{
+    _Float16 hv = (_Float16)(float)x;
+    uint16_t b;
+    std::memcpy(&b, &hv, 2);
+    return b;
+}
+
+struct Cplx { double re, im; };
+Cplx wpow(int64_t M, int64_t e)             // exp(-2 pi i e / M)
+{
+    const double two_pi = 6.283185307179586476925286766559;
+    e %= M;
+    if (e < 0) e += M;
+    double a = two_pi * (double)e / (double)M;
+    return {std::cos(a), -std::sin(a)};
+}
+Cplx cmulh(Cplx a, Cplx b) { return {a.re * b.re - a.im * b.im, a.re * b.im + a.im * b.re}; }
+Cplx conjh(Cplx a) { return {a.re, -a.im}; }
+
+// One MFMA operand (64 lanes x 8 16-bit slots) of the real form of a complex matrix G:
+// lane (c16, q), slot 2r+s multiplies data element e_in = 16 t + 4 q + r, part s (0 = re, 1 = im),
+// and contributes to output e_out = 16 ct + c16, part `part`.
+template <typename Fn>
+void fill_operand(uint16_t *dst, bool f16, int t, int ct, int part, Fn G)
+{
+    for (int lane = 0; lane < 64; ++lane) {
+        int c16 = lane % 16, q = lane / 16;
+        for (int r = 0; r < 4; ++r) {
+            Cplx g = G(16 * t + 4 * q + r, 16 * ct + c16);
+            double v0 = part == 0 ? g.re : g.im;     // multiplies the real part of the data
+            double v1 = part == 0 ? -g.im : g.re;    // multiplies the imaginary part
+            dst[lane * 8 + 2 * r + 0] = f16 ? to_f16(v0) : to_bf16(v0);
+            dst[lane * 8 + 2 * r + 1] = f16 ? to_f16(v1) : to_bf16(v1);
+        }
+    }
+}
+
+template <int N2, int N3>
+int build_tables(fftconv_plan *p)
+{
+    using G = Geo<N2, N3>;
+    constexpr int64_t M = G::M;
+    const bool f16 = p->dtype == FFTCONV_F16;
+    const size_t n_u4 = (size_t)G::TAB1 + G::TAB2 + 2 * (size_t)G::TAB3 + G::TAB2I + G::TAB1I;
+    const size_t n_f2 = (size_t)G::TWA + G::TWB;
+    std::vector<uint16_t> ops(n_u4 * 8);
+    std::vector<float2> tw(n_f2);
+    size_t o = 0;
+    auto next = [&]() { uint16_t *d = ops.data() + o * 8; o += 64; return d; };
+    // tab1 [ct][part]: W_N1^{n1 k1}, n1 < 16
+    for (int ct = 0; ct < 2; ++ct)
+        for (int part = 0; part < 2; ++part)
+            fill_operand(next(), f16, 0, ct, part, [&](int n1, int k1) { return wpow(N1, (int64_t)n1 * k1); });
+    // tab2 [n3][t][ct][part]: W_N2^{n2 k2} W_{N2 N3}^{k2 n3}
+    for (int n3 = 0; n3 < N3; ++n3)
+        for (int t = 0; t < G::R2; ++t)
+            for (int ct = 0; ct < G::R2; ++ct)
+                for (int part = 0; part < 2; ++part)
+                    fill_operand(next(), f16, t, ct, part, [&](int n2, int k2) {
+                        return cmulh(wpow(N2, (int64_t)n2 * k2), wpow((int64_t)N2 * N3, (int64_t)k2 * n3));
+                    });
+    // tab3 [t][ct][part]: W_N3^{n3 k3}
+    for (int t = 0; t < G::R3; ++t)
+        for (int ct = 0; ct < G::R3; ++ct)
+            for (int part = 0; part < 2; ++part)
+                fill_operand(next(), f16, t, ct, part, [&](int n3, int k3) { return wpow(N3, (int64_t)n3 * k3); });
+    // tab3i: conj(W_N3^{k3 n3})
+    for (int t = 0; t < G::R3; ++t)
+        for (int ct = 0; ct < G::R3; ++ct)
+            for (int part = 0; part < 2; ++part)
+                fill_operand(next(), f16, t, ct, part,
+                             [&](int k3, int n3) { return conjh(wpow(N3, (int64_t)n3 * k3)); });
+    // tab2i [k1][t][ct][part]: conj(W_N2^{k2 n2} W_{N1 N2}^{k1 n2})
+    for (int k1 = 0; k1 < N1; ++k1)
+        for (int t = 0; t < G::R2; ++t)
+            for (int ct = 0; ct < G::R2; ++ct)
+                for (int part = 0; part < 2; ++part)
+                    fill_operand(next(), f16, t, ct, part, [&](int k2, int n2) {
+                        return conjh(cmulh(wpow(N2, (int64_t)n2 * k2), wpow((int64_t)N1 * N2, (int64_t)k1 * n2)));
+                    });
+    // tab1i [t][part]: conj(W_N1^{k1 n1}), output rows n1 < 16
+    for (int t = 0; t < 2; ++t)
+        for (int part = 0; part < 2; ++part)
+            fill_operand(next(), f16, t, 0, part, [&](int k1, int n1) { return conjh(wpow(N1, (int64_t)n1 * k1)); });
+    if (o != n_u4) {
+        set_error("fused3: operand table size mismatch");
+        return FFTCONV_EINVAL;
+    }
+    // twa [n3][rt][ct][r][lane]: W_M^{k1 (N3 n2 + n3)}, k1 = 16 ct + c16, n2 = 16 rt + 4 q + r
+    size_t w = 0;
+    for (int n3 = 0; n3 < N3; ++n3)
+        for (int rt = 0; rt < G::R2; ++rt)
+            for (int ct = 0; ct < 2; ++ct)
+                for (int r = 0; r < 4; ++r)
+                    for (int lane = 0; lane < 64; ++lane) {
+                        int k1 = 16 * ct + lane % 16, n2 = 16 * rt + 4 * (lane / 16) + r;
+                        Cplx v = wpow(M, (int64_t)k1 * ((int64_t)N3 * n2 + n3));
+                        tw[w++] = make_float2((float)v.re, (float)v.im);
+                    }
+    // twb [k1][ct2][ct3][r][lane]: conj(W_M^{(k1 + N1 k2) n3}), n3 = 16 ct3 + c16, k2 = 16 ct2 + 4 q + r
+    for (int k1 = 0; k1 < N1; ++k1)
+        for (int ct2 = 0; ct2 < G::R2; ++ct2)
+            for (int ct3 = 0; ct3 < G::R3; ++ct3)
+                for (int r = 0; r < 4; ++r)
+                    for (int lane = 0; lane < 64; ++lane) {
+                        int n3 = 16 * ct3 + lane % 16, k2 = 16 * ct2 + 4 * (lane / 16) + r;
+                        Cplx v = conjh(wpow(M, ((int64_t)k1 + (int64_t)N1 * k2) * n3));
+                        tw[w++] = make_float2((float)v.re, (float)v.im);
+                    }
+    const size_t bytes = n_u4 * 16 + n_f2 * 8;
+    FC_HIP(hipMalloc(&p->f3.consts, bytes));
+    p->f3.consts_bytes = bytes;
+    FC_HIP(hipMemcpy(p->f3.consts, ops.data(), n_u4 * 16, hipMemcpyHostToDevice));
+    FC_HIP(hipMemcpy((char *)p->f3.consts + n_u4 * 16, tw.data(), n_f2 * 8, hipMemcpyHostToDevice));
+    return FFTCONV_OK;
+}
+
+template <int N2, int N3>
+Consts consts_of(const fftconv_plan *p)
+{
+    using G = Geo<N2, N3>;
+    Consts c;
+    const uint4 *b = (const uint4 *)p->f3.consts;
+    c.tab1 = b;
+    c.tab2 = c.tab1 + G::TAB1;
+    c.tab3 = c.tab2 + G::TAB2;
+    c.tab3i = c.tab3 + G::TAB3;
+    c.tab2i = c.tab3i + G::TAB3;
+    c.tab1i = c.tab2i + G::TAB2I;
+    c.twa = (const float2 *)(c.tab1i + G::TAB1I);
+    c.twb = c.twa + G::TWA;
+    return c;
+}
+
+template <int N2, int N3, typename TT, bool REGC>
+int launch(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, hipStream_t s)
+{
+    using G = Geo<N2, N3>;
+    auto kern = k_fused3<N2, N3, TT, REGC>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        FC_HIP(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   (int)G::LDS_BYTES));
+        attr_set = true;
+    }
+    const int npairs = (int)((B + 1) / 2);
+    // enough workgroups to fill 256 CUs a few times over, but keep k_f[h] reuse when H alone does that
+    int split = 1;
+    while ((int64_t)p->H * split < 1024 && split * 2 <= npairs) split *= 2;
+    const int ppw = (npairs + split - 1) / split;
+    const int ny = (npairs + ppw - 1) / ppw;
+    hipLaunchKernelGGL(kern, dim3((unsigned)p->H, (unsigned)ny), dim3(NT), G::LDS_BYTES, s, (const uint16_t *)u,
+                       (uint16_t *)y, (const float2 *)kf, consts_of<N2, N3>(p), (int)B, (int)p->H, (int)p->N, ppw);
+    FC_HIP(hipGetLastError());
+    return FFTCONV_OK;
+}
+
+}  // namespace
+
+bool fused3_supported(int64_t N, int64_t M, int dtype)
+{
+    if (dtype != FFTCONV_F16 && dtype != FFTCONV_BF16) return false;
+    if (M != 8192) return false;
+    return N <= M / 2 && N % 8 == 0;
+}
+
+int fused3_init(fftconv_plan *p)
+{
+    p->f3.N1 = N1;
+    switch (p->M) {
+    case 8192:
+        p->f3.N2 = 16;
+        p->f3.N3 = 16;
+        return build_tables<16, 16>(p);
+    default:
+        set_error("fused3: no kernel for fft_size=%lld", (long long)p->M);
+        return FFTCONV_EUNSUPPORTED;
+    }
+}
+
+void fused3_destroy(fftconv_plan *p)
+{
+    if (p->f3.consts) (void)hipFree(p->f3.consts);
+    p->f3.consts = nullptr;
+}
+
+size_t fused3_kf_bytes(const fftconv_plan *p) { return (size_t)(p->H * p->M) * sizeof(float2); }
+
+int fused3_pack_kf(const fftconv_plan *p, const double2 *spec, int64_t h0, int64_t nh, const uint8_t *keep_dev,
+                   int64_t n_blocks, void *kf, hipStream_t s)
+{
+    const int bs = 256;
+    const unsigned grid = (unsigned)((nh * p->M + bs - 1) / bs);
+    switch (p->M) {
+    case 8192:
+        hipLaunchKernelGGL((k_pack_fused3<16, 16>), dim3(grid), dim3(bs), 0, s, spec, (float2 *)kf,
+                           staged_fac_list(p), h0, nh, keep_dev, n_blocks);
+        break;
+    default:
+        set_error("fused3: no kernel for fft_size=%lld", (long long)p->M);
+        return FFTCONV_EUNSUPPORTED;
+    }
+    FC_HIP(hipGetLastError());
+    return FFTCONV_OK;
+}
+
+int fused3_forward(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, hipStream_t s)
+{
+    if (((uintptr_t)u | (uintptr_t)y) & 15) {
+        set_error("fftconv_forward: u and y must be 16-byte aligned for this plan");
+        return FFTCONV_EINVAL;
+    }
+    const bool f16 = p->dtype == FFTCONV_F16;
+    switch (p->M) {
+    case 8192:
+        return f16 ? launch<16, 16, F16, true>(p, u, kf, y, B, s) : launch<16, 16, BF16, true>(p, u, kf, y, B, s);
+    default:
+        set_error("fused3: no kernel for fft_size=%lld", (long long)p->M);
+        return FFTCONV_EUNSUPPORTED;
+    }
+}
+
+}  // namespace fftconv

@@ -25,11 +25,6 @@ namespace fftconv {
 
 namespace {
 
-struct FacList {
-    int nf;
-    int fac[MAX_FACTORS];
-};
-
 template <typename T> struct C2;
 template <> struct C2<float> { using type = float2; };
 template <> struct C2<double> { using type = double2; };
@@ -144,17 +139,6 @@ __global__ void k_store_real(const float2 *x, Out *y, int64_t N, int64_t M, int6
     store_real(y, idx, x[row * M + n].x);
 }
 
-__host__ __device__ inline int64_t freq_to_pos(int64_t f, const FacList &fl, int64_t M)
-{
-    int64_t p = 0, S = M;
-    for (int i = 0; i < fl.nf; ++i) {
-        S /= fl.fac[i];
-        p += (f % fl.fac[i]) * S;
-        f /= fl.fac[i];
-    }
-    return p;
-}
-
 // spectra in position order (fp64) -> staged k_f (fp32 pairs, same position order), scaled 1/M,
 // with dropped frequency blocks zeroed.
 __global__ void k_pack_staged(const double2 *spec, float2 *kf, FacList fl, int64_t M, int64_t h0, int64_t nh,
@@ -170,13 +154,7 @@ __global__ void k_pack_staged(const double2 *spec, float2 *kf, FacList fl, int64
     kf[(h0 + h) * M + p] = make_float2((float)(v.x * sc), (float)(v.y * sc));
 }
 
-FacList fac_list(const fftconv_plan *p)
-{
-    FacList fl;
-    fl.nf = p->st.nf;
-    for (int i = 0; i < MAX_FACTORS; ++i) fl.fac[i] = (int)p->st.fac[i];
-    return fl;
-}
+FacList fac_list(const fftconv_plan *p) { return staged_fac_list(p); }
 
 inline unsigned grid_for(int64_t n, int bs) { return (unsigned)((n + bs - 1) / bs); }
 
@@ -340,11 +318,12 @@ int staged_pack_kf(const fftconv_plan *p, const double2 *spec, int64_t h0, int64
     return FFTCONV_OK;
 }
 
-// frequency -> position in the staged order (host side; used by other paths' packers)
-int64_t staged_freq_to_pos(const fftconv_plan *p, int64_t f)
+FacList staged_fac_list(const fftconv_plan *p)
 {
-    FacList fl = fac_list(p);
-    return freq_to_pos(f, fl, p->M);
+    FacList fl;
+    fl.nf = p->st.nf;
+    for (int i = 0; i < MAX_FACTORS; ++i) fl.fac[i] = (int)p->st.fac[i];
+    return fl;
 }
 
 }  // namespace fftconv

@@ -75,3 +75,23 @@ def test_partial_filter_small():
     for variant in ("dense", "skip"):
         err, _ = check_all_sequences(w, variant=variant)
         assert err <= TOL["f32"]
+
+
+# ---------------------------------------------------------------- fused 3-stage MFMA path
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("B,H,N", [
+    (2, 1, 4096),       # one pair, one channel
+    (3, 5, 4096),       # odd batch: the last pair has no partner row
+    (8, 3, 4096),
+    (1, 2, 4096),       # B = 1
+    (4, 2, 2048),       # N < fft_size/2: the tail of the padded half is implicit zeros too
+    (2, 2, 1000),       # ragged N (multiple of 8)
+])
+def test_fused3_fft8192(dtype, B, H, N):
+    w = synth.scaled(W["cfg2"], B=B, H=H, N=N, fft_size=8192, dtype=dtype)
+    err, plan = check_all_sequences(w)
+    print("fused 8192 %s B=%d H=%d N=%d path=%s factors=%s err=%.3e" % (dtype, B, H, N, plan.path, plan.factors, err),
+          flush=True)
+    assert plan.path == "fused3"
+    assert err <= TOL[dtype]
