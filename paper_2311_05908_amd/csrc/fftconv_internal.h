@@ -59,6 +59,7 @@ struct StagedTables {
 // Fused single-kernel path for 16-bit I/O, fft_size = N1*N2*N3 (Algorithm 3).
 struct Fused3Tables {
     int N1 = 0, N2 = 0, N3 = 0;
+    int num_cu = 0;                   // compute units of the plan's device (persistent grid size)
     void *consts = nullptr;           // operand tables in the kernel's lane order
     size_t consts_bytes = 0;
 };

@@ -40,10 +40,19 @@
 //   phase B (per k1):  stage 3, k_f, inverse 3, twiddle, inverse 2 -> LDS in place
 //   phase C (per n3):  inverse stage 1                -> LDS staging -> HBM
 #include <cmath>
+#include <cstdlib>
 #include <cstring>
 #include <vector>
 
 #include "fftconv_internal.h"
+
+// Timing probes (development builds only, -DFUSED3_PROBE): a launch-time mask switches whole
+// phases off so their cost can be read from the difference.  Results are then meaningless.
+#ifdef FUSED3_PROBE
+#define PROBE_ON(bit) (!(probe & (bit)))
+#else
+#define PROBE_ON(bit) true
+#endif
 
 namespace fftconv {
 
@@ -104,6 +113,7 @@ template <int N2, int N3> struct Geo {
     static constexpr int UB_ELEMS = 2 * SU;
     static constexpr size_t LDS_BYTES = (size_t)XB_WORDS * 4 + (size_t)UB_ELEMS * 2 * 2;
     static constexpr int CHUNKS = M / 8 / NT;    // 16-byte chunks of a pair's input per thread
+    static constexpr int CPS = CHUNKS / 2;       // ... per row of the pair
     // table sizes (entries)
     static constexpr int TAB1 = 2 * 2 * 64;                 // [ct][part][lane] uint4
     static constexpr int TAB2 = N3 * R2 * R2 * 2 * 64;      // [n3][t][ct][part][lane]
@@ -131,7 +141,7 @@ __device__ __forceinline__ void cmul_ip(float &re, float &im, float2 w)
 template <int N2, int N3, typename TT, bool REGC>
 __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *__restrict__ u, uint16_t *__restrict__ y,
                                               const float2 *__restrict__ kf, Consts cs, int B, int H, int N,
-                                              int pairs_per_wg)
+                                              int probe)
 {
     using G = Geo<N2, N3>;
     constexpr int R2 = G::R2, R3 = G::R3, C3 = G::C3, C1 = G::C1;
@@ -141,11 +151,13 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *__restrict__ u, u
     uint16_t *YB = UB + G::UB_ELEMS;
 
     const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, q = l >> 4, c16 = l & 15;
-    const int h = blockIdx.x;
+    // Persistent workgroup: a contiguous range [t0, t1) of work items t = h * npairs + pair, so the
+    // constant tables are loaded once and k_f[h] once per channel the range touches.
     const int npairs = (B + 1) / 2;
-    const int pair0 = blockIdx.y * pairs_per_wg;
-    const int pair1 = min(npairs, pair0 + pairs_per_wg);
-    if (pair0 >= pair1) return;
+    const long long T = (long long)H * npairs;
+    const int t0 = (int)(T * blockIdx.x / gridDim.x);
+    const int t1 = (int)(T * (blockIdx.x + 1) / gridDim.x);
+    if (t0 >= t1) return;
 
     // ---------------- constants (per-lane operand tables) ----------------
     uint4 tab1[2][2], tab1i[2][2], tab3[R3][R3][2], tab3i[R3][R3][2];
@@ -199,11 +211,18 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *__restrict__ u, u
 #pragma unroll
             for (int b = 0; b < R3; ++b)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int idx = (((c * R2 + a) * R3 + b) * 4 + r) * 64 + l;
-                    twb[i][a][b][r] = cs.twb[idx];
-                    kfr[i][a][b][r] = kf[(size_t)h * G::KF_PER_H + idx];
-                }
+                for (int r = 0; r < 4; ++r)
+                    twb[i][a][b][r] = cs.twb[(((c * R2 + a) * R3 + b) * 4 + r) * 64 + l];
+    };
+    auto load_kf = [&](int i, int h) {
+        const int c = w * C1 + i;
+#pragma unroll
+        for (int a = 0; a < R2; ++a)
+#pragma unroll
+            for (int b = 0; b < R3; ++b)
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    kfr[i][a][b][r] = kf[(size_t)h * G::KF_PER_H + (((c * R2 + a) * R3 + b) * 4 + r) * 64 + l];
     };
     if constexpr (REGC) {
 #pragma unroll
@@ -214,27 +233,25 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *__restrict__ u, u
 
     // ---------------- input prefetch (registers) ----------------
     uint4 pre[G::CHUNKS];
-    auto issue_loads = [&](int pair) {
+    auto issue_loads = [&](int t) {
+        const int h = t / npairs, pair = t - h * npairs;
 #pragma unroll
         for (int j = 0; j < G::CHUNKS; ++j) {
-            const int ch = tid + NT * j;                 // chunk id within the pair
-            const int s = ch / (G::M / 16);
-            const int n = (ch % (G::M / 16)) * 8;
+            const int s = j / G::CPS;                    // which row of the pair (wave-uniform)
+            const int n = (tid + NT * (j % G::CPS)) * 8;
             const int b = 2 * pair + s;
             uint4 v = make_uint4(0, 0, 0, 0);
-            if (b < B && n < N) v = *(const uint4 *)(u + ((size_t)b * H + h) * N + n);
+            const uint16_t *row = u + ((size_t)b * H + h) * N;
+            if (PROBE_ON(8) && t < t1 && b < B && n < N) v = *(const uint4 *)(row + n);
             pre[j] = v;
         }
     };
-    issue_loads(pair0);
-
-    for (int pair = pair0; pair < pair1; ++pair) {
-        // ---- P0: prefetched input -> UB
+    // prefetched input -> UB (padded layout)
+    auto stage_in = [&]() {
 #pragma unroll
         for (int j = 0; j < G::CHUNKS; ++j) {
-            const int ch = tid + NT * j;
-            const int s = ch / (G::M / 16);
-            const int n = (ch % (G::M / 16)) * 8;
+            const int s = j / G::CPS;
+            const int n = (tid + NT * (j % G::CPS)) * 8;
             const int n3 = n % N3, n2 = (n / N3) % N2, n1 = n / (N2 * N3);
             uint32_t *dst = (uint32_t *)(UB + s * G::SU + n1 * G::PQ1 + n2 * G::PR + n3);
             dst[0] = pre[j].x;
@@ -242,166 +259,283 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *__restrict__ u, u
             dst[2] = pre[j].z;
             dst[3] = pre[j].w;
         }
-        __syncthreads();
-        if (pair + 1 < pair1) issue_loads(pair + 1);
-
-        // ---- phase A: per n3 = c: stage 1, twiddle, stage 2 -> XB
-#pragma unroll
-        for (int i = 0; i < C3; ++i) {
-            const int c = w * C3 + i;
-            if constexpr (!REGC) load_A(i);
-            uint4 x2[2][R2];                              // stage-2 operands [k1 tile][K step = n2 tile]
-#pragma unroll
-            for (int rt = 0; rt < R2; ++rt) {
-                // operand of stage 1: row n2 = 16 rt + c16, slots (2r+s) = u_s[n1 = 4q + r]
-                const uint16_t *p0 = UB + (4 * q) * G::PQ1 + (16 * rt + c16) * G::PR + c;
-                uint32_t d[4];
-#pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    d[r] = (uint32_t)p0[r * G::PQ1] | ((uint32_t)p0[G::SU + r * G::PQ1] << 16);
-                const uint4 x1 = make_uint4(d[0], d[1], d[2], d[3]);
-#pragma unroll
-                for (int ct = 0; ct < 2; ++ct) {
-                    f32x4 z = {0.f, 0.f, 0.f, 0.f};
-                    f32x4 dre = TT::mfma(x1, tab1[ct][0], z);
-                    f32x4 dim = TT::mfma(x1, tab1[ct][1], z);
-                    uint32_t o[4];
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        float re = dre[r], im = dim[r];
-                        cmul_ip(re, im, twa[i][rt][ct][r]);
-                        o[r] = TT::pack(re, im);
-                    }
-                    x2[ct][rt] = make_uint4(o[0], o[1], o[2], o[3]);
-                }
-            }
-#pragma unroll
-            for (int ct = 0; ct < 2; ++ct)
-#pragma unroll
-                for (int ct2 = 0; ct2 < R2; ++ct2) {
-                    f32x4 dre = {0.f, 0.f, 0.f, 0.f}, dim = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                    for (int t = 0; t < R2; ++t) {
-                        dre = TT::mfma(x2[ct][t], tab2[i][t][ct2][0], dre);
-                        dim = TT::mfma(x2[ct][t], tab2[i][t][ct2][1], dim);
-                    }
-                    // lane: k2 = 16 ct2 + c16; reg r: k1 = 16 ct + 4q + r
-                    uint32_t *dst = XB + c * G::PN3 + (16 * ct + 4 * q) * G::PK1 + 16 * ct2 + c16;
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) dst[r * G::PK1] = TT::pack(dre[r], dim[r]);
-                }
-        }
-        __syncthreads();
-
-        // ---- phase B: per k1 = c: stage 3, k_f, inverse 3, twiddle, inverse 2 -> XB in place
-#pragma unroll
-        for (int i = 0; i < C1; ++i) {
-            const int c = w * C1 + i;
-            if constexpr (!REGC) load_B(i);
-            uint4 x3[R2][R3];
-#pragma unroll
-            for (int ct2 = 0; ct2 < R2; ++ct2)
-#pragma unroll
-                for (int t = 0; t < R3; ++t) {
-                    const uint32_t *src = XB + (16 * t + 4 * q) * G::PN3 + c * G::PK1 + 16 * ct2 + c16;
-                    x3[ct2][t] = make_uint4(src[0], src[G::PN3], src[2 * G::PN3], src[3 * G::PN3]);
-                }
-            uint4 x3i[R2][R3];                            // [k2 tile][K step = k3 tile]
-#pragma unroll
-            for (int ct2 = 0; ct2 < R2; ++ct2)
-#pragma unroll
-                for (int ct3 = 0; ct3 < R3; ++ct3) {
-                    f32x4 dre = {0.f, 0.f, 0.f, 0.f}, dim = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                    for (int t = 0; t < R3; ++t) {        // matrix is the A operand: rows k3, data columns k2
-                        dre = TT::mfma(tab3[t][ct3][0], x3[ct2][t], dre);
-                        dim = TT::mfma(tab3[t][ct3][1], x3[ct2][t], dim);
-                    }
-                    uint32_t o[4];
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        float re = dre[r], im = dim[r];
-                        cmul_ip(re, im, kfr[i][ct2][ct3][r]);
-                        o[r] = TT::pack(re, im);
-                    }
-                    x3i[ct2][ct3] = make_uint4(o[0], o[1], o[2], o[3]);
-                }
-            uint4 x2i[R3][R2];                            // [n3 tile][K step = k2 tile]
-#pragma unroll
-            for (int ct2 = 0; ct2 < R2; ++ct2)
-#pragma unroll
-                for (int cn3 = 0; cn3 < R3; ++cn3) {
-                    f32x4 dre = {0.f, 0.f, 0.f, 0.f}, dim = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                    for (int t = 0; t < R3; ++t) {
-                        dre = TT::mfma(x3i[ct2][t], tab3i[t][cn3][0], dre);
-                        dim = TT::mfma(x3i[ct2][t], tab3i[t][cn3][1], dim);
-                    }
-                    uint32_t o[4];
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        float re = dre[r], im = dim[r];
-                        cmul_ip(re, im, twb[i][ct2][cn3][r]);
-                        o[r] = TT::pack(re, im);
-                    }
-                    x2i[cn3][ct2] = make_uint4(o[0], o[1], o[2], o[3]);
-                }
-#pragma unroll
-            for (int cn3 = 0; cn3 < R3; ++cn3)
-#pragma unroll
-                for (int cn2 = 0; cn2 < R2; ++cn2) {
-                    f32x4 dre = {0.f, 0.f, 0.f, 0.f}, dim = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                    for (int t = 0; t < R2; ++t) {
-                        dre = TT::mfma(x2i[cn3][t], tab2i[i][t][cn2][0], dre);
-                        dim = TT::mfma(x2i[cn3][t], tab2i[i][t][cn2][1], dim);
-                    }
-                    // lane: n2 = 16 cn2 + c16; reg r: n3 = 16 cn3 + 4q + r
-                    uint32_t *dst = XB + (16 * cn3 + 4 * q) * G::PN3 + c * G::PK1 + 16 * cn2 + c16;
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) dst[r * G::PN3] = TT::pack(dre[r], dim[r]);
-                }
-        }
-        __syncthreads();
-
-        // ---- phase C: per n3 = c: inverse stage 1 (n1 < 16; re -> row b, im -> row b+1) -> YB
-#pragma unroll
-        for (int i = 0; i < C3; ++i) {
-            const int c = w * C3 + i;
-#pragma unroll
-            for (int cn2 = 0; cn2 < R2; ++cn2) {
-                f32x4 dre = {0.f, 0.f, 0.f, 0.f}, dim = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int t = 0; t < 2; ++t) {
-                    const uint32_t *src = XB + c * G::PN3 + (16 * t + 4 * q) * G::PK1 + 16 * cn2 + c16;
-                    const uint4 x = make_uint4(src[0], src[G::PK1], src[2 * G::PK1], src[3 * G::PK1]);
-                    dre = TT::mfma(tab1i[t][0], x, dre);
-                    dim = TT::mfma(tab1i[t][1], x, dim);
-                }
-                // lane: n2 = 16 cn2 + c16; reg r: n1 = 4q + r
-                uint16_t *dst = YB + (4 * q) * G::PQ1 + (16 * cn2 + c16) * G::PR + c;
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    dst[r * G::PQ1] = TT::cvt(dre[r]);
-                    dst[G::SU + r * G::PQ1] = TT::cvt(dim[r]);
-                }
-            }
-        }
-        __syncthreads();
-
-        // ---- store: YB -> y, 16 bytes per lane, coalesced
+    };
+    // YB -> y, 16 bytes per lane, coalesced
+    auto store_out = [&](int t) {
+        const int h = t / npairs, pair = t - h * npairs;
 #pragma unroll
         for (int j = 0; j < G::CHUNKS; ++j) {
-            const int ch = tid + NT * j;
-            const int s = ch / (G::M / 16);
-            const int n = (ch % (G::M / 16)) * 8;
+            const int s = j / G::CPS;
+            const int n = (tid + NT * (j % G::CPS)) * 8;
             const int b = 2 * pair + s;
             const int n3 = n % N3, n2 = (n / N3) % N2, n1 = n / (N2 * N3);
             const uint32_t *src = (const uint32_t *)(YB + s * G::SU + n1 * G::PQ1 + n2 * G::PR + n3);
             const uint4 v = make_uint4(src[0], src[1], src[2], src[3]);
-            if (b < B && n < N) *(uint4 *)(y + ((size_t)b * H + h) * N + n) = v;
+            uint16_t *row = y + ((size_t)b * H + h) * N;
+            if (PROBE_ON(16) && b < B && n < N) *(uint4 *)(row + n) = v;
         }
+    };
+
+    // Pipeline over pairs (3 barriers per pair):
+    //   [A(p) + store(p-1)] | [B(p)] | [C(p) + stage_in(p+1) + issue_loads(p+2)] |
+    issue_loads(t0);
+    stage_in();
+    issue_loads(t0 + 1);
+    __syncthreads();
+
+    const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
+    int h_cur = -1;
+    for (int t = t0; t < t1; ++t) {
+        {
+            const int h = t / npairs;
+            if (h != h_cur) {                             // new channel: fetch its k_f (used in phase B)
+                h_cur = h;
+                if constexpr (REGC) {
+#pragma unroll
+                    for (int i = 0; i < C1; ++i) load_kf(i, h);
+                }
+            }
+        }
+        // ================= phase A: per n3 = c: stage 1, twiddle, stage 2 -> XB
+        {
+            uint4 x1[C3][R2];
+            if (PROBE_ON(1))
+#pragma unroll
+            for (int i = 0; i < C3; ++i) {
+                const int c = w * C3 + i;
+                if constexpr (!REGC) load_A(i);
+#pragma unroll
+                for (int rt = 0; rt < R2; ++rt) {
+                    // operand of stage 1: row n2 = 16 rt + c16, slots (2r+s) = u_s[n1 = 4q + r]
+                    const uint16_t *p0 = UB + (4 * q) * G::PQ1 + (16 * rt + c16) * G::PR + c;
+                    uint32_t d[4];
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        d[r] = (uint32_t)p0[r * G::PQ1] | ((uint32_t)p0[G::SU + r * G::PQ1] << 16);
+                    x1[i][rt] = make_uint4(d[0], d[1], d[2], d[3]);
+                }
+            }
+            if (t > t0) store_out(t - 1);
+            if (PROBE_ON(1)) {
+            f32x4 d1[C3][R2][2][2];
+#pragma unroll
+            for (int i = 0; i < C3; ++i)
+#pragma unroll
+                for (int rt = 0; rt < R2; ++rt)
+#pragma unroll
+                    for (int ct = 0; ct < 2; ++ct) {
+                        d1[i][rt][ct][0] = TT::mfma(x1[i][rt], tab1[ct][0], zero4);
+                        d1[i][rt][ct][1] = TT::mfma(x1[i][rt], tab1[ct][1], zero4);
+                    }
+            uint4 x2[C3][2][R2];                          // stage-2 operands [k1 tile][K step = n2 tile]
+#pragma unroll
+            for (int i = 0; i < C3; ++i)
+#pragma unroll
+                for (int rt = 0; rt < R2; ++rt)
+#pragma unroll
+                    for (int ct = 0; ct < 2; ++ct) {
+                        uint32_t o[4];
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            float re = d1[i][rt][ct][0][r], im = d1[i][rt][ct][1][r];
+                            cmul_ip(re, im, twa[i][rt][ct][r]);
+                            o[r] = TT::pack(re, im);
+                        }
+                        x2[i][ct][rt] = make_uint4(o[0], o[1], o[2], o[3]);
+                    }
+            f32x4 d2[C3][2][R2][2];
+#pragma unroll
+            for (int i = 0; i < C3; ++i)
+#pragma unroll
+                for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+                    for (int ct2 = 0; ct2 < R2; ++ct2) {
+                        f32x4 dre = zero4, dim = zero4;
+#pragma unroll
+                        for (int ks = 0; ks < R2; ++ks) {
+                            dre = TT::mfma(x2[i][ct][ks], tab2[i][ks][ct2][0], dre);
+                            dim = TT::mfma(x2[i][ct][ks], tab2[i][ks][ct2][1], dim);
+                        }
+                        d2[i][ct][ct2][0] = dre;
+                        d2[i][ct][ct2][1] = dim;
+                    }
+#pragma unroll
+            for (int i = 0; i < C3; ++i) {
+                const int c = w * C3 + i;
+#pragma unroll
+                for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+                    for (int ct2 = 0; ct2 < R2; ++ct2) {
+                        // lane: k2 = 16 ct2 + c16; reg r: k1 = 16 ct + 4q + r
+                        uint32_t *dst = XB + c * G::PN3 + (16 * ct + 4 * q) * G::PK1 + 16 * ct2 + c16;
+#pragma unroll
+                        for (int r = 0; r < 4; ++r)
+                            dst[r * G::PK1] = TT::pack(d2[i][ct][ct2][0][r], d2[i][ct][ct2][1][r]);
+                    }
+            }
+            }
+        }
+        __syncthreads();
+
+        // ================= phase B: per k1 = c: stage 3, k_f, inverse 3, twiddle, inverse 2 -> XB in place
+        if (PROBE_ON(2)) {
+            uint4 x3[C1][R2][R3];
+#pragma unroll
+            for (int i = 0; i < C1; ++i) {
+                const int c = w * C1 + i;
+                if constexpr (!REGC) {
+                    load_B(i);
+                    load_kf(i, h_cur);
+                }
+#pragma unroll
+                for (int ct2 = 0; ct2 < R2; ++ct2)
+#pragma unroll
+                    for (int ks = 0; ks < R3; ++ks) {
+                        const uint32_t *src = XB + (16 * ks + 4 * q) * G::PN3 + c * G::PK1 + 16 * ct2 + c16;
+                        x3[i][ct2][ks] = make_uint4(src[0], src[G::PN3], src[2 * G::PN3], src[3 * G::PN3]);
+                    }
+            }
+            f32x4 d3[C1][R2][R3][2];
+#pragma unroll
+            for (int i = 0; i < C1; ++i)
+#pragma unroll
+                for (int ct2 = 0; ct2 < R2; ++ct2)
+#pragma unroll
+                    for (int ct3 = 0; ct3 < R3; ++ct3) {
+                        f32x4 dre = zero4, dim = zero4;
+#pragma unroll
+                        for (int ks = 0; ks < R3; ++ks) {  // matrix is the A operand: rows k3, data columns k2
+                            dre = TT::mfma(tab3[ks][ct3][0], x3[i][ct2][ks], dre);
+                            dim = TT::mfma(tab3[ks][ct3][1], x3[i][ct2][ks], dim);
+                        }
+                        d3[i][ct2][ct3][0] = dre;
+                        d3[i][ct2][ct3][1] = dim;
+                    }
+            uint4 x3i[C1][R2][R3];                        // [k2 tile][K step = k3 tile]
+#pragma unroll
+            for (int i = 0; i < C1; ++i)
+#pragma unroll
+                for (int ct2 = 0; ct2 < R2; ++ct2)
+#pragma unroll
+                    for (int ct3 = 0; ct3 < R3; ++ct3) {
+                        uint32_t o[4];
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            float re = d3[i][ct2][ct3][0][r], im = d3[i][ct2][ct3][1][r];
+                            cmul_ip(re, im, kfr[i][ct2][ct3][r]);
+                            o[r] = TT::pack(re, im);
+                        }
+                        x3i[i][ct2][ct3] = make_uint4(o[0], o[1], o[2], o[3]);
+                    }
+            f32x4 d3i[C1][R2][R3][2];
+#pragma unroll
+            for (int i = 0; i < C1; ++i)
+#pragma unroll
+                for (int ct2 = 0; ct2 < R2; ++ct2)
+#pragma unroll
+                    for (int cn3 = 0; cn3 < R3; ++cn3) {
+                        f32x4 dre = zero4, dim = zero4;
+#pragma unroll
+                        for (int ks = 0; ks < R3; ++ks) {
+                            dre = TT::mfma(x3i[i][ct2][ks], tab3i[ks][cn3][0], dre);
+                            dim = TT::mfma(x3i[i][ct2][ks], tab3i[ks][cn3][1], dim);
+                        }
+                        d3i[i][ct2][cn3][0] = dre;
+                        d3i[i][ct2][cn3][1] = dim;
+                    }
+            uint4 x2i[C1][R3][R2];                        // [n3 tile][K step = k2 tile]
+#pragma unroll
+            for (int i = 0; i < C1; ++i)
+#pragma unroll
+                for (int ct2 = 0; ct2 < R2; ++ct2)
+#pragma unroll
+                    for (int cn3 = 0; cn3 < R3; ++cn3) {
+                        uint32_t o[4];
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            float re = d3i[i][ct2][cn3][0][r], im = d3i[i][ct2][cn3][1][r];
+                            cmul_ip(re, im, twb[i][ct2][cn3][r]);
+                            o[r] = TT::pack(re, im);
+                        }
+                        x2i[i][cn3][ct2] = make_uint4(o[0], o[1], o[2], o[3]);
+                    }
+            f32x4 d2i[C1][R3][R2][2];
+#pragma unroll
+            for (int i = 0; i < C1; ++i)
+#pragma unroll
+                for (int cn3 = 0; cn3 < R3; ++cn3)
+#pragma unroll
+                    for (int cn2 = 0; cn2 < R2; ++cn2) {
+                        f32x4 dre = zero4, dim = zero4;
+#pragma unroll
+                        for (int ks = 0; ks < R2; ++ks) {
+                            dre = TT::mfma(x2i[i][cn3][ks], tab2i[i][ks][cn2][0], dre);
+                            dim = TT::mfma(x2i[i][cn3][ks], tab2i[i][ks][cn2][1], dim);
+                        }
+                        d2i[i][cn3][cn2][0] = dre;
+                        d2i[i][cn3][cn2][1] = dim;
+                    }
+#pragma unroll
+            for (int i = 0; i < C1; ++i) {
+                const int c = w * C1 + i;
+#pragma unroll
+                for (int cn3 = 0; cn3 < R3; ++cn3)
+#pragma unroll
+                    for (int cn2 = 0; cn2 < R2; ++cn2) {
+                        // lane: n2 = 16 cn2 + c16; reg r: n3 = 16 cn3 + 4q + r
+                        uint32_t *dst = XB + (16 * cn3 + 4 * q) * G::PN3 + c * G::PK1 + 16 * cn2 + c16;
+#pragma unroll
+                        for (int r = 0; r < 4; ++r)
+                            dst[r * G::PN3] = TT::pack(d2i[i][cn3][cn2][0][r], d2i[i][cn3][cn2][1][r]);
+                    }
+            }
+        }
+        __syncthreads();
+
+        // ================= phase C: per n3 = c: inverse stage 1 (n1 < 16; re -> row b, im -> row b+1) -> YB
+        {
+            uint4 x1i[C3][R2][2];
+            if (PROBE_ON(4))
+#pragma unroll
+            for (int i = 0; i < C3; ++i) {
+                const int c = w * C3 + i;
+#pragma unroll
+                for (int cn2 = 0; cn2 < R2; ++cn2)
+#pragma unroll
+                    for (int ks = 0; ks < 2; ++ks) {
+                        const uint32_t *src = XB + c * G::PN3 + (16 * ks + 4 * q) * G::PK1 + 16 * cn2 + c16;
+                        x1i[i][cn2][ks] = make_uint4(src[0], src[G::PK1], src[2 * G::PK1], src[3 * G::PK1]);
+                    }
+            }
+            // next pair's input: registers -> UB (its readers finished before the previous barrier),
+            // then start the loads of the pair after that
+            stage_in();
+            issue_loads(t + 2);
+            if (PROBE_ON(4))
+#pragma unroll
+            for (int i = 0; i < C3; ++i) {
+                const int c = w * C3 + i;
+#pragma unroll
+                for (int cn2 = 0; cn2 < R2; ++cn2) {
+                    f32x4 dre = zero4, dim = zero4;
+#pragma unroll
+                    for (int ks = 0; ks < 2; ++ks) {
+                        dre = TT::mfma(tab1i[ks][0], x1i[i][cn2][ks], dre);
+                        dim = TT::mfma(tab1i[ks][1], x1i[i][cn2][ks], dim);
+                    }
+                    // lane: n2 = 16 cn2 + c16; reg r: n1 = 4q + r
+                    uint16_t *dst = YB + (4 * q) * G::PQ1 + (16 * cn2 + c16) * G::PR + c;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        dst[r * G::PQ1] = TT::cvt(dre[r]);
+                        dst[G::SU + r * G::PQ1] = TT::cvt(dim[r]);
+                    }
+                }
+            }
+        }
+        __syncthreads();
     }
+    store_out(t1 - 1);
 }
 
 // k_f in the fused kernel's per-lane order: [h][k1][k2 tile][k3 tile][r][lane] float2, where the
@@ -569,6 +703,16 @@ Consts consts_of(const fftconv_plan *p)
     return c;
 }
 
+int probe_mask()
+{
+#ifdef FUSED3_PROBE
+    const char *e = getenv("FUSED3_PROBE");
+    return e ? atoi(e) : 0;
+#else
+    return 0;
+#endif
+}
+
 template <int N2, int N3, typename TT, bool REGC>
 int launch(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, hipStream_t s)
 {
@@ -580,14 +724,16 @@ int launch(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_
                                    (int)G::LDS_BYTES));
         attr_set = true;
     }
-    const int npairs = (int)((B + 1) / 2);
-    // enough workgroups to fill 256 CUs a few times over, but keep k_f[h] reuse when H alone does that
-    int split = 1;
-    while ((int64_t)p->H * split < 1024 && split * 2 <= npairs) split *= 2;
-    const int ppw = (npairs + split - 1) / split;
-    const int ny = (npairs + ppw - 1) / ppw;
-    hipLaunchKernelGGL(kern, dim3((unsigned)p->H, (unsigned)ny), dim3(NT), G::LDS_BYTES, s, (const uint16_t *)u,
-                       (uint16_t *)y, (const float2 *)kf, consts_of<N2, N3>(p), (int)B, (int)p->H, (int)p->N, ppw);
+    const int64_t npairs = (B + 1) / 2;
+    const int64_t T = p->H * npairs;
+    if (T >= ((int64_t)1 << 31)) {
+        set_error("fftconv_forward: H * ceil(B/2) = %lld work items exceed the fused kernel's 2^31 limit", (long long)T);
+        return FFTCONV_EUNSUPPORTED;
+    }
+    // one persistent workgroup per compute unit (fewer when there is less work than that)
+    const int grid = (int)(T < p->f3.num_cu ? T : p->f3.num_cu);
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NT), G::LDS_BYTES, s, (const uint16_t *)u, (uint16_t *)y,
+                       (const float2 *)kf, consts_of<N2, N3>(p), (int)B, (int)p->H, (int)p->N, probe_mask());
     FC_HIP(hipGetLastError());
     return FFTCONV_OK;
 }
@@ -604,6 +750,9 @@ bool fused3_supported(int64_t N, int64_t M, int dtype)
 int fused3_init(fftconv_plan *p)
 {
     p->f3.N1 = N1;
+    hipDeviceProp_t prop;
+    FC_HIP(hipGetDeviceProperties(&prop, p->device));
+    p->f3.num_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
     switch (p->M) {
     case 8192:
         p->f3.N2 = 16;

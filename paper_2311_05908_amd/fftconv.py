@@ -42,9 +42,10 @@ def load():
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(_build.LIB):
+    path = os.environ.get("FFTCONV_LIBRARY", _build.LIB)     # override: a development build of the same ABI
+    if not os.path.exists(path):
         _build.build()
-    lib = ctypes.CDLL(_build.LIB)
+    lib = ctypes.CDLL(path)
     vp, i64, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
     lib.fftconv_plan_create.argtypes = [ctypes.POINTER(vp), i64, i64, i64, ci]
     lib.fftconv_plan_create.restype = ci
