@@ -276,8 +276,10 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *__restrict__ u, u
         }
     };
 
-    // Pipeline over pairs (3 barriers per pair):
-    //   [A(p) + store(p-1)] | [B(p)] | [C(p) + stage_in(p+1) + issue_loads(p+2)] |
+    // Pipeline over work items (3 barriers each):
+    //   [A(t)] | [B(t) + store(t-1) + stage_in(t+1) + issue_loads(t+2)] | [C(t)] |
+    // UB is read in A(t) and rewritten in B(t); YB is written in C(t) and read in B(t+1); XB planes
+    // change owner only across barriers.
     issue_loads(t0);
     stage_in();
     issue_loads(t0 + 1);
@@ -297,6 +299,8 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *__restrict__ u, u
             }
         }
         // ================= phase A: per n3 = c: stage 1, twiddle, stage 2 -> XB
+        // (all operand reads first, then tile by tile compute -> write, so that the LDS
+        //  traffic of one tile drains while the next tile computes)
         {
             uint4 x1[C3][R2];
             if (PROBE_ON(1))
@@ -315,37 +319,26 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *__restrict__ u, u
                     x1[i][rt] = make_uint4(d[0], d[1], d[2], d[3]);
                 }
             }
-            if (t > t0) store_out(t - 1);
-            if (PROBE_ON(1)) {
-            f32x4 d1[C3][R2][2][2];
+            if (PROBE_ON(1))
 #pragma unroll
-            for (int i = 0; i < C3; ++i)
-#pragma unroll
-                for (int rt = 0; rt < R2; ++rt)
-#pragma unroll
-                    for (int ct = 0; ct < 2; ++ct) {
-                        d1[i][rt][ct][0] = TT::mfma(x1[i][rt], tab1[ct][0], zero4);
-                        d1[i][rt][ct][1] = TT::mfma(x1[i][rt], tab1[ct][1], zero4);
-                    }
-            uint4 x2[C3][2][R2];                          // stage-2 operands [k1 tile][K step = n2 tile]
-#pragma unroll
-            for (int i = 0; i < C3; ++i)
+            for (int i = 0; i < C3; ++i) {
+                const int c = w * C3 + i;
+                uint4 x2[2][R2];                          // stage-2 operands [k1 tile][K step = n2 tile]
 #pragma unroll
                 for (int rt = 0; rt < R2; ++rt)
 #pragma unroll
                     for (int ct = 0; ct < 2; ++ct) {
+                        const f32x4 dre = TT::mfma(x1[i][rt], tab1[ct][0], zero4);
+                        const f32x4 dim = TT::mfma(x1[i][rt], tab1[ct][1], zero4);
                         uint32_t o[4];
 #pragma unroll
                         for (int r = 0; r < 4; ++r) {
-                            float re = d1[i][rt][ct][0][r], im = d1[i][rt][ct][1][r];
+                            float re = dre[r], im = dim[r];
                             cmul_ip(re, im, twa[i][rt][ct][r]);
                             o[r] = TT::pack(re, im);
                         }
-                        x2[i][ct][rt] = make_uint4(o[0], o[1], o[2], o[3]);
+                        x2[ct][rt] = make_uint4(o[0], o[1], o[2], o[3]);
                     }
-            f32x4 d2[C3][2][R2][2];
-#pragma unroll
-            for (int i = 0; i < C3; ++i)
 #pragma unroll
                 for (int ct = 0; ct < 2; ++ct)
 #pragma unroll
@@ -353,33 +346,22 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *__restrict__ u, u
                         f32x4 dre = zero4, dim = zero4;
 #pragma unroll
                         for (int ks = 0; ks < R2; ++ks) {
-                            dre = TT::mfma(x2[i][ct][ks], tab2[i][ks][ct2][0], dre);
-                            dim = TT::mfma(x2[i][ct][ks], tab2[i][ks][ct2][1], dim);
+                            dre = TT::mfma(x2[ct][ks], tab2[i][ks][ct2][0], dre);
+                            dim = TT::mfma(x2[ct][ks], tab2[i][ks][ct2][1], dim);
                         }
-                        d2[i][ct][ct2][0] = dre;
-                        d2[i][ct][ct2][1] = dim;
-                    }
-#pragma unroll
-            for (int i = 0; i < C3; ++i) {
-                const int c = w * C3 + i;
-#pragma unroll
-                for (int ct = 0; ct < 2; ++ct)
-#pragma unroll
-                    for (int ct2 = 0; ct2 < R2; ++ct2) {
                         // lane: k2 = 16 ct2 + c16; reg r: k1 = 16 ct + 4q + r
                         uint32_t *dst = XB + c * G::PN3 + (16 * ct + 4 * q) * G::PK1 + 16 * ct2 + c16;
 #pragma unroll
-                        for (int r = 0; r < 4; ++r)
-                            dst[r * G::PK1] = TT::pack(d2[i][ct][ct2][0][r], d2[i][ct][ct2][1][r]);
+                        for (int r = 0; r < 4; ++r) dst[r * G::PK1] = TT::pack(dre[r], dim[r]);
                     }
-            }
             }
         }
         __syncthreads();
 
         // ================= phase B: per k1 = c: stage 3, k_f, inverse 3, twiddle, inverse 2 -> XB in place
-        if (PROBE_ON(2)) {
+        {
             uint4 x3[C1][R2][R3];
+            if (PROBE_ON(2))
 #pragma unroll
             for (int i = 0; i < C1; ++i) {
                 const int c = w * C1 + i;
@@ -395,9 +377,20 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *__restrict__ u, u
                         x3[i][ct2][ks] = make_uint4(src[0], src[G::PN3], src[2 * G::PN3], src[3 * G::PN3]);
                     }
             }
-            f32x4 d3[C1][R2][R3][2];
+            // The staging traffic rides in this compute-heavy phase: the previous pair's output
+            // (YB, complete since the last barrier) goes to HBM, the next pair's prefetched input
+            // goes to UB (its readers finished before the last barrier), and the loads of the pair
+            // after that start.
+            // (stage_in first: it waits for the prefetch, and on this target loads and stores
+            //  retire through one counter, so it must not sit behind freshly issued stores)
+            stage_in();
+            issue_loads(t + 2);
+            if (t > t0) store_out(t - 1);
+            if (PROBE_ON(2))
 #pragma unroll
-            for (int i = 0; i < C1; ++i)
+            for (int i = 0; i < C1; ++i) {
+                const int c = w * C1 + i;
+                uint4 x3i[R2][R3];                        // [k2 tile][K step = k3 tile]
 #pragma unroll
                 for (int ct2 = 0; ct2 < R2; ++ct2)
 #pragma unroll
@@ -408,28 +401,16 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *__restrict__ u, u
                             dre = TT::mfma(tab3[ks][ct3][0], x3[i][ct2][ks], dre);
                             dim = TT::mfma(tab3[ks][ct3][1], x3[i][ct2][ks], dim);
                         }
-                        d3[i][ct2][ct3][0] = dre;
-                        d3[i][ct2][ct3][1] = dim;
-                    }
-            uint4 x3i[C1][R2][R3];                        // [k2 tile][K step = k3 tile]
-#pragma unroll
-            for (int i = 0; i < C1; ++i)
-#pragma unroll
-                for (int ct2 = 0; ct2 < R2; ++ct2)
-#pragma unroll
-                    for (int ct3 = 0; ct3 < R3; ++ct3) {
                         uint32_t o[4];
 #pragma unroll
                         for (int r = 0; r < 4; ++r) {
-                            float re = d3[i][ct2][ct3][0][r], im = d3[i][ct2][ct3][1][r];
+                            float re = dre[r], im = dim[r];
                             cmul_ip(re, im, kfr[i][ct2][ct3][r]);
                             o[r] = TT::pack(re, im);
                         }
-                        x3i[i][ct2][ct3] = make_uint4(o[0], o[1], o[2], o[3]);
+                        x3i[ct2][ct3] = make_uint4(o[0], o[1], o[2], o[3]);
                     }
-            f32x4 d3i[C1][R2][R3][2];
-#pragma unroll
-            for (int i = 0; i < C1; ++i)
+                uint4 x2i[R3][R2];                        // [n3 tile][K step = k2 tile]
 #pragma unroll
                 for (int ct2 = 0; ct2 < R2; ++ct2)
 #pragma unroll
@@ -437,31 +418,18 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *__restrict__ u, u
                         f32x4 dre = zero4, dim = zero4;
 #pragma unroll
                         for (int ks = 0; ks < R3; ++ks) {
-                            dre = TT::mfma(x3i[i][ct2][ks], tab3i[ks][cn3][0], dre);
-                            dim = TT::mfma(x3i[i][ct2][ks], tab3i[ks][cn3][1], dim);
+                            dre = TT::mfma(x3i[ct2][ks], tab3i[ks][cn3][0], dre);
+                            dim = TT::mfma(x3i[ct2][ks], tab3i[ks][cn3][1], dim);
                         }
-                        d3i[i][ct2][cn3][0] = dre;
-                        d3i[i][ct2][cn3][1] = dim;
-                    }
-            uint4 x2i[C1][R3][R2];                        // [n3 tile][K step = k2 tile]
-#pragma unroll
-            for (int i = 0; i < C1; ++i)
-#pragma unroll
-                for (int ct2 = 0; ct2 < R2; ++ct2)
-#pragma unroll
-                    for (int cn3 = 0; cn3 < R3; ++cn3) {
                         uint32_t o[4];
 #pragma unroll
                         for (int r = 0; r < 4; ++r) {
-                            float re = d3i[i][ct2][cn3][0][r], im = d3i[i][ct2][cn3][1][r];
+                            float re = dre[r], im = dim[r];
                             cmul_ip(re, im, twb[i][ct2][cn3][r]);
                             o[r] = TT::pack(re, im);
                         }
-                        x2i[i][cn3][ct2] = make_uint4(o[0], o[1], o[2], o[3]);
+                        x2i[cn3][ct2] = make_uint4(o[0], o[1], o[2], o[3]);
                     }
-            f32x4 d2i[C1][R3][R2][2];
-#pragma unroll
-            for (int i = 0; i < C1; ++i)
 #pragma unroll
                 for (int cn3 = 0; cn3 < R3; ++cn3)
 #pragma unroll
@@ -469,24 +437,13 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *__restrict__ u, u
                         f32x4 dre = zero4, dim = zero4;
 #pragma unroll
                         for (int ks = 0; ks < R2; ++ks) {
-                            dre = TT::mfma(x2i[i][cn3][ks], tab2i[i][ks][cn2][0], dre);
-                            dim = TT::mfma(x2i[i][cn3][ks], tab2i[i][ks][cn2][1], dim);
+                            dre = TT::mfma(x2i[cn3][ks], tab2i[i][ks][cn2][0], dre);
+                            dim = TT::mfma(x2i[cn3][ks], tab2i[i][ks][cn2][1], dim);
                         }
-                        d2i[i][cn3][cn2][0] = dre;
-                        d2i[i][cn3][cn2][1] = dim;
-                    }
-#pragma unroll
-            for (int i = 0; i < C1; ++i) {
-                const int c = w * C1 + i;
-#pragma unroll
-                for (int cn3 = 0; cn3 < R3; ++cn3)
-#pragma unroll
-                    for (int cn2 = 0; cn2 < R2; ++cn2) {
                         // lane: n2 = 16 cn2 + c16; reg r: n3 = 16 cn3 + 4q + r
                         uint32_t *dst = XB + (16 * cn3 + 4 * q) * G::PN3 + c * G::PK1 + 16 * cn2 + c16;
 #pragma unroll
-                        for (int r = 0; r < 4; ++r)
-                            dst[r * G::PN3] = TT::pack(d2i[i][cn3][cn2][0][r], d2i[i][cn3][cn2][1][r]);
+                        for (int r = 0; r < 4; ++r) dst[r * G::PN3] = TT::pack(dre[r], dim[r]);
                     }
             }
         }
@@ -507,10 +464,6 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *__restrict__ u, u
                         x1i[i][cn2][ks] = make_uint4(src[0], src[G::PK1], src[2 * G::PK1], src[3 * G::PK1]);
                     }
             }
-            // next pair's input: registers -> UB (its readers finished before the previous barrier),
-            // then start the loads of the pair after that
-            stage_in();
-            issue_loads(t + 2);
             if (PROBE_ON(4))
 #pragma unroll
             for (int i = 0; i < C3; ++i) {
