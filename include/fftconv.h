@@ -102,7 +102,12 @@ int fftconv_forward_partial(const fftconv_plan *plan, const void *u, const void 
  * then every frequency bin f whose block is dropped is set to zero.
  *   block_keep: host, n_blocks bytes, 1 = keep; n_blocks a power of two that
  *   divides fft_size; block j holds the natural-order frequencies
- *   f in [j * fft_size / n_blocks, (j+1) * fft_size / n_blocks). */
+ *   f in [j * fft_size / n_blocks, (j+1) * fft_size / n_blocks).
+ * The convolution with the masked spectrum K~ is defined as
+ * y = Re(iFFT(K~ . FFT(u))).  For real u this equals iFFT(K' . FFT(u)) with
+ * K'[f] = K[f] * (keep[f] + keep[fft_size - f]) / 2, and K' is what is stored:
+ * a bin whose mirror bin is masked differently carries weight 1/2 (a block
+ * mask is at most one bin per block edge away from mirror symmetry). */
 int fftconv_filter_fft_sparse(const fftconv_plan *plan, const float *k, int64_t Nk,
                               const uint8_t *block_keep, int64_t n_blocks, void *k_f, void *stream);
 

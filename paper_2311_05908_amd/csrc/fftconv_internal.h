@@ -64,6 +64,19 @@ struct Fused3Tables {
     size_t consts_bytes = 0;
 };
 
+// Weight of frequency bin f under a block mask (Section 3.3, frequency-sparse filters).  The
+// output is defined as Re(IDFT(mask . K . U)) for real u; that equals IDFT(K' . U) with the
+// Hermitian part K'[f] = K[f] (mask[f] + mask[M-f]) / 2, and only a Hermitian K' (a real filter)
+// lets two real sequences share one complex transform.  So a bin whose mirror is masked
+// differently gets weight 1/2.  keep == nullptr means no mask.
+__host__ __device__ inline double mask_weight(const uint8_t *keep, int64_t n_blocks, int64_t f, int64_t M)
+{
+    if (!keep) return 1.0;
+    const int64_t per = M / n_blocks;
+    const int64_t fm = f == 0 ? 0 : M - f;
+    return 0.5 * ((keep[f / per] ? 1.0 : 0.0) + (keep[fm / per] ? 1.0 : 0.0));
+}
+
 }  // namespace fftconv
 
 struct fftconv_plan {

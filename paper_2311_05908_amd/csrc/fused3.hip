@@ -180,6 +180,16 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *__restrict__ u, u
                 tab3[t][c][p] = cs.tab3[((t * R3 + c) * 2 + p) * 64 + l];
                 tab3i[t][c][p] = cs.tab3i[((t * R3 + c) * 2 + p) * 64 + l];
             }
+    // When the tables are streamed (REGC false) the loads must stay inside the loop over work
+    // items: an opaque zero added to the lane offset keeps the compiler from hoisting them.
+    int lz = l;
+    auto opaque = [&]() {
+        if constexpr (!REGC) {
+            int z = 0;
+            asm volatile("" : "+v"(z));
+            lz = l + z;
+        }
+    };
     auto load_A = [&](int i) {
         const int c = w * C3 + i;
 #pragma unroll
@@ -188,14 +198,14 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *__restrict__ u, u
             for (int ct = 0; ct < R2; ++ct)
 #pragma unroll
                 for (int p = 0; p < 2; ++p)
-                    tab2[i][t][ct][p] = cs.tab2[(((c * R2 + t) * R2 + ct) * 2 + p) * 64 + l];
+                    tab2[i][t][ct][p] = cs.tab2[(((c * R2 + t) * R2 + ct) * 2 + p) * 64 + lz];
 #pragma unroll
         for (int rt = 0; rt < R2; ++rt)
 #pragma unroll
             for (int ct = 0; ct < 2; ++ct)
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
-                    twa[i][rt][ct][r] = cs.twa[(((c * R2 + rt) * 2 + ct) * 4 + r) * 64 + l];
+                    twa[i][rt][ct][r] = cs.twa[(((c * R2 + rt) * 2 + ct) * 4 + r) * 64 + lz];
     };
     auto load_B = [&](int i) {
         const int c = w * C1 + i;
@@ -205,14 +215,14 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *__restrict__ u, u
             for (int ct = 0; ct < R2; ++ct)
 #pragma unroll
                 for (int p = 0; p < 2; ++p)
-                    tab2i[i][t][ct][p] = cs.tab2i[(((c * R2 + t) * R2 + ct) * 2 + p) * 64 + l];
+                    tab2i[i][t][ct][p] = cs.tab2i[(((c * R2 + t) * R2 + ct) * 2 + p) * 64 + lz];
 #pragma unroll
         for (int a = 0; a < R2; ++a)
 #pragma unroll
             for (int b = 0; b < R3; ++b)
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
-                    twb[i][a][b][r] = cs.twb[(((c * R2 + a) * R3 + b) * 4 + r) * 64 + l];
+                    twb[i][a][b][r] = cs.twb[(((c * R2 + a) * R3 + b) * 4 + r) * 64 + lz];
     };
     auto load_kf = [&](int i, int h) {
         const int c = w * C1 + i;
@@ -222,7 +232,7 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *__restrict__ u, u
             for (int b = 0; b < R3; ++b)
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
-                    kfr[i][a][b][r] = kf[(size_t)h * G::KF_PER_H + (((c * R2 + a) * R3 + b) * 4 + r) * 64 + l];
+                    kfr[i][a][b][r] = kf[(size_t)h * G::KF_PER_H + (((c * R2 + a) * R3 + b) * 4 + r) * 64 + lz];
     };
     if constexpr (REGC) {
 #pragma unroll
@@ -288,6 +298,7 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *__restrict__ u, u
     const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
     int h_cur = -1;
     for (int t = t0; t < t1; ++t) {
+        opaque();
         {
             const int h = t / npairs;
             if (h != h_cur) {                             // new channel: fetch its k_f (used in phase B)
@@ -307,7 +318,6 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *__restrict__ u, u
 #pragma unroll
             for (int i = 0; i < C3; ++i) {
                 const int c = w * C3 + i;
-                if constexpr (!REGC) load_A(i);
 #pragma unroll
                 for (int rt = 0; rt < R2; ++rt) {
                     // operand of stage 1: row n2 = 16 rt + c16, slots (2r+s) = u_s[n1 = 4q + r]
@@ -323,6 +333,7 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *__restrict__ u, u
 #pragma unroll
             for (int i = 0; i < C3; ++i) {
                 const int c = w * C3 + i;
+                if constexpr (!REGC) load_A(i);           // this tile's matrices and twiddles (L2-resident tables)
                 uint4 x2[2][R2];                          // stage-2 operands [k1 tile][K step = n2 tile]
 #pragma unroll
                 for (int rt = 0; rt < R2; ++rt)
@@ -365,10 +376,6 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *__restrict__ u, u
 #pragma unroll
             for (int i = 0; i < C1; ++i) {
                 const int c = w * C1 + i;
-                if constexpr (!REGC) {
-                    load_B(i);
-                    load_kf(i, h_cur);
-                }
 #pragma unroll
                 for (int ct2 = 0; ct2 < R2; ++ct2)
 #pragma unroll
@@ -390,6 +397,10 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *__restrict__ u, u
 #pragma unroll
             for (int i = 0; i < C1; ++i) {
                 const int c = w * C1 + i;
+                if constexpr (!REGC) {
+                    load_B(i);
+                    load_kf(i, h_cur);
+                }
                 uint4 x3i[R2][R3];                        // [k2 tile][K step = k3 tile]
 #pragma unroll
                 for (int ct2 = 0; ct2 < R2; ++ct2)
@@ -506,8 +517,7 @@ __global__ void k_pack_fused3(const double2 *spec, float2 *kf, FacList fl, int64
     int lane = ((k3 % 16) / 4) * 16 + (k2 % 16), r = k3 % 4;
     int64_t dst = ((((int64_t)k1 * G::R2 + k2 / 16) * G::R3 + k3 / 16) * 4 + r) * 64 + lane;
     double2 v = spec[h * M + freq_to_pos(f, fl, M)];
-    double sc = 1.0 / (double)M;
-    if (keep && !keep[f / (M / n_blocks)]) sc = 0.0;
+    double sc = mask_weight(keep, n_blocks, f, M) / (double)M;
     kf[(h0 + h) * M + dst] = make_float2((float)(v.x * sc), (float)(v.y * sc));
 }
 
@@ -696,7 +706,7 @@ int launch(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_
 bool fused3_supported(int64_t N, int64_t M, int dtype)
 {
     if (dtype != FFTCONV_F16 && dtype != FFTCONV_BF16) return false;
-    if (M != 8192) return false;
+    if (M != 8192 && M != 16384) return false;
     return N <= M / 2 && N % 8 == 0;
 }
 
@@ -711,6 +721,10 @@ int fused3_init(fftconv_plan *p)
         p->f3.N2 = 16;
         p->f3.N3 = 16;
         return build_tables<16, 16>(p);
+    case 16384:
+        p->f3.N2 = 32;
+        p->f3.N3 = 16;
+        return build_tables<32, 16>(p);
     default:
         set_error("fused3: no kernel for fft_size=%lld", (long long)p->M);
         return FFTCONV_EUNSUPPORTED;
@@ -735,6 +749,10 @@ int fused3_pack_kf(const fftconv_plan *p, const double2 *spec, int64_t h0, int64
         hipLaunchKernelGGL((k_pack_fused3<16, 16>), dim3(grid), dim3(bs), 0, s, spec, (float2 *)kf,
                            staged_fac_list(p), h0, nh, keep_dev, n_blocks);
         break;
+    case 16384:
+        hipLaunchKernelGGL((k_pack_fused3<32, 16>), dim3(grid), dim3(bs), 0, s, spec, (float2 *)kf,
+                           staged_fac_list(p), h0, nh, keep_dev, n_blocks);
+        break;
     default:
         set_error("fused3: no kernel for fft_size=%lld", (long long)p->M);
         return FFTCONV_EUNSUPPORTED;
@@ -753,6 +771,8 @@ int fused3_forward(const fftconv_plan *p, const void *u, const void *kf, void *y
     switch (p->M) {
     case 8192:
         return f16 ? launch<16, 16, F16, true>(p, u, kf, y, B, s) : launch<16, 16, BF16, true>(p, u, kf, y, B, s);
+    case 16384:
+        return f16 ? launch<32, 16, F16, false>(p, u, kf, y, B, s) : launch<32, 16, BF16, false>(p, u, kf, y, B, s);
     default:
         set_error("fused3: no kernel for fft_size=%lld", (long long)p->M);
         return FFTCONV_EUNSUPPORTED;

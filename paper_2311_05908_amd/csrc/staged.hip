@@ -149,8 +149,7 @@ __global__ void k_pack_staged(const double2 *spec, float2 *kf, FacList fl, int64
     int64_t h = idx / M, f = idx % M;
     int64_t p = freq_to_pos(f, fl, M);
     double2 v = spec[h * M + p];
-    double sc = 1.0 / (double)M;
-    if (keep && !keep[f / (M / n_blocks)]) sc = 0.0;
+    double sc = mask_weight(keep, n_blocks, f, M) / (double)M;
     kf[(h0 + h) * M + p] = make_float2((float)(v.x * sc), (float)(v.y * sc));
 }
 

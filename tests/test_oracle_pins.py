@@ -213,3 +213,17 @@ def test_rel_l2_metric():
     y = np.array([[3.0, 4.0], [0.0, 0.0]])
     r = np.array([[3.0, 0.0], [0.0, 0.0]])
     assert np.allclose(oracle.rel_l2_per_sequence(y, r), [4.0 / 3.0, 0.0])
+
+
+def test_masked_filter_spectrum_is_the_hermitian_part_of_the_masked_spectrum():
+    # Re(IDFT(keep . K)) has spectrum K[f] (keep[f] + keep[M-f]) / 2: the form the library stores.
+    M = 64
+    kext = RNG.standard_normal((1, M))
+    keep = np.zeros(M, dtype=np.uint8)
+    keep[:8] = 1
+    keep[M - 8:] = 1                      # block mask: bin 56 kept, its mirror bin 8 is not
+    kt = oracle.mask_filter(kext, keep)[0]
+    K = np.fft.fft(kext[0])
+    mirror = keep[(-np.arange(M)) % M]
+    assert np.allclose(np.fft.fft(kt), K * (keep + mirror) / 2.0, atol=1e-11)
+    assert (keep != mirror).sum() == 2    # the asymmetry the weight 1/2 is there for

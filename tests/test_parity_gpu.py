@@ -95,3 +95,29 @@ def test_fused3_fft8192(dtype, B, H, N):
           flush=True)
     assert plan.path == "fused3"
     assert err <= TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("B,H,N", [
+    (2, 2, 8192),
+    (5, 3, 8192),       # odd batch
+    (2, 1, 4000),       # ragged N
+])
+def test_fused3_fft16384(dtype, B, H, N):
+    w = synth.scaled(W["cfg5a"], B=B, H=H, N=N, fft_size=16384, dtype=dtype, Nk=0)
+    err, plan = check_all_sequences(w)
+    print("fused 16384 %s B=%d H=%d N=%d path=%s factors=%s err=%.3e" % (dtype, B, H, N, plan.path, plan.factors, err),
+          flush=True)
+    assert plan.path == "fused3" and plan.factors == [32, 32, 16]
+    assert err <= TOL[dtype]
+
+
+def test_cfg5_variants_reduced_batch():
+    """Partial and frequency-sparse filters on fft 16384 (reduced B, H), dense and skipping entry points."""
+    wa = synth.scaled(W["cfg5a"], B=4, H=3)
+    wb = synth.scaled(W["cfg5b"], B=4, H=3)
+    for w in (wa, wb):
+        for variant in ("dense", "skip"):
+            err, plan = check_all_sequences(w, variant=variant)
+            print("%s %s path=%s err=%.3e" % (w.name, variant, plan.path, err), flush=True)
+            assert err <= TOL[w.dtype]
