@@ -89,6 +89,9 @@ int fftconv_plan_create(fftconv_plan **out, int64_t N, int64_t fft_size, int64_t
         if (fused3_supported(N, fft_size, dtype)) {
             p->path = PATH_FUSED3;
             rc = fused3_init(p);
+        } else if (multipass_supported(N, fft_size, dtype)) {
+            p->path = PATH_MULTIPASS;
+            rc = multipass_init(p);
         } else {
             p->path = PATH_STAGED;
         }
@@ -114,13 +117,21 @@ int fftconv_plan_destroy(fftconv_plan *p)
 size_t fftconv_kf_bytes(const fftconv_plan *p)
 {
     if (!p) return 0;
-    return p->path == PATH_FUSED3 ? fused3_kf_bytes(p) : staged_kf_bytes(p);
+    switch (p->path) {
+    case PATH_FUSED3: return fused3_kf_bytes(p);
+    case PATH_MULTIPASS: return multipass_kf_bytes(p);
+    default: return staged_kf_bytes(p);
+    }
 }
 
 size_t fftconv_workspace_bytes(const fftconv_plan *p, int64_t B)
 {
     if (!p || B <= 0) return 0;
-    return p->path == PATH_STAGED ? staged_workspace_bytes(p, B) : 0;
+    switch (p->path) {
+    case PATH_FUSED3: return 0;
+    case PATH_MULTIPASS: return multipass_workspace_bytes(p, B);
+    default: return staged_workspace_bytes(p, B);
+    }
 }
 
 static int filter_fft_impl(const fftconv_plan *p, const float *k, int64_t Nk, const uint8_t *block_keep,
@@ -152,8 +163,11 @@ static int filter_fft_impl(const fftconv_plan *p, const float *k, int64_t Nk, co
         double2 *spec = nullptr;
         rc = staged_filter_transform(p, k, Nk, h0, nh, s, &spec);
         if (rc) return rc;
-        rc = p->path == PATH_FUSED3 ? fused3_pack_kf(p, spec, h0, nh, keep_dev, n_blocks, k_f, s)
-                                    : staged_pack_kf(p, spec, h0, nh, keep_dev, n_blocks, k_f, s);
+        switch (p->path) {
+        case PATH_FUSED3: rc = fused3_pack_kf(p, spec, h0, nh, keep_dev, n_blocks, k_f, s); break;
+        case PATH_MULTIPASS: rc = multipass_pack_kf(p, spec, h0, nh, keep_dev, n_blocks, k_f, s); break;
+        default: rc = staged_pack_kf(p, spec, h0, nh, keep_dev, n_blocks, k_f, s); break;
+        }
         if (rc) return rc;
     }
     return FFTCONV_OK;
@@ -214,6 +228,8 @@ int fftconv_forward(const fftconv_plan *p, const void *u, const void *k_f, void 
     switch (p->path) {
     case PATH_FUSED3:
         return fused3_forward(p, u, k_f, y, B, s);
+    case PATH_MULTIPASS:
+        return multipass_forward(p, u, k_f, y, B, workspace, s);
     default:
         return staged_forward(p, u, k_f, y, B, workspace, s);
     }
@@ -276,6 +292,11 @@ int fftconv_plan_factors(const fftconv_plan *p, int64_t *factors, int max_factor
         int64_t f[3] = {p->f3.N1, p->f3.N2, p->f3.N3};
         for (; n < 3 && n < max_factors; ++n) factors[n] = f[n];
         return 3;
+    }
+    if (p->path == PATH_MULTIPASS) {
+        int64_t f[4] = {p->M / ((int64_t)p->f3.N1 * p->f3.N2 * p->f3.N3), p->f3.N1, p->f3.N2, p->f3.N3};
+        for (; n < 4 && n < max_factors; ++n) factors[n] = f[n];
+        return 4;
     }
     for (; n < p->st.nf && n < max_factors; ++n) factors[n] = p->st.fac[n];
     return p->st.nf;

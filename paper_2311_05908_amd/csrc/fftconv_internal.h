@@ -119,5 +119,26 @@ size_t fused3_kf_bytes(const fftconv_plan *p);
 int fused3_pack_kf(const fftconv_plan *p, const double2 *spec, int64_t h0, int64_t nh,
                    const uint8_t *keep_dev, int64_t n_blocks, void *kf, hipStream_t s);
 int fused3_forward(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, hipStream_t s);
+// the 8192-point complex-row kernel used as the inner step of the multi-pass path
+int fused3_init_inner(fftconv_plan *p);
+int fused3_inner_rows(const fftconv_plan *p, void *rows, const void *kf, int64_t rows_per_kf, int64_t kf_rows,
+                      hipStream_t s);
+// slot of inner frequency fi (< 8192) in the 8192-point kernel's per-lane k_f order
+__host__ __device__ inline int fused3_kf_slot_8192(int64_t fi)
+{
+    const int k1 = (int)(fi % 32), k2 = (int)((fi / 32) % 16), k3 = (int)(fi / 512);
+    const int lane = (k3 / 4) * 16 + k2, r = k3 % 4;
+    return (k1 * 4 + r) * 64 + lane;
+}
+
+// ---- multi-pass path (multipass.hip)
+bool multipass_supported(int64_t N, int64_t M, int dtype);
+int multipass_init(fftconv_plan *p);
+size_t multipass_kf_bytes(const fftconv_plan *p);
+size_t multipass_workspace_bytes(const fftconv_plan *p, int64_t B);
+int multipass_pack_kf(const fftconv_plan *p, const double2 *spec, int64_t h0, int64_t nh,
+                      const uint8_t *keep_dev, int64_t n_blocks, void *kf, hipStream_t s);
+int multipass_forward(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, void *workspace,
+                      hipStream_t s);
 
 }  // namespace fftconv

@@ -112,14 +112,20 @@ template <int N2, int N3> struct Geo {
     static constexpr int SU = (N1 / 2) * PQ1;
     static constexpr int UB_ELEMS = 2 * SU;
     static constexpr size_t LDS_BYTES = (size_t)XB_WORDS * 4 + (size_t)UB_ELEMS * 2 * 2;
+    // complex-row variant: staging of 16-bit (re, im) pairs, 32-bit words: (n1, n2, n3) -> n1*PQ1C + n2*PRC + n3
+    static constexpr int PRC = N3 + 1;
+    static constexpr int PQ1C = N2 * PRC + 4;
+    static constexpr int UBC_WORDS = N1 * PQ1C;
+    static constexpr size_t LDS_BYTES_C = (size_t)XB_WORDS * 4 + (size_t)UBC_WORDS * 4 * 2;
+    static constexpr int CHUNKS_C = M / 4 / NT;  // 16-byte chunks (4 complex points) of a row per thread
     static constexpr int CHUNKS = M / 8 / NT;    // 16-byte chunks of a pair's input per thread
     static constexpr int CPS = CHUNKS / 2;       // ... per row of the pair
     // table sizes (entries)
-    static constexpr int TAB1 = 2 * 2 * 64;                 // [ct][part][lane] uint4
+    static constexpr int TAB1 = 2 * 2 * 2 * 64;             // [K step][ct][part][lane] uint4
     static constexpr int TAB2 = N3 * R2 * R2 * 2 * 64;      // [n3][t][ct][part][lane]
     static constexpr int TAB3 = R3 * R3 * 2 * 64;           // [t][ct][part][lane]
     static constexpr int TAB2I = N1 * R2 * R2 * 2 * 64;     // [k1][t][ct][part][lane]
-    static constexpr int TAB1I = 2 * 2 * 64;                // [t][part][lane]
+    static constexpr int TAB1I = 2 * 2 * 2 * 64;            // [K step][row tile][part][lane]
     static constexpr int TWA = N3 * R2 * 2 * 4 * 64;        // [n3][rt][ct][r][lane] float2
     static constexpr int TWB = N1 * R2 * R3 * 4 * 64;       // [k1][ct2][ct3][r][lane] float2
     static constexpr int KF_PER_H = N1 * R2 * R3 * 4 * 64;  // == M
@@ -138,29 +144,37 @@ __device__ __forceinline__ void cmul_ip(float &re, float &im, float2 w)
     im = i;
 }
 
-template <int N2, int N3, typename TT, bool REGC>
-__global__ void __launch_bounds__(NT) k_fused3(const uint16_t *__restrict__ u, uint16_t *__restrict__ y,
+// CPLX = false: u, y are (B, H, N) real rows; a work item is a pair of batch rows of one channel.
+// CPLX = true : u, y are (B, H, M) rows of 16-bit (re, im) pairs (u may equal y); a work item is
+//               one row, transformed in full (no implicit zeros), circular convolution of length M.
+//               This is the inner step of the multi-pass scheme (Algorithm 4).
+template <int N2, int N3, typename TT, bool REGC, bool CPLX>
+__global__ void __launch_bounds__(NT) k_fused3(const uint16_t *u, uint16_t *y,
                                               const float2 *__restrict__ kf, Consts cs, int B, int H, int N,
                                               int probe)
 {
     using G = Geo<N2, N3>;
     constexpr int R2 = G::R2, R3 = G::R3, C3 = G::C3, C1 = G::C1;
+    constexpr int KS1 = CPLX ? 2 : 1;            // K steps of forward stage 1 (n1 < 16 only when zero padded)
+    constexpr int RT1 = CPLX ? 2 : 1;            // output row tiles of inverse stage 1
+    constexpr int NCH = CPLX ? G::CHUNKS_C : G::CHUNKS;
     extern __shared__ uint32_t smem[];
     uint32_t *XB = smem;
     uint16_t *UB = (uint16_t *)(smem + G::XB_WORDS);
-    uint16_t *YB = UB + G::UB_ELEMS;
+    uint16_t *YB = UB + (CPLX ? 2 * G::UBC_WORDS : G::UB_ELEMS);
+    uint32_t *UBC = (uint32_t *)UB, *YBC = (uint32_t *)YB;
 
     const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, q = l >> 4, c16 = l & 15;
     // Persistent workgroup: a contiguous range [t0, t1) of work items t = h * npairs + pair, so the
     // constant tables are loaded once and k_f[h] once per channel the range touches.
-    const int npairs = (B + 1) / 2;
+    const int npairs = CPLX ? B : (B + 1) / 2;
     const long long T = (long long)H * npairs;
     const int t0 = (int)(T * blockIdx.x / gridDim.x);
     const int t1 = (int)(T * (blockIdx.x + 1) / gridDim.x);
     if (t0 >= t1) return;
 
     // ---------------- constants (per-lane operand tables) ----------------
-    uint4 tab1[2][2], tab1i[2][2], tab3[R3][R3][2], tab3i[R3][R3][2];
+    uint4 tab1[KS1][2][2], tab1i[2][RT1][2], tab3[R3][R3][2], tab3i[R3][R3][2];
     uint4 tab2[C3][R2][R2][2], tab2i[C1][R2][R2][2];
     float2 twa[C3][R2][2][4], twb[C1][R2][R3][4], kfr[C1][R2][R3][4];
 
@@ -168,8 +182,10 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *__restrict__ u, u
     for (int a = 0; a < 2; ++a)
 #pragma unroll
         for (int p = 0; p < 2; ++p) {
-            tab1[a][p] = cs.tab1[(a * 2 + p) * 64 + l];
-            tab1i[a][p] = cs.tab1i[(a * 2 + p) * 64 + l];
+#pragma unroll
+            for (int ks = 0; ks < KS1; ++ks) tab1[ks][a][p] = cs.tab1[((ks * 2 + a) * 2 + p) * 64 + l];
+#pragma unroll
+            for (int rt = 0; rt < RT1; ++rt) tab1i[a][rt][p] = cs.tab1i[((a * 2 + rt) * 2 + p) * 64 + l];
         }
 #pragma unroll
     for (int t = 0; t < R3; ++t)
@@ -242,9 +258,18 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *__restrict__ u, u
     }
 
     // ---------------- input prefetch (registers) ----------------
-    uint4 pre[G::CHUNKS];
+    uint4 pre[NCH];
     auto issue_loads = [&](int t) {
         const int h = t / npairs, pair = t - h * npairs;
+        if constexpr (CPLX) {
+            const uint16_t *row = u + ((size_t)pair * H + h) * (size_t)(2 * G::M);
+#pragma unroll
+            for (int j = 0; j < NCH; ++j) {
+                uint4 v = make_uint4(0, 0, 0, 0);
+                if (t < t1) v = *(const uint4 *)(row + (size_t)(tid + NT * j) * 8);
+                pre[j] = v;
+            }
+        } else
 #pragma unroll
         for (int j = 0; j < G::CHUNKS; ++j) {
             const int s = j / G::CPS;                    // which row of the pair (wave-uniform)
@@ -258,6 +283,18 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *__restrict__ u, u
     };
     // prefetched input -> UB (padded layout)
     auto stage_in = [&]() {
+        if constexpr (CPLX) {
+#pragma unroll
+            for (int j = 0; j < NCH; ++j) {
+                const int n = (tid + NT * j) * 4;
+                const int n3 = n % N3, n2 = (n / N3) % N2, n1 = n / (N2 * N3);
+                uint32_t *dst = UBC + n1 * G::PQ1C + n2 * G::PRC + n3;
+                dst[0] = pre[j].x;
+                dst[1] = pre[j].y;
+                dst[2] = pre[j].z;
+                dst[3] = pre[j].w;
+            }
+        } else
 #pragma unroll
         for (int j = 0; j < G::CHUNKS; ++j) {
             const int s = j / G::CPS;
@@ -273,6 +310,16 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *__restrict__ u, u
     // YB -> y, 16 bytes per lane, coalesced
     auto store_out = [&](int t) {
         const int h = t / npairs, pair = t - h * npairs;
+        if constexpr (CPLX) {
+            uint16_t *row = y + ((size_t)pair * H + h) * (size_t)(2 * G::M);
+#pragma unroll
+            for (int j = 0; j < NCH; ++j) {
+                const int n = (tid + NT * j) * 4;
+                const int n3 = n % N3, n2 = (n / N3) % N2, n1 = n / (N2 * N3);
+                const uint32_t *src = YBC + n1 * G::PQ1C + n2 * G::PRC + n3;
+                *(uint4 *)(row + (size_t)n * 2) = make_uint4(src[0], src[1], src[2], src[3]);
+            }
+        } else
 #pragma unroll
         for (int j = 0; j < G::CHUNKS; ++j) {
             const int s = j / G::CPS;
@@ -313,20 +360,29 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *__restrict__ u, u
         // (all operand reads first, then tile by tile compute -> write, so that the LDS
         //  traffic of one tile drains while the next tile computes)
         {
-            uint4 x1[C3][R2];
+            uint4 x1[C3][R2][KS1];
             if (PROBE_ON(1))
 #pragma unroll
             for (int i = 0; i < C3; ++i) {
                 const int c = w * C3 + i;
 #pragma unroll
                 for (int rt = 0; rt < R2; ++rt) {
-                    // operand of stage 1: row n2 = 16 rt + c16, slots (2r+s) = u_s[n1 = 4q + r]
-                    const uint16_t *p0 = UB + (4 * q) * G::PQ1 + (16 * rt + c16) * G::PR + c;
-                    uint32_t d[4];
+                    if constexpr (CPLX) {
+                        // row n2 = 16 rt + c16, slots (2r, 2r+1) = (re, im) of x[n1 = 16 ks + 4q + r]
 #pragma unroll
-                    for (int r = 0; r < 4; ++r)
-                        d[r] = (uint32_t)p0[r * G::PQ1] | ((uint32_t)p0[G::SU + r * G::PQ1] << 16);
-                    x1[i][rt] = make_uint4(d[0], d[1], d[2], d[3]);
+                        for (int ks = 0; ks < KS1; ++ks) {
+                            const uint32_t *p0 = UBC + (16 * ks + 4 * q) * G::PQ1C + (16 * rt + c16) * G::PRC + c;
+                            x1[i][rt][ks] = make_uint4(p0[0], p0[G::PQ1C], p0[2 * G::PQ1C], p0[3 * G::PQ1C]);
+                        }
+                    } else {
+                        // operand of stage 1: row n2 = 16 rt + c16, slots (2r+s) = u_s[n1 = 4q + r]
+                        const uint16_t *p0 = UB + (4 * q) * G::PQ1 + (16 * rt + c16) * G::PR + c;
+                        uint32_t d[4];
+#pragma unroll
+                        for (int r = 0; r < 4; ++r)
+                            d[r] = (uint32_t)p0[r * G::PQ1] | ((uint32_t)p0[G::SU + r * G::PQ1] << 16);
+                        x1[i][rt][0] = make_uint4(d[0], d[1], d[2], d[3]);
+                    }
                 }
             }
             if (PROBE_ON(1))
@@ -339,8 +395,12 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *__restrict__ u, u
                 for (int rt = 0; rt < R2; ++rt)
 #pragma unroll
                     for (int ct = 0; ct < 2; ++ct) {
-                        const f32x4 dre = TT::mfma(x1[i][rt], tab1[ct][0], zero4);
-                        const f32x4 dim = TT::mfma(x1[i][rt], tab1[ct][1], zero4);
+                        f32x4 dre = zero4, dim = zero4;
+#pragma unroll
+                        for (int ks = 0; ks < KS1; ++ks) {
+                            dre = TT::mfma(x1[i][rt][ks], tab1[ks][ct][0], dre);
+                            dim = TT::mfma(x1[i][rt][ks], tab1[ks][ct][1], dim);
+                        }
                         uint32_t o[4];
 #pragma unroll
                         for (int r = 0; r < 4; ++r) {
@@ -480,21 +540,29 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *__restrict__ u, u
             for (int i = 0; i < C3; ++i) {
                 const int c = w * C3 + i;
 #pragma unroll
-                for (int cn2 = 0; cn2 < R2; ++cn2) {
-                    f32x4 dre = zero4, dim = zero4;
+                for (int cn2 = 0; cn2 < R2; ++cn2)
 #pragma unroll
-                    for (int ks = 0; ks < 2; ++ks) {
-                        dre = TT::mfma(tab1i[ks][0], x1i[i][cn2][ks], dre);
-                        dim = TT::mfma(tab1i[ks][1], x1i[i][cn2][ks], dim);
-                    }
-                    // lane: n2 = 16 cn2 + c16; reg r: n1 = 4q + r
-                    uint16_t *dst = YB + (4 * q) * G::PQ1 + (16 * cn2 + c16) * G::PR + c;
+                    for (int rt = 0; rt < RT1; ++rt) {
+                        f32x4 dre = zero4, dim = zero4;
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        dst[r * G::PQ1] = TT::cvt(dre[r]);
-                        dst[G::SU + r * G::PQ1] = TT::cvt(dim[r]);
+                        for (int ks = 0; ks < 2; ++ks) {
+                            dre = TT::mfma(tab1i[ks][rt][0], x1i[i][cn2][ks], dre);
+                            dim = TT::mfma(tab1i[ks][rt][1], x1i[i][cn2][ks], dim);
+                        }
+                        // lane: n2 = 16 cn2 + c16; reg r: n1 = 16 rt + 4q + r
+                        if constexpr (CPLX) {
+                            uint32_t *dst = YBC + (16 * rt + 4 * q) * G::PQ1C + (16 * cn2 + c16) * G::PRC + c;
+#pragma unroll
+                            for (int r = 0; r < 4; ++r) dst[r * G::PQ1C] = TT::pack(dre[r], dim[r]);
+                        } else {
+                            uint16_t *dst = YB + (4 * q) * G::PQ1 + (16 * cn2 + c16) * G::PR + c;
+#pragma unroll
+                            for (int r = 0; r < 4; ++r) {
+                                dst[r * G::PQ1] = TT::cvt(dre[r]);
+                                dst[G::SU + r * G::PQ1] = TT::cvt(dim[r]);
+                            }
+                        }
                     }
-                }
             }
         }
         __syncthreads();
@@ -581,10 +649,11 @@ int build_tables(fftconv_plan *p)
     std::vector<float2> tw(n_f2);
     size_t o = 0;
     auto next = [&]() { uint16_t *d = ops.data() + o * 8; o += 64; return d; };
-    // tab1 [ct][part]: W_N1^{n1 k1}, n1 < 16
-    for (int ct = 0; ct < 2; ++ct)
-        for (int part = 0; part < 2; ++part)
-            fill_operand(next(), f16, 0, ct, part, [&](int n1, int k1) { return wpow(N1, (int64_t)n1 * k1); });
+    // tab1 [K step][ct][part]: W_N1^{n1 k1}; zero-padded real input only meets K step 0 (n1 < 16)
+    for (int ks = 0; ks < 2; ++ks)
+        for (int ct = 0; ct < 2; ++ct)
+            for (int part = 0; part < 2; ++part)
+                fill_operand(next(), f16, ks, ct, part, [&](int n1, int k1) { return wpow(N1, (int64_t)n1 * k1); });
     // tab2 [n3][t][ct][part]: W_N2^{n2 k2} W_{N2 N3}^{k2 n3}
     for (int n3 = 0; n3 < N3; ++n3)
         for (int t = 0; t < G::R2; ++t)
@@ -612,10 +681,12 @@ int build_tables(fftconv_plan *p)
                     fill_operand(next(), f16, t, ct, part, [&](int k2, int n2) {
                         return conjh(cmulh(wpow(N2, (int64_t)n2 * k2), wpow((int64_t)N1 * N2, (int64_t)k1 * n2)));
                     });
-    // tab1i [t][part]: conj(W_N1^{k1 n1}), output rows n1 < 16
+    // tab1i [K step][row tile][part]: conj(W_N1^{k1 n1}); the causal kernel only forms row tile 0 (n1 < 16)
     for (int t = 0; t < 2; ++t)
-        for (int part = 0; part < 2; ++part)
-            fill_operand(next(), f16, t, 0, part, [&](int k1, int n1) { return conjh(wpow(N1, (int64_t)n1 * k1)); });
+        for (int rt = 0; rt < 2; ++rt)
+            for (int part = 0; part < 2; ++part)
+                fill_operand(next(), f16, t, rt, part,
+                             [&](int k1, int n1) { return conjh(wpow(N1, (int64_t)n1 * k1)); });
     if (o != n_u4) {
         set_error("fused3: operand table size mismatch");
         return FFTCONV_EINVAL;
@@ -676,27 +747,30 @@ int probe_mask()
 #endif
 }
 
-template <int N2, int N3, typename TT, bool REGC>
-int launch(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, hipStream_t s)
+// Rows: for the causal kernel (CPLX false) B batch rows of H channels, N samples each; for the
+// complex-row kernel B rows per k_f row, H k_f rows.
+template <int N2, int N3, typename TT, bool REGC, bool CPLX>
+int launch(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, int64_t H, int64_t N,
+           hipStream_t s)
 {
     using G = Geo<N2, N3>;
-    auto kern = k_fused3<N2, N3, TT, REGC>;
+    auto kern = k_fused3<N2, N3, TT, REGC, CPLX>;
+    constexpr size_t lds = CPLX ? G::LDS_BYTES_C : G::LDS_BYTES;
     static bool attr_set = false;
     if (!attr_set) {
-        FC_HIP(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                   (int)G::LDS_BYTES));
+        FC_HIP(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         attr_set = true;
     }
-    const int64_t npairs = (B + 1) / 2;
-    const int64_t T = p->H * npairs;
+    const int64_t npairs = CPLX ? B : (B + 1) / 2;
+    const int64_t T = H * npairs;
     if (T >= ((int64_t)1 << 31)) {
         set_error("fftconv_forward: H * ceil(B/2) = %lld work items exceed the fused kernel's 2^31 limit", (long long)T);
         return FFTCONV_EUNSUPPORTED;
     }
     // one persistent workgroup per compute unit (fewer when there is less work than that)
     const int grid = (int)(T < p->f3.num_cu ? T : p->f3.num_cu);
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NT), G::LDS_BYTES, s, (const uint16_t *)u, (uint16_t *)y,
-                       (const float2 *)kf, consts_of<N2, N3>(p), (int)B, (int)p->H, (int)p->N, probe_mask());
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NT), lds, s, (const uint16_t *)u, (uint16_t *)y,
+                       (const float2 *)kf, consts_of<N2, N3>(p), (int)B, (int)H, (int)N, probe_mask());
     FC_HIP(hipGetLastError());
     return FFTCONV_OK;
 }
@@ -729,6 +803,25 @@ int fused3_init(fftconv_plan *p)
         set_error("fused3: no kernel for fft_size=%lld", (long long)p->M);
         return FFTCONV_EUNSUPPORTED;
     }
+}
+
+int fused3_init_inner(fftconv_plan *p)
+{
+    p->f3.N1 = N1;
+    p->f3.N2 = 16;
+    p->f3.N3 = 16;
+    hipDeviceProp_t prop;
+    FC_HIP(hipGetDeviceProperties(&prop, p->device));
+    p->f3.num_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    return build_tables<16, 16>(p);
+}
+
+int fused3_inner_rows(const fftconv_plan *p, void *rows, const void *kf, int64_t rows_per_kf, int64_t kf_rows,
+                      hipStream_t s)
+{
+    if (p->dtype == FFTCONV_F16)
+        return launch<16, 16, F16, false, true>(p, rows, kf, rows, rows_per_kf, kf_rows, Geo<16, 16>::M, s);
+    return launch<16, 16, BF16, false, true>(p, rows, kf, rows, rows_per_kf, kf_rows, Geo<16, 16>::M, s);
 }
 
 void fused3_destroy(fftconv_plan *p)
@@ -770,9 +863,11 @@ int fused3_forward(const fftconv_plan *p, const void *u, const void *kf, void *y
     const bool f16 = p->dtype == FFTCONV_F16;
     switch (p->M) {
     case 8192:
-        return f16 ? launch<16, 16, F16, true>(p, u, kf, y, B, s) : launch<16, 16, BF16, true>(p, u, kf, y, B, s);
+        return f16 ? launch<16, 16, F16, true, false>(p, u, kf, y, B, p->H, p->N, s)
+                   : launch<16, 16, BF16, true, false>(p, u, kf, y, B, p->H, p->N, s);
     case 16384:
-        return f16 ? launch<32, 16, F16, false>(p, u, kf, y, B, s) : launch<32, 16, BF16, false>(p, u, kf, y, B, s);
+        return f16 ? launch<32, 16, F16, false, false>(p, u, kf, y, B, p->H, p->N, s)
+                   : launch<32, 16, BF16, false, false>(p, u, kf, y, B, p->H, p->N, s);
     default:
         set_error("fused3: no kernel for fft_size=%lld", (long long)p->M);
         return FFTCONV_EUNSUPPORTED;

@@ -121,3 +121,34 @@ def test_cfg5_variants_reduced_batch():
             err, plan = check_all_sequences(w, variant=variant)
             print("%s %s path=%s err=%.3e" % (w.name, variant, plan.path, err), flush=True)
             assert err <= TOL[w.dtype]
+
+
+# ---------------------------------------------------------------- multi-pass path (Algorithm 4)
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("B,H,N,M", [
+    (3, 2, 16384, 32768),      # outer length 4, odd batch
+    (2, 2, 32768, 65536),      # outer length 8
+    (1, 1, 10000, 32768),      # ragged N, B = 1
+])
+def test_multipass_all_outputs(dtype, B, H, N, M):
+    w = synth.scaled(W["cfg3"], B=B, H=H, N=N, fft_size=M, dtype=dtype)
+    err, plan = check_all_sequences(w)
+    print("multipass %s B=%d H=%d N=%d M=%d path=%s factors=%s err=%.3e" % (dtype, B, H, N, M, plan.path, plan.factors, err),
+          flush=True)
+    assert plan.path == "multipass"
+    assert err <= TOL[dtype]
+
+
+@pytest.mark.parametrize("B,H,N,M", [
+    (2, 1, 1 << 17, 1 << 18),      # outer length 32 = 16 x 2
+    (1, 2, 1 << 20, 1 << 21),      # the very long configuration at H = 2: outer length 256 = 16 x 16
+])
+def test_multipass_long_sampled_positions(B, H, N, M):
+    from parity_util import check_sampled_positions
+    w = synth.scaled(W["cfg4"], B=B, H=H, N=N, fft_size=M)
+    err, plan = check_sampled_positions(w)
+    print("multipass long B=%d H=%d N=%d M=%d path=%s factors=%s err=%.3e" % (B, H, N, M, plan.path, plan.factors, err),
+          flush=True)
+    assert plan.path == "multipass"
+    assert err <= TOL[w.dtype]
