@@ -58,3 +58,36 @@ def test_cfg2_full_size_sampled_sequences():
     y2 = plan.forward(u, kf)
     torch.cuda.synchronize()
     assert torch.equal(y, y2)
+
+
+def test_cfg3_full_size_sampled_sequences():
+    w = W["cfg3"]
+    worst, plan, _ = run_full(w, 8)
+    print("cfg3 full: path=%s factors=%s worst sampled rel L2 = %.3e" % (plan.path, plan.factors, worst), flush=True)
+    assert worst <= TOL[w.dtype]
+
+
+def test_cfg5a_partial_full_size_both_entry_points():
+    w = W["cfg5a"]
+    for variant in ("dense", "skip"):
+        worst, plan, _ = run_full(w, 12, variant=variant)
+        print("cfg5a full %s: path=%s worst sampled rel L2 = %.3e" % (variant, plan.path, worst), flush=True)
+        assert worst <= TOL[w.dtype]
+
+
+def test_cfg5b_frequency_sparse_full_size_both_entry_points():
+    w = W["cfg5b"]
+    for variant in ("dense", "skip"):
+        worst, plan, _ = run_full(w, 4, variant=variant)
+        print("cfg5b full %s: path=%s worst sampled rel L2 = %.3e" % (variant, plan.path, worst), flush=True)
+        assert worst <= TOL[w.dtype]
+
+
+def test_cfg4_very_long_full_size_sampled_positions():
+    from parity_util import check_sampled_positions
+    w = W["cfg4"]
+    err, plan = check_sampled_positions(w, n_pos=24)
+    print("cfg4 full: path=%s factors=%s worst rel L2 over sampled positions = %.3e" % (plan.path, plan.factors, err),
+          flush=True)
+    assert plan.path == "multipass"
+    assert err <= TOL[w.dtype]
