@@ -44,7 +44,10 @@
 #include <cstring>
 #include <vector>
 
-#include "fftconv_internal.h"
+#include <hip/hip_bf16.h>
+#include <hip/hip_fp16.h>
+
+#include "fused3_common.h"
 
 // Timing probes (development builds only, -DFUSED3_PROBE): a launch-time mask switches whole
 // phases off so their cost can be read from the difference.  Results are then meaningless.
@@ -58,91 +61,7 @@ namespace fftconv {
 
 namespace {
 
-constexpr int N1 = 32;
-constexpr int NT = 512;
-constexpr int NW = NT / 64;
-
-typedef __attribute__((ext_vector_type(4))) float f32x4;
-typedef __attribute__((ext_vector_type(2))) float f32x2;
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
-typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
-typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
-
-struct BF16 {
-    static __device__ __forceinline__ f32x4 mfma(uint4 a, uint4 b, f32x4 c)
-    {
-        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c,
-                                                       0, 0, 0);
-    }
-    static __device__ __forceinline__ uint32_t pack(float lo, float hi)
-    {
-        f32x2 v = {lo, hi};
-        return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
-    }
-    static __device__ __forceinline__ uint16_t cvt(float x) { return __builtin_bit_cast(uint16_t, (__bf16)x); }
-};
-struct F16 {
-    static __device__ __forceinline__ f32x4 mfma(uint4 a, uint4 b, f32x4 c)
-    {
-        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0,
-                                                      0, 0);
-    }
-    static __device__ __forceinline__ uint32_t pack(float lo, float hi)
-    {
-        f32x2 v = {lo, hi};
-        return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));
-    }
-    static __device__ __forceinline__ uint16_t cvt(float x) { return __builtin_bit_cast(uint16_t, (_Float16)x); }
-};
-
-template <int N2, int N3> struct Geo {
-    static constexpr int M = N1 * N2 * N3;
-    static constexpr int R2 = N2 / 16, R3 = N3 / 16;
-    static constexpr int C3 = N3 / NW;           // n3 values per wave (phases A, C)
-    static constexpr int C1 = N1 / NW;           // k1 values per wave (phase B)
-    // exchange buffer, 32-bit words: X(k1,k2,n3) = n3*PN3 + k1*PK1 + k2.
-    // 4*PK1 and 4*PN3 are 16 mod 32, which spreads the 4 lane groups of a wave over the banks.
-    static constexpr int PK1 = N2 + 4;
-    static constexpr int PN3 = N1 * PK1 + 4;
-    static constexpr int XB_WORDS = N3 * PN3;
-    // staging of u / y, 16-bit elements: (s, n1, n2, n3) -> s*SU + n1*PQ1 + n2*PR + n3
-    static constexpr int PR = N3 + 2;
-    static constexpr int PQ1 = N2 * PR + 8;
-    static constexpr int SU = (N1 / 2) * PQ1;
-    static constexpr int UB_ELEMS = 2 * SU;
-    static constexpr size_t LDS_BYTES = (size_t)XB_WORDS * 4 + (size_t)UB_ELEMS * 2 * 2;
-    // complex-row variant: staging of 16-bit (re, im) pairs, 32-bit words: (n1, n2, n3) -> n1*PQ1C + n2*PRC + n3
-    static constexpr int PRC = N3 + 1;
-    static constexpr int PQ1C = N2 * PRC + 4;
-    static constexpr int UBC_WORDS = N1 * PQ1C;
-    static constexpr size_t LDS_BYTES_C = (size_t)XB_WORDS * 4 + (size_t)UBC_WORDS * 4 * 2;
-    static constexpr int CHUNKS_C = M / 4 / NT;  // 16-byte chunks (4 complex points) of a row per thread
-    static constexpr int CHUNKS = M / 8 / NT;    // 16-byte chunks of a pair's input per thread
-    static constexpr int CPS = CHUNKS / 2;       // ... per row of the pair
-    // table sizes (entries)
-    static constexpr int TAB1 = 2 * 2 * 2 * 64;             // [K step][ct][part][lane] uint4
-    static constexpr int TAB2 = N3 * R2 * R2 * 2 * 64;      // [n3][t][ct][part][lane]
-    static constexpr int TAB3 = R3 * R3 * 2 * 64;           // [t][ct][part][lane]
-    static constexpr int TAB2I = N1 * R2 * R2 * 2 * 64;     // [k1][t][ct][part][lane]
-    static constexpr int TAB1I = 2 * 2 * 2 * 64;            // [K step][row tile][part][lane]
-    static constexpr int TWA = N3 * R2 * 2 * 4 * 64;        // [n3][rt][ct][r][lane] float2
-    static constexpr int TWB = N1 * R2 * R3 * 4 * 64;       // [k1][ct2][ct3][r][lane] float2
-    static constexpr int KF_PER_H = N1 * R2 * R3 * 4 * 64;  // == M
-};
-
-struct Consts {
-    const uint4 *tab1, *tab2, *tab3, *tab3i, *tab2i, *tab1i;
-    const float2 *twa, *twb;
-};
-
-__device__ __forceinline__ void cmul_ip(float &re, float &im, float2 w)
-{
-    float r = re * w.x - im * w.y;
-    float i = re * w.y + im * w.x;
-    re = r;
-    im = i;
-}
+using namespace f3;
 
 // CPLX = false: u, y are (B, H, N) real rows; a work item is a pair of batch rows of one channel.
 // CPLX = true : u, y are (B, H, M) rows of 16-bit (re, im) pairs (u may equal y); a work item is
@@ -416,14 +335,14 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *u, uint16_t *y,
                     for (int ct2 = 0; ct2 < R2; ++ct2) {
                         f32x4 dre = zero4, dim = zero4;
 #pragma unroll
-                        for (int ks = 0; ks < R2; ++ks) {
-                            dre = TT::mfma(x2[ct][ks], tab2[i][ks][ct2][0], dre);
-                            dim = TT::mfma(x2[ct][ks], tab2[i][ks][ct2][1], dim);
+                        for (int ks = 0; ks < R2; ++ks) {   // matrix as the A operand: rows k2, data columns k1
+                            dre = TT::mfma(tab2[i][ks][ct2][0], x2[ct][ks], dre);
+                            dim = TT::mfma(tab2[i][ks][ct2][1], x2[ct][ks], dim);
                         }
-                        // lane: k2 = 16 ct2 + c16; reg r: k1 = 16 ct + 4q + r
-                        uint32_t *dst = XB + c * G::PN3 + (16 * ct + 4 * q) * G::PK1 + 16 * ct2 + c16;
-#pragma unroll
-                        for (int r = 0; r < 4; ++r) dst[r * G::PK1] = TT::pack(dre[r], dim[r]);
+                        // lane: k1 = 16 ct + c16; reg r: k2 = 16 ct2 + 4q + r -> 4 consecutive words, one 16-byte write
+                        uint32_t *dst = XB + c * G::PN3 + (16 * ct + c16) * G::PK1 + 16 * ct2 + 4 * q;
+                        *(uint4 *)dst = make_uint4(TT::pack(dre[0], dim[0]), TT::pack(dre[1], dim[1]),
+                                                   TT::pack(dre[2], dim[2]), TT::pack(dre[3], dim[3]));
                     }
             }
         }
@@ -507,14 +426,14 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *u, uint16_t *y,
                     for (int cn2 = 0; cn2 < R2; ++cn2) {
                         f32x4 dre = zero4, dim = zero4;
 #pragma unroll
-                        for (int ks = 0; ks < R2; ++ks) {
-                            dre = TT::mfma(x2i[cn3][ks], tab2i[i][ks][cn2][0], dre);
-                            dim = TT::mfma(x2i[cn3][ks], tab2i[i][ks][cn2][1], dim);
+                        for (int ks = 0; ks < R2; ++ks) {   // matrix as the A operand: rows n2, data columns n3
+                            dre = TT::mfma(tab2i[i][ks][cn2][0], x2i[cn3][ks], dre);
+                            dim = TT::mfma(tab2i[i][ks][cn2][1], x2i[cn3][ks], dim);
                         }
-                        // lane: n2 = 16 cn2 + c16; reg r: n3 = 16 cn3 + 4q + r
-                        uint32_t *dst = XB + (16 * cn3 + 4 * q) * G::PN3 + c * G::PK1 + 16 * cn2 + c16;
-#pragma unroll
-                        for (int r = 0; r < 4; ++r) dst[r * G::PN3] = TT::pack(dre[r], dim[r]);
+                        // lane: n3 = 16 cn3 + c16; reg r: n2 = 16 cn2 + 4q + r -> one 16-byte write
+                        uint32_t *dst = XB + (16 * cn3 + c16) * G::PN3 + c * G::PK1 + 16 * cn2 + 4 * q;
+                        *(uint4 *)dst = make_uint4(TT::pack(dre[0], dim[0]), TT::pack(dre[1], dim[1]),
+                                                   TT::pack(dre[2], dim[2]), TT::pack(dre[3], dim[3]));
                     }
             }
         }
@@ -572,9 +491,10 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *u, uint16_t *y,
 
 // k_f in the fused kernel's per-lane order: [h][k1][k2 tile][k3 tile][r][lane] float2, where the
 // lane holds k2 = 16 tile + lane%16 and k3 = 16 tile + 4 (lane/16) + r.
+// fmt 0: fp32 pairs; fmt 1 / 2: 16-bit constant pairs for TT::ctw (bf16 dot-product / fp16 packed form)
 template <int N2, int N3>
 __global__ void k_pack_fused3(const double2 *spec, float2 *kf, FacList fl, int64_t h0, int64_t nh,
-                              const uint8_t *keep, int64_t n_blocks)
+                              const uint8_t *keep, int64_t n_blocks, int fmt)
 {
     using G = Geo<N2, N3>;
     constexpr int64_t M = G::M;
@@ -586,7 +506,22 @@ __global__ void k_pack_fused3(const double2 *spec, float2 *kf, FacList fl, int64
     int64_t dst = ((((int64_t)k1 * G::R2 + k2 / 16) * G::R3 + k3 / 16) * 4 + r) * 64 + lane;
     double2 v = spec[h * M + freq_to_pos(f, fl, M)];
     double sc = mask_weight(keep, n_blocks, f, M) / (double)M;
-    kf[(h0 + h) * M + dst] = make_float2((float)(v.x * sc), (float)(v.y * sc));
+    if (fmt == 0) {
+        kf[(h0 + h) * M + dst] = make_float2((float)(v.x * sc), (float)(v.y * sc));
+    } else {
+        uint2 c;
+        if (fmt == 1)
+            c = ctw_const(v.x * sc, v.y * sc, 1, [](double x) {
+                __hip_bfloat16 b = __float2bfloat16((float)x);
+                return *(uint16_t *)&b;
+            });
+        else
+            c = ctw_const(v.x * sc, v.y * sc, 2, [](double x) {
+                __half hv = __float2half_rn((float)x);
+                return *(uint16_t *)&hv;
+            });
+        ((uint2 *)kf)[(h0 + h) * M + dst] = c;
+    }
 }
 
 // ---------------------------------------------------------------- host side
@@ -647,6 +582,9 @@ int build_tables(fftconv_plan *p)
     const size_t n_f2 = (size_t)G::TWA + G::TWB;
     std::vector<uint16_t> ops(n_u4 * 8);
     std::vector<float2> tw(n_f2);
+    std::vector<uint2> tw16(n_f2);
+    const int cfmt = f16 ? 2 : 1;
+    auto hi16 = [&](double v) { return f16 ? to_f16(v) : to_bf16(v); };
     size_t o = 0;
     auto next = [&]() { uint16_t *d = ops.data() + o * 8; o += 64; return d; };
     // tab1 [K step][ct][part]: W_N1^{n1 k1}; zero-padded real input only meets K step 0 (n1 < 16)
@@ -700,6 +638,7 @@ int build_tables(fftconv_plan *p)
                     for (int lane = 0; lane < 64; ++lane) {
                         int k1 = 16 * ct + lane % 16, n2 = 16 * rt + 4 * (lane / 16) + r;
                         Cplx v = wpow(M, (int64_t)k1 * ((int64_t)N3 * n2 + n3));
+                        tw16[w] = ctw_const(v.re, v.im, cfmt, hi16);
                         tw[w++] = make_float2((float)v.re, (float)v.im);
                     }
     // twb [k1][ct2][ct3][r][lane]: conj(W_M^{(k1 + N1 k2) n3}), n3 = 16 ct3 + c16, k2 = 16 ct2 + 4 q + r
@@ -710,31 +649,16 @@ int build_tables(fftconv_plan *p)
                     for (int lane = 0; lane < 64; ++lane) {
                         int n3 = 16 * ct3 + lane % 16, k2 = 16 * ct2 + 4 * (lane / 16) + r;
                         Cplx v = conjh(wpow(M, ((int64_t)k1 + (int64_t)N1 * k2) * n3));
+                        tw16[w] = ctw_const(v.re, v.im, cfmt, hi16);
                         tw[w++] = make_float2((float)v.re, (float)v.im);
                     }
-    const size_t bytes = n_u4 * 16 + n_f2 * 8;
+    const size_t bytes = n_u4 * 16 + 2 * n_f2 * 8;
     FC_HIP(hipMalloc(&p->f3.consts, bytes));
     p->f3.consts_bytes = bytes;
     FC_HIP(hipMemcpy(p->f3.consts, ops.data(), n_u4 * 16, hipMemcpyHostToDevice));
     FC_HIP(hipMemcpy((char *)p->f3.consts + n_u4 * 16, tw.data(), n_f2 * 8, hipMemcpyHostToDevice));
+    FC_HIP(hipMemcpy((char *)p->f3.consts + n_u4 * 16 + n_f2 * 8, tw16.data(), n_f2 * 8, hipMemcpyHostToDevice));
     return FFTCONV_OK;
-}
-
-template <int N2, int N3>
-Consts consts_of(const fftconv_plan *p)
-{
-    using G = Geo<N2, N3>;
-    Consts c;
-    const uint4 *b = (const uint4 *)p->f3.consts;
-    c.tab1 = b;
-    c.tab2 = c.tab1 + G::TAB1;
-    c.tab3 = c.tab2 + G::TAB2;
-    c.tab3i = c.tab3 + G::TAB3;
-    c.tab2i = c.tab3i + G::TAB3;
-    c.tab1i = c.tab2i + G::TAB2I;
-    c.twa = (const float2 *)(c.tab1i + G::TAB1I);
-    c.twb = c.twa + G::TWA;
-    return c;
 }
 
 int probe_mask()
@@ -839,12 +763,13 @@ int fused3_pack_kf(const fftconv_plan *p, const double2 *spec, int64_t h0, int64
     const unsigned grid = (unsigned)((nh * p->M + bs - 1) / bs);
     switch (p->M) {
     case 8192:
+        // the wave-specialised 8192 kernel takes k_f as 16-bit constant pairs
         hipLaunchKernelGGL((k_pack_fused3<16, 16>), dim3(grid), dim3(bs), 0, s, spec, (float2 *)kf,
-                           staged_fac_list(p), h0, nh, keep_dev, n_blocks);
+                           staged_fac_list(p), h0, nh, keep_dev, n_blocks, p->dtype == FFTCONV_F16 ? 2 : 1);
         break;
     case 16384:
         hipLaunchKernelGGL((k_pack_fused3<32, 16>), dim3(grid), dim3(bs), 0, s, spec, (float2 *)kf,
-                           staged_fac_list(p), h0, nh, keep_dev, n_blocks);
+                           staged_fac_list(p), h0, nh, keep_dev, n_blocks, 0);
         break;
     default:
         set_error("fused3: no kernel for fft_size=%lld", (long long)p->M);
@@ -863,8 +788,7 @@ int fused3_forward(const fftconv_plan *p, const void *u, const void *kf, void *y
     const bool f16 = p->dtype == FFTCONV_F16;
     switch (p->M) {
     case 8192:
-        return f16 ? launch<16, 16, F16, true, false>(p, u, kf, y, B, p->H, p->N, s)
-                   : launch<16, 16, BF16, true, false>(p, u, kf, y, B, p->H, p->N, s);
+        return fused3_ws_launch(p, u, kf, y, B, s);     // wave-specialised schedule (fused3_ws.hip)
     case 16384:
         return f16 ? launch<32, 16, F16, false, false>(p, u, kf, y, B, p->H, p->N, s)
                    : launch<32, 16, BF16, false, false>(p, u, kf, y, B, p->H, p->N, s);

@@ -1,0 +1,184 @@
+// Definitions shared by the fused order-3 kernels (fused3.hip, fused3_ws.hip): MFMA wrappers,
+// tile geometry / LDS layouts of fft_size = 32 * N2 * N3, and the table pointers.
+#pragma once
+
+#include "fftconv_internal.h"
+
+namespace fftconv {
+namespace f3 {
+
+constexpr int N1 = 32;
+constexpr int NT = 512;
+constexpr int NW = NT / 64;
+
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
+
+struct BF16 {
+    static __device__ __forceinline__ f32x4 mfma(uint4 a, uint4 b, f32x4 c)
+    {
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c,
+                                                       0, 0, 0);
+    }
+    static __device__ __forceinline__ uint32_t pack(float lo, float hi)
+    {
+        f32x2 v = {lo, hi};
+        return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+    }
+    static __device__ __forceinline__ uint16_t cvt(float x) { return __builtin_bit_cast(uint16_t, (__bf16)x); }
+    // Four complex products (re[r] + i im[r]) * w[r], each packed as a 16-bit (re, im) pair;
+    // c[r] = { (wr, -wi), (wi, wr) } as bf16 pairs.  The operand is rounded to bf16 first, the two
+    // dot products of each point accumulate in fp32: 4 vector ops per point instead of 5.
+    // Written as one asm block because the compiler would pick the accumulate-only form of the dot
+    // product (one extra move per product).  On this target a DOT result may be read by another
+    // vector op only 3 issue slots later; the compiler cannot see into the block, so the order
+    // below keeps every producer / consumer pair at least 3 instructions apart.  The packs that
+    // read MFMA results stay outside the block, where the compiler places the MFMA wait states.
+    static __device__ __forceinline__ uint4 ctw4(f32x4 re, f32x4 im, const uint2 (&c)[4])
+    {
+        const uint32_t p0 = pack(re[0], im[0]), p1 = pack(re[1], im[1]);
+        const uint32_t p2 = pack(re[2], im[2]), p3 = pack(re[3], im[3]);
+        uint32_t t0, t1, t2, t3, t4, t5, t6, t7;
+        asm("v_dot2_f32_bf16 %0, %8, %12, 0\n\t"
+            "v_dot2_f32_bf16 %1, %8, %13, 0\n\t"
+            "v_dot2_f32_bf16 %2, %9, %14, 0\n\t"
+            "v_dot2_f32_bf16 %3, %9, %15, 0\n\t"
+            "v_dot2_f32_bf16 %4, %10, %16, 0\n\t"
+            "v_dot2_f32_bf16 %5, %10, %17, 0\n\t"
+            "v_dot2_f32_bf16 %6, %11, %18, 0\n\t"
+            "v_dot2_f32_bf16 %7, %11, %19, 0\n\t"
+            "v_cvt_pk_bf16_f32 %0, %0, %1\n\t"
+            "v_cvt_pk_bf16_f32 %2, %2, %3\n\t"
+            "v_cvt_pk_bf16_f32 %4, %4, %5\n\t"
+            "v_cvt_pk_bf16_f32 %6, %6, %7"
+            : "=&v"(t0), "=&v"(t1), "=&v"(t2), "=&v"(t3), "=&v"(t4), "=&v"(t5), "=&v"(t6), "=&v"(t7)
+            : "v"(p0), "v"(p1), "v"(p2), "v"(p3), "v"(c[0].x), "v"(c[0].y), "v"(c[1].x), "v"(c[1].y),
+              "v"(c[2].x), "v"(c[2].y), "v"(c[3].x), "v"(c[3].y));
+        return make_uint4(t0, t2, t4, t6);
+    }
+    static constexpr int CFMT = 1;
+};
+struct F16 {
+    static __device__ __forceinline__ f32x4 mfma(uint4 a, uint4 b, f32x4 c)
+    {
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0,
+                                                      0, 0);
+    }
+    static __device__ __forceinline__ uint32_t pack(float lo, float hi)
+    {
+        f32x2 v = {lo, hi};
+        return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));
+    }
+    static __device__ __forceinline__ uint16_t cvt(float x) { return __builtin_bit_cast(uint16_t, (_Float16)x); }
+    // Four complex products in packed fp16 arithmetic (3 vector ops per point);
+    // c[r] = { (wr, wr), (-wi, wi) } as fp16 pairs.
+    static __device__ __forceinline__ uint4 ctw4(f32x4 re, f32x4 im, const uint2 (&c)[4])
+    {
+        uint32_t o[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            f32x2 v = {re[r], im[r]};
+            const f16x2 p = __builtin_convertvector(v, f16x2);
+            const f16x2 t = p * __builtin_bit_cast(f16x2, c[r].x);
+            const f16x2 sw = {p[1], p[0]};
+            o[r] = __builtin_bit_cast(uint32_t, __builtin_elementwise_fma(sw, __builtin_bit_cast(f16x2, c[r].y), t));
+        }
+        return make_uint4(o[0], o[1], o[2], o[3]);
+    }
+    static constexpr int CFMT = 2;
+};
+
+template <int N2, int N3> struct Geo {
+    static constexpr int M = N1 * N2 * N3;
+    static constexpr int R2 = N2 / 16, R3 = N3 / 16;
+    static constexpr int C3 = N3 / NW;           // n3 values per wave (phases A, C)
+    static constexpr int C1 = N1 / NW;           // k1 values per wave (phase B)
+    // exchange buffer, 32-bit words: X(k1,k2,n3) = n3*PN3 + k1*PK1 + k2.
+    // 4*PK1 and 4*PN3 are 16 mod 32, which spreads the 4 lane groups of a wave over the banks.
+    static constexpr int PK1 = N2 + 4;
+    static constexpr int PN3 = N1 * PK1 + 4;
+    static constexpr int XB_WORDS = N3 * PN3;
+    // staging of u / y, 16-bit elements: (s, n1, n2, n3) -> s*SU + n1*PQ1 + n2*PR + n3
+    static constexpr int PR = N3 + 2;
+    static constexpr int PQ1 = N2 * PR + 8;
+    static constexpr int SU = (N1 / 2) * PQ1;
+    static constexpr int UB_ELEMS = 2 * SU;
+    static constexpr size_t LDS_BYTES = (size_t)XB_WORDS * 4 + (size_t)UB_ELEMS * 2 * 2;
+    // complex-row variant: staging of 16-bit (re, im) pairs, 32-bit words: (n1, n2, n3) -> n1*PQ1C + n2*PRC + n3
+    static constexpr int PRC = N3 + 1;
+    static constexpr int PQ1C = N2 * PRC + 4;
+    static constexpr int UBC_WORDS = N1 * PQ1C;
+    static constexpr size_t LDS_BYTES_C = (size_t)XB_WORDS * 4 + (size_t)UBC_WORDS * 4 * 2;
+    static constexpr int CHUNKS_C = M / 4 / NT;  // 16-byte chunks (4 complex points) of a row per thread
+    static constexpr int CHUNKS = M / 8 / NT;    // 16-byte chunks of a pair's input per thread
+    static constexpr int CPS = CHUNKS / 2;       // ... per row of the pair
+    // table sizes (entries)
+    static constexpr int TAB1 = 2 * 2 * 2 * 64;             // [K step][ct][part][lane] uint4
+    static constexpr int TAB2 = N3 * R2 * R2 * 2 * 64;      // [n3][t][ct][part][lane]
+    static constexpr int TAB3 = R3 * R3 * 2 * 64;           // [t][ct][part][lane]
+    static constexpr int TAB2I = N1 * R2 * R2 * 2 * 64;     // [k1][t][ct][part][lane]
+    static constexpr int TAB1I = 2 * 2 * 2 * 64;            // [K step][row tile][part][lane]
+    static constexpr int TWA = N3 * R2 * 2 * 4 * 64;        // [n3][rt][ct][r][lane] float2
+    static constexpr int TWB = N1 * R2 * R3 * 4 * 64;       // [k1][ct2][ct3][r][lane] float2
+    static constexpr int KF_PER_H = N1 * R2 * R3 * 4 * 64;  // == M
+};
+
+struct Consts {
+    const uint4 *tab1, *tab2, *tab3, *tab3i, *tab2i, *tab1i;
+    const float2 *twa, *twb;
+    const uint2 *twa16, *twb16;       // the same twiddles as 16-bit constant pairs for TT::ctw
+};
+
+// 16-bit constant pair of a complex factor (wr, wi) in the form TT::ctw expects
+// (fmt 1: bf16 dot-product form, fmt 2: fp16 packed-math form).  hi16(x) converts one value.
+template <typename F> __host__ __device__ inline uint2 ctw_const(double wr, double wi, int fmt, F hi16)
+{
+    uint2 c;
+    if (fmt == 1) {
+        c.x = (uint32_t)hi16(wr) | ((uint32_t)hi16(-wi) << 16);
+        c.y = (uint32_t)hi16(wi) | ((uint32_t)hi16(wr) << 16);
+    } else {
+        c.x = (uint32_t)hi16(wr) | ((uint32_t)hi16(wr) << 16);
+        c.y = (uint32_t)hi16(-wi) | ((uint32_t)hi16(wi) << 16);
+    }
+    return c;
+}
+
+__device__ __forceinline__ void cmul_ip(float &re, float &im, float2 w)
+{
+    float r = re * w.x - im * w.y;
+    float i = re * w.y + im * w.x;
+    re = r;
+    im = i;
+}
+
+
+template <int N2, int N3>
+inline Consts consts_of(const fftconv_plan *p)
+{
+    using G = Geo<N2, N3>;
+    Consts c;
+    const uint4 *b = (const uint4 *)p->f3.consts;
+    c.tab1 = b;
+    c.tab2 = c.tab1 + G::TAB1;
+    c.tab3 = c.tab2 + G::TAB2;
+    c.tab3i = c.tab3 + G::TAB3;
+    c.tab2i = c.tab3i + G::TAB3;
+    c.tab1i = c.tab2i + G::TAB2I;
+    c.twa = (const float2 *)(c.tab1i + G::TAB1I);
+    c.twb = c.twa + G::TWA;
+    c.twa16 = (const uint2 *)(c.twb + G::TWB);
+    c.twb16 = c.twa16 + G::TWA;
+    return c;
+}
+
+
+// wave-specialised kernel for fft_size 8192 (fused3_ws.hip)
+int fused3_ws_launch(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, hipStream_t s);
+
+}  // namespace f3
+}  // namespace fftconv

@@ -1,0 +1,363 @@
+// Wave-specialised fused causal FFT convolution, fft_size 8192 = 32*16*16, 16-bit I/O
+// (paper Algorithm 3; same arithmetic, tables and k_f layout as k_fused3 in fused3.hip).
+//
+// Why a second schedule: with every wave running the same phase at the same time, all eight
+// waves of a workgroup meet the same LDS latencies and barriers together and the SIMDs idle
+// ~40 % of the time.  Here the workgroup is split by role and software-pipelined over work
+// items (a work item = one pair of batch rows of one channel):
+//   waves 0-3 ("outer"): phase A of item s+1 (stage 1, twiddle, stage 2 -> XB), phase C of
+//                        item s-1 (inverse stage 1 -> YB), and all staging: prefetch of item
+//                        s+3 from HBM, input of item s+2 into UB, output of item s-2 to HBM;
+//   waves 4-7 ("inner"): phase B of item s (stage 3, k_f, inverse 3, twiddle, inverse 2, in place).
+// Each SIMD holds one wave of each role, so while one waits on LDS the other computes, and a
+// step needs ONE workgroup barrier.  XB, UB and YB are double buffered by item parity:
+//   XB[t&1]: written by A(t) in step t-1, rewritten in place by B(t) in step t, read by C(t) in step t+1;
+//            A(t+2) reuses it in step t+1, and every outer wave reads (C) and rewrites (A) only its own n3 planes.
+//   UB[t&1]: written in step t-2, read by A(t) in step t-1.   YB[t&1]: written by C(t) in step t+1, read in step t+2.
+// Each role keeps only its own constant tables in registers (outer: stage-1/2 matrices and the
+// forward twiddles of its 4 n3 planes; inner: stage-3 matrices, k_f[h], inverse twiddles and
+// per-k1 inverse matrices of its 8 k1 planes).
+#include <cstdlib>
+
+#include "fused3_common.h"
+
+#ifdef FUSED3_PROBE
+#define WPROBE(bit) (!(probe & (bit)))
+// development build only: time stamps of one workgroup, read back with fftconv_debug_stamps()
+__device__ unsigned long long g_stamps[8 * 16 * 16];
+#define STAMP(k)                                                                              \
+    do {                                                                                      \
+        if (blockIdx.x == 3 && l == 0 && s >= t0 + 40 && s < t0 + 56)                         \
+            g_stamps[(w * 16 + (s - t0 - 40)) * 16 + (k)] = __builtin_amdgcn_s_memtime();     \
+    } while (0)
+extern "C" int fftconv_debug_stamps(unsigned long long *dst)
+{
+    return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(g_stamps), sizeof(g_stamps));
+}
+#else
+#define WPROBE(bit) true
+#define STAMP(k) do { } while (0)
+#endif
+
+namespace fftconv {
+namespace f3 {
+
+namespace {
+
+using G = Geo<16, 16>;
+constexpr int XBW = G::XB_WORDS;
+constexpr int UBE = G::UB_ELEMS;
+constexpr size_t WS_LDS_BYTES = (size_t)2 * XBW * 4 + (size_t)4 * UBE * 2;
+constexpr int PT = 256;                       // threads per role
+constexpr int PCH = G::M / 8 / PT;            // 16-byte input chunks per outer-role thread and item (4)
+
+// FULL: B even and N == fft_size/2, so every load and store of a work item is in range and
+// unconditional (the compiler can then count outstanding memory operations exactly).
+template <typename TT, bool FULL>
+__global__ void __launch_bounds__(NT) k_fused3_ws(const uint16_t *__restrict__ u, uint16_t *__restrict__ y,
+                                                 const uint2 *__restrict__ kf, Consts cs, int B, int H, int N, int probe)
+{
+    extern __shared__ uint32_t smem[];
+    uint32_t *const XBb = smem;                                   // [2][XBW]
+    uint16_t *const UBb = (uint16_t *)(smem + 2 * XBW);           // [2][UBE]
+    uint16_t *const YBb = UBb + 2 * UBE;                          // [2][UBE]
+
+    const int tid = threadIdx.x, l = tid & 63, q = l >> 4, c16 = l & 15;
+    // the wave index as a scalar, so that the role branch is a uniform branch and each wave runs
+    // exactly one of the two loops (both execute the same number of workgroup barriers)
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int npairs = (B + 1) / 2;
+    const long long T = (long long)H * npairs;
+    const int t0 = (int)(T * blockIdx.x / gridDim.x);
+    const int t1 = (int)(T * (blockIdx.x + 1) / gridDim.x);
+    if (t0 >= t1) return;
+    const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
+
+    if (w < 4) {
+        // =========================== outer role: phases A and C, staging ===========================
+        const int ptid = tid;                                     // 0..255
+        uint4 tab1[2][2], tab1i[2][2], tab2[4][2];
+        uint2 twa[4][2][4];
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+            for (int p = 0; p < 2; ++p) {
+                tab1[a][p] = cs.tab1[((0 * 2 + a) * 2 + p) * 64 + l];       // K step 0 only (n1 < 16)
+                tab1i[a][p] = cs.tab1i[((a * 2 + 0) * 2 + p) * 64 + l];     // row tile 0 only (n1 < 16)
+            }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int c = 4 * w + i;
+#pragma unroll
+            for (int p = 0; p < 2; ++p) tab2[i][p] = cs.tab2[(c * 2 + p) * 64 + l];
+#pragma unroll
+            for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) twa[i][ct][r] = cs.twa16[((c * 2 + ct) * 4 + r) * 64 + l];
+        }
+        // input prefetch: the loads of item s+2 are issued at the start of step s and staged at its end
+        uint4 pre[PCH];
+        auto issue_loads = [&](int t) {
+            const int h = t / npairs, pair = t - h * npairs;
+#pragma unroll
+            for (int j = 0; j < PCH; ++j) {
+                const int s = j / 2;
+                const int n = (ptid + PT * (j % 2)) * 8;
+                const int b = 2 * pair + s;
+                if constexpr (FULL) {
+                    // past the end of the range the last item is fetched again (in range, result unused)
+                    const int tc = t < t1 ? t : t1 - 1;
+                    const int hc = tc / npairs, pc = tc - hc * npairs;
+                    const uint16_t *row = u + ((size_t)(2 * pc + s) * H + hc) * N;
+                    pre[j] = *(const uint4 *)(row + n);
+                } else {
+                    uint4 v = make_uint4(0, 0, 0, 0);
+                    const uint16_t *row = u + ((size_t)b * H + h) * N;
+                    if (t < t1 && b < B && n < N) v = *(const uint4 *)(row + n);
+                    pre[j] = v;
+                }
+            }
+        };
+        auto stage_in = [&](uint16_t *UB) {
+#pragma unroll
+            for (int j = 0; j < PCH; ++j) {
+                const int s = j / 2;
+                const int n = (ptid + PT * (j % 2)) * 8;
+                const int n3 = n % 16, n2 = (n / 16) % 16, n1 = n / 256;
+                uint32_t *dst = (uint32_t *)(UB + s * G::SU + n1 * G::PQ1 + n2 * G::PR + n3);
+                dst[0] = pre[j].x;
+                dst[1] = pre[j].y;
+                dst[2] = pre[j].z;
+                dst[3] = pre[j].w;
+            }
+        };
+        auto store_out = [&](int t, const uint16_t *YB) {
+            const int h = t / npairs, pair = t - h * npairs;
+#pragma unroll
+            for (int j = 0; j < PCH; ++j) {
+                const int s = j / 2;
+                const int n = (ptid + PT * (j % 2)) * 8;
+                const int b = 2 * pair + s;
+                const int n3 = n % 16, n2 = (n / 16) % 16, n1 = n / 256;
+                const uint32_t *src = (const uint32_t *)(YB + s * G::SU + n1 * G::PQ1 + n2 * G::PR + n3);
+                const uint4 v = make_uint4(src[0], src[1], src[2], src[3]);
+                uint16_t *row = y + ((size_t)b * H + h) * N;
+                if (FULL || (b < B && n < N)) *(uint4 *)(row + n) = v;
+            }
+        };
+
+        // prologue: item t0 staged; item t0+1 is fetched at the start of the first step
+        issue_loads(t0);
+        stage_in(UBb + (t0 & 1) * UBE);
+        __syncthreads();
+
+        for (int s = t0 - 1; s <= t1 + 1; ++s) {
+            const bool doC = WPROBE(1) && s - 1 >= t0 && s - 1 < t1;
+            const bool doA = WPROBE(2) && s + 1 < t1;
+            STAMP(0);
+            if (WPROBE(8)) issue_loads(s + 2);
+            STAMP(1);
+            // ---- phase C of item s-1: inverse stage 1, n1 < 16; re -> row b, im -> row b+1 -> YB
+            if (doC) {
+                const uint32_t *XB = XBb + ((s - 1) & 1) * XBW;
+                uint32_t *YB32 = (uint32_t *)(YBb + ((s - 1) & 1) * UBE);
+                auto read_c = [&](int i, uint4 (&x)[2]) {
+#pragma unroll
+                    for (int ks = 0; ks < 2; ++ks) {
+                        const uint32_t *src = XB + (4 * w + i) * G::PN3 + (16 * ks + 4 * q) * G::PK1 + c16;
+                        x[ks] = make_uint4(src[0], src[G::PK1], src[2 * G::PK1], src[3 * G::PK1]);
+                    }
+                };
+                uint4 xc[2][2][2];                                // [buffer][plane of the pair][K step]
+                read_c(0, xc[0][0]);
+                read_c(1, xc[0][1]);
+#pragma unroll
+                for (int ip = 0; ip < 2; ++ip) {
+                    if (ip == 0) {
+                        read_c(2, xc[1][0]);
+                        read_c(3, xc[1][1]);
+                    }
+                    f32x4 dre[2], dim[2];
+#pragma unroll
+                    for (int k = 0; k < 2; ++k) {
+                        dre[k] = zero4;
+                        dim[k] = zero4;
+#pragma unroll
+                        for (int ks = 0; ks < 2; ++ks) {
+                            dre[k] = TT::mfma(tab1i[ks][0], xc[ip][k][ks], dre[k]);
+                            dim[k] = TT::mfma(tab1i[ks][1], xc[ip][k][ks], dim[k]);
+                        }
+                    }
+                    // lane: n2 = c16; reg r: n1 = 4q + r; the two planes are adjacent n3 -> one word each
+                    const int ce = 4 * w + 2 * ip;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const int e = (4 * q + r) * G::PQ1 + c16 * G::PR + ce;
+                        YB32[e / 2] = TT::pack(dre[0][r], dre[1][r]);
+                        YB32[(G::SU + e) / 2] = TT::pack(dim[0][r], dim[1][r]);
+                    }
+                }
+            }
+            STAMP(2);
+            // ---- phase A of item s+1: stage 1, twiddle, stage 2 -> XB
+            if (doA) {
+                uint32_t *XB = XBb + ((s + 1) & 1) * XBW;
+                // rows n2 = c16; slots (2r+s) = u_s[n1 = 4q + r]; two adjacent n3 planes per 32-bit word
+                const uint32_t *UB32 = (const uint32_t *)(UBb + ((s + 1) & 1) * UBE);
+                uint32_t w0[2][4], w1[2][4];
+#pragma unroll
+                for (int ip = 0; ip < 2; ++ip)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const int e = (4 * q + r) * G::PQ1 + c16 * G::PR + 4 * w + 2 * ip;
+                        w0[ip][r] = UB32[e / 2];
+                        w1[ip][r] = UB32[(G::SU + e) / 2];
+                    }
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int c = 4 * w + i;
+                    const uint32_t sel = (i & 1) ? 0x07060302u : 0x05040100u;
+                    const uint4 x1 = make_uint4(__builtin_amdgcn_perm(w1[i / 2][0], w0[i / 2][0], sel),
+                                                __builtin_amdgcn_perm(w1[i / 2][1], w0[i / 2][1], sel),
+                                                __builtin_amdgcn_perm(w1[i / 2][2], w0[i / 2][2], sel),
+                                                __builtin_amdgcn_perm(w1[i / 2][3], w0[i / 2][3], sel));
+                    uint4 x2[2];
+#pragma unroll
+                    for (int ct = 0; ct < 2; ++ct) {
+                        const f32x4 dre = TT::mfma(x1, tab1[ct][0], zero4);
+                        const f32x4 dim = TT::mfma(x1, tab1[ct][1], zero4);
+                        x2[ct] = TT::ctw4(dre, dim, twa[i][ct]);
+                    }
+#pragma unroll
+                    for (int ct = 0; ct < 2; ++ct) {
+                        const f32x4 dre = TT::mfma(tab2[i][0], x2[ct], zero4);
+                        const f32x4 dim = TT::mfma(tab2[i][1], x2[ct], zero4);
+                        // lane: k1 = 16 ct + c16; reg r: k2 = 4q + r
+                        uint32_t *dst = XB + c * G::PN3 + (16 * ct + c16) * G::PK1 + 4 * q;
+                        *(uint4 *)dst = make_uint4(TT::pack(dre[0], dim[0]), TT::pack(dre[1], dim[1]),
+                                                   TT::pack(dre[2], dim[2]), TT::pack(dre[3], dim[3]));
+                    }
+                }
+            }
+            STAMP(3);
+            // ---- staging: input of item s+2 (its loads were issued at the start of this step) -> UB,
+            //      then output of item s-2 -> HBM.  The input goes first: it waits for the loads, and
+            //      loads and stores retire through one counter on this target.
+            if (WPROBE(8) && s + 2 < t1) stage_in(UBb + ((s + 2) & 1) * UBE);
+            STAMP(4);
+            if (WPROBE(16) && s - 2 >= t0) store_out(s - 2, YBb + ((s - 2) & 1) * UBE);
+            STAMP(5);
+            __syncthreads();
+            STAMP(6);
+        }
+    } else {
+        // =========================== inner role: phase B ===========================
+        const int wq = w - 4;
+        uint4 tab3[2], tab3i[2], tab2i[8][2];
+        uint2 twb[8][4], kfr[8][4];
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            tab3[p] = cs.tab3[p * 64 + l];
+            tab3i[p] = cs.tab3i[p * 64 + l];
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int c = 8 * wq + i;
+#pragma unroll
+            for (int p = 0; p < 2; ++p) tab2i[i][p] = cs.tab2i[(c * 2 + p) * 64 + l];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) twb[i][r] = cs.twb16[(c * 4 + r) * 64 + l];
+        }
+        __syncthreads();                                          // pairs with the outer role's prologue barrier
+        int h_cur = -1;
+        for (int s = t0 - 1; s <= t1 + 1; ++s) {
+            STAMP(0);
+            if (WPROBE(4) && s >= t0 && s < t1) {
+                const int h = s / npairs;
+                if (h != h_cur) {                                 // new channel: its k_f slice for this wave's k1 planes
+                    h_cur = h;
+#pragma unroll
+                    for (int i = 0; i < 8; ++i)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r)
+                            kfr[i][r] = kf[(size_t)h * G::KF_PER_H + ((8 * wq + i) * 4 + r) * 64 + l];
+                }
+                uint32_t *XB = XBb + (s & 1) * XBW;
+                // operand of stage 3 for plane k1: columns k2 = c16, slots = (re, im) of n3 = 4q + r;
+                // read two planes ahead of the one being computed
+                auto read_plane = [&](int i) {
+                    const uint32_t *src = XB + (4 * q) * G::PN3 + (8 * wq + i) * G::PK1 + c16;
+                    return make_uint4(src[0], src[G::PN3], src[2 * G::PN3], src[3 * G::PN3]);
+                };
+                uint4 xq[3];
+#pragma unroll
+                for (int i = 0; i < 2; ++i) xq[i] = read_plane(i);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const int c = 8 * wq + i;
+                    if (i + 2 < 8) xq[(i + 2) % 3] = read_plane(i + 2);
+                    const uint4 x3v = xq[i % 3];
+                    // stage 3: matrix rows k3, data columns k2
+                    f32x4 dre = TT::mfma(tab3[0], x3v, zero4);
+                    f32x4 dim = TT::mfma(tab3[1], x3v, zero4);
+                    const uint4 x3i = TT::ctw4(dre, dim, kfr[i]);
+                    // inverse stage 3: rows k2, contraction over k3
+                    dre = TT::mfma(x3i, tab3i[0], zero4);
+                    dim = TT::mfma(x3i, tab3i[1], zero4);
+                    const uint4 x2i = TT::ctw4(dre, dim, twb[i]);
+                    // inverse stage 2: matrix rows n2, data columns n3
+                    dre = TT::mfma(tab2i[i][0], x2i, zero4);
+                    dim = TT::mfma(tab2i[i][1], x2i, zero4);
+                    // lane: n3 = c16; reg r: n2 = 4q + r -> one 16-byte write, in place
+                    uint32_t *dst = XB + c16 * G::PN3 + c * G::PK1 + 4 * q;
+                    *(uint4 *)dst = make_uint4(TT::pack(dre[0], dim[0]), TT::pack(dre[1], dim[1]),
+                                               TT::pack(dre[2], dim[2]), TT::pack(dre[3], dim[3]));
+                }
+            }
+            STAMP(5);
+            __syncthreads();
+            STAMP(6);
+        }
+    }
+}
+
+}  // namespace
+
+static int ws_probe()
+{
+#ifdef FUSED3_PROBE
+    const char *e = getenv("FUSED3_PROBE");
+    return e ? atoi(e) : 0;
+#else
+    return 0;
+#endif
+}
+
+int fused3_ws_launch(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, hipStream_t s)
+{
+    const int64_t npairs = (B + 1) / 2;
+    const int64_t T = p->H * npairs;
+    if (T >= ((int64_t)1 << 31) - 8) {
+        set_error("fftconv_forward: H * ceil(B/2) = %lld work items exceed the fused kernel's limit", (long long)T);
+        return FFTCONV_EUNSUPPORTED;
+    }
+    const bool full = (B % 2 == 0) && p->N == G::M / 2;
+    const bool f16 = p->dtype == FFTCONV_F16;
+    void (*kern)(const uint16_t *, uint16_t *, const uint2 *, Consts, int, int, int, int) =
+        f16 ? (full ? k_fused3_ws<F16, true> : k_fused3_ws<F16, false>)
+            : (full ? k_fused3_ws<BF16, true> : k_fused3_ws<BF16, false>);
+    static bool attr_set[4] = {false, false, false, false};
+    const int slot = (f16 ? 2 : 0) + (full ? 1 : 0);
+    if (!attr_set[slot]) {
+        FC_HIP(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)WS_LDS_BYTES));
+        attr_set[slot] = true;
+    }
+    const int grid = (int)(T < p->f3.num_cu ? T : p->f3.num_cu);
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NT), WS_LDS_BYTES, s, (const uint16_t *)u, (uint16_t *)y,
+                       (const uint2 *)kf, consts_of<16, 16>(p), (int)B, (int)p->H, (int)p->N, ws_probe());
+    FC_HIP(hipGetLastError());
+    return FFTCONV_OK;
+}
+
+}  // namespace f3
+}  // namespace fftconv
