@@ -215,7 +215,7 @@ OuterGeo outer_geo(int64_t M)
     g.No = (int)(M / MI);
     g.Ra = g.No < 16 ? g.No : 16;
     g.Rb = g.No / g.Ra;
-    g.CT = g.No > 256 ? 16 : 32;
+    g.CT = MI / g.No < TB ? MI / g.No : TB;      // No * CT <= 8192 points per block, at most one column per thread
     return g;
 }
 
