@@ -170,6 +170,18 @@ static int filter_fft_impl(const fftconv_plan *p, const float *k, int64_t Nk, co
         }
         if (rc) return rc;
     }
+    // a short filter of a plan that can run partial convolutions as short segments: add the
+    // short transform's spectrum behind the dense one
+    if (!block_keep && fused3_short_ok(p, Nk)) {
+        for (int64_t h0 = 0; h0 < p->H; h0 += p->filt_chunk) {
+            int64_t nh = p->H - h0 < p->filt_chunk ? p->H - h0 : p->filt_chunk;
+            double2 *spec = nullptr;
+            rc = staged_filter_transform_sub(p, 8192, k, Nk, h0, nh, s, &spec);
+            if (rc) return rc;
+            rc = fused3_pack_kf_short(p, spec, h0, nh, k_f, s);
+            if (rc) return rc;
+        }
+    }
     return FFTCONV_OK;
 }
 
@@ -245,6 +257,7 @@ int fftconv_forward_partial(const fftconv_plan *p, const void *u, const void *k_
         return FFTCONV_EINVAL;
     }
     if (B == 0) return FFTCONV_OK;
+    if (fused3_short_ok(p, Nk)) return fused3_forward_short(p, u, k_f, y, B, Nk, (hipStream_t)stream);
     return fftconv_forward(p, u, k_f, y, B, H, N, workspace, stream);
 }
 
@@ -260,6 +273,9 @@ int fftconv_forward_freq_sparse(const fftconv_plan *p, const void *u, const void
         return FFTCONV_EINVAL;
     }
     if (B == 0) return FFTCONV_OK;
+    if (p->path == PATH_FUSED3)
+        return fused3_forward_sparse(p, u, k_f, y, B, fused3_live_slots(p, block_keep, n_blocks),
+                                     (hipStream_t)stream);
     return fftconv_forward(p, u, k_f, y, B, H, N, workspace, stream);
 }
 

@@ -62,6 +62,9 @@ struct Fused3Tables {
     int num_cu = 0;                   // compute units of the plan's device (persistent grid size)
     void *consts = nullptr;           // operand tables in the kernel's lane order
     size_t consts_bytes = 0;
+    // fft 16384 plans also carry the 8192-point tables: a short (partial) filter runs as overlapping
+    // 8192-point segments, and k_f then holds a second, 8192-point spectrum after the dense one
+    void *consts_short = nullptr;
 };
 
 // Weight of frequency bin f under a block mask (Section 3.3, frequency-sparse filters).  The
@@ -110,6 +113,9 @@ int staged_filter_transform(const fftconv_plan *p, const float *k, int64_t Nk, i
 int staged_pack_kf(const fftconv_plan *p, const double2 *spec, int64_t h0, int64_t nh,
                    const uint8_t *keep_dev, int64_t n_blocks, void *kf, hipStream_t s);
 FacList staged_fac_list(const fftconv_plan *p);
+FacList staged_factors_for(int64_t M);
+int staged_filter_transform_sub(const fftconv_plan *p, int64_t Msub, const float *k, int64_t Nk, int64_t h0,
+                                int64_t nh, hipStream_t s, double2 **result);
 
 // ---- fused 3-stage path (fused3.hip)
 bool fused3_supported(int64_t N, int64_t M, int dtype);
@@ -119,15 +125,44 @@ size_t fused3_kf_bytes(const fftconv_plan *p);
 int fused3_pack_kf(const fftconv_plan *p, const double2 *spec, int64_t h0, int64_t nh,
                    const uint8_t *keep_dev, int64_t n_blocks, void *kf, hipStream_t s);
 int fused3_forward(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, hipStream_t s);
+// frequency-sparse forward: live = number of accumulator registers (1..4) that can hold non-zero k_f
+int fused3_forward_sparse(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, int live,
+                          hipStream_t s);
+int fused3_live_slots(const fftconv_plan *p, const uint8_t *block_keep, int64_t n_blocks);
+// partial convolution by overlapping short segments; returns FFTCONV_EUNSUPPORTED if this plan / Nk cannot
+bool fused3_short_ok(const fftconv_plan *p, int64_t Nk);
+int fused3_pack_kf_short(const fftconv_plan *p, const double2 *spec, int64_t h0, int64_t nh, void *kf, hipStream_t s);
+int fused3_forward_short(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, int64_t Nk,
+                         hipStream_t s);
 // the 8192-point complex-row kernel used as the inner step of the multi-pass path
 int fused3_init_inner(fftconv_plan *p);
 int fused3_inner_rows(const fftconv_plan *p, void *rows, const void *kf, int64_t rows_per_kf, int64_t kf_rows,
                       hipStream_t s);
+// Order of the innermost frequency digit k3 (N3 values) inside the fused kernels.  Stage 3 leaves
+// k3 in an accumulator slot (tile t, lane group q, register r) = index 16 t + 4 q + r.  The digits are
+// ranked by closeness to DC (0, N3-1, 1, N3-2, ...: k3 is the most significant digit of the
+// natural frequency, so this is low |f| first) and rank j goes to q = j % 4, r = (j % 16) / 4:
+// a low-pass frequency mask then leaves whole registers r zero in every lane, which the
+// frequency-sparse kernels skip (Appendix A.4: sparsity in the first dimension of k_f).
+__host__ __device__ inline int k3_at_index(int idx, int N3)
+{
+    const int t = idx / 16, i = idx % 16;
+    const int j = 16 * t + (i / 4) + 4 * (i % 4);          // rank held by this slot
+    return (j & 1) ? N3 - 1 - (j >> 1) : (j >> 1);
+}
+__host__ __device__ inline int k3_index(int k3, int N3)
+{
+    const int j = k3 < N3 / 2 ? 2 * k3 : 2 * (N3 - 1 - k3) + 1;
+    const int t = j / 16, jj = j % 16;
+    return 16 * t + 4 * (jj % 4) + jj / 4;
+}
+
 // slot of inner frequency fi (< 8192) in the 8192-point kernel's per-lane k_f order
 __host__ __device__ inline int fused3_kf_slot_8192(int64_t fi)
 {
     const int k1 = (int)(fi % 32), k2 = (int)((fi / 32) % 16), k3 = (int)(fi / 512);
-    const int lane = (k3 / 4) * 16 + k2, r = k3 % 4;
+    const int idx = k3_index(k3, 16);
+    const int lane = (idx / 4) * 16 + k2, r = idx % 4;
     return (k1 * 4 + r) * 64 + lane;
 }
 

@@ -67,7 +67,9 @@ using namespace f3;
 // CPLX = true : u, y are (B, H, M) rows of 16-bit (re, im) pairs (u may equal y); a work item is
 //               one row, transformed in full (no implicit zeros), circular convolution of length M.
 //               This is the inner step of the multi-pass scheme (Algorithm 4).
-template <int N2, int N3, typename TT, bool REGC, bool CPLX>
+// LIVE: accumulator registers r < LIVE of stage 3 may meet non-zero k_f (frequency-sparse filters
+//       ordered as in k3_at_index()); for r >= LIVE the product is zero and is not formed.
+template <int N2, int N3, typename TT, bool REGC, bool CPLX, int LIVE = 4>
 __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *u, uint16_t *y,
                                               const float2 *__restrict__ kf, Consts cs, int B, int H, int N,
                                               int probe)
@@ -166,7 +168,7 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *u, uint16_t *y,
 #pragma unroll
             for (int b = 0; b < R3; ++b)
 #pragma unroll
-                for (int r = 0; r < 4; ++r)
+                for (int r = 0; r < LIVE; ++r)
                     kfr[i][a][b][r] = kf[(size_t)h * G::KF_PER_H + (((c * R2 + a) * R3 + b) * 4 + r) * 64 + lz];
     };
     if constexpr (REGC) {
@@ -394,9 +396,13 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *u, uint16_t *y,
                         uint32_t o[4];
 #pragma unroll
                         for (int r = 0; r < 4; ++r) {
-                            float re = dre[r], im = dim[r];
-                            cmul_ip(re, im, kfr[i][ct2][ct3][r]);
-                            o[r] = TT::pack(re, im);
+                            if (r < LIVE) {
+                                float re = dre[r], im = dim[r];
+                                cmul_ip(re, im, kfr[i][ct2][ct3][r]);
+                                o[r] = TT::pack(re, im);
+                            } else {
+                                o[r] = 0;                         // k_f is zero for every k3 held in this slot
+                            }
                         }
                         x3i[ct2][ct3] = make_uint4(o[0], o[1], o[2], o[3]);
                     }
@@ -490,7 +496,7 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *u, uint16_t *y,
 }
 
 // k_f in the fused kernel's per-lane order: [h][k1][k2 tile][k3 tile][r][lane] float2, where the
-// lane holds k2 = 16 tile + lane%16 and k3 = 16 tile + 4 (lane/16) + r.
+// lane holds k2 = 16 tile + lane%16 and k3 = k3_at_index(16 tile + 4 (lane/16) + r).
 // fmt 0: fp32 pairs; fmt 1 / 2: 16-bit constant pairs for TT::ctw (bf16 dot-product / fp16 packed form)
 template <int N2, int N3>
 __global__ void k_pack_fused3(const double2 *spec, float2 *kf, FacList fl, int64_t h0, int64_t nh,
@@ -502,8 +508,9 @@ __global__ void k_pack_fused3(const double2 *spec, float2 *kf, FacList fl, int64
     if (idx >= nh * M) return;
     int64_t h = idx / M, f = idx % M;
     int k1 = (int)(f % N1), k2 = (int)((f / N1) % N2), k3 = (int)(f / (N1 * N2));
-    int lane = ((k3 % 16) / 4) * 16 + (k2 % 16), r = k3 % 4;
-    int64_t dst = ((((int64_t)k1 * G::R2 + k2 / 16) * G::R3 + k3 / 16) * 4 + r) * 64 + lane;
+    const int slot = k3_index(k3, N3);                     // accumulator slot 16 t + 4 q + r of this k3
+    int lane = ((slot % 16) / 4) * 16 + (k2 % 16), r = slot % 4;
+    int64_t dst = ((((int64_t)k1 * G::R2 + k2 / 16) * G::R3 + slot / 16) * 4 + r) * 64 + lane;
     double2 v = spec[h * M + freq_to_pos(f, fl, M)];
     double sc = mask_weight(keep, n_blocks, f, M) / (double)M;
     if (fmt == 0) {
@@ -573,7 +580,7 @@ void fill_operand(uint16_t *dst, bool f16, int t, int ct, int part, Fn G)
 }
 
 template <int N2, int N3>
-int build_tables(fftconv_plan *p)
+int build_tables(fftconv_plan *p, void **dest)
 {
     using G = Geo<N2, N3>;
     constexpr int64_t M = G::M;
@@ -600,17 +607,18 @@ int build_tables(fftconv_plan *p)
                     fill_operand(next(), f16, t, ct, part, [&](int n2, int k2) {
                         return cmulh(wpow(N2, (int64_t)n2 * k2), wpow((int64_t)N2 * N3, (int64_t)k2 * n3));
                     });
-    // tab3 [t][ct][part]: W_N3^{n3 k3}
-    for (int t = 0; t < G::R3; ++t)
-        for (int ct = 0; ct < G::R3; ++ct)
-            for (int part = 0; part < 2; ++part)
-                fill_operand(next(), f16, t, ct, part, [&](int n3, int k3) { return wpow(N3, (int64_t)n3 * k3); });
-    // tab3i: conj(W_N3^{k3 n3})
+    // tab3 [t][ct][part]: W_N3^{n3 k3}, output rows in the k3 order of k3_at_index()
     for (int t = 0; t < G::R3; ++t)
         for (int ct = 0; ct < G::R3; ++ct)
             for (int part = 0; part < 2; ++part)
                 fill_operand(next(), f16, t, ct, part,
-                             [&](int k3, int n3) { return conjh(wpow(N3, (int64_t)n3 * k3)); });
+                             [&](int n3, int idx) { return wpow(N3, (int64_t)n3 * k3_at_index(idx, N3)); });
+    // tab3i: conj(W_N3^{k3 n3}), contraction slots in the same k3 order
+    for (int t = 0; t < G::R3; ++t)
+        for (int ct = 0; ct < G::R3; ++ct)
+            for (int part = 0; part < 2; ++part)
+                fill_operand(next(), f16, t, ct, part,
+                             [&](int idx, int n3) { return conjh(wpow(N3, (int64_t)n3 * k3_at_index(idx, N3))); });
     // tab2i [k1][t][ct][part]: conj(W_N2^{k2 n2} W_{N1 N2}^{k1 n2})
     for (int k1 = 0; k1 < N1; ++k1)
         for (int t = 0; t < G::R2; ++t)
@@ -653,11 +661,11 @@ int build_tables(fftconv_plan *p)
                         tw[w++] = make_float2((float)v.re, (float)v.im);
                     }
     const size_t bytes = n_u4 * 16 + 2 * n_f2 * 8;
-    FC_HIP(hipMalloc(&p->f3.consts, bytes));
-    p->f3.consts_bytes = bytes;
-    FC_HIP(hipMemcpy(p->f3.consts, ops.data(), n_u4 * 16, hipMemcpyHostToDevice));
-    FC_HIP(hipMemcpy((char *)p->f3.consts + n_u4 * 16, tw.data(), n_f2 * 8, hipMemcpyHostToDevice));
-    FC_HIP(hipMemcpy((char *)p->f3.consts + n_u4 * 16 + n_f2 * 8, tw16.data(), n_f2 * 8, hipMemcpyHostToDevice));
+    FC_HIP(hipMalloc(dest, bytes));
+    p->f3.consts_bytes += bytes;
+    FC_HIP(hipMemcpy(*dest, ops.data(), n_u4 * 16, hipMemcpyHostToDevice));
+    FC_HIP(hipMemcpy((char *)*dest + n_u4 * 16, tw.data(), n_f2 * 8, hipMemcpyHostToDevice));
+    FC_HIP(hipMemcpy((char *)*dest + n_u4 * 16 + n_f2 * 8, tw16.data(), n_f2 * 8, hipMemcpyHostToDevice));
     return FFTCONV_OK;
 }
 
@@ -673,12 +681,12 @@ int probe_mask()
 
 // Rows: for the causal kernel (CPLX false) B batch rows of H channels, N samples each; for the
 // complex-row kernel B rows per k_f row, H k_f rows.
-template <int N2, int N3, typename TT, bool REGC, bool CPLX>
+template <int N2, int N3, typename TT, bool REGC, bool CPLX, int LIVE = 4>
 int launch(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, int64_t H, int64_t N,
            hipStream_t s)
 {
     using G = Geo<N2, N3>;
-    auto kern = k_fused3<N2, N3, TT, REGC, CPLX>;
+    auto kern = k_fused3<N2, N3, TT, REGC, CPLX, LIVE>;
     constexpr size_t lds = CPLX ? G::LDS_BYTES_C : G::LDS_BYTES;
     static bool attr_set = false;
     if (!attr_set) {
@@ -718,15 +726,67 @@ int fused3_init(fftconv_plan *p)
     case 8192:
         p->f3.N2 = 16;
         p->f3.N3 = 16;
-        return build_tables<16, 16>(p);
-    case 16384:
+        return build_tables<16, 16>(p, &p->f3.consts);
+    case 16384: {
         p->f3.N2 = 32;
         p->f3.N3 = 16;
-        return build_tables<32, 16>(p);
+        int rc = build_tables<32, 16>(p, &p->f3.consts);
+        if (rc) return rc;
+        return build_tables<16, 16>(p, &p->f3.consts_short);     // for partial convolutions, see fused3_forward_short
+    }
     default:
         set_error("fused3: no kernel for fft_size=%lld", (long long)p->M);
         return FFTCONV_EUNSUPPORTED;
     }
+}
+
+int fused3_forward_sparse(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, int live,
+                          hipStream_t s)
+{
+    if (p->M != 16384 || live >= 3) return fused3_forward(p, u, kf, y, B, s);
+    if (((uintptr_t)u | (uintptr_t)y) & 15) {
+        set_error("fftconv_forward_freq_sparse: u and y must be 16-byte aligned for this plan");
+        return FFTCONV_EINVAL;
+    }
+    const bool f16 = p->dtype == FFTCONV_F16;
+    if (live <= 1)
+        return f16 ? launch<32, 16, F16, false, false, 1>(p, u, kf, y, B, p->H, p->N, s)
+                   : launch<32, 16, BF16, false, false, 1>(p, u, kf, y, B, p->H, p->N, s);
+    return f16 ? launch<32, 16, F16, false, false, 2>(p, u, kf, y, B, p->H, p->N, s)
+               : launch<32, 16, BF16, false, false, 2>(p, u, kf, y, B, p->H, p->N, s);
+}
+
+// Number of accumulator registers (1..4) of stage 3 that can meet a non-zero bin under a block mask
+// (mirror bins count: a bin keeps weight 1/2 when only its mirror is kept).
+int fused3_live_slots(const fftconv_plan *p, const uint8_t *block_keep, int64_t n_blocks)
+{
+    const int N3 = p->f3.N3;
+    const int64_t per_row = p->M / N3, per_blk = p->M / n_blocks;
+    int live = 1;
+    for (int k3 = 0; k3 < N3; ++k3) {
+        bool kept = false;
+        for (int side = 0; side < 2 && !kept; ++side) {
+            // bins of this row, or their mirror images M - f
+            int64_t lo = (int64_t)k3 * per_row, hi = lo + per_row - 1;
+            if (side) {
+                const int64_t mlo = (p->M - hi) % p->M, mhi = (p->M - lo) % p->M;
+                if (lo == 0) {                  // row 0 mirrors to {0} and [M - per_row + 1, M - 1]
+                    kept = block_keep[0] != 0;
+                    lo = p->M - per_row + 1;
+                    hi = p->M - 1;
+                } else {
+                    lo = mlo;
+                    hi = mhi;
+                }
+            }
+            for (int64_t b = lo / per_blk; b <= hi / per_blk && !kept; ++b) kept = block_keep[b] != 0;
+        }
+        if (kept) {
+            const int r = k3_index(k3, N3) % 4;
+            if (r + 1 > live) live = r + 1;
+        }
+    }
+    return live;
 }
 
 int fused3_init_inner(fftconv_plan *p)
@@ -737,7 +797,7 @@ int fused3_init_inner(fftconv_plan *p)
     hipDeviceProp_t prop;
     FC_HIP(hipGetDeviceProperties(&prop, p->device));
     p->f3.num_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
-    return build_tables<16, 16>(p);
+    return build_tables<16, 16>(p, &p->f3.consts);
 }
 
 int fused3_inner_rows(const fftconv_plan *p, void *rows, const void *kf, int64_t rows_per_kf, int64_t kf_rows,
@@ -751,10 +811,57 @@ int fused3_inner_rows(const fftconv_plan *p, void *rows, const void *kf, int64_t
 void fused3_destroy(fftconv_plan *p)
 {
     if (p->f3.consts) (void)hipFree(p->f3.consts);
+    if (p->f3.consts_short) (void)hipFree(p->f3.consts_short);
     p->f3.consts = nullptr;
+    p->f3.consts_short = nullptr;
 }
 
-size_t fused3_kf_bytes(const fftconv_plan *p) { return (size_t)(p->H * p->M) * sizeof(float2); }
+constexpr int64_t SHORT_M = 8192;          // transform length of the segments of a partial convolution
+constexpr int64_t SHORT_MAX_P = 2048;      // most history a segment may carry (at least half of it is output)
+
+size_t fused3_kf_bytes(const fftconv_plan *p)
+{
+    // fft 16384 plans: dense spectrum, then the 8192-point spectrum of a short filter
+    const int64_t bins = p->M + (p->f3.consts_short ? SHORT_M : 0);
+    return (size_t)(p->H * bins) * sizeof(float2);
+}
+
+static int64_t history_of(int64_t Nk) { return (Nk - 1 + 7) / 8 * 8; }
+
+bool fused3_short_ok(const fftconv_plan *p, int64_t Nk)
+{
+    return p->path == PATH_FUSED3 && p->f3.consts_short != nullptr && Nk >= 1 && history_of(Nk) <= SHORT_MAX_P;
+}
+
+int fused3_pack_kf_short(const fftconv_plan *p, const double2 *spec, int64_t h0, int64_t nh, void *kf, hipStream_t s)
+{
+    const int bs = 256;
+    const unsigned grid = (unsigned)((nh * SHORT_M + bs - 1) / bs);
+    float2 *dst = (float2 *)kf + p->H * p->M;
+    hipLaunchKernelGGL((k_pack_fused3<16, 16>), dim3(grid), dim3(bs), 0, s, spec, dst, staged_factors_for(SHORT_M), h0,
+                       nh, (const uint8_t *)nullptr, (int64_t)1, p->dtype == FFTCONV_F16 ? 2 : 1);
+    FC_HIP(hipGetLastError());
+    return FFTCONV_OK;
+}
+
+// Partial convolution (Section 3.3) of a fft-16384 plan: the filter covers Nk <= 2049 taps, so
+// every output depends on at most P = Nk - 1 (rounded up to 8) earlier inputs and the row can be cut
+// into overlapping windows that each fit the 8192-point kernel (overlap-save).  The outermost
+// factor of the decomposition is skipped altogether: 8192-point transforms instead of 16384-point
+// ones, register-resident tables, 1/2 of the k_f bytes.
+int fused3_forward_short(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, int64_t Nk,
+                         hipStream_t s)
+{
+    if (((uintptr_t)u | (uintptr_t)y) & 15) {
+        set_error("fftconv_forward_partial: u and y must be 16-byte aligned for this plan");
+        return FFTCONV_EINVAL;
+    }
+    const int P = (int)history_of(Nk);
+    const int Lo = (int)(SHORT_M / 2) - P;
+    const int nseg = p->N <= SHORT_M / 2 ? 1 : 1 + (int)((p->N - SHORT_M / 2 + Lo - 1) / Lo);
+    const float2 *kf_short = (const float2 *)kf + p->H * p->M;
+    return fused3_ws_launch(p, p->f3.consts_short, u, kf_short, y, B, nseg, P, s);
+}
 
 int fused3_pack_kf(const fftconv_plan *p, const double2 *spec, int64_t h0, int64_t nh, const uint8_t *keep_dev,
                    int64_t n_blocks, void *kf, hipStream_t s)
@@ -788,7 +895,7 @@ int fused3_forward(const fftconv_plan *p, const void *u, const void *kf, void *y
     const bool f16 = p->dtype == FFTCONV_F16;
     switch (p->M) {
     case 8192:
-        return fused3_ws_launch(p, u, kf, y, B, s);     // wave-specialised schedule (fused3_ws.hip)
+        return fused3_ws_launch(p, p->f3.consts, u, kf, y, B, 1, 0, s);     // wave-specialised schedule (fused3_ws.hip)
     case 16384:
         return f16 ? launch<32, 16, F16, false, false>(p, u, kf, y, B, p->H, p->N, s)
                    : launch<32, 16, BF16, false, false>(p, u, kf, y, B, p->H, p->N, s);

@@ -158,11 +158,11 @@ __device__ __forceinline__ void cmul_ip(float &re, float &im, float2 w)
 
 
 template <int N2, int N3>
-inline Consts consts_of(const fftconv_plan *p)
+inline Consts consts_at(const void *base)
 {
     using G = Geo<N2, N3>;
     Consts c;
-    const uint4 *b = (const uint4 *)p->f3.consts;
+    const uint4 *b = (const uint4 *)base;
     c.tab1 = b;
     c.tab2 = c.tab1 + G::TAB1;
     c.tab3 = c.tab2 + G::TAB2;
@@ -178,7 +178,11 @@ inline Consts consts_of(const fftconv_plan *p)
 
 
 // wave-specialised kernel for fft_size 8192 (fused3_ws.hip)
-int fused3_ws_launch(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, hipStream_t s);
+template <int N2, int N3>
+inline Consts consts_of(const fftconv_plan *p) { return consts_at<N2, N3>(p->f3.consts); }
+
+int fused3_ws_launch(const fftconv_plan *p, const void *consts, const void *u, const void *kf, void *y, int64_t B,
+                     int nseg, int P, hipStream_t s);
 
 }  // namespace f3
 }  // namespace fftconv

@@ -55,7 +55,8 @@ constexpr int PCH = G::M / 8 / PT;            // 16-byte input chunks per outer-
 // unconditional (the compiler can then count outstanding memory operations exactly).
 template <typename TT, bool FULL>
 __global__ void __launch_bounds__(NT) k_fused3_ws(const uint16_t *__restrict__ u, uint16_t *__restrict__ y,
-                                                 const uint2 *__restrict__ kf, Consts cs, int B, int H, int N, int probe)
+                                                 const uint2 *__restrict__ kf, Consts cs, int B, int H, int N, int nseg, int P, int Lo,
+                                                 int probe)
 {
     extern __shared__ uint32_t smem[];
     uint32_t *const XBb = smem;                                   // [2][XBW]
@@ -66,8 +67,13 @@ __global__ void __launch_bounds__(NT) k_fused3_ws(const uint16_t *__restrict__ u
     // the wave index as a scalar, so that the role branch is a uniform branch and each wave runs
     // exactly one of the two loops (both execute the same number of workgroup barriers)
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // A work item is (channel h, pair of batch rows, segment).  Segments exist only for partial
+    // convolutions (a filter much shorter than the sequence): the row is cut into overlapping
+    // windows of at most fft/2 samples, segment 0 yields outputs [0, fft/2), segment j >= 1 yields Lo
+    // outputs and reads P samples of history before them (P >= filter length - 1), i.e. overlap-save.
     const int npairs = (B + 1) / 2;
-    const long long T = (long long)H * npairs;
+    const int per_h = npairs * nseg;
+    const long long T = (long long)H * per_h;
     const int t0 = (int)(T * blockIdx.x / gridDim.x);
     const int t1 = (int)(T * (blockIdx.x + 1) / gridDim.x);
     if (t0 >= t1) return;
@@ -98,22 +104,24 @@ __global__ void __launch_bounds__(NT) k_fused3_ws(const uint16_t *__restrict__ u
         // input prefetch: the loads of item s+2 are issued at the start of step s and staged at its end
         uint4 pre[PCH];
         auto issue_loads = [&](int t) {
-            const int h = t / npairs, pair = t - h * npairs;
+            const int h = t / per_h, rem = t - h * per_h;
+            const int pair = rem / nseg, seg = rem - pair * nseg;
 #pragma unroll
             for (int j = 0; j < PCH; ++j) {
                 const int s = j / 2;
                 const int n = (ptid + PT * (j % 2)) * 8;
                 const int b = 2 * pair + s;
                 if constexpr (FULL) {
-                    // past the end of the range the last item is fetched again (in range, result unused)
+                    // (nseg == 1) past the end of the range the last item is fetched again (in range, unused)
                     const int tc = t < t1 ? t : t1 - 1;
                     const int hc = tc / npairs, pc = tc - hc * npairs;
                     const uint16_t *row = u + ((size_t)(2 * pc + s) * H + hc) * N;
                     pre[j] = *(const uint4 *)(row + n);
                 } else {
                     uint4 v = make_uint4(0, 0, 0, 0);
-                    const uint16_t *row = u + ((size_t)b * H + h) * N;
-                    if (t < t1 && b < B && n < N) v = *(const uint4 *)(row + n);
+                    const int in_ofs = seg == 0 ? 0 : G::M / 2 + (seg - 1) * Lo - P;
+                    const uint16_t *row = u + ((size_t)b * H + h) * N + in_ofs;
+                    if (t < t1 && b < B && n < N - in_ofs) v = *(const uint4 *)(row + n);
                     pre[j] = v;
                 }
             }
@@ -132,7 +140,11 @@ __global__ void __launch_bounds__(NT) k_fused3_ws(const uint16_t *__restrict__ u
             }
         };
         auto store_out = [&](int t, const uint16_t *YB) {
-            const int h = t / npairs, pair = t - h * npairs;
+            const int h = t / per_h, rem = t - h * per_h;
+            const int pair = rem / nseg, seg = rem - pair * nseg;
+            const int skip = seg == 0 ? 0 : P;                    // outputs before `skip` lack history: dropped
+            const int out_ofs = seg == 0 ? 0 : G::M / 2 + (seg - 1) * Lo;
+            const int out_len = min(seg == 0 ? G::M / 2 : Lo, N - out_ofs);
 #pragma unroll
             for (int j = 0; j < PCH; ++j) {
                 const int s = j / 2;
@@ -141,8 +153,12 @@ __global__ void __launch_bounds__(NT) k_fused3_ws(const uint16_t *__restrict__ u
                 const int n3 = n % 16, n2 = (n / 16) % 16, n1 = n / 256;
                 const uint32_t *src = (const uint32_t *)(YB + s * G::SU + n1 * G::PQ1 + n2 * G::PR + n3);
                 const uint4 v = make_uint4(src[0], src[1], src[2], src[3]);
-                uint16_t *row = y + ((size_t)b * H + h) * N;
-                if (FULL || (b < B && n < N)) *(uint4 *)(row + n) = v;
+                if constexpr (FULL) {
+                    *(uint4 *)(y + ((size_t)b * H + h) * N + n) = v;
+                } else {
+                    uint16_t *row = y + ((size_t)b * H + h) * N + out_ofs;
+                    if (b < B && n >= skip && n - skip < out_len) *(uint4 *)(row + (n - skip)) = v;
+                }
             }
         };
 
@@ -273,7 +289,7 @@ __global__ void __launch_bounds__(NT) k_fused3_ws(const uint16_t *__restrict__ u
         for (int s = t0 - 1; s <= t1 + 1; ++s) {
             STAMP(0);
             if (WPROBE(4) && s >= t0 && s < t1) {
-                const int h = s / npairs;
+                const int h = s / per_h;
                 if (h != h_cur) {                                 // new channel: its k_f slice for this wave's k1 planes
                     h_cur = h;
 #pragma unroll
@@ -333,17 +349,21 @@ static int ws_probe()
 #endif
 }
 
-int fused3_ws_launch(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, hipStream_t s)
+// nseg == 1: plain causal convolution (N <= fft/2).  nseg > 1: overlap-save segments of a partial
+// convolution, P samples of history per segment, Lo = fft/2 - P outputs per later segment.
+int fused3_ws_launch(const fftconv_plan *p, const void *consts, const void *u, const void *kf, void *y, int64_t B,
+                     int nseg, int P, hipStream_t s)
 {
     const int64_t npairs = (B + 1) / 2;
-    const int64_t T = p->H * npairs;
+    const int64_t T = p->H * npairs * nseg;
+    const int Lo = G::M / 2 - P;
     if (T >= ((int64_t)1 << 31) - 8) {
         set_error("fftconv_forward: H * ceil(B/2) = %lld work items exceed the fused kernel's limit", (long long)T);
         return FFTCONV_EUNSUPPORTED;
     }
-    const bool full = (B % 2 == 0) && p->N == G::M / 2;
+    const bool full = (B % 2 == 0) && p->N == G::M / 2 && nseg == 1;
     const bool f16 = p->dtype == FFTCONV_F16;
-    void (*kern)(const uint16_t *, uint16_t *, const uint2 *, Consts, int, int, int, int) =
+    void (*kern)(const uint16_t *, uint16_t *, const uint2 *, Consts, int, int, int, int, int, int, int) =
         f16 ? (full ? k_fused3_ws<F16, true> : k_fused3_ws<F16, false>)
             : (full ? k_fused3_ws<BF16, true> : k_fused3_ws<BF16, false>);
     static bool attr_set[4] = {false, false, false, false};
@@ -354,7 +374,7 @@ int fused3_ws_launch(const fftconv_plan *p, const void *u, const void *kf, void 
     }
     const int grid = (int)(T < p->f3.num_cu ? T : p->f3.num_cu);
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NT), WS_LDS_BYTES, s, (const uint16_t *)u, (uint16_t *)y,
-                       (const uint2 *)kf, consts_of<16, 16>(p), (int)B, (int)p->H, (int)p->N, ws_probe());
+                       (const uint2 *)kf, consts_at<16, 16>(consts), (int)B, (int)p->H, (int)p->N, nseg, P, Lo, ws_probe());
     FC_HIP(hipGetLastError());
     return FFTCONV_OK;
 }

@@ -23,6 +23,8 @@
 
 namespace fftconv {
 
+FacList staged_factors_for(int64_t M);
+
 namespace {
 
 template <typename T> struct C2;
@@ -65,9 +67,10 @@ __global__ void k_load_padded(const In *src, V *dst, int64_t len, int64_t M, int
 }
 
 // Forward stage: out[prefix, k, r] = W_M^{k R r} * sum_n W_{Nj}^{n k} in[prefix, n, r].
+// tws: stride of the twiddle table when it was built for a multiple tws*M of this transform length
 template <typename V>
 __global__ void k_stage_fwd(const V *in, V *out, const V *w, int64_t M, int Nj, int64_t Sj, int64_t Rj,
-                            int64_t nrows)
+                            int64_t nrows, int64_t tws)
 {
     int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= nrows * M) return;
@@ -82,13 +85,13 @@ __global__ void k_stage_fwd(const V *in, V *out, const V *w, int64_t M, int Nj, 
     int ph = 0;                                   // (n*k) mod Nj
     for (int n = 0; n < Nj; ++n) {
         V x = in[base + (int64_t)n * Sj];
-        V t = cmul(x, w[(int64_t)ph * step]);
+        V t = cmul(x, w[(int64_t)ph * step * tws]);
         acc.x += t.x;
         acc.y += t.y;
         ph += k;
         if (ph >= Nj) ph -= Nj;
     }
-    out[idx] = cmul(acc, w[(int64_t)k * Rj * r]);  // k*Rj*r < Nj*Rj*Sj = M
+    out[idx] = cmul(acc, w[(int64_t)k * Rj * r * tws]);  // k*Rj*r < Nj*Rj*Sj = M
 }
 
 // Inverse stage: out[prefix, n, r] = sum_k conj(W_{Nj}^{n k} W_M^{k R r}) in[prefix, k, r].
@@ -158,16 +161,17 @@ FacList fac_list(const fftconv_plan *p) { return staged_fac_list(p); }
 inline unsigned grid_for(int64_t n, int bs) { return (unsigned)((n + bs - 1) / bs); }
 
 template <typename V>
-int run_stages_fwd(const fftconv_plan *p, V *a, V *b, const V *w, int64_t nrows, hipStream_t s, V **result)
+int run_stages_fwd(const FacList &fl, int64_t M, int64_t tws, V *a, V *b, const V *w, int64_t nrows, hipStream_t s,
+                   V **result)
 {
     const int bs = 256;
-    int64_t M = p->M, S = M, R = 1;
+    int64_t S = M, R = 1;
     V *src = a, *dst = b;
-    for (int i = 0; i < p->st.nf; ++i) {
-        int Nj = (int)p->st.fac[i];
+    for (int i = 0; i < fl.nf; ++i) {
+        int Nj = fl.fac[i];
         S /= Nj;
         hipLaunchKernelGGL(k_stage_fwd<V>, dim3(grid_for(nrows * M, bs)), dim3(bs), 0, s, src, dst, w, M, Nj, S, R,
-                           nrows);
+                           nrows, tws);
         FC_HIP(hipGetLastError());
         R *= Nj;
         V *t = src; src = dst; dst = t;
@@ -181,13 +185,9 @@ int run_stages_fwd(const fftconv_plan *p, V *a, V *b, const V *w, int64_t nrows,
 int staged_init(fftconv_plan *p)
 {
     // factors of 16, remainder (2, 4 or 8) last
-    int lg = 0;
-    while (((int64_t)1 << lg) < p->M) ++lg;
-    int nf = 0;
-    int rem = lg;
-    while (rem >= 4) { p->st.fac[nf++] = 16; rem -= 4; }
-    if (rem) p->st.fac[nf++] = (int64_t)1 << rem;
-    p->st.nf = nf;
+    const FacList fl0 = staged_factors_for(p->M);
+    p->st.nf = fl0.nf;
+    for (int i = 0; i < MAX_FACTORS; ++i) p->st.fac[i] = fl0.fac[i];
 
     int64_t M = p->M;
     std::vector<double2> w64((size_t)M);
@@ -261,7 +261,7 @@ static int staged_forward_t(const fftconv_plan *p, const IO *u, const float2 *kf
                            a, N, M, nrows);
         FC_HIP(hipGetLastError());
         float2 *x = nullptr;
-        int rc = run_stages_fwd<float2>(p, a, b, p->st.w32, nrows, s, &x);
+        int rc = run_stages_fwd<float2>(fac_list(p), M, 1, a, b, p->st.w32, nrows, s, &x);
         if (rc) return rc;
         hipLaunchKernelGGL(k_pointwise, dim3(grid_for(nrows * M, bs)), dim3(bs), 0, s, x, kf, M, H, row0, nrows);
         FC_HIP(hipGetLastError());
@@ -304,7 +304,33 @@ int staged_filter_transform(const fftconv_plan *p, const float *k, int64_t Nk, i
     hipLaunchKernelGGL((k_load_padded<double2, float>), dim3(grid_for(nh * p->M, bs)), dim3(bs), 0, s, k + h0 * Nk,
                        p->filt_a, Nk, p->M, nh);
     FC_HIP(hipGetLastError());
-    return run_stages_fwd<double2>(p, p->filt_a, p->filt_b, p->st.w64, nh, s, result);
+    return run_stages_fwd<double2>(fac_list(p), p->M, 1, p->filt_a, p->filt_b, p->st.w64, nh, s, result);
+}
+
+FacList staged_factors_for(int64_t M)
+{
+    FacList fl;
+    for (int i = 0; i < MAX_FACTORS; ++i) fl.fac[i] = 0;
+    int lg = 0;
+    while (((int64_t)1 << lg) < M) ++lg;
+    int nf = 0, rem = lg;
+    while (rem >= 4) { fl.fac[nf++] = 16; rem -= 4; }
+    if (rem) fl.fac[nf++] = 1 << rem;
+    fl.nf = nf;
+    return fl;
+}
+
+// The same transform at a shorter length Msub (a divisor of the plan's fft_size), reusing the
+// plan's twiddle table with a stride and its scratch buffers.
+int staged_filter_transform_sub(const fftconv_plan *p, int64_t Msub, const float *k, int64_t Nk, int64_t h0,
+                                int64_t nh, hipStream_t s, double2 **result)
+{
+    const int bs = 256;
+    hipLaunchKernelGGL((k_load_padded<double2, float>), dim3(grid_for(nh * Msub, bs)), dim3(bs), 0, s, k + h0 * Nk,
+                       p->filt_a, Nk, Msub, nh);
+    FC_HIP(hipGetLastError());
+    return run_stages_fwd<double2>(staged_factors_for(Msub), Msub, p->M / Msub, p->filt_a, p->filt_b, p->st.w64, nh, s,
+                                   result);
 }
 
 int staged_pack_kf(const fftconv_plan *p, const double2 *spec, int64_t h0, int64_t nh, const uint8_t *keep_dev,

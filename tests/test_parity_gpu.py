@@ -152,3 +152,35 @@ def test_multipass_long_sampled_positions(B, H, N, M):
           flush=True)
     assert plan.path == "multipass"
     assert err <= TOL[w.dtype]
+
+
+@pytest.mark.parametrize("B,H,N,Nk", [
+    (2, 2, 8192, 1024),     # 3 overlapping 8192-point segments
+    (3, 2, 8192, 2049),     # longest filter the segment path takes (2048 samples of history), odd batch
+    (2, 1, 8192, 2050),     # one tap more: falls back to the dense 16384-point kernel
+    (2, 2, 8192, 1),        # a single tap: no history at all
+    (2, 1, 6000, 100),      # ragged length, last segment partly out of range
+    (2, 1, 4096, 512),      # sequence fits one segment
+])
+def test_partial_convolution_segment_path(B, H, N, Nk):
+    w = synth.scaled(W["cfg5a"], B=B, H=H, N=N, Nk=Nk)
+    err_dense, _ = check_all_sequences(w, variant="dense")
+    err_skip, plan = check_all_sequences(w, variant="skip")
+    print("partial B=%d H=%d N=%d Nk=%d path=%s dense err=%.3e segments err=%.3e" % (B, H, N, Nk, plan.path, err_dense, err_skip),
+          flush=True)
+    assert err_dense <= TOL[w.dtype] and err_skip <= TOL[w.dtype]
+
+
+@pytest.mark.parametrize("keep_blocks", [
+    (0, 1, 2, 3, 28, 29, 30, 31),                     # the low-pass of config 5b: one live accumulator slot
+    tuple(range(8)) + tuple(range(24, 32)),           # half of the spectrum: two live slots
+    (0, 1, 2, 3),                                     # one-sided mask: mirror bins get weight 1/2
+    (5, 6, 20, 31),                                   # scattered blocks: nothing can be skipped
+    (16,),                                            # only the block at the Nyquist edge
+])
+def test_frequency_sparse_masks_fft16384(keep_blocks):
+    w = synth.scaled(W["cfg5b"], B=3, H=2, keep_blocks=keep_blocks, n_blocks=32)
+    for variant in ("dense", "skip"):
+        err, plan = check_all_sequences(w, variant=variant)
+        print("freq-sparse keep=%s %s path=%s err=%.3e" % (keep_blocks, variant, plan.path, err), flush=True)
+        assert err <= TOL[w.dtype]
