@@ -16,7 +16,8 @@
 //            real part -> row b, imaginary part -> row b+1.
 // S lives in the caller's workspace as 16-bit (re, im) pairs, M per pair of rows, and is
 // rewritten in place by pass B.  The outer DFT of length No is itself split in two
-// (No = Ra * Rb, Ra = min(16, No)) inside one workgroup, on the vector ALUs in fp32.
+// (No = Ra * Rb, Ra = min(16, No)) inside one workgroup: in-register radix-2 butterflies on the
+// vector ALUs in fp32, one thread per column, so HBM sees rows of consecutive columns.
 #include <hip/hip_bf16.h>
 #include <hip/hip_fp16.h>
 
@@ -27,7 +28,7 @@ namespace fftconv {
 namespace {
 
 constexpr int MI = 8192;
-constexpr int TB = 256;          // threads per block of the outer passes
+constexpr int TB = 512;          // threads per block of the outer passes
 
 __device__ __forceinline__ float2 cmulf(float2 a, float2 b)
 {
@@ -69,127 +70,257 @@ struct OuterGeo {
     int No, Ra, Rb, CT;          // outer length, its two factors, columns per block
 };
 
-// ---- pass A: zero-padded pair of real rows -> outer forward DFT -> twiddle -> S
-template <bool F16>
-__global__ void __launch_bounds__(TB) k_outer_fwd(const uint16_t *__restrict__ u, uint32_t *__restrict__ S,
-                                                 OuterGeo g, int B, int H, int N, int64_t M)
+// cos / sin of 2 pi j / 32: every twiddle of the in-register transforms below (lengths <= 32)
+__device__ constexpr float C32[32] = {1.000000000f, 0.980785280f, 0.923879533f, 0.831469612f, 0.707106781f, 0.555570233f, 0.382683432f, 0.195090322f, 0.000000000f, -0.195090322f, -0.382683432f, -0.555570233f, -0.707106781f, -0.831469612f, -0.923879533f, -0.980785280f, -1.000000000f, -0.980785280f, -0.923879533f, -0.831469612f, -0.707106781f, -0.555570233f, -0.382683432f, -0.195090322f, -0.000000000f, 0.195090322f, 0.382683432f, 0.555570233f, 0.707106781f, 0.831469612f, 0.923879533f, 0.980785280f};
+__device__ constexpr float S32[32] = {0.000000000f, 0.195090322f, 0.382683432f, 0.555570233f, 0.707106781f, 0.831469612f, 0.923879533f, 0.980785280f, 1.000000000f, 0.980785280f, 0.923879533f, 0.831469612f, 0.707106781f, 0.555570233f, 0.382683432f, 0.195090322f, 0.000000000f, -0.195090322f, -0.382683432f, -0.555570233f, -0.707106781f, -0.831469612f, -0.923879533f, -0.980785280f, -1.000000000f, -0.980785280f, -0.923879533f, -0.831469612f, -0.707106781f, -0.555570233f, -0.382683432f, -0.195090322f};
+
+constexpr int bitrev(int v, int bits)
+{
+    int r = 0;
+    for (int i = 0; i < bits; ++i) r |= ((v >> i) & 1) << (bits - 1 - i);
+    return r;
+}
+constexpr int ilog2(int v) { return v <= 1 ? 0 : 1 + ilog2(v / 2); }
+
+// In-register DFT of length R (power of two <= 32), natural order in and out, unnormalised;
+// INV conjugates the kernel.  Radix-2 decimation in time, fully unrolled so every index and
+// twiddle is a compile-time constant.
+template <int R, bool INV> __device__ __forceinline__ void dft_reg(float2 (&x)[R])
+{
+    constexpr int LG = ilog2(R);
+#pragma unroll
+    for (int i = 0; i < R; ++i) {
+        const int j = bitrev(i, LG);
+        if (j > i) {
+            const float2 t = x[i];
+            x[i] = x[j];
+            x[j] = t;
+        }
+    }
+#pragma unroll
+    for (int len = 2; len <= R; len *= 2) {
+#pragma unroll
+        for (int blk = 0; blk < R; blk += len) {
+#pragma unroll
+            for (int j = 0; j < len / 2; ++j) {
+                const int q = j * (32 / len);                  // twiddle W_32^q, 0 <= q < 16
+                const float2 a = x[blk + j], b = x[blk + j + len / 2];
+                float2 t;
+                if (q == 0) {
+                    t = b;
+                } else if (q == 8) {                           // -i forward, +i inverse
+                    t = INV ? make_float2(-b.y, b.x) : make_float2(b.y, -b.x);
+                } else {
+                    const float wr = C32[q];
+                    const float wi = INV ? S32[q] : -S32[q];
+                    t = make_float2(b.x * wr - b.y * wi, b.x * wi + b.y * wr);
+                }
+                x[blk + j] = make_float2(a.x + t.x, a.y + t.y);
+                x[blk + j + len / 2] = make_float2(a.x - t.x, a.y - t.y);
+            }
+        }
+    }
+}
+
+// ---- pass A: zero-padded pair of real rows -> outer forward DFT (No = RA * RB) -> twiddle -> S.
+// One block = CT consecutive columns r of one (pair, channel); one thread = CV adjacent columns of
+// one butterfly, so that 16-bit input moves as 2*CV-byte and S as 4*CV-byte accesses.
+// Step 1: for every b2 < RB the length-RA transform over a (inputs a >= RA/2 are the implicit
+// zeros), times W_No^{ka b2}, into the fp32 LDS tile T[ka*RB + b2][c].  Step 2: for every ka the
+// length-RB transform over b2, times W_M^{r ko} (ko = ka + RA kb, by recurrence over kb), to S.
+template <bool F16, int RA, int RB, int CV>
+__global__ void __launch_bounds__(TB, 4) k_outer_fwd(const uint16_t *__restrict__ u, uint32_t *__restrict__ S, int CT,
+                                                 int B, int H, int N, int64_t M)
 {
     extern __shared__ float2 sm[];
-    const int No = g.No, Ra = g.Ra, Rb = g.Rb, CT = g.CT;
+    constexpr int No = RA * RB;
     float2 *wno = sm;                              // W_No^j, j < No
     float2 *T = sm + No;                           // [No][CT]
-    uint32_t *zin = (uint32_t *)(T + (size_t)No * CT);   // [No/2][CT] packed (row b, row b+1) 16-bit
     const int tid = threadIdx.x;
-    const int c = tid % CT, grp = tid / CT, G = TB / CT;
     const int r0 = blockIdx.x * CT;
     const int ph = blockIdx.y;                     // pair * H + h
     const int pair = ph / H, h = ph % H;
+    const int b0 = 2 * pair;
+    const bool two = b0 + 1 < B;
+    const uint16_t *row0 = u + ((size_t)b0 * H + h) * N;
+    const uint16_t *row1 = u + ((size_t)(b0 + (two ? 1 : 0)) * H + h) * N;
+    const bool wide = CV == 2 && N % 2 == 0;       // rows start 4-byte aligned
+    const int CG = CT / CV;                        // column groups
     for (int j = tid; j < No; j += TB) wno[j] = wm(j, 2.0f / (float)No);
-    const int half = No / 2;
-    for (int e = tid; e < half * CT; e += TB) {
-        const int no = e / CT, cc = e % CT;
-        const int64_t n = (int64_t)no * MI + r0 + cc;
-        uint32_t lo = 0, hi = 0;
-        if (n < N) {
-            const int b0 = 2 * pair;
-            lo = u[((size_t)b0 * H + h) * N + n];
-            if (b0 + 1 < B) hi = u[((size_t)(b0 + 1) * H + h) * N + n];
+    __syncthreads();
+    for (int e = tid; e < RB * CG; e += TB) {
+        const int c = (e % CG) * CV, b2 = e / CG;
+        uint32_t in0[RA / 2], in1[RA / 2];         // CV 16-bit values of row b / row b+1
+#pragma unroll
+        for (int a = 0; a < RA / 2; ++a) {
+            const int64_t n = (int64_t)(a * RB + b2) * MI + r0 + c;
+            in0[a] = in1[a] = 0;
+            if (wide) {
+                if (n < N) {
+                    in0[a] = *(const uint32_t *)(row0 + n);
+                    if (two) in1[a] = *(const uint32_t *)(row1 + n);
+                }
+            } else {
+#pragma unroll
+                for (int v = 0; v < CV; ++v)
+                    if (n + v < N) {
+                        in0[a] |= (uint32_t)row0[n + v] << (16 * v);
+                        if (two) in1[a] |= (uint32_t)row1[n + v] << (16 * v);
+                    }
+            }
         }
-        zin[e] = lo | (hi << 16);
+        float2 o[RA][CV];
+#pragma unroll
+        for (int v = 0; v < CV; ++v) {
+            float2 x[RA];
+#pragma unroll
+            for (int a = 0; a < RA; ++a) {
+                x[a] = make_float2(0.f, 0.f);
+                if (a < RA / 2)                                      // (row b, row b+1) = (re, im)
+                    x[a] = unpack2<F16>(((in0[a] >> (16 * v)) & 0xffffu) | ((in1[a] >> (16 * v)) << 16));
+            }
+            dft_reg<RA, false>(x);
+#pragma unroll
+            for (int ka = 0; ka < RA; ++ka) o[ka][v] = cmulf(x[ka], wno[ka * b2]);
+        }
+#pragma unroll
+        for (int ka = 0; ka < RA; ++ka) {
+            float2 *dst = &T[(ka * RB + b2) * CT + c];
+            if constexpr (CV == 2)
+                *(float4 *)dst = make_float4(o[ka][0].x, o[ka][0].y, o[ka][1].x, o[ka][1].y);
+            else
+                *dst = o[ka][0];
+        }
     }
     __syncthreads();
-    // step 1: T[ka*Rb + b2] = W_No^{ka b2} * sum_{a < Ra/2} z[a*Rb + b2] W_Ra^{a ka}
-    for (int o = grp; o < No; o += G) {
-        const int ka = o / Rb, b2 = o % Rb;
-        float2 acc = make_float2(0.f, 0.f);
-        int ph2 = 0;                               // (a * ka) mod Ra
-        for (int a = 0; a < Ra / 2; ++a) {
-            const float2 z = unpack2<F16>(zin[(a * Rb + b2) * CT + c]);   // (row b, row b+1) = (re, im)
-            const float2 t = cmulf(z, wno[ph2 * Rb]);
-            acc.x += t.x;
-            acc.y += t.y;
-            ph2 += ka;
-            if (ph2 >= Ra) ph2 -= Ra;
-        }
-        T[o * CT + c] = cmulf(acc, wno[ka * b2]);
-    }
-    __syncthreads();
-    // step 2: A[ka + Ra*kb] = sum_{b2} T[ka*Rb + b2] W_Rb^{b2 kb};  S = A * W_M^{r ko}
     const float ihm = 2.0f / (float)M;
-    for (int o = grp; o < No; o += G) {
-        const int ka = o % Ra, kb = o / Ra;        // o = ko
-        float2 acc = make_float2(0.f, 0.f);
-        int ph2 = 0;                               // (b2 * kb) mod Rb
-        for (int b2 = 0; b2 < Rb; ++b2) {
-            const float2 t = cmulf(T[(ka * Rb + b2) * CT + c], wno[ph2 * Ra]);
-            acc.x += t.x;
-            acc.y += t.y;
-            ph2 += kb;
-            if (ph2 >= Rb) ph2 -= Rb;
+    for (int e = tid; e < RA * CG; e += TB) {
+        const int c = (e % CG) * CV, ka = e / CG;
+        uint32_t o[RB][CV];
+#pragma unroll
+        for (int v = 0; v < CV; ++v) {
+            float2 x[RB];
+#pragma unroll
+            for (int b2 = 0; b2 < RB; ++b2) x[b2] = T[(ka * RB + b2) * CT + c + v];
+            dft_reg<RB, false>(x);
+            const int r = r0 + c + v;
+            float2 w = wm((int)(((int64_t)r * ka) % M), ihm);                 // W_M^{r ka}
+            const float2 step = wm((int)(((int64_t)r * RA) % M), ihm);        // W_M^{r RA}
+#pragma unroll
+            for (int kb = 0; kb < RB; ++kb) {
+                const float2 t = cmulf(x[kb], w);
+                o[kb][v] = (uint32_t)cv16<F16>(t.x) | ((uint32_t)cv16<F16>(t.y) << 16);
+                w = cmulf(w, step);
+            }
         }
-        const int r = r0 + c;
-        const int e = (int)(((int64_t)r * o) % M);
-        acc = cmulf(acc, wm(e, ihm));
-        S[((size_t)ph * No + o) * MI + r] = (uint32_t)cv16<F16>(acc.x) | ((uint32_t)cv16<F16>(acc.y) << 16);
+#pragma unroll
+        for (int kb = 0; kb < RB; ++kb) {
+            uint32_t *dst = &S[((size_t)ph * No + ka + RA * kb) * MI + r0 + c];
+            if constexpr (CV == 2)
+                *(uint2 *)dst = make_uint2(o[kb][0], o[kb][1]);
+            else
+                *dst = o[kb][0];
+        }
     }
 }
 
 // ---- pass C: S -> conjugate twiddle -> outer inverse DFT -> the two real rows of the pair
-template <bool F16>
-__global__ void __launch_bounds__(TB) k_outer_inv(const uint32_t *__restrict__ S, uint16_t *__restrict__ y,
-                                                 OuterGeo g, int B, int H, int N, int64_t M)
+template <bool F16, int RA, int RB, int CV>
+__global__ void __launch_bounds__(TB, 4) k_outer_inv(const uint32_t *__restrict__ S, uint16_t *__restrict__ y, int CT,
+                                                 int B, int H, int N, int64_t M)
 {
     extern __shared__ float2 sm[];
-    const int No = g.No, Ra = g.Ra, Rb = g.Rb, CT = g.CT;
+    constexpr int No = RA * RB;
     float2 *wno = sm;
-    float2 *X = sm + No;                           // [No][CT] twiddled input
-    float2 *T = X + (size_t)No * CT;               // [No][CT]
+    float2 *T = sm + No;                           // [No][CT]
     const int tid = threadIdx.x;
-    const int c = tid % CT, grp = tid / CT, G = TB / CT;
     const int r0 = blockIdx.x * CT;
     const int ph = blockIdx.y;
     const int pair = ph / H, h = ph % H;
+    const int b0 = 2 * pair;
+    const bool two = b0 + 1 < B;
+    const bool wide = CV == 2 && N % 2 == 0;
+    const int CG = CT / CV;
     for (int j = tid; j < No; j += TB) wno[j] = wm(j, 2.0f / (float)No);
+    __syncthreads();
     const float ihm = 2.0f / (float)M;
-    for (int e = tid; e < No * CT; e += TB) {
-        const int ko = e / CT, cc = e % CT;
-        const int r = r0 + cc;
-        const float2 v = unpack2<F16>(S[((size_t)ph * No + ko) * MI + r]);
-        X[e] = cmulcf(v, wm((int)(((int64_t)r * ko) % M), ihm));
+    // step 1: T[ka*RB + b2] = conj(W_No^{ka b2}) * sum_{kb} conj(W_RB^{b2 kb}) conj(W_M^{r ko}) S[ko], ko = ka + RA kb
+    for (int e = tid; e < RA * CG; e += TB) {
+        const int c = (e % CG) * CV, ka = e / CG;
+        uint32_t in[RB][CV];
+#pragma unroll
+        for (int kb = 0; kb < RB; ++kb) {
+            const uint32_t *src = &S[((size_t)ph * No + ka + RA * kb) * MI + r0 + c];
+            if constexpr (CV == 2) {
+                const uint2 t = *(const uint2 *)src;
+                in[kb][0] = t.x;
+                in[kb][1] = t.y;
+            } else {
+                in[kb][0] = *src;
+            }
+        }
+        float2 o[RB][CV];
+#pragma unroll
+        for (int v = 0; v < CV; ++v) {
+            const int r = r0 + c + v;
+            float2 w = wm((int)(((int64_t)r * ka) % M), ihm);
+            const float2 step = wm((int)(((int64_t)r * RA) % M), ihm);
+            float2 x[RB];
+#pragma unroll
+            for (int kb = 0; kb < RB; ++kb) {
+                x[kb] = cmulcf(unpack2<F16>(in[kb][v]), w);
+                w = cmulf(w, step);
+            }
+            dft_reg<RB, true>(x);
+#pragma unroll
+            for (int b2 = 0; b2 < RB; ++b2) o[b2][v] = cmulcf(x[b2], wno[ka * b2]);
+        }
+#pragma unroll
+        for (int b2 = 0; b2 < RB; ++b2) {
+            float2 *dst = &T[(ka * RB + b2) * CT + c];
+            if constexpr (CV == 2)
+                *(float4 *)dst = make_float4(o[b2][0].x, o[b2][0].y, o[b2][1].x, o[b2][1].y);
+            else
+                *dst = o[b2][0];
+        }
     }
     __syncthreads();
-    // step 1: T[ka*Rb + b2] = conj(W_No^{ka b2}) * sum_{kb} X[ka + Ra*kb] conj(W_Rb^{b2 kb})
-    for (int o = grp; o < No; o += G) {
-        const int ka = o / Rb, b2 = o % Rb;
-        float2 acc = make_float2(0.f, 0.f);
-        int ph2 = 0;                               // (b2 * kb) mod Rb
-        for (int kb = 0; kb < Rb; ++kb) {
-            const float2 t = cmulcf(X[(ka + Ra * kb) * CT + c], wno[ph2 * Ra]);
-            acc.x += t.x;
-            acc.y += t.y;
-            ph2 += b2;
-            if (ph2 >= Rb) ph2 -= Rb;
+    // step 2: z[a*RB + b2] = sum_{ka} conj(W_RA^{a ka}) T[ka*RB + b2], kept for a < RA/2 (n < M/2)
+    uint16_t *row0 = y + ((size_t)b0 * H + h) * N;
+    uint16_t *row1 = y + ((size_t)(b0 + (two ? 1 : 0)) * H + h) * N;
+    for (int e = tid; e < RB * CG; e += TB) {
+        const int c = (e % CG) * CV, b2 = e / CG;
+        uint32_t o0[RA / 2], o1[RA / 2];
+#pragma unroll
+        for (int a = 0; a < RA / 2; ++a) o0[a] = o1[a] = 0;
+#pragma unroll
+        for (int v = 0; v < CV; ++v) {
+            float2 x[RA];
+#pragma unroll
+            for (int ka = 0; ka < RA; ++ka) x[ka] = T[(ka * RB + b2) * CT + c + v];
+            dft_reg<RA, true>(x);
+#pragma unroll
+            for (int a = 0; a < RA / 2; ++a) {
+                o0[a] |= (uint32_t)cv16<F16>(x[a].x) << (16 * v);
+                o1[a] |= (uint32_t)cv16<F16>(x[a].y) << (16 * v);
+            }
         }
-        T[o * CT + c] = cmulcf(acc, wno[ka * b2]);
-    }
-    __syncthreads();
-    // step 2: z[a*Rb + b2] = sum_{ka} T[ka*Rb + b2] conj(W_Ra^{a ka}),  a < Ra/2 (n < M/2)
-    for (int o = grp; o < No / 2; o += G) {        // o = no = a*Rb + b2
-        const int a = o / Rb, b2 = o % Rb;
-        float2 acc = make_float2(0.f, 0.f);
-        int ph2 = 0;                               // (a * ka) mod Ra
-        for (int ka = 0; ka < Ra; ++ka) {
-            const float2 t = cmulcf(T[(ka * Rb + b2) * CT + c], wno[ph2 * Rb]);
-            acc.x += t.x;
-            acc.y += t.y;
-            ph2 += a;
-            if (ph2 >= Ra) ph2 -= Ra;
-        }
-        const int64_t n = (int64_t)o * MI + r0 + c;
-        if (n < N) {
-            const int b0 = 2 * pair;
-            y[((size_t)b0 * H + h) * N + n] = cv16<F16>(acc.x);
-            if (b0 + 1 < B) y[((size_t)(b0 + 1) * H + h) * N + n] = cv16<F16>(acc.y);
+#pragma unroll
+        for (int a = 0; a < RA / 2; ++a) {
+            const int64_t n = (int64_t)(a * RB + b2) * MI + r0 + c;
+            if (wide) {
+                if (n < N) {
+                    *(uint32_t *)(row0 + n) = o0[a];
+                    if (two) *(uint32_t *)(row1 + n) = o1[a];
+                }
+            } else {
+#pragma unroll
+                for (int v = 0; v < CV; ++v)
+                    if (n + v < N) {
+                        row0[n + v] = (uint16_t)(o0[a] >> (16 * v));
+                        if (two) row1[n + v] = (uint16_t)(o1[a] >> (16 * v));
+                    }
+            }
         }
     }
 }
@@ -215,8 +346,52 @@ OuterGeo outer_geo(int64_t M)
     g.No = (int)(M / MI);
     g.Ra = g.No < 16 ? g.No : 16;
     g.Rb = g.No / g.Ra;
-    g.CT = MI / g.No < TB ? MI / g.No : TB;      // No * CT <= 8192 points per block, at most one column per thread
+    // fp32 tile T[No][CT] of 64 KiB (two blocks per compute unit), at least 32 columns
+    g.CT = MI / g.No < 32 ? 32 : MI / g.No;
     return g;
+}
+
+template <bool F16, int RA, int RB>
+int launch_outer(bool inverse, const OuterGeo &g, dim3 grid, const void *src, void *dst, int B, int H, int N, int64_t M,
+                 hipStream_t s)
+{
+    constexpr int CV = RB <= 16 ? 2 : 1;           // two columns per thread while the registers allow
+    const size_t lds = sizeof(float2) * ((size_t)g.No + (size_t)g.No * g.CT);
+    static bool attr_set = false;
+    if (!attr_set) {
+        FC_HIP(hipFuncSetAttribute((const void *)k_outer_fwd<F16, RA, RB, CV>,
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+        FC_HIP(hipFuncSetAttribute((const void *)k_outer_inv<F16, RA, RB, CV>,
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+        attr_set = true;
+    }
+    if (!inverse)
+        hipLaunchKernelGGL((k_outer_fwd<F16, RA, RB, CV>), grid, dim3(TB), lds, s, (const uint16_t *)src,
+                           (uint32_t *)dst, g.CT, B, H, N, M);
+    else
+        hipLaunchKernelGGL((k_outer_inv<F16, RA, RB, CV>), grid, dim3(TB), lds, s, (const uint32_t *)src,
+                           (uint16_t *)dst, g.CT, B, H, N, M);
+    FC_HIP(hipGetLastError());
+    return FFTCONV_OK;
+}
+
+template <bool F16>
+int dispatch_outer(bool inverse, const OuterGeo &g, dim3 grid, const void *src, void *dst, int B, int H, int N,
+                   int64_t M, hipStream_t s)
+{
+    switch (g.No) {
+    case 4: return launch_outer<F16, 4, 1>(inverse, g, grid, src, dst, B, H, N, M, s);
+    case 8: return launch_outer<F16, 8, 1>(inverse, g, grid, src, dst, B, H, N, M, s);
+    case 16: return launch_outer<F16, 16, 1>(inverse, g, grid, src, dst, B, H, N, M, s);
+    case 32: return launch_outer<F16, 16, 2>(inverse, g, grid, src, dst, B, H, N, M, s);
+    case 64: return launch_outer<F16, 16, 4>(inverse, g, grid, src, dst, B, H, N, M, s);
+    case 128: return launch_outer<F16, 16, 8>(inverse, g, grid, src, dst, B, H, N, M, s);
+    case 256: return launch_outer<F16, 16, 16>(inverse, g, grid, src, dst, B, H, N, M, s);
+    case 512: return launch_outer<F16, 16, 32>(inverse, g, grid, src, dst, B, H, N, M, s);
+    default:
+        set_error("multipass: unsupported outer length %d", g.No);
+        return FFTCONV_EUNSUPPORTED;
+    }
 }
 
 }  // namespace
@@ -262,33 +437,13 @@ int multipass_forward(const fftconv_plan *p, const void *u, const void *kf, void
     const bool f16 = p->dtype == FFTCONV_F16;
     uint32_t *S = (uint32_t *)workspace;
     const dim3 grid((unsigned)(MI / g.CT), (unsigned)rows);
-    const size_t lds_a = sizeof(float2) * (g.No + (size_t)g.No * g.CT) + sizeof(uint32_t) * (size_t)(g.No / 2) * g.CT;
-    const size_t lds_c = sizeof(float2) * (g.No + 2 * (size_t)g.No * g.CT);
-    static bool attr_set = false;
-    if (!attr_set) {
-        FC_HIP(hipFuncSetAttribute((const void *)k_outer_fwd<true>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
-        FC_HIP(hipFuncSetAttribute((const void *)k_outer_fwd<false>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
-        FC_HIP(hipFuncSetAttribute((const void *)k_outer_inv<true>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
-        FC_HIP(hipFuncSetAttribute((const void *)k_outer_inv<false>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
-        attr_set = true;
-    }
-    if (f16)
-        hipLaunchKernelGGL(k_outer_fwd<true>, grid, dim3(TB), lds_a, s, (const uint16_t *)u, S, g, (int)B, (int)p->H,
-                           (int)p->N, p->M);
-    else
-        hipLaunchKernelGGL(k_outer_fwd<false>, grid, dim3(TB), lds_a, s, (const uint16_t *)u, S, g, (int)B, (int)p->H,
-                           (int)p->N, p->M);
-    FC_HIP(hipGetLastError());
-    int rc = fused3_inner_rows(p, S, kf, npairs, p->H * g.No, s);
+    int rc = f16 ? dispatch_outer<true>(false, g, grid, u, S, (int)B, (int)p->H, (int)p->N, p->M, s)
+                 : dispatch_outer<false>(false, g, grid, u, S, (int)B, (int)p->H, (int)p->N, p->M, s);
     if (rc) return rc;
-    if (f16)
-        hipLaunchKernelGGL(k_outer_inv<true>, grid, dim3(TB), lds_c, s, S, (uint16_t *)y, g, (int)B, (int)p->H,
-                           (int)p->N, p->M);
-    else
-        hipLaunchKernelGGL(k_outer_inv<false>, grid, dim3(TB), lds_c, s, S, (uint16_t *)y, g, (int)B, (int)p->H,
-                           (int)p->N, p->M);
-    FC_HIP(hipGetLastError());
-    return FFTCONV_OK;
+    rc = fused3_inner_rows(p, S, kf, npairs, p->H * g.No, s);
+    if (rc) return rc;
+    return f16 ? dispatch_outer<true>(true, g, grid, S, y, (int)B, (int)p->H, (int)p->N, p->M, s)
+               : dispatch_outer<false>(true, g, grid, S, y, (int)B, (int)p->H, (int)p->N, p->M, s);
 }
 
 }  // namespace fftconv
