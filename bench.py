@@ -21,6 +21,22 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0            # MI355X published HBM3E peak
+COPY_BYTES = 1 << 28             # size of the --copy-calibration kernel's source (and destination)
+TRAFFIC_TABLE = os.path.join(ROOT, "profiles", "hbm_traffic.md")
+
+
+def measured_traffic(workload: str):
+    """HBM bytes per launch of the workload's dominant kernel, from the committed rocprofv3 --pmc
+    summary (FETCH_SIZE and WRITE_SIZE, each scaled by the copy kernel's reading); None if the table
+    has no row for this workload.  Row format: | workload | kernel | fetch bytes | write bytes | total bytes |"""
+    try:
+        for line in open(TRAFFIC_TABLE):
+            cells = [c.strip() for c in line.strip().strip("|").split("|")]
+            if len(cells) >= 5 and cells[0] == workload:
+                return float(cells[4])
+    except OSError:
+        pass
+    return None
 
 
 def algorithmic_bytes(w) -> int:
@@ -66,6 +82,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=300)
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also launch a plain elementwise copy of %d MiB (read once, written once) before the "
+                         "warm-up, as the known-size reference for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE" % (COPY_BYTES >> 20))
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (sequences are independent; see DESIGN.md for how the "
@@ -93,6 +112,14 @@ def main():
     u = u_cpu.to(dev)
     y = torch.empty_like(u)
     torch.cuda.synchronize()
+
+    if args.copy_calibration:
+        src = torch.zeros(COPY_BYTES // 4, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.mul(src, 1.0, out=dst)           # one elementwise kernel: COPY_BYTES read, COPY_BYTES written
+        torch.cuda.synchronize()
+        del src, dst
 
     def step():
         if bk is not None:
@@ -157,8 +184,8 @@ def main():
                    "dense_ms_per_step": dense_ms,
                    "speedup_vs_dense": None if dense_ms is None else dense_ms / ms_per_step},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                     "kernel": "k_fused3" if plan.path == "fused3" else plan.path,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(w.name),
+                     "kernel": ("k_fused3_ws" if w.fft_size == 8192 else "k_fused3") if plan.path == "fused3" else plan.path,
                      "algorithmic_bytes": abytes},
     }
     if not args.no_cpu_baseline:
