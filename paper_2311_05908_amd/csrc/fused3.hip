@@ -712,7 +712,7 @@ int launch(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_
 bool fused3_supported(int64_t N, int64_t M, int dtype)
 {
     if (dtype != FFTCONV_F16 && dtype != FFTCONV_BF16) return false;
-    if (M != 8192 && M != 16384) return false;
+    if (M != 8192 && M != 16384 && M != 32768) return false;
     return N <= M / 2 && N % 8 == 0;
 }
 
@@ -734,6 +734,10 @@ int fused3_init(fftconv_plan *p)
         if (rc) return rc;
         return build_tables<16, 16>(p, &p->f3.consts_short);     // for partial convolutions, see fused3_forward_short
     }
+    case 32768:
+        p->f3.N2 = 32;
+        p->f3.N3 = 32;
+        return fused3_big_init(p);
     default:
         set_error("fused3: no kernel for fft_size=%lld", (long long)p->M);
         return FFTCONV_EUNSUPPORTED;
@@ -821,6 +825,7 @@ constexpr int64_t SHORT_MAX_P = 2048;      // most history a segment may carry (
 
 size_t fused3_kf_bytes(const fftconv_plan *p)
 {
+    if (p->M == 32768) return fused3_big_kf_bytes(p);
     // fft 16384 plans: dense spectrum, then the 8192-point spectrum of a short filter
     const int64_t bins = p->M + (p->f3.consts_short ? SHORT_M : 0);
     return (size_t)(p->H * bins) * sizeof(float2);
@@ -878,6 +883,8 @@ int fused3_pack_kf(const fftconv_plan *p, const double2 *spec, int64_t h0, int64
         hipLaunchKernelGGL((k_pack_fused3<32, 16>), dim3(grid), dim3(bs), 0, s, spec, (float2 *)kf,
                            staged_fac_list(p), h0, nh, keep_dev, n_blocks, 0);
         break;
+    case 32768:
+        return fused3_big_pack_kf(p, spec, h0, nh, keep_dev, n_blocks, kf, s);
     default:
         set_error("fused3: no kernel for fft_size=%lld", (long long)p->M);
         return FFTCONV_EUNSUPPORTED;
@@ -899,6 +906,8 @@ int fused3_forward(const fftconv_plan *p, const void *u, const void *kf, void *y
     case 16384:
         return f16 ? launch<32, 16, F16, false, false>(p, u, kf, y, B, p->H, p->N, s)
                    : launch<32, 16, BF16, false, false>(p, u, kf, y, B, p->H, p->N, s);
+    case 32768:
+        return fused3_big_forward(p, u, kf, y, B, s);
     default:
         set_error("fused3: no kernel for fft_size=%lld", (long long)p->M);
         return FFTCONV_EUNSUPPORTED;

@@ -1,0 +1,668 @@
+// Fused causal FFT convolution for fft_size 32768 = 32*32*32, 16-bit I/O (paper Algorithm 3:
+// whole sequence on chip, u read once, y written once).  Same arithmetic and index maps as the
+// smaller fused kernels (fused3.hip): time n = (n1*32 + n2)*32 + n3, frequency
+// f = k1 + 32*k2 + 1024*k3, two batch rows of a channel share one complex transform, the zero half
+// of the padded input is never touched.
+//
+// What this size changes:
+//  * The exchange buffer X(k1,k2,n3) of one pair is 128 KiB of 16-bit (re, im) pairs: it is the only
+//    thing in LDS.  There is no staging buffer for u and y; every wave owns four adjacent n3
+//    planes, so a lane moves the 4 x 16-bit values it needs as one 8-byte global access
+//    (rows of 64 bytes are completed by the 8 waves of the workgroup, through the L1/L2 caches).
+//    The input of the next pair is prefetched into registers in MFMA-operand order.
+//  * The per-plane constant tables (stage-2 matrices with folded twiddles, elementwise twiddles,
+//    k_f) do not fit in registers: they are streamed from L2, each one plane ahead of its use.
+//    Twiddles and k_f are 16-bit (re, im) constants for packed arithmetic (fp16: 4 bytes per
+//    point, op_sel / neg modifiers do the complex product; bf16: 8 bytes, dot-product form).
+//  * The inverse innermost stage reuses the forward stage-3 matrix: the pointwise product writes
+//    conj(A3 * k_f), the (symmetric) forward matrix then yields the conjugate of the inverse
+//    transform, and the following twiddle product conjugates back.  Both conjugations are free
+//    (instruction modifiers for fp16, sign pattern of the constants for bf16), and 32 registers
+//    of matrix are saved.
+//  * Schedule per pair, 2 workgroup barriers: [phase B] | [phase C of this pair, then phase A of
+//    the next one: a wave reads and rewrites only its own n3 planes, so no barrier in between].
+#include <cmath>
+#include <cstring>
+#include <vector>
+
+#include "fused3_common.h"
+
+namespace fftconv {
+namespace f3 {
+
+namespace {
+
+constexpr int BM = 32768;                     // fft size
+constexpr int BPK1 = 36;                      // X(k1,k2,n3) word = n3*BPN3 + k1*BPK1 + k2
+constexpr int BPN3 = 32 * BPK1 + 4;
+constexpr int BXB_WORDS = 32 * BPN3;
+constexpr size_t BIG_LDS_BYTES = (size_t)BXB_WORDS * 4;
+
+// bf16: dot-product form.  Constant of a factor (wr, wi): { (wr, -wi), (wi, wr) }, which yields
+// z * w; the tables of the conjugating products hold { (wr, -wi), (-wi, -wr) } instead, which yields
+// conj(z * w) from the same instructions (CONJ is a table matter for this type).
+struct B16 {
+    using CW = uint2;
+    static __device__ __forceinline__ f32x4 mfma(uint4 a, uint4 b, f32x4 c) { return BF16::mfma(a, b, c); }
+    static __device__ __forceinline__ uint32_t pack(float lo, float hi) { return BF16::pack(lo, hi); }
+    template <bool CONJ> static __device__ __forceinline__ uint4 ctw4(f32x4 re, f32x4 im, const CW (&c)[4])
+    {
+        return BF16::ctw4(re, im, c);
+    }
+    static __host__ __device__ inline CW cconst(uint32_t re, uint32_t im, bool conj)   // 16-bit patterns
+    {
+        const uint32_t nre = re ^ 0x8000u, nim = im ^ 0x8000u;
+        return conj ? make_uint2(re | (nim << 16), nim | (nre << 16)) : make_uint2(re | (nim << 16), im | (re << 16));
+    }
+};
+
+// fp16: packed arithmetic.  Constant of a factor: the pair (wr, wi); the operand selectors
+// broadcast / swap halves and the neg modifiers supply the signs:
+//   t   = (zr*wr, zi*wr)
+//   out = (zi*(-wi) + t.lo, zr*wi + t.hi)            CONJ negates the high half of both steps.
+struct H16 {
+    using CW = uint32_t;
+    static __device__ __forceinline__ f32x4 mfma(uint4 a, uint4 b, f32x4 c) { return F16::mfma(a, b, c); }
+    static __device__ __forceinline__ uint32_t pack(float lo, float hi) { return F16::pack(lo, hi); }
+    static __host__ __device__ inline CW cconst(uint32_t re, uint32_t im, bool) { return re | (im << 16); }
+    template <bool CONJ> static __device__ __forceinline__ uint4 ctw4(f32x4 re, f32x4 im, const CW (&c)[4])
+    {
+        uint32_t o[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const uint32_t p = pack(re[r], im[r]);
+            uint32_t t;
+            if constexpr (!CONJ) {
+                asm("v_pk_mul_f16 %0, %1, %2 op_sel:[0,0] op_sel_hi:[1,0]" : "=v"(t) : "v"(p), "v"(c[r]));
+                asm("v_pk_fma_f16 %0, %1, %2, %3 op_sel:[1,1,0] op_sel_hi:[0,1,1] neg_lo:[0,1,0]"
+                    : "=v"(o[r])
+                    : "v"(p), "v"(c[r]), "v"(t));
+            } else {
+                asm("v_pk_mul_f16 %0, %1, %2 op_sel:[0,0] op_sel_hi:[1,0] neg_hi:[0,1]"
+                    : "=v"(t)
+                    : "v"(p), "v"(c[r]));
+                asm("v_pk_fma_f16 %0, %1, %2, %3 op_sel:[1,1,0] op_sel_hi:[0,1,1] neg_lo:[0,1,0] neg_hi:[0,1,0]"
+                    : "=v"(o[r])
+                    : "v"(p), "v"(c[r]), "v"(t));
+            }
+        }
+        return make_uint4(o[0], o[1], o[2], o[3]);
+    }
+};
+
+template <typename CW> struct BigConsts {
+    const uint4 *tab1;    // [ct][part][lane]                 W_32^{n1 k1}, n1 < 16
+    const uint4 *tab1i;   // [K step][part][lane]             conj(W_32^{k1 n1}), n1 < 16
+    const uint4 *tab3;    // [K step][tile][part][lane]       W_32^{n3 k3}
+    const uint4 *tab2;    // [n3][K step][tile][part][lane]   W_32^{n2 k2} W_1024^{k2 n3}
+    const uint4 *tab2i;   // [k1][K step][tile][part][lane]   conj(W_32^{k2 n2} W_1024^{k1 n2})
+    const CW *twa;        // [n3][rt][ct][r][lane]            W_M^{k1 (32 n2 + n3)}
+    const CW *twb;        // [k1][ct2][ct3][r][lane]          W_M^{(k1 + 32 k2) n3}, used as conj(z * w)
+};
+constexpr size_t BIG_U4 = (size_t)(4 + 4 + 8 + 32 * 8 + 32 * 8) * 64;
+
+// nothing may be moved across: pins where the streamed table loads are issued
+#define SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
+
+// FULL: B even and N == 16384, every access of a work item is in range.
+template <typename TT, bool FULL>
+__global__ void __launch_bounds__(NT) k_fused3_big(const uint16_t *__restrict__ u, uint16_t *__restrict__ y,
+                                                  const typename TT::CW *__restrict__ kf, BigConsts<typename TT::CW> cs,
+                                                  int B, int H, int N)
+{
+    using CW = typename TT::CW;
+    extern __shared__ uint32_t XB[];
+    const int tid = threadIdx.x, l = tid & 63, q = l >> 4, c16 = l & 15;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // persistent workgroup: a contiguous range of work items t = h * npairs + pair
+    const int npairs = (B + 1) / 2;
+    const long long T = (long long)H * npairs;
+    const int t0 = (int)(T * blockIdx.x / gridDim.x);
+    const int t1 = (int)(T * (blockIdx.x + 1) / gridDim.x);
+    if (t0 >= t1) return;
+    const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
+
+    // LDS base addresses of this lane, chosen so that every access below is base + a small constant
+    uint32_t *const wrA = XB + 4 * w * BPN3 + c16 * BPK1 + 4 * q;         // + i*BPN3 + 16 ct*BPK1 + 16 ct2
+    const uint32_t *const rdC = XB + 4 * w * BPN3 + 4 * q * BPK1 + c16;   // + i*BPN3 + (16 ks + r)*BPK1 + 16 cn2
+    const uint32_t *const rdB0 = XB + (4 * q) * BPN3 + 4 * w * BPK1 + c16;        // + r*BPN3 + i*BPK1 + 16 ct2
+    const uint32_t *const rdB1 = rdB0 + 16 * BPN3;                                // K step 1
+    uint32_t *const wrB0 = XB + c16 * BPN3 + 4 * w * BPK1 + 4 * q;                // + i*BPK1 + 16 cn2
+    uint32_t *const wrB1 = wrB0 + 16 * BPN3;                                      // n3 tile 1
+
+    uint4 tab1[2][2], tab1i[2][2], tab3[2][2][2];
+    uint4 tabA[2][2][2], tabB[2][2][2];          // stage-2 / inverse stage-2 matrices of the current plane
+    CW twaR[2][2][4], twbR[2][2][4], kfR[2][2][4];
+    uint2 pre[2][2][4];                           // next pair's input: [row of the pair][n2 tile][r], 4 n3 planes each
+
+    // The tables are loop invariant but must be re-read for every work item (they do not fit in
+    // registers): an opaque zero added to the lane offset keeps the loads inside the loop.
+    // (unsigned, so that a load is "uniform base + 32-bit lane offset + immediate" and needs no
+    //  64-bit address registers)
+    uint32_t lz = (uint32_t)l;
+    auto opaque = [&]() {
+        uint32_t z = 0;
+        asm volatile("" : "+v"(z));
+        lz = ((uint32_t)l + z) & 63u;
+    };
+    auto load_fixed_outer = [&]() {
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+            for (int p = 0; p < 2; ++p) {
+                tab1[a][p] = (cs.tab1 + (a * 2 + p) * 64)[lz];
+                tab1i[a][p] = (cs.tab1i + (a * 2 + p) * 64)[lz];
+            }
+    };
+    auto load_tab3 = [&]() {
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+            for (int b = 0; b < 2; ++b)
+#pragma unroll
+                for (int p = 0; p < 2; ++p) tab3[a][b][p] = (cs.tab3 + ((a * 2 + b) * 2 + p) * 64)[lz];
+    };
+    auto load_tabA = [&](int i) {
+        const int c = 4 * w + i;
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+            for (int b = 0; b < 2; ++b)
+#pragma unroll
+                for (int p = 0; p < 2; ++p) tabA[a][b][p] = (cs.tab2 + (((c * 2 + a) * 2 + b) * 2 + p) * 64)[lz];
+    };
+    auto load_twa = [&](int i) {
+        const int c = 4 * w + i;
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+            for (int b = 0; b < 2; ++b)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) twaR[a][b][r] = (cs.twa + (((c * 2 + a) * 2 + b) * 4 + r) * 64)[lz];
+    };
+    auto load_tabB = [&](int i) {
+        const int c = 4 * w + i;
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+            for (int b = 0; b < 2; ++b)
+#pragma unroll
+                for (int p = 0; p < 2; ++p) tabB[a][b][p] = (cs.tab2i + (((c * 2 + a) * 2 + b) * 2 + p) * 64)[lz];
+    };
+    auto load_twb = [&](int i) {
+        const int c = 4 * w + i;
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+            for (int b = 0; b < 2; ++b)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) twbR[a][b][r] = (cs.twb + (((c * 2 + a) * 2 + b) * 4 + r) * 64)[lz];
+    };
+    auto load_kf = [&](int i, int h) {
+        const int c = 4 * w + i;
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+            for (int b = 0; b < 2; ++b)
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    kfR[a][b][r] = (kf + (size_t)h * BM + (((c * 2 + a) * 2 + b) * 4 + r) * 64)[lz];
+    };
+    // element offset inside a row of u / y of this lane's 4-plane group: n1 = 4q + r, n2 = 16 tile + c16, n3 = 4w
+    auto elem = [&](int tile, int r) { return (4 * q + r) * 1024 + (16 * tile + c16) * 32 + 4 * w; };
+    auto issue_pre = [&](int t) {
+        const int h = t / npairs, pair = t - h * npairs;
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            const int b = 2 * pair + s;
+            const uint16_t *row = u + ((size_t)(FULL ? b : min(b, B - 1)) * H + h) * N;
+#pragma unroll
+            for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int n = elem(rt, r);
+                    if constexpr (FULL) {
+                        pre[s][rt][r] = *(const uint2 *)(row + n);
+                    } else {
+                        uint2 v = make_uint2(0, 0);
+                        if (b < B && n < N) v = *(const uint2 *)(row + n);
+                        pre[s][rt][r] = v;
+                    }
+                }
+        }
+    };
+
+    // ---- phase A of one pair: stage 1, twiddle, stage 2 -> XB (this wave's 4 n3 planes).
+    // On entry tab1, tabA and twaR hold plane 0's tables; the others follow one plane ahead.
+    auto phase_A = [&]() {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t sel = (i & 1) ? 0x07060302u : 0x05040100u;
+            uint4 x2[2][2];                               // stage-2 operands [k1 tile][K step = n2 tile]
+#pragma unroll
+            for (int rt = 0; rt < 2; ++rt) {
+                // rows n2 = 16 rt + c16; slots (2r+s) = u_s[n1 = 4q + r]
+                uint32_t d[4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const uint32_t lo = i < 2 ? pre[0][rt][r].x : pre[0][rt][r].y;
+                    const uint32_t hi = i < 2 ? pre[1][rt][r].x : pre[1][rt][r].y;
+                    d[r] = __builtin_amdgcn_perm(hi, lo, sel);
+                }
+                const uint4 x1 = make_uint4(d[0], d[1], d[2], d[3]);
+#pragma unroll
+                for (int ct = 0; ct < 2; ++ct) {
+                    const f32x4 dre = TT::mfma(x1, tab1[ct][0], zero4);
+                    const f32x4 dim = TT::mfma(x1, tab1[ct][1], zero4);
+                    // lane: k1 = 16 ct + c16; reg r: n2 = 16 rt + 4q + r
+                    x2[ct][rt] = TT::template ctw4<false>(dre, dim, twaR[rt][ct]);
+                }
+            }
+            SCHED_FENCE();
+            if (i + 1 < 4) load_twa(i + 1);
+            SCHED_FENCE();
+#pragma unroll
+            for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+                for (int ct2 = 0; ct2 < 2; ++ct2) {
+                    f32x4 dre = zero4, dim = zero4;
+#pragma unroll
+                    for (int ks = 0; ks < 2; ++ks) {      // matrix as the A operand: rows k2, data columns k1
+                        dre = TT::mfma(tabA[ks][ct2][0], x2[ct][ks], dre);
+                        dim = TT::mfma(tabA[ks][ct2][1], x2[ct][ks], dim);
+                    }
+                    // lane: k1 = 16 ct + c16; reg r: k2 = 16 ct2 + 4q + r -> one 16-byte write
+                    uint32_t *dst = wrA + i * BPN3 + 16 * ct * BPK1 + 16 * ct2;
+                    *(uint4 *)dst = make_uint4(TT::pack(dre[0], dim[0]), TT::pack(dre[1], dim[1]),
+                                               TT::pack(dre[2], dim[2]), TT::pack(dre[3], dim[3]));
+                }
+            SCHED_FENCE();
+            if (i + 1 < 4) load_tabA(i + 1);
+            SCHED_FENCE();
+        }
+    };
+
+    // ---- phase C of one pair: inverse stage 1 (n1 < 16) on this wave's 4 n3 planes; the results
+    // (real part -> row b, imaginary part -> row b+1) are returned packed, 4 planes per 8 bytes.
+    uint2 yo[2][2][4];                                    // [row of the pair][n2 tile][r]
+    auto phase_C = [&]() {
+        // one n2 tile of one plane: lane: n2 = 16 cn2 + c16; reg r: n1 = 4q + r
+        auto tile = [&](int i, int cn2, f32x4 &dre, f32x4 &dim) {
+            const uint32_t *src = rdC + i * BPN3 + 16 * cn2;
+            dre = zero4;
+            dim = zero4;
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) {
+                const uint32_t *s2 = src + 16 * ks * BPK1;
+                const uint4 x = make_uint4(s2[0], s2[BPK1], s2[2 * BPK1], s2[3 * BPK1]);
+                dre = TT::mfma(tab1i[ks][0], x, dre);
+                dim = TT::mfma(tab1i[ks][1], x, dim);
+            }
+        };
+#pragma unroll
+        for (int ip = 0; ip < 2; ++ip)
+#pragma unroll
+            for (int cn2 = 0; cn2 < 2; ++cn2) {
+                f32x4 are, aim, bre, bim;
+                SCHED_FENCE();
+                tile(2 * ip, cn2, are, aim);
+                tile(2 * ip + 1, cn2, bre, bim);
+                // the two planes are adjacent n3 -> one word
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const uint32_t wre = TT::pack(are[r], bre[r]);
+                    const uint32_t wim = TT::pack(aim[r], bim[r]);
+                    if (ip == 0) {
+                        yo[0][cn2][r].x = wre;
+                        yo[1][cn2][r].x = wim;
+                    } else {
+                        yo[0][cn2][r].y = wre;
+                        yo[1][cn2][r].y = wim;
+                    }
+                }
+                SCHED_FENCE();
+            }
+    };
+    auto store_y = [&](int t) {
+        const int h = t / npairs, pair = t - h * npairs;
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            const int b = 2 * pair + s;
+            uint16_t *row = y + ((size_t)(FULL ? b : min(b, B - 1)) * H + h) * N;
+#pragma unroll
+            for (int cn2 = 0; cn2 < 2; ++cn2)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int n = elem(cn2, r);
+                    if (FULL || (b < B && n < N)) *(uint2 *)(row + n) = yo[s][cn2][r];
+                }
+        }
+    };
+
+    // ---- phase B of one pair: per k1 plane (4 per wave): stage 3, k_f, inverse 3, twiddle,
+    // inverse 2, in place.  On entry tab3, kfR, twbR, tabB hold plane 0's tables.
+    auto phase_B = [&](int h) {
+        auto read_plane = [&](int i, uint4 (&x)[2][2]) {
+#pragma unroll
+            for (int ct2 = 0; ct2 < 2; ++ct2)
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks) {
+                    const uint32_t *src = (ks ? rdB1 : rdB0) + i * BPK1 + 16 * ct2;
+                    x[ct2][ks] = make_uint4(src[0], src[BPN3], src[2 * BPN3], src[3 * BPN3]);
+                }
+        };
+        uint4 x3[2][2];                                   // [k2 tile][K step = n3 tile]
+        read_plane(0, x3);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            uint4 x3i[2][2];                              // [k2 tile][K step = k3 tile], holds conj(A3 k_f)
+#pragma unroll
+            for (int ct2 = 0; ct2 < 2; ++ct2)
+#pragma unroll
+                for (int ct3 = 0; ct3 < 2; ++ct3) {
+                    f32x4 dre = zero4, dim = zero4;
+#pragma unroll
+                    for (int ks = 0; ks < 2; ++ks) {      // matrix is the A operand: rows k3, data columns k2
+                        dre = TT::mfma(tab3[ks][ct3][0], x3[ct2][ks], dre);
+                        dim = TT::mfma(tab3[ks][ct3][1], x3[ct2][ks], dim);
+                    }
+                    // lane: k2 = 16 ct2 + c16; reg r: k3 = 16 ct3 + 4q + r
+                    x3i[ct2][ct3] = TT::template ctw4<true>(dre, dim, kfR[ct2][ct3]);
+                }
+            SCHED_FENCE();
+            if (i + 1 < 4) {
+                load_kf(i + 1, h);
+                read_plane(i + 1, x3);                    // its latency hides behind the rest of this plane
+            }
+            SCHED_FENCE();
+            uint4 x2i[2][2];                              // [n3 tile][K step = k2 tile]
+#pragma unroll
+            for (int ct2 = 0; ct2 < 2; ++ct2)
+#pragma unroll
+                for (int cn3 = 0; cn3 < 2; ++cn3) {
+                    f32x4 dre = zero4, dim = zero4;
+#pragma unroll
+                    for (int ks = 0; ks < 2; ++ks) {      // data rows k2, the forward matrix as the B operand
+                        dre = TT::mfma(x3i[ct2][ks], tab3[ks][cn3][0], dre);
+                        dim = TT::mfma(x3i[ct2][ks], tab3[ks][cn3][1], dim);
+                    }
+                    // = conj of the inverse transform.  lane: n3 = 16 cn3 + c16; reg r: k2 = 16 ct2 + 4q + r
+                    x2i[cn3][ct2] = TT::template ctw4<true>(dre, dim, twbR[ct2][cn3]);
+                }
+            SCHED_FENCE();
+            if (i + 1 < 4) load_twb(i + 1);
+            SCHED_FENCE();
+#pragma unroll
+            for (int cn3 = 0; cn3 < 2; ++cn3)
+#pragma unroll
+                for (int cn2 = 0; cn2 < 2; ++cn2) {
+                    f32x4 dre = zero4, dim = zero4;
+#pragma unroll
+                    for (int ks = 0; ks < 2; ++ks) {      // matrix as the A operand: rows n2, data columns n3
+                        dre = TT::mfma(tabB[ks][cn2][0], x2i[cn3][ks], dre);
+                        dim = TT::mfma(tabB[ks][cn2][1], x2i[cn3][ks], dim);
+                    }
+                    // lane: n3 = 16 cn3 + c16; reg r: n2 = 16 cn2 + 4q + r -> one 16-byte write
+                    uint32_t *dst = (cn3 ? wrB1 : wrB0) + i * BPK1 + 16 * cn2;
+                    *(uint4 *)dst = make_uint4(TT::pack(dre[0], dim[0]), TT::pack(dre[1], dim[1]),
+                                               TT::pack(dre[2], dim[2]), TT::pack(dre[3], dim[3]));
+                }
+            SCHED_FENCE();
+            if (i + 1 < 4) load_tabB(i + 1);
+            SCHED_FENCE();
+        }
+    };
+
+    // ---- prologue: phase A of the first pair
+    opaque();
+    issue_pre(t0);
+    load_fixed_outer();
+    load_tabA(0);
+    load_twa(0);
+    phase_A();
+    SCHED_FENCE();
+    load_tab3();
+    load_kf(0, t0 / npairs);
+    load_twb(0);
+    load_tabB(0);
+    SCHED_FENCE();
+    __syncthreads();
+
+    for (int t = t0; t < t1; ++t) {
+        opaque();
+        // Past the end of the range the last pair is prepared once more (in range, never used):
+        // the loop body stays free of branches.
+        const int tn = t + 1 < t1 ? t + 1 : t;
+        phase_B(t / npairs);
+        SCHED_FENCE();
+        // tables of the next phase and the next pair's input: in flight across the barrier and phase C
+        load_fixed_outer();
+        load_tabA(0);
+        load_twa(0);
+        issue_pre(tn);
+        SCHED_FENCE();
+        __syncthreads();
+        phase_C();
+        phase_A();
+        SCHED_FENCE();
+        load_tab3();
+        load_kf(0, tn / npairs);
+        load_twb(0);
+        load_tabB(0);
+        SCHED_FENCE();
+        // the stores go last: loads and stores retire through one counter on this target, and
+        // nothing issued after them is waited for before the next barrier
+        store_y(t);
+        __syncthreads();
+    }
+}
+
+// k_f in the kernel's per-lane order: [h][k1][k2 tile][k3 tile][r][lane]; the lane holds
+// k2 = 16 tile + lane%16 and k3 = 16 tile + 4 (lane/16) + r.  Scaled by 1/M.
+template <typename TT>
+__global__ void k_pack_big(const double2 *spec, typename TT::CW *kf, FacList fl, int64_t h0, int64_t nh,
+                           const uint8_t *keep, int64_t n_blocks)
+{
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= nh * BM) return;
+    const int64_t h = idx / BM, f = idx % BM;
+    const int k1 = (int)(f % 32), k2 = (int)((f / 32) % 32), k3 = (int)(f / 1024);
+    const int lane = ((k3 % 16) / 4) * 16 + (k2 % 16), r = k3 % 4;
+    const int64_t dst = ((((int64_t)k1 * 2 + k2 / 16) * 2 + k3 / 16) * 4 + r) * 64 + lane;
+    const double2 v = spec[h * BM + freq_to_pos(f, fl, BM)];
+    const double sc = mask_weight(keep, n_blocks, f, BM) / (double)BM;
+    const uint32_t pr = TT::pack((float)(v.x * sc), (float)(v.y * sc));      // (re, im) 16-bit pair
+    kf[(h0 + h) * BM + dst] = TT::cconst(pr & 0xffffu, pr >> 16, true);       // the kernel forms conj(A3 * k_f)
+}
+
+// ---------------------------------------------------------------- host side
+
+uint16_t h_bf16(double x)
+{
+    float f = (float)x;
+    uint32_t b;
+    std::memcpy(&b, &f, 4);
+    b += 0x7fffu + ((b >> 16) & 1u);          // round to nearest even (finite inputs only)
+    return (uint16_t)(b >> 16);
+}
+uint16_t h_f16(double x)
+{
+    _Float16 hv = (_Float16)(float)x;
+    uint16_t b;
+    std::memcpy(&b, &hv, 2);
+    return b;
+}
+struct Cx { double re, im; };
+Cx wp(int64_t M, int64_t e)                   // exp(-2 pi i e / M)
+{
+    const double two_pi = 6.283185307179586476925286766559;
+    e %= M;
+    if (e < 0) e += M;
+    const double a = two_pi * (double)e / (double)M;
+    return {std::cos(a), -std::sin(a)};
+}
+Cx cm(Cx a, Cx b) { return {a.re * b.re - a.im * b.im, a.re * b.im + a.im * b.re}; }
+Cx cj(Cx a) { return {a.re, -a.im}; }
+
+// One MFMA operand (64 lanes x 8 16-bit slots) of the real form of a complex matrix G: lane
+// (c16, q), slot 2r+s multiplies data element e_in = 16 t + 4 q + r, part s (0 = re, 1 = im), and
+// contributes to output element e_out = 16 ct + c16, part `part`.
+template <typename Fn> void fill_op(uint16_t *dst, bool f16, int t, int ct, int part, Fn G)
+{
+    for (int lane = 0; lane < 64; ++lane) {
+        const int c16 = lane % 16, q = lane / 16;
+        for (int r = 0; r < 4; ++r) {
+            const Cx g = G(16 * t + 4 * q + r, 16 * ct + c16);
+            const double v0 = part == 0 ? g.re : g.im;
+            const double v1 = part == 0 ? -g.im : g.re;
+            dst[lane * 8 + 2 * r + 0] = f16 ? h_f16(v0) : h_bf16(v0);
+            dst[lane * 8 + 2 * r + 1] = f16 ? h_f16(v1) : h_bf16(v1);
+        }
+    }
+}
+
+template <typename CW> BigConsts<CW> big_consts_at(const void *base)
+{
+    BigConsts<CW> c;
+    const uint4 *b = (const uint4 *)base;
+    c.tab1 = b;
+    c.tab1i = c.tab1 + 4 * 64;
+    c.tab3 = c.tab1i + 4 * 64;
+    c.tab2 = c.tab3 + 8 * 64;
+    c.tab2i = c.tab2 + 32 * 8 * 64;
+    c.twa = (const CW *)(c.tab2i + 32 * 8 * 64);
+    c.twb = c.twa + BM;
+    return c;
+}
+
+template <typename TT, bool FULL>
+int launch_big(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, hipStream_t s)
+{
+    using CW = typename TT::CW;
+    auto kern = k_fused3_big<TT, FULL>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        FC_HIP(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)BIG_LDS_BYTES));
+        attr_set = true;
+    }
+    const int64_t T = p->H * ((B + 1) / 2);
+    if (T >= ((int64_t)1 << 31) - 8) {
+        set_error("fftconv_forward: H * ceil(B/2) = %lld work items exceed the fused kernel's limit", (long long)T);
+        return FFTCONV_EUNSUPPORTED;
+    }
+    const int grid = (int)(T < p->f3.num_cu ? T : p->f3.num_cu);
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NT), BIG_LDS_BYTES, s, (const uint16_t *)u, (uint16_t *)y,
+                       (const CW *)kf, big_consts_at<CW>(p->f3.consts), (int)B, (int)p->H, (int)p->N);
+    FC_HIP(hipGetLastError());
+    return FFTCONV_OK;
+}
+
+}  // namespace
+
+int fused3_big_init(fftconv_plan *p)
+{
+    const bool f16 = p->dtype == FFTCONV_F16;
+    const int64_t M = BM;
+    std::vector<uint16_t> ops(BIG_U4 * 8);
+    size_t o = 0;
+    auto next = [&]() { uint16_t *d = ops.data() + o * 8; o += 64; return d; };
+    for (int ct = 0; ct < 2; ++ct)                        // tab1: K step 0 only (n1 < 16)
+        for (int part = 0; part < 2; ++part)
+            fill_op(next(), f16, 0, ct, part, [&](int n1, int k1) { return wp(32, (int64_t)n1 * k1); });
+    for (int ks = 0; ks < 2; ++ks)                        // tab1i: row tile 0 only (n1 < 16)
+        for (int part = 0; part < 2; ++part)
+            fill_op(next(), f16, ks, 0, part, [&](int k1, int n1) { return cj(wp(32, (int64_t)n1 * k1)); });
+    for (int ks = 0; ks < 2; ++ks)                        // tab3 (forward; also serves the inverse, see the kernel)
+        for (int ct = 0; ct < 2; ++ct)
+            for (int part = 0; part < 2; ++part)
+                fill_op(next(), f16, ks, ct, part, [&](int n3, int k3) { return wp(32, (int64_t)n3 * k3); });
+    for (int n3 = 0; n3 < 32; ++n3)                       // tab2
+        for (int ks = 0; ks < 2; ++ks)
+            for (int ct = 0; ct < 2; ++ct)
+                for (int part = 0; part < 2; ++part)
+                    fill_op(next(), f16, ks, ct, part, [&](int n2, int k2) {
+                        return cm(wp(32, (int64_t)n2 * k2), wp(1024, (int64_t)k2 * n3));
+                    });
+    for (int k1 = 0; k1 < 32; ++k1)                       // tab2i
+        for (int ks = 0; ks < 2; ++ks)
+            for (int ct = 0; ct < 2; ++ct)
+                for (int part = 0; part < 2; ++part)
+                    fill_op(next(), f16, ks, ct, part, [&](int k2, int n2) {
+                        return cj(cm(wp(32, (int64_t)n2 * k2), wp(1024, (int64_t)k1 * n2)));
+                    });
+    if (o != BIG_U4) {
+        set_error("fused3 (32768): operand table size mismatch");
+        return FFTCONV_EINVAL;
+    }
+    // twiddles as 16-bit constants in the form TT::ctw4 expects
+    const size_t cw = f16 ? 4 : 8;
+    std::vector<uint32_t> tw((size_t)2 * BM * (cw / 4));
+    auto put = [&](size_t idx, Cx v, bool conj) {
+        const uint32_t re = f16 ? h_f16(v.re) : h_bf16(v.re), im = f16 ? h_f16(v.im) : h_bf16(v.im);
+        if (f16) {
+            tw[idx] = H16::cconst(re, im, conj);
+        } else {
+            const uint2 c = B16::cconst(re, im, conj);
+            tw[2 * idx] = c.x;
+            tw[2 * idx + 1] = c.y;
+        }
+    };
+    size_t e = 0;
+    for (int n3 = 0; n3 < 32; ++n3)                       // twa: k1 = 16 ct + c16, n2 = 16 rt + 4 q + r
+        for (int rt = 0; rt < 2; ++rt)
+            for (int ct = 0; ct < 2; ++ct)
+                for (int r = 0; r < 4; ++r)
+                    for (int lane = 0; lane < 64; ++lane) {
+                        const int k1 = 16 * ct + lane % 16, n2 = 16 * rt + 4 * (lane / 16) + r;
+                        put(e++, wp(M, (int64_t)k1 * (32 * n2 + n3)), false);
+                    }
+    for (int k1 = 0; k1 < 32; ++k1)                       // twb: n3 = 16 ct3 + c16, k2 = 16 ct2 + 4 q + r
+        for (int ct2 = 0; ct2 < 2; ++ct2)
+            for (int ct3 = 0; ct3 < 2; ++ct3)
+                for (int r = 0; r < 4; ++r)
+                    for (int lane = 0; lane < 64; ++lane) {
+                        const int n3 = 16 * ct3 + lane % 16, k2 = 16 * ct2 + 4 * (lane / 16) + r;
+                        put(e++, wp(M, ((int64_t)k1 + 32 * (int64_t)k2) * n3), true);
+                    }
+    const size_t bytes = BIG_U4 * 16 + tw.size() * 4;
+    FC_HIP(hipMalloc(&p->f3.consts, bytes));
+    p->f3.consts_bytes += bytes;
+    FC_HIP(hipMemcpy(p->f3.consts, ops.data(), BIG_U4 * 16, hipMemcpyHostToDevice));
+    FC_HIP(hipMemcpy((char *)p->f3.consts + BIG_U4 * 16, tw.data(), tw.size() * 4, hipMemcpyHostToDevice));
+    return FFTCONV_OK;
+}
+
+size_t fused3_big_kf_bytes(const fftconv_plan *p)
+{
+    return (size_t)(p->H * BM) * (p->dtype == FFTCONV_F16 ? sizeof(uint32_t) : sizeof(uint2));
+}
+
+int fused3_big_pack_kf(const fftconv_plan *p, const double2 *spec, int64_t h0, int64_t nh, const uint8_t *keep_dev,
+                       int64_t n_blocks, void *kf, hipStream_t s)
+{
+    const int bs = 256;
+    const unsigned grid = (unsigned)((nh * BM + bs - 1) / bs);
+    if (p->dtype == FFTCONV_F16)
+        hipLaunchKernelGGL(k_pack_big<H16>, dim3(grid), dim3(bs), 0, s, spec, (uint32_t *)kf, staged_fac_list(p), h0, nh,
+                           keep_dev, n_blocks);
+    else
+        hipLaunchKernelGGL(k_pack_big<B16>, dim3(grid), dim3(bs), 0, s, spec, (uint2 *)kf, staged_fac_list(p), h0, nh,
+                           keep_dev, n_blocks);
+    FC_HIP(hipGetLastError());
+    return FFTCONV_OK;
+}
+
+int fused3_big_forward(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, hipStream_t s)
+{
+    if (((uintptr_t)u | (uintptr_t)y) & 7) {
+        set_error("fftconv_forward: u and y must be 8-byte aligned for this plan");
+        return FFTCONV_EINVAL;
+    }
+    const bool full = (B % 2 == 0) && p->N == BM / 2;
+    if (p->dtype == FFTCONV_F16)
+        return full ? launch_big<H16, true>(p, u, kf, y, B, s) : launch_big<H16, false>(p, u, kf, y, B, s);
+    return full ? launch_big<B16, true>(p, u, kf, y, B, s) : launch_big<B16, false>(p, u, kf, y, B, s);
+}
+
+}  // namespace f3
+}  // namespace fftconv

@@ -112,6 +112,24 @@ def test_fused3_fft16384(dtype, B, H, N):
     assert err <= TOL[dtype]
 
 
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("B,H,N", [
+    (2, 1, 16384),      # one pair, one channel
+    (3, 2, 16384),      # odd batch: the last pair has no partner row
+    (8, 3, 16384),      # several pairs per channel, several channels per workgroup range
+    (1, 2, 16384),      # B = 1
+    (4, 2, 8192),       # N < fft_size/2
+    (2, 2, 10000),      # ragged N (multiple of 8)
+])
+def test_fused3_fft32768(dtype, B, H, N):
+    w = synth.scaled(W["cfg3"], B=B, H=H, N=N, fft_size=32768, dtype=dtype)
+    err, plan = check_all_sequences(w)
+    print("fused 32768 %s B=%d H=%d N=%d path=%s factors=%s err=%.3e" % (dtype, B, H, N, plan.path, plan.factors, err),
+          flush=True)
+    assert plan.path == "fused3" and plan.factors == [32, 32, 32]
+    assert err <= TOL[dtype]
+
+
 def test_cfg5_variants_reduced_batch():
     """Partial and frequency-sparse filters on fft 16384 (reduced B, H), dense and skipping entry points."""
     wa = synth.scaled(W["cfg5a"], B=4, H=3)
@@ -127,9 +145,9 @@ def test_cfg5_variants_reduced_batch():
 
 @pytest.mark.parametrize("dtype", ["bf16", "f16"])
 @pytest.mark.parametrize("B,H,N,M", [
-    (3, 2, 16384, 32768),      # outer length 4, odd batch
-    (2, 2, 32768, 65536),      # outer length 8
-    (1, 1, 10000, 32768),      # ragged N, B = 1
+    (3, 2, 32768, 65536),      # outer length 8, odd batch
+    (2, 1, 65536, 131072),     # outer length 16
+    (1, 1, 20000, 65536),      # ragged N, B = 1
 ])
 def test_multipass_all_outputs(dtype, B, H, N, M):
     w = synth.scaled(W["cfg3"], B=B, H=H, N=N, fft_size=M, dtype=dtype)
