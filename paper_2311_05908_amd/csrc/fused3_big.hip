@@ -6,10 +6,9 @@
 //
 // What this size changes:
 //  * The exchange buffer X(k1,k2,n3) of one pair is 128 KiB of 16-bit (re, im) pairs: it is the only
-//    thing in LDS.  There is no staging buffer for u and y; every wave owns four adjacent n3
-//    planes, so a lane moves the 4 x 16-bit values it needs as one 8-byte global access
-//    (rows of 64 bytes are completed by the 8 waves of the workgroup, through the L1/L2 caches).
-//    The input of the next pair is prefetched into registers in MFMA-operand order.
+//    thing in LDS.  u and y are staged through it while it is free (between the last read of one
+//    pair and the first write of the next), so HBM sees 16-byte chunks in memory order; the input
+//    of the next pair waits in registers until then.
 //  * The per-plane constant tables (stage-2 matrices with folded twiddles, elementwise twiddles,
 //    k_f) do not fit in registers: they are streamed from L2, each one plane ahead of its use.
 //    Twiddles and k_f are 16-bit (re, im) constants for packed arithmetic (fp16: 4 bytes per
@@ -19,8 +18,8 @@
 //    transform, and the following twiddle product conjugates back.  Both conjugations are free
 //    (instruction modifiers for fp16, sign pattern of the constants for bf16), and 32 registers
 //    of matrix are saved.
-//  * Schedule per pair, 2 workgroup barriers: [phase B] | [phase C of this pair, then phase A of
-//    the next one: a wave reads and rewrites only its own n3 planes, so no barrier in between].
+//  * Schedule per pair, 5 workgroup barriers: [phase B] | [phase C into registers] | [y and the next
+//    u into the staging areas] | [staging into registers] | [phase A of the next pair, store y].
 #include <cmath>
 #include <cstring>
 #include <vector>
@@ -114,12 +113,16 @@ __global__ void __launch_bounds__(NT) k_fused3_big(const uint16_t *__restrict__ 
     extern __shared__ uint32_t XB[];
     const int tid = threadIdx.x, l = tid & 63, q = l >> 4, c16 = l & 15;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    // persistent workgroup: a contiguous range of work items t = h * npairs + pair
+    // Persistent workgroup; a work item t = h * npairs + pair.  Workgroups are dealt to the 8
+    // accelerator dies (each with its own L2) round-robin, so die x = blockIdx % 8 takes the
+    // channels h = x mod 8 and its workgroups walk through them side by side: at any time the
+    // workgroups of a die share a few channels, whose k_f then stays in that die's L2.
     const int npairs = (B + 1) / 2;
-    const long long T = (long long)H * npairs;
-    const int t0 = (int)(T * blockIdx.x / gridDim.x);
-    const int t1 = (int)(T * (blockIdx.x + 1) / gridDim.x);
-    if (t0 >= t1) return;
+    const int nx = gridDim.x % 8 == 0 ? 8 : 1;                    // dies the grid is spread over
+    const int x = blockIdx.x % nx, nb = gridDim.x / nx, jb = blockIdx.x / nx;
+    const int n_local = ((H - x + nx - 1) / nx) * npairs;         // work items of this die
+    if (jb >= n_local) return;
+    auto item = [&](int v) { return ((v / npairs) * nx + x) * npairs + v % npairs; };
     const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
 
     // LDS base addresses of this lane, chosen so that every access below is base + a small constant
@@ -133,7 +136,8 @@ __global__ void __launch_bounds__(NT) k_fused3_big(const uint16_t *__restrict__ 
     uint4 tab1[2][2], tab1i[2][2], tab3[2][2][2];
     uint4 tabA[2][2][2], tabB[2][2][2];          // stage-2 / inverse stage-2 matrices of the current plane
     CW twaR[2][2][4], twbR[2][2][4], kfR[2][2][4];
-    uint2 pre[2][2][4];                           // next pair's input: [row of the pair][n2 tile][r], 4 n3 planes each
+    uint4 pre[8];                                 // next pair's input, 16-byte chunks in memory order
+    uint2 x1r[2][2][4];                           // the same in operand order: [row of the pair][n2 tile][r], 4 n3 planes each
 
     // The tables are loop invariant but must be re-read for every work item (they do not fit in
     // registers): an opaque zero added to the lane offset keeps the loads inside the loop.
@@ -208,28 +212,58 @@ __global__ void __launch_bounds__(NT) k_fused3_big(const uint16_t *__restrict__ 
                 for (int r = 0; r < 4; ++r)
                     kfR[a][b][r] = (kf + (size_t)h * BM + (((c * 2 + a) * 2 + b) * 4 + r) * 64)[lz];
     };
-    // element offset inside a row of u / y of this lane's 4-plane group: n1 = 4q + r, n2 = 16 tile + c16, n3 = 4w
-    auto elem = [&](int tile, int r) { return (4 * q + r) * 1024 + (16 * tile + c16) * 32 + 4 * w; };
+    // Input and output pass through LDS so that HBM sees whole 16-byte chunks in memory order
+    // (8-byte pieces of a 64-byte row written by 8 different waves cost partial-line fills and
+    // write-backs).  Between phase C and phase A the exchange buffer is free: its bytes
+    // [0, SB_BYTES) stage y of this pair, [SB_BYTES, 2 SB_BYTES) stage u of the next one, both as
+    // (row of the pair, n1 < 16, n2) rows of 32 n3 values, 72 bytes apart (conflict-free 8-byte
+    // accesses in operand order, 8-byte aligned 16-byte chunks in memory order).
+    constexpr int SB_ROW = 72, SB_BYTES = 2 * 16 * 32 * SB_ROW;
+    static_assert(2 * SB_BYTES <= (int)BIG_LDS_BYTES, "staging areas must fit in the exchange buffer");
+    char *const YS = (char *)XB, *const US = (char *)XB + SB_BYTES;
+    // chunk j of this thread: g = tid + 512 j -> row of the pair g / 2048, elements [8 (g % 2048), +8)
     auto issue_pre = [&](int t) {
         const int h = t / npairs, pair = t - h * npairs;
 #pragma unroll
-        for (int s = 0; s < 2; ++s) {
+        for (int j = 0; j < 8; ++j) {
+            const int s = j / 4;                              // wave-uniform: 4 chunks per thread and row
+            const int n = (tid + NT * (j % 4)) * 8;
             const int b = 2 * pair + s;
             const uint16_t *row = u + ((size_t)(FULL ? b : min(b, B - 1)) * H + h) * N;
+            if constexpr (FULL) {
+                pre[j] = *(const uint4 *)(row + n);
+            } else {
+                uint4 v = make_uint4(0, 0, 0, 0);
+                if (b < B && n < N) v = *(const uint4 *)(row + n);
+                pre[j] = v;
+            }
+        }
+    };
+    // byte offset of chunk j inside a staging area
+    auto chunk_ofs = [&](int j) {
+        const int s = j / 4;
+        const int n = (tid + NT * (j % 4)) * 8;               // n = (n1*32 + n2)*32 + n3, n3 in {0, 8, 16, 24}
+        return (s * 512 + n / 32) * SB_ROW + (n % 32) * 2;
+    };
+    // byte offset of this lane's operand-order piece: n1 = 4q + r, n2 = 16 tile + c16, n3 = 4w .. 4w+3
+    auto piece_ofs = [&](int s, int tile, int r) {
+        return ((s * 16 + 4 * q + r) * 32 + 16 * tile + c16) * SB_ROW + 8 * w;
+    };
+    auto stage_in = [&]() {                                   // pre -> US
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            uint2 *dst = (uint2 *)(US + chunk_ofs(j));
+            dst[0] = make_uint2(pre[j].x, pre[j].y);
+            dst[1] = make_uint2(pre[j].z, pre[j].w);
+        }
+    };
+    auto read_x1 = [&]() {                                    // US -> operand order
+#pragma unroll
+        for (int s = 0; s < 2; ++s)
 #pragma unroll
             for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int n = elem(rt, r);
-                    if constexpr (FULL) {
-                        pre[s][rt][r] = *(const uint2 *)(row + n);
-                    } else {
-                        uint2 v = make_uint2(0, 0);
-                        if (b < B && n < N) v = *(const uint2 *)(row + n);
-                        pre[s][rt][r] = v;
-                    }
-                }
-        }
+                for (int r = 0; r < 4; ++r) x1r[s][rt][r] = *(const uint2 *)(US + piece_ofs(s, rt, r));
     };
 
     // ---- phase A of one pair: stage 1, twiddle, stage 2 -> XB (this wave's 4 n3 planes).
@@ -245,8 +279,8 @@ __global__ void __launch_bounds__(NT) k_fused3_big(const uint16_t *__restrict__ 
                 uint32_t d[4];
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    const uint32_t lo = i < 2 ? pre[0][rt][r].x : pre[0][rt][r].y;
-                    const uint32_t hi = i < 2 ? pre[1][rt][r].x : pre[1][rt][r].y;
+                    const uint32_t lo = i < 2 ? x1r[0][rt][r].x : x1r[0][rt][r].y;
+                    const uint32_t hi = i < 2 ? x1r[1][rt][r].x : x1r[1][rt][r].y;
                     d[r] = __builtin_amdgcn_perm(hi, lo, sel);
                 }
                 const uint4 x1 = make_uint4(d[0], d[1], d[2], d[3]);
@@ -323,19 +357,32 @@ __global__ void __launch_bounds__(NT) k_fused3_big(const uint16_t *__restrict__ 
                 SCHED_FENCE();
             }
     };
-    auto store_y = [&](int t) {
-        const int h = t / npairs, pair = t - h * npairs;
+    uint4 yc[8];                                          // y of this pair, 16-byte chunks in memory order
+    auto stage_out = [&]() {                              // yo -> YS
 #pragma unroll
-        for (int s = 0; s < 2; ++s) {
-            const int b = 2 * pair + s;
-            uint16_t *row = y + ((size_t)(FULL ? b : min(b, B - 1)) * H + h) * N;
+        for (int s = 0; s < 2; ++s)
 #pragma unroll
             for (int cn2 = 0; cn2 < 2; ++cn2)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int n = elem(cn2, r);
-                    if (FULL || (b < B && n < N)) *(uint2 *)(row + n) = yo[s][cn2][r];
-                }
+                for (int r = 0; r < 4; ++r) *(uint2 *)(YS + piece_ofs(s, cn2, r)) = yo[s][cn2][r];
+    };
+    auto read_y = [&]() {                                 // YS -> memory order
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const uint2 *src = (const uint2 *)(YS + chunk_ofs(j));
+            const uint2 a = src[0], b = src[1];
+            yc[j] = make_uint4(a.x, a.y, b.x, b.y);
+        }
+    };
+    auto store_y = [&](int t) {
+        const int h = t / npairs, pair = t - h * npairs;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int s = j / 4;
+            const int n = (tid + NT * (j % 4)) * 8;
+            const int b = 2 * pair + s;
+            uint16_t *row = y + ((size_t)(FULL ? b : min(b, B - 1)) * H + h) * N;
+            if (FULL || (b < B && n < N)) *(uint4 *)(row + n) = yc[j];
         }
     };
 
@@ -415,24 +462,30 @@ __global__ void __launch_bounds__(NT) k_fused3_big(const uint16_t *__restrict__ 
 
     // ---- prologue: phase A of the first pair
     opaque();
-    issue_pre(t0);
+    issue_pre(item(jb));
     load_fixed_outer();
     load_tabA(0);
     load_twa(0);
+    stage_in();
+    __syncthreads();
+    read_x1();
+    __syncthreads();
     phase_A();
     SCHED_FENCE();
     load_tab3();
-    load_kf(0, t0 / npairs);
+    load_kf(0, item(jb) / npairs);
     load_twb(0);
     load_tabB(0);
     SCHED_FENCE();
     __syncthreads();
 
-    for (int t = t0; t < t1; ++t) {
+    // Per pair, 5 workgroup barriers:
+    //   [B(t)] | [C(t) -> registers] | [y(t), u(t+1) -> staging] | [staging -> registers] | [A(t+1); store y(t)] |
+    for (int v = jb; v < n_local; v += nb) {
         opaque();
         // Past the end of the range the last pair is prepared once more (in range, never used):
         // the loop body stays free of branches.
-        const int tn = t + 1 < t1 ? t + 1 : t;
+        const int t = item(v), tn = v + nb < n_local ? item(v + nb) : t;
         phase_B(t / npairs);
         SCHED_FENCE();
         // tables of the next phase and the next pair's input: in flight across the barrier and phase C
@@ -443,6 +496,13 @@ __global__ void __launch_bounds__(NT) k_fused3_big(const uint16_t *__restrict__ 
         SCHED_FENCE();
         __syncthreads();
         phase_C();
+        __syncthreads();                                  // every wave has read its planes: the buffer is free
+        stage_out();
+        stage_in();
+        __syncthreads();
+        read_y();
+        read_x1();
+        __syncthreads();                                  // staging consumed: phase A may overwrite it
         phase_A();
         SCHED_FENCE();
         load_tab3();
@@ -550,7 +610,9 @@ int launch_big(const fftconv_plan *p, const void *u, const void *kf, void *y, in
         set_error("fftconv_forward: H * ceil(B/2) = %lld work items exceed the fused kernel's limit", (long long)T);
         return FFTCONV_EUNSUPPORTED;
     }
-    const int grid = (int)(T < p->f3.num_cu ? T : p->f3.num_cu);
+    // one persistent workgroup per compute unit, a multiple of 8 (see the kernel's work split)
+    int grid = (int)(T < p->f3.num_cu ? T : p->f3.num_cu);
+    if (grid >= 8) grid -= grid % 8;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NT), BIG_LDS_BYTES, s, (const uint16_t *)u, (uint16_t *)y,
                        (const CW *)kf, big_consts_at<CW>(p->f3.consts), (int)B, (int)p->H, (int)p->N);
     FC_HIP(hipGetLastError());
@@ -654,8 +716,8 @@ int fused3_big_pack_kf(const fftconv_plan *p, const double2 *spec, int64_t h0, i
 
 int fused3_big_forward(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, hipStream_t s)
 {
-    if (((uintptr_t)u | (uintptr_t)y) & 7) {
-        set_error("fftconv_forward: u and y must be 8-byte aligned for this plan");
+    if (((uintptr_t)u | (uintptr_t)y) & 15) {
+        set_error("fftconv_forward: u and y must be 16-byte aligned for this plan");
         return FFTCONV_EINVAL;
     }
     const bool full = (B % 2 == 0) && p->N == BM / 2;
