@@ -21,10 +21,29 @@
 //  * Schedule per pair, 5 workgroup barriers: [phase B] | [phase C into registers] | [y and the next
 //    u into the staging areas] | [staging into registers] | [phase A of the next pair, store y].
 #include <cmath>
+#include <cstdlib>
 #include <cstring>
 #include <vector>
 
 #include "fused3_common.h"
+
+#ifdef FUSED3_PROBE
+// development build only: time stamps of one workgroup, read back with fftconv_debug_stamps_big()
+__device__ unsigned long long g_stamps_big[8 * 8 * 16];
+#define BSTAMP(k)                                                                                 \
+    do {                                                                                          \
+        if (blockIdx.x == 3 && l == 0 && it >= 4 && it < 12)                                      \
+            g_stamps_big[(w * 8 + (it - 4)) * 16 + (k)] = __builtin_amdgcn_s_memtime();           \
+    } while (0)
+extern "C" int fftconv_debug_stamps_big(unsigned long long *dst)
+{
+    return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(g_stamps_big), sizeof(g_stamps_big));
+}
+#define BPROBE(bit) (!(probe & (bit)))
+#else
+#define BSTAMP(k) do { } while (0)
+#define BPROBE(bit) true
+#endif
 
 namespace fftconv {
 namespace f3 {
@@ -107,7 +126,7 @@ constexpr size_t BIG_U4 = (size_t)(4 + 4 + 8 + 32 * 8 + 32 * 8) * 64;
 template <typename TT, bool FULL>
 __global__ void __launch_bounds__(NT) k_fused3_big(const uint16_t *__restrict__ u, uint16_t *__restrict__ y,
                                                   const typename TT::CW *__restrict__ kf, BigConsts<typename TT::CW> cs,
-                                                  int B, int H, int N)
+                                                  int B, int H, int N, int probe)
 {
     using CW = typename TT::CW;
     extern __shared__ uint32_t XB[];
@@ -293,7 +312,7 @@ __global__ void __launch_bounds__(NT) k_fused3_big(const uint16_t *__restrict__ 
                 }
             }
             SCHED_FENCE();
-            if (i + 1 < 4) load_twa(i + 1);
+            if (i + 1 < 4 && BPROBE(2)) load_twa(i + 1);
             SCHED_FENCE();
 #pragma unroll
             for (int ct = 0; ct < 2; ++ct)
@@ -311,7 +330,7 @@ __global__ void __launch_bounds__(NT) k_fused3_big(const uint16_t *__restrict__ 
                                                TT::pack(dre[2], dim[2]), TT::pack(dre[3], dim[3]));
                 }
             SCHED_FENCE();
-            if (i + 1 < 4) load_tabA(i + 1);
+            if (i + 1 < 4 && BPROBE(2)) load_tabA(i + 1);
             SCHED_FENCE();
         }
     };
@@ -418,7 +437,7 @@ __global__ void __launch_bounds__(NT) k_fused3_big(const uint16_t *__restrict__ 
                 }
             SCHED_FENCE();
             if (i + 1 < 4) {
-                load_kf(i + 1, h);
+                if (BPROBE(1)) load_kf(i + 1, h);
                 read_plane(i + 1, x3);                    // its latency hides behind the rest of this plane
             }
             SCHED_FENCE();
@@ -437,7 +456,7 @@ __global__ void __launch_bounds__(NT) k_fused3_big(const uint16_t *__restrict__ 
                     x2i[cn3][ct2] = TT::template ctw4<true>(dre, dim, twbR[ct2][cn3]);
                 }
             SCHED_FENCE();
-            if (i + 1 < 4) load_twb(i + 1);
+            if (i + 1 < 4 && BPROBE(1)) load_twb(i + 1);
             SCHED_FENCE();
 #pragma unroll
             for (int cn3 = 0; cn3 < 2; ++cn3)
@@ -455,7 +474,7 @@ __global__ void __launch_bounds__(NT) k_fused3_big(const uint16_t *__restrict__ 
                                                TT::pack(dre[2], dim[2]), TT::pack(dre[3], dim[3]));
                 }
             SCHED_FENCE();
-            if (i + 1 < 4) load_tabB(i + 1);
+            if (i + 1 < 4 && BPROBE(1)) load_tabB(i + 1);
             SCHED_FENCE();
         }
     };
@@ -467,9 +486,9 @@ __global__ void __launch_bounds__(NT) k_fused3_big(const uint16_t *__restrict__ 
     load_tabA(0);
     load_twa(0);
     stage_in();
-    __syncthreads();
+    lds_barrier();
     read_x1();
-    __syncthreads();
+    lds_barrier();
     phase_A();
     SCHED_FENCE();
     load_tab3();
@@ -477,34 +496,46 @@ __global__ void __launch_bounds__(NT) k_fused3_big(const uint16_t *__restrict__ 
     load_twb(0);
     load_tabB(0);
     SCHED_FENCE();
-    __syncthreads();
+    lds_barrier();
 
     // Per pair, 5 workgroup barriers:
     //   [B(t)] | [C(t) -> registers] | [y(t), u(t+1) -> staging] | [staging -> registers] | [A(t+1); store y(t)] |
+    [[maybe_unused]] int it = -1;
     for (int v = jb; v < n_local; v += nb) {
+        ++it;
+        BSTAMP(0);
         opaque();
         // Past the end of the range the last pair is prepared once more (in range, never used):
         // the loop body stays free of branches.
         const int t = item(v), tn = v + nb < n_local ? item(v + nb) : t;
         phase_B(t / npairs);
         SCHED_FENCE();
+        BSTAMP(1);
         // tables of the next phase and the next pair's input: in flight across the barrier and phase C
         load_fixed_outer();
         load_tabA(0);
         load_twa(0);
         issue_pre(tn);
         SCHED_FENCE();
-        __syncthreads();
+        lds_barrier();
+        BSTAMP(2);
         phase_C();
-        __syncthreads();                                  // every wave has read its planes: the buffer is free
+        BSTAMP(3);
+        lds_barrier();                                  // every wave has read its planes: the buffer is free
+        BSTAMP(4);
         stage_out();
         stage_in();
-        __syncthreads();
+        BSTAMP(5);
+        lds_barrier();
+        BSTAMP(6);
         read_y();
         read_x1();
-        __syncthreads();                                  // staging consumed: phase A may overwrite it
+        BSTAMP(7);
+        lds_barrier();                                  // staging consumed: phase A may overwrite it
+        BSTAMP(8);
         phase_A();
         SCHED_FENCE();
+        BSTAMP(9);
         load_tab3();
         load_kf(0, tn / npairs);
         load_twb(0);
@@ -513,7 +544,9 @@ __global__ void __launch_bounds__(NT) k_fused3_big(const uint16_t *__restrict__ 
         // the stores go last: loads and stores retire through one counter on this target, and
         // nothing issued after them is waited for before the next barrier
         store_y(t);
-        __syncthreads();
+        BSTAMP(10);
+        lds_barrier();
+        BSTAMP(11);
     }
 }
 
@@ -595,6 +628,16 @@ template <typename CW> BigConsts<CW> big_consts_at(const void *base)
     return c;
 }
 
+int big_probe()
+{
+#ifdef FUSED3_PROBE
+    const char *e = getenv("FUSED3_PROBE");
+    return e ? atoi(e) : 0;
+#else
+    return 0;
+#endif
+}
+
 template <typename TT, bool FULL>
 int launch_big(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, hipStream_t s)
 {
@@ -614,7 +657,7 @@ int launch_big(const fftconv_plan *p, const void *u, const void *kf, void *y, in
     int grid = (int)(T < p->f3.num_cu ? T : p->f3.num_cu);
     if (grid >= 8) grid -= grid % 8;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NT), BIG_LDS_BYTES, s, (const uint16_t *)u, (uint16_t *)y,
-                       (const CW *)kf, big_consts_at<CW>(p->f3.consts), (int)B, (int)p->H, (int)p->N);
+                       (const CW *)kf, big_consts_at<CW>(p->f3.consts), (int)B, (int)p->H, (int)p->N, big_probe());
     FC_HIP(hipGetLastError());
     return FFTCONV_OK;
 }

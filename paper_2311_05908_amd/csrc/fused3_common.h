@@ -92,6 +92,16 @@ struct F16 {
     static constexpr int CFMT = 2;
 };
 
+// Workgroup barrier for exchanges through LDS only.  __syncthreads() also waits for every
+// outstanding global load and store of the wave (its fence covers global memory), which would
+// throw away the prefetches and stores these kernels keep in flight across barriers.  LDS
+// operations of a wave complete in order, so once its LDS counter is zero its writes are visible
+// to, and its reads are finished before, whatever the other waves do after the barrier.
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 template <int N2, int N3> struct Geo {
     static constexpr int M = N1 * N2 * N3;
     static constexpr int R2 = N2 / 16, R3 = N3 / 16;

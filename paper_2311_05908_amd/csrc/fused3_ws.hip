@@ -165,7 +165,7 @@ __global__ void __launch_bounds__(NT) k_fused3_ws(const uint16_t *__restrict__ u
         // prologue: item t0 staged; item t0+1 is fetched at the start of the first step
         issue_loads(t0);
         stage_in(UBb + (t0 & 1) * UBE);
-        __syncthreads();
+        lds_barrier();
 
         for (int s = t0 - 1; s <= t1 + 1; ++s) {
             const bool doC = WPROBE(1) && s - 1 >= t0 && s - 1 < t1;
@@ -263,7 +263,7 @@ __global__ void __launch_bounds__(NT) k_fused3_ws(const uint16_t *__restrict__ u
             STAMP(4);
             if (WPROBE(16) && s - 2 >= t0) store_out(s - 2, YBb + ((s - 2) & 1) * UBE);
             STAMP(5);
-            __syncthreads();
+            lds_barrier();
             STAMP(6);
         }
     } else {
@@ -284,7 +284,7 @@ __global__ void __launch_bounds__(NT) k_fused3_ws(const uint16_t *__restrict__ u
 #pragma unroll
             for (int r = 0; r < 4; ++r) twb[i][r] = cs.twb16[(c * 4 + r) * 64 + l];
         }
-        __syncthreads();                                          // pairs with the outer role's prologue barrier
+        lds_barrier();                                          // pairs with the outer role's prologue barrier
         int h_cur = -1;
         for (int s = t0 - 1; s <= t1 + 1; ++s) {
             STAMP(0);
@@ -331,7 +331,7 @@ __global__ void __launch_bounds__(NT) k_fused3_ws(const uint16_t *__restrict__ u
                 }
             }
             STAMP(5);
-            __syncthreads();
+            lds_barrier();
             STAMP(6);
         }
     }
