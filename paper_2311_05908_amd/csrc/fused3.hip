@@ -86,13 +86,34 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *u, uint16_t *y,
     uint32_t *UBC = (uint32_t *)UB, *YBC = (uint32_t *)YB;
 
     const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, q = l >> 4, c16 = l & 15;
-    // Persistent workgroup: a contiguous range [t0, t1) of work items t = h * npairs + pair, so the
-    // constant tables are loaded once and k_f[h] once per channel the range touches.
+    // Persistent workgroup; a work item t = h * npairs + pair.
+    //  REGC (k_f and tables in registers): a contiguous range of items, so k_f[h] is loaded once per
+    //  channel the range touches.
+    //  otherwise (k_f streamed from L2 for every item): workgroups are dealt to the 8 accelerator
+    //  dies round-robin, each die has its own L2; die x = blockIdx % 8 takes the channels
+    //  h = x mod 8 and its workgroups walk through them side by side, so that at any time a die
+    //  works on a few channels only and their k_f stays in its L2.
     const int npairs = CPLX ? B : (B + 1) / 2;
     const long long T = (long long)H * npairs;
-    const int t0 = (int)(T * blockIdx.x / gridDim.x);
-    const int t1 = (int)(T * (blockIdx.x + 1) / gridDim.x);
-    if (t0 >= t1) return;
+    const int nx = (!REGC && gridDim.x % 8 == 0) ? 8 : 1;
+    const int x = blockIdx.x % nx, nb = gridDim.x / nx, jb = blockIdx.x / nx;
+    int first, stride, cnt;                               // local item k is v = first + k * stride
+    if constexpr (REGC) {
+        const int t0 = (int)(T * blockIdx.x / gridDim.x), t1 = (int)(T * (blockIdx.x + 1) / gridDim.x);
+        first = t0;
+        stride = 1;
+        cnt = t1 - t0;
+    } else {
+        const int n_local = ((H - x + nx - 1) / nx) * npairs;
+        first = jb;
+        stride = nb;
+        cnt = jb < n_local ? (n_local - jb + nb - 1) / nb : 0;
+    }
+    if (cnt <= 0) return;
+    auto item = [&](int k) {
+        const int v = first + k * stride;
+        return REGC ? v : ((v / npairs) * nx + x) * npairs + v % npairs;
+    };
 
     // ---------------- constants (per-lane operand tables) ----------------
     uint4 tab1[KS1][2][2], tab1i[2][RT1][2], tab3[R3][R3][2], tab3i[R3][R3][2];
@@ -180,14 +201,15 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *u, uint16_t *y,
 
     // ---------------- input prefetch (registers) ----------------
     uint4 pre[NCH];
-    auto issue_loads = [&](int t) {
+    auto issue_loads = [&](int k) {
+        const int t = item(k < cnt ? k : cnt - 1);
         const int h = t / npairs, pair = t - h * npairs;
         if constexpr (CPLX) {
             const uint16_t *row = u + ((size_t)pair * H + h) * (size_t)(2 * G::M);
 #pragma unroll
             for (int j = 0; j < NCH; ++j) {
                 uint4 v = make_uint4(0, 0, 0, 0);
-                if (t < t1) v = *(const uint4 *)(row + (size_t)(tid + NT * j) * 8);
+                if (k < cnt) v = *(const uint4 *)(row + (size_t)(tid + NT * j) * 8);
                 pre[j] = v;
             }
         } else
@@ -198,7 +220,7 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *u, uint16_t *y,
             const int b = 2 * pair + s;
             uint4 v = make_uint4(0, 0, 0, 0);
             const uint16_t *row = u + ((size_t)b * H + h) * N;
-            if (PROBE_ON(8) && t < t1 && b < B && n < N) v = *(const uint4 *)(row + n);
+            if (PROBE_ON(8) && k < cnt && b < B && n < N) v = *(const uint4 *)(row + n);
             pre[j] = v;
         }
     };
@@ -229,7 +251,8 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *u, uint16_t *y,
         }
     };
     // YB -> y, 16 bytes per lane, coalesced
-    auto store_out = [&](int t) {
+    auto store_out = [&](int k) {
+        const int t = item(k);
         const int h = t / npairs, pair = t - h * npairs;
         if constexpr (CPLX) {
             uint16_t *row = y + ((size_t)pair * H + h) * (size_t)(2 * G::M);
@@ -258,17 +281,17 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *u, uint16_t *y,
     //   [A(t)] | [B(t) + store(t-1) + stage_in(t+1) + issue_loads(t+2)] | [C(t)] |
     // UB is read in A(t) and rewritten in B(t); YB is written in C(t) and read in B(t+1); XB planes
     // change owner only across barriers.
-    issue_loads(t0);
+    issue_loads(0);
     stage_in();
-    issue_loads(t0 + 1);
+    issue_loads(1);
     __syncthreads();
 
     const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
     int h_cur = -1;
-    for (int t = t0; t < t1; ++t) {
+    for (int k = 0; k < cnt; ++k) {
         opaque();
         {
-            const int h = t / npairs;
+            const int h = item(k) / npairs;
             if (h != h_cur) {                             // new channel: fetch its k_f (used in phase B)
                 h_cur = h;
                 if constexpr (REGC) {
@@ -372,8 +395,8 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *u, uint16_t *y,
             // (stage_in first: it waits for the prefetch, and on this target loads and stores
             //  retire through one counter, so it must not sit behind freshly issued stores)
             stage_in();
-            issue_loads(t + 2);
-            if (t > t0) store_out(t - 1);
+            issue_loads(k + 2);
+            if (k > 0) store_out(k - 1);
             if (PROBE_ON(2))
 #pragma unroll
             for (int i = 0; i < C1; ++i) {
@@ -492,7 +515,7 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *u, uint16_t *y,
         }
         __syncthreads();
     }
-    store_out(t1 - 1);
+    store_out(cnt - 1);
 }
 
 // k_f in the fused kernel's per-lane order: [h][k1][k2 tile][k3 tile][r][lane] float2, where the
@@ -699,8 +722,10 @@ int launch(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_
         set_error("fftconv_forward: H * ceil(B/2) = %lld work items exceed the fused kernel's 2^31 limit", (long long)T);
         return FFTCONV_EUNSUPPORTED;
     }
-    // one persistent workgroup per compute unit (fewer when there is less work than that)
-    const int grid = (int)(T < p->f3.num_cu ? T : p->f3.num_cu);
+    // one persistent workgroup per compute unit (fewer when there is less work than that); a
+    // multiple of 8 for the streamed-table kernels (see the kernel's work split)
+    int grid = (int)(T < p->f3.num_cu ? T : p->f3.num_cu);
+    if (!REGC && grid >= 8) grid -= grid % 8;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NT), lds, s, (const uint16_t *)u, (uint16_t *)y,
                        (const float2 *)kf, consts_of<N2, N3>(p), (int)B, (int)H, (int)N, probe_mask());
     FC_HIP(hipGetLastError());
