@@ -284,7 +284,7 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *u, uint16_t *y,
     issue_loads(0);
     stage_in();
     issue_loads(1);
-    __syncthreads();
+    lds_barrier();
 
     const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
     int h_cur = -1;
@@ -371,7 +371,7 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *u, uint16_t *y,
                     }
             }
         }
-        __syncthreads();
+        lds_barrier();
 
         // ================= phase B: per k1 = c: stage 3, k_f, inverse 3, twiddle, inverse 2 -> XB in place
         {
@@ -466,7 +466,7 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *u, uint16_t *y,
                     }
             }
         }
-        __syncthreads();
+        lds_barrier();
 
         // ================= phase C: per n3 = c: inverse stage 1 (n1 < 16; re -> row b, im -> row b+1) -> YB
         {
@@ -513,7 +513,7 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *u, uint16_t *y,
                     }
             }
         }
-        __syncthreads();
+        lds_barrier();
     }
     store_out(cnt - 1);
 }
