@@ -3,7 +3,8 @@
 Thin numpy front end of ``conv_oracle.c`` (plain C, term-by-term sums in
 double precision; see that file's header for the definitions it follows:
 paper Section 2.1 for the convolution, Eq. 1 for its circular form, Section
-3.3 / Appendix A.4 for partial and frequency-sparse filters).
+3.3 / Appendix A.4 for partial and frequency-sparse filters, Section 3.1 /
+4.1 for the gated form).
 
 Nothing in the product package may import this module; it shares no code with
 the HIP library.  Allowed callers: ``tests/``, ``__graft_entry__.smoke()`` and
@@ -124,6 +125,39 @@ def mask_filter(kext, keep) -> np.ndarray:
     if rc != 0:
         raise RuntimeError("oracle_mask_filter failed (%d)" % rc)
     return out
+
+
+def round_to(x, dtype: str) -> np.ndarray:
+    """Round fp64 values to the I/O dtype ("f32", "f16", "bf16"), nearest even, and return them as fp64.
+
+    bf16 is the upper half of fp32: round the fp32 bit pattern to 16 bits (finite inputs only).
+    """
+    x = np.asarray(x, dtype=np.float64)
+    if dtype == "f32":
+        return x.astype(np.float32).astype(np.float64)
+    if dtype == "f16":
+        return x.astype(np.float16).astype(np.float64)
+    if dtype == "bf16":
+        b = np.ascontiguousarray(x.astype(np.float32)).view(np.uint32).astype(np.uint64)
+        b = (b + 0x7FFF + ((b >> 16) & 1)) & 0xFFFF0000
+        return b.astype(np.uint32).view(np.float32).astype(np.float64)
+    raise ValueError("dtype must be f32, f16 or bf16")
+
+
+def fftconv_gated(u, w, v, kext, M: int | None = None, dtype: str = "f32") -> np.ndarray:
+    """Gated convolution y = v . ((u . w) * k) (Section 3.1, "Domain-Specific Optimizations"; Section 4.1).
+
+    u, w, v: (B,H,N), w and/or v may be None (no gate on that side).  The elementwise product u . w is
+    what the transform consumes, so it is rounded to the I/O dtype first (for 16-bit inputs the
+    product itself is exact in fp32); the convolution and the output gate are exact fp64.
+    """
+    p = _f64(u)
+    if w is not None:
+        p = round_to(p * _f64(w), dtype)
+    y = fftconv(p, kext, M)
+    if v is not None:
+        y = y * _f64(v)
+    return y
 
 
 def num_threads() -> int:

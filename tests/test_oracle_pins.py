@@ -227,3 +227,68 @@ def test_masked_filter_spectrum_is_the_hermitian_part_of_the_masked_spectrum():
     mirror = keep[(-np.arange(M)) % M]
     assert np.allclose(np.fft.fft(kt), K * (keep + mirror) / 2.0, atol=1e-11)
     assert (keep != mirror).sum() == 2    # the asymmetry the weight 1/2 is there for
+
+
+# ---------------------------------------------------------------- gated convolution (Section 3.1 / 4.1)
+
+def test_round_to_matches_library_casts_including_ties():
+    import torch
+    x = RNG.standard_normal(4096) * np.exp(RNG.uniform(-8, 8, 4096))
+    # exact ties of the bf16 grid: 1 + (2j+1) * 2^-8, and of the fp16 grid: 1 + (2j+1) * 2^-11
+    ties_b = 1.0 + (2 * np.arange(64) + 1) * 2.0 ** -8
+    ties_h = 1.0 + (2 * np.arange(64) + 1) * 2.0 ** -11
+    for vals in (x, ties_b, -ties_b, ties_h):
+        t = torch.from_numpy(vals.astype(np.float32))
+        assert np.array_equal(oracle.round_to(vals.astype(np.float32), "bf16"), t.to(torch.bfloat16).double().numpy())
+        assert np.array_equal(oracle.round_to(vals.astype(np.float32), "f16"), t.to(torch.float16).double().numpy())
+    assert np.array_equal(oracle.round_to(x, "f32"), x.astype(np.float32).astype(np.float64))
+
+
+def test_gated_with_unit_gates_is_the_plain_convolution():
+    u = RNG.standard_normal((2, 3, 20))
+    k = RNG.standard_normal((3, 20))
+    ones = np.ones_like(u)
+    ref = oracle.fftconv(u.astype(np.float32), k, 40)
+    for w, v in ((ones, ones), (None, ones), (ones, None), (None, None)):
+        assert np.allclose(oracle.fftconv_gated(u.astype(np.float32), w, v, k, 40, "f32"), ref, rtol=0, atol=1e-12)
+
+
+def test_gated_integer_inputs_are_exact():
+    B, H, N = 2, 2, 17
+    u = RNG.integers(-4, 5, (B, H, N)).astype(np.float64)
+    w = RNG.integers(-2, 3, (B, H, N)).astype(np.float64)
+    v = RNG.integers(-3, 4, (B, H, N)).astype(np.float64)
+    k = RNG.integers(-4, 5, (H, N)).astype(np.float64)
+    for dtype in ("f32", "f16", "bf16"):          # |u w| <= 8: exact in every dtype
+        y = oracle.fftconv_gated(u, w, v, k, 2 * N, dtype)
+        for b in range(B):
+            for h in range(H):
+                want = v[b, h] * np.convolve(u[b, h] * w[b, h], k[h])[:N]
+                assert np.array_equal(y[b, h], want)
+
+
+def test_gated_input_gate_as_a_window_and_output_gate_as_a_selector():
+    u = RNG.standard_normal((1, 2, 32)).astype(np.float32).astype(np.float64)
+    k = RNG.standard_normal((2, 32))
+    w = np.zeros_like(u)
+    w[..., :10] = 1.0
+    ut = u.copy()
+    ut[..., 10:] = 0.0
+    v = np.zeros_like(u)
+    v[..., 5] = 2.0
+    y = oracle.fftconv_gated(u, w, v, k, 64, "f32")
+    ref = oracle.fftconv(ut, k, 64)
+    assert np.allclose(y[..., 5], 2.0 * ref[..., 5], rtol=0, atol=1e-12)
+    assert np.count_nonzero(np.delete(y, 5, axis=-1)) == 0
+
+
+def test_gated_product_is_rounded_to_the_io_dtype_before_the_transform():
+    # (1 + 2^-7)^2 = 1 + 2^-6 + 2^-14 is not a bf16 number: it rounds to 1 + 2^-6 before the convolution
+    u = np.full((1, 1, 4), 1.0 + 2.0 ** -7)
+    w = u.copy()
+    k = np.zeros((1, 4))
+    k[0, 0] = 1.0                                  # delta: y = rounded product
+    y_b = oracle.fftconv_gated(u, w, None, k, 8, "bf16")
+    y_f = oracle.fftconv_gated(u, w, None, k, 8, "f32")
+    assert np.array_equal(y_b, np.full((1, 1, 4), 1.0 + 2.0 ** -6))
+    assert np.array_equal(y_f, np.full((1, 1, 4), (1.0 + 2.0 ** -7) ** 2))
