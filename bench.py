@@ -39,11 +39,12 @@ def measured_traffic(workload: str):
     return None
 
 
-def algorithmic_bytes(w) -> int:
+def algorithmic_bytes(w, gated=False) -> int:
     """Bytes the method must move per launch: u in, y out (I/O dtype) and k_f once
-    per channel, counted as 16-bit (re, im) pairs whatever the stored format."""
+    per channel, counted as 16-bit (re, im) pairs whatever the stored format; the gated
+    form reads two more tensors of the shape of u."""
     s = 4 if w.dtype == "f32" else 2
-    return 2 * w.B * w.H * w.N * s + w.H * w.fft_size * 4
+    return (4 if gated else 2) * w.B * w.H * w.N * s + w.H * w.fft_size * 4
 
 
 def time_oracle(w, u_cpu, k, budget_s=12.0):
@@ -82,6 +83,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=300)
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--gated", action="store_true",
+                    help="time the gated form y = v . ((u . w) * k) instead (not the headline metric)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch a plain elementwise copy of %d MiB (read once, written once) before the "
                          "warm-up, as the known-size reference for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE" % (COPY_BYTES >> 20))
@@ -111,6 +114,8 @@ def main():
     kf = plan.filter_fft(kd, block_keep=bk)
     u = u_cpu.to(dev)
     y = torch.empty_like(u)
+    gw = synth.gen_gate(w, "w").to(dev) if args.gated else None
+    gv = synth.gen_gate(w, "v").to(dev) if args.gated else None
     torch.cuda.synchronize()
 
     if args.copy_calibration:
@@ -122,7 +127,9 @@ def main():
         del src, dst
 
     def step():
-        if bk is not None:
+        if args.gated:
+            plan.forward_gated(u, gw, gv, kf, out=y)
+        elif bk is not None:
             plan.forward_freq_sparse(u, kf, bk, out=y)
         elif w.Nk:
             plan.forward_partial(u, kf, w.Nk, out=y)
@@ -147,7 +154,7 @@ def main():
     ms_per_step = e0.elapsed_time(e1) / args.steps
     assert torch.isfinite(y.float()).all(), "non-finite output"
     dense_ms = None
-    if bk is not None or w.Nk:
+    if (bk is not None or w.Nk) and not args.gated:
         # sparse workloads: the dense entry point on the same (masked / truncated) k_f, for the speed-up
         for _ in range(args.warmup):
             plan.forward(u, kf, out=y)
@@ -160,11 +167,11 @@ def main():
         dense_ms = d0.elapsed_time(d1) / args.steps
 
     nseq = w.B * w.H
-    abytes = algorithmic_bytes(w)
+    abytes = algorithmic_bytes(w, args.gated)
     avg_kernel_ms = ms_per_step          # one kernel launch per step on the fused paths
     achieved = abytes / (avg_kernel_ms * 1e-3) / 1e9
     out = {
-        "metric": "FFT-conv sequences/ms + achieved HBM TB/s at B=64,H=768,N=4096 bf16",
+        "metric": ("gated " if args.gated else "") + "FFT-conv sequences/ms + achieved HBM TB/s at B=64,H=768,N=4096 bf16",
         "value": nseq / ms_per_step,
         "unit": "sequences/ms",
         "n_gpus": 1,
@@ -176,20 +183,20 @@ def main():
         "vs_baseline": None,
         "dtype": w.dtype,
         "data": "synthetic",
-        "config": {"workload": "%s: causal FFT conv B=%d H=%d N=%d fft_size=%d %s I/O, fp32 accumulate"
-                               % (w.name, w.B, w.H, w.N, w.fft_size, w.dtype),
+        "config": {"workload": "%s: %scausal FFT conv B=%d H=%d N=%d fft_size=%d %s I/O, fp32 accumulate"
+                               % (w.name, "gated " if args.gated else "", w.B, w.H, w.N, w.fft_size, w.dtype),
                    "path": plan.path, "factors": plan.factors,
                    "achieved_TBps": achieved / 1e3, "wall_ms_per_step": t_wall / args.steps * 1e3,
                    "input_gen_s": t_gen,
                    "dense_ms_per_step": dense_ms,
                    "speedup_vs_dense": None if dense_ms is None else dense_ms / ms_per_step},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(w.name),
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None if args.gated else measured_traffic(w.name),
                      "kernel": ("k_fused3_ws" if w.fft_size == 8192 else "k_fused3") if plan.path == "fused3" else plan.path,
                      "algorithmic_bytes": abytes},
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = time_oracle(w, u_cpu, k)
+        out["cpu_baseline"] = time_oracle(w, u_cpu, k)     # the convolution itself; the gates add O(N) per sequence
     print(json.dumps(out))
 
 

@@ -118,6 +118,23 @@ int fftconv_forward_freq_sparse(const fftconv_plan *plan, const void *u, const v
                                 const uint8_t *block_keep, int64_t n_blocks, void *y,
                                 int64_t B, int64_t H, int64_t N, void *workspace, void *stream);
 
+/* Bytes of workspace fftconv_forward_gated needs for batch size B: fftconv_workspace_bytes plus,
+ * for plans whose kernel does not fuse the gates, room for the gated input (B*H*N elements). */
+size_t fftconv_workspace_bytes_gated(const fftconv_plan *plan, int64_t B);
+
+/* Gated convolution (Section 3.1 "Domain-Specific Optimizations"; Section 4.1):
+ *     y = v . ((u . w) * k)          (. elementwise, * the convolution of fftconv_forward)
+ *   w, v: device, (B, H, N) in the plan's I/O dtype like u; either may be NULL (no gate on that
+ *   side; both NULL is fftconv_forward).  v must not alias y.
+ * Arithmetic: the product u . w is rounded to the I/O dtype (nearest even) before the transform
+ * (it is what the matrix cores consume); the output gate multiplies the convolution result after
+ * it has been rounded to the I/O dtype, and the product is rounded again.  Plans that run the fused
+ * 8192-point kernel apply both gates inside it (u, w, v each read once, y written once); other
+ * plans run one elementwise kernel per gate around fftconv_forward.
+ * workspace: at least fftconv_workspace_bytes_gated(plan, B) bytes, may be NULL when that is 0. */
+int fftconv_forward_gated(const fftconv_plan *plan, const void *u, const void *w, const void *v, const void *k_f,
+                          void *y, int64_t B, int64_t H, int64_t N, void *workspace, void *stream);
+
 /* Fraction of k_f that a cut-off pattern zeroes (Appendix A.4): k_f is viewed
  * as an ndim-dimensional array of shape dims[0..ndim) and, in every dimension
  * i, the last cuts[i] indices are set to zero (cuts[i] = how much of that

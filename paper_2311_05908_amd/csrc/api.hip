@@ -279,6 +279,48 @@ int fftconv_forward_freq_sparse(const fftconv_plan *p, const void *u, const void
     return fftconv_forward(p, u, k_f, y, B, H, N, workspace, stream);
 }
 
+static size_t elem_bytes(const fftconv_plan *p) { return p->dtype == FFTCONV_F32 ? 4 : 2; }
+static size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+size_t fftconv_workspace_bytes_gated(const fftconv_plan *p, int64_t B)
+{
+    if (!p || B <= 0) return 0;
+    const size_t base = fftconv_workspace_bytes(p, B);
+    if (fused3_gates_fused(p)) return base;
+    return align256(base) + (size_t)(B * p->H * p->N) * elem_bytes(p);
+}
+
+int fftconv_forward_gated(const fftconv_plan *p, const void *u, const void *w, const void *v, const void *k_f, void *y,
+                          int64_t B, int64_t H, int64_t N, void *workspace, void *stream)
+{
+    if (!w && !v) return fftconv_forward(p, u, k_f, y, B, H, N, workspace, stream);
+    // the checks of fftconv_forward, against the larger workspace
+    int rc = forward_check(p, u, k_f, y, B, H, N, (void *)1, "fftconv_forward_gated");
+    if (rc || B == 0) return rc;
+    if (v == y) {
+        set_error("fftconv_forward_gated: v must not alias y");
+        return FFTCONV_EINVAL;
+    }
+    if (!workspace && fftconv_workspace_bytes_gated(p, B) != 0) {
+        set_error("fftconv_forward_gated: this plan needs %zu bytes of workspace for B=%lld",
+                  fftconv_workspace_bytes_gated(p, B), (long long)B);
+        return FFTCONV_EINVAL;
+    }
+    hipStream_t s = (hipStream_t)stream;
+    if (fused3_gates_fused(p)) return fused3_forward_gated(p, u, w, v, k_f, y, B, s);
+    const int64_t n = B * p->H * p->N;
+    const void *src = u;
+    if (w) {
+        void *prod = (char *)workspace + align256(fftconv_workspace_bytes(p, B));
+        rc = gate_multiply(p->dtype, u, w, prod, n, s);
+        if (rc) return rc;
+        src = prod;
+    }
+    rc = fftconv_forward(p, src, k_f, y, B, H, N, workspace, stream);
+    if (rc || !v) return rc;
+    return gate_multiply(p->dtype, y, v, y, n, s);
+}
+
 double fftconv_sparsity_fraction(const int64_t *dims, const int64_t *cuts, int ndim)
 {
     if (!dims || !cuts || ndim < 1) return -1.0;

@@ -166,6 +166,13 @@ __host__ __device__ inline int fused3_kf_slot_8192(int64_t fi)
     return (k1 * 4 + r) * 64 + lane;
 }
 
+// gated form y = v . ((u . w) * k): true when the plan's kernel applies the gates itself
+bool fused3_gates_fused(const fftconv_plan *p);
+int fused3_forward_gated(const fftconv_plan *p, const void *u, const void *w, const void *v, const void *kf, void *y,
+                         int64_t B, hipStream_t s);
+// out[i] = a[i] * b[i] rounded to the I/O dtype (staged.hip); out may alias a
+int gate_multiply(int dtype, const void *a, const void *b, void *out, int64_t n, hipStream_t s);
+
 // ---- multi-pass path (multipass.hip)
 bool multipass_supported(int64_t N, int64_t M, int dtype);
 int multipass_init(fftconv_plan *p);

@@ -918,6 +918,18 @@ int fused3_pack_kf(const fftconv_plan *p, const double2 *spec, int64_t h0, int64
     return FFTCONV_OK;
 }
 
+bool fused3_gates_fused(const fftconv_plan *p) { return p->path == PATH_FUSED3 && p->M == 8192; }
+
+int fused3_forward_gated(const fftconv_plan *p, const void *u, const void *w, const void *v, const void *kf, void *y,
+                         int64_t B, hipStream_t s)
+{
+    if (((uintptr_t)u | (uintptr_t)y | (uintptr_t)w | (uintptr_t)v) & 15) {
+        set_error("fftconv_forward_gated: u, w, v and y must be 16-byte aligned for this plan");
+        return FFTCONV_EINVAL;
+    }
+    return fused3_ws_launch(p, p->f3.consts, u, kf, y, B, 1, 0, s, w, v);
+}
+
 int fused3_forward(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, hipStream_t s)
 {
     if (((uintptr_t)u | (uintptr_t)y) & 15) {

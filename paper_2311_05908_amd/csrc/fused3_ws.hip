@@ -53,10 +53,13 @@ constexpr int PCH = G::M / 8 / PT;            // 16-byte input chunks per outer-
 
 // FULL: B even and N == fft_size/2, so every load and store of a work item is in range and
 // unconditional (the compiler can then count outstanding memory operations exactly).
-template <typename TT, bool FULL>
+// GATE (gated form y = v . ((u . w) * k), Section 3.1 / 4.1; needs nseg == 1): bit 0 = the input gate
+// wg multiplies u on its way into LDS, bit 1 = the output gate vg multiplies y on its way out; the
+// gates travel with the staging traffic of the outer role (16-byte chunks, one item ahead / behind).
+template <typename TT, bool FULL, int GATE>
 __global__ void __launch_bounds__(NT) k_fused3_ws(const uint16_t *__restrict__ u, uint16_t *__restrict__ y,
                                                  const uint2 *__restrict__ kf, Consts cs, int B, int H, int N, int nseg, int P, int Lo,
-                                                 int probe)
+                                                 int probe, const uint16_t *__restrict__ wg, const uint16_t *__restrict__ vg)
 {
     extern __shared__ uint32_t smem[];
     uint32_t *const XBb = smem;                                   // [2][XBW]
@@ -103,6 +106,7 @@ __global__ void __launch_bounds__(NT) k_fused3_ws(const uint16_t *__restrict__ u
         }
         // input prefetch: the loads of item s+2 are issued at the start of step s and staged at its end
         uint4 pre[PCH];
+        uint4 prew[(GATE & 1) ? PCH : 1], prev[(GATE & 2) ? PCH : 1];
         auto issue_loads = [&](int t) {
             const int h = t / per_h, rem = t - h * per_h;
             const int pair = rem / nseg, seg = rem - pair * nseg;
@@ -115,14 +119,37 @@ __global__ void __launch_bounds__(NT) k_fused3_ws(const uint16_t *__restrict__ u
                     // (nseg == 1) past the end of the range the last item is fetched again (in range, unused)
                     const int tc = t < t1 ? t : t1 - 1;
                     const int hc = tc / npairs, pc = tc - hc * npairs;
-                    const uint16_t *row = u + ((size_t)(2 * pc + s) * H + hc) * N;
-                    pre[j] = *(const uint4 *)(row + n);
+                    const size_t ofs = ((size_t)(2 * pc + s) * H + hc) * N + n;
+                    pre[j] = *(const uint4 *)(u + ofs);
+                    if constexpr (GATE & 1) prew[j] = *(const uint4 *)(wg + ofs);
                 } else {
                     uint4 v = make_uint4(0, 0, 0, 0);
                     const int in_ofs = seg == 0 ? 0 : G::M / 2 + (seg - 1) * Lo - P;
                     const uint16_t *row = u + ((size_t)b * H + h) * N + in_ofs;
-                    if (t < t1 && b < B && n < N - in_ofs) v = *(const uint4 *)(row + n);
+                    const bool ok = t < t1 && b < B && n < N - in_ofs;
+                    if (ok) v = *(const uint4 *)(row + n);
                     pre[j] = v;
+                    if constexpr (GATE & 1) {
+                        uint4 g = make_uint4(0, 0, 0, 0);
+                        if (ok) g = *(const uint4 *)(wg + ((size_t)b * H + h) * N + n);     // nseg == 1: in_ofs == 0
+                        prew[j] = g;
+                    }
+                }
+            }
+        };
+        // output gate of item t (the item stored at the end of this step)
+        auto issue_loads_v = [&](int t) {
+            if constexpr (GATE & 2) {
+                const int tc = t < t0 ? t0 : t;
+                const int h = tc / per_h, pair = tc - h * per_h;
+#pragma unroll
+                for (int j = 0; j < PCH; ++j) {
+                    const int s = j / 2;
+                    const int n = (ptid + PT * (j % 2)) * 8;
+                    const int b = 2 * pair + s;
+                    uint4 g = make_uint4(0, 0, 0, 0);
+                    if (FULL || (b < B && n < N)) g = *(const uint4 *)(vg + ((size_t)b * H + h) * N + n);
+                    prev[j] = g;
                 }
             }
         };
@@ -133,10 +160,12 @@ __global__ void __launch_bounds__(NT) k_fused3_ws(const uint16_t *__restrict__ u
                 const int n = (ptid + PT * (j % 2)) * 8;
                 const int n3 = n % 16, n2 = (n / 16) % 16, n1 = n / 256;
                 uint32_t *dst = (uint32_t *)(UB + s * G::SU + n1 * G::PQ1 + n2 * G::PR + n3);
-                dst[0] = pre[j].x;
-                dst[1] = pre[j].y;
-                dst[2] = pre[j].z;
-                dst[3] = pre[j].w;
+                uint4 v = pre[j];
+                if constexpr (GATE & 1) v = TT::mul8(v, prew[j]);
+                dst[0] = v.x;
+                dst[1] = v.y;
+                dst[2] = v.z;
+                dst[3] = v.w;
             }
         };
         auto store_out = [&](int t, const uint16_t *YB) {
@@ -152,7 +181,8 @@ __global__ void __launch_bounds__(NT) k_fused3_ws(const uint16_t *__restrict__ u
                 const int b = 2 * pair + s;
                 const int n3 = n % 16, n2 = (n / 16) % 16, n1 = n / 256;
                 const uint32_t *src = (const uint32_t *)(YB + s * G::SU + n1 * G::PQ1 + n2 * G::PR + n3);
-                const uint4 v = make_uint4(src[0], src[1], src[2], src[3]);
+                uint4 v = make_uint4(src[0], src[1], src[2], src[3]);
+                if constexpr (GATE & 2) v = TT::mul8(v, prev[j]);
                 if constexpr (FULL) {
                     *(uint4 *)(y + ((size_t)b * H + h) * N + n) = v;
                 } else {
@@ -172,6 +202,7 @@ __global__ void __launch_bounds__(NT) k_fused3_ws(const uint16_t *__restrict__ u
             const bool doA = WPROBE(2) && s + 1 < t1;
             STAMP(0);
             if (WPROBE(8)) issue_loads(s + 2);
+            issue_loads_v(s - 2);
             STAMP(1);
             // ---- phase C of item s-1: inverse stage 1, n1 < 16; re -> row b, im -> row b+1 -> YB
             if (doC) {
@@ -352,7 +383,7 @@ static int ws_probe()
 // nseg == 1: plain causal convolution (N <= fft/2).  nseg > 1: overlap-save segments of a partial
 // convolution, P samples of history per segment, Lo = fft/2 - P outputs per later segment.
 int fused3_ws_launch(const fftconv_plan *p, const void *consts, const void *u, const void *kf, void *y, int64_t B,
-                     int nseg, int P, hipStream_t s)
+                     int nseg, int P, hipStream_t s, const void *wg, const void *vg)
 {
     const int64_t npairs = (B + 1) / 2;
     const int64_t T = p->H * npairs * nseg;
@@ -361,20 +392,30 @@ int fused3_ws_launch(const fftconv_plan *p, const void *consts, const void *u, c
         set_error("fftconv_forward: H * ceil(B/2) = %lld work items exceed the fused kernel's limit", (long long)T);
         return FFTCONV_EUNSUPPORTED;
     }
+    if ((wg || vg) && nseg != 1) {
+        set_error("fused 8192 kernel: gates cannot be combined with overlapping segments");
+        return FFTCONV_EUNSUPPORTED;
+    }
     const bool full = (B % 2 == 0) && p->N == G::M / 2 && nseg == 1;
     const bool f16 = p->dtype == FFTCONV_F16;
-    void (*kern)(const uint16_t *, uint16_t *, const uint2 *, Consts, int, int, int, int, int, int, int) =
-        f16 ? (full ? k_fused3_ws<F16, true> : k_fused3_ws<F16, false>)
-            : (full ? k_fused3_ws<BF16, true> : k_fused3_ws<BF16, false>);
-    static bool attr_set[4] = {false, false, false, false};
-    const int slot = (f16 ? 2 : 0) + (full ? 1 : 0);
-    if (!attr_set[slot]) {
+    const int gate = (wg ? 1 : 0) | (vg ? 2 : 0);
+    using Kern = void (*)(const uint16_t *, uint16_t *, const uint2 *, Consts, int, int, int, int, int, int, int,
+                          const uint16_t *, const uint16_t *);
+    static const Kern table[2][2][4] = {
+        {{k_fused3_ws<BF16, false, 0>, k_fused3_ws<BF16, false, 1>, k_fused3_ws<BF16, false, 2>, k_fused3_ws<BF16, false, 3>},
+         {k_fused3_ws<BF16, true, 0>, k_fused3_ws<BF16, true, 1>, k_fused3_ws<BF16, true, 2>, k_fused3_ws<BF16, true, 3>}},
+        {{k_fused3_ws<F16, false, 0>, k_fused3_ws<F16, false, 1>, k_fused3_ws<F16, false, 2>, k_fused3_ws<F16, false, 3>},
+         {k_fused3_ws<F16, true, 0>, k_fused3_ws<F16, true, 1>, k_fused3_ws<F16, true, 2>, k_fused3_ws<F16, true, 3>}}};
+    const Kern kern = table[f16 ? 1 : 0][full ? 1 : 0][gate];
+    static bool attr_set[2][2][4] = {};
+    if (!attr_set[f16 ? 1 : 0][full ? 1 : 0][gate]) {
         FC_HIP(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)WS_LDS_BYTES));
-        attr_set[slot] = true;
+        attr_set[f16 ? 1 : 0][full ? 1 : 0][gate] = true;
     }
     const int grid = (int)(T < p->f3.num_cu ? T : p->f3.num_cu);
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NT), WS_LDS_BYTES, s, (const uint16_t *)u, (uint16_t *)y,
-                       (const uint2 *)kf, consts_at<16, 16>(consts), (int)B, (int)p->H, (int)p->N, nseg, P, Lo, ws_probe());
+                       (const uint2 *)kf, consts_at<16, 16>(consts), (int)B, (int)p->H, (int)p->N, nseg, P, Lo, ws_probe(),
+                       (const uint16_t *)wg, (const uint16_t *)vg);
     FC_HIP(hipGetLastError());
     return FFTCONV_OK;
 }

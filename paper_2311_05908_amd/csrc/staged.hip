@@ -18,6 +18,7 @@
 #include <hip/hip_fp16.h>
 
 #include <cmath>
+#include <type_traits>
 
 #include "fftconv_internal.h"
 
@@ -349,6 +350,37 @@ FacList staged_fac_list(const fftconv_plan *p)
     fl.nf = p->st.nf;
     for (int i = 0; i < MAX_FACTORS; ++i) fl.fac[i] = (int)p->st.fac[i];
     return fl;
+}
+
+// Elementwise gate of the gated convolution for plans without a fused-gate kernel:
+// out = a * b, the fp32 product rounded to the I/O dtype (exact product for 16-bit inputs).
+template <typename T> __global__ void k_gate_multiply(const T *a, const T *b, T *out, int64_t n)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    if constexpr (std::is_same<T, float>::value)
+        out[i] = a[i] * b[i];
+    else if constexpr (std::is_same<T, __half>::value)
+        out[i] = __float2half_rn(__half2float(a[i]) * __half2float(b[i]));
+    else
+        out[i] = __float2bfloat16(__bfloat162float(a[i]) * __bfloat162float(b[i]));
+}
+
+int gate_multiply(int dtype, const void *a, const void *b, void *out, int64_t n, hipStream_t s)
+{
+    const int bs = 256;
+    const unsigned grid = (unsigned)((n + bs - 1) / bs);
+    if (dtype == FFTCONV_F32)
+        hipLaunchKernelGGL(k_gate_multiply<float>, dim3(grid), dim3(bs), 0, s, (const float *)a, (const float *)b,
+                           (float *)out, n);
+    else if (dtype == FFTCONV_F16)
+        hipLaunchKernelGGL(k_gate_multiply<__half>, dim3(grid), dim3(bs), 0, s, (const __half *)a, (const __half *)b,
+                           (__half *)out, n);
+    else
+        hipLaunchKernelGGL(k_gate_multiply<__hip_bfloat16>, dim3(grid), dim3(bs), 0, s, (const __hip_bfloat16 *)a,
+                           (const __hip_bfloat16 *)b, (__hip_bfloat16 *)out, n);
+    FC_HIP(hipGetLastError());
+    return FFTCONV_OK;
 }
 
 }  // namespace fftconv

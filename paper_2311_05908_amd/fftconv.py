@@ -21,7 +21,7 @@ EXPORTS = [
     "fftconv_plan_create", "fftconv_plan_destroy", "fftconv_kf_bytes", "fftconv_workspace_bytes",
     "fftconv_filter_fft", "fftconv_forward", "fftconv_forward_partial", "fftconv_filter_fft_sparse",
     "fftconv_forward_freq_sparse", "fftconv_sparsity_fraction", "fftconv_plan_path", "fftconv_plan_factors",
-    "fftconv_strerror", "fftconv_last_error",
+    "fftconv_strerror", "fftconv_last_error", "fftconv_workspace_bytes_gated", "fftconv_forward_gated",
 ]
 
 _lib = None
@@ -65,6 +65,10 @@ def load():
     lib.fftconv_filter_fft_sparse.restype = ci
     lib.fftconv_forward_freq_sparse.argtypes = [vp, vp, vp, vp, i64, vp, i64, i64, i64, vp, vp]
     lib.fftconv_forward_freq_sparse.restype = ci
+    lib.fftconv_workspace_bytes_gated.argtypes = [vp, i64]
+    lib.fftconv_workspace_bytes_gated.restype = ctypes.c_size_t
+    lib.fftconv_forward_gated.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, vp, vp]
+    lib.fftconv_forward_gated.restype = ci
     lib.fftconv_sparsity_fraction.argtypes = [ctypes.POINTER(i64), ctypes.POINTER(i64), ci]
     lib.fftconv_sparsity_fraction.restype = ctypes.c_double
     lib.fftconv_plan_path.argtypes = [vp]
@@ -141,8 +145,11 @@ class Plan:
     def workspace_bytes(self, B: int) -> int:
         return int(self._lib.fftconv_workspace_bytes(self._h, int(B)))
 
-    def _workspace(self, B: int, device):
-        need = self.workspace_bytes(B)
+    def workspace_bytes_gated(self, B: int) -> int:
+        return int(self._lib.fftconv_workspace_bytes_gated(self._h, int(B)))
+
+    def _workspace(self, B: int, device, gated: bool = False):
+        need = self.workspace_bytes_gated(B) if gated else self.workspace_bytes(B)
         if need == 0:
             return None
         if self._ws is None or self._ws.numel() < need or self._ws.device != device:
@@ -177,6 +184,22 @@ class Plan:
         ws = self._workspace(u.shape[0], u.device)
         _check(self._lib.fftconv_forward(self._h, u.data_ptr(), kf.data_ptr(), y.data_ptr(), u.shape[0], self.H,
                                          self.N, None if ws is None else ws.data_ptr(), _stream_ptr()))
+        return y
+
+    def forward_gated(self, u, w, v, kf, out=None):
+        """fftconv_forward_gated: y = v . ((u . w) * k); w and/or v may be None."""
+        self._check_u(u)
+        for g in (w, v):
+            if g is not None:
+                self._check_u(g)
+                if g.shape != u.shape:
+                    raise ValueError("gates must have the shape of u")
+        y = torch.empty_like(u) if out is None else out
+        ws = self._workspace(u.shape[0], u.device, gated=True)
+        _check(self._lib.fftconv_forward_gated(self._h, u.data_ptr(), None if w is None else w.data_ptr(),
+                                               None if v is None else v.data_ptr(), kf.data_ptr(), y.data_ptr(),
+                                               u.shape[0], self.H, self.N, None if ws is None else ws.data_ptr(),
+                                               _stream_ptr()))
         return y
 
     def forward_partial(self, u, kf, Nk: int, out=None):

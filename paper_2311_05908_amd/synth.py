@@ -89,6 +89,22 @@ def gen_u(w: Workload, b_indices=None) -> torch.Tensor:
     return torch.stack(rows, 0)
 
 
+def gen_gate(w: Workload, which: str, b_indices=None) -> torch.Tensor:
+    """Gate tensor of the gated convolution ("w": input gate, "v": output gate): N(0,1) per element,
+    rounded to the I/O dtype, one counter-based stream per batch row like gen_u.  Stands in for the
+    linear projections of the layer input that Hyena / M2 use as gates."""
+    if b_indices is None:
+        b_indices = range(w.B)
+    seed = w.seed_u + {"w": 100, "v": 200}[which]
+    rows = []
+    for b in b_indices:
+        g = np.random.Generator(np.random.Philox(key=[seed, int(b)]))
+        rows.append(torch.from_numpy(g.standard_normal((w.H, w.N), dtype=np.float32)).to(TORCH_DTYPE[w.dtype]))
+    if not rows:
+        return torch.empty((0, w.H, w.N), dtype=TORCH_DTYPE[w.dtype])
+    return torch.stack(rows, 0)
+
+
 def gen_alpha(w: Workload) -> np.ndarray:
     lo, hi = w.alpha
     if lo == hi:

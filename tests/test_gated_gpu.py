@@ -1,0 +1,107 @@
+"""Gated convolution y = v . ((u . w) * k) through the C ABI against the CPU oracle:
+the fused-gate 8192-point kernel and the elementwise-kernel route of the other plans."""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2311_05908_amd import fftconv, synth
+from parity_util import TOL
+
+pytestmark = pytest.mark.gpu
+W = synth.WORKLOADS
+
+
+def run_gated(w, use_w=True, use_v=True):
+    u = synth.gen_u(w)
+    gw = synth.gen_gate(w, "w") if use_w else None
+    gv = synth.gen_gate(w, "v") if use_v else None
+    k = synth.gen_k(w)
+    plan = fftconv.Plan(w.N, w.fft_size, w.H, w.dtype)
+    kf = plan.filter_fft(torch.from_numpy(k).cuda())
+    y = plan.forward_gated(u.cuda(), None if gw is None else gw.cuda(), None if gv is None else gv.cuda(), kf)
+    torch.cuda.synchronize()
+    assert torch.isfinite(y.float()).all()
+    return u, gw, gv, k, y.cpu(), plan
+
+
+def check_all(w, use_w=True, use_v=True):
+    u, gw, gv, k, y, plan = run_gated(w, use_w, use_v)
+    ref = oracle.fftconv_gated(u.double().numpy(), None if gw is None else gw.double().numpy(),
+                               None if gv is None else gv.double().numpy(), k, w.fft_size, w.dtype)
+    return float(oracle.rel_l2_per_sequence(y.double().numpy(), ref).max()), plan
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("B,H,N,use_w,use_v", [
+    (2, 1, 4096, True, True),
+    (3, 5, 4096, True, True),       # odd batch
+    (8, 3, 4096, True, False),      # input gate only
+    (8, 3, 4096, False, True),      # output gate only
+    (2, 2, 1000, True, True),       # ragged N
+    (1, 2, 2048, True, True),       # B = 1, N < fft/2
+])
+def test_gated_fused_fft8192(dtype, B, H, N, use_w, use_v):
+    w = synth.scaled(W["cfg2"], B=B, H=H, N=N, fft_size=8192, dtype=dtype)
+    err, plan = check_all(w, use_w, use_v)
+    print("gated fused 8192 %s B=%d H=%d N=%d w=%d v=%d path=%s err=%.3e" % (dtype, B, H, N, use_w, use_v, plan.path, err),
+          flush=True)
+    assert plan.path == "fused3" and plan.workspace_bytes_gated(B) == 0
+    assert err <= TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype,B,H,N,M", [
+    ("f32", 2, 3, 256, 512),        # staged path
+    ("f32", 3, 2, 300, 1024),
+    ("bf16", 2, 2, 200, 512),       # staged path, 16-bit
+    ("bf16", 3, 2, 8192, 16384),    # fused 16384 kernel, gates by elementwise kernels
+    ("f16", 2, 2, 16384, 32768),    # fused 32768 kernel
+    ("bf16", 2, 1, 32768, 65536),   # multi-pass
+])
+def test_gated_other_plans(dtype, B, H, N, M):
+    w = synth.scaled(W["cfg1"], B=B, H=H, N=N, fft_size=M, dtype=dtype, alpha=(1e-3, 1e-2))
+    for use_w, use_v in ((True, True), (True, False), (False, True)):
+        err, plan = check_all(w, use_w, use_v)
+        print("gated %s B=%d H=%d N=%d M=%d w=%d v=%d path=%s err=%.3e" % (dtype, B, H, N, M, use_w, use_v, plan.path, err),
+              flush=True)
+        assert plan.workspace_bytes_gated(B) >= plan.workspace_bytes(B) + B * H * N * (4 if dtype == "f32" else 2)
+        assert err <= TOL[dtype]
+
+
+def test_gated_without_gates_is_forward_and_errors():
+    w = synth.scaled(W["cfg2"], B=2, H=2)
+    u = synth.gen_u(w).cuda()
+    k = synth.gen_k(w)
+    plan = fftconv.Plan(w.N, w.fft_size, w.H, w.dtype)
+    kf = plan.filter_fft(torch.from_numpy(k).cuda())
+    assert torch.equal(plan.forward_gated(u, None, None, kf), plan.forward(u, kf))
+    y = torch.empty_like(u)
+    lib = fftconv.load()
+    rc = lib.fftconv_forward_gated(plan._h, u.data_ptr(), u.data_ptr(), y.data_ptr(), kf.data_ptr(), y.data_ptr(),
+                                   2, 2, w.N, None, None)
+    assert rc == -1                                     # v aliases y
+    # a plan that needs workspace for the gated input refuses a NULL workspace
+    w2 = synth.scaled(W["cfg1"], B=2, H=2, N=256, fft_size=512, dtype="f32")
+    p2 = fftconv.Plan(w2.N, w2.fft_size, w2.H, w2.dtype)
+    u2 = synth.gen_u(w2).cuda()
+    kf2 = p2.filter_fft(torch.from_numpy(synth.gen_k(w2)).cuda())
+    y2 = torch.empty_like(u2)
+    rc = lib.fftconv_forward_gated(p2._h, u2.data_ptr(), u2.data_ptr(), None, kf2.data_ptr(), y2.data_ptr(),
+                                   2, 2, w2.N, None, None)
+    assert rc == -1
+
+
+def test_gated_cfg2_full_size_sampled_sequences():
+    w = W["cfg2"]
+    u, gw, gv, k, y, plan = run_gated(w)
+    assert plan.path == "fused3"
+    kext = oracle.extend_filter(k, w.fft_size)
+    worst = 0.0
+    for b, h in synth.sample_sequences(w, 28):
+        ref = oracle.fftconv_gated(u[b, h].double().numpy()[None, None], gw[b, h].double().numpy()[None, None],
+                                   gv[b, h].double().numpy()[None, None], kext[h][None], None, w.dtype)[0, 0]
+        worst = max(worst, float(oracle.rel_l2_per_sequence(y[b, h].double().numpy(), ref)))
+    print("gated cfg2 full: worst sampled rel L2 = %.3e" % worst, flush=True)
+    assert worst <= TOL[w.dtype]
