@@ -47,6 +47,10 @@ def _load():
         lib.oracle_fftconv_at.restype = ctypes.c_int
         lib.oracle_mask_filter.argtypes = [p, p, p, i64, i64]
         lib.oracle_mask_filter.restype = ctypes.c_int
+        lib.oracle_backward_u.argtypes = [p, p, p, i64, i64, i64, i64]
+        lib.oracle_backward_u.restype = ctypes.c_int
+        lib.oracle_backward_k.argtypes = [p, p, p, i64, i64, i64, i64, i64]
+        lib.oracle_backward_k.restype = ctypes.c_int
         lib.oracle_num_threads.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -158,6 +162,34 @@ def fftconv_gated(u, w, v, kext, M: int | None = None, dtype: str = "f32") -> np
     if v is not None:
         y = y * _f64(v)
     return y
+
+
+def backward_u(dy, kext, M: int | None = None) -> np.ndarray:
+    """du[b,h,j] = sum_i dy[b,h,i] * kext[h,(i-j) mod M]: gradient of fftconv with respect to u."""
+    dy = _f64(dy)
+    kext = _f64(kext)
+    if M is not None and kext.shape[1] != M:
+        kext = extend_filter(kext, M)
+    B, H, N = dy.shape
+    if kext.shape[0] != H:
+        raise ValueError("filter rows must equal H")
+    du = np.empty_like(dy)
+    if _load().oracle_backward_u(dy.ctypes.data, kext.ctypes.data, du.ctypes.data, B, H, N, kext.shape[1]) != 0:
+        raise ValueError("oracle_backward_u rejected its sizes")
+    return du
+
+
+def backward_k(u, dy, M: int, Nk: int) -> np.ndarray:
+    """dk[h,t] = sum_b sum_i dy[b,h,i] * upad[b,h,(i-t) mod M] for t < Nk: gradient with respect to the filter taps."""
+    u = _f64(u)
+    dy = _f64(dy)
+    if u.shape != dy.shape:
+        raise ValueError("u and dy differ in shape")
+    B, H, N = u.shape
+    dk = np.empty((H, Nk), dtype=np.float64)
+    if _load().oracle_backward_k(u.ctypes.data, dy.ctypes.data, dk.ctypes.data, B, H, N, int(M), int(Nk)) != 0:
+        raise ValueError("oracle_backward_k rejected its sizes")
+    return dk
 
 
 def num_threads() -> int:

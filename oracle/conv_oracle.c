@@ -155,6 +155,58 @@ int oracle_mask_filter(const double *kext, const uint8_t *keep, double *out, int
     return rc;
 }
 
+/* Backward pass (Section 3.1 "Kernel Fusion and Recomputation"; Section 4.1 backward tables): for
+ * a loss L with dy = dL/dy, the gradients of the definition at the top of this file are its
+ * partial derivatives written out term by term,
+ *     dy[i]/du[j]    = kext[(i-j) mod M]         =>  du[b,h,j] = sum_{i<N} dy[b,h,i] kext[h,(i-j) mod M]
+ *     dy[i]/dkext[t] = u[j] where (i-j) mod M = t =>  dk[h,t]   = sum_b sum_{i<N} dy[b,h,i] upad[b,h,(i-t) mod M]
+ * (upad = u laid out on M samples, zero beyond N).  No FFT, no reuse of the forward code.
+ * dy, u, du: (B,H,N); kext: (H,M); dk: (H,Nk), the first Nk taps.  Returns 0, or -1 on bad sizes. */
+int oracle_backward_u(const double *dy, const double *kext, double *du, int64_t B, int64_t H, int64_t N, int64_t M)
+{
+    if (B < 0 || H < 0 || N < 1 || M < N) return -1;
+    int64_t nseq = B * H;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t s = 0; s < nseq; ++s) {
+        const double *g = dy + s * N;
+        const double *kr = kext + (s % H) * M;
+        double *out = du + s * N;
+        for (int64_t j = 0; j < N; ++j) {
+            double acc = 0.0;
+            for (int64_t i = 0; i < N; ++i) {
+                int64_t t = i - j;
+                if (t < 0) t += M;
+                acc += g[i] * kr[t];
+            }
+            out[j] = acc;
+        }
+    }
+    return 0;
+}
+
+int oracle_backward_k(const double *u, const double *dy, double *dk, int64_t B, int64_t H, int64_t N, int64_t M,
+                      int64_t Nk)
+{
+    if (B < 0 || H < 0 || N < 1 || M < N || Nk < 1 || Nk > M) return -1;
+    int64_t ntap = H * Nk;
+#pragma omp parallel for schedule(dynamic, 16)
+    for (int64_t e = 0; e < ntap; ++e) {
+        int64_t h = e / Nk, t = e % Nk;
+        double acc = 0.0;
+        for (int64_t b = 0; b < B; ++b) {
+            const double *ur = u + (b * H + h) * N;
+            const double *g = dy + (b * H + h) * N;
+            for (int64_t i = 0; i < N; ++i) {
+                int64_t j = i - t;
+                if (j < 0) j += M;
+                if (j < N) acc += g[i] * ur[j];
+            }
+        }
+        dk[e] = acc;
+    }
+    return 0;
+}
+
 /* Number of threads the parallel loops above run on. */
 int oracle_num_threads(void)
 {

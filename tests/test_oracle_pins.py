@@ -292,3 +292,65 @@ def test_gated_product_is_rounded_to_the_io_dtype_before_the_transform():
     y_f = oracle.fftconv_gated(u, w, None, k, 8, "f32")
     assert np.array_equal(y_b, np.full((1, 1, 4), 1.0 + 2.0 ** -6))
     assert np.array_equal(y_f, np.full((1, 1, 4), (1.0 + 2.0 ** -7) ** 2))
+
+
+# ---------------------------------------------------------------- backward pass
+
+def test_backward_is_the_adjoint_of_the_forward_map():
+    # y is bilinear in (u, k): <dy, conv(u, k)> = <du, u> = <dk, k> for every u, k, dy
+    for (B, H, N, M, Nk) in ((2, 3, 16, 32, 16), (1, 2, 12, 12, 12), (3, 1, 9, 20, 5), (2, 2, 8, 11, 11)):
+        u = RNG.standard_normal((B, H, N))
+        dy = RNG.standard_normal((B, H, N))
+        k = RNG.standard_normal((H, Nk))
+        kext = oracle.extend_filter(k, M)
+        lhs = float((dy * oracle.fftconv(u, kext)).sum())
+        du = oracle.backward_u(dy, kext)
+        dk = oracle.backward_k(u, dy, M, Nk)
+        assert abs(lhs - float((du * u).sum())) <= 1e-10 * (1 + abs(lhs))
+        assert abs(lhs - float((dk * k).sum())) <= 1e-10 * (1 + abs(lhs))
+
+
+def test_backward_matches_library_correlation_in_the_causal_case():
+    B, H, N = 2, 2, 24
+    u = RNG.standard_normal((B, H, N))
+    dy = RNG.standard_normal((B, H, N))
+    k = RNG.standard_normal((H, N))
+    du = oracle.backward_u(dy, k, 2 * N)
+    dk = oracle.backward_k(u, dy, 2 * N, N)
+    for h in range(H):
+        want_k = np.zeros(N)
+        for b in range(B):
+            # du[j] = sum_{i >= j} dy[i] k[i-j]; dk[t] = sum_{i >= t} dy[i] u[i-t]
+            assert np.allclose(du[b, h], np.correlate(dy[b, h], k[h], "full")[N - 1:], rtol=0, atol=1e-12)
+            want_k += np.correlate(dy[b, h], u[b, h], "full")[N - 1:]
+        assert np.allclose(dk[h], want_k, rtol=0, atol=1e-12)
+
+
+def test_backward_agrees_with_finite_differences_of_the_forward_oracle():
+    B, H, N, M, Nk = 1, 2, 6, 8, 8                     # M < 2N: wrapped taps take part
+    u = RNG.standard_normal((B, H, N))
+    k = RNG.standard_normal((H, Nk))
+    dy = RNG.standard_normal((B, H, N))
+    kext = oracle.extend_filter(k, M)
+    du = oracle.backward_u(dy, kext)
+    dk = oracle.backward_k(u, dy, M, Nk)
+    loss = lambda uu, kk: float((dy * oracle.fftconv(uu, oracle.extend_filter(kk, M))).sum())
+    base = loss(u, k)
+    for idx in np.ndindex(u.shape):
+        up = u.copy()
+        up[idx] += 1.0                                 # the map is linear in u: a unit step is exact
+        assert abs((loss(up, k) - base) - du[idx]) <= 1e-10
+    for idx in np.ndindex(k.shape):
+        kp = k.copy()
+        kp[idx] += 1.0
+        assert abs((loss(u, kp) - base) - dk[idx]) <= 1e-10
+
+
+def test_backward_integer_inputs_are_exact_and_channel_reduction_runs_over_the_batch():
+    B, H, N = 3, 2, 10
+    u = RNG.integers(-3, 4, (B, H, N)).astype(np.float64)
+    dy = RNG.integers(-3, 4, (B, H, N)).astype(np.float64)
+    dk = oracle.backward_k(u, dy, 2 * N, N)
+    per_row = sum(oracle.backward_k(u[b:b + 1], dy[b:b + 1], 2 * N, N) for b in range(B))
+    assert np.array_equal(dk, per_row)
+    assert np.array_equal(dk, np.round(dk))
