@@ -83,6 +83,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=300)
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--backward", action="store_true",
+                    help="time the backward pass (du and dk) instead (not the headline metric)")
     ap.add_argument("--gated", action="store_true",
                     help="time the gated form y = v . ((u . w) * k) instead (not the headline metric)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -125,6 +127,32 @@ def main():
             torch.mul(src, 1.0, out=dst)           # one elementwise kernel: COPY_BYTES read, COPY_BYTES written
         torch.cuda.synchronize()
         del src, dst
+
+    if args.backward:
+        dy = synth.gen_gate(w, "dy").to(dev)
+        kfa = plan.filter_fft_adjoint(kd)
+        dk = torch.empty((w.H, w.filter_len), dtype=torch.float32, device=dev)
+        du = torch.empty_like(u)
+        times = {}
+        for name, fn in (("du", lambda: plan.backward_input(dy, kfa, out=du)),
+                         ("dk", lambda: plan.backward_filter(u, dy, w.filter_len, out=dk))):
+            n_it = max(3, min(args.steps, 30))
+            for _ in range(3):
+                fn()
+            torch.cuda.synchronize()
+            b0, b1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            b0.record()
+            for _ in range(n_it):
+                fn()
+            b1.record()
+            torch.cuda.synchronize()
+            times[name] = b0.elapsed_time(b1) / n_it
+        print(json.dumps({"metric": "backward FFT-conv ms per call", "unit": "ms", "n_gpus": 1, "data": "synthetic",
+                          "dtype": w.dtype, "value": times["du"] + times["dk"], "higher_is_better": False,
+                          "config": {"workload": "%s backward: B=%d H=%d N=%d fft_size=%d Nk=%d" %
+                                     (w.name, w.B, w.H, w.N, w.fft_size, w.filter_len),
+                                     "du_ms": times["du"], "dk_ms": times["dk"], "path": plan.path}}))
+        return
 
     def step():
         if args.gated:

@@ -135,6 +135,27 @@ size_t fftconv_workspace_bytes_gated(const fftconv_plan *plan, int64_t B);
 int fftconv_forward_gated(const fftconv_plan *plan, const void *u, const void *w, const void *v, const void *k_f,
                           void *y, int64_t B, int64_t H, int64_t N, void *workspace, void *stream);
 
+/* Backward pass (Section 3.1 "Kernel Fusion and Recomputation"; Section 4.1).  With dy = dL/dy of
+ * y = fftconv_forward(u, k_f), nothing of the forward pass is kept; both gradients are recomputed
+ * from u, k and dy:
+ *     du[b,h,j] = sum_i dy[b,h,i] k[h,(i-j) mod fft_size]          = iFFT(FFT(pad(dy)) . conj(k_f))[0:N]
+ *     dk[h,t]   = sum_b sum_i dy[b,h,i] u_pad[b,h,(i-t) mod fft_size] = Re iFFT(sum_b conj(FFT(pad(u))) . FFT(pad(dy)))[t]
+ *
+ * fftconv_filter_fft_adjoint: as fftconv_filter_fft, but the spectrum of the filter reversed in time
+ * (the conjugate spectrum).  The buffer has fftconv_kf_bytes() bytes and is only meant for
+ * fftconv_backward_input.
+ * fftconv_backward_input: du from dy and the adjoint spectrum; arguments, layouts, workspace and
+ * kernels are those of fftconv_forward (du must not alias dy).
+ * fftconv_backward_filter: dk (device, (H, Nk) fp32, 1 <= Nk <= fft_size) from u and dy (device,
+ * (B, H, N), plan dtype); the reduction over the batch runs in frequency space in fp32, in the
+ * order of b (results are reproducible).  workspace: fftconv_workspace_bytes_backward_filter bytes. */
+int fftconv_filter_fft_adjoint(const fftconv_plan *plan, const float *k, int64_t Nk, void *k_f, void *stream);
+int fftconv_backward_input(const fftconv_plan *plan, const void *dy, const void *k_f_adjoint, void *du,
+                           int64_t B, int64_t H, int64_t N, void *workspace, void *stream);
+size_t fftconv_workspace_bytes_backward_filter(const fftconv_plan *plan, int64_t B);
+int fftconv_backward_filter(const fftconv_plan *plan, const void *u, const void *dy, float *dk, int64_t Nk,
+                            int64_t B, int64_t H, int64_t N, void *workspace, void *stream);
+
 /* Fraction of k_f that a cut-off pattern zeroes (Appendix A.4): k_f is viewed
  * as an ndim-dimensional array of shape dims[0..ndim) and, in every dimension
  * i, the last cuts[i] indices are set to zero (cuts[i] = how much of that

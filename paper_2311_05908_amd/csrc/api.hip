@@ -135,7 +135,7 @@ size_t fftconv_workspace_bytes(const fftconv_plan *p, int64_t B)
 }
 
 static int filter_fft_impl(const fftconv_plan *p, const float *k, int64_t Nk, const uint8_t *block_keep,
-                           int64_t n_blocks, void *k_f, void *stream, const char *who)
+                           int64_t n_blocks, void *k_f, void *stream, const char *who, bool adjoint = false)
 {
     int rc = check_plan(p, who);
     if (rc) return rc;
@@ -161,7 +161,7 @@ static int filter_fft_impl(const fftconv_plan *p, const float *k, int64_t Nk, co
     for (int64_t h0 = 0; h0 < p->H; h0 += p->filt_chunk) {
         int64_t nh = p->H - h0 < p->filt_chunk ? p->H - h0 : p->filt_chunk;
         double2 *spec = nullptr;
-        rc = staged_filter_transform(p, k, Nk, h0, nh, s, &spec);
+        rc = staged_filter_transform(p, k, Nk, h0, nh, s, &spec, adjoint);
         if (rc) return rc;
         switch (p->path) {
         case PATH_FUSED3: rc = fused3_pack_kf(p, spec, h0, nh, keep_dev, n_blocks, k_f, s); break;
@@ -172,7 +172,7 @@ static int filter_fft_impl(const fftconv_plan *p, const float *k, int64_t Nk, co
     }
     // a short filter of a plan that can run partial convolutions as short segments: add the
     // short transform's spectrum behind the dense one
-    if (!block_keep && fused3_short_ok(p, Nk)) {
+    if (!block_keep && !adjoint && fused3_short_ok(p, Nk)) {
         for (int64_t h0 = 0; h0 < p->H; h0 += p->filt_chunk) {
             int64_t nh = p->H - h0 < p->filt_chunk ? p->H - h0 : p->filt_chunk;
             double2 *spec = nullptr;
@@ -245,6 +245,47 @@ int fftconv_forward(const fftconv_plan *p, const void *u, const void *k_f, void 
     default:
         return staged_forward(p, u, k_f, y, B, workspace, s);
     }
+}
+
+int fftconv_filter_fft_adjoint(const fftconv_plan *p, const float *k, int64_t Nk, void *k_f, void *stream)
+{
+    return filter_fft_impl(p, k, Nk, nullptr, 1, k_f, stream, "fftconv_filter_fft_adjoint", true);
+}
+
+int fftconv_backward_input(const fftconv_plan *p, const void *dy, const void *k_f_adjoint, void *du, int64_t B,
+                           int64_t H, int64_t N, void *workspace, void *stream)
+{
+    int rc = forward_check(p, dy, k_f_adjoint, du, B, H, N, workspace, "fftconv_backward_input");
+    if (rc || B == 0) return rc;
+    // the same kernels as the forward pass: du = iFFT(FFT(pad(dy)) . conj(k_f))[0:N]
+    return fftconv_forward(p, dy, k_f_adjoint, du, B, H, N, workspace, stream);
+}
+
+size_t fftconv_workspace_bytes_backward_filter(const fftconv_plan *p, int64_t B)
+{
+    if (!p || B <= 0) return 0;
+    return staged_backward_filter_bytes(p);
+}
+
+int fftconv_backward_filter(const fftconv_plan *p, const void *u, const void *dy, float *dk, int64_t Nk, int64_t B,
+                            int64_t H, int64_t N, void *workspace, void *stream)
+{
+    int rc = check_plan(p, "fftconv_backward_filter");
+    if (rc) return rc;
+    if (B < 0 || H != p->H || N != p->N) {
+        set_error("fftconv_backward_filter: B=%lld must be >= 0 and (H=%lld, N=%lld) equal the plan's (H=%lld, N=%lld)",
+                  (long long)B, (long long)H, (long long)N, (long long)p->H, (long long)p->N);
+        return FFTCONV_EINVAL;
+    }
+    if (Nk < 1 || Nk > p->M) {
+        set_error("fftconv_backward_filter: Nk=%lld must satisfy 1 <= Nk <= fft_size", (long long)Nk);
+        return FFTCONV_EINVAL;
+    }
+    if (!dk || (B > 0 && (!u || !dy || !workspace))) {
+        set_error("fftconv_backward_filter: u, dy, dk and workspace must not be NULL");
+        return FFTCONV_EINVAL;
+    }
+    return staged_backward_filter(p, u, dy, dk, Nk, B, workspace, (hipStream_t)stream);
 }
 
 int fftconv_forward_partial(const fftconv_plan *p, const void *u, const void *k_f, void *y, int64_t B, int64_t H,

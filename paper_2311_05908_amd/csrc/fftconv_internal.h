@@ -107,8 +107,9 @@ int staged_forward(const fftconv_plan *p, const void *u, const void *kf, void *y
                    void *workspace, hipStream_t s);
 // fp64 transform of zero-padded filters into p->filt_a for channels [h0, h0+nh):
 // on return filt_a holds position-ordered spectra (position -> frequency via staged_pos_to_freq).
+// adjoint: the spectrum of the circularly time-reversed filter (= the conjugate spectrum)
 int staged_filter_transform(const fftconv_plan *p, const float *k, int64_t Nk, int64_t h0, int64_t nh,
-                            hipStream_t s, double2 **result);
+                            hipStream_t s, double2 **result, bool adjoint = false);
 // scatter of the fp64 spectra into the staged path's own k_f layout
 int staged_pack_kf(const fftconv_plan *p, const double2 *spec, int64_t h0, int64_t nh,
                    const uint8_t *keep_dev, int64_t n_blocks, void *kf, hipStream_t s);
@@ -172,6 +173,12 @@ int fused3_forward_gated(const fftconv_plan *p, const void *u, const void *w, co
                          int64_t B, hipStream_t s);
 // out[i] = a[i] * b[i] rounded to the I/O dtype (staged.hip); out may alias a
 int gate_multiply(int dtype, const void *a, const void *b, void *out, int64_t n, hipStream_t s);
+
+// filter gradient dk[h,t] = sum_b sum_i dy[b,h,i] upad[b,h,(i-t) mod M], t < Nk, through the generic
+// one-kernel-per-stage transforms in fp32 (staged.hip); any plan
+size_t staged_backward_filter_bytes(const fftconv_plan *p);
+int staged_backward_filter(const fftconv_plan *p, const void *u, const void *dy, float *dk, int64_t Nk, int64_t B,
+                           void *workspace, hipStream_t s);
 
 // ---- multi-pass path (multipass.hip)
 bool multipass_supported(int64_t N, int64_t M, int dtype);

@@ -56,11 +56,14 @@ __device__ __forceinline__ void store_real(__hip_bfloat16 *p, int64_t i, float v
 
 // Zero-padded real input -> complex buffer (imaginary part 0, zeros for n >= len).
 template <typename V, typename In>
-__global__ void k_load_padded(const In *src, V *dst, int64_t len, int64_t M, int64_t nrows)
+__global__ void k_load_padded(const In *src, V *dst, int64_t len, int64_t M, int64_t nrows, bool reversed = false)
 {
     int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= nrows * M) return;
     int64_t row = idx / M, n = idx % M;
+    // reversed: position n holds tap (M - n) mod M, the circularly time-reversed sequence, whose
+    // spectrum is the conjugate of the original's (real input)
+    if (reversed && n != 0) n = M - n;
     V v;
     v.x = n < len ? (decltype(v.x))load_real(src, row * len + n) : 0;
     v.y = 0;
@@ -299,11 +302,11 @@ int staged_forward(const fftconv_plan *p, const void *u, const void *kf, void *y
 }
 
 int staged_filter_transform(const fftconv_plan *p, const float *k, int64_t Nk, int64_t h0, int64_t nh, hipStream_t s,
-                            double2 **result)
+                            double2 **result, bool adjoint)
 {
     const int bs = 256;
     hipLaunchKernelGGL((k_load_padded<double2, float>), dim3(grid_for(nh * p->M, bs)), dim3(bs), 0, s, k + h0 * Nk,
-                       p->filt_a, Nk, p->M, nh);
+                       p->filt_a, Nk, p->M, nh, adjoint);
     FC_HIP(hipGetLastError());
     return run_stages_fwd<double2>(fac_list(p), p->M, 1, p->filt_a, p->filt_b, p->st.w64, nh, s, result);
 }
@@ -350,6 +353,115 @@ FacList staged_fac_list(const fftconv_plan *p)
     fl.nf = p->st.nf;
     for (int i = 0; i < MAX_FACTORS; ++i) fl.fac[i] = (int)p->st.fac[i];
     return fl;
+}
+
+// ---- filter gradient (backward pass, Section 3.1 "Kernel Fusion and Recomputation"):
+//   dk_f[h] = sum_b conj(FFT(pad(u[b,h]))) . FFT(pad(dy[b,h]))   (reduction over the batch in frequency space,
+//   nothing of the forward pass is stored), dk[h] = Re(iFFT(dk_f[h]))[0:Nk].
+// acc[h, p] (+)= conj(xu[r, p]) * xdy[r, p] for the rows r of one batch index (distinct channels, so no two
+// threads meet and the sum over b runs in a fixed order)
+__global__ void k_accumulate_corr(float2 *acc, const float2 *xu, const float2 *xdy, int64_t M, int64_t nrows, bool first)
+{
+    int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= nrows * M) return;
+    const float2 a = xu[idx], b = xdy[idx];
+    float2 v = make_float2(a.x * b.x + a.y * b.y, a.x * b.y - a.y * b.x);
+    if (!first) {
+        const float2 o = acc[idx];
+        v.x += o.x;
+        v.y += o.y;
+    }
+    acc[idx] = v;
+}
+
+__global__ void k_zero_f32(float *x, int64_t n)
+{
+    int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx < n) x[idx] = 0.f;
+}
+
+__global__ void k_store_dk(const float2 *x, float *dk, int64_t Nk, int64_t M, int64_t nrows, float scale)
+{
+    int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= nrows * Nk) return;
+    int64_t row = idx / Nk, t = idx % Nk;
+    dk[idx] = x[row * M + t].x * scale;
+}
+
+static int64_t bwd_chunk(const fftconv_plan *p) { return p->H < p->fwd_chunk_cap ? p->H : p->fwd_chunk_cap; }
+
+size_t staged_backward_filter_bytes(const fftconv_plan *p)
+{
+    // dk_f accumulator for every channel + two ping-pong pairs (u and dy) of one chunk of channels
+    return (size_t)((p->H + 4 * bwd_chunk(p)) * p->M) * sizeof(float2);
+}
+
+template <typename IO>
+static int staged_backward_filter_t(const fftconv_plan *p, const IO *u, const IO *dy, float *dk, int64_t Nk, int64_t B,
+                                    void *workspace, hipStream_t s)
+{
+    const int bs = 256;
+    const int64_t M = p->M, N = p->N, H = p->H, chunk = bwd_chunk(p);
+    float2 *acc = (float2 *)workspace;
+    float2 *a1 = acc + H * M, *b1 = a1 + chunk * M, *a2 = b1 + chunk * M, *b2 = a2 + chunk * M;
+    if (B == 0) {                                 // an empty batch: dk = 0
+        hipLaunchKernelGGL(k_zero_f32, dim3(grid_for(H * Nk, bs)), dim3(bs), 0, s, dk, H * Nk);
+        FC_HIP(hipGetLastError());
+        return FFTCONV_OK;
+    }
+    for (int64_t b = 0; b < B; ++b)
+        for (int64_t h0 = 0; h0 < H; h0 += chunk) {
+            const int64_t nrows = H - h0 < chunk ? H - h0 : chunk;
+            const int64_t row0 = b * H + h0;
+            float2 *xu = nullptr, *xdy = nullptr;
+            hipLaunchKernelGGL((k_load_padded<float2, IO>), dim3(grid_for(nrows * M, bs)), dim3(bs), 0, s, u + row0 * N,
+                               a1, N, M, nrows, false);
+            FC_HIP(hipGetLastError());
+            int rc = run_stages_fwd<float2>(fac_list(p), M, 1, a1, b1, p->st.w32, nrows, s, &xu);
+            if (rc) return rc;
+            hipLaunchKernelGGL((k_load_padded<float2, IO>), dim3(grid_for(nrows * M, bs)), dim3(bs), 0, s, dy + row0 * N,
+                               a2, N, M, nrows, false);
+            FC_HIP(hipGetLastError());
+            rc = run_stages_fwd<float2>(fac_list(p), M, 1, a2, b2, p->st.w32, nrows, s, &xdy);
+            if (rc) return rc;
+            hipLaunchKernelGGL(k_accumulate_corr, dim3(grid_for(nrows * M, bs)), dim3(bs), 0, s, acc + h0 * M, xu, xdy, M,
+                               nrows, b == 0);
+            FC_HIP(hipGetLastError());
+        }
+    for (int64_t h0 = 0; h0 < H; h0 += chunk) {
+        const int64_t nrows = H - h0 < chunk ? H - h0 : chunk;
+        float2 *src = acc + h0 * M, *dst = a1;
+        int64_t S = 1, R = M;
+        for (int i = p->st.nf - 1; i >= 0; --i) {
+            const int Nj = (int)p->st.fac[i];
+            R /= Nj;
+            hipLaunchKernelGGL(k_stage_inv<float2>, dim3(grid_for(nrows * M, bs)), dim3(bs), 0, s, src, dst, p->st.w32, M,
+                               Nj, S, R, nrows);
+            FC_HIP(hipGetLastError());
+            S *= Nj;
+            float2 *t = src;
+            src = dst;
+            dst = t;
+        }
+        hipLaunchKernelGGL(k_store_dk, dim3(grid_for(nrows * Nk, bs)), dim3(bs), 0, s, src, dk + h0 * Nk, Nk, M, nrows,
+                           1.0f / (float)M);
+        FC_HIP(hipGetLastError());
+    }
+    return FFTCONV_OK;
+}
+
+int staged_backward_filter(const fftconv_plan *p, const void *u, const void *dy, float *dk, int64_t Nk, int64_t B,
+                           void *workspace, hipStream_t s)
+{
+    switch (p->dtype) {
+    case FFTCONV_F32:
+        return staged_backward_filter_t<float>(p, (const float *)u, (const float *)dy, dk, Nk, B, workspace, s);
+    case FFTCONV_F16:
+        return staged_backward_filter_t<__half>(p, (const __half *)u, (const __half *)dy, dk, Nk, B, workspace, s);
+    default:
+        return staged_backward_filter_t<__hip_bfloat16>(p, (const __hip_bfloat16 *)u, (const __hip_bfloat16 *)dy, dk, Nk,
+                                                        B, workspace, s);
+    }
 }
 
 // Elementwise gate of the gated convolution for plans without a fused-gate kernel:

@@ -22,6 +22,8 @@ EXPORTS = [
     "fftconv_filter_fft", "fftconv_forward", "fftconv_forward_partial", "fftconv_filter_fft_sparse",
     "fftconv_forward_freq_sparse", "fftconv_sparsity_fraction", "fftconv_plan_path", "fftconv_plan_factors",
     "fftconv_strerror", "fftconv_last_error", "fftconv_workspace_bytes_gated", "fftconv_forward_gated",
+    "fftconv_filter_fft_adjoint", "fftconv_backward_input", "fftconv_workspace_bytes_backward_filter",
+    "fftconv_backward_filter",
 ]
 
 _lib = None
@@ -69,6 +71,14 @@ def load():
     lib.fftconv_workspace_bytes_gated.restype = ctypes.c_size_t
     lib.fftconv_forward_gated.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, vp, vp]
     lib.fftconv_forward_gated.restype = ci
+    lib.fftconv_filter_fft_adjoint.argtypes = [vp, vp, i64, vp, vp]
+    lib.fftconv_filter_fft_adjoint.restype = ci
+    lib.fftconv_backward_input.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, vp]
+    lib.fftconv_backward_input.restype = ci
+    lib.fftconv_workspace_bytes_backward_filter.argtypes = [vp, i64]
+    lib.fftconv_workspace_bytes_backward_filter.restype = ctypes.c_size_t
+    lib.fftconv_backward_filter.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, vp, vp]
+    lib.fftconv_backward_filter.restype = ci
     lib.fftconv_sparsity_fraction.argtypes = [ctypes.POINTER(i64), ctypes.POINTER(i64), ci]
     lib.fftconv_sparsity_fraction.restype = ctypes.c_double
     lib.fftconv_plan_path.argtypes = [vp]
@@ -201,6 +211,37 @@ class Plan:
                                                u.shape[0], self.H, self.N, None if ws is None else ws.data_ptr(),
                                                _stream_ptr()))
         return y
+
+    def filter_fft_adjoint(self, k: torch.Tensor) -> torch.Tensor:
+        """fftconv_filter_fft_adjoint: the k_f buffer fftconv_backward_input takes."""
+        self._check_k(k)
+        kf = torch.empty(self.kf_bytes(), dtype=torch.uint8, device=k.device)
+        _check(self._lib.fftconv_filter_fft_adjoint(self._h, k.data_ptr(), k.shape[1], kf.data_ptr(), _stream_ptr()))
+        return kf
+
+    def backward_input(self, dy, kf_adjoint, out=None):
+        """fftconv_backward_input: du."""
+        self._check_u(dy)
+        du = torch.empty_like(dy) if out is None else out
+        ws = self._workspace(dy.shape[0], dy.device)
+        _check(self._lib.fftconv_backward_input(self._h, dy.data_ptr(), kf_adjoint.data_ptr(), du.data_ptr(),
+                                                dy.shape[0], self.H, self.N, None if ws is None else ws.data_ptr(),
+                                                _stream_ptr()))
+        return du
+
+    def backward_filter(self, u, dy, Nk: int, out=None):
+        """fftconv_backward_filter: dk, (H, Nk) fp32."""
+        self._check_u(u)
+        self._check_u(dy)
+        if u.shape != dy.shape:
+            raise ValueError("u and dy differ in shape")
+        dk = torch.empty((self.H, int(Nk)), dtype=torch.float32, device=u.device) if out is None else out
+        need = int(self._lib.fftconv_workspace_bytes_backward_filter(self._h, u.shape[0]))
+        if getattr(self, "_ws_bk", None) is None or self._ws_bk.numel() < need or self._ws_bk.device != u.device:
+            self._ws_bk = torch.empty(max(need, 1), dtype=torch.uint8, device=u.device)
+        _check(self._lib.fftconv_backward_filter(self._h, u.data_ptr(), dy.data_ptr(), dk.data_ptr(), int(Nk),
+                                                 u.shape[0], self.H, self.N, self._ws_bk.data_ptr(), _stream_ptr()))
+        return dk
 
     def forward_partial(self, u, kf, Nk: int, out=None):
         """fftconv_forward_partial."""

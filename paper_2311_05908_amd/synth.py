@@ -90,12 +90,13 @@ def gen_u(w: Workload, b_indices=None) -> torch.Tensor:
 
 
 def gen_gate(w: Workload, which: str, b_indices=None) -> torch.Tensor:
-    """Gate tensor of the gated convolution ("w": input gate, "v": output gate): N(0,1) per element,
+    """Gate tensor of the gated convolution ("w": input gate, "v": output gate) or upstream gradient of
+    the backward pass ("dy"): N(0,1) per element,
     rounded to the I/O dtype, one counter-based stream per batch row like gen_u.  Stands in for the
     linear projections of the layer input that Hyena / M2 use as gates."""
     if b_indices is None:
         b_indices = range(w.B)
-    seed = w.seed_u + {"w": 100, "v": 200}[which]
+    seed = w.seed_u + {"w": 100, "v": 200, "dy": 300}[which]
     rows = []
     for b in b_indices:
         g = np.random.Generator(np.random.Philox(key=[seed, int(b)]))

@@ -1,0 +1,84 @@
+"""Backward pass through the C ABI against the CPU oracle: du (the forward kernels on the adjoint
+spectrum) and dk (batch reduction in frequency space)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2311_05908_amd import fftconv, synth
+from parity_util import TOL
+
+pytestmark = pytest.mark.gpu
+W = synth.WORKLOADS
+
+SHAPES = [
+    ("f32", 2, 3, 256, 512, 256),       # staged
+    ("f32", 3, 2, 300, 1024, 100),      # staged, ragged N, short filter
+    ("f32", 2, 2, 256, 256, 256),       # fft_size = N: the wrapped taps take part
+    ("bf16", 3, 2, 4096, 8192, 4096),   # fused 8192, odd batch
+    ("f16", 2, 3, 4096, 8192, 1000),
+    ("bf16", 2, 2, 8192, 16384, 8192),  # fused 16384
+    ("f16", 2, 1, 16384, 32768, 16384), # fused 32768
+    ("bf16", 1, 1, 32768, 65536, 4096), # multi-pass
+]
+
+
+@pytest.mark.parametrize("dtype,B,H,N,M,Nk", SHAPES)
+def test_backward_input_and_filter(dtype, B, H, N, M, Nk):
+    w = synth.scaled(W["cfg1"], B=B, H=H, N=N, fft_size=M, dtype=dtype, alpha=(1e-3, 1e-2))
+    u = synth.gen_u(w)
+    dy = synth.gen_gate(w, "dy")
+    k = synth.gen_k(w)[:, :Nk].copy()
+    plan = fftconv.Plan(N, M, H, dtype)
+    kd = torch.from_numpy(k).cuda()
+    kfa = plan.filter_fft_adjoint(kd)
+    du = plan.backward_input(dy.cuda(), kfa)
+    dk = plan.backward_filter(u.cuda(), dy.cuda(), Nk)
+    torch.cuda.synchronize()
+    assert torch.isfinite(du.float()).all() and torch.isfinite(dk).all()
+    du_ref = oracle.backward_u(dy.double().numpy(), k, M)
+    dk_ref = oracle.backward_k(u.double().numpy(), dy.double().numpy(), M, Nk)
+    e_u = float(oracle.rel_l2_per_sequence(du.cpu().double().numpy(), du_ref).max())
+    e_k = float(oracle.rel_l2_per_sequence(dk.cpu().double().numpy(), dk_ref).max())
+    print("backward %s B=%d H=%d N=%d M=%d Nk=%d path=%s du err=%.3e dk err=%.3e" % (dtype, B, H, N, M, Nk, plan.path, e_u, e_k),
+          flush=True)
+    assert e_u <= TOL[dtype]
+    assert e_k <= TOL["f32"]            # dk is computed in fp32 from the (exact) 16-bit inputs
+    # the forward pass on the same plan still sees the ordinary spectrum
+    y = plan.forward(u.cuda(), plan.filter_fft(kd))
+    y_ref = oracle.fftconv(u.double().numpy(), k, M)
+    assert float(oracle.rel_l2_per_sequence(y.cpu().double().numpy(), y_ref).max()) <= TOL[dtype]
+
+
+def test_backward_empty_batch_and_errors():
+    plan = fftconv.Plan(256, 512, 2, "f32")
+    u = torch.zeros((0, 2, 256), device="cuda")
+    dk = plan.backward_filter(u, u, 16)
+    assert dk.shape == (2, 16) and float(dk.abs().max()) == 0.0
+    lib = fftconv.load()
+    x = torch.zeros((1, 2, 256), device="cuda")
+    out = torch.zeros((2, 16), device="cuda")
+    assert lib.fftconv_backward_filter(plan._h, x.data_ptr(), x.data_ptr(), out.data_ptr(), 0, 1, 2, 256, x.data_ptr(), None) == -1
+    assert lib.fftconv_backward_filter(plan._h, x.data_ptr(), x.data_ptr(), out.data_ptr(), 16, 1, 2, 256, None, None) == -1
+    assert lib.fftconv_backward_filter(plan._h, x.data_ptr(), x.data_ptr(), out.data_ptr(), 16, 1, 3, 256, x.data_ptr(), None) == -1
+
+
+def test_backward_cfg2_full_size_sampled():
+    w = W["cfg2"]
+    u = synth.gen_u(w)
+    dy = synth.gen_gate(w, "dy")
+    k = synth.gen_k(w)
+    plan = fftconv.Plan(w.N, w.fft_size, w.H, w.dtype)
+    du = plan.backward_input(dy.cuda(), plan.filter_fft_adjoint(torch.from_numpy(k).cuda()))
+    dk = plan.backward_filter(u.cuda(), dy.cuda(), w.N)
+    torch.cuda.synchronize()
+    worst_u = 0.0
+    for b, h in synth.sample_sequences(w, 20):
+        ref = oracle.backward_u(dy[b, h].double().numpy()[None, None], k[h][None], w.fft_size)[0, 0]
+        worst_u = max(worst_u, float(oracle.rel_l2_per_sequence(du[b, h].cpu().double().numpy(), ref)))
+    worst_k = 0.0
+    for h in (0, 401, w.H - 1):
+        ref = oracle.backward_k(u[:, h:h + 1].double().numpy(), dy[:, h:h + 1].double().numpy(), w.fft_size, w.N)[0]
+        worst_k = max(worst_k, float(oracle.rel_l2_per_sequence(dk[h].cpu().double().numpy(), ref)))
+    print("backward cfg2 full: du worst rel L2 = %.3e, dk worst rel L2 = %.3e" % (worst_u, worst_k), flush=True)
+    assert worst_u <= TOL[w.dtype] and worst_k <= TOL["f32"]
