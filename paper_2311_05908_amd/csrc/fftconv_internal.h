@@ -180,6 +180,16 @@ size_t staged_backward_filter_bytes(const fftconv_plan *p);
 int staged_backward_filter(const fftconv_plan *p, const void *u, const void *dy, float *dk, int64_t Nk, int64_t B,
                            void *workspace, hipStream_t s);
 
+int staged_inverse_to_dk(const fftconv_plan *p, float2 *spec, float2 *other, int64_t nrows, float *dk, int64_t Nk,
+                         hipStream_t s);
+int64_t staged_backward_chunk(const fftconv_plan *p);
+// fused filter gradient of the 8192-point plans (fused3_dk.hip)
+namespace f3 {
+bool fused3_dk_supported(const fftconv_plan *p);
+int fused3_dk_accumulate(const fftconv_plan *p, const void *u, const void *dy, void *dkf, int64_t B, hipStream_t s);
+int fused3_dk_unpack(const fftconv_plan *p, const void *dkf, void *spec, int64_t h0, int64_t nh, hipStream_t s);
+}  // namespace f3
+
 // ---- multi-pass path (multipass.hip)
 bool multipass_supported(int64_t N, int64_t M, int dtype);
 int multipass_init(fftconv_plan *p);

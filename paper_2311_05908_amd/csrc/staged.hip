@@ -390,6 +390,34 @@ __global__ void k_store_dk(const float2 *x, float *dk, int64_t Nk, int64_t M, in
 
 static int64_t bwd_chunk(const fftconv_plan *p) { return p->H < p->fwd_chunk_cap ? p->H : p->fwd_chunk_cap; }
 
+// dk rows from position-ordered spectra: unnormalised inverse stages (ping-pong between spec and other,
+// both nrows * M), real part of the first Nk samples, times 1/M.  spec is overwritten.
+int staged_inverse_to_dk(const fftconv_plan *p, float2 *spec, float2 *other, int64_t nrows, float *dk, int64_t Nk,
+                         hipStream_t s)
+{
+    const int bs = 256;
+    const int64_t M = p->M;
+    float2 *src = spec, *dst = other;
+    int64_t S = 1, R = M;
+    for (int i = p->st.nf - 1; i >= 0; --i) {
+        const int Nj = (int)p->st.fac[i];
+        R /= Nj;
+        hipLaunchKernelGGL(k_stage_inv<float2>, dim3(grid_for(nrows * M, bs)), dim3(bs), 0, s, src, dst, p->st.w32, M, Nj,
+                           S, R, nrows);
+        FC_HIP(hipGetLastError());
+        S *= Nj;
+        float2 *t = src;
+        src = dst;
+        dst = t;
+    }
+    hipLaunchKernelGGL(k_store_dk, dim3(grid_for(nrows * Nk, bs)), dim3(bs), 0, s, src, dk, Nk, M, nrows,
+                       1.0f / (float)M);
+    FC_HIP(hipGetLastError());
+    return FFTCONV_OK;
+}
+
+int64_t staged_backward_chunk(const fftconv_plan *p) { return bwd_chunk(p); }
+
 size_t staged_backward_filter_bytes(const fftconv_plan *p)
 {
     // dk_f accumulator for every channel + two ping-pong pairs (u and dy) of one chunk of channels
@@ -430,22 +458,8 @@ static int staged_backward_filter_t(const fftconv_plan *p, const IO *u, const IO
         }
     for (int64_t h0 = 0; h0 < H; h0 += chunk) {
         const int64_t nrows = H - h0 < chunk ? H - h0 : chunk;
-        float2 *src = acc + h0 * M, *dst = a1;
-        int64_t S = 1, R = M;
-        for (int i = p->st.nf - 1; i >= 0; --i) {
-            const int Nj = (int)p->st.fac[i];
-            R /= Nj;
-            hipLaunchKernelGGL(k_stage_inv<float2>, dim3(grid_for(nrows * M, bs)), dim3(bs), 0, s, src, dst, p->st.w32, M,
-                               Nj, S, R, nrows);
-            FC_HIP(hipGetLastError());
-            S *= Nj;
-            float2 *t = src;
-            src = dst;
-            dst = t;
-        }
-        hipLaunchKernelGGL(k_store_dk, dim3(grid_for(nrows * Nk, bs)), dim3(bs), 0, s, src, dk + h0 * Nk, Nk, M, nrows,
-                           1.0f / (float)M);
-        FC_HIP(hipGetLastError());
+        int rc = staged_inverse_to_dk(p, acc + h0 * M, a1, nrows, dk + h0 * Nk, Nk, s);
+        if (rc) return rc;
     }
     return FFTCONV_OK;
 }

@@ -17,6 +17,8 @@ SHAPES = [
     ("f32", 2, 2, 256, 256, 256),       # fft_size = N: the wrapped taps take part
     ("bf16", 3, 2, 4096, 8192, 4096),   # fused 8192, odd batch
     ("f16", 2, 3, 4096, 8192, 1000),
+    ("bf16", 8, 5, 4096, 8192, 4096),   # several pairs per channel, channels shared out over workgroups
+    ("bf16", 1, 2, 1000, 8192, 1000),   # B = 1, ragged N
     ("bf16", 2, 2, 8192, 16384, 8192),  # fused 16384
     ("f16", 2, 1, 16384, 32768, 16384), # fused 32768
     ("bf16", 1, 1, 32768, 65536, 4096), # multi-pass
@@ -43,7 +45,8 @@ def test_backward_input_and_filter(dtype, B, H, N, M, Nk):
     print("backward %s B=%d H=%d N=%d M=%d Nk=%d path=%s du err=%.3e dk err=%.3e" % (dtype, B, H, N, M, Nk, plan.path, e_u, e_k),
           flush=True)
     assert e_u <= TOL[dtype]
-    assert e_k <= TOL["f32"]            # dk is computed in fp32 from the (exact) 16-bit inputs
+    # 8192-point plans transform u and dy on the matrix cores (16-bit operands); the others in fp32
+    assert e_k <= (TOL[dtype] if (plan.path == "fused3" and M == 8192) else TOL["f32"])
     # the forward pass on the same plan still sees the ordinary spectrum
     y = plan.forward(u.cuda(), plan.filter_fft(kd))
     y_ref = oracle.fftconv(u.double().numpy(), k, M)
@@ -81,4 +84,4 @@ def test_backward_cfg2_full_size_sampled():
         ref = oracle.backward_k(u[:, h:h + 1].double().numpy(), dy[:, h:h + 1].double().numpy(), w.fft_size, w.N)[0]
         worst_k = max(worst_k, float(oracle.rel_l2_per_sequence(dk[h].cpu().double().numpy(), ref)))
     print("backward cfg2 full: du worst rel L2 = %.3e, dk worst rel L2 = %.3e" % (worst_u, worst_k), flush=True)
-    assert worst_u <= TOL[w.dtype] and worst_k <= TOL["f32"]
+    assert worst_u <= TOL[w.dtype] and worst_k <= TOL[w.dtype]
