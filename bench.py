@@ -74,6 +74,38 @@ def time_oracle(w, u_cpu, k, budget_s=12.0):
     }
 
 
+def sweep(torch, fftconv, synth, dev, args):
+    """Causal forward pass, bf16, N = fft/2, B*H*N = 2^27 elements at every size (B*H >= 1)."""
+    for lg in range(8, 23):
+        M = 1 << lg
+        N = M // 2
+        rows = max(1, (1 << 27) // N)
+        H = min(768, rows)
+        B = max(1, rows // H)
+        plan = fftconv.Plan(N, M, H, "bf16")
+        g = torch.Generator(device="cpu").manual_seed(lg)
+        k = (torch.randn(H, N, generator=g) * torch.exp(-1e-3 * torch.arange(N))[None]).to(dev)
+        kf = plan.filter_fft(k)
+        u = torch.randn(B, H, N, generator=g).to(torch.bfloat16).to(dev)
+        y = torch.empty_like(u)
+        steps = max(3, min(args.steps, 20))
+        for _ in range(3):
+            plan.forward(u, kf, out=y)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            plan.forward(u, kf, out=y)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / steps
+        nbytes = 2 * B * H * N * 2 + H * M * 4
+        print(json.dumps({"fft_size": M, "N": N, "B": B, "H": H, "path": plan.path, "factors": plan.factors,
+                          "ms_per_step": ms, "sequences_per_ms": B * H / ms, "achieved_TBps": nbytes / ms / 1e9}),
+              flush=True)
+        del plan, kf, u, y, k
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -83,6 +115,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=300)
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sweep", action="store_true",
+                    help="forward pass over every power-of-two fft size 256 .. 4M at a fixed amount of data "
+                         "(one JSON line per size; not the headline metric)")
     ap.add_argument("--backward", action="store_true",
                     help="time the backward pass (du and dk) instead (not the headline metric)")
     ap.add_argument("--gated", action="store_true",
@@ -102,9 +137,12 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
-    w = synth.WORKLOADS[args.workload]
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.sweep:
+        sweep(torch, fftconv, synth, dev, args)
+        return
+    w = synth.WORKLOADS[args.workload]
 
     t0 = time.perf_counter()
     u_cpu = synth.gen_u(w)

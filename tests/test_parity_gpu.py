@@ -202,3 +202,16 @@ def test_frequency_sparse_masks_fft16384(keep_blocks):
         err, plan = check_all_sequences(w, variant=variant)
         print("freq-sparse keep=%s %s path=%s err=%.3e" % (keep_blocks, variant, plan.path, err), flush=True)
         assert err <= TOL[w.dtype]
+
+
+# ---------------------------------------------------------------- every transform length the plan accepts
+
+@pytest.mark.parametrize("lg", list(range(8, 23)))
+def test_every_power_of_two_fft_size_sampled_positions(lg):
+    """fft_size = 256 .. 4M (the paper's range), causal N = fft_size/2, bf16: all paths in turn."""
+    from parity_util import check_sampled_positions
+    M = 1 << lg
+    w = synth.scaled(W["cfg4"], B=2, H=2, N=M // 2, fft_size=M, dtype="bf16", alpha=(1e-4, 1e-4))
+    err, plan = check_sampled_positions(w, n_pos=16)
+    print("fft 2^%d path=%s factors=%s err=%.3e" % (lg, plan.path, plan.factors, err), flush=True)
+    assert err <= TOL["bf16"]
