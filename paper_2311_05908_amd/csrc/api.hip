@@ -86,7 +86,10 @@ int fftconv_plan_create(fftconv_plan **out, int64_t N, int64_t fft_size, int64_t
         rc = FFTCONV_ENOMEM;
     }
     if (rc == FFTCONV_OK) {
-        if (fused3_supported(N, fft_size, dtype)) {
+        if (small_supported(N, fft_size, dtype)) {
+            p->path = PATH_SMALL;
+            rc = small_init(p);
+        } else if (fused3_supported(N, fft_size, dtype)) {
             p->path = PATH_FUSED3;
             rc = fused3_init(p);
         } else if (multipass_supported(N, fft_size, dtype)) {
@@ -120,6 +123,7 @@ size_t fftconv_kf_bytes(const fftconv_plan *p)
     switch (p->path) {
     case PATH_FUSED3: return fused3_kf_bytes(p);
     case PATH_MULTIPASS: return multipass_kf_bytes(p);
+    case PATH_SMALL: return small_kf_bytes(p);
     default: return staged_kf_bytes(p);
     }
 }
@@ -129,6 +133,7 @@ size_t fftconv_workspace_bytes(const fftconv_plan *p, int64_t B)
     if (!p || B <= 0) return 0;
     switch (p->path) {
     case PATH_FUSED3: return 0;
+    case PATH_SMALL: return 0;
     case PATH_MULTIPASS: return multipass_workspace_bytes(p, B);
     default: return staged_workspace_bytes(p, B);
     }
@@ -166,6 +171,7 @@ static int filter_fft_impl(const fftconv_plan *p, const float *k, int64_t Nk, co
         switch (p->path) {
         case PATH_FUSED3: rc = fused3_pack_kf(p, spec, h0, nh, keep_dev, n_blocks, k_f, s); break;
         case PATH_MULTIPASS: rc = multipass_pack_kf(p, spec, h0, nh, keep_dev, n_blocks, k_f, s); break;
+        case PATH_SMALL: rc = small_pack_kf(p, spec, h0, nh, keep_dev, n_blocks, k_f, s); break;
         default: rc = staged_pack_kf(p, spec, h0, nh, keep_dev, n_blocks, k_f, s); break;
         }
         if (rc) return rc;
@@ -242,6 +248,8 @@ int fftconv_forward(const fftconv_plan *p, const void *u, const void *k_f, void 
         return fused3_forward(p, u, k_f, y, B, s);
     case PATH_MULTIPASS:
         return multipass_forward(p, u, k_f, y, B, workspace, s);
+    case PATH_SMALL:
+        return small_forward(p, u, k_f, y, B, s);
     default:
         return staged_forward(p, u, k_f, y, B, workspace, s);
     }
@@ -394,6 +402,7 @@ const char *fftconv_plan_path(const fftconv_plan *p)
     switch (p->path) {
     case PATH_FUSED3: return "fused3";
     case PATH_MULTIPASS: return "multipass";
+    case PATH_SMALL: return "small";
     default: return "staged";
     }
 }
@@ -406,6 +415,12 @@ int fftconv_plan_factors(const fftconv_plan *p, int64_t *factors, int max_factor
         int64_t f[3] = {p->f3.N1, p->f3.N2, p->f3.N3};
         for (; n < 3 && n < max_factors; ++n) factors[n] = f[n];
         return 3;
+    }
+    if (p->path == PATH_SMALL) {
+        int64_t f[3] = {p->f3.N1, p->f3.N2, p->f3.N3};
+        const int nf = p->f3.N3 > 1 ? 3 : 2;
+        for (; n < nf && n < max_factors; ++n) factors[n] = f[n];
+        return nf;
     }
     if (p->path == PATH_MULTIPASS) {
         int64_t f[4] = {p->M / ((int64_t)p->f3.N1 * p->f3.N2 * p->f3.N3), p->f3.N1, p->f3.N2, p->f3.N3};

@@ -1,0 +1,61 @@
+// In-register DFTs of power-of-two length <= 32 on the vector ALUs (fp32), shared by the outer
+// passes of the multi-pass path and by the small-transform kernel.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+namespace fftconv {
+
+// cos / sin of 2 pi j / 32: every twiddle of the transforms below
+__device__ constexpr float C32[32] = {1.000000000f, 0.980785280f, 0.923879533f, 0.831469612f, 0.707106781f, 0.555570233f, 0.382683432f, 0.195090322f, 0.000000000f, -0.195090322f, -0.382683432f, -0.555570233f, -0.707106781f, -0.831469612f, -0.923879533f, -0.980785280f, -1.000000000f, -0.980785280f, -0.923879533f, -0.831469612f, -0.707106781f, -0.555570233f, -0.382683432f, -0.195090322f, -0.000000000f, 0.195090322f, 0.382683432f, 0.555570233f, 0.707106781f, 0.831469612f, 0.923879533f, 0.980785280f};
+__device__ constexpr float S32[32] = {0.000000000f, 0.195090322f, 0.382683432f, 0.555570233f, 0.707106781f, 0.831469612f, 0.923879533f, 0.980785280f, 1.000000000f, 0.980785280f, 0.923879533f, 0.831469612f, 0.707106781f, 0.555570233f, 0.382683432f, 0.195090322f, 0.000000000f, -0.195090322f, -0.382683432f, -0.555570233f, -0.707106781f, -0.831469612f, -0.923879533f, -0.980785280f, -1.000000000f, -0.980785280f, -0.923879533f, -0.831469612f, -0.707106781f, -0.555570233f, -0.382683432f, -0.195090322f};
+
+constexpr int bitrev(int v, int bits)
+{
+    int r = 0;
+    for (int i = 0; i < bits; ++i) r |= ((v >> i) & 1) << (bits - 1 - i);
+    return r;
+}
+constexpr int ilog2(int v) { return v <= 1 ? 0 : 1 + ilog2(v / 2); }
+
+// In-register DFT of length R (power of two <= 32), natural order in and out, unnormalised;
+// INV conjugates the kernel.  Radix-2 decimation in time, fully unrolled so every index and
+// twiddle is a compile-time constant.
+template <int R, bool INV> __device__ __forceinline__ void dft_reg(float2 (&x)[R])
+{
+    constexpr int LG = ilog2(R);
+#pragma unroll
+    for (int i = 0; i < R; ++i) {
+        const int j = bitrev(i, LG);
+        if (j > i) {
+            const float2 t = x[i];
+            x[i] = x[j];
+            x[j] = t;
+        }
+    }
+#pragma unroll
+    for (int len = 2; len <= R; len *= 2) {
+#pragma unroll
+        for (int blk = 0; blk < R; blk += len) {
+#pragma unroll
+            for (int j = 0; j < len / 2; ++j) {
+                const int q = j * (32 / len);                  // twiddle W_32^q, 0 <= q < 16
+                const float2 a = x[blk + j], b = x[blk + j + len / 2];
+                float2 t;
+                if (q == 0) {
+                    t = b;
+                } else if (q == 8) {                           // -i forward, +i inverse
+                    t = INV ? make_float2(-b.y, b.x) : make_float2(b.y, -b.x);
+                } else {
+                    const float wr = C32[q];
+                    const float wi = INV ? S32[q] : -S32[q];
+                    t = make_float2(b.x * wr - b.y * wi, b.x * wi + b.y * wr);
+                }
+                x[blk + j] = make_float2(a.x + t.x, a.y + t.y);
+                x[blk + j + len / 2] = make_float2(a.x - t.x, a.y - t.y);
+            }
+        }
+    }
+}
+
+}  // namespace fftconv

@@ -23,7 +23,7 @@ void set_error(const char *fmt, ...);
         }                                                                                 \
     } while (0)
 
-enum Path { PATH_STAGED = 0, PATH_FUSED3 = 1, PATH_MULTIPASS = 2 };
+enum Path { PATH_STAGED = 0, PATH_FUSED3 = 1, PATH_MULTIPASS = 2, PATH_SMALL = 3 };
 
 constexpr int MAX_FACTORS = 8;
 
@@ -189,6 +189,14 @@ bool fused3_dk_supported(const fftconv_plan *p);
 int fused3_dk_accumulate(const fftconv_plan *p, const void *u, const void *dy, void *dkf, int64_t B, hipStream_t s);
 int fused3_dk_unpack(const fftconv_plan *p, const void *dkf, void *spec, int64_t h0, int64_t nh, hipStream_t s);
 }  // namespace f3
+
+// ---- short transforms, fft_size 256 .. 4096, any dtype (small.hip); radices reported in f3.N1..N3
+bool small_supported(int64_t N, int64_t M, int dtype);
+int small_init(fftconv_plan *p);
+size_t small_kf_bytes(const fftconv_plan *p);
+int small_pack_kf(const fftconv_plan *p, const double2 *spec, int64_t h0, int64_t nh, const uint8_t *keep_dev,
+                  int64_t n_blocks, void *kf, hipStream_t s);
+int small_forward(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, hipStream_t s);
 
 // ---- multi-pass path (multipass.hip)
 bool multipass_supported(int64_t N, int64_t M, int dtype);

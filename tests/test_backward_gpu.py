@@ -12,8 +12,9 @@ pytestmark = pytest.mark.gpu
 W = synth.WORKLOADS
 
 SHAPES = [
-    ("f32", 2, 3, 256, 512, 256),       # staged
-    ("f32", 3, 2, 300, 1024, 100),      # staged, ragged N, short filter
+    ("f32", 2, 3, 256, 512, 256),       # short-transform kernel
+    ("f32", 3, 2, 300, 1024, 100),      # ragged N, short filter
+    ("f32", 2, 2, 4096, 8192, 4096),    # staged
     ("f32", 2, 2, 256, 256, 256),       # fft_size = N: the wrapped taps take part
     ("bf16", 3, 2, 4096, 8192, 4096),   # fused 8192, odd batch
     ("f16", 2, 3, 4096, 8192, 1000),

@@ -53,9 +53,10 @@ def test_gated_fused_fft8192(dtype, B, H, N, use_w, use_v):
 
 
 @pytest.mark.parametrize("dtype,B,H,N,M", [
-    ("f32", 2, 3, 256, 512),        # staged path
+    ("f32", 2, 3, 256, 512),        # short-transform kernel
     ("f32", 3, 2, 300, 1024),
-    ("bf16", 2, 2, 200, 512),       # staged path, 16-bit
+    ("bf16", 2, 2, 200, 512),
+    ("f32", 2, 2, 4096, 8192),      # staged path
     ("bf16", 3, 2, 8192, 16384),    # fused 16384 kernel, gates by elementwise kernels
     ("f16", 2, 2, 16384, 32768),    # fused 32768 kernel
     ("bf16", 2, 1, 32768, 65536),   # multi-pass

@@ -29,6 +29,38 @@ def test_small_shapes_all_dtypes(dtype, B, H, N, M):
     w = synth.scaled(W["cfg2"], B=B, H=H, N=N, fft_size=M, dtype=dtype, alpha=(1e-2, 1e-1))
     err, plan = check_all_sequences(w)
     print("%s B=%d H=%d N=%d M=%d path=%s err=%.3e" % (dtype, B, H, N, M, plan.path, err), flush=True)
+    assert plan.path == "small"
+    assert err <= TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype,B,H,N,M", [
+    ("bf16", 37, 3, 100, 256),       # 16 pairs per workgroup pass, a ragged last group, odd batch
+    ("f16", 9, 5, 256, 512),         # 8 pairs per pass
+    ("f32", 7, 3, 512, 1024),        # 4 pairs per pass
+    ("bf16", 4, 3, 1024, 2048),      # three passes, radices 16, 16, 8
+    ("f32", 3, 2, 4096, 4096),       # one pair per pass, circular
+])
+def test_small_transform_kernel_group_shapes(dtype, B, H, N, M):
+    w = synth.scaled(W["cfg2"], B=B, H=H, N=N, fft_size=M, dtype=dtype, alpha=(1e-2, 1e-1))
+    err, plan = check_all_sequences(w)
+    print("small %s B=%d H=%d N=%d M=%d path=%s factors=%s err=%.3e" % (dtype, B, H, N, M, plan.path, plan.factors, err),
+          flush=True)
+    assert plan.path == "small"
+    assert err <= TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype,B,H,N,M", [
+    ("f32", 2, 2, 4096, 8192),       # fp32 I/O beyond the short-transform kernel
+    ("f32", 1, 2, 5000, 16384),      # ragged N
+    ("bf16", 2, 2, 8192, 8192),      # circular (N > fft/2) with 16-bit I/O
+    ("f16", 3, 1, 4100, 8192),       # N not a multiple of 8
+])
+def test_generic_staged_path(dtype, B, H, N, M):
+    w = synth.scaled(W["cfg2"], B=B, H=H, N=N, fft_size=M, dtype=dtype, alpha=(1e-2, 1e-1))
+    err, plan = check_all_sequences(w)
+    print("staged %s B=%d H=%d N=%d M=%d path=%s factors=%s err=%.3e" % (dtype, B, H, N, M, plan.path, plan.factors, err),
+          flush=True)
+    assert plan.path == "staged"
     assert err <= TOL[dtype]
 
 
