@@ -82,6 +82,31 @@ __device__ __forceinline__ void radix_pass(float2 *z, const float2 *wt, int L, i
     }
 }
 
+// The innermost pass of both directions in one go: blocks of R adjacent points; forward butterfly, product
+// with k_f at the block's positions, inverse butterfly, written back in place (no twiddles at sub-length 1).
+template <int R, int M>
+__device__ __forceinline__ void middle_pass(float2 *z, const float2 *__restrict__ kf, const int *s_h, int tid)
+{
+#pragma unroll 1
+    for (int bi = tid; bi < PTS / R; bi += NTS) {
+        const int base = bi * R;
+        const int slot = base / M, p = base - slot * M;
+        const int h = s_h[slot];
+        float2 x[R];
+#pragma unroll
+        for (int m = 0; m < R; ++m) x[m] = z[pad(base + m)];
+        dft_reg<R, false>(x);
+        if (h >= 0) {
+            const float2 *kr = kf + (int64_t)h * M + p;
+#pragma unroll
+            for (int k = 0; k < R; ++k) x[k] = cmul2(x[k], kr[k]);
+        }
+        dft_reg<R, true>(x);
+#pragma unroll
+        for (int m = 0; m < R; ++m) z[pad(base + m)] = x[m];
+    }
+}
+
 // kf: [h][position] fp32 pairs, scaled by 1/M; wtab: W_M^t, t < M.
 template <int M, int R0, int R1, int R2, typename IO>
 __global__ void __launch_bounds__(NTS) k_small(const IO *__restrict__ u, IO *__restrict__ y,
@@ -93,68 +118,112 @@ __global__ void __launch_bounds__(NTS) k_small(const IO *__restrict__ u, IO *__r
     extern __shared__ float2 smem_small[];
     float2 *const z = smem_small;                                 // [PTS + PTS / 16]
     float2 *const wt = smem_small + PTS + PTS / 16;               // [M]
+    __shared__ int s_h[P], s_pair[P];                             // channel and pair of each slot (-1: no work)
     const int tid = threadIdx.x;
     for (int t = tid; t < M; t += NTS) wt[t] = wtab[t];
     const int npairs = (B + 1) / 2;
     const long long T = (long long)H * npairs;                    // work items t = h * npairs + pair
     const long long groups = (T + P - 1) / P;
+    // 16-byte accesses of 8 (16-bit) or 4 (fp32) consecutive samples when the rows allow it
+    constexpr int VEC = sizeof(IO) == 2 ? 8 : 4;
+    const bool vec_ok = (N % VEC == 0) && ((((uintptr_t)u | (uintptr_t)y) & 15) == 0);
     for (long long g = blockIdx.x; g < groups; g += gridDim.x) {
-        __syncthreads();                                          // z is free again (and wt is loaded)
-        // ---- load: point i = pair slot i / M, sample n = i % M; zeros for n >= N and for a missing row
-#pragma unroll 4
-        for (int i = tid; i < PTS; i += NTS) {
-            const int slot = i / M, n = i - slot * M;
-            const long long t = g * P + slot;
-            float2 v = make_float2(0.f, 0.f);
-            if (t < T && n < N) {
-                const int h = (int)(t / npairs), pair = (int)(t - (long long)h * npairs);
-                const int64_t row = ((int64_t)(2 * pair) * H + h) * N;
-                v.x = ld(u, row + n);
-                if (2 * pair + 1 < B) v.y = ld(u, row + (int64_t)H * N + n);
-            }
-            z[pad(i)] = v;
+        __syncthreads();                                          // z and the slot table are free again (and wt is loaded)
+        if (tid < P) {
+            const long long t = g * P + tid;
+            const int h = t < T ? (int)(t / npairs) : -1;
+            s_h[tid] = h;
+            s_pair[tid] = t < T ? (int)(t - (long long)h * npairs) : -1;
         }
         __syncthreads();
-        // ---- forward passes
+        // ---- load: point i = pair slot i / M, sample n = i % M; zeros for n >= N and for a missing row
+        if (vec_ok) {
+#pragma unroll
+            for (int c = tid; c < PTS / VEC; c += NTS) {
+                const int i = c * VEC, slot = i / M, n = i - slot * M;
+                const int h = s_h[slot], pair = s_pair[slot];
+                float re[VEC], im[VEC];
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) re[e] = im[e] = 0.f;
+                if (h >= 0 && n < N) {
+                    const int64_t row = ((int64_t)(2 * pair) * H + h) * N + n;
+                    const uint4 a = *(const uint4 *)(u + row);
+                    uint4 b4 = make_uint4(0, 0, 0, 0);
+                    if (2 * pair + 1 < B) b4 = *(const uint4 *)(u + row + (int64_t)H * N);
+                    alignas(16) IO ta[VEC], tb[VEC];
+                    *(uint4 *)ta = a;
+                    *(uint4 *)tb = b4;
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) {
+                        re[e] = ld(ta, e);
+                        im[e] = ld(tb, e);
+                    }
+                }
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) z[pad(i) + e] = make_float2(re[e], im[e]);
+            }
+        } else {
+#pragma unroll 4
+            for (int i = tid; i < PTS; i += NTS) {
+                const int slot = i / M, n = i - slot * M;
+                const int h = s_h[slot], pair = s_pair[slot];
+                float2 v = make_float2(0.f, 0.f);
+                if (h >= 0 && n < N) {
+                    const int64_t row = ((int64_t)(2 * pair) * H + h) * N;
+                    v.x = ld(u, row + n);
+                    if (2 * pair + 1 < B) v.y = ld(u, row + (int64_t)H * N + n);
+                }
+                z[pad(i)] = v;
+            }
+        }
+        __syncthreads();
+        // ---- forward passes (decimation in frequency), the innermost pass of both directions fused
+        //      with the product by k_f[h], inverse passes mirrored
         radix_pass<R0, false>(z, wt, M, 1, tid);
         __syncthreads();
-        radix_pass<R1, false>(z, wt, M / R0, R0, tid);
-        __syncthreads();
         if constexpr (R2 > 1) {
-            radix_pass<R2, false>(z, wt, M / (R0 * R1), R0 * R1, tid);
+            radix_pass<R1, false>(z, wt, M / R0, R0, tid);
+            __syncthreads();
+            middle_pass<R2, M>(z, kf, s_h, tid);
+            __syncthreads();
+            radix_pass<R1, true>(z, wt, M / R0, R0, tid);
+            __syncthreads();
+        } else {
+            middle_pass<R1, M>(z, kf, s_h, tid);
             __syncthreads();
         }
-        // ---- pointwise product with k_f[h] (the thread's own points: no barrier needed around it)
-#pragma unroll 4
-        for (int i = tid; i < PTS; i += NTS) {
-            const int slot = i / M, p = i - slot * M;
-            const long long t = g * P + slot;
-            if (t < T) {
-                const int h = (int)(t / npairs);
-                z[pad(i)] = cmul2(z[pad(i)], kf[(int64_t)h * M + p]);
-            }
-        }
-        __syncthreads();
-        // ---- inverse passes, mirrored
-        if constexpr (R2 > 1) {
-            radix_pass<R2, true>(z, wt, M / (R0 * R1), R0 * R1, tid);
-            __syncthreads();
-        }
-        radix_pass<R1, true>(z, wt, M / R0, R0, tid);
-        __syncthreads();
         radix_pass<R0, true>(z, wt, M, 1, tid);
         __syncthreads();
         // ---- store: real part -> row b, imaginary part -> row b+1
+        if (vec_ok) {
+#pragma unroll
+            for (int c = tid; c < PTS / VEC; c += NTS) {
+                const int i = c * VEC, slot = i / M, n = i - slot * M;
+                const int h = s_h[slot], pair = s_pair[slot];
+                if (h >= 0 && n < N) {
+                    alignas(16) IO ta[VEC], tb[VEC];
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) {
+                        const float2 v = z[pad(i) + e];
+                        st(ta, e, v.x);
+                        st(tb, e, v.y);
+                    }
+                    const int64_t row = ((int64_t)(2 * pair) * H + h) * N + n;
+                    *(uint4 *)(y + row) = *(const uint4 *)ta;
+                    if (2 * pair + 1 < B) *(uint4 *)(y + row + (int64_t)H * N) = *(const uint4 *)tb;
+                }
+            }
+        } else {
 #pragma unroll 4
-        for (int i = tid; i < PTS; i += NTS) {
-            const int slot = i / M, n = i - slot * M;
-            const long long t = g * P + slot;
-            if (t < T && n < N) {
-                const int h = (int)(t / npairs), pair = (int)(t - (long long)h * npairs);
-                const int64_t row = ((int64_t)(2 * pair) * H + h) * N;
-                const float2 v = z[pad(i)];
-                st(y, row + n, v.x);
-                if (2 * pair + 1 < B) st(y, row + (int64_t)H * N + n, v.y);
+            for (int i = tid; i < PTS; i += NTS) {
+                const int slot = i / M, n = i - slot * M;
+                const int h = s_h[slot], pair = s_pair[slot];
+                if (h >= 0 && n < N) {
+                    const int64_t row = ((int64_t)(2 * pair) * H + h) * N;
+                    const float2 v = z[pad(i)];
+                    st(y, row + n, v.x);
+                    if (2 * pair + 1 < B) st(y, row + (int64_t)H * N + n, v.y);
+                }
             }
         }
     }
