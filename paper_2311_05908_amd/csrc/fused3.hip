@@ -76,6 +76,8 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *u, uint16_t *y,
 {
     using G = Geo<N2, N3>;
     constexpr int R2 = G::R2, R3 = G::R3, C3 = G::C3, C1 = G::C1;
+    // streamed tables are requested one tile ahead of their use when two tiles' worth fits in registers
+    constexpr bool AHEAD = !REGC && N2 == 16;
     constexpr int KS1 = CPLX ? 2 : 1;            // K steps of forward stage 1 (n1 < 16 only when zero padded)
     constexpr int RT1 = CPLX ? 2 : 1;            // output row tiles of inverse stage 1
     constexpr int NCH = CPLX ? G::CHUNKS_C : G::CHUNKS;
@@ -284,6 +286,7 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *u, uint16_t *y,
     issue_loads(0);
     stage_in();
     issue_loads(1);
+    if constexpr (AHEAD) load_A(0);
     lds_barrier();
 
     const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
@@ -333,7 +336,12 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *u, uint16_t *y,
 #pragma unroll
             for (int i = 0; i < C3; ++i) {
                 const int c = w * C3 + i;
-                if constexpr (!REGC) load_A(i);           // this tile's matrices and twiddles (L2-resident tables)
+                // streamed tables (L2-resident): requested one tile ahead where the registers allow
+                if constexpr (AHEAD) {
+                    if (i + 1 < C3) load_A(i + 1);
+                } else if constexpr (!REGC) {
+                    load_A(i);
+                }
                 uint4 x2[2][R2];                          // stage-2 operands [k1 tile][K step = n2 tile]
 #pragma unroll
                 for (int rt = 0; rt < R2; ++rt)
@@ -370,6 +378,10 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *u, uint16_t *y,
                                                    TT::pack(dre[2], dim[2]), TT::pack(dre[3], dim[3]));
                     }
             }
+            if constexpr (AHEAD) {                        // phase B's first tile: in flight across the barrier
+                load_B(0);
+                load_kf(0, h_cur);
+            }
         }
         lds_barrier();
 
@@ -401,7 +413,12 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *u, uint16_t *y,
 #pragma unroll
             for (int i = 0; i < C1; ++i) {
                 const int c = w * C1 + i;
-                if constexpr (!REGC) {
+                if constexpr (AHEAD) {
+                    if (i + 1 < C1) {
+                        load_B(i + 1);
+                        load_kf(i + 1, h_cur);
+                    }
+                } else if constexpr (!REGC) {
                     load_B(i);
                     load_kf(i, h_cur);
                 }
@@ -512,6 +529,7 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *u, uint16_t *y,
                         }
                     }
             }
+            if constexpr (AHEAD) load_A(0);               // the next item's first phase-A tile
         }
         lds_barrier();
     }
