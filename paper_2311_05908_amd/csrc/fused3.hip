@@ -771,9 +771,11 @@ int fused3_init(fftconv_plan *p)
         p->f3.N3 = 16;
         return build_tables<16, 16>(p, &p->f3.consts);
     case 16384: {
-        p->f3.N2 = 32;
-        p->f3.N3 = 16;
-        int rc = build_tables<32, 16>(p, &p->f3.consts);
+        // 32 * 16 * 32 on the streamed-table kernel of fused3_big.hip: the per-plane stage-2 matrices are then
+        // 16 x 16 (a quarter of the bytes of a 32 * 32 * 16 split)
+        p->f3.N2 = 16;
+        p->f3.N3 = 32;
+        int rc = fused3_big_init(p);
         if (rc) return rc;
         return build_tables<16, 16>(p, &p->f3.consts_short);     // for partial convolutions, see fused3_forward_short
     }
@@ -790,17 +792,8 @@ int fused3_init(fftconv_plan *p)
 int fused3_forward_sparse(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, int live,
                           hipStream_t s)
 {
-    if (p->M != 16384 || live >= 3) return fused3_forward(p, u, kf, y, B, s);
-    if (((uintptr_t)u | (uintptr_t)y) & 15) {
-        set_error("fftconv_forward_freq_sparse: u and y must be 16-byte aligned for this plan");
-        return FFTCONV_EINVAL;
-    }
-    const bool f16 = p->dtype == FFTCONV_F16;
-    if (live <= 1)
-        return f16 ? launch<32, 16, F16, false, false, 1>(p, u, kf, y, B, p->H, p->N, s)
-                   : launch<32, 16, BF16, false, false, 1>(p, u, kf, y, B, p->H, p->N, s);
-    return f16 ? launch<32, 16, F16, false, false, 2>(p, u, kf, y, B, p->H, p->N, s)
-               : launch<32, 16, BF16, false, false, 2>(p, u, kf, y, B, p->H, p->N, s);
+    (void)live;
+    return fused3_forward(p, u, kf, y, B, s);
 }
 
 // Number of accumulator registers (1..4) of stage 3 that can meet a non-zero bin under a block mask
@@ -869,9 +862,9 @@ constexpr int64_t SHORT_MAX_P = 2048;      // most history a segment may carry (
 size_t fused3_kf_bytes(const fftconv_plan *p)
 {
     if (p->M == 32768) return fused3_big_kf_bytes(p);
-    // fft 16384 plans: dense spectrum, then the 8192-point spectrum of a short filter
-    const int64_t bins = p->M + (p->f3.consts_short ? SHORT_M : 0);
-    return (size_t)(p->H * bins) * sizeof(float2);
+    // fft 16384 plans: dense spectrum, then the 8192-point spectrum of a short filter (8 bytes per bin)
+    if (p->M == 16384) return fused3_big_kf_bytes(p) + (size_t)(p->H * SHORT_M) * sizeof(float2);
+    return (size_t)(p->H * p->M) * sizeof(float2);
 }
 
 static int64_t history_of(int64_t Nk) { return (Nk - 1 + 7) / 8 * 8; }
@@ -885,7 +878,7 @@ int fused3_pack_kf_short(const fftconv_plan *p, const double2 *spec, int64_t h0,
 {
     const int bs = 256;
     const unsigned grid = (unsigned)((nh * SHORT_M + bs - 1) / bs);
-    float2 *dst = (float2 *)kf + p->H * p->M;
+    float2 *dst = (float2 *)((char *)kf + fused3_big_kf_bytes(p));
     hipLaunchKernelGGL((k_pack_fused3<16, 16>), dim3(grid), dim3(bs), 0, s, spec, dst, staged_factors_for(SHORT_M), h0,
                        nh, (const uint8_t *)nullptr, (int64_t)1, p->dtype == FFTCONV_F16 ? 2 : 1);
     FC_HIP(hipGetLastError());
@@ -907,7 +900,7 @@ int fused3_forward_short(const fftconv_plan *p, const void *u, const void *kf, v
     const int P = (int)history_of(Nk);
     const int Lo = (int)(SHORT_M / 2) - P;
     const int nseg = p->N <= SHORT_M / 2 ? 1 : 1 + (int)((p->N - SHORT_M / 2 + Lo - 1) / Lo);
-    const float2 *kf_short = (const float2 *)kf + p->H * p->M;
+    const float2 *kf_short = (const float2 *)((const char *)kf + fused3_big_kf_bytes(p));
     return fused3_ws_launch(p, p->f3.consts_short, u, kf_short, y, B, nseg, P, s);
 }
 
@@ -923,9 +916,6 @@ int fused3_pack_kf(const fftconv_plan *p, const double2 *spec, int64_t h0, int64
                            staged_fac_list(p), h0, nh, keep_dev, n_blocks, p->dtype == FFTCONV_F16 ? 2 : 1);
         break;
     case 16384:
-        hipLaunchKernelGGL((k_pack_fused3<32, 16>), dim3(grid), dim3(bs), 0, s, spec, (float2 *)kf,
-                           staged_fac_list(p), h0, nh, keep_dev, n_blocks, 0);
-        break;
     case 32768:
         return fused3_big_pack_kf(p, spec, h0, nh, keep_dev, n_blocks, kf, s);
     default:
@@ -954,13 +944,10 @@ int fused3_forward(const fftconv_plan *p, const void *u, const void *kf, void *y
         set_error("fftconv_forward: u and y must be 16-byte aligned for this plan");
         return FFTCONV_EINVAL;
     }
-    const bool f16 = p->dtype == FFTCONV_F16;
     switch (p->M) {
     case 8192:
         return fused3_ws_launch(p, p->f3.consts, u, kf, y, B, 1, 0, s);     // wave-specialised schedule (fused3_ws.hip)
     case 16384:
-        return f16 ? launch<32, 16, F16, false, false>(p, u, kf, y, B, p->H, p->N, s)
-                   : launch<32, 16, BF16, false, false>(p, u, kf, y, B, p->H, p->N, s);
     case 32768:
         return fused3_big_forward(p, u, kf, y, B, s);
     default:

@@ -1,7 +1,7 @@
-// Fused causal FFT convolution for fft_size 32768 = 32*32*32, 16-bit I/O (paper Algorithm 3:
+// Fused causal FFT convolution for fft_size 32768 = 32*32*32 and 16384 = 32*16*32, 16-bit I/O (paper Algorithm 3:
 // whole sequence on chip, u read once, y written once).  Same arithmetic and index maps as the
-// smaller fused kernels (fused3.hip): time n = (n1*32 + n2)*32 + n3, frequency
-// f = k1 + 32*k2 + 1024*k3, two batch rows of a channel share one complex transform, the zero half
+// smaller fused kernels (fused3.hip): time n = (n1*N2 + n2)*32 + n3, frequency
+// f = k1 + 32*k2 + 32*N2*k3, two batch rows of a channel share one complex transform, the zero half
 // of the padded input is never touched.
 //
 // What this size changes:
@@ -50,11 +50,17 @@ namespace f3 {
 
 namespace {
 
-constexpr int BM = 32768;                     // fft size
-constexpr int BPK1 = 36;                      // X(k1,k2,n3) word = n3*BPN3 + k1*BPK1 + k2
-constexpr int BPN3 = 32 * BPK1 + 4;
-constexpr int BXB_WORDS = 32 * BPN3;
-constexpr size_t BIG_LDS_BYTES = (size_t)BXB_WORDS * 4;
+// fft_size = 32 * N2 * 32 with N2 = 32 (32768) or 16 (16384)
+template <int N2> struct BigGeo {
+    static constexpr int M = 1024 * N2;
+    static constexpr int R2 = N2 / 16;                    // 16-wide tiles of the middle digit
+    static constexpr int PK1 = N2 + 4;                    // X(k1,k2,n3) word = n3*PN3 + k1*PK1 + k2
+    static constexpr int PN3 = 32 * PK1 + 4;
+    static constexpr int XB_WORDS = 32 * PN3;
+    static constexpr size_t LDS_BYTES = (size_t)XB_WORDS * 4;
+    static constexpr int NCH = M / 4096;                  // 16-byte chunks of a pair's input per thread
+    static constexpr size_t U4 = (size_t)(4 + 4 + 8 + 2 * 32 * R2 * R2 * 2) * 64;   // operand tables, uint4 entries
+};
 
 // bf16: dot-product form.  Constant of a factor (wr, wi): { (wr, -wi), (wi, wr) }, which yields
 // z * w; the tables of the conjugating products hold { (wr, -wi), (-wi, -wr) } instead, which yields
@@ -112,23 +118,24 @@ template <typename CW> struct BigConsts {
     const uint4 *tab1;    // [ct][part][lane]                 W_32^{n1 k1}, n1 < 16
     const uint4 *tab1i;   // [K step][part][lane]             conj(W_32^{k1 n1}), n1 < 16
     const uint4 *tab3;    // [K step][tile][part][lane]       W_32^{n3 k3}
-    const uint4 *tab2;    // [n3][K step][tile][part][lane]   W_32^{n2 k2} W_1024^{k2 n3}
-    const uint4 *tab2i;   // [k1][K step][tile][part][lane]   conj(W_32^{k2 n2} W_1024^{k1 n2})
+    const uint4 *tab2;    // [n3][K step][tile][part][lane]   W_N2^{n2 k2} W_{32 N2}^{k2 n3}
+    const uint4 *tab2i;   // [k1][K step][tile][part][lane]   conj(W_N2^{k2 n2} W_{32 N2}^{k1 n2})
     const CW *twa;        // [n3][rt][ct][r][lane]            W_M^{k1 (32 n2 + n3)}
     const CW *twb;        // [k1][ct2][ct3][r][lane]          W_M^{(k1 + 32 k2) n3}, used as conj(z * w)
 };
-constexpr size_t BIG_U4 = (size_t)(4 + 4 + 8 + 32 * 8 + 32 * 8) * 64;
 
 // nothing may be moved across: pins where the streamed table loads are issued
 #define SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
 
-// FULL: B even and N == 16384, every access of a work item is in range.
-template <typename TT, bool FULL>
+// FULL: B even and N == fft_size / 2, every access of a work item is in range.
+template <typename TT, bool FULL, int N2>
 __global__ void __launch_bounds__(NT) k_fused3_big(const uint16_t *__restrict__ u, uint16_t *__restrict__ y,
                                                   const typename TT::CW *__restrict__ kf, BigConsts<typename TT::CW> cs,
                                                   int B, int H, int N, int probe)
 {
     using CW = typename TT::CW;
+    using BG = BigGeo<N2>;
+    constexpr int BM = BG::M, BPK1 = BG::PK1, BPN3 = BG::PN3, R2 = BG::R2, NCH = BG::NCH;
     extern __shared__ uint32_t XB[];
     const int tid = threadIdx.x, l = tid & 63, q = l >> 4, c16 = l & 15;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -153,10 +160,10 @@ __global__ void __launch_bounds__(NT) k_fused3_big(const uint16_t *__restrict__ 
     uint32_t *const wrB1 = wrB0 + 16 * BPN3;                                      // n3 tile 1
 
     uint4 tab1[2][2], tab1i[2][2], tab3[2][2][2];
-    uint4 tabA[2][2][2], tabB[2][2][2];          // stage-2 / inverse stage-2 matrices of the current plane
-    CW twaR[2][2][4], twbR[2][2][4], kfR[2][2][4];
-    uint4 pre[8];                                 // next pair's input, 16-byte chunks in memory order
-    uint2 x1r[2][2][4];                           // the same in operand order: [row of the pair][n2 tile][r], 4 n3 planes each
+    uint4 tabA[R2][R2][2], tabB[R2][R2][2];      // stage-2 / inverse stage-2 matrices of the current plane
+    CW twaR[R2][2][4], twbR[R2][2][4], kfR[R2][2][4];
+    uint4 pre[NCH];                               // next pair's input, 16-byte chunks in memory order
+    uint2 x1r[2][R2][4];                          // the same in operand order: [row of the pair][n2 tile][r], 4 n3 planes each
 
     // The tables are loop invariant but must be re-read for every work item (they do not fit in
     // registers): an opaque zero added to the lane offset keeps the loads inside the loop.
@@ -188,48 +195,48 @@ __global__ void __launch_bounds__(NT) k_fused3_big(const uint16_t *__restrict__ 
     auto load_tabA = [&](int i) {
         const int c = 4 * w + i;
 #pragma unroll
-        for (int a = 0; a < 2; ++a)
+        for (int a = 0; a < R2; ++a)
 #pragma unroll
-            for (int b = 0; b < 2; ++b)
+            for (int b = 0; b < R2; ++b)
 #pragma unroll
-                for (int p = 0; p < 2; ++p) tabA[a][b][p] = (cs.tab2 + (((c * 2 + a) * 2 + b) * 2 + p) * 64)[lz];
+                for (int p = 0; p < 2; ++p) tabA[a][b][p] = (cs.tab2 + (((c * R2 + a) * R2 + b) * 2 + p) * 64)[lz];
     };
     auto load_twa = [&](int i) {
         const int c = 4 * w + i;
 #pragma unroll
-        for (int a = 0; a < 2; ++a)
+        for (int a = 0; a < R2; ++a)
 #pragma unroll
             for (int b = 0; b < 2; ++b)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) twaR[a][b][r] = (cs.twa + (((c * 2 + a) * 2 + b) * 4 + r) * 64)[lz];
+                for (int r = 0; r < 4; ++r) twaR[a][b][r] = (cs.twa + (((c * R2 + a) * 2 + b) * 4 + r) * 64)[lz];
     };
     auto load_tabB = [&](int i) {
         const int c = 4 * w + i;
 #pragma unroll
-        for (int a = 0; a < 2; ++a)
+        for (int a = 0; a < R2; ++a)
 #pragma unroll
-            for (int b = 0; b < 2; ++b)
+            for (int b = 0; b < R2; ++b)
 #pragma unroll
-                for (int p = 0; p < 2; ++p) tabB[a][b][p] = (cs.tab2i + (((c * 2 + a) * 2 + b) * 2 + p) * 64)[lz];
+                for (int p = 0; p < 2; ++p) tabB[a][b][p] = (cs.tab2i + (((c * R2 + a) * R2 + b) * 2 + p) * 64)[lz];
     };
     auto load_twb = [&](int i) {
         const int c = 4 * w + i;
 #pragma unroll
-        for (int a = 0; a < 2; ++a)
+        for (int a = 0; a < R2; ++a)
 #pragma unroll
             for (int b = 0; b < 2; ++b)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) twbR[a][b][r] = (cs.twb + (((c * 2 + a) * 2 + b) * 4 + r) * 64)[lz];
+                for (int r = 0; r < 4; ++r) twbR[a][b][r] = (cs.twb + (((c * R2 + a) * 2 + b) * 4 + r) * 64)[lz];
     };
     auto load_kf = [&](int i, int h) {
         const int c = 4 * w + i;
 #pragma unroll
-        for (int a = 0; a < 2; ++a)
+        for (int a = 0; a < R2; ++a)
 #pragma unroll
             for (int b = 0; b < 2; ++b)
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
-                    kfR[a][b][r] = (kf + (size_t)h * BM + (((c * 2 + a) * 2 + b) * 4 + r) * 64)[lz];
+                    kfR[a][b][r] = (kf + (size_t)h * BM + (((c * R2 + a) * 2 + b) * 4 + r) * 64)[lz];
     };
     // Input and output pass through LDS so that HBM sees whole 16-byte chunks in memory order
     // (8-byte pieces of a 64-byte row written by 8 different waves cost partial-line fills and
@@ -237,16 +244,16 @@ __global__ void __launch_bounds__(NT) k_fused3_big(const uint16_t *__restrict__ 
     // [0, SB_BYTES) stage y of this pair, [SB_BYTES, 2 SB_BYTES) stage u of the next one, both as
     // (row of the pair, n1 < 16, n2) rows of 32 n3 values, 72 bytes apart (conflict-free 8-byte
     // accesses in operand order, 8-byte aligned 16-byte chunks in memory order).
-    constexpr int SB_ROW = 72, SB_BYTES = 2 * 16 * 32 * SB_ROW;
-    static_assert(2 * SB_BYTES <= (int)BIG_LDS_BYTES, "staging areas must fit in the exchange buffer");
+    constexpr int SB_ROW = 72, SB_BYTES = 2 * 16 * N2 * SB_ROW;
+    static_assert(2 * SB_BYTES <= (int)BG::LDS_BYTES, "staging areas must fit in the exchange buffer");
     char *const YS = (char *)XB, *const US = (char *)XB + SB_BYTES;
-    // chunk j of this thread: g = tid + 512 j -> row of the pair g / 2048, elements [8 (g % 2048), +8)
+    // chunk j of this thread: row of the pair j / (NCH/2), elements [8 (tid + 512 (j % (NCH/2))), +8)
     auto issue_pre = [&](int t) {
         const int h = t / npairs, pair = t - h * npairs;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const int s = j / 4;                              // wave-uniform: 4 chunks per thread and row
-            const int n = (tid + NT * (j % 4)) * 8;
+        for (int j = 0; j < NCH; ++j) {
+            const int s = j / (NCH / 2);                      // wave-uniform: NCH/2 chunks per thread and row
+            const int n = (tid + NT * (j % (NCH / 2))) * 8;
             const int b = 2 * pair + s;
             const uint16_t *row = u + ((size_t)(FULL ? b : min(b, B - 1)) * H + h) * N;
             if constexpr (FULL) {
@@ -260,17 +267,17 @@ __global__ void __launch_bounds__(NT) k_fused3_big(const uint16_t *__restrict__ 
     };
     // byte offset of chunk j inside a staging area
     auto chunk_ofs = [&](int j) {
-        const int s = j / 4;
-        const int n = (tid + NT * (j % 4)) * 8;               // n = (n1*32 + n2)*32 + n3, n3 in {0, 8, 16, 24}
-        return (s * 512 + n / 32) * SB_ROW + (n % 32) * 2;
+        const int s = j / (NCH / 2);
+        const int n = (tid + NT * (j % (NCH / 2))) * 8;       // n = (n1*N2 + n2)*32 + n3, n3 in {0, 8, 16, 24}
+        return (s * 16 * N2 + n / 32) * SB_ROW + (n % 32) * 2;
     };
     // byte offset of this lane's operand-order piece: n1 = 4q + r, n2 = 16 tile + c16, n3 = 4w .. 4w+3
     auto piece_ofs = [&](int s, int tile, int r) {
-        return ((s * 16 + 4 * q + r) * 32 + 16 * tile + c16) * SB_ROW + 8 * w;
+        return ((s * 16 + 4 * q + r) * N2 + 16 * tile + c16) * SB_ROW + 8 * w;
     };
     auto stage_in = [&]() {                                   // pre -> US
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
+        for (int j = 0; j < NCH; ++j) {
             uint2 *dst = (uint2 *)(US + chunk_ofs(j));
             dst[0] = make_uint2(pre[j].x, pre[j].y);
             dst[1] = make_uint2(pre[j].z, pre[j].w);
@@ -280,7 +287,7 @@ __global__ void __launch_bounds__(NT) k_fused3_big(const uint16_t *__restrict__ 
 #pragma unroll
         for (int s = 0; s < 2; ++s)
 #pragma unroll
-            for (int rt = 0; rt < 2; ++rt)
+            for (int rt = 0; rt < R2; ++rt)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) x1r[s][rt][r] = *(const uint2 *)(US + piece_ofs(s, rt, r));
     };
@@ -291,9 +298,9 @@ __global__ void __launch_bounds__(NT) k_fused3_big(const uint16_t *__restrict__ 
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const uint32_t sel = (i & 1) ? 0x07060302u : 0x05040100u;
-            uint4 x2[2][2];                               // stage-2 operands [k1 tile][K step = n2 tile]
+            uint4 x2[2][R2];                              // stage-2 operands [k1 tile][K step = n2 tile]
 #pragma unroll
-            for (int rt = 0; rt < 2; ++rt) {
+            for (int rt = 0; rt < R2; ++rt) {
                 // rows n2 = 16 rt + c16; slots (2r+s) = u_s[n1 = 4q + r]
                 uint32_t d[4];
 #pragma unroll
@@ -317,10 +324,10 @@ __global__ void __launch_bounds__(NT) k_fused3_big(const uint16_t *__restrict__ 
 #pragma unroll
             for (int ct = 0; ct < 2; ++ct)
 #pragma unroll
-                for (int ct2 = 0; ct2 < 2; ++ct2) {
+                for (int ct2 = 0; ct2 < R2; ++ct2) {
                     f32x4 dre = zero4, dim = zero4;
 #pragma unroll
-                    for (int ks = 0; ks < 2; ++ks) {      // matrix as the A operand: rows k2, data columns k1
+                    for (int ks = 0; ks < R2; ++ks) {     // matrix as the A operand: rows k2, data columns k1
                         dre = TT::mfma(tabA[ks][ct2][0], x2[ct][ks], dre);
                         dim = TT::mfma(tabA[ks][ct2][1], x2[ct][ks], dim);
                     }
@@ -337,7 +344,7 @@ __global__ void __launch_bounds__(NT) k_fused3_big(const uint16_t *__restrict__ 
 
     // ---- phase C of one pair: inverse stage 1 (n1 < 16) on this wave's 4 n3 planes; the results
     // (real part -> row b, imaginary part -> row b+1) are returned packed, 4 planes per 8 bytes.
-    uint2 yo[2][2][4];                                    // [row of the pair][n2 tile][r]
+    uint2 yo[2][R2][4];                                   // [row of the pair][n2 tile][r]
     auto phase_C = [&]() {
         // one n2 tile of one plane: lane: n2 = 16 cn2 + c16; reg r: n1 = 4q + r
         auto tile = [&](int i, int cn2, f32x4 &dre, f32x4 &dim) {
@@ -355,7 +362,7 @@ __global__ void __launch_bounds__(NT) k_fused3_big(const uint16_t *__restrict__ 
 #pragma unroll
         for (int ip = 0; ip < 2; ++ip)
 #pragma unroll
-            for (int cn2 = 0; cn2 < 2; ++cn2) {
+            for (int cn2 = 0; cn2 < R2; ++cn2) {
                 f32x4 are, aim, bre, bim;
                 SCHED_FENCE();
                 tile(2 * ip, cn2, are, aim);
@@ -376,18 +383,18 @@ __global__ void __launch_bounds__(NT) k_fused3_big(const uint16_t *__restrict__ 
                 SCHED_FENCE();
             }
     };
-    uint4 yc[8];                                          // y of this pair, 16-byte chunks in memory order
+    uint4 yc[NCH];                                        // y of this pair, 16-byte chunks in memory order
     auto stage_out = [&]() {                              // yo -> YS
 #pragma unroll
         for (int s = 0; s < 2; ++s)
 #pragma unroll
-            for (int cn2 = 0; cn2 < 2; ++cn2)
+            for (int cn2 = 0; cn2 < R2; ++cn2)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) *(uint2 *)(YS + piece_ofs(s, cn2, r)) = yo[s][cn2][r];
     };
     auto read_y = [&]() {                                 // YS -> memory order
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
+        for (int j = 0; j < NCH; ++j) {
             const uint2 *src = (const uint2 *)(YS + chunk_ofs(j));
             const uint2 a = src[0], b = src[1];
             yc[j] = make_uint4(a.x, a.y, b.x, b.y);
@@ -396,9 +403,9 @@ __global__ void __launch_bounds__(NT) k_fused3_big(const uint16_t *__restrict__ 
     auto store_y = [&](int t) {
         const int h = t / npairs, pair = t - h * npairs;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const int s = j / 4;
-            const int n = (tid + NT * (j % 4)) * 8;
+        for (int j = 0; j < NCH; ++j) {
+            const int s = j / (NCH / 2);
+            const int n = (tid + NT * (j % (NCH / 2))) * 8;
             const int b = 2 * pair + s;
             uint16_t *row = y + ((size_t)(FULL ? b : min(b, B - 1)) * H + h) * N;
             if (FULL || (b < B && n < N)) *(uint4 *)(row + n) = yc[j];
@@ -408,22 +415,22 @@ __global__ void __launch_bounds__(NT) k_fused3_big(const uint16_t *__restrict__ 
     // ---- phase B of one pair: per k1 plane (4 per wave): stage 3, k_f, inverse 3, twiddle,
     // inverse 2, in place.  On entry tab3, kfR, twbR, tabB hold plane 0's tables.
     auto phase_B = [&](int h) {
-        auto read_plane = [&](int i, uint4 (&x)[2][2]) {
+        auto read_plane = [&](int i, uint4 (&x)[R2][2]) {
 #pragma unroll
-            for (int ct2 = 0; ct2 < 2; ++ct2)
+            for (int ct2 = 0; ct2 < R2; ++ct2)
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks) {
                     const uint32_t *src = (ks ? rdB1 : rdB0) + i * BPK1 + 16 * ct2;
                     x[ct2][ks] = make_uint4(src[0], src[BPN3], src[2 * BPN3], src[3 * BPN3]);
                 }
         };
-        uint4 x3[2][2];                                   // [k2 tile][K step = n3 tile]
+        uint4 x3[R2][2];                                  // [k2 tile][K step = n3 tile]
         read_plane(0, x3);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            uint4 x3i[2][2];                              // [k2 tile][K step = k3 tile], holds conj(A3 k_f)
+            uint4 x3i[R2][2];                             // [k2 tile][K step = k3 tile], holds conj(A3 k_f)
 #pragma unroll
-            for (int ct2 = 0; ct2 < 2; ++ct2)
+            for (int ct2 = 0; ct2 < R2; ++ct2)
 #pragma unroll
                 for (int ct3 = 0; ct3 < 2; ++ct3) {
                     f32x4 dre = zero4, dim = zero4;
@@ -441,9 +448,9 @@ __global__ void __launch_bounds__(NT) k_fused3_big(const uint16_t *__restrict__ 
                 read_plane(i + 1, x3);                    // its latency hides behind the rest of this plane
             }
             SCHED_FENCE();
-            uint4 x2i[2][2];                              // [n3 tile][K step = k2 tile]
+            uint4 x2i[2][R2];                             // [n3 tile][K step = k2 tile]
 #pragma unroll
-            for (int ct2 = 0; ct2 < 2; ++ct2)
+            for (int ct2 = 0; ct2 < R2; ++ct2)
 #pragma unroll
                 for (int cn3 = 0; cn3 < 2; ++cn3) {
                     f32x4 dre = zero4, dim = zero4;
@@ -461,10 +468,10 @@ __global__ void __launch_bounds__(NT) k_fused3_big(const uint16_t *__restrict__ 
 #pragma unroll
             for (int cn3 = 0; cn3 < 2; ++cn3)
 #pragma unroll
-                for (int cn2 = 0; cn2 < 2; ++cn2) {
+                for (int cn2 = 0; cn2 < R2; ++cn2) {
                     f32x4 dre = zero4, dim = zero4;
 #pragma unroll
-                    for (int ks = 0; ks < 2; ++ks) {      // matrix as the A operand: rows n2, data columns n3
+                    for (int ks = 0; ks < R2; ++ks) {     // matrix as the A operand: rows n2, data columns n3
                         dre = TT::mfma(tabB[ks][cn2][0], x2i[cn3][ks], dre);
                         dim = TT::mfma(tabB[ks][cn2][1], x2i[cn3][ks], dim);
                     }
@@ -552,16 +559,18 @@ __global__ void __launch_bounds__(NT) k_fused3_big(const uint16_t *__restrict__ 
 
 // k_f in the kernel's per-lane order: [h][k1][k2 tile][k3 tile][r][lane]; the lane holds
 // k2 = 16 tile + lane%16 and k3 = 16 tile + 4 (lane/16) + r.  Scaled by 1/M.
-template <typename TT>
+template <typename TT, int N2>
 __global__ void k_pack_big(const double2 *spec, typename TT::CW *kf, FacList fl, int64_t h0, int64_t nh,
                            const uint8_t *keep, int64_t n_blocks)
 {
+    constexpr int64_t BM = BigGeo<N2>::M;
+    constexpr int R2 = BigGeo<N2>::R2;
     const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= nh * BM) return;
     const int64_t h = idx / BM, f = idx % BM;
-    const int k1 = (int)(f % 32), k2 = (int)((f / 32) % 32), k3 = (int)(f / 1024);
+    const int k1 = (int)(f % 32), k2 = (int)((f / 32) % N2), k3 = (int)(f / (32 * N2));
     const int lane = ((k3 % 16) / 4) * 16 + (k2 % 16), r = k3 % 4;
-    const int64_t dst = ((((int64_t)k1 * 2 + k2 / 16) * 2 + k3 / 16) * 4 + r) * 64 + lane;
+    const int64_t dst = ((((int64_t)k1 * R2 + k2 / 16) * 2 + k3 / 16) * 4 + r) * 64 + lane;
     const double2 v = spec[h * BM + freq_to_pos(f, fl, BM)];
     const double sc = mask_weight(keep, n_blocks, f, BM) / (double)BM;
     const uint32_t pr = TT::pack((float)(v.x * sc), (float)(v.y * sc));      // (re, im) 16-bit pair
@@ -614,17 +623,18 @@ template <typename Fn> void fill_op(uint16_t *dst, bool f16, int t, int ct, int 
     }
 }
 
-template <typename CW> BigConsts<CW> big_consts_at(const void *base)
+template <typename CW, int N2> BigConsts<CW> big_consts_at(const void *base)
 {
+    using BG = BigGeo<N2>;
     BigConsts<CW> c;
     const uint4 *b = (const uint4 *)base;
     c.tab1 = b;
     c.tab1i = c.tab1 + 4 * 64;
     c.tab3 = c.tab1i + 4 * 64;
     c.tab2 = c.tab3 + 8 * 64;
-    c.tab2i = c.tab2 + 32 * 8 * 64;
-    c.twa = (const CW *)(c.tab2i + 32 * 8 * 64);
-    c.twb = c.twa + BM;
+    c.tab2i = c.tab2 + 32 * BG::R2 * BG::R2 * 2 * 64;
+    c.twa = (const CW *)(c.tab2i + 32 * BG::R2 * BG::R2 * 2 * 64);
+    c.twb = c.twa + BG::M;
     return c;
 }
 
@@ -638,14 +648,15 @@ int big_probe()
 #endif
 }
 
-template <typename TT, bool FULL>
+template <typename TT, bool FULL, int N2>
 int launch_big(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, hipStream_t s)
 {
     using CW = typename TT::CW;
-    auto kern = k_fused3_big<TT, FULL>;
+    using BG = BigGeo<N2>;
+    auto kern = k_fused3_big<TT, FULL, N2>;
     static bool attr_set = false;
     if (!attr_set) {
-        FC_HIP(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)BIG_LDS_BYTES));
+        FC_HIP(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)BG::LDS_BYTES));
         attr_set = true;
     }
     const int64_t T = p->H * ((B + 1) / 2);
@@ -656,19 +667,19 @@ int launch_big(const fftconv_plan *p, const void *u, const void *kf, void *y, in
     // one persistent workgroup per compute unit, a multiple of 8 (see the kernel's work split)
     int grid = (int)(T < p->f3.num_cu ? T : p->f3.num_cu);
     if (grid >= 8) grid -= grid % 8;
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NT), BIG_LDS_BYTES, s, (const uint16_t *)u, (uint16_t *)y,
-                       (const CW *)kf, big_consts_at<CW>(p->f3.consts), (int)B, (int)p->H, (int)p->N, big_probe());
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NT), BG::LDS_BYTES, s, (const uint16_t *)u, (uint16_t *)y,
+                       (const CW *)kf, (big_consts_at<CW, N2>(p->f3.consts)), (int)B, (int)p->H, (int)p->N, big_probe());
     FC_HIP(hipGetLastError());
     return FFTCONV_OK;
 }
 
-}  // namespace
-
-int fused3_big_init(fftconv_plan *p)
+template <int N2> int big_init_t(fftconv_plan *p)
 {
+    using BG = BigGeo<N2>;
+    constexpr int R2 = BG::R2;
     const bool f16 = p->dtype == FFTCONV_F16;
-    const int64_t M = BM;
-    std::vector<uint16_t> ops(BIG_U4 * 8);
+    const int64_t M = BG::M;
+    std::vector<uint16_t> ops(BG::U4 * 8);
     size_t o = 0;
     auto next = [&]() { uint16_t *d = ops.data() + o * 8; o += 64; return d; };
     for (int ct = 0; ct < 2; ++ct)                        // tab1: K step 0 only (n1 < 16)
@@ -682,26 +693,26 @@ int fused3_big_init(fftconv_plan *p)
             for (int part = 0; part < 2; ++part)
                 fill_op(next(), f16, ks, ct, part, [&](int n3, int k3) { return wp(32, (int64_t)n3 * k3); });
     for (int n3 = 0; n3 < 32; ++n3)                       // tab2
-        for (int ks = 0; ks < 2; ++ks)
-            for (int ct = 0; ct < 2; ++ct)
+        for (int ks = 0; ks < R2; ++ks)
+            for (int ct = 0; ct < R2; ++ct)
                 for (int part = 0; part < 2; ++part)
                     fill_op(next(), f16, ks, ct, part, [&](int n2, int k2) {
-                        return cm(wp(32, (int64_t)n2 * k2), wp(1024, (int64_t)k2 * n3));
+                        return cm(wp(N2, (int64_t)n2 * k2), wp(32 * N2, (int64_t)k2 * n3));
                     });
     for (int k1 = 0; k1 < 32; ++k1)                       // tab2i
-        for (int ks = 0; ks < 2; ++ks)
-            for (int ct = 0; ct < 2; ++ct)
+        for (int ks = 0; ks < R2; ++ks)
+            for (int ct = 0; ct < R2; ++ct)
                 for (int part = 0; part < 2; ++part)
                     fill_op(next(), f16, ks, ct, part, [&](int k2, int n2) {
-                        return cj(cm(wp(32, (int64_t)n2 * k2), wp(1024, (int64_t)k1 * n2)));
+                        return cj(cm(wp(N2, (int64_t)n2 * k2), wp(32 * N2, (int64_t)k1 * n2)));
                     });
-    if (o != BIG_U4) {
-        set_error("fused3 (32768): operand table size mismatch");
+    if (o != BG::U4) {
+        set_error("fused3 (32 x N2 x 32): operand table size mismatch");
         return FFTCONV_EINVAL;
     }
     // twiddles as 16-bit constants in the form TT::ctw4 expects
     const size_t cw = f16 ? 4 : 8;
-    std::vector<uint32_t> tw((size_t)2 * BM * (cw / 4));
+    std::vector<uint32_t> tw((size_t)2 * M * (cw / 4));
     auto put = [&](size_t idx, Cx v, bool conj) {
         const uint32_t re = f16 ? h_f16(v.re) : h_bf16(v.re), im = f16 ? h_f16(v.im) : h_bf16(v.im);
         if (f16) {
@@ -714,7 +725,7 @@ int fused3_big_init(fftconv_plan *p)
     };
     size_t e = 0;
     for (int n3 = 0; n3 < 32; ++n3)                       // twa: k1 = 16 ct + c16, n2 = 16 rt + 4 q + r
-        for (int rt = 0; rt < 2; ++rt)
+        for (int rt = 0; rt < R2; ++rt)
             for (int ct = 0; ct < 2; ++ct)
                 for (int r = 0; r < 4; ++r)
                     for (int lane = 0; lane < 64; ++lane) {
@@ -722,39 +733,61 @@ int fused3_big_init(fftconv_plan *p)
                         put(e++, wp(M, (int64_t)k1 * (32 * n2 + n3)), false);
                     }
     for (int k1 = 0; k1 < 32; ++k1)                       // twb: n3 = 16 ct3 + c16, k2 = 16 ct2 + 4 q + r
-        for (int ct2 = 0; ct2 < 2; ++ct2)
+        for (int ct2 = 0; ct2 < R2; ++ct2)
             for (int ct3 = 0; ct3 < 2; ++ct3)
                 for (int r = 0; r < 4; ++r)
                     for (int lane = 0; lane < 64; ++lane) {
                         const int n3 = 16 * ct3 + lane % 16, k2 = 16 * ct2 + 4 * (lane / 16) + r;
                         put(e++, wp(M, ((int64_t)k1 + 32 * (int64_t)k2) * n3), true);
                     }
-    const size_t bytes = BIG_U4 * 16 + tw.size() * 4;
+    const size_t bytes = BG::U4 * 16 + tw.size() * 4;
     FC_HIP(hipMalloc(&p->f3.consts, bytes));
     p->f3.consts_bytes += bytes;
-    FC_HIP(hipMemcpy(p->f3.consts, ops.data(), BIG_U4 * 16, hipMemcpyHostToDevice));
-    FC_HIP(hipMemcpy((char *)p->f3.consts + BIG_U4 * 16, tw.data(), tw.size() * 4, hipMemcpyHostToDevice));
+    FC_HIP(hipMemcpy(p->f3.consts, ops.data(), BG::U4 * 16, hipMemcpyHostToDevice));
+    FC_HIP(hipMemcpy((char *)p->f3.consts + BG::U4 * 16, tw.data(), tw.size() * 4, hipMemcpyHostToDevice));
     return FFTCONV_OK;
 }
 
+template <int N2>
+int big_pack_t(const fftconv_plan *p, const double2 *spec, int64_t h0, int64_t nh, const uint8_t *keep_dev,
+               int64_t n_blocks, void *kf, hipStream_t s)
+{
+    const int bs = 256;
+    const unsigned grid = (unsigned)((nh * BigGeo<N2>::M + bs - 1) / bs);
+    if (p->dtype == FFTCONV_F16)
+        hipLaunchKernelGGL((k_pack_big<H16, N2>), dim3(grid), dim3(bs), 0, s, spec, (uint32_t *)kf, staged_fac_list(p), h0,
+                           nh, keep_dev, n_blocks);
+    else
+        hipLaunchKernelGGL((k_pack_big<B16, N2>), dim3(grid), dim3(bs), 0, s, spec, (uint2 *)kf, staged_fac_list(p), h0,
+                           nh, keep_dev, n_blocks);
+    FC_HIP(hipGetLastError());
+    return FFTCONV_OK;
+}
+
+template <int N2>
+int big_forward_t(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, hipStream_t s)
+{
+    const bool full = (B % 2 == 0) && p->N == BigGeo<N2>::M / 2;
+    if (p->dtype == FFTCONV_F16)
+        return full ? launch_big<H16, true, N2>(p, u, kf, y, B, s) : launch_big<H16, false, N2>(p, u, kf, y, B, s);
+    return full ? launch_big<B16, true, N2>(p, u, kf, y, B, s) : launch_big<B16, false, N2>(p, u, kf, y, B, s);
+}
+
+}  // namespace
+
+// fft_size 32768 = 32 * 32 * 32 and 16384 = 32 * 16 * 32
+int fused3_big_init(fftconv_plan *p) { return p->M == 32768 ? big_init_t<32>(p) : big_init_t<16>(p); }
+
 size_t fused3_big_kf_bytes(const fftconv_plan *p)
 {
-    return (size_t)(p->H * BM) * (p->dtype == FFTCONV_F16 ? sizeof(uint32_t) : sizeof(uint2));
+    return (size_t)(p->H * p->M) * (p->dtype == FFTCONV_F16 ? sizeof(uint32_t) : sizeof(uint2));
 }
 
 int fused3_big_pack_kf(const fftconv_plan *p, const double2 *spec, int64_t h0, int64_t nh, const uint8_t *keep_dev,
                        int64_t n_blocks, void *kf, hipStream_t s)
 {
-    const int bs = 256;
-    const unsigned grid = (unsigned)((nh * BM + bs - 1) / bs);
-    if (p->dtype == FFTCONV_F16)
-        hipLaunchKernelGGL(k_pack_big<H16>, dim3(grid), dim3(bs), 0, s, spec, (uint32_t *)kf, staged_fac_list(p), h0, nh,
-                           keep_dev, n_blocks);
-    else
-        hipLaunchKernelGGL(k_pack_big<B16>, dim3(grid), dim3(bs), 0, s, spec, (uint2 *)kf, staged_fac_list(p), h0, nh,
-                           keep_dev, n_blocks);
-    FC_HIP(hipGetLastError());
-    return FFTCONV_OK;
+    return p->M == 32768 ? big_pack_t<32>(p, spec, h0, nh, keep_dev, n_blocks, kf, s)
+                         : big_pack_t<16>(p, spec, h0, nh, keep_dev, n_blocks, kf, s);
 }
 
 int fused3_big_forward(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, hipStream_t s)
@@ -763,10 +796,7 @@ int fused3_big_forward(const fftconv_plan *p, const void *u, const void *kf, voi
         set_error("fftconv_forward: u and y must be 16-byte aligned for this plan");
         return FFTCONV_EINVAL;
     }
-    const bool full = (B % 2 == 0) && p->N == BM / 2;
-    if (p->dtype == FFTCONV_F16)
-        return full ? launch_big<H16, true>(p, u, kf, y, B, s) : launch_big<H16, false>(p, u, kf, y, B, s);
-    return full ? launch_big<B16, true>(p, u, kf, y, B, s) : launch_big<B16, false>(p, u, kf, y, B, s);
+    return p->M == 32768 ? big_forward_t<32>(p, u, kf, y, B, s) : big_forward_t<16>(p, u, kf, y, B, s);
 }
 
 }  // namespace f3

@@ -140,7 +140,7 @@ def test_fused3_fft16384(dtype, B, H, N):
     err, plan = check_all_sequences(w)
     print("fused 16384 %s B=%d H=%d N=%d path=%s factors=%s err=%.3e" % (dtype, B, H, N, plan.path, plan.factors, err),
           flush=True)
-    assert plan.path == "fused3" and plan.factors == [32, 32, 16]
+    assert plan.path == "fused3" and plan.factors == [32, 16, 32]
     assert err <= TOL[dtype]
 
 
