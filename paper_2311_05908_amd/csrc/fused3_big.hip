@@ -11,13 +11,15 @@
 //    of the next pair waits in registers until then.
 //  * The per-plane constant tables (stage-2 matrices with folded twiddles, elementwise twiddles,
 //    k_f) do not fit in registers: they are streamed from L2, each one plane ahead of its use.
-//    Twiddles and k_f are 16-bit (re, im) constants for packed arithmetic (fp16: 4 bytes per
-//    point, op_sel / neg modifiers do the complex product; bf16: 8 bytes, dot-product form).
+//    Twiddles and k_f are 16-bit (re, im) constants, 4 bytes per point (fp16: packed arithmetic,
+//    op_sel / neg modifiers do the complex product; bf16: dot-product form, the swapped pair is
+//    derived in registers).  The load path of a compute unit moves about 64 bytes per clock
+//    whether a line comes from L1 or L2, and streaming these tables is the largest single cost
+//    of the kernel, so table bytes count for more than a few vector instructions.
 //  * The inverse innermost stage reuses the forward stage-3 matrix: the pointwise product writes
 //    conj(A3 * k_f), the (symmetric) forward matrix then yields the conjugate of the inverse
 //    transform, and the following twiddle product conjugates back.  Both conjugations are free
-//    (instruction modifiers for fp16, sign pattern of the constants for bf16), and 32 registers
-//    of matrix are saved.
+//    (instruction modifiers), and 32 registers of matrix are saved.
 //  * Schedule per pair, 5 workgroup barriers: [phase B] | [phase C into registers] | [y and the next
 //    u into the staging areas] | [staging into registers] | [phase A of the next pair, store y].
 #include <cmath>
@@ -35,6 +37,15 @@ __device__ unsigned long long g_stamps_big[8 * 8 * 16];
         if (blockIdx.x == 3 && l == 0 && it >= 4 && it < 12)                                      \
             g_stamps_big[(w * 8 + (it - 4)) * 16 + (k)] = __builtin_amdgcn_s_memtime();           \
     } while (0)
+__device__ unsigned long long g_span_big[1024 * 2];
+extern "C" int fftconv_debug_span_big(unsigned long long *dst)
+{
+    return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(g_span_big), sizeof(g_span_big));
+}
+#define BSPAN(k)                                                                                  \
+    do {                                                                                          \
+        if (threadIdx.x == 0 && blockIdx.x < 1024) g_span_big[blockIdx.x * 2 + (k)] = __builtin_amdgcn_s_memtime(); \
+    } while (0)
 extern "C" int fftconv_debug_stamps_big(unsigned long long *dst)
 {
     return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(g_stamps_big), sizeof(g_stamps_big));
@@ -42,6 +53,7 @@ extern "C" int fftconv_debug_stamps_big(unsigned long long *dst)
 #define BPROBE(bit) (!(probe & (bit)))
 #else
 #define BSTAMP(k) do { } while (0)
+#define BSPAN(k) do { } while (0)
 #define BPROBE(bit) true
 #endif
 
@@ -55,29 +67,61 @@ template <int N2> struct BigGeo {
     static constexpr int M = 1024 * N2;
     static constexpr int R2 = N2 / 16;                    // 16-wide tiles of the middle digit
     static constexpr int PK1 = N2 + 4;                    // X(k1,k2,n3) word = n3*PN3 + k1*PK1 + k2
-    static constexpr int PN3 = 32 * PK1 + 4;
+    // 4 words off a multiple of 32; short rather than long for the smaller size (the last k1 row
+    // needs no padding), which brings two workgroups' buffers under the 160 KB of a compute unit
+    static constexpr int PN3 = 32 * PK1 + (N2 == 16 ? -4 : 4);
     static constexpr int XB_WORDS = 32 * PN3;
     static constexpr size_t LDS_BYTES = (size_t)XB_WORDS * 4;
     static constexpr int NCH = M / 4096;                  // 16-byte chunks of a pair's input per thread
     static constexpr size_t U4 = (size_t)(4 + 4 + 8 + 2 * 32 * R2 * R2 * 2) * 64;   // operand tables, uint4 entries
 };
 
-// bf16: dot-product form.  Constant of a factor (wr, wi): { (wr, -wi), (wi, wr) }, which yields
-// z * w; the tables of the conjugating products hold { (wr, -wi), (-wi, -wr) } instead, which yields
-// conj(z * w) from the same instructions (CONJ is a table matter for this type).
+// bf16: dot-product form.  Constant of a factor: the pair (wr, wi), 4 bytes (every constant is
+// streamed from L2 once per use, and the load path of a compute unit is what bounds the kernel:
+// an 8-byte form ready for both dot products costs more than the one rotate that derives the
+// swapped pair here).  With z = (zr, zi) rounded to bf16:
+//   re = dot(z, (wr, wi)) with the high product negated      = zr wr - zi wi
+//   im = dot(z, (wi, wr))                                    = zr wi + zi wr     CONJ negates both products.
+// Results accumulate in fp32 and are rounded once into the packed pair.  One asm block: the
+// compiler would pick the accumulate-only form of the dot product (an extra move each), and a
+// DOT result may be read by another vector op only 3 issue slots later on this target, which the
+// order below respects.
 struct B16 {
-    using CW = uint2;
+    using CW = uint32_t;
     static __device__ __forceinline__ f32x4 mfma(uint4 a, uint4 b, f32x4 c) { return BF16::mfma(a, b, c); }
     static __device__ __forceinline__ uint32_t pack(float lo, float hi) { return BF16::pack(lo, hi); }
     template <bool CONJ> static __device__ __forceinline__ uint4 ctw4(f32x4 re, f32x4 im, const CW (&c)[4])
     {
-        return BF16::ctw4(re, im, c);
+        const uint32_t p0 = pack(re[0], im[0]), p1 = pack(re[1], im[1]);
+        const uint32_t p2 = pack(re[2], im[2]), p3 = pack(re[3], im[3]);
+        uint32_t t0, t1, t2, t3, t4, t5, t6, t7;
+#define B16_CTW4(IMNEG)                                                                            \
+        asm("v_alignbit_b32 %1, %12, %12, 16\n\t"                                                   \
+            "v_alignbit_b32 %3, %13, %13, 16\n\t"                                                   \
+            "v_alignbit_b32 %5, %14, %14, 16\n\t"                                                   \
+            "v_alignbit_b32 %7, %15, %15, 16\n\t"                                                   \
+            "v_dot2_f32_bf16 %0, %8, %12, 0 neg_hi:[0,1,0]\n\t"                                     \
+            "v_dot2_f32_bf16 %1, %8, %1, 0" IMNEG "\n\t"                                            \
+            "v_dot2_f32_bf16 %2, %9, %13, 0 neg_hi:[0,1,0]\n\t"                                     \
+            "v_dot2_f32_bf16 %3, %9, %3, 0" IMNEG "\n\t"                                            \
+            "v_dot2_f32_bf16 %4, %10, %14, 0 neg_hi:[0,1,0]\n\t"                                    \
+            "v_dot2_f32_bf16 %5, %10, %5, 0" IMNEG "\n\t"                                           \
+            "v_dot2_f32_bf16 %6, %11, %15, 0 neg_hi:[0,1,0]\n\t"                                    \
+            "v_dot2_f32_bf16 %7, %11, %7, 0" IMNEG "\n\t"                                           \
+            "v_cvt_pk_bf16_f32 %0, %0, %1\n\t"                                                      \
+            "v_cvt_pk_bf16_f32 %2, %2, %3\n\t"                                                      \
+            "v_cvt_pk_bf16_f32 %4, %4, %5\n\t"                                                      \
+            "v_cvt_pk_bf16_f32 %6, %6, %7"                                                          \
+            : "=&v"(t0), "=&v"(t1), "=&v"(t2), "=&v"(t3), "=&v"(t4), "=&v"(t5), "=&v"(t6), "=&v"(t7) \
+            : "v"(p0), "v"(p1), "v"(p2), "v"(p3), "v"(c[0]), "v"(c[1]), "v"(c[2]), "v"(c[3]))
+        if constexpr (CONJ)
+            B16_CTW4(" neg_lo:[0,1,0] neg_hi:[0,1,0]");
+        else
+            B16_CTW4("");
+#undef B16_CTW4
+        return make_uint4(t0, t2, t4, t6);
     }
-    static __host__ __device__ inline CW cconst(uint32_t re, uint32_t im, bool conj)   // 16-bit patterns
-    {
-        const uint32_t nre = re ^ 0x8000u, nim = im ^ 0x8000u;
-        return conj ? make_uint2(re | (nim << 16), nim | (nre << 16)) : make_uint2(re | (nim << 16), im | (re << 16));
-    }
+    static __host__ __device__ inline CW cconst(uint32_t re, uint32_t im, bool) { return re | (im << 16); }   // 16-bit patterns
 };
 
 // fp16: packed arithmetic.  Constant of a factor: the pair (wr, wi); the operand selectors
@@ -129,7 +173,7 @@ template <typename CW> struct BigConsts {
 
 // FULL: B even and N == fft_size / 2, every access of a work item is in range.
 template <typename TT, bool FULL, int N2>
-__global__ void __launch_bounds__(NT) k_fused3_big(const uint16_t *__restrict__ u, uint16_t *__restrict__ y,
+__global__ void __launch_bounds__(NT, N2 == 16 ? 4 : 2) k_fused3_big(const uint16_t *__restrict__ u, uint16_t *__restrict__ y,
                                                   const typename TT::CW *__restrict__ kf, BigConsts<typename TT::CW> cs,
                                                   int B, int H, int N, int probe)
 {
@@ -148,6 +192,7 @@ __global__ void __launch_bounds__(NT) k_fused3_big(const uint16_t *__restrict__ 
     const int x = blockIdx.x % nx, nb = gridDim.x / nx, jb = blockIdx.x / nx;
     const int n_local = ((H - x + nx - 1) / nx) * npairs;         // work items of this die
     if (jb >= n_local) return;
+    BSPAN(0);
     auto item = [&](int v) { return ((v / npairs) * nx + x) * npairs + v % npairs; };
     const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
 
@@ -160,8 +205,11 @@ __global__ void __launch_bounds__(NT) k_fused3_big(const uint16_t *__restrict__ 
     uint32_t *const wrB1 = wrB0 + 16 * BPN3;                                      // n3 tile 1
 
     uint4 tab1[2][2], tab1i[2][2], tab3[2][2][2];
-    uint4 tabA[R2][R2][2], tabB[R2][R2][2];      // stage-2 / inverse stage-2 matrices of the current plane
-    CW twaR[R2][2][4], twbR[R2][2][4], kfR[R2][2][4];
+    // streamed per-plane tables, PD planes in flight (plane i lives in slot i % PD): the smaller transform
+    // has short planes and spare registers, so it requests two planes ahead
+    constexpr int PD = 1;
+    uint4 tabA[PD][R2][R2][2], tabB[PD][R2][R2][2];      // stage-2 / inverse stage-2 matrices
+    CW twaR[PD][R2][2][4], twbR[PD][R2][2][4], kfR[PD][R2][2][4];
     uint4 pre[NCH];                               // next pair's input, 16-byte chunks in memory order
     uint2 x1r[2][R2][4];                          // the same in operand order: [row of the pair][n2 tile][r], 4 n3 planes each
 
@@ -193,50 +241,50 @@ __global__ void __launch_bounds__(NT) k_fused3_big(const uint16_t *__restrict__ 
                 for (int p = 0; p < 2; ++p) tab3[a][b][p] = (cs.tab3 + ((a * 2 + b) * 2 + p) * 64)[lz];
     };
     auto load_tabA = [&](int i) {
-        const int c = 4 * w + i;
+        const int c = BPROBE(4) ? 4 * w + i : 0, sl = i % PD;
 #pragma unroll
         for (int a = 0; a < R2; ++a)
 #pragma unroll
             for (int b = 0; b < R2; ++b)
 #pragma unroll
-                for (int p = 0; p < 2; ++p) tabA[a][b][p] = (cs.tab2 + (((c * R2 + a) * R2 + b) * 2 + p) * 64)[lz];
+                for (int p = 0; p < 2; ++p) tabA[sl][a][b][p] = (cs.tab2 + (((c * R2 + a) * R2 + b) * 2 + p) * 64)[lz];
     };
     auto load_twa = [&](int i) {
-        const int c = 4 * w + i;
+        const int c = BPROBE(4) ? 4 * w + i : 0, sl = i % PD;
 #pragma unroll
         for (int a = 0; a < R2; ++a)
 #pragma unroll
             for (int b = 0; b < 2; ++b)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) twaR[a][b][r] = (cs.twa + (((c * R2 + a) * 2 + b) * 4 + r) * 64)[lz];
+                for (int r = 0; r < 4; ++r) twaR[sl][a][b][r] = (cs.twa + (((c * R2 + a) * 2 + b) * 4 + r) * 64)[lz];
     };
     auto load_tabB = [&](int i) {
-        const int c = 4 * w + i;
+        const int c = BPROBE(4) ? 4 * w + i : 0, sl = i % PD;
 #pragma unroll
         for (int a = 0; a < R2; ++a)
 #pragma unroll
             for (int b = 0; b < R2; ++b)
 #pragma unroll
-                for (int p = 0; p < 2; ++p) tabB[a][b][p] = (cs.tab2i + (((c * R2 + a) * R2 + b) * 2 + p) * 64)[lz];
+                for (int p = 0; p < 2; ++p) tabB[sl][a][b][p] = (cs.tab2i + (((c * R2 + a) * R2 + b) * 2 + p) * 64)[lz];
     };
     auto load_twb = [&](int i) {
-        const int c = 4 * w + i;
+        const int c = BPROBE(4) ? 4 * w + i : 0, sl = i % PD;
 #pragma unroll
         for (int a = 0; a < R2; ++a)
 #pragma unroll
             for (int b = 0; b < 2; ++b)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) twbR[a][b][r] = (cs.twb + (((c * R2 + a) * 2 + b) * 4 + r) * 64)[lz];
+                for (int r = 0; r < 4; ++r) twbR[sl][a][b][r] = (cs.twb + (((c * R2 + a) * 2 + b) * 4 + r) * 64)[lz];
     };
     auto load_kf = [&](int i, int h) {
-        const int c = 4 * w + i;
+        const int c = BPROBE(4) ? 4 * w + i : 0, sl = i % PD;
 #pragma unroll
         for (int a = 0; a < R2; ++a)
 #pragma unroll
             for (int b = 0; b < 2; ++b)
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
-                    kfR[a][b][r] = (kf + (size_t)h * BM + (((c * R2 + a) * 2 + b) * 4 + r) * 64)[lz];
+                    kfR[sl][a][b][r] = (kf + (size_t)(BPROBE(4) ? h : 0) * BM + (((c * R2 + a) * 2 + b) * 4 + r) * 64)[lz];
     };
     // Input and output pass through LDS so that HBM sees whole 16-byte chunks in memory order
     // (8-byte pieces of a 64-byte row written by 8 different waves cost partial-line fills and
@@ -315,11 +363,11 @@ __global__ void __launch_bounds__(NT) k_fused3_big(const uint16_t *__restrict__ 
                     const f32x4 dre = TT::mfma(x1, tab1[ct][0], zero4);
                     const f32x4 dim = TT::mfma(x1, tab1[ct][1], zero4);
                     // lane: k1 = 16 ct + c16; reg r: n2 = 16 rt + 4q + r
-                    x2[ct][rt] = TT::template ctw4<false>(dre, dim, twaR[rt][ct]);
+                    x2[ct][rt] = TT::template ctw4<false>(dre, dim, twaR[i % PD][rt][ct]);
                 }
             }
             SCHED_FENCE();
-            if (i + 1 < 4 && BPROBE(2)) load_twa(i + 1);
+            if (i + PD < 4 && BPROBE(2)) load_twa(i + PD);
             SCHED_FENCE();
 #pragma unroll
             for (int ct = 0; ct < 2; ++ct)
@@ -328,8 +376,8 @@ __global__ void __launch_bounds__(NT) k_fused3_big(const uint16_t *__restrict__ 
                     f32x4 dre = zero4, dim = zero4;
 #pragma unroll
                     for (int ks = 0; ks < R2; ++ks) {     // matrix as the A operand: rows k2, data columns k1
-                        dre = TT::mfma(tabA[ks][ct2][0], x2[ct][ks], dre);
-                        dim = TT::mfma(tabA[ks][ct2][1], x2[ct][ks], dim);
+                        dre = TT::mfma(tabA[i % PD][ks][ct2][0], x2[ct][ks], dre);
+                        dim = TT::mfma(tabA[i % PD][ks][ct2][1], x2[ct][ks], dim);
                     }
                     // lane: k1 = 16 ct + c16; reg r: k2 = 16 ct2 + 4q + r -> one 16-byte write
                     uint32_t *dst = wrA + i * BPN3 + 16 * ct * BPK1 + 16 * ct2;
@@ -337,7 +385,7 @@ __global__ void __launch_bounds__(NT) k_fused3_big(const uint16_t *__restrict__ 
                                                TT::pack(dre[2], dim[2]), TT::pack(dre[3], dim[3]));
                 }
             SCHED_FENCE();
-            if (i + 1 < 4 && BPROBE(2)) load_tabA(i + 1);
+            if (i + PD < 4 && BPROBE(2)) load_tabA(i + PD);
             SCHED_FENCE();
         }
     };
@@ -440,13 +488,11 @@ __global__ void __launch_bounds__(NT) k_fused3_big(const uint16_t *__restrict__ 
                         dim = TT::mfma(tab3[ks][ct3][1], x3[ct2][ks], dim);
                     }
                     // lane: k2 = 16 ct2 + c16; reg r: k3 = 16 ct3 + 4q + r
-                    x3i[ct2][ct3] = TT::template ctw4<true>(dre, dim, kfR[ct2][ct3]);
+                    x3i[ct2][ct3] = TT::template ctw4<true>(dre, dim, kfR[i % PD][ct2][ct3]);
                 }
             SCHED_FENCE();
-            if (i + 1 < 4) {
-                if (BPROBE(1)) load_kf(i + 1, h);
-                read_plane(i + 1, x3);                    // its latency hides behind the rest of this plane
-            }
+            if (i + PD < 4 && BPROBE(1)) load_kf(i + PD, h);
+            if (i + 1 < 4) read_plane(i + 1, x3);         // its latency hides behind the rest of this plane
             SCHED_FENCE();
             uint4 x2i[2][R2];                             // [n3 tile][K step = k2 tile]
 #pragma unroll
@@ -460,10 +506,10 @@ __global__ void __launch_bounds__(NT) k_fused3_big(const uint16_t *__restrict__ 
                         dim = TT::mfma(x3i[ct2][ks], tab3[ks][cn3][1], dim);
                     }
                     // = conj of the inverse transform.  lane: n3 = 16 cn3 + c16; reg r: k2 = 16 ct2 + 4q + r
-                    x2i[cn3][ct2] = TT::template ctw4<true>(dre, dim, twbR[ct2][cn3]);
+                    x2i[cn3][ct2] = TT::template ctw4<true>(dre, dim, twbR[i % PD][ct2][cn3]);
                 }
             SCHED_FENCE();
-            if (i + 1 < 4 && BPROBE(1)) load_twb(i + 1);
+            if (i + PD < 4 && BPROBE(1)) load_twb(i + PD);
             SCHED_FENCE();
 #pragma unroll
             for (int cn3 = 0; cn3 < 2; ++cn3)
@@ -472,8 +518,8 @@ __global__ void __launch_bounds__(NT) k_fused3_big(const uint16_t *__restrict__ 
                     f32x4 dre = zero4, dim = zero4;
 #pragma unroll
                     for (int ks = 0; ks < R2; ++ks) {     // matrix as the A operand: rows n2, data columns n3
-                        dre = TT::mfma(tabB[ks][cn2][0], x2i[cn3][ks], dre);
-                        dim = TT::mfma(tabB[ks][cn2][1], x2i[cn3][ks], dim);
+                        dre = TT::mfma(tabB[i % PD][ks][cn2][0], x2i[cn3][ks], dre);
+                        dim = TT::mfma(tabB[i % PD][ks][cn2][1], x2i[cn3][ks], dim);
                     }
                     // lane: n3 = 16 cn3 + c16; reg r: n2 = 16 cn2 + 4q + r -> one 16-byte write
                     uint32_t *dst = (cn3 ? wrB1 : wrB0) + i * BPK1 + 16 * cn2;
@@ -481,7 +527,7 @@ __global__ void __launch_bounds__(NT) k_fused3_big(const uint16_t *__restrict__ 
                                                TT::pack(dre[2], dim[2]), TT::pack(dre[3], dim[3]));
                 }
             SCHED_FENCE();
-            if (i + 1 < 4 && BPROBE(1)) load_tabB(i + 1);
+            if (i + PD < 4 && BPROBE(1)) load_tabB(i + PD);
             SCHED_FENCE();
         }
     };
@@ -490,8 +536,11 @@ __global__ void __launch_bounds__(NT) k_fused3_big(const uint16_t *__restrict__ 
     opaque();
     issue_pre(item(jb));
     load_fixed_outer();
-    load_tabA(0);
-    load_twa(0);
+#pragma unroll
+    for (int i = 0; i < PD; ++i) {
+        load_tabA(i);
+        load_twa(i);
+    }
     stage_in();
     lds_barrier();
     read_x1();
@@ -499,9 +548,12 @@ __global__ void __launch_bounds__(NT) k_fused3_big(const uint16_t *__restrict__ 
     phase_A();
     SCHED_FENCE();
     load_tab3();
-    load_kf(0, item(jb) / npairs);
-    load_twb(0);
-    load_tabB(0);
+#pragma unroll
+    for (int i = 0; i < PD; ++i) {
+        load_kf(i, item(jb) / npairs);
+        load_twb(i);
+        load_tabB(i);
+    }
     SCHED_FENCE();
     lds_barrier();
 
@@ -520,8 +572,11 @@ __global__ void __launch_bounds__(NT) k_fused3_big(const uint16_t *__restrict__ 
         BSTAMP(1);
         // tables of the next phase and the next pair's input: in flight across the barrier and phase C
         load_fixed_outer();
-        load_tabA(0);
-        load_twa(0);
+#pragma unroll
+        for (int i = 0; i < PD; ++i) {
+            load_tabA(i);
+            load_twa(i);
+        }
         issue_pre(tn);
         SCHED_FENCE();
         lds_barrier();
@@ -544,9 +599,12 @@ __global__ void __launch_bounds__(NT) k_fused3_big(const uint16_t *__restrict__ 
         SCHED_FENCE();
         BSTAMP(9);
         load_tab3();
-        load_kf(0, tn / npairs);
-        load_twb(0);
-        load_tabB(0);
+#pragma unroll
+        for (int i = 0; i < PD; ++i) {
+            load_kf(i, tn / npairs);
+            load_twb(i);
+            load_tabB(i);
+        }
         SCHED_FENCE();
         // the stores go last: loads and stores retire through one counter on this target, and
         // nothing issued after them is waited for before the next barrier
@@ -555,6 +613,7 @@ __global__ void __launch_bounds__(NT) k_fused3_big(const uint16_t *__restrict__ 
         lds_barrier();
         BSTAMP(11);
     }
+    BSPAN(1);
 }
 
 // k_f in the kernel's per-lane order: [h][k1][k2 tile][k3 tile][r][lane]; the lane holds
@@ -658,14 +717,21 @@ int launch_big(const fftconv_plan *p, const void *u, const void *kf, void *y, in
     if (!attr_set) {
         FC_HIP(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)BG::LDS_BYTES));
         attr_set = true;
+#ifdef FUSED3_PROBE
+        int nblk = -1;
+        hipOccupancyMaxActiveBlocksPerMultiprocessor(&nblk, (const void *)kern, NT, BG::LDS_BYTES);
+        fprintf(stderr, "k_fused3_big<N2=%d>: %d resident workgroups per compute unit, LDS %zu\n", N2, nblk, BG::LDS_BYTES);
+#endif
     }
     const int64_t T = p->H * ((B + 1) / 2);
     if (T >= ((int64_t)1 << 31) - 8) {
         set_error("fftconv_forward: H * ceil(B/2) = %lld work items exceed the fused kernel's limit", (long long)T);
         return FFTCONV_EUNSUPPORTED;
     }
-    // one persistent workgroup per compute unit, a multiple of 8 (see the kernel's work split)
-    int grid = (int)(T < p->f3.num_cu ? T : p->f3.num_cu);
+    // persistent workgroups, as many as are resident at once (two per compute unit for the smaller
+    // size: 80 KB of LDS and 128 registers each), a multiple of 8 (see the kernel's work split)
+    const int64_t resident = (int64_t)p->f3.num_cu * (N2 == 16 ? 2 : 1);
+    int grid = (int)(T < resident ? T : resident);
     if (grid >= 8) grid -= grid % 8;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NT), BG::LDS_BYTES, s, (const uint16_t *)u, (uint16_t *)y,
                        (const CW *)kf, (big_consts_at<CW, N2>(p->f3.consts)), (int)B, (int)p->H, (int)p->N, big_probe());
@@ -711,17 +777,10 @@ template <int N2> int big_init_t(fftconv_plan *p)
         return FFTCONV_EINVAL;
     }
     // twiddles as 16-bit constants in the form TT::ctw4 expects
-    const size_t cw = f16 ? 4 : 8;
-    std::vector<uint32_t> tw((size_t)2 * M * (cw / 4));
+    std::vector<uint32_t> tw((size_t)2 * M);
     auto put = [&](size_t idx, Cx v, bool conj) {
         const uint32_t re = f16 ? h_f16(v.re) : h_bf16(v.re), im = f16 ? h_f16(v.im) : h_bf16(v.im);
-        if (f16) {
-            tw[idx] = H16::cconst(re, im, conj);
-        } else {
-            const uint2 c = B16::cconst(re, im, conj);
-            tw[2 * idx] = c.x;
-            tw[2 * idx + 1] = c.y;
-        }
+        tw[idx] = f16 ? H16::cconst(re, im, conj) : B16::cconst(re, im, conj);
     };
     size_t e = 0;
     for (int n3 = 0; n3 < 32; ++n3)                       // twa: k1 = 16 ct + c16, n2 = 16 rt + 4 q + r
@@ -758,7 +817,7 @@ int big_pack_t(const fftconv_plan *p, const double2 *spec, int64_t h0, int64_t n
         hipLaunchKernelGGL((k_pack_big<H16, N2>), dim3(grid), dim3(bs), 0, s, spec, (uint32_t *)kf, staged_fac_list(p), h0,
                            nh, keep_dev, n_blocks);
     else
-        hipLaunchKernelGGL((k_pack_big<B16, N2>), dim3(grid), dim3(bs), 0, s, spec, (uint2 *)kf, staged_fac_list(p), h0,
+        hipLaunchKernelGGL((k_pack_big<B16, N2>), dim3(grid), dim3(bs), 0, s, spec, (uint32_t *)kf, staged_fac_list(p), h0,
                            nh, keep_dev, n_blocks);
     FC_HIP(hipGetLastError());
     return FFTCONV_OK;
@@ -780,7 +839,7 @@ int fused3_big_init(fftconv_plan *p) { return p->M == 32768 ? big_init_t<32>(p) 
 
 size_t fused3_big_kf_bytes(const fftconv_plan *p)
 {
-    return (size_t)(p->H * p->M) * (p->dtype == FFTCONV_F16 ? sizeof(uint32_t) : sizeof(uint2));
+    return (size_t)(p->H * p->M) * sizeof(uint32_t);
 }
 
 int fused3_big_pack_kf(const fftconv_plan *p, const double2 *spec, int64_t h0, int64_t nh, const uint8_t *keep_dev,
