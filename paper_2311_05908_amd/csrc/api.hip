@@ -338,7 +338,7 @@ int fftconv_forward_freq_sparse(const fftconv_plan *p, const void *u, const void
     }
     if (B == 0) return FFTCONV_OK;
     if (p->path == PATH_FUSED3)
-        return fused3_forward_sparse(p, u, k_f, y, B, fused3_live_slots(p, block_keep, n_blocks),
+        return fused3_forward_sparse(p, u, k_f, y, B, fused3_live_k3(p, block_keep, n_blocks),
                                      (hipStream_t)stream);
     return fftconv_forward(p, u, k_f, y, B, H, N, workspace, stream);
 }

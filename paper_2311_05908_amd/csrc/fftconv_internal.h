@@ -127,9 +127,9 @@ int fused3_pack_kf(const fftconv_plan *p, const double2 *spec, int64_t h0, int64
                    const uint8_t *keep_dev, int64_t n_blocks, void *kf, hipStream_t s);
 int fused3_forward(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, hipStream_t s);
 // frequency-sparse forward: live = number of accumulator registers (1..4) that can hold non-zero k_f
-int fused3_forward_sparse(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, int live,
+int fused3_forward_sparse(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, uint32_t live_k3,
                           hipStream_t s);
-int fused3_live_slots(const fftconv_plan *p, const uint8_t *block_keep, int64_t n_blocks);
+uint32_t fused3_live_k3(const fftconv_plan *p, const uint8_t *block_keep, int64_t n_blocks);
 // partial convolution by overlapping short segments; returns FFTCONV_EUNSUPPORTED if this plan / Nk cannot
 bool fused3_short_ok(const fftconv_plan *p, int64_t Nk);
 int fused3_pack_kf_short(const fftconv_plan *p, const double2 *spec, int64_t h0, int64_t nh, void *kf, hipStream_t s);

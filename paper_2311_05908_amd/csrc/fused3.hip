@@ -789,20 +789,30 @@ int fused3_init(fftconv_plan *p)
     }
 }
 
-int fused3_forward_sparse(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, int live,
+// Frequency-sparse filter (Appendix A.4): live_k3 comes from fused3_live_k3().  The kernels for
+// 16384 and 32768 skip the half of the innermost stage that only meets zeroed bins when the mask
+// allows; the 8192 kernel runs dense (same result: the zeroed bins are zero in k_f).
+int fused3_forward_sparse(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, uint32_t live_k3,
                           hipStream_t s)
 {
-    (void)live;
+    if (p->M == 16384 || p->M == 32768) {
+        if (((uintptr_t)u | (uintptr_t)y) & 15) {
+            set_error("fftconv_forward_freq_sparse: u and y must be 16-byte aligned for this plan");
+            return FFTCONV_EINVAL;
+        }
+        return fused3_big_forward(p, u, kf, y, B, live_k3, s);
+    }
     return fused3_forward(p, u, kf, y, B, s);
 }
 
-// Number of accumulator registers (1..4) of stage 3 that can meet a non-zero bin under a block mask
-// (mirror bins count: a bin keeps weight 1/2 when only its mirror is kept).
-int fused3_live_slots(const fftconv_plan *p, const uint8_t *block_keep, int64_t n_blocks)
+// Which values of the most significant frequency digit k3 (f = k1 + 32 k2 + 32 N2 k3) can meet a
+// non-zero bin under a block mask: bit k3 of the result.  Mirror bins count: two real rows share
+// one complex transform, so a bin keeps weight 1/2 when only its mirror image M - f is kept.
+uint32_t fused3_live_k3(const fftconv_plan *p, const uint8_t *block_keep, int64_t n_blocks)
 {
     const int N3 = p->f3.N3;
     const int64_t per_row = p->M / N3, per_blk = p->M / n_blocks;
-    int live = 1;
+    uint32_t live = 0;
     for (int k3 = 0; k3 < N3; ++k3) {
         bool kept = false;
         for (int side = 0; side < 2 && !kept; ++side) {
@@ -821,10 +831,7 @@ int fused3_live_slots(const fftconv_plan *p, const uint8_t *block_keep, int64_t 
             }
             for (int64_t b = lo / per_blk; b <= hi / per_blk && !kept; ++b) kept = block_keep[b] != 0;
         }
-        if (kept) {
-            const int r = k3_index(k3, N3) % 4;
-            if (r + 1 > live) live = r + 1;
-        }
+        if (kept) live |= 1u << k3;
     }
     return live;
 }
@@ -949,7 +956,7 @@ int fused3_forward(const fftconv_plan *p, const void *u, const void *kf, void *y
         return fused3_ws_launch(p, p->f3.consts, u, kf, y, B, 1, 0, s);     // wave-specialised schedule (fused3_ws.hip)
     case 16384:
     case 32768:
-        return fused3_big_forward(p, u, kf, y, B, s);
+        return fused3_big_forward(p, u, kf, y, B, 0xffffffffu, s);
     default:
         set_error("fused3: no kernel for fft_size=%lld", (long long)p->M);
         return FFTCONV_EUNSUPPORTED;

@@ -76,6 +76,27 @@ template <int N2> struct BigGeo {
     static constexpr size_t U4 = (size_t)(4 + 4 + 8 + 2 * 32 * R2 * R2 * 2) * 64;   // operand tables, uint4 entries
 };
 
+// Order of the innermost digit (n3 in time, k3 in frequency; 32 values) inside phase B: slot
+// m = 16 tile + 4 q + r of a stage-3 operand or result holds digit sigma(m).  Tile 0 holds the
+// 16 digits nearest zero on the circle ({0..7} and {24..31}), tile 1 the rest.  k3 is the most
+// significant digit of the natural frequency, so a filter whose spectrum is confined to low
+// |f| (Appendix A.4: sparsity in the first dimension of k_f) leaves tile 1 of k3 empty, and the
+// HALF3 kernels skip its matrix products, its k_f and its share of the inverse contraction.
+// The same order on both digits keeps the stage-3 matrix symmetric (see the conjugation trick
+// above); on the n3 side it only changes which LDS rows a lane addresses.
+__host__ __device__ inline int big_sigma(int m)
+{
+    const int t = m / 16, q = (m % 16) / 4, r = m % 4;
+    const int base = t == 0 ? (q < 2 ? 4 * q : 16 + 4 * q) : 8 + 4 * q;
+    return base + r;
+}
+__host__ __device__ inline int big_sigma_inv(int d)
+{
+    if (d < 8) return d;
+    if (d >= 24) return d - 16;
+    return 16 + (d - 8);
+}
+
 // bf16: dot-product form.  Constant of a factor: the pair (wr, wi), 4 bytes (every constant is
 // streamed from L2 once per use, and the load path of a compute unit is what bounds the kernel:
 // an 8-byte form ready for both dot products costs more than the one rotate that derives the
@@ -172,7 +193,8 @@ template <typename CW> struct BigConsts {
 #define SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
 
 // FULL: B even and N == fft_size / 2, every access of a work item is in range.
-template <typename TT, bool FULL, int N2>
+// HALF3: k_f is zero wherever k3 is in tile 1 of the order above.
+template <typename TT, bool FULL, int N2, bool HALF3>
 __global__ void __launch_bounds__(NT, N2 == 16 ? 4 : 2) k_fused3_big(const uint16_t *__restrict__ u, uint16_t *__restrict__ y,
                                                   const typename TT::CW *__restrict__ kf, BigConsts<typename TT::CW> cs,
                                                   int B, int H, int N, int probe)
@@ -180,6 +202,7 @@ __global__ void __launch_bounds__(NT, N2 == 16 ? 4 : 2) k_fused3_big(const uint1
     using CW = typename TT::CW;
     using BG = BigGeo<N2>;
     constexpr int BM = BG::M, BPK1 = BG::PK1, BPN3 = BG::PN3, R2 = BG::R2, NCH = BG::NCH;
+    constexpr int T3 = HALF3 ? 1 : 2;                             // live k3 tiles
     extern __shared__ uint32_t XB[];
     const int tid = threadIdx.x, l = tid & 63, q = l >> 4, c16 = l & 15;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -199,10 +222,11 @@ __global__ void __launch_bounds__(NT, N2 == 16 ? 4 : 2) k_fused3_big(const uint1
     // LDS base addresses of this lane, chosen so that every access below is base + a small constant
     uint32_t *const wrA = XB + 4 * w * BPN3 + c16 * BPK1 + 4 * q;         // + i*BPN3 + 16 ct*BPK1 + 16 ct2
     const uint32_t *const rdC = XB + 4 * w * BPN3 + 4 * q * BPK1 + c16;   // + i*BPN3 + (16 ks + r)*BPK1 + 16 cn2
-    const uint32_t *const rdB0 = XB + (4 * q) * BPN3 + 4 * w * BPK1 + c16;        // + r*BPN3 + i*BPK1 + 16 ct2
-    const uint32_t *const rdB1 = rdB0 + 16 * BPN3;                                // K step 1
-    uint32_t *const wrB0 = XB + c16 * BPN3 + 4 * w * BPK1 + 4 * q;                // + i*BPK1 + 16 cn2
-    uint32_t *const wrB1 = wrB0 + 16 * BPN3;                                      // n3 tile 1
+    // phase B addresses n3 in the order big_sigma(): slots 4q .. 4q+3 of a tile are adjacent rows
+    const uint32_t *const rdB0 = XB + big_sigma(4 * q) * BPN3 + 4 * w * BPK1 + c16;       // + r*BPN3 + i*BPK1 + 16 ct2
+    const uint32_t *const rdB1 = XB + big_sigma(16 + 4 * q) * BPN3 + 4 * w * BPK1 + c16;  // K step 1
+    uint32_t *const wrB0 = XB + big_sigma(c16) * BPN3 + 4 * w * BPK1 + 4 * q;             // + i*BPK1 + 16 cn2
+    uint32_t *const wrB1 = XB + big_sigma(16 + c16) * BPN3 + 4 * w * BPK1 + 4 * q;        // n3 tile 1
 
     uint4 tab1[2][2], tab1i[2][2], tab3[2][2][2];
     // streamed per-plane tables, PD planes in flight (plane i lives in slot i % PD): the smaller transform
@@ -281,7 +305,7 @@ __global__ void __launch_bounds__(NT, N2 == 16 ? 4 : 2) k_fused3_big(const uint1
 #pragma unroll
         for (int a = 0; a < R2; ++a)
 #pragma unroll
-            for (int b = 0; b < 2; ++b)
+            for (int b = 0; b < T3; ++b)
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
                     kfR[sl][a][b][r] = (kf + (size_t)(BPROBE(4) ? h : 0) * BM + (((c * R2 + a) * 2 + b) * 4 + r) * 64)[lz];
@@ -462,7 +486,7 @@ __global__ void __launch_bounds__(NT, N2 == 16 ? 4 : 2) k_fused3_big(const uint1
 
     // ---- phase B of one pair: per k1 plane (4 per wave): stage 3, k_f, inverse 3, twiddle,
     // inverse 2, in place.  On entry tab3, kfR, twbR, tabB hold plane 0's tables.
-    auto phase_B = [&](int h) {
+    auto phase_B = [&](int h, [[maybe_unused]] int it) {
         auto read_plane = [&](int i, uint4 (&x)[R2][2]) {
 #pragma unroll
             for (int ct2 = 0; ct2 < R2; ++ct2)
@@ -480,14 +504,14 @@ __global__ void __launch_bounds__(NT, N2 == 16 ? 4 : 2) k_fused3_big(const uint1
 #pragma unroll
             for (int ct2 = 0; ct2 < R2; ++ct2)
 #pragma unroll
-                for (int ct3 = 0; ct3 < 2; ++ct3) {
+                for (int ct3 = 0; ct3 < T3; ++ct3) {
                     f32x4 dre = zero4, dim = zero4;
 #pragma unroll
                     for (int ks = 0; ks < 2; ++ks) {      // matrix is the A operand: rows k3, data columns k2
                         dre = TT::mfma(tab3[ks][ct3][0], x3[ct2][ks], dre);
                         dim = TT::mfma(tab3[ks][ct3][1], x3[ct2][ks], dim);
                     }
-                    // lane: k2 = 16 ct2 + c16; reg r: k3 = 16 ct3 + 4q + r
+                    // lane: k2 = 16 ct2 + c16; reg r: k3 = big_sigma(16 ct3 + 4q + r)
                     x3i[ct2][ct3] = TT::template ctw4<true>(dre, dim, kfR[i % PD][ct2][ct3]);
                 }
             SCHED_FENCE();
@@ -501,11 +525,11 @@ __global__ void __launch_bounds__(NT, N2 == 16 ? 4 : 2) k_fused3_big(const uint1
                 for (int cn3 = 0; cn3 < 2; ++cn3) {
                     f32x4 dre = zero4, dim = zero4;
 #pragma unroll
-                    for (int ks = 0; ks < 2; ++ks) {      // data rows k2, the forward matrix as the B operand
+                    for (int ks = 0; ks < T3; ++ks) {     // data rows k2, the forward matrix as the B operand
                         dre = TT::mfma(x3i[ct2][ks], tab3[ks][cn3][0], dre);
                         dim = TT::mfma(x3i[ct2][ks], tab3[ks][cn3][1], dim);
                     }
-                    // = conj of the inverse transform.  lane: n3 = 16 cn3 + c16; reg r: k2 = 16 ct2 + 4q + r
+                    // = conj of the inverse transform.  lane: n3 = big_sigma(16 cn3 + c16); reg r: k2 = 16 ct2 + 4q + r
                     x2i[cn3][ct2] = TT::template ctw4<true>(dre, dim, twbR[i % PD][ct2][cn3]);
                 }
             SCHED_FENCE();
@@ -529,6 +553,7 @@ __global__ void __launch_bounds__(NT, N2 == 16 ? 4 : 2) k_fused3_big(const uint1
             SCHED_FENCE();
             if (i + PD < 4 && BPROBE(1)) load_tabB(i + PD);
             SCHED_FENCE();
+            BSTAMP(12 + i);
         }
     };
 
@@ -567,7 +592,7 @@ __global__ void __launch_bounds__(NT, N2 == 16 ? 4 : 2) k_fused3_big(const uint1
         // Past the end of the range the last pair is prepared once more (in range, never used):
         // the loop body stays free of branches.
         const int t = item(v), tn = v + nb < n_local ? item(v + nb) : t;
-        phase_B(t / npairs);
+        phase_B(t / npairs, it);
         SCHED_FENCE();
         BSTAMP(1);
         // tables of the next phase and the next pair's input: in flight across the barrier and phase C
@@ -617,7 +642,7 @@ __global__ void __launch_bounds__(NT, N2 == 16 ? 4 : 2) k_fused3_big(const uint1
 }
 
 // k_f in the kernel's per-lane order: [h][k1][k2 tile][k3 tile][r][lane]; the lane holds
-// k2 = 16 tile + lane%16 and k3 = 16 tile + 4 (lane/16) + r.  Scaled by 1/M.
+// k2 = 16 tile + lane%16 and k3 = big_sigma(16 tile + 4 (lane/16) + r).  Scaled by 1/M.
 template <typename TT, int N2>
 __global__ void k_pack_big(const double2 *spec, typename TT::CW *kf, FacList fl, int64_t h0, int64_t nh,
                            const uint8_t *keep, int64_t n_blocks)
@@ -628,8 +653,9 @@ __global__ void k_pack_big(const double2 *spec, typename TT::CW *kf, FacList fl,
     if (idx >= nh * BM) return;
     const int64_t h = idx / BM, f = idx % BM;
     const int k1 = (int)(f % 32), k2 = (int)((f / 32) % N2), k3 = (int)(f / (32 * N2));
-    const int lane = ((k3 % 16) / 4) * 16 + (k2 % 16), r = k3 % 4;
-    const int64_t dst = ((((int64_t)k1 * R2 + k2 / 16) * 2 + k3 / 16) * 4 + r) * 64 + lane;
+    const int m3 = big_sigma_inv(k3);
+    const int lane = ((m3 % 16) / 4) * 16 + (k2 % 16), r = m3 % 4;
+    const int64_t dst = ((((int64_t)k1 * R2 + k2 / 16) * 2 + m3 / 16) * 4 + r) * 64 + lane;
     const double2 v = spec[h * BM + freq_to_pos(f, fl, BM)];
     const double sc = mask_weight(keep, n_blocks, f, BM) / (double)BM;
     const uint32_t pr = TT::pack((float)(v.x * sc), (float)(v.y * sc));      // (re, im) 16-bit pair
@@ -707,12 +733,12 @@ int big_probe()
 #endif
 }
 
-template <typename TT, bool FULL, int N2>
+template <typename TT, bool FULL, int N2, bool HALF3>
 int launch_big(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, hipStream_t s)
 {
     using CW = typename TT::CW;
     using BG = BigGeo<N2>;
-    auto kern = k_fused3_big<TT, FULL, N2>;
+    auto kern = k_fused3_big<TT, FULL, N2, HALF3>;
     static bool attr_set = false;
     if (!attr_set) {
         FC_HIP(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)BG::LDS_BYTES));
@@ -757,7 +783,8 @@ template <int N2> int big_init_t(fftconv_plan *p)
     for (int ks = 0; ks < 2; ++ks)                        // tab3 (forward; also serves the inverse, see the kernel)
         for (int ct = 0; ct < 2; ++ct)
             for (int part = 0; part < 2; ++part)
-                fill_op(next(), f16, ks, ct, part, [&](int n3, int k3) { return wp(32, (int64_t)n3 * k3); });
+                fill_op(next(), f16, ks, ct, part,
+                        [&](int m3, int j3) { return wp(32, (int64_t)big_sigma(m3) * big_sigma(j3)); });   // slots, both digits
     for (int n3 = 0; n3 < 32; ++n3)                       // tab2
         for (int ks = 0; ks < R2; ++ks)
             for (int ct = 0; ct < R2; ++ct)
@@ -791,12 +818,12 @@ template <int N2> int big_init_t(fftconv_plan *p)
                         const int k1 = 16 * ct + lane % 16, n2 = 16 * rt + 4 * (lane / 16) + r;
                         put(e++, wp(M, (int64_t)k1 * (32 * n2 + n3)), false);
                     }
-    for (int k1 = 0; k1 < 32; ++k1)                       // twb: n3 = 16 ct3 + c16, k2 = 16 ct2 + 4 q + r
+    for (int k1 = 0; k1 < 32; ++k1)                       // twb: n3 = big_sigma(16 ct3 + c16), k2 = 16 ct2 + 4 q + r
         for (int ct2 = 0; ct2 < R2; ++ct2)
             for (int ct3 = 0; ct3 < 2; ++ct3)
                 for (int r = 0; r < 4; ++r)
                     for (int lane = 0; lane < 64; ++lane) {
-                        const int n3 = 16 * ct3 + lane % 16, k2 = 16 * ct2 + 4 * (lane / 16) + r;
+                        const int n3 = big_sigma(16 * ct3 + lane % 16), k2 = 16 * ct2 + 4 * (lane / 16) + r;
                         put(e++, wp(M, ((int64_t)k1 + 32 * (int64_t)k2) * n3), true);
                     }
     const size_t bytes = BG::U4 * 16 + tw.size() * 4;
@@ -823,13 +850,19 @@ int big_pack_t(const fftconv_plan *p, const double2 *spec, int64_t h0, int64_t n
     return FFTCONV_OK;
 }
 
-template <int N2>
-int big_forward_t(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, hipStream_t s)
+template <typename TT, int N2, bool HALF3>
+int big_forward_tt(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, hipStream_t s)
 {
     const bool full = (B % 2 == 0) && p->N == BigGeo<N2>::M / 2;
+    return full ? launch_big<TT, true, N2, HALF3>(p, u, kf, y, B, s) : launch_big<TT, false, N2, HALF3>(p, u, kf, y, B, s);
+}
+
+template <int N2>
+int big_forward_t(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, bool half3, hipStream_t s)
+{
     if (p->dtype == FFTCONV_F16)
-        return full ? launch_big<H16, true, N2>(p, u, kf, y, B, s) : launch_big<H16, false, N2>(p, u, kf, y, B, s);
-    return full ? launch_big<B16, true, N2>(p, u, kf, y, B, s) : launch_big<B16, false, N2>(p, u, kf, y, B, s);
+        return half3 ? big_forward_tt<H16, N2, true>(p, u, kf, y, B, s) : big_forward_tt<H16, N2, false>(p, u, kf, y, B, s);
+    return half3 ? big_forward_tt<B16, N2, true>(p, u, kf, y, B, s) : big_forward_tt<B16, N2, false>(p, u, kf, y, B, s);
 }
 
 }  // namespace
@@ -849,13 +882,19 @@ int fused3_big_pack_kf(const fftconv_plan *p, const double2 *spec, int64_t h0, i
                          : big_pack_t<16>(p, spec, h0, nh, keep_dev, n_blocks, kf, s);
 }
 
-int fused3_big_forward(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, hipStream_t s)
+// live_k3: bit d set when the digit k3 = d of the frequency (the most significant one, 32 values)
+// may meet a non-zero bin of k_f; all ones for a dense filter.
+int fused3_big_forward(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, uint32_t live_k3,
+                       hipStream_t s)
 {
     if (((uintptr_t)u | (uintptr_t)y) & 15) {
         set_error("fftconv_forward: u and y must be 16-byte aligned for this plan");
         return FFTCONV_EINVAL;
     }
-    return p->M == 32768 ? big_forward_t<32>(p, u, kf, y, B, s) : big_forward_t<16>(p, u, kf, y, B, s);
+    bool half3 = true;                                    // no live digit in tile 1 of the kernel's order
+    for (int d = 0; d < 32; ++d)
+        if (((live_k3 >> d) & 1u) && big_sigma_inv(d) >= 16) half3 = false;
+    return p->M == 32768 ? big_forward_t<32>(p, u, kf, y, B, half3, s) : big_forward_t<16>(p, u, kf, y, B, half3, s);
 }
 
 }  // namespace f3

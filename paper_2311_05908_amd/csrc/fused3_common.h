@@ -233,7 +233,8 @@ int fused3_big_init(fftconv_plan *p);
 size_t fused3_big_kf_bytes(const fftconv_plan *p);
 int fused3_big_pack_kf(const fftconv_plan *p, const double2 *spec, int64_t h0, int64_t nh, const uint8_t *keep_dev,
                        int64_t n_blocks, void *kf, hipStream_t s);
-int fused3_big_forward(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, hipStream_t s);
+int fused3_big_forward(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, uint32_t live_k3,
+                       hipStream_t s);
 
 }  // namespace f3
 }  // namespace fftconv
