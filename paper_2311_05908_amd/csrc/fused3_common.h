@@ -125,6 +125,98 @@ struct F16 {
     static constexpr int CFMT = 2;
 };
 
+// ---- complex products with 4-byte constants: the traits of the kernels that stream their tables
+//      or keep them in registers by the plane (fused3_big.hip, fused3_ws.hip)
+
+// bf16: dot-product form.  Constant of a factor: the pair (wr, wi), 4 bytes (every constant is
+// streamed from L2 once per use by the kernels for the larger sizes, whose bound is the load
+// path of a compute unit, and the others keep them in registers, where 4 bytes halve the cost:
+// an 8-byte form ready for both dot products costs more than the one rotate that derives the
+// swapped pair here).  With z = (zr, zi) rounded to bf16:
+//   re = dot(z, (wr, wi)) with the high product negated      = zr wr - zi wi
+//   im = dot(z, (wi, wr))                                    = zr wi + zi wr     CONJ negates both products.
+// Results accumulate in fp32 and are rounded once into the packed pair.  One asm block: the
+// compiler would pick the accumulate-only form of the dot product (an extra move each), and a
+// DOT result may be read by another vector op only 3 issue slots later on this target, which the
+// order below respects.
+struct B16 {
+    using CW = uint32_t;
+    static __device__ __forceinline__ f32x4 mfma(uint4 a, uint4 b, f32x4 c) { return BF16::mfma(a, b, c); }
+    static __device__ __forceinline__ uint32_t pack(float lo, float hi) { return BF16::pack(lo, hi); }
+    template <bool CONJ> static __device__ __forceinline__ uint4 ctw4(f32x4 re, f32x4 im, const CW (&c)[4])
+    {
+        const uint32_t p0 = pack(re[0], im[0]), p1 = pack(re[1], im[1]);
+        const uint32_t p2 = pack(re[2], im[2]), p3 = pack(re[3], im[3]);
+        uint32_t t0, t1, t2, t3, t4, t5, t6, t7;
+#define B16_CTW4(IMNEG)                                                                            \
+        asm("v_alignbit_b32 %1, %12, %12, 16\n\t"                                                   \
+            "v_alignbit_b32 %3, %13, %13, 16\n\t"                                                   \
+            "v_alignbit_b32 %5, %14, %14, 16\n\t"                                                   \
+            "v_alignbit_b32 %7, %15, %15, 16\n\t"                                                   \
+            "v_dot2_f32_bf16 %0, %8, %12, 0 neg_hi:[0,1,0]\n\t"                                     \
+            "v_dot2_f32_bf16 %1, %8, %1, 0" IMNEG "\n\t"                                            \
+            "v_dot2_f32_bf16 %2, %9, %13, 0 neg_hi:[0,1,0]\n\t"                                     \
+            "v_dot2_f32_bf16 %3, %9, %3, 0" IMNEG "\n\t"                                            \
+            "v_dot2_f32_bf16 %4, %10, %14, 0 neg_hi:[0,1,0]\n\t"                                    \
+            "v_dot2_f32_bf16 %5, %10, %5, 0" IMNEG "\n\t"                                           \
+            "v_dot2_f32_bf16 %6, %11, %15, 0 neg_hi:[0,1,0]\n\t"                                    \
+            "v_dot2_f32_bf16 %7, %11, %7, 0" IMNEG "\n\t"                                           \
+            "v_cvt_pk_bf16_f32 %0, %0, %1\n\t"                                                      \
+            "v_cvt_pk_bf16_f32 %2, %2, %3\n\t"                                                      \
+            "v_cvt_pk_bf16_f32 %4, %4, %5\n\t"                                                      \
+            "v_cvt_pk_bf16_f32 %6, %6, %7"                                                          \
+            : "=&v"(t0), "=&v"(t1), "=&v"(t2), "=&v"(t3), "=&v"(t4), "=&v"(t5), "=&v"(t6), "=&v"(t7) \
+            : "v"(p0), "v"(p1), "v"(p2), "v"(p3), "v"(c[0]), "v"(c[1]), "v"(c[2]), "v"(c[3]))
+        if constexpr (CONJ)
+            B16_CTW4(" neg_lo:[0,1,0] neg_hi:[0,1,0]");
+        else
+            B16_CTW4("");
+#undef B16_CTW4
+        return make_uint4(t0, t2, t4, t6);
+    }
+    static __host__ __device__ inline CW cconst(uint32_t re, uint32_t im, bool) { return re | (im << 16); }   // 16-bit patterns
+    // from the 8-byte table form of BF16::ctw4, { (wr, -wi), (wi, wr) }
+    static __device__ __forceinline__ CW from_table(uint2 c) { return c.x ^ 0x80000000u; }
+    static __device__ __forceinline__ uint4 mul8(uint4 a, uint4 b) { return BF16::mul8(a, b); }
+};
+
+// fp16: packed arithmetic.  Constant of a factor: the pair (wr, wi); the operand selectors
+// broadcast / swap halves and the neg modifiers supply the signs:
+//   t   = (zr*wr, zi*wr)
+//   out = (zi*(-wi) + t.lo, zr*wi + t.hi)            CONJ negates the high half of both steps.
+struct H16 {
+    using CW = uint32_t;
+    static __device__ __forceinline__ f32x4 mfma(uint4 a, uint4 b, f32x4 c) { return F16::mfma(a, b, c); }
+    static __device__ __forceinline__ uint32_t pack(float lo, float hi) { return F16::pack(lo, hi); }
+    static __host__ __device__ inline CW cconst(uint32_t re, uint32_t im, bool) { return re | (im << 16); }
+    // from the 8-byte table form of F16::ctw4, { (wr, wr), (-wi, wi) }
+    static __device__ __forceinline__ CW from_table(uint2 c) { return (c.x & 0xffffu) | (c.y & 0xffff0000u); }
+    static __device__ __forceinline__ uint4 mul8(uint4 a, uint4 b) { return F16::mul8(a, b); }
+    template <bool CONJ> static __device__ __forceinline__ uint4 ctw4(f32x4 re, f32x4 im, const CW (&c)[4])
+    {
+        uint32_t o[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const uint32_t p = pack(re[r], im[r]);
+            uint32_t t;
+            if constexpr (!CONJ) {
+                asm("v_pk_mul_f16 %0, %1, %2 op_sel:[0,0] op_sel_hi:[1,0]" : "=v"(t) : "v"(p), "v"(c[r]));
+                asm("v_pk_fma_f16 %0, %1, %2, %3 op_sel:[1,1,0] op_sel_hi:[0,1,1] neg_lo:[0,1,0]"
+                    : "=v"(o[r])
+                    : "v"(p), "v"(c[r]), "v"(t));
+            } else {
+                asm("v_pk_mul_f16 %0, %1, %2 op_sel:[0,0] op_sel_hi:[1,0] neg_hi:[0,1]"
+                    : "=v"(t)
+                    : "v"(p), "v"(c[r]));
+                asm("v_pk_fma_f16 %0, %1, %2, %3 op_sel:[1,1,0] op_sel_hi:[0,1,1] neg_lo:[0,1,0] neg_hi:[0,1,0]"
+                    : "=v"(o[r])
+                    : "v"(p), "v"(c[r]), "v"(t));
+            }
+        }
+        return make_uint4(o[0], o[1], o[2], o[3]);
+    }
+};
+
 // Workgroup barrier for exchanges through LDS only.  __syncthreads() also waits for every
 // outstanding global load and store of the wave (its fence covers global memory), which would
 // throw away the prefetches and stores these kernels keep in flight across barriers.  LDS
