@@ -74,6 +74,15 @@ template <int N2> struct BigGeo {
     static constexpr size_t LDS_BYTES = (size_t)XB_WORDS * 4;
     static constexpr int NCH = M / 4096;                  // 16-byte chunks of a pair's input per thread
     static constexpr size_t U4 = (size_t)(4 + 4 + 8 + 2 * 32 * R2 * R2 * 2) * 64;   // operand tables, uint4 entries
+    // byte offsets of the tables inside the constant block (layouts: see BigConsts)
+    static constexpr int OFF_TAB1 = 0, OFF_TAB1I = 4 * 1024, OFF_TAB3 = 8 * 1024, OFF_TAB2 = 16 * 1024;
+    static constexpr int PLANE2 = R2 * R2 * 2 * 1024;     // bytes of one plane's stage-2 matrix
+    static constexpr int OFF_TAB2I = OFF_TAB2 + 32 * PLANE2;
+    static constexpr int OFF_TWA = OFF_TAB2I + 32 * PLANE2;
+    static constexpr int PLANEW = R2 * 2 * 4 * 256;       // bytes of one plane's twiddles (and k_f)
+    static constexpr int OFF_TWB = OFF_TWA + 32 * PLANEW;
+    static constexpr int CONST_BYTES = OFF_TWB + 32 * PLANEW;
+    static_assert((size_t)OFF_TWA == U4 * 16 && 32 * PLANEW == M * 4, "table layout");
 };
 
 // Order of the innermost digit (n3 in time, k3 in frequency; 32 values) inside phase B: slot
@@ -97,15 +106,19 @@ __host__ __device__ inline int big_sigma_inv(int d)
     return 16 + (d - 8);
 }
 
-template <typename CW> struct BigConsts {
-    const uint4 *tab1;    // [ct][part][lane]                 W_32^{n1 k1}, n1 < 16
-    const uint4 *tab1i;   // [K step][part][lane]             conj(W_32^{k1 n1}), n1 < 16
-    const uint4 *tab3;    // [K step][tile][part][lane]       W_32^{n3 k3}
-    const uint4 *tab2;    // [n3][K step][tile][part][lane]   W_N2^{n2 k2} W_{32 N2}^{k2 n3}
-    const uint4 *tab2i;   // [k1][K step][tile][part][lane]   conj(W_N2^{k2 n2} W_{32 N2}^{k1 n2})
-    const CW *twa;        // [n3][rt][ct][r][lane]            W_M^{k1 (32 n2 + n3)}
-    const CW *twb;        // [k1][ct2][ct3][r][lane]          W_M^{(k1 + 32 k2) n3}, used as conj(z * w)
-};
+// The constant block of a plan, one allocation (byte offsets in BigGeo):
+//   tab1   [ct][part][lane] uint4                  W_32^{n1 k1}, n1 < 16
+//   tab1i  [K step][part][lane]                    conj(W_32^{k1 n1}), n1 < 16
+//   tab3   [K step][tile][part][lane]              W_32^{n3 k3}, both digits in the order big_sigma()
+//   tab2   [n3][K step][tile][part][lane]          W_N2^{n2 k2} W_{32 N2}^{k2 n3}
+//   tab2i  [k1][K step][tile][part][lane]          conj(W_N2^{k2 n2} W_{32 N2}^{k1 n2})
+//   twa    [n3][rt][ct][r][lane] 4-byte constants  W_M^{k1 (32 n2 + n3)}
+//   twb    [k1][ct2][ct3][r][lane]                 W_M^{(k1 + 32 k2) n3}, used as conj(z * w)
+// The kernel reads it, and k_f, through buffer descriptors: a load is then "descriptor + scalar
+// byte offset + lane offset + immediate", and the scalar offset of a plane is one SALU add.  With
+// plain pointers every 4 KB piece of a table needed a 64-bit base of its own; the compiler
+// computed those bases ahead of the loop and, out of scalar registers, parked them in vector
+// lanes, which cost a fifth of the kernel's vector instructions at N2 = 32.
 
 // nothing may be moved across: pins where the streamed table loads are issued
 #define SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
@@ -114,12 +127,12 @@ template <typename CW> struct BigConsts {
 // HALF3: k_f is zero wherever k3 is in tile 1 of the order above.
 template <typename TT, bool FULL, int N2, bool HALF3>
 __global__ void __launch_bounds__(NT, N2 == 16 ? 4 : 2) k_fused3_big(const uint16_t *__restrict__ u, uint16_t *__restrict__ y,
-                                                  const typename TT::CW *__restrict__ kf, BigConsts<typename TT::CW> cs,
-                                                  int B, int H, int N, int probe)
+                                                  const void *__restrict__ kf, const void *__restrict__ consts,
+                                                  uint32_t kf_bytes, int B, int H, int N, int probe)
 {
     using CW = typename TT::CW;
     using BG = BigGeo<N2>;
-    constexpr int BM = BG::M, BPK1 = BG::PK1, BPN3 = BG::PN3, R2 = BG::R2, NCH = BG::NCH;
+    constexpr int BPK1 = BG::PK1, BPN3 = BG::PN3, R2 = BG::R2, NCH = BG::NCH;
     constexpr int T3 = HALF3 ? 1 : 2;                             // live k3 tiles
     extern __shared__ uint32_t XB[];
     const int tid = threadIdx.x, l = tid & 63, q = l >> 4, c16 = l & 15;
@@ -156,22 +169,34 @@ __global__ void __launch_bounds__(NT, N2 == 16 ? 4 : 2) k_fused3_big(const uint1
     uint2 x1r[2][R2][4];                          // the same in operand order: [row of the pair][n2 tile][r], 4 n3 planes each
 
     // The tables are loop invariant but must be re-read for every work item (they do not fit in
-    // registers): an opaque zero added to the lane offset keeps the loads inside the loop.
-    // (unsigned, so that a load is "uniform base + 32-bit lane offset + immediate" and needs no
-    //  64-bit address registers)
-    uint32_t lz = (uint32_t)l;
+    // registers): opaque zeros added to the lane offset and to the scalar offset keep the loads,
+    // and the arithmetic of their offsets, inside the loop.
+    const __amdgpu_buffer_rsrc_t rc = __builtin_amdgcn_make_buffer_rsrc((void *)consts, 0, BG::CONST_BYTES, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rk = __builtin_amdgcn_make_buffer_rsrc((void *)kf, 0, (int)kf_bytes, 0x00020000);
+    int vo4 = 4 * l, vo16 = 16 * l, sz = 0;       // lane offsets of 4- and 16-byte entries; scalar zero
     auto opaque = [&]() {
-        uint32_t z = 0;
+        int z = 0;
         asm volatile("" : "+v"(z));
-        lz = ((uint32_t)l + z) & 63u;
+        vo4 = 4 * l + z;
+        vo16 = 16 * l + z;
+        asm volatile("s_mov_b32 %0, 0" : "=s"(sz));
+    };
+    // entry `ofs` (bytes, compile-time) of the piece that starts at scalar byte offset `base`
+    auto ld16 = [&](const __amdgpu_buffer_rsrc_t &r, int base, int ofs) {
+        typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+        const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, vo16 + (ofs & 4095), base + (ofs & ~4095), 0);
+        return make_uint4(v.x, v.y, v.z, v.w);
+    };
+    auto ld4 = [&](const __amdgpu_buffer_rsrc_t &r, int base, int ofs) {
+        return (CW)__builtin_amdgcn_raw_buffer_load_b32(r, vo4 + (ofs & 4095), base + (ofs & ~4095), 0);
     };
     auto load_fixed_outer = [&]() {
 #pragma unroll
         for (int a = 0; a < 2; ++a)
 #pragma unroll
             for (int p = 0; p < 2; ++p) {
-                tab1[a][p] = (cs.tab1 + (a * 2 + p) * 64)[lz];
-                tab1i[a][p] = (cs.tab1i + (a * 2 + p) * 64)[lz];
+                tab1[a][p] = ld16(rc, sz, BG::OFF_TAB1 + (a * 2 + p) * 1024);
+                tab1i[a][p] = ld16(rc, sz, BG::OFF_TAB1I + (a * 2 + p) * 1024);
             }
     };
     auto load_tab3 = [&]() {
@@ -180,53 +205,57 @@ __global__ void __launch_bounds__(NT, N2 == 16 ? 4 : 2) k_fused3_big(const uint1
 #pragma unroll
             for (int b = 0; b < 2; ++b)
 #pragma unroll
-                for (int p = 0; p < 2; ++p) tab3[a][b][p] = (cs.tab3 + ((a * 2 + b) * 2 + p) * 64)[lz];
+                for (int p = 0; p < 2; ++p) tab3[a][b][p] = ld16(rc, sz, BG::OFF_TAB3 + ((a * 2 + b) * 2 + p) * 1024);
     };
     auto load_tabA = [&](int i) {
         const int c = BPROBE(4) ? 4 * w + i : 0, sl = i % PD;
+        const int base = sz + c * BG::PLANE2;
 #pragma unroll
         for (int a = 0; a < R2; ++a)
 #pragma unroll
             for (int b = 0; b < R2; ++b)
 #pragma unroll
-                for (int p = 0; p < 2; ++p) tabA[sl][a][b][p] = (cs.tab2 + (((c * R2 + a) * R2 + b) * 2 + p) * 64)[lz];
+                for (int p = 0; p < 2; ++p) tabA[sl][a][b][p] = ld16(rc, base, BG::OFF_TAB2 + ((a * R2 + b) * 2 + p) * 1024);
     };
     auto load_twa = [&](int i) {
         const int c = BPROBE(4) ? 4 * w + i : 0, sl = i % PD;
+        const int base = sz + c * BG::PLANEW;
 #pragma unroll
         for (int a = 0; a < R2; ++a)
 #pragma unroll
             for (int b = 0; b < 2; ++b)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) twaR[sl][a][b][r] = (cs.twa + (((c * R2 + a) * 2 + b) * 4 + r) * 64)[lz];
+                for (int r = 0; r < 4; ++r) twaR[sl][a][b][r] = ld4(rc, base, BG::OFF_TWA + ((a * 2 + b) * 4 + r) * 256);
     };
     auto load_tabB = [&](int i) {
         const int c = BPROBE(4) ? 4 * w + i : 0, sl = i % PD;
+        const int base = sz + c * BG::PLANE2;
 #pragma unroll
         for (int a = 0; a < R2; ++a)
 #pragma unroll
             for (int b = 0; b < R2; ++b)
 #pragma unroll
-                for (int p = 0; p < 2; ++p) tabB[sl][a][b][p] = (cs.tab2i + (((c * R2 + a) * R2 + b) * 2 + p) * 64)[lz];
+                for (int p = 0; p < 2; ++p) tabB[sl][a][b][p] = ld16(rc, base, BG::OFF_TAB2I + ((a * R2 + b) * 2 + p) * 1024);
     };
     auto load_twb = [&](int i) {
         const int c = BPROBE(4) ? 4 * w + i : 0, sl = i % PD;
+        const int base = sz + c * BG::PLANEW;
 #pragma unroll
         for (int a = 0; a < R2; ++a)
 #pragma unroll
             for (int b = 0; b < 2; ++b)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) twbR[sl][a][b][r] = (cs.twb + (((c * R2 + a) * 2 + b) * 4 + r) * 64)[lz];
+                for (int r = 0; r < 4; ++r) twbR[sl][a][b][r] = ld4(rc, base, BG::OFF_TWB + ((a * 2 + b) * 4 + r) * 256);
     };
     auto load_kf = [&](int i, int h) {
         const int c = BPROBE(4) ? 4 * w + i : 0, sl = i % PD;
+        const int base = sz + ((BPROBE(4) ? h : 0) * 32 + c) * BG::PLANEW;
 #pragma unroll
         for (int a = 0; a < R2; ++a)
 #pragma unroll
             for (int b = 0; b < T3; ++b)
 #pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    kfR[sl][a][b][r] = (kf + (size_t)(BPROBE(4) ? h : 0) * BM + (((c * R2 + a) * 2 + b) * 4 + r) * 64)[lz];
+                for (int r = 0; r < 4; ++r) kfR[sl][a][b][r] = ld4(rk, base, ((a * 2 + b) * 4 + r) * 256);
     };
     // Input and output pass through LDS so that HBM sees whole 16-byte chunks in memory order
     // (8-byte pieces of a 64-byte row written by 8 different waves cost partial-line fills and
@@ -626,21 +655,6 @@ template <typename Fn> void fill_op(uint16_t *dst, bool f16, int t, int ct, int 
     }
 }
 
-template <typename CW, int N2> BigConsts<CW> big_consts_at(const void *base)
-{
-    using BG = BigGeo<N2>;
-    BigConsts<CW> c;
-    const uint4 *b = (const uint4 *)base;
-    c.tab1 = b;
-    c.tab1i = c.tab1 + 4 * 64;
-    c.tab3 = c.tab1i + 4 * 64;
-    c.tab2 = c.tab3 + 8 * 64;
-    c.tab2i = c.tab2 + 32 * BG::R2 * BG::R2 * 2 * 64;
-    c.twa = (const CW *)(c.tab2i + 32 * BG::R2 * BG::R2 * 2 * 64);
-    c.twb = c.twa + BG::M;
-    return c;
-}
-
 int big_probe()
 {
 #ifdef FUSED3_PROBE
@@ -654,7 +668,6 @@ int big_probe()
 template <typename TT, bool FULL, int N2, bool HALF3>
 int launch_big(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, hipStream_t s)
 {
-    using CW = typename TT::CW;
     using BG = BigGeo<N2>;
     auto kern = k_fused3_big<TT, FULL, N2, HALF3>;
     static bool attr_set = false;
@@ -668,6 +681,12 @@ int launch_big(const fftconv_plan *p, const void *u, const void *kf, void *y, in
 #endif
     }
     const int64_t T = p->H * ((B + 1) / 2);
+    const int64_t kf_bytes = p->H * BG::M * 4;
+    if (kf_bytes >= ((int64_t)1 << 31)) {
+        set_error("fftconv_forward: H * fft_size = %lld exceeds the fused kernel's k_f addressing (2^29 bins)",
+                  (long long)(p->H * BG::M));
+        return FFTCONV_EUNSUPPORTED;
+    }
     if (T >= ((int64_t)1 << 31) - 8) {
         set_error("fftconv_forward: H * ceil(B/2) = %lld work items exceed the fused kernel's limit", (long long)T);
         return FFTCONV_EUNSUPPORTED;
@@ -678,7 +697,7 @@ int launch_big(const fftconv_plan *p, const void *u, const void *kf, void *y, in
     int grid = (int)(T < resident ? T : resident);
     if (grid >= 8) grid -= grid % 8;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NT), BG::LDS_BYTES, s, (const uint16_t *)u, (uint16_t *)y,
-                       (const CW *)kf, (big_consts_at<CW, N2>(p->f3.consts)), (int)B, (int)p->H, (int)p->N, big_probe());
+                       kf, (const void *)p->f3.consts, (uint32_t)kf_bytes, (int)B, (int)p->H, (int)p->N, big_probe());
     FC_HIP(hipGetLastError());
     return FFTCONV_OK;
 }
