@@ -258,7 +258,7 @@ def main():
                    "speedup_vs_dense": None if dense_ms is None else dense_ms / ms_per_step},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": None if args.gated else measured_traffic(w.name),
-                     "kernel": ("k_fused3_ws" if w.fft_size == 8192 else "k_fused3") if plan.path == "fused3" else plan.path,
+                     "kernel": ("k_fused3_ws" if w.fft_size == 8192 else "k_fused3_big") if plan.path == "fused3" else plan.path,
                      "algorithmic_bytes": abytes},
     }
     if not args.no_cpu_baseline:
