@@ -75,10 +75,11 @@ def time_oracle(w, u_cpu, k, budget_s=12.0):
 
 
 def sweep(torch, fftconv, synth, dev, args):
-    """Causal forward pass, bf16, N = fft/2, B*H*N = 2^27 elements at every size (B*H >= 1)."""
+    """Forward pass, bf16, B*H*N = 2^27 elements at every size (B*H >= 1): causal (N = fft/2) or,
+    with --circular, the input filling the transform (N = fft)."""
     for lg in range(8, 23):
         M = 1 << lg
-        N = M // 2
+        N = M if args.circular else M // 2
         rows = max(1, (1 << 27) // N)
         H = min(768, rows)
         B = max(1, rows // H)
@@ -100,7 +101,8 @@ def sweep(torch, fftconv, synth, dev, args):
         torch.cuda.synchronize()
         ms = e0.elapsed_time(e1) / steps
         nbytes = 2 * B * H * N * 2 + H * M * 4
-        print(json.dumps({"fft_size": M, "N": N, "B": B, "H": H, "path": plan.path, "factors": plan.factors,
+        print(json.dumps({"fft_size": M, "N": N, "B": B, "H": H, "form": "circular" if args.circular else "causal",
+                          "path": plan.path, "factors": plan.factors,
                           "ms_per_step": ms, "sequences_per_ms": B * H / ms, "achieved_TBps": nbytes / ms / 1e9}),
               flush=True)
         del plan, kf, u, y, k
@@ -118,6 +120,7 @@ def main():
     ap.add_argument("--sweep", action="store_true",
                     help="forward pass over every power-of-two fft size 256 .. 4M at a fixed amount of data "
                          "(one JSON line per size; not the headline metric)")
+    ap.add_argument("--circular", action="store_true", help="with --sweep: N = fft_size instead of fft_size / 2")
     ap.add_argument("--backward", action="store_true",
                     help="time the backward pass (du and dk) instead (not the headline metric)")
     ap.add_argument("--gated", action="store_true",

@@ -2,7 +2,11 @@
 // (paper Algorithm 4 and Section 3.1 "Kernel Fusion": the outermost matrix
 // operation of the forward and of the inverse transform takes one trip through
 // HBM each, everything inside stays fused).  16-bit I/O, fft_size M = No * Mi with
-// Mi = 8192 (the fused inner transform) and No = M / Mi in [4, 512].
+// Mi = 8192 (the fused inner transform) and No = M / Mi in [1, 512].  Causal shapes (N <= M/2)
+// of the sizes the single-kernel paths do not take, and every shape with N > M/2 (circular
+// convolution, Section 2.1: the input fills the transform) from M = 8192 up: the kernels are
+// instantiated with and without the implicit zero half (FULLN).  No = 1 has no outer transform:
+// pass A only packs a pair of rows into a complex row, pass C unpacks it.
 //
 // Index maps: time n = no*Mi + r, frequency f = ko + No*f'.  Then
 //   W_M^{n f} = W_No^{no ko} * W_M^{r ko} * W_Mi^{r f'},
@@ -74,15 +78,16 @@ struct OuterGeo {
 // ---- pass A: zero-padded pair of real rows -> outer forward DFT (No = RA * RB) -> twiddle -> S.
 // One block = CT consecutive columns r of one (pair, channel); one thread = CV adjacent columns of
 // one butterfly, so that 16-bit input moves as 2*CV-byte and S as 4*CV-byte accesses.
-// Step 1: for every b2 < RB the length-RA transform over a (inputs a >= RA/2 are the implicit
-// zeros), times W_No^{ka b2}, into the fp32 LDS tile T[ka*RB + b2][c].  Step 2: for every ka the
+// Step 1: for every b2 < RB the length-RA transform over a (unless FULLN, inputs a >= RA/2 are the
+// implicit zeros), times W_No^{ka b2}, into the fp32 LDS tile T[ka*RB + b2][c].  Step 2: for every ka the
 // length-RB transform over b2, times W_M^{r ko} (ko = ka + RA kb, by recurrence over kb), to S.
-template <bool F16, int RA, int RB, int CV>
+template <bool F16, int RA, int RB, int CV, bool FULLN>
 __global__ void __launch_bounds__(TB, 4) k_outer_fwd(const uint16_t *__restrict__ u, uint32_t *__restrict__ S, int CT,
                                                  int B, int H, int N, int64_t M)
 {
     extern __shared__ float2 sm[];
     constexpr int No = RA * RB;
+    constexpr int RAIN = FULLN ? RA : RA / 2;      // outer rows that can hold input
     float2 *wno = sm;                              // W_No^j, j < No
     float2 *T = sm + No;                           // [No][CT]
     const int tid = threadIdx.x;
@@ -99,9 +104,9 @@ __global__ void __launch_bounds__(TB, 4) k_outer_fwd(const uint16_t *__restrict_
     __syncthreads();
     for (int e = tid; e < RB * CG; e += TB) {
         const int c = (e % CG) * CV, b2 = e / CG;
-        uint32_t in0[RA / 2], in1[RA / 2];         // CV 16-bit values of row b / row b+1
+        uint32_t in0[RAIN], in1[RAIN];             // CV 16-bit values of row b / row b+1
 #pragma unroll
-        for (int a = 0; a < RA / 2; ++a) {
+        for (int a = 0; a < RAIN; ++a) {
             const int64_t n = (int64_t)(a * RB + b2) * MI + r0 + c;
             in0[a] = in1[a] = 0;
             if (wide) {
@@ -125,7 +130,7 @@ __global__ void __launch_bounds__(TB, 4) k_outer_fwd(const uint16_t *__restrict_
 #pragma unroll
             for (int a = 0; a < RA; ++a) {
                 x[a] = make_float2(0.f, 0.f);
-                if (a < RA / 2)                                      // (row b, row b+1) = (re, im)
+                if (a < RAIN)                                        // (row b, row b+1) = (re, im)
                     x[a] = unpack2<F16>(((in0[a] >> (16 * v)) & 0xffffu) | ((in1[a] >> (16 * v)) << 16));
             }
             dft_reg<RA, false>(x);
@@ -174,12 +179,13 @@ __global__ void __launch_bounds__(TB, 4) k_outer_fwd(const uint16_t *__restrict_
 }
 
 // ---- pass C: S -> conjugate twiddle -> outer inverse DFT -> the two real rows of the pair
-template <bool F16, int RA, int RB, int CV>
+template <bool F16, int RA, int RB, int CV, bool FULLN>
 __global__ void __launch_bounds__(TB, 4) k_outer_inv(const uint32_t *__restrict__ S, uint16_t *__restrict__ y, int CT,
                                                  int B, int H, int N, int64_t M)
 {
     extern __shared__ float2 sm[];
     constexpr int No = RA * RB;
+    constexpr int RAIN = FULLN ? RA : RA / 2;      // outer rows that are kept
     float2 *wno = sm;
     float2 *T = sm + No;                           // [No][CT]
     const int tid = threadIdx.x;
@@ -234,14 +240,14 @@ __global__ void __launch_bounds__(TB, 4) k_outer_inv(const uint32_t *__restrict_
         }
     }
     __syncthreads();
-    // step 2: z[a*RB + b2] = sum_{ka} conj(W_RA^{a ka}) T[ka*RB + b2], kept for a < RA/2 (n < M/2)
+    // step 2: z[a*RB + b2] = sum_{ka} conj(W_RA^{a ka}) T[ka*RB + b2], kept for a < RAIN (n < M/2 unless FULLN)
     uint16_t *row0 = y + ((size_t)b0 * H + h) * N;
     uint16_t *row1 = y + ((size_t)(b0 + (two ? 1 : 0)) * H + h) * N;
     for (int e = tid; e < RB * CG; e += TB) {
         const int c = (e % CG) * CV, b2 = e / CG;
-        uint32_t o0[RA / 2], o1[RA / 2];
+        uint32_t o0[RAIN], o1[RAIN];
 #pragma unroll
-        for (int a = 0; a < RA / 2; ++a) o0[a] = o1[a] = 0;
+        for (int a = 0; a < RAIN; ++a) o0[a] = o1[a] = 0;
 #pragma unroll
         for (int v = 0; v < CV; ++v) {
             float2 x[RA];
@@ -249,13 +255,13 @@ __global__ void __launch_bounds__(TB, 4) k_outer_inv(const uint32_t *__restrict_
             for (int ka = 0; ka < RA; ++ka) x[ka] = T[(ka * RB + b2) * CT + c + v];
             dft_reg<RA, true>(x);
 #pragma unroll
-            for (int a = 0; a < RA / 2; ++a) {
+            for (int a = 0; a < RAIN; ++a) {
                 o0[a] |= (uint32_t)cv16<F16>(x[a].x) << (16 * v);
                 o1[a] |= (uint32_t)cv16<F16>(x[a].y) << (16 * v);
             }
         }
 #pragma unroll
-        for (int a = 0; a < RA / 2; ++a) {
+        for (int a = 0; a < RAIN; ++a) {
             const int64_t n = (int64_t)(a * RB + b2) * MI + r0 + c;
             if (wide) {
                 if (n < N) {
@@ -300,28 +306,39 @@ OuterGeo outer_geo(int64_t M)
     return g;
 }
 
-template <bool F16, int RA, int RB>
-int launch_outer(bool inverse, const OuterGeo &g, dim3 grid, const void *src, void *dst, int B, int H, int N, int64_t M,
-                 hipStream_t s)
+template <bool F16, int RA, int RB, bool FULLN>
+int launch_outer_t(bool inverse, const OuterGeo &g, dim3 grid, const void *src, void *dst, int B, int H, int N, int64_t M,
+                   hipStream_t s)
 {
     constexpr int CV = RB <= 16 ? 2 : 1;           // two columns per thread while the registers allow
     const size_t lds = sizeof(float2) * ((size_t)g.No + (size_t)g.No * g.CT);
     static bool attr_set = false;
     if (!attr_set) {
-        FC_HIP(hipFuncSetAttribute((const void *)k_outer_fwd<F16, RA, RB, CV>,
+        FC_HIP(hipFuncSetAttribute((const void *)k_outer_fwd<F16, RA, RB, CV, FULLN>,
                                    hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
-        FC_HIP(hipFuncSetAttribute((const void *)k_outer_inv<F16, RA, RB, CV>,
+        FC_HIP(hipFuncSetAttribute((const void *)k_outer_inv<F16, RA, RB, CV, FULLN>,
                                    hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
         attr_set = true;
     }
     if (!inverse)
-        hipLaunchKernelGGL((k_outer_fwd<F16, RA, RB, CV>), grid, dim3(TB), lds, s, (const uint16_t *)src,
+        hipLaunchKernelGGL((k_outer_fwd<F16, RA, RB, CV, FULLN>), grid, dim3(TB), lds, s, (const uint16_t *)src,
                            (uint32_t *)dst, g.CT, B, H, N, M);
     else
-        hipLaunchKernelGGL((k_outer_inv<F16, RA, RB, CV>), grid, dim3(TB), lds, s, (const uint32_t *)src,
+        hipLaunchKernelGGL((k_outer_inv<F16, RA, RB, CV, FULLN>), grid, dim3(TB), lds, s, (const uint32_t *)src,
                            (uint16_t *)dst, g.CT, B, H, N, M);
     FC_HIP(hipGetLastError());
     return FFTCONV_OK;
+}
+
+// the half-input instantiation needs an outer transform (No >= 2) and N <= M/2
+template <bool F16, int RA, int RB>
+int launch_outer(bool inverse, const OuterGeo &g, dim3 grid, const void *src, void *dst, int B, int H, int N, int64_t M,
+                 hipStream_t s)
+{
+    if constexpr (RA >= 2) {
+        if ((int64_t)N <= M / 2) return launch_outer_t<F16, RA, RB, false>(inverse, g, grid, src, dst, B, H, N, M, s);
+    }
+    return launch_outer_t<F16, RA, RB, true>(inverse, g, grid, src, dst, B, H, N, M, s);
 }
 
 template <bool F16>
@@ -329,6 +346,8 @@ int dispatch_outer(bool inverse, const OuterGeo &g, dim3 grid, const void *src, 
                    int64_t M, hipStream_t s)
 {
     switch (g.No) {
+    case 1: return launch_outer<F16, 1, 1>(inverse, g, grid, src, dst, B, H, N, M, s);
+    case 2: return launch_outer<F16, 2, 1>(inverse, g, grid, src, dst, B, H, N, M, s);
     case 4: return launch_outer<F16, 4, 1>(inverse, g, grid, src, dst, B, H, N, M, s);
     case 8: return launch_outer<F16, 8, 1>(inverse, g, grid, src, dst, B, H, N, M, s);
     case 16: return launch_outer<F16, 16, 1>(inverse, g, grid, src, dst, B, H, N, M, s);
@@ -348,8 +367,8 @@ int dispatch_outer(bool inverse, const OuterGeo &g, dim3 grid, const void *src, 
 bool multipass_supported(int64_t N, int64_t M, int dtype)
 {
     if (dtype != FFTCONV_F16 && dtype != FFTCONV_BF16) return false;
-    if (M < 4 * MI || M > 512 * (int64_t)MI) return false;
-    return N <= M / 2;
+    if (M < MI || M > 512 * (int64_t)MI) return false;
+    return N >= 1 && N <= M;
 }
 
 int multipass_init(fftconv_plan *p) { return fused3_init_inner(p); }

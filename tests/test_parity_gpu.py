@@ -52,8 +52,7 @@ def test_small_transform_kernel_group_shapes(dtype, B, H, N, M):
 @pytest.mark.parametrize("dtype,B,H,N,M", [
     ("f32", 2, 2, 4096, 8192),       # fp32 I/O beyond the short-transform kernel
     ("f32", 1, 2, 5000, 16384),      # ragged N
-    ("bf16", 2, 2, 8192, 8192),      # circular (N > fft/2) with 16-bit I/O
-    ("f16", 3, 1, 4100, 8192),       # N not a multiple of 8
+    ("f32", 2, 1, 8192, 8192),       # circular
 ])
 def test_generic_staged_path(dtype, B, H, N, M):
     w = synth.scaled(W["cfg2"], B=B, H=H, N=N, fft_size=M, dtype=dtype, alpha=(1e-2, 1e-1))
@@ -182,6 +181,27 @@ def test_cfg5_variants_reduced_batch():
     (1, 1, 20000, 65536),      # ragged N, B = 1
 ])
 def test_multipass_all_outputs(dtype, B, H, N, M):
+    w = synth.scaled(W["cfg3"], B=B, H=H, N=N, fft_size=M, dtype=dtype)
+    err, plan = check_all_sequences(w)
+    print("multipass %s B=%d H=%d N=%d M=%d path=%s factors=%s err=%.3e" % (dtype, B, H, N, M, plan.path, plan.factors, err),
+          flush=True)
+    assert plan.path == "multipass"
+    assert err <= TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype,B,H,N,M", [
+    ("bf16", 2, 2, 8192, 8192),      # circular, no outer transform (a pair of rows is packed, convolved, unpacked)
+    ("f16", 3, 1, 4100, 8192),       # causal, N not a multiple of 8: the same route
+    ("bf16", 3, 2, 16384, 16384),    # circular, outer length 2
+    ("f16", 2, 1, 9000, 16384),      # N > fft/2, ragged
+    ("bf16", 1, 2, 8190, 16384),     # causal, N not a multiple of 8, outer length 2 with the implicit zero half
+    ("bf16", 2, 1, 32768, 32768),    # circular, outer length 4
+    ("f16", 1, 1, 65536, 65536),     # circular, outer length 8
+    ("bf16", 1, 1, 50000, 65536),    # N > fft/2, wrap-around taps
+])
+def test_multipass_circular_and_ragged(dtype, B, H, N, M):
+    """16-bit shapes with the input filling more than half of the transform (Section 2.1: circular convolution)
+    and ragged causal shapes from fft 8192 up: outer passes without the implicit zero half."""
     w = synth.scaled(W["cfg3"], B=B, H=H, N=N, fft_size=M, dtype=dtype)
     err, plan = check_all_sequences(w)
     print("multipass %s B=%d H=%d N=%d M=%d path=%s factors=%s err=%.3e" % (dtype, B, H, N, M, plan.path, plan.factors, err),
