@@ -101,7 +101,11 @@ def sweep(torch, fftconv, synth, dev, args):
         torch.cuda.synchronize()
         ms = e0.elapsed_time(e1) / steps
         nbytes = 2 * B * H * N * 2 + H * M * 4
+        # Section 3.2, Eq. 2 with this chip's constants: the order it would pick and its cost for this batch
+        mach = fftconv.machine_preset(fftconv.MACHINE_MI355X)
+        mp, mf, mc = fftconv.plan_order(mach, M)
         print(json.dumps({"fft_size": M, "N": N, "B": B, "H": H, "form": "circular" if args.circular else "causal",
+                          "model_order": mp, "model_factors": mf, "model_ms": mc * B * H * 1e3,
                           "path": plan.path, "factors": plan.factors,
                           "ms_per_step": ms, "sequences_per_ms": B * H / ms, "achieved_TBps": nbytes / ms / 1e9}),
               flush=True)

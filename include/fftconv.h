@@ -163,6 +163,33 @@ int fftconv_backward_filter(const fftconv_plan *plan, const void *u, const void 
  * or a negative value on bad arguments.  Host-only helper. */
 double fftconv_sparsity_fraction(const int64_t *dims, const int64_t *cuts, int ndim);
 
+/* Cost model of an order-p decomposition (Section 3.2, Eq. 2).  Host-only helpers.
+ *     C = B H sum_{i=1..p} ( 16 N N_i / gamma(N_i) + 4 N / omega(i) )          [seconds]
+ * gamma(N_i) = tau_M if N_i >= mu else tau_G; omega(i) = sigma_S when the intermediate of step i stays
+ * on chip, sigma_H otherwise: the innermost three steps form one fused kernel whose first step reads
+ * from HBM and whose later steps stay on chip iff the subsequence it works on (N over the outer
+ * factors) is at most sram_seq; every step outside it goes through HBM.
+ * fftconv_machine_preset: FFTCONV_MACHINE_MI355X = constants measured on this chip with this library's
+ * kernels, FFTCONV_MACHINE_A100_PAPER = the paper's table for A100-40GB (Appendix C).
+ * fftconv_cost_model: C for factors[0..p) (outermost first, product N); negative on bad arguments.
+ * fftconv_balanced_factors: power-of-two factors of N as equal as possible, larger first.
+ * fftconv_plan_order: the order p in {2, 3, 4} with balanced factors that minimises C for B = H = 1;
+ * writes p, its factors (room for 4) and the cost; any output pointer may be NULL. */
+typedef struct fftconv_machine {
+    double sigma_H;     /* achievable HBM bandwidth, bytes / s */
+    double sigma_S;     /* achievable on-chip memory bandwidth, bytes / s */
+    double tau_M;       /* achievable matrix-unit rate, FLOP / s */
+    double tau_G;       /* achievable general arithmetic rate, FLOP / s */
+    int mu;             /* size of the matrix-multiply unit */
+    int64_t sram_seq;   /* longest sequence whose intermediates stay on chip */
+} fftconv_machine;
+#define FFTCONV_MACHINE_MI355X 0
+#define FFTCONV_MACHINE_A100_PAPER 1
+void fftconv_machine_preset(int which, fftconv_machine *m);
+double fftconv_cost_model(const fftconv_machine *m, int64_t B, int64_t H, int64_t N, int p, const int64_t *factors);
+int fftconv_balanced_factors(int64_t N, int p, int64_t *factors);
+int fftconv_plan_order(const fftconv_machine *m, int64_t N, int *p, int64_t *factors, double *cost);
+
 /* Name of the kernel family the plan dispatches to ("staged", "fused3", ...);
  * for logs and benchmarks.  Never NULL for a valid plan. */
 const char *fftconv_plan_path(const fftconv_plan *plan);

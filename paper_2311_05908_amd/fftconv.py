@@ -23,10 +23,20 @@ EXPORTS = [
     "fftconv_forward_freq_sparse", "fftconv_sparsity_fraction", "fftconv_plan_path", "fftconv_plan_factors",
     "fftconv_strerror", "fftconv_last_error", "fftconv_workspace_bytes_gated", "fftconv_forward_gated",
     "fftconv_filter_fft_adjoint", "fftconv_backward_input", "fftconv_workspace_bytes_backward_filter",
-    "fftconv_backward_filter",
+    "fftconv_backward_filter", "fftconv_machine_preset", "fftconv_cost_model", "fftconv_balanced_factors",
+    "fftconv_plan_order",
 ]
 
 _lib = None
+
+
+class Machine(ctypes.Structure):
+    """fftconv_machine: the constants of the cost model (Section 3.2, Eq. 2)."""
+    _fields_ = [("sigma_H", ctypes.c_double), ("sigma_S", ctypes.c_double), ("tau_M", ctypes.c_double),
+                ("tau_G", ctypes.c_double), ("mu", ctypes.c_int), ("sram_seq", ctypes.c_int64)]
+
+
+MACHINE_MI355X, MACHINE_A100_PAPER = 0, 1
 
 
 class FFTConvError(RuntimeError):
@@ -81,6 +91,15 @@ def load():
     lib.fftconv_backward_filter.restype = ci
     lib.fftconv_sparsity_fraction.argtypes = [ctypes.POINTER(i64), ctypes.POINTER(i64), ci]
     lib.fftconv_sparsity_fraction.restype = ctypes.c_double
+    mp = ctypes.POINTER(Machine)
+    lib.fftconv_machine_preset.argtypes = [ci, mp]
+    lib.fftconv_machine_preset.restype = None
+    lib.fftconv_cost_model.argtypes = [mp, i64, i64, i64, ci, ctypes.POINTER(i64)]
+    lib.fftconv_cost_model.restype = ctypes.c_double
+    lib.fftconv_balanced_factors.argtypes = [i64, ci, ctypes.POINTER(i64)]
+    lib.fftconv_balanced_factors.restype = ci
+    lib.fftconv_plan_order.argtypes = [mp, i64, ctypes.POINTER(ci), ctypes.POINTER(i64), ctypes.POINTER(ctypes.c_double)]
+    lib.fftconv_plan_order.restype = ci
     lib.fftconv_plan_path.argtypes = [vp]
     lib.fftconv_plan_path.restype = ctypes.c_char_p
     lib.fftconv_plan_factors.argtypes = [vp, ctypes.POINTER(i64), ci]
@@ -114,6 +133,42 @@ def sparsity_fraction(dims, cuts) -> float:
     if v < 0:
         raise ValueError("bad sparsity pattern")
     return v
+
+
+def machine_preset(which: int = MACHINE_MI355X) -> Machine:
+    """fftconv_machine_preset."""
+    m = Machine()
+    load().fftconv_machine_preset(which, ctypes.byref(m))
+    return m
+
+
+def cost_model(machine: Machine, B: int, H: int, N: int, factors) -> float:
+    """fftconv_cost_model: Eq. 2 in seconds for the given factors (outermost first)."""
+    arr = (ctypes.c_int64 * len(factors))(*factors)
+    v = load().fftconv_cost_model(ctypes.byref(machine), B, H, N, len(factors), arr)
+    if v < 0:
+        raise ValueError("bad decomposition")
+    return v
+
+
+def balanced_factors(N: int, p: int):
+    """fftconv_balanced_factors."""
+    arr = (ctypes.c_int64 * 8)()
+    rc = load().fftconv_balanced_factors(N, p, arr)
+    if rc:
+        raise ValueError("N must be a power of two and 1 <= p <= 8")
+    return [int(arr[i]) for i in range(p)]
+
+
+def plan_order(machine: Machine, N: int):
+    """fftconv_plan_order: (p, factors, cost per sequence in seconds) of the cheapest order in {2, 3, 4}."""
+    p = ctypes.c_int()
+    arr = (ctypes.c_int64 * 4)()
+    c = ctypes.c_double()
+    rc = load().fftconv_plan_order(ctypes.byref(machine), N, ctypes.byref(p), arr, ctypes.byref(c))
+    if rc:
+        raise ValueError("N must be a power of two >= 4")
+    return p.value, [int(arr[i]) for i in range(p.value)], c.value
 
 
 class Plan:
