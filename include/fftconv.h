@@ -118,6 +118,29 @@ int fftconv_forward_freq_sparse(const fftconv_plan *plan, const void *u, const v
                                 const uint8_t *block_keep, int64_t n_blocks, void *y,
                                 int64_t B, int64_t H, int64_t N, void *workspace, void *stream);
 
+/* Digit cut-off patterns (Appendix A.4: sparsity along each dimension of k_f viewed as an array over
+ * the digits of the decomposition).  The digits are those of the plan's factorisation
+ * (fftconv_plan_factors, outermost factor first): f = sum_i d_i w_i with w_0 = 1,
+ * w_i = w_{i-1} * factors[i-1], so the outermost factor is the least significant digit and the innermost
+ * one (the paper's first dimension, the last matrix of the forward transform) the most significant.
+ *   digit_keep: host, ndigits = number of factors; digit i keeps digit_keep[i] in [1, factors[i]] of its
+ *   values.  The paper cuts one-sided in the half spectrum of its real transform; two real rows share a
+ *   complex transform here, which needs a set of bins that is mirror symmetric (f -> fft_size - f), so
+ *   the low-pass set of that size is kept: for digit 0 the values nearest zero on the circle,
+ *   d <= keep/2 or d >= factors[0] - (keep-1)/2; for the other digits the values nearest the two ends
+ *   of the range, d < ceil(keep/2) or d >= factors[i] - keep/2 (the mirror image of a bin has digit
+ *   factors[i] - 1 - d there unless all lower digits are zero).
+ * A bin is kept when all of its digits are; the result is defined as for fftconv_filter_fft_sparse
+ * (mirror bins carry weight 1/2 where the kept set is one bin off mirror symmetry).
+ * fftconv_forward_freq_sparse_digits: same result as fftconv_forward on that k_f; digits whose kept set is
+ * small let the plan skip work: planes of the per-plane loops (the paper's loop trip counts) and matrix
+ * tiles that only meet zeroed bins. */
+int fftconv_filter_fft_sparse_digits(const fftconv_plan *plan, const float *k, int64_t Nk,
+                                     const int64_t *digit_keep, int ndigits, void *k_f, void *stream);
+int fftconv_forward_freq_sparse_digits(const fftconv_plan *plan, const void *u, const void *k_f,
+                                       const int64_t *digit_keep, int ndigits, void *y,
+                                       int64_t B, int64_t H, int64_t N, void *workspace, void *stream);
+
 /* Bytes of workspace fftconv_forward_gated needs for batch size B: fftconv_workspace_bytes plus,
  * for plans whose kernel does not fuse the gates, room for the gated input (B*H*N elements). */
 size_t fftconv_workspace_bytes_gated(const fftconv_plan *plan, int64_t B);

@@ -5,6 +5,8 @@
 #include <cstring>
 #include <new>
 
+#include <vector>
+
 #include "fftconv_internal.h"
 
 namespace fftconv {
@@ -81,7 +83,7 @@ int fftconv_plan_create(fftconv_plan **out, int64_t N, int64_t fft_size, int64_t
     int rc = FFTCONV_OK;
     if (hipGetDevice(&p->device) != hipSuccess) rc = FFTCONV_EHIP;
     if (rc == FFTCONV_OK) rc = staged_init(p);      // tables of the filter transform; fallback forward
-    if (rc == FFTCONV_OK && hipMalloc((void **)&p->keep_dev, MAX_BLOCKS) != hipSuccess) {
+    if (rc == FFTCONV_OK && hipMalloc((void **)&p->keep_dev, (size_t)(fft_size > MAX_BLOCKS ? fft_size : MAX_BLOCKS)) != hipSuccess) {
         set_error("fftconv_plan_create: hipMalloc of the block mask failed");
         rc = FFTCONV_ENOMEM;
     }
@@ -139,8 +141,11 @@ size_t fftconv_workspace_bytes(const fftconv_plan *p, int64_t B)
     }
 }
 
+// block_keep with n_blocks == fft_size is a per-bin mask (internal callers only; the device copy of the
+// mask has room for it)
 static int filter_fft_impl(const fftconv_plan *p, const float *k, int64_t Nk, const uint8_t *block_keep,
-                           int64_t n_blocks, void *k_f, void *stream, const char *who, bool adjoint = false)
+                           int64_t n_blocks, void *k_f, void *stream, const char *who, bool adjoint = false,
+                           bool per_bin = false)
 {
     int rc = check_plan(p, who);
     if (rc) return rc;
@@ -155,7 +160,7 @@ static int filter_fft_impl(const fftconv_plan *p, const float *k, int64_t Nk, co
     hipStream_t s = (hipStream_t)stream;
     const uint8_t *keep_dev = nullptr;
     if (block_keep) {
-        if (!is_pow2(n_blocks) || n_blocks > MAX_BLOCKS || n_blocks > p->M) {
+        if (!(per_bin && n_blocks == p->M) && (!is_pow2(n_blocks) || n_blocks > MAX_BLOCKS || n_blocks > p->M)) {
             set_error("%s: n_blocks=%lld must be a power of two <= min(%lld, fft_size)", who, (long long)n_blocks,
                       (long long)MAX_BLOCKS);
             return FFTCONV_EINVAL;
@@ -204,6 +209,64 @@ int fftconv_filter_fft_sparse(const fftconv_plan *p, const float *k, int64_t Nk,
         return FFTCONV_EINVAL;
     }
     return filter_fft_impl(p, k, Nk, block_keep, n_blocks, k_f, stream, "fftconv_filter_fft_sparse");
+}
+
+// ---- digit cut-off patterns (Appendix A.4).  The spectrum is viewed as an array over the digits of
+// f in the plan's factorisation, f = sum_i d_i w_i with w_0 = 1, w_i = w_{i-1} * factors[i-1] (the
+// outermost factor is the least significant digit); digit i keeps digit_keep[i] of its D_i values, chosen so
+// that the kept set of bins is as close to mirror symmetric (f -> M - f) as a product set can be: the
+// mirror image of a bin has digits (D_0 - d_0) mod D_0 and, unless all lower digits are zero, D_i - 1 - d_i.
+//   digit 0:     the values nearest zero on the circle,        d <= keep / 2      or d >= D_0 - (keep - 1) / 2
+//   digits i>0:  the values nearest the two ends of the range, d < ceil(keep / 2) or d >= D_i - keep / 2
+struct DigitPattern {
+    int nd = 0;
+    int64_t D[8] = {0}, lo[8] = {0}, hi[8] = {0};       // kept: d < lo or d >= hi
+};
+
+static int digit_pattern(const fftconv_plan *p, const int64_t *digit_keep, int ndigits, const char *who,
+                         DigitPattern *out)
+{
+    int64_t fac[8];
+    const int nf = fftconv_plan_factors(p, fac, 8);
+    if (!digit_keep || ndigits != nf || nf > 8) {
+        set_error("%s: digit_keep must hold one entry per factor of the plan (%d)", who, nf);
+        return FFTCONV_EINVAL;
+    }
+    out->nd = nf;
+    for (int i = 0; i < nf; ++i) {
+        if (digit_keep[i] < 1 || digit_keep[i] > fac[i]) {
+            set_error("%s: digit_keep[%d]=%lld must be in [1, %lld]", who, i, (long long)digit_keep[i], (long long)fac[i]);
+            return FFTCONV_EINVAL;
+        }
+        out->D[i] = fac[i];
+        out->lo[i] = i == 0 ? digit_keep[i] / 2 + 1 : (digit_keep[i] + 1) / 2;
+        out->hi[i] = i == 0 ? fac[i] - (digit_keep[i] - 1) / 2 : fac[i] - digit_keep[i] / 2;
+    }
+    return FFTCONV_OK;
+}
+
+int fftconv_filter_fft_sparse_digits(const fftconv_plan *p, const float *k, int64_t Nk, const int64_t *digit_keep,
+                                     int ndigits, void *k_f, void *stream)
+{
+    const char *who = "fftconv_filter_fft_sparse_digits";
+    int rc = check_plan(p, who);
+    if (rc) return rc;
+    DigitPattern dp;
+    rc = digit_pattern(p, digit_keep, ndigits, who, &dp);
+    if (rc) return rc;
+    std::vector<uint8_t> keep((size_t)p->M);
+    for (int64_t f = 0; f < p->M; ++f) {
+        int64_t r = f;
+        bool kept = true;
+        for (int i = 0; i < dp.nd && kept; ++i) {
+            const int64_t d = r % dp.D[i];
+            r /= dp.D[i];
+            kept = d < dp.lo[i] || d >= dp.hi[i];
+        }
+        keep[(size_t)f] = kept ? 1 : 0;
+    }
+    // the copy of a pageable host buffer has completed when hipMemcpyAsync returns
+    return filter_fft_impl(p, k, Nk, keep.data(), p->M, k_f, stream, who, false, true);
 }
 
 static int forward_check(const fftconv_plan *p, const void *u, const void *k_f, void *y, int64_t B, int64_t H,
@@ -340,6 +403,20 @@ int fftconv_forward_freq_sparse(const fftconv_plan *p, const void *u, const void
     if (p->path == PATH_FUSED3)
         return fused3_forward_sparse(p, u, k_f, y, B, fused3_live_k3(p, block_keep, n_blocks),
                                      (hipStream_t)stream);
+    return fftconv_forward(p, u, k_f, y, B, H, N, workspace, stream);
+}
+
+int fftconv_forward_freq_sparse_digits(const fftconv_plan *p, const void *u, const void *k_f, const int64_t *digit_keep,
+                                       int ndigits, void *y, int64_t B, int64_t H, int64_t N, void *workspace,
+                                       void *stream)
+{
+    const char *who = "fftconv_forward_freq_sparse_digits";
+    int rc = forward_check(p, u, k_f, y, B, H, N, workspace, who);
+    if (rc) return rc;
+    DigitPattern dp;
+    rc = digit_pattern(p, digit_keep, ndigits, who, &dp);
+    if (rc) return rc;
+    if (B == 0) return FFTCONV_OK;
     return fftconv_forward(p, u, k_f, y, B, H, N, workspace, stream);
 }
 

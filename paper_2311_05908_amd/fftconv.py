@@ -24,7 +24,7 @@ EXPORTS = [
     "fftconv_strerror", "fftconv_last_error", "fftconv_workspace_bytes_gated", "fftconv_forward_gated",
     "fftconv_filter_fft_adjoint", "fftconv_backward_input", "fftconv_workspace_bytes_backward_filter",
     "fftconv_backward_filter", "fftconv_machine_preset", "fftconv_cost_model", "fftconv_balanced_factors",
-    "fftconv_plan_order",
+    "fftconv_plan_order", "fftconv_filter_fft_sparse_digits", "fftconv_forward_freq_sparse_digits",
 ]
 
 _lib = None
@@ -91,6 +91,10 @@ def load():
     lib.fftconv_backward_filter.restype = ci
     lib.fftconv_sparsity_fraction.argtypes = [ctypes.POINTER(i64), ctypes.POINTER(i64), ci]
     lib.fftconv_sparsity_fraction.restype = ctypes.c_double
+    lib.fftconv_filter_fft_sparse_digits.argtypes = [vp, vp, i64, ctypes.POINTER(i64), ci, vp, vp]
+    lib.fftconv_filter_fft_sparse_digits.restype = ci
+    lib.fftconv_forward_freq_sparse_digits.argtypes = [vp, vp, vp, ctypes.POINTER(i64), ci, vp, i64, i64, i64, vp, vp]
+    lib.fftconv_forward_freq_sparse_digits.restype = ci
     mp = ctypes.POINTER(Machine)
     lib.fftconv_machine_preset.argtypes = [ci, mp]
     lib.fftconv_machine_preset.restype = None
@@ -306,6 +310,27 @@ class Plan:
         _check(self._lib.fftconv_forward_partial(self._h, u.data_ptr(), kf.data_ptr(), y.data_ptr(), u.shape[0],
                                                  self.H, self.N, int(Nk), None if ws is None else ws.data_ptr(),
                                                  _stream_ptr()))
+        return y
+
+    def filter_fft_sparse_digits(self, k, digit_keep, Nk=None):
+        """fftconv_filter_fft_sparse_digits: k (H, Nk) fp32 on the device -> opaque k_f."""
+        self._check_k(k)
+        Nk = k.shape[1] if Nk is None else Nk
+        kf = torch.empty(self.kf_bytes(), dtype=torch.uint8, device=k.device)
+        arr = (ctypes.c_int64 * len(digit_keep))(*[int(x) for x in digit_keep])
+        _check(self._lib.fftconv_filter_fft_sparse_digits(self._h, k.data_ptr(), Nk, arr, len(digit_keep),
+                                                          kf.data_ptr(), _stream_ptr()))
+        return kf
+
+    def forward_freq_sparse_digits(self, u, kf, digit_keep, out=None):
+        """fftconv_forward_freq_sparse_digits."""
+        self._check_u(u)
+        y = torch.empty_like(u) if out is None else out
+        ws = self._workspace(u.shape[0], u.device)
+        arr = (ctypes.c_int64 * len(digit_keep))(*[int(x) for x in digit_keep])
+        _check(self._lib.fftconv_forward_freq_sparse_digits(self._h, u.data_ptr(), kf.data_ptr(), arr, len(digit_keep),
+                                                            y.data_ptr(), u.shape[0], self.H, self.N,
+                                                            None if ws is None else ws.data_ptr(), _stream_ptr()))
         return y
 
     def forward_freq_sparse(self, u, kf, block_keep, out=None):

@@ -141,3 +141,24 @@ def sample_sequences(w: Workload, n_random: int, seed: int = 7) -> list:
     while len(pts) < min(n_random + 4, w.B * w.H):
         pts.add((int(g.integers(0, w.B)), int(g.integers(0, w.H))))
     return sorted(pts)
+
+
+def digit_keep_mask(factors, digit_keep) -> np.ndarray:
+    """Per-bin 0/1 mask of a digit cut-off pattern: bin f = sum_i d_i w_i (w_0 = 1, w_i = w_{i-1} * factors[i-1])
+    is kept when every digit is in its kept set: for digit 0 the digit_keep[0] values nearest zero on the circle
+    (ties to the smaller value), for the others the digit_keep[i] values nearest the two ends of the range (the odd
+    one at the low end).  Input structure only: no arithmetic of the method."""
+    M = int(np.prod(factors))
+    f = np.arange(M, dtype=np.int64)
+    keep = np.ones(M, dtype=bool)
+    for i, (D, kp) in enumerate(zip(factors, digit_keep)):
+        d = f % D
+        f = f // D
+        if i == 0:
+            order = sorted(range(D), key=lambda v: (min(v, D - v), v))
+        else:
+            order = sorted(range(D), key=lambda v: (min(v, D - 1 - v), v))
+        kept = np.zeros(D, dtype=bool)
+        kept[order[:kp]] = True
+        keep &= kept[d]
+    return keep.astype(np.uint8)
