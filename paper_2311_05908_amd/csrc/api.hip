@@ -417,6 +417,29 @@ int fftconv_forward_freq_sparse_digits(const fftconv_plan *p, const void *u, con
     rc = digit_pattern(p, digit_keep, ndigits, who, &dp);
     if (rc) return rc;
     if (B == 0) return FFTCONV_OK;
+    // values of a digit that can meet a non-zero bin: the kept ones and their images under both forms of the
+    // mirror map (d -> (D - d) mod D and d -> D - 1 - d), as a bit mask (digits of at most 32 values)
+    auto live_mask = [&](int i) -> uint32_t {
+        if (dp.D[i] > 32) return 0xffffffffu;
+        uint32_t m = 0;
+        for (int64_t d = 0; d < dp.D[i]; ++d)
+            if (d < dp.lo[i] || d >= dp.hi[i]) m |= (1u << d) | (1u << ((dp.D[i] - d) % dp.D[i])) | (1u << (dp.D[i] - 1 - d));
+        if (dp.D[i] < 32) m |= ~((1u << dp.D[i]) - 1u);
+        return m;
+    };
+    if (p->path == PATH_FUSED3)          // digits (k1, k2, k3)
+        return fused3_forward_sparse(p, u, k_f, y, B, live_mask(2), (hipStream_t)stream, live_mask(0));
+    if (p->path == PATH_MULTIPASS) {
+        // digit 0 is the outer frequency ko; kept: ko < lo or ko >= hi, whose mirror images (No - ko) mod No
+        // are ko <= lo - 1 and ko >= No - (lo - 1)
+        if (!workspace && fftconv_workspace_bytes(p, B) > 0) {
+            set_error("%s: workspace is NULL", who);
+            return FFTCONV_EINVAL;
+        }
+        const int64_t a = dp.lo[0] - 1;                  // largest kept distance from zero
+        const int64_t lo = a + 1, hi = dp.D[0] - a;
+        return multipass_forward(p, u, k_f, y, B, workspace, (hipStream_t)stream, (int)lo, (int)hi);
+    }
     return fftconv_forward(p, u, k_f, y, B, H, N, workspace, stream);
 }
 

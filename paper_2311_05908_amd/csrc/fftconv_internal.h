@@ -128,7 +128,7 @@ int fused3_pack_kf(const fftconv_plan *p, const double2 *spec, int64_t h0, int64
 int fused3_forward(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, hipStream_t s);
 // frequency-sparse forward: live = number of accumulator registers (1..4) that can hold non-zero k_f
 int fused3_forward_sparse(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, uint32_t live_k3,
-                          hipStream_t s);
+                          hipStream_t s, uint32_t live_k1 = 0xffffffffu);
 uint32_t fused3_live_k3(const fftconv_plan *p, const uint8_t *block_keep, int64_t n_blocks);
 // partial convolution by overlapping short segments; returns FFTCONV_EUNSUPPORTED if this plan / Nk cannot
 bool fused3_short_ok(const fftconv_plan *p, int64_t Nk);
@@ -138,7 +138,7 @@ int fused3_forward_short(const fftconv_plan *p, const void *u, const void *kf, v
 // the 8192-point complex-row kernel used as the inner step of the multi-pass path
 int fused3_init_inner(fftconv_plan *p);
 int fused3_inner_rows(const fftconv_plan *p, void *rows, const void *kf, int64_t rows_per_kf, int64_t kf_rows,
-                      hipStream_t s);
+                      hipStream_t s, int ko_n = 0, int ko_lo = 0, int ko_hi = 0);
 // Order of the innermost frequency digit k3 (N3 values) inside the fused kernels.  Stage 3 leaves
 // k3 in an accumulator slot (tile t, lane group q, register r) = index 16 t + 4 q + r.  The digits are
 // ranked by closeness to DC (0, N3-1, 1, N3-2, ...: k3 is the most significant digit of the
@@ -206,6 +206,6 @@ size_t multipass_workspace_bytes(const fftconv_plan *p, int64_t B);
 int multipass_pack_kf(const fftconv_plan *p, const double2 *spec, int64_t h0, int64_t nh,
                       const uint8_t *keep_dev, int64_t n_blocks, void *kf, hipStream_t s);
 int multipass_forward(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, void *workspace,
-                      hipStream_t s);
+                      hipStream_t s, int ko_lo = 0, int ko_hi = 0);
 
 }  // namespace fftconv

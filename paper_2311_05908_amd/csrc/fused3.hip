@@ -69,10 +69,14 @@ using namespace f3;
 //               This is the inner step of the multi-pass scheme (Algorithm 4).
 // LIVE: accumulator registers r < LIVE of stage 3 may meet non-zero k_f (frequency-sparse filters
 //       ordered as in k3_at_index()); for r >= LIVE the product is zero and is not formed.
+// Row skipping (CPLX, frequency-sparse filters, Appendix A.4: the trip count of the outer loop): with
+// KoN > 0 the rows come in groups of KoN (the outer frequency digit ko) of which only ko < ko_lo and
+// ko >= ko_hi can meet a non-zero bin; H then counts the live rows only and rows_of() maps a live row to its
+// place among all rows.  The other rows are neither read nor written.
 template <int N2, int N3, typename TT, bool REGC, bool CPLX, int LIVE = 4>
 __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *u, uint16_t *y,
                                               const float2 *__restrict__ kf, Consts cs, int B, int H, int N,
-                                              int probe)
+                                              int probe, int KoN, int ko_lo, int ko_hi)
 {
     using G = Geo<N2, N3>;
     constexpr int R2 = G::R2, R3 = G::R3, C3 = G::C3, C1 = G::C1;
@@ -115,6 +119,13 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *u, uint16_t *y,
     auto item = [&](int k) {
         const int v = first + k * stride;
         return REGC ? v : ((v / npairs) * nx + x) * npairs + v % npairs;
+    };
+    const int ko_live = KoN > 0 ? ko_lo + KoN - ko_hi : 1;
+    const int Hrows = KoN > 0 ? (H / ko_live) * KoN : H;        // rows per pair in memory
+    auto row_of = [&](int h) {                                   // live row -> row among all
+        if (KoN <= 0) return h;
+        const int g = h / ko_live, j = h - g * ko_live;
+        return g * KoN + (j < ko_lo ? j : j - ko_lo + ko_hi);
     };
 
     // ---------------- constants (per-lane operand tables) ----------------
@@ -207,7 +218,7 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *u, uint16_t *y,
         const int t = item(k < cnt ? k : cnt - 1);
         const int h = t / npairs, pair = t - h * npairs;
         if constexpr (CPLX) {
-            const uint16_t *row = u + ((size_t)pair * H + h) * (size_t)(2 * G::M);
+            const uint16_t *row = u + ((size_t)pair * Hrows + row_of(h)) * (size_t)(2 * G::M);
 #pragma unroll
             for (int j = 0; j < NCH; ++j) {
                 uint4 v = make_uint4(0, 0, 0, 0);
@@ -257,7 +268,7 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *u, uint16_t *y,
         const int t = item(k);
         const int h = t / npairs, pair = t - h * npairs;
         if constexpr (CPLX) {
-            uint16_t *row = y + ((size_t)pair * H + h) * (size_t)(2 * G::M);
+            uint16_t *row = y + ((size_t)pair * Hrows + row_of(h)) * (size_t)(2 * G::M);
 #pragma unroll
             for (int j = 0; j < NCH; ++j) {
                 const int n = (tid + NT * j) * 4;
@@ -294,7 +305,7 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *u, uint16_t *y,
     for (int k = 0; k < cnt; ++k) {
         opaque();
         {
-            const int h = item(k) / npairs;
+            const int h = row_of(item(k) / npairs);
             if (h != h_cur) {                             // new channel: fetch its k_f (used in phase B)
                 h_cur = h;
                 if constexpr (REGC) {
@@ -724,7 +735,7 @@ int probe_mask()
 // complex-row kernel B rows per k_f row, H k_f rows.
 template <int N2, int N3, typename TT, bool REGC, bool CPLX, int LIVE = 4>
 int launch(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, int64_t H, int64_t N,
-           hipStream_t s)
+           hipStream_t s, int KoN = 0, int ko_lo = 0, int ko_hi = 0)
 {
     using G = Geo<N2, N3>;
     auto kern = k_fused3<N2, N3, TT, REGC, CPLX, LIVE>;
@@ -745,7 +756,7 @@ int launch(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_
     int grid = (int)(T < p->f3.num_cu ? T : p->f3.num_cu);
     if (!REGC && grid >= 8) grid -= grid % 8;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NT), lds, s, (const uint16_t *)u, (uint16_t *)y,
-                       (const float2 *)kf, consts_of<N2, N3>(p), (int)B, (int)H, (int)N, probe_mask());
+                       (const float2 *)kf, consts_of<N2, N3>(p), (int)B, (int)H, (int)N, probe_mask(), KoN, ko_lo, ko_hi);
     FC_HIP(hipGetLastError());
     return FFTCONV_OK;
 }
@@ -789,11 +800,12 @@ int fused3_init(fftconv_plan *p)
     }
 }
 
-// Frequency-sparse filter (Appendix A.4): live_k3 comes from fused3_live_k3().  The kernels for
-// 16384 and 32768 skip the half of the innermost stage that only meets zeroed bins when the mask
-// allows; the 8192 kernel runs dense (same result: the zeroed bins are zero in k_f).
+// Frequency-sparse filter (Appendix A.4): live_k3 / live_k1 have a bit set for every value of the digit that
+// can meet a non-zero bin of k_f.  The kernels for 16384 and 32768 skip the half of the innermost stage
+// that only meets zeroed bins when live_k3 allows; the 8192 kernel skips the k1 planes that are not live
+// (the trip count of its per-plane loop).
 int fused3_forward_sparse(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, uint32_t live_k3,
-                          hipStream_t s)
+                          hipStream_t s, uint32_t live_k1)
 {
     if (p->M == 16384 || p->M == 32768) {
         if (((uintptr_t)u | (uintptr_t)y) & 15) {
@@ -801,6 +813,13 @@ int fused3_forward_sparse(const fftconv_plan *p, const void *u, const void *kf, 
             return FFTCONV_EINVAL;
         }
         return fused3_big_forward(p, u, kf, y, B, live_k3, s);
+    }
+    if (p->M == 8192 && live_k1 != 0xffffffffu) {
+        if (((uintptr_t)u | (uintptr_t)y) & 15) {
+            set_error("fftconv_forward_freq_sparse: u and y must be 16-byte aligned for this plan");
+            return FFTCONV_EINVAL;
+        }
+        return fused3_ws_launch(p, p->f3.consts, u, kf, y, B, 1, 0, s, nullptr, nullptr, live_k1);
     }
     return fused3_forward(p, u, kf, y, B, s);
 }
@@ -847,12 +866,21 @@ int fused3_init_inner(fftconv_plan *p)
     return build_tables<16, 16>(p, &p->f3.consts);
 }
 
+// ko_n > 0: the k_f rows come in groups of ko_n (outer frequency digit ko); only ko < ko_lo and ko >= ko_hi
+// are processed (the others hold zero spectra and their rows are never touched).  ko_n = 0: every row.
 int fused3_inner_rows(const fftconv_plan *p, void *rows, const void *kf, int64_t rows_per_kf, int64_t kf_rows,
-                      hipStream_t s)
+                      hipStream_t s, int ko_n, int ko_lo, int ko_hi)
 {
+    int64_t live_rows = kf_rows;
+    if (ko_n > 0) {
+        if (ko_lo >= ko_hi) ko_n = 0;                            // everything live
+        else live_rows = kf_rows / ko_n * (ko_lo + ko_n - ko_hi);
+    }
     if (p->dtype == FFTCONV_F16)
-        return launch<16, 16, F16, false, true>(p, rows, kf, rows, rows_per_kf, kf_rows, Geo<16, 16>::M, s);
-    return launch<16, 16, BF16, false, true>(p, rows, kf, rows, rows_per_kf, kf_rows, Geo<16, 16>::M, s);
+        return launch<16, 16, F16, false, true>(p, rows, kf, rows, rows_per_kf, live_rows, Geo<16, 16>::M, s, ko_n, ko_lo,
+                                                ko_hi);
+    return launch<16, 16, BF16, false, true>(p, rows, kf, rows, rows_per_kf, live_rows, Geo<16, 16>::M, s, ko_n, ko_lo,
+                                             ko_hi);
 }
 
 void fused3_destroy(fftconv_plan *p)

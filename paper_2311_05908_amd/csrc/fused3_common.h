@@ -317,8 +317,10 @@ template <int N2, int N3>
 inline Consts consts_of(const fftconv_plan *p) { return consts_at<N2, N3>(p->f3.consts); }
 
 // wg / vg: input / output gate of the gated form (nullptr = none; only with nseg == 1)
+// live_k1: bit k1 clear = k_f is zero on that k1 plane (skipped; ungated calls only)
 int fused3_ws_launch(const fftconv_plan *p, const void *consts, const void *u, const void *kf, void *y, int64_t B,
-                     int nseg, int P, hipStream_t s, const void *wg = nullptr, const void *vg = nullptr);
+                     int nseg, int P, hipStream_t s, const void *wg = nullptr, const void *vg = nullptr,
+                     uint32_t live_k1 = 0xffffffffu);
 
 // fused kernel for fft_size 32768 (fused3_big.hip): own tables (in p->f3.consts) and k_f layout
 int fused3_big_init(fftconv_plan *p);

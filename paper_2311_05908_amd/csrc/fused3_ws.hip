@@ -56,10 +56,13 @@ constexpr int PCH = G::M / 8 / PT;            // 16-byte input chunks per outer-
 // GATE (gated form y = v . ((u . w) * k), Section 3.1 / 4.1; needs nseg == 1): bit 0 = the input gate
 // wg multiplies u on its way into LDS, bit 1 = the output gate vg multiplies y on its way out; the
 // gates travel with the staging traffic of the outer role (16-byte chunks, one item ahead / behind).
-template <typename TT, bool FULL, int GATE>
+// SKIP1 (frequency-sparse filters, Appendix A.4: the trip count of the per-plane loop): bit k1 of live_k1
+// clear means k_f is zero on the whole plane k1; phase B then writes zeros for it instead of computing.
+template <typename TT, bool FULL, int GATE, bool SKIP1 = false>
 __global__ void __launch_bounds__(NT) k_fused3_ws(const uint16_t *__restrict__ u, uint16_t *__restrict__ y,
                                                  const uint2 *__restrict__ kf, Consts cs, int B, int H, int N, int nseg, int P, int Lo,
-                                                 int probe, const uint16_t *__restrict__ wg, const uint16_t *__restrict__ vg)
+                                                 int probe, const uint16_t *__restrict__ wg, const uint16_t *__restrict__ vg,
+                                                 uint32_t live_k1)
 {
     extern __shared__ uint32_t smem[];
     uint32_t *const XBb = smem;                                   // [2][XBW]
@@ -343,6 +346,12 @@ __global__ void __launch_bounds__(NT) k_fused3_ws(const uint16_t *__restrict__ u
                 for (int i = 0; i < 8; ++i) {
                     const int c = 8 * wq + i;
                     if (i + 2 < 8) xq[(i + 2) % 3] = read_plane(i + 2);
+                    if constexpr (SKIP1) {
+                        if (!((live_k1 >> c) & 1u)) {             // wave-uniform
+                            *(uint4 *)(XB + c16 * G::PN3 + c * G::PK1 + 4 * q) = make_uint4(0, 0, 0, 0);
+                            continue;
+                        }
+                    }
                     const uint4 x3v = xq[i % 3];
                     // stage 3: matrix rows k3, data columns k2
                     f32x4 dre = TT::mfma(tab3[0], x3v, zero4);
@@ -383,7 +392,7 @@ static int ws_probe()
 // nseg == 1: plain causal convolution (N <= fft/2).  nseg > 1: overlap-save segments of a partial
 // convolution, P samples of history per segment, Lo = fft/2 - P outputs per later segment.
 int fused3_ws_launch(const fftconv_plan *p, const void *consts, const void *u, const void *kf, void *y, int64_t B,
-                     int nseg, int P, hipStream_t s, const void *wg, const void *vg)
+                     int nseg, int P, hipStream_t s, const void *wg, const void *vg, uint32_t live_k1)
 {
     const int64_t npairs = (B + 1) / 2;
     const int64_t T = p->H * npairs * nseg;
@@ -400,22 +409,26 @@ int fused3_ws_launch(const fftconv_plan *p, const void *consts, const void *u, c
     const bool f16 = p->dtype == FFTCONV_F16;
     const int gate = (wg ? 1 : 0) | (vg ? 2 : 0);
     using Kern = void (*)(const uint16_t *, uint16_t *, const uint2 *, Consts, int, int, int, int, int, int, int,
-                          const uint16_t *, const uint16_t *);
+                          const uint16_t *, const uint16_t *, uint32_t);
     static const Kern table[2][2][4] = {
         {{k_fused3_ws<BF16, false, 0>, k_fused3_ws<BF16, false, 1>, k_fused3_ws<BF16, false, 2>, k_fused3_ws<BF16, false, 3>},
          {k_fused3_ws<BF16, true, 0>, k_fused3_ws<BF16, true, 1>, k_fused3_ws<BF16, true, 2>, k_fused3_ws<BF16, true, 3>}},
         {{k_fused3_ws<F16, false, 0>, k_fused3_ws<F16, false, 1>, k_fused3_ws<F16, false, 2>, k_fused3_ws<F16, false, 3>},
          {k_fused3_ws<F16, true, 0>, k_fused3_ws<F16, true, 1>, k_fused3_ws<F16, true, 2>, k_fused3_ws<F16, true, 3>}}};
-    const Kern kern = table[f16 ? 1 : 0][full ? 1 : 0][gate];
-    static bool attr_set[2][2][4] = {};
-    if (!attr_set[f16 ? 1 : 0][full ? 1 : 0][gate]) {
+    // plane skipping: plain (ungated) convolution only
+    static const Kern table_skip[2][2] = {{k_fused3_ws<BF16, false, 0, true>, k_fused3_ws<BF16, true, 0, true>},
+                                          {k_fused3_ws<F16, false, 0, true>, k_fused3_ws<F16, true, 0, true>}};
+    const bool skip = live_k1 != 0xffffffffu && gate == 0;
+    const Kern kern = skip ? table_skip[f16 ? 1 : 0][full ? 1 : 0] : table[f16 ? 1 : 0][full ? 1 : 0][gate];
+    static bool attr_set[2][2][5] = {};
+    if (!attr_set[f16 ? 1 : 0][full ? 1 : 0][skip ? 4 : gate]) {
         FC_HIP(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)WS_LDS_BYTES));
-        attr_set[f16 ? 1 : 0][full ? 1 : 0][gate] = true;
+        attr_set[f16 ? 1 : 0][full ? 1 : 0][skip ? 4 : gate] = true;
     }
     const int grid = (int)(T < p->f3.num_cu ? T : p->f3.num_cu);
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NT), WS_LDS_BYTES, s, (const uint16_t *)u, (uint16_t *)y,
                        (const uint2 *)kf, consts_at<16, 16>(consts), (int)B, (int)p->H, (int)p->N, nseg, P, Lo, ws_probe(),
-                       (const uint16_t *)wg, (const uint16_t *)vg);
+                       (const uint16_t *)wg, (const uint16_t *)vg, live_k1);
     FC_HIP(hipGetLastError());
     return FFTCONV_OK;
 }

@@ -83,7 +83,7 @@ struct OuterGeo {
 // length-RB transform over b2, times W_M^{r ko} (ko = ka + RA kb, by recurrence over kb), to S.
 template <bool F16, int RA, int RB, int CV, bool FULLN>
 __global__ void __launch_bounds__(TB, 4) k_outer_fwd(const uint16_t *__restrict__ u, uint32_t *__restrict__ S, int CT,
-                                                 int B, int H, int N, int64_t M)
+                                                 int B, int H, int N, int64_t M, int ko_lo, int ko_hi)
 {
     extern __shared__ float2 sm[];
     constexpr int No = RA * RB;
@@ -169,7 +169,9 @@ __global__ void __launch_bounds__(TB, 4) k_outer_fwd(const uint16_t *__restrict_
         }
 #pragma unroll
         for (int kb = 0; kb < RB; ++kb) {
-            uint32_t *dst = &S[((size_t)ph * No + ka + RA * kb) * MI + r0 + c];
+            const int ko = ka + RA * kb;
+            if (ko >= ko_lo && ko < ko_hi) continue;          // row of a zeroed part of the spectrum: never used
+            uint32_t *dst = &S[((size_t)ph * No + ko) * MI + r0 + c];
             if constexpr (CV == 2)
                 *(uint2 *)dst = make_uint2(o[kb][0], o[kb][1]);
             else
@@ -181,7 +183,7 @@ __global__ void __launch_bounds__(TB, 4) k_outer_fwd(const uint16_t *__restrict_
 // ---- pass C: S -> conjugate twiddle -> outer inverse DFT -> the two real rows of the pair
 template <bool F16, int RA, int RB, int CV, bool FULLN>
 __global__ void __launch_bounds__(TB, 4) k_outer_inv(const uint32_t *__restrict__ S, uint16_t *__restrict__ y, int CT,
-                                                 int B, int H, int N, int64_t M)
+                                                 int B, int H, int N, int64_t M, int ko_lo, int ko_hi)
 {
     extern __shared__ float2 sm[];
     constexpr int No = RA * RB;
@@ -205,8 +207,12 @@ __global__ void __launch_bounds__(TB, 4) k_outer_inv(const uint32_t *__restrict_
         uint32_t in[RB][CV];
 #pragma unroll
         for (int kb = 0; kb < RB; ++kb) {
-            const uint32_t *src = &S[((size_t)ph * No + ka + RA * kb) * MI + r0 + c];
-            if constexpr (CV == 2) {
+            const int ko = ka + RA * kb;
+            const uint32_t *src = &S[((size_t)ph * No + ko) * MI + r0 + c];
+            if (ko >= ko_lo && ko < ko_hi) {                  // zeroed part of the spectrum: the row is zero
+#pragma unroll
+                for (int v = 0; v < CV; ++v) in[kb][v] = 0;
+            } else if constexpr (CV == 2) {
                 const uint2 t = *(const uint2 *)src;
                 in[kb][0] = t.x;
                 in[kb][1] = t.y;
@@ -308,7 +314,7 @@ OuterGeo outer_geo(int64_t M)
 
 template <bool F16, int RA, int RB, bool FULLN>
 int launch_outer_t(bool inverse, const OuterGeo &g, dim3 grid, const void *src, void *dst, int B, int H, int N, int64_t M,
-                   hipStream_t s)
+                   hipStream_t s, int ko_lo, int ko_hi)
 {
     constexpr int CV = RB <= 16 ? 2 : 1;           // two columns per thread while the registers allow
     const size_t lds = sizeof(float2) * ((size_t)g.No + (size_t)g.No * g.CT);
@@ -322,10 +328,10 @@ int launch_outer_t(bool inverse, const OuterGeo &g, dim3 grid, const void *src, 
     }
     if (!inverse)
         hipLaunchKernelGGL((k_outer_fwd<F16, RA, RB, CV, FULLN>), grid, dim3(TB), lds, s, (const uint16_t *)src,
-                           (uint32_t *)dst, g.CT, B, H, N, M);
+                           (uint32_t *)dst, g.CT, B, H, N, M, ko_lo, ko_hi);
     else
         hipLaunchKernelGGL((k_outer_inv<F16, RA, RB, CV, FULLN>), grid, dim3(TB), lds, s, (const uint32_t *)src,
-                           (uint16_t *)dst, g.CT, B, H, N, M);
+                           (uint16_t *)dst, g.CT, B, H, N, M, ko_lo, ko_hi);
     FC_HIP(hipGetLastError());
     return FFTCONV_OK;
 }
@@ -333,29 +339,30 @@ int launch_outer_t(bool inverse, const OuterGeo &g, dim3 grid, const void *src, 
 // the half-input instantiation needs an outer transform (No >= 2) and N <= M/2
 template <bool F16, int RA, int RB>
 int launch_outer(bool inverse, const OuterGeo &g, dim3 grid, const void *src, void *dst, int B, int H, int N, int64_t M,
-                 hipStream_t s)
+                 hipStream_t s, int ko_lo, int ko_hi)
 {
     if constexpr (RA >= 2) {
-        if ((int64_t)N <= M / 2) return launch_outer_t<F16, RA, RB, false>(inverse, g, grid, src, dst, B, H, N, M, s);
+        if ((int64_t)N <= M / 2)
+            return launch_outer_t<F16, RA, RB, false>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi);
     }
-    return launch_outer_t<F16, RA, RB, true>(inverse, g, grid, src, dst, B, H, N, M, s);
+    return launch_outer_t<F16, RA, RB, true>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi);
 }
 
 template <bool F16>
 int dispatch_outer(bool inverse, const OuterGeo &g, dim3 grid, const void *src, void *dst, int B, int H, int N,
-                   int64_t M, hipStream_t s)
+                   int64_t M, hipStream_t s, int ko_lo, int ko_hi)
 {
     switch (g.No) {
-    case 1: return launch_outer<F16, 1, 1>(inverse, g, grid, src, dst, B, H, N, M, s);
-    case 2: return launch_outer<F16, 2, 1>(inverse, g, grid, src, dst, B, H, N, M, s);
-    case 4: return launch_outer<F16, 4, 1>(inverse, g, grid, src, dst, B, H, N, M, s);
-    case 8: return launch_outer<F16, 8, 1>(inverse, g, grid, src, dst, B, H, N, M, s);
-    case 16: return launch_outer<F16, 16, 1>(inverse, g, grid, src, dst, B, H, N, M, s);
-    case 32: return launch_outer<F16, 16, 2>(inverse, g, grid, src, dst, B, H, N, M, s);
-    case 64: return launch_outer<F16, 16, 4>(inverse, g, grid, src, dst, B, H, N, M, s);
-    case 128: return launch_outer<F16, 16, 8>(inverse, g, grid, src, dst, B, H, N, M, s);
-    case 256: return launch_outer<F16, 16, 16>(inverse, g, grid, src, dst, B, H, N, M, s);
-    case 512: return launch_outer<F16, 16, 32>(inverse, g, grid, src, dst, B, H, N, M, s);
+    case 1: return launch_outer<F16, 1, 1>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi);
+    case 2: return launch_outer<F16, 2, 1>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi);
+    case 4: return launch_outer<F16, 4, 1>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi);
+    case 8: return launch_outer<F16, 8, 1>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi);
+    case 16: return launch_outer<F16, 16, 1>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi);
+    case 32: return launch_outer<F16, 16, 2>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi);
+    case 64: return launch_outer<F16, 16, 4>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi);
+    case 128: return launch_outer<F16, 16, 8>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi);
+    case 256: return launch_outer<F16, 16, 16>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi);
+    case 512: return launch_outer<F16, 16, 32>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi);
     default:
         set_error("multipass: unsupported outer length %d", g.No);
         return FFTCONV_EUNSUPPORTED;
@@ -392,8 +399,10 @@ int multipass_pack_kf(const fftconv_plan *p, const double2 *spec, int64_t h0, in
     return FFTCONV_OK;
 }
 
+// ko_lo, ko_hi: outer frequency digits ko in [ko_lo, ko_hi) only meet zeroed bins of k_f (frequency-sparse
+// filters); their rows of the workspace are skipped by all three passes.  ko_lo >= ko_hi: none.
 int multipass_forward(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, void *workspace,
-                      hipStream_t s)
+                      hipStream_t s, int ko_lo, int ko_hi)
 {
     const OuterGeo g = outer_geo(p->M);
     const int64_t npairs = (B + 1) / 2;
@@ -405,13 +414,14 @@ int multipass_forward(const fftconv_plan *p, const void *u, const void *kf, void
     const bool f16 = p->dtype == FFTCONV_F16;
     uint32_t *S = (uint32_t *)workspace;
     const dim3 grid((unsigned)(MI / g.CT), (unsigned)rows);
-    int rc = f16 ? dispatch_outer<true>(false, g, grid, u, S, (int)B, (int)p->H, (int)p->N, p->M, s)
-                 : dispatch_outer<false>(false, g, grid, u, S, (int)B, (int)p->H, (int)p->N, p->M, s);
+    if (ko_lo >= ko_hi) ko_lo = ko_hi = g.No;            // nothing skipped
+    int rc = f16 ? dispatch_outer<true>(false, g, grid, u, S, (int)B, (int)p->H, (int)p->N, p->M, s, ko_lo, ko_hi)
+                 : dispatch_outer<false>(false, g, grid, u, S, (int)B, (int)p->H, (int)p->N, p->M, s, ko_lo, ko_hi);
     if (rc) return rc;
-    rc = fused3_inner_rows(p, S, kf, npairs, p->H * g.No, s);
+    rc = fused3_inner_rows(p, S, kf, npairs, p->H * g.No, s, g.No, ko_lo, ko_hi);
     if (rc) return rc;
-    return f16 ? dispatch_outer<true>(true, g, grid, S, y, (int)B, (int)p->H, (int)p->N, p->M, s)
-               : dispatch_outer<false>(true, g, grid, S, y, (int)B, (int)p->H, (int)p->N, p->M, s);
+    return f16 ? dispatch_outer<true>(true, g, grid, S, y, (int)B, (int)p->H, (int)p->N, p->M, s, ko_lo, ko_hi)
+               : dispatch_outer<false>(true, g, grid, S, y, (int)B, (int)p->H, (int)p->N, p->M, s, ko_lo, ko_hi);
 }
 
 }  // namespace fftconv
