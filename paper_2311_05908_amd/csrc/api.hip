@@ -88,12 +88,12 @@ int fftconv_plan_create(fftconv_plan **out, int64_t N, int64_t fft_size, int64_t
         rc = FFTCONV_ENOMEM;
     }
     if (rc == FFTCONV_OK) {
-        if (small_supported(N, fft_size, dtype)) {
-            p->path = PATH_SMALL;
-            rc = small_init(p);
-        } else if (fused3_supported(N, fft_size, dtype)) {
+        if (fused3_supported(N, fft_size, dtype)) {     // 16-bit causal shapes, fft 512 .. 32768
             p->path = PATH_FUSED3;
             rc = fused3_init(p);
+        } else if (small_supported(N, fft_size, dtype)) {
+            p->path = PATH_SMALL;
+            rc = small_init(p);
         } else if (multipass_supported(N, fft_size, dtype)) {
             p->path = PATH_MULTIPASS;
             rc = multipass_init(p);

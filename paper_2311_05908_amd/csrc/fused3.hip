@@ -550,9 +550,11 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *u, uint16_t *y,
 // k_f in the fused kernel's per-lane order: [h][k1][k2 tile][k3 tile][r][lane] float2, where the
 // lane holds k2 = 16 tile + lane%16 and k3 = k3_at_index(16 tile + 4 (lane/16) + r).
 // fmt 0: fp32 pairs; fmt 1 / 2: 16-bit constant pairs for TT::ctw (bf16 dot-product / fp16 packed form)
+// groups > 1: spec holds spectra of length Ms = M / groups; slot (k1, k2, k3) of the kernel's 8192-point
+// layout takes bin k1 % N1s + N1s (k2 + N2 k3) of it (the same spectrum for every group), see build_tables().
 template <int N2, int N3>
 __global__ void k_pack_fused3(const double2 *spec, float2 *kf, FacList fl, int64_t h0, int64_t nh,
-                              const uint8_t *keep, int64_t n_blocks, int fmt)
+                              const uint8_t *keep, int64_t n_blocks, int fmt, int groups)
 {
     using G = Geo<N2, N3>;
     constexpr int64_t M = G::M;
@@ -560,11 +562,14 @@ __global__ void k_pack_fused3(const double2 *spec, float2 *kf, FacList fl, int64
     if (idx >= nh * M) return;
     int64_t h = idx / M, f = idx % M;
     int k1 = (int)(f % N1), k2 = (int)((f / N1) % N2), k3 = (int)(f / (N1 * N2));
+    const int N1s = N1 / groups;
+    const int64_t Ms = M / groups;
+    const int64_t fs = (k1 % N1s) + (int64_t)N1s * (k2 + (int64_t)N2 * k3);      // bin of the (sub-)transform
     const int slot = k3_index(k3, N3);                     // accumulator slot 16 t + 4 q + r of this k3
     int lane = ((slot % 16) / 4) * 16 + (k2 % 16), r = slot % 4;
     int64_t dst = ((((int64_t)k1 * G::R2 + k2 / 16) * G::R3 + slot / 16) * 4 + r) * 64 + lane;
-    double2 v = spec[h * M + freq_to_pos(f, fl, M)];
-    double sc = mask_weight(keep, n_blocks, f, M) / (double)M;
+    double2 v = spec[h * Ms + freq_to_pos(fs, fl, Ms)];
+    double sc = mask_weight(keep, n_blocks, fs, Ms) / (double)Ms;
     if (fmt == 0) {
         kf[(h0 + h) * M + dst] = make_float2((float)(v.x * sc), (float)(v.y * sc));
     } else {
@@ -631,11 +636,30 @@ void fill_operand(uint16_t *dst, bool f16, int t, int ct, int part, Fn G)
     }
 }
 
+// groups > 1 (N2 = N3 = 16 only): the tables of `groups` independent transforms of length Ms = 8192 / groups
+// = N1s * 16 * 16 (N1s = 32 / groups) that share one pass of the 8192-point kernel.  The outermost stage
+// becomes block diagonal: input rows n1 < 16 are the causal halves (N1s / 2 rows each) of the groups,
+// output k1 = g * N1s + k1' is frequency digit k1' of group g; the twiddles and the folded stage-2 inverse
+// matrices are those of a length-Ms transform; stages 2 and 3 do not change (N2 N3 = 256 either way).
+// groups = 32 (fft 256 = 1 * 16 * 16): the outer factor is 1 and a row n1 of the input slot holds the causal
+// halves of two groups, group 2 n1 in n2 < 8 and group 2 n1 + 1 in n2 >= 8.  Stage 1 copies the row to both
+// planes k1 = 2 n1, 2 n1 + 1, the elementwise twiddle zeroes the other group's half, and each plane runs its own
+// circular transform of length 256: the odd group works in a frame shifted by 128 samples, where its N <= 128
+// outputs still depend only on inputs at or before them.  The per-plane inverse stage-2 matrices keep only the
+// plane's own half of n2, so that inverse stage 1 (a sum over the two planes) reassembles the row.
 template <int N2, int N3>
-int build_tables(fftconv_plan *p, void **dest)
+int build_tables(fftconv_plan *p, void **dest, int groups = 1)
 {
     using G = Geo<N2, N3>;
     constexpr int64_t M = G::M;
+    const int N1s = N1 / groups, H1 = N1s / 2;                  // sub-transform: outer factor, its causal half
+    const int64_t Ms = M / groups;
+    const bool halves = groups == N1;                            // two groups per input row
+    auto g_of_k1 = [&](int k1) { return halves ? k1 / 2 : k1 / N1s; };          // (row of the pair of groups when halves)
+    auto g_of_n1 = [&](int n1) { return groups == 1 ? 0 : halves ? n1 : n1 / H1; };   // n1 < 16 when groups > 1
+    auto sub_n1 = [&](int n1) { return groups == 1 ? n1 : halves ? 0 : n1 % H1; };
+    auto own_half = [&](int k1, int n2) { return !halves || ((n2 >= N2 / 2) == ((k1 & 1) != 0)); };
+    const Cplx zero_c = {0.0, 0.0};
     const bool f16 = p->dtype == FFTCONV_F16;
     const size_t n_u4 = (size_t)G::TAB1 + G::TAB2 + 2 * (size_t)G::TAB3 + G::TAB2I + G::TAB1I;
     const size_t n_f2 = (size_t)G::TWA + G::TWB;
@@ -650,7 +674,10 @@ int build_tables(fftconv_plan *p, void **dest)
     for (int ks = 0; ks < 2; ++ks)
         for (int ct = 0; ct < 2; ++ct)
             for (int part = 0; part < 2; ++part)
-                fill_operand(next(), f16, ks, ct, part, [&](int n1, int k1) { return wpow(N1, (int64_t)n1 * k1); });
+                fill_operand(next(), f16, ks, ct, part, [&](int n1, int k1) {
+                    if (groups > 1 && (n1 >= 16 || g_of_n1(n1) != g_of_k1(k1))) return zero_c;
+                    return wpow(N1s, (int64_t)sub_n1(n1) * (k1 % N1s));
+                });
     // tab2 [n3][t][ct][part]: W_N2^{n2 k2} W_{N2 N3}^{k2 n3}
     for (int n3 = 0; n3 < N3; ++n3)
         for (int t = 0; t < G::R2; ++t)
@@ -677,14 +704,17 @@ int build_tables(fftconv_plan *p, void **dest)
             for (int ct = 0; ct < G::R2; ++ct)
                 for (int part = 0; part < 2; ++part)
                     fill_operand(next(), f16, t, ct, part, [&](int k2, int n2) {
-                        return conjh(cmulh(wpow(N2, (int64_t)n2 * k2), wpow((int64_t)N1 * N2, (int64_t)k1 * n2)));
+                        if (!own_half(k1, n2)) return zero_c;
+                        return conjh(cmulh(wpow(N2, (int64_t)n2 * k2), wpow((int64_t)N1s * N2, (int64_t)(k1 % N1s) * n2)));
                     });
     // tab1i [K step][row tile][part]: conj(W_N1^{k1 n1}); the causal kernel only forms row tile 0 (n1 < 16)
     for (int t = 0; t < 2; ++t)
         for (int rt = 0; rt < 2; ++rt)
             for (int part = 0; part < 2; ++part)
-                fill_operand(next(), f16, t, rt, part,
-                             [&](int k1, int n1) { return conjh(wpow(N1, (int64_t)n1 * k1)); });
+                fill_operand(next(), f16, t, rt, part, [&](int k1, int n1) {
+                    if (groups > 1 && (n1 >= 16 || g_of_n1(n1) != g_of_k1(k1))) return zero_c;
+                    return conjh(wpow(N1s, (int64_t)sub_n1(n1) * (k1 % N1s)));
+                });
     if (o != n_u4) {
         set_error("fused3: operand table size mismatch");
         return FFTCONV_EINVAL;
@@ -697,7 +727,7 @@ int build_tables(fftconv_plan *p, void **dest)
                 for (int r = 0; r < 4; ++r)
                     for (int lane = 0; lane < 64; ++lane) {
                         int k1 = 16 * ct + lane % 16, n2 = 16 * rt + 4 * (lane / 16) + r;
-                        Cplx v = wpow(M, (int64_t)k1 * ((int64_t)N3 * n2 + n3));
+                        Cplx v = own_half(k1, n2) ? wpow(Ms, (int64_t)(k1 % N1s) * ((int64_t)N3 * n2 + n3)) : zero_c;
                         tw16[w] = ctw_const(v.re, v.im, cfmt, hi16);
                         tw[w++] = make_float2((float)v.re, (float)v.im);
                     }
@@ -708,7 +738,7 @@ int build_tables(fftconv_plan *p, void **dest)
                 for (int r = 0; r < 4; ++r)
                     for (int lane = 0; lane < 64; ++lane) {
                         int n3 = 16 * ct3 + lane % 16, k2 = 16 * ct2 + 4 * (lane / 16) + r;
-                        Cplx v = conjh(wpow(M, ((int64_t)k1 + (int64_t)N1 * k2) * n3));
+                        Cplx v = conjh(wpow(Ms, ((int64_t)(k1 % N1s) + (int64_t)N1s * k2) * n3));
                         tw16[w] = ctw_const(v.re, v.im, cfmt, hi16);
                         tw[w++] = make_float2((float)v.re, (float)v.im);
                     }
@@ -766,7 +796,8 @@ int launch(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_
 bool fused3_supported(int64_t N, int64_t M, int dtype)
 {
     if (dtype != FFTCONV_F16 && dtype != FFTCONV_BF16) return false;
-    if (M != 8192 && M != 16384 && M != 32768) return false;
+    // 256 .. 4096: 8192 / fft_size transforms share one pass of the 8192-point kernel
+    if (M != 256 && M != 512 && M != 1024 && M != 2048 && M != 4096 && M != 8192 && M != 16384 && M != 32768) return false;
     return N <= M / 2 && N % 8 == 0;
 }
 
@@ -777,6 +808,15 @@ int fused3_init(fftconv_plan *p)
     FC_HIP(hipGetDeviceProperties(&prop, p->device));
     p->f3.num_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
     switch (p->M) {
+    case 256:
+    case 512:
+    case 1024:
+    case 2048:
+    case 4096:
+        p->f3.N1 = (int)(p->M / 256);
+        p->f3.N2 = 16;
+        p->f3.N3 = 16;
+        return build_tables<16, 16>(p, &p->f3.consts, (int)(8192 / p->M));
     case 8192:
         p->f3.N2 = 16;
         p->f3.N3 = 16;
@@ -899,7 +939,7 @@ size_t fused3_kf_bytes(const fftconv_plan *p)
     if (p->M == 32768) return fused3_big_kf_bytes(p);
     // fft 16384 plans: dense spectrum, then the 8192-point spectrum of a short filter (8 bytes per bin)
     if (p->M == 16384) return fused3_big_kf_bytes(p) + (size_t)(p->H * SHORT_M) * sizeof(float2);
-    return (size_t)(p->H * p->M) * sizeof(float2);
+    return (size_t)(p->H * 8192) * sizeof(float2);             // fft <= 8192: the 8192 slots of the wave-specialised kernel
 }
 
 static int64_t history_of(int64_t Nk) { return (Nk - 1 + 7) / 8 * 8; }
@@ -915,7 +955,7 @@ int fused3_pack_kf_short(const fftconv_plan *p, const double2 *spec, int64_t h0,
     const unsigned grid = (unsigned)((nh * SHORT_M + bs - 1) / bs);
     float2 *dst = (float2 *)((char *)kf + fused3_big_kf_bytes(p));
     hipLaunchKernelGGL((k_pack_fused3<16, 16>), dim3(grid), dim3(bs), 0, s, spec, dst, staged_factors_for(SHORT_M), h0,
-                       nh, (const uint8_t *)nullptr, (int64_t)1, p->dtype == FFTCONV_F16 ? 2 : 1);
+                       nh, (const uint8_t *)nullptr, (int64_t)1, p->dtype == FFTCONV_F16 ? 2 : 1, 1);
     FC_HIP(hipGetLastError());
     return FFTCONV_OK;
 }
@@ -943,13 +983,21 @@ int fused3_pack_kf(const fftconv_plan *p, const double2 *spec, int64_t h0, int64
                    int64_t n_blocks, void *kf, hipStream_t s)
 {
     const int bs = 256;
-    const unsigned grid = (unsigned)((nh * p->M + bs - 1) / bs);
     switch (p->M) {
-    case 8192:
-        // the wave-specialised 8192 kernel takes k_f as 16-bit constant pairs
+    case 256:
+    case 512:
+    case 1024:
+    case 2048:
+    case 4096:
+    case 8192: {
+        // the wave-specialised 8192 kernel takes k_f as 16-bit constant pairs; shorter transforms fill its
+        // 8192 slots with 8192 / fft_size copies of their spectrum (see build_tables())
+        const unsigned grid = (unsigned)((nh * 8192 + bs - 1) / bs);
         hipLaunchKernelGGL((k_pack_fused3<16, 16>), dim3(grid), dim3(bs), 0, s, spec, (float2 *)kf,
-                           staged_fac_list(p), h0, nh, keep_dev, n_blocks, p->dtype == FFTCONV_F16 ? 2 : 1);
+                           staged_fac_list(p), h0, nh, keep_dev, n_blocks, p->dtype == FFTCONV_F16 ? 2 : 1,
+                           (int)(8192 / p->M));
         break;
+    }
     case 16384:
     case 32768:
         return fused3_big_pack_kf(p, spec, h0, nh, keep_dev, n_blocks, kf, s);
@@ -961,7 +1009,7 @@ int fused3_pack_kf(const fftconv_plan *p, const double2 *spec, int64_t h0, int64
     return FFTCONV_OK;
 }
 
-bool fused3_gates_fused(const fftconv_plan *p) { return p->path == PATH_FUSED3 && p->M == 8192; }
+bool fused3_gates_fused(const fftconv_plan *p) { return p->path == PATH_FUSED3 && p->M <= 8192; }
 
 int fused3_forward_gated(const fftconv_plan *p, const void *u, const void *w, const void *v, const void *kf, void *y,
                          int64_t B, hipStream_t s)
@@ -980,6 +1028,11 @@ int fused3_forward(const fftconv_plan *p, const void *u, const void *kf, void *y
         return FFTCONV_EINVAL;
     }
     switch (p->M) {
+    case 256:
+    case 512:
+    case 1024:
+    case 2048:
+    case 4096:
     case 8192:
         return fused3_ws_launch(p, p->f3.consts, u, kf, y, B, 1, 0, s);     // wave-specialised schedule (fused3_ws.hip)
     case 16384:

@@ -53,6 +53,9 @@ constexpr int PCH = G::M / 8 / PT;            // 16-byte input chunks per outer-
 
 // FULL: B even and N == fft_size/2, so every load and store of a work item is in range and
 // unconditional (the compiler can then count outstanding memory operations exactly).
+// groups > 1 (nseg == 1): a work item holds `groups` pairs of rows of a transform of length 8192 / groups (tables
+// from build_tables(..., groups)): positions [g * half, (g + 1) * half) of its 4096-sample input / output slot,
+// half = 2^lg_half = fft_size / 2, belong to the pair 2 (pair * groups + g), of which the first N are real samples.
 // GATE (gated form y = v . ((u . w) * k), Section 3.1 / 4.1; needs nseg == 1): bit 0 = the input gate
 // wg multiplies u on its way into LDS, bit 1 = the output gate vg multiplies y on its way out; the
 // gates travel with the staging traffic of the outer role (16-byte chunks, one item ahead / behind).
@@ -62,7 +65,7 @@ template <typename TT, bool FULL, int GATE, bool SKIP1 = false>
 __global__ void __launch_bounds__(NT) k_fused3_ws(const uint16_t *__restrict__ u, uint16_t *__restrict__ y,
                                                  const uint2 *__restrict__ kf, Consts cs, int B, int H, int N, int nseg, int P, int Lo,
                                                  int probe, const uint16_t *__restrict__ wg, const uint16_t *__restrict__ vg,
-                                                 uint32_t live_k1)
+                                                 uint32_t live_k1, int groups, int lg_half)
 {
     extern __shared__ uint32_t smem[];
     uint32_t *const XBb = smem;                                   // [2][XBW]
@@ -77,7 +80,7 @@ __global__ void __launch_bounds__(NT) k_fused3_ws(const uint16_t *__restrict__ u
     // convolutions (a filter much shorter than the sequence): the row is cut into overlapping
     // windows of at most fft/2 samples, segment 0 yields outputs [0, fft/2), segment j >= 1 yields Lo
     // outputs and reads P samples of history before them (P >= filter length - 1), i.e. overlap-save.
-    const int npairs = (B + 1) / 2;
+    const int npairs = (B + 2 * groups - 1) / (2 * groups);
     const int per_h = npairs * nseg;
     const long long T = (long long)H * per_h;
     const int t0 = (int)(T * blockIdx.x / gridDim.x);
@@ -88,6 +91,14 @@ __global__ void __launch_bounds__(NT) k_fused3_ws(const uint16_t *__restrict__ u
     if (w < 4) {
         // =========================== outer role: phases A and C, staging ===========================
         const int ptid = tid;                                     // 0..255
+        // chunk j of this thread sits at position cn[j % 2] of the item's slot: group cg[], offset co[] in its row
+        int cg[2], co[2];
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            const int n = (ptid + PT * e) * 8;
+            cg[e] = n >> lg_half;
+            co[e] = n & ((1 << lg_half) - 1);
+        }
         uint4 tab1[2][2], tab1i[2][2], tab2[4][2];
         uint2 twa[4][2][4];
 #pragma unroll
@@ -116,16 +127,16 @@ __global__ void __launch_bounds__(NT) k_fused3_ws(const uint16_t *__restrict__ u
 #pragma unroll
             for (int j = 0; j < PCH; ++j) {
                 const int s = j / 2;
-                const int n = (ptid + PT * (j % 2)) * 8;
-                const int b = 2 * pair + s;
+                const int n = co[j % 2];
                 if constexpr (FULL) {
                     // (nseg == 1) past the end of the range the last item is fetched again (in range, unused)
                     const int tc = t < t1 ? t : t1 - 1;
                     const int hc = tc / npairs, pc = tc - hc * npairs;
-                    const size_t ofs = ((size_t)(2 * pc + s) * H + hc) * N + n;
+                    const size_t ofs = ((size_t)(2 * (pc * groups + cg[j % 2]) + s) * H + hc) * N + n;
                     pre[j] = *(const uint4 *)(u + ofs);
                     if constexpr (GATE & 1) prew[j] = *(const uint4 *)(wg + ofs);
                 } else {
+                    const int b = 2 * (pair * groups + cg[j % 2]) + s;
                     uint4 v = make_uint4(0, 0, 0, 0);
                     const int in_ofs = seg == 0 ? 0 : G::M / 2 + (seg - 1) * Lo - P;
                     const uint16_t *row = u + ((size_t)b * H + h) * N + in_ofs;
@@ -148,8 +159,8 @@ __global__ void __launch_bounds__(NT) k_fused3_ws(const uint16_t *__restrict__ u
 #pragma unroll
                 for (int j = 0; j < PCH; ++j) {
                     const int s = j / 2;
-                    const int n = (ptid + PT * (j % 2)) * 8;
-                    const int b = 2 * pair + s;
+                    const int n = co[j % 2];
+                    const int b = 2 * (pair * groups + cg[j % 2]) + s;
                     uint4 g = make_uint4(0, 0, 0, 0);
                     if (FULL || (b < B && n < N)) g = *(const uint4 *)(vg + ((size_t)b * H + h) * N + n);
                     prev[j] = g;
@@ -180,17 +191,18 @@ __global__ void __launch_bounds__(NT) k_fused3_ws(const uint16_t *__restrict__ u
 #pragma unroll
             for (int j = 0; j < PCH; ++j) {
                 const int s = j / 2;
-                const int n = (ptid + PT * (j % 2)) * 8;
-                const int b = 2 * pair + s;
+                const int n = (ptid + PT * (j % 2)) * 8;          // position in the item's slot
+                const int nr = co[j % 2];                         // ... in its row
+                const int b = 2 * (pair * groups + cg[j % 2]) + s;
                 const int n3 = n % 16, n2 = (n / 16) % 16, n1 = n / 256;
                 const uint32_t *src = (const uint32_t *)(YB + s * G::SU + n1 * G::PQ1 + n2 * G::PR + n3);
                 uint4 v = make_uint4(src[0], src[1], src[2], src[3]);
                 if constexpr (GATE & 2) v = TT::mul8(v, prev[j]);
                 if constexpr (FULL) {
-                    *(uint4 *)(y + ((size_t)b * H + h) * N + n) = v;
+                    *(uint4 *)(y + ((size_t)b * H + h) * N + nr) = v;
                 } else {
                     uint16_t *row = y + ((size_t)b * H + h) * N + out_ofs;
-                    if (b < B && n >= skip && n - skip < out_len) *(uint4 *)(row + (n - skip)) = v;
+                    if (b < B && nr >= skip && nr - skip < out_len) *(uint4 *)(row + (nr - skip)) = v;
                 }
             }
         };
@@ -394,7 +406,11 @@ static int ws_probe()
 int fused3_ws_launch(const fftconv_plan *p, const void *consts, const void *u, const void *kf, void *y, int64_t B,
                      int nseg, int P, hipStream_t s, const void *wg, const void *vg, uint32_t live_k1)
 {
-    const int64_t npairs = (B + 1) / 2;
+    // plans for fft 512 .. 4096 put 8192 / fft transforms into one work item (their tables say so)
+    const int groups = p->M < G::M && consts == p->f3.consts ? (int)(G::M / p->M) : 1;
+    int lg_half = 0;
+    while ((G::M / 2 / groups) >> (lg_half + 1)) ++lg_half;
+    const int64_t npairs = (B + 2 * groups - 1) / (2 * groups);
     const int64_t T = p->H * npairs * nseg;
     const int Lo = G::M / 2 - P;
     if (T >= ((int64_t)1 << 31) - 8) {
@@ -405,11 +421,15 @@ int fused3_ws_launch(const fftconv_plan *p, const void *consts, const void *u, c
         set_error("fused 8192 kernel: gates cannot be combined with overlapping segments");
         return FFTCONV_EUNSUPPORTED;
     }
-    const bool full = (B % 2 == 0) && p->N == G::M / 2 && nseg == 1;
+    if (groups > 1 && nseg != 1) {
+        set_error("fused 8192 kernel: grouped short transforms cannot be combined with overlapping segments");
+        return FFTCONV_EUNSUPPORTED;
+    }
+    const bool full = (B % (2 * groups) == 0) && p->N == G::M / 2 / groups && nseg == 1;
     const bool f16 = p->dtype == FFTCONV_F16;
     const int gate = (wg ? 1 : 0) | (vg ? 2 : 0);
     using Kern = void (*)(const uint16_t *, uint16_t *, const uint2 *, Consts, int, int, int, int, int, int, int,
-                          const uint16_t *, const uint16_t *, uint32_t);
+                          const uint16_t *, const uint16_t *, uint32_t, int, int);
     static const Kern table[2][2][4] = {
         {{k_fused3_ws<BF16, false, 0>, k_fused3_ws<BF16, false, 1>, k_fused3_ws<BF16, false, 2>, k_fused3_ws<BF16, false, 3>},
          {k_fused3_ws<BF16, true, 0>, k_fused3_ws<BF16, true, 1>, k_fused3_ws<BF16, true, 2>, k_fused3_ws<BF16, true, 3>}},
@@ -428,7 +448,7 @@ int fused3_ws_launch(const fftconv_plan *p, const void *consts, const void *u, c
     const int grid = (int)(T < p->f3.num_cu ? T : p->f3.num_cu);
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NT), WS_LDS_BYTES, s, (const uint16_t *)u, (uint16_t *)y,
                        (const uint2 *)kf, consts_at<16, 16>(consts), (int)B, (int)p->H, (int)p->N, nseg, P, Lo, ws_probe(),
-                       (const uint16_t *)wg, (const uint16_t *)vg, live_k1);
+                       (const uint16_t *)wg, (const uint16_t *)vg, live_k1, groups, lg_half);
     FC_HIP(hipGetLastError());
     return FFTCONV_OK;
 }

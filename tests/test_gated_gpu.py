@@ -44,9 +44,22 @@ def check_all(w, use_w=True, use_v=True):
     (1, 2, 2048, True, True),       # B = 1, N < fft/2
 ])
 def test_gated_fused_fft8192(dtype, B, H, N, use_w, use_v):
-    w = synth.scaled(W["cfg2"], B=B, H=H, N=N, fft_size=8192, dtype=dtype)
+    _gated_fused(dtype, B, H, N, 8192, use_w, use_v)
+
+
+@pytest.mark.parametrize("dtype,B,H,N,M,use_w,use_v", [
+    ("bf16", 5, 2, 2048, 4096, True, True),     # short transforms grouped on the 8192-point kernel: gates fused too
+    ("f16", 16, 1, 1024, 2048, True, False),
+    ("bf16", 9, 3, 200, 512, False, True),
+])
+def test_gated_fused_short_transforms(dtype, B, H, N, M, use_w, use_v):
+    _gated_fused(dtype, B, H, N, M, use_w, use_v)
+
+
+def _gated_fused(dtype, B, H, N, M, use_w, use_v):
+    w = synth.scaled(W["cfg2"], B=B, H=H, N=N, fft_size=M, dtype=dtype)
     err, plan = check_all(w, use_w, use_v)
-    print("gated fused 8192 %s B=%d H=%d N=%d w=%d v=%d path=%s err=%.3e" % (dtype, B, H, N, use_w, use_v, plan.path, err),
+    print("gated fused %d %s B=%d H=%d N=%d w=%d v=%d path=%s err=%.3e" % (M, dtype, B, H, N, use_w, use_v, plan.path, err),
           flush=True)
     assert plan.path == "fused3" and plan.workspace_bytes_gated(B) == 0
     assert err <= TOL[dtype]
@@ -55,7 +68,7 @@ def test_gated_fused_fft8192(dtype, B, H, N, use_w, use_v):
 @pytest.mark.parametrize("dtype,B,H,N,M", [
     ("f32", 2, 3, 256, 512),        # short-transform kernel
     ("f32", 3, 2, 300, 1024),
-    ("bf16", 2, 2, 200, 512),
+    ("bf16", 2, 2, 204, 512),       # 16-bit I/O with N not a multiple of 8 stays on that kernel
     ("f32", 2, 2, 4096, 8192),      # staged path
     ("bf16", 3, 2, 8192, 16384),    # fused 16384 kernel, gates by elementwise kernels
     ("f16", 2, 2, 16384, 32768),    # fused 32768 kernel

@@ -29,15 +29,17 @@ def test_small_shapes_all_dtypes(dtype, B, H, N, M):
     w = synth.scaled(W["cfg2"], B=B, H=H, N=N, fft_size=M, dtype=dtype, alpha=(1e-2, 1e-1))
     err, plan = check_all_sequences(w)
     print("%s B=%d H=%d N=%d M=%d path=%s err=%.3e" % (dtype, B, H, N, M, plan.path, err), flush=True)
-    assert plan.path == "small"
+    # 16-bit causal shapes with N a multiple of 8 share the 8192-point kernel; the rest is the short-transform kernel
+    grouped = dtype != "f32" and N <= M // 2 and N % 8 == 0
+    assert plan.path == ("fused3" if grouped else "small")
     assert err <= TOL[dtype]
 
 
 @pytest.mark.parametrize("dtype,B,H,N,M", [
     ("bf16", 37, 3, 100, 256),       # 16 pairs per workgroup pass, a ragged last group, odd batch
-    ("f16", 9, 5, 256, 512),         # 8 pairs per pass
+    ("f16", 9, 5, 260, 512),         # 8 pairs per pass
     ("f32", 7, 3, 512, 1024),        # 4 pairs per pass
-    ("bf16", 4, 3, 1024, 2048),      # three passes, radices 16, 16, 8
+    ("bf16", 4, 3, 1028, 2048),      # three passes, radices 16, 16, 8 (N > fft/2 keeps 16-bit I/O on this kernel)
     ("f32", 3, 2, 4096, 4096),       # one pair per pass, circular
 ])
 def test_small_transform_kernel_group_shapes(dtype, B, H, N, M):
@@ -46,6 +48,31 @@ def test_small_transform_kernel_group_shapes(dtype, B, H, N, M):
     print("small %s B=%d H=%d N=%d M=%d path=%s factors=%s err=%.3e" % (dtype, B, H, N, M, plan.path, plan.factors, err),
           flush=True)
     assert plan.path == "small"
+    assert err <= TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype,B,H,N,M", [
+    ("bf16", 4, 3, 2048, 4096),      # 2 transforms per pass of the 8192-point kernel, every row present
+    ("f16", 5, 2, 2048, 4096),       # odd batch: the last pair and the last group are partly empty
+    ("bf16", 16, 2, 1024, 2048),     # 4 per pass
+    ("f16", 3, 3, 1000, 2048),       # N < fft/2: the tail of every group's slot is implicit zeros
+    ("bf16", 37, 2, 512, 1024),      # 8 per pass, ragged batch
+    ("f16", 64, 1, 256, 512),        # 16 per pass
+    ("bf16", 7, 2, 200, 512),
+    ("bf16", 1, 1, 2048, 4096),      # a single row
+    ("bf16", 64, 2, 128, 256),       # 32 per pass: two transforms share an input row, the odd one in a shifted frame
+    ("f16", 67, 3, 128, 256),
+    ("bf16", 5, 1, 64, 256),         # N < fft/2
+])
+def test_short_transforms_grouped_on_the_8192_kernel(dtype, B, H, N, M):
+    """fft 256 .. 4096, 16-bit I/O: 8192 / fft transforms share one work item of the wave-specialised kernel
+    (block-diagonal outermost stage)."""
+    w = synth.scaled(W["cfg2"], B=B, H=H, N=N, fft_size=M, dtype=dtype, alpha=(1e-2, 1e-1))
+    err, plan = check_all_sequences(w)
+    print("grouped %s B=%d H=%d N=%d M=%d path=%s factors=%s err=%.3e" % (dtype, B, H, N, M, plan.path, plan.factors, err),
+          flush=True)
+    assert plan.path == "fused3"
+    assert plan.factors == [M // 256, 16, 16]
     assert err <= TOL[dtype]
 
 
