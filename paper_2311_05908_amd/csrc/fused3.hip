@@ -47,6 +47,8 @@
 #include <hip/hip_bf16.h>
 #include <hip/hip_fp16.h>
 
+#include <type_traits>
+
 #include "fused3_common.h"
 
 // Timing probes (development builds only, -DFUSED3_PROBE): a launch-time mask switches whole
@@ -75,7 +77,7 @@ using namespace f3;
 // place among all rows.  The other rows are neither read nor written.
 template <int N2, int N3, typename TT, bool REGC, bool CPLX, int LIVE = 4>
 __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *u, uint16_t *y,
-                                              const float2 *__restrict__ kf, Consts cs, int B, int H, int N,
+                                              const uint32_t *__restrict__ kf, Consts cs, int B, int H, int N,
                                               int probe, int KoN, int ko_lo, int ko_hi)
 {
     using G = Geo<N2, N3>;
@@ -131,7 +133,10 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *u, uint16_t *y,
     // ---------------- constants (per-lane operand tables) ----------------
     uint4 tab1[KS1][2][2], tab1i[2][RT1][2], tab3[R3][R3][2], tab3i[R3][R3][2];
     uint4 tab2[C3][R2][R2][2], tab2i[C1][R2][R2][2];
-    float2 twa[C3][R2][2][4], twb[C1][R2][R3][4], kfr[C1][R2][R3][4];
+    float2 twa[C3][R2][2][4], twb[C1][R2][R3][4];
+    // k_f: 4-byte 16-bit (re, im) constants (it is streamed for every row: as many bytes as the row itself at 8)
+    using T4 = typename std::conditional<std::is_same<TT, F16>::value, H16, B16>::type;
+    uint32_t kfr[C1][R2][R3][4];
 
 #pragma unroll
     for (int a = 0; a < 2; ++a)
@@ -444,16 +449,14 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *u, uint16_t *y,
                             dre = TT::mfma(tab3[ks][ct3][0], x3[i][ct2][ks], dre);
                             dim = TT::mfma(tab3[ks][ct3][1], x3[i][ct2][ks], dim);
                         }
+                        // the product runs in fp32 (plain multiply-adds overlap with the matrix cores of the
+                        // other wave, the 16-bit dot products do not); the constant is widened in two cheap ops
                         uint32_t o[4];
 #pragma unroll
                         for (int r = 0; r < 4; ++r) {
-                            if (r < LIVE) {
-                                float re = dre[r], im = dim[r];
-                                cmul_ip(re, im, kfr[i][ct2][ct3][r]);
-                                o[r] = TT::pack(re, im);
-                            } else {
-                                o[r] = 0;                         // k_f is zero for every k3 held in this slot
-                            }
+                            float re = dre[r], im = dim[r];
+                            cmul_ip(re, im, T4::widen(kfr[i][ct2][ct3][r]));
+                            o[r] = TT::pack(re, im);
                         }
                         x3i[ct2][ct3] = make_uint4(o[0], o[1], o[2], o[3]);
                     }
@@ -786,7 +789,7 @@ int launch(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_
     int grid = (int)(T < p->f3.num_cu ? T : p->f3.num_cu);
     if (!REGC && grid >= 8) grid -= grid % 8;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NT), lds, s, (const uint16_t *)u, (uint16_t *)y,
-                       (const float2 *)kf, consts_of<N2, N3>(p), (int)B, (int)H, (int)N, probe_mask(), KoN, ko_lo, ko_hi);
+                       (const uint32_t *)kf, consts_of<N2, N3>(p), (int)B, (int)H, (int)N, probe_mask(), KoN, ko_lo, ko_hi);
     FC_HIP(hipGetLastError());
     return FFTCONV_OK;
 }

@@ -177,6 +177,11 @@ struct B16 {
     static __host__ __device__ inline CW cconst(uint32_t re, uint32_t im, bool) { return re | (im << 16); }   // 16-bit patterns
     // from the 8-byte table form of BF16::ctw4, { (wr, -wi), (wi, wr) }
     static __device__ __forceinline__ CW from_table(uint2 c) { return c.x ^ 0x80000000u; }
+    // the constant as an fp32 pair
+    static __device__ __forceinline__ float2 widen(CW c)
+    {
+        return make_float2(__uint_as_float(c << 16), __uint_as_float(c & 0xffff0000u));
+    }
     static __device__ __forceinline__ uint4 mul8(uint4 a, uint4 b) { return BF16::mul8(a, b); }
 };
 
@@ -191,6 +196,12 @@ struct H16 {
     static __host__ __device__ inline CW cconst(uint32_t re, uint32_t im, bool) { return re | (im << 16); }
     // from the 8-byte table form of F16::ctw4, { (wr, wr), (-wi, wi) }
     static __device__ __forceinline__ CW from_table(uint2 c) { return (c.x & 0xffffu) | (c.y & 0xffff0000u); }
+    // the constant as an fp32 pair
+    static __device__ __forceinline__ float2 widen(CW c)
+    {
+        const f16x2 h = __builtin_bit_cast(f16x2, c);
+        return make_float2((float)h[0], (float)h[1]);
+    }
     static __device__ __forceinline__ uint4 mul8(uint4 a, uint4 b) { return F16::mul8(a, b); }
     template <bool CONJ> static __device__ __forceinline__ uint4 ctw4(f32x4 re, f32x4 im, const CW (&c)[4])
     {

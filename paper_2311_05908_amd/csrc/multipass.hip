@@ -167,15 +167,23 @@ __global__ void __launch_bounds__(TB, 4) k_outer_fwd(const uint16_t *__restrict_
                 w = cmulf(w, step);
             }
         }
-#pragma unroll
-        for (int kb = 0; kb < RB; ++kb) {
-            const int ko = ka + RA * kb;
-            if (ko >= ko_lo && ko < ko_hi) continue;          // row of a zeroed part of the spectrum: never used
-            uint32_t *dst = &S[((size_t)ph * No + ko) * MI + r0 + c];
+        auto put = [&](int kb) {
+            uint32_t *dst = &S[((size_t)ph * No + ka + RA * kb) * MI + r0 + c];
             if constexpr (CV == 2)
                 *(uint2 *)dst = make_uint2(o[kb][0], o[kb][1]);
             else
                 *dst = o[kb][0];
+        };
+        if (ko_lo >= ko_hi) {                             // dense: unconditional stores, back to back
+#pragma unroll
+            for (int kb = 0; kb < RB; ++kb) put(kb);
+        } else {
+            // frequency-sparse filter: rows of a zeroed part of the spectrum are never used
+#pragma unroll
+            for (int kb = 0; kb < RB; ++kb) {
+                const int ko = ka + RA * kb;
+                if (ko < ko_lo || ko >= ko_hi) put(kb);
+            }
         }
     }
 }
@@ -286,8 +294,9 @@ __global__ void __launch_bounds__(TB, 4) k_outer_inv(const uint32_t *__restrict_
     }
 }
 
-// k_f for the multi-pass path: [h][ko][inner order of f'] fp32 pairs, f = ko + No*f', scaled 1/M.
-__global__ void k_pack_multipass(const double2 *spec, float2 *kf, FacList fl, int64_t M, int No, int64_t h0,
+// k_f for the multi-pass path: [h][ko][inner order of f'] 16-bit (re, im) pairs, f = ko + No*f', scaled 1/M.
+template <bool F16>
+__global__ void k_pack_multipass(const double2 *spec, uint32_t *kf, FacList fl, int64_t M, int No, int64_t h0,
                                  int64_t nh, const uint8_t *keep, int64_t n_blocks)
 {
     int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -298,7 +307,7 @@ __global__ void k_pack_multipass(const double2 *spec, float2 *kf, FacList fl, in
     const double2 v = spec[h * M + freq_to_pos(f, fl, M)];
     const double sc = mask_weight(keep, n_blocks, f, M) / (double)M;
     kf[((h0 + h) * No + ko) * (int64_t)MI + fused3_kf_slot_8192(fi)] =
-        make_float2((float)(v.x * sc), (float)(v.y * sc));
+        (uint32_t)cv16<F16>((float)(v.x * sc)) | ((uint32_t)cv16<F16>((float)(v.y * sc)) << 16);
 }
 
 OuterGeo outer_geo(int64_t M)
@@ -380,7 +389,7 @@ bool multipass_supported(int64_t N, int64_t M, int dtype)
 
 int multipass_init(fftconv_plan *p) { return fused3_init_inner(p); }
 
-size_t multipass_kf_bytes(const fftconv_plan *p) { return (size_t)(p->H * p->M) * sizeof(float2); }
+size_t multipass_kf_bytes(const fftconv_plan *p) { return (size_t)(p->H * p->M) * sizeof(uint32_t); }
 
 size_t multipass_workspace_bytes(const fftconv_plan *p, int64_t B)
 {
@@ -393,8 +402,12 @@ int multipass_pack_kf(const fftconv_plan *p, const double2 *spec, int64_t h0, in
 {
     const int bs = 256;
     const unsigned grid = (unsigned)((nh * p->M + bs - 1) / bs);
-    hipLaunchKernelGGL(k_pack_multipass, dim3(grid), dim3(bs), 0, s, spec, (float2 *)kf, staged_fac_list(p), p->M,
-                       (int)(p->M / MI), h0, nh, keep_dev, n_blocks);
+    if (p->dtype == FFTCONV_F16)
+        hipLaunchKernelGGL(k_pack_multipass<true>, dim3(grid), dim3(bs), 0, s, spec, (uint32_t *)kf, staged_fac_list(p),
+                           p->M, (int)(p->M / MI), h0, nh, keep_dev, n_blocks);
+    else
+        hipLaunchKernelGGL(k_pack_multipass<false>, dim3(grid), dim3(bs), 0, s, spec, (uint32_t *)kf, staged_fac_list(p),
+                           p->M, (int)(p->M / MI), h0, nh, keep_dev, n_blocks);
     FC_HIP(hipGetLastError());
     return FFTCONV_OK;
 }
