@@ -128,11 +128,11 @@ __global__ void k_stage_inv(const V *in, V *out, const V *w, int64_t M, int Nj, 
     out[idx] = acc;
 }
 
-// The same two stages for fp32 data with the length-R transform done in registers (R a power of two <= 32):
-// one thread per (row, prefix, r) loads its R inputs once, instead of R loads per output.  Used by the fp32
-// forward path and by the filter gradient; the fp64 filter transform keeps the plain kernels above.
-template <int R>
-__global__ void k_stage_fwd_reg(const float2 *in, float2 *out, const float2 *w, int64_t M, int64_t Sj, int64_t Rj,
+// The same two stages with the length-R transform done in registers (R a power of two <= 32): one thread per
+// (row, prefix, r) loads its R inputs once, instead of R loads per output.  The plain kernels above remain for
+// factors these do not cover.
+template <int R, typename V>
+__global__ void k_stage_fwd_reg(const V *in, V *out, const V *w, int64_t M, int64_t Sj, int64_t Rj,
                                 int64_t nrows, int64_t tws)
 {
     const int64_t per_row = M / R;
@@ -141,7 +141,7 @@ __global__ void k_stage_fwd_reg(const float2 *in, float2 *out, const float2 *w, 
     const int64_t row = idx / per_row, q = idx % per_row;
     const int64_t r = q % Sj, prefix = q / Sj;
     const int64_t base = row * M + prefix * (R * Sj) + r;
-    float2 x[R];
+    V x[R];
 #pragma unroll
     for (int n = 0; n < R; ++n) x[n] = in[base + (int64_t)n * Sj];
     dft_reg<R, false>(x);
@@ -149,8 +149,8 @@ __global__ void k_stage_fwd_reg(const float2 *in, float2 *out, const float2 *w, 
     for (int k = 0; k < R; ++k) out[base + (int64_t)k * Sj] = cmul(x[k], w[(int64_t)k * Rj * r * tws]);
 }
 
-template <int R>
-__global__ void k_stage_inv_reg(const float2 *in, float2 *out, const float2 *w, int64_t M, int64_t Sj, int64_t Rj,
+template <int R, typename V>
+__global__ void k_stage_inv_reg(const V *in, V *out, const V *w, int64_t M, int64_t Sj, int64_t Rj,
                                 int64_t nrows)
 {
     const int64_t per_row = M / R;
@@ -159,7 +159,7 @@ __global__ void k_stage_inv_reg(const float2 *in, float2 *out, const float2 *w, 
     const int64_t row = idx / per_row, q = idx % per_row;
     const int64_t r = q % Sj, prefix = q / Sj;
     const int64_t base = row * M + prefix * (R * Sj) + r;
-    float2 x[R];
+    V x[R];
 #pragma unroll
     for (int k = 0; k < R; ++k) x[k] = cmul_conj(in[base + (int64_t)k * Sj], w[(int64_t)k * Rj * r]);   // k Rj r < M
     dft_reg<R, true>(x);
@@ -169,8 +169,9 @@ __global__ void k_stage_inv_reg(const float2 *in, float2 *out, const float2 *w, 
 
 inline unsigned grid_of(int64_t n, int bs) { return (unsigned)((n + bs - 1) / bs); }
 
-// one fp32 stage, in registers when the factor allows; returns false if it does not
-bool launch_stage_reg(bool inverse, const float2 *src, float2 *dst, const float2 *w, int64_t M, int Nj, int64_t S,
+// one stage, in registers when the factor allows; returns false if it does not
+template <typename V>
+bool launch_stage_reg(bool inverse, const V *src, V *dst, const V *w, int64_t M, int Nj, int64_t S,
                       int64_t R, int64_t nrows, int64_t tws, hipStream_t s)
 {
     const int bs = 256;
@@ -178,9 +179,9 @@ bool launch_stage_reg(bool inverse, const float2 *src, float2 *dst, const float2
 #define STAGE_REG(RR)                                                                                          \
     case RR:                                                                                                   \
         if (inverse)                                                                                           \
-            hipLaunchKernelGGL(k_stage_inv_reg<RR>, dim3(grid), dim3(bs), 0, s, src, dst, w, M, S, R, nrows);   \
+            hipLaunchKernelGGL((k_stage_inv_reg<RR, V>), dim3(grid), dim3(bs), 0, s, src, dst, w, M, S, R, nrows);   \
         else                                                                                                   \
-            hipLaunchKernelGGL(k_stage_fwd_reg<RR>, dim3(grid), dim3(bs), 0, s, src, dst, w, M, S, R, nrows, tws); \
+            hipLaunchKernelGGL((k_stage_fwd_reg<RR, V>), dim3(grid), dim3(bs), 0, s, src, dst, w, M, S, R, nrows, tws); \
         return true;
     switch (Nj) {
         STAGE_REG(2)
@@ -240,9 +241,7 @@ int run_stages_fwd(const FacList &fl, int64_t M, int64_t tws, V *a, V *b, const 
     for (int i = 0; i < fl.nf; ++i) {
         int Nj = fl.fac[i];
         S /= Nj;
-        bool done = false;
-        if constexpr (std::is_same<V, float2>::value) done = launch_stage_reg(false, src, dst, w, M, Nj, S, R, nrows, tws, s);
-        if (!done)
+        if (!launch_stage_reg<V>(false, src, dst, w, M, Nj, S, R, nrows, tws, s))
             hipLaunchKernelGGL(k_stage_fwd<V>, dim3(grid_for(nrows * M, bs)), dim3(bs), 0, s, src, dst, w, M, Nj, S, R,
                                nrows, tws);
         FC_HIP(hipGetLastError());
@@ -343,7 +342,7 @@ static int staged_forward_t(const fftconv_plan *p, const IO *u, const float2 *kf
         for (int i = p->st.nf - 1; i >= 0; --i) {
             int Nj = (int)p->st.fac[i];
             R /= Nj;
-            if (!launch_stage_reg(true, src, dst, p->st.w32, M, Nj, S, R, nrows, 1, s))
+            if (!launch_stage_reg<float2>(true, src, dst, p->st.w32, M, Nj, S, R, nrows, 1, s))
                 hipLaunchKernelGGL(k_stage_inv<float2>, dim3(grid_for(nrows * M, bs)), dim3(bs), 0, s, src, dst,
                                    p->st.w32, M, Nj, S, R, nrows);
             FC_HIP(hipGetLastError());
@@ -472,7 +471,7 @@ int staged_inverse_to_dk(const fftconv_plan *p, float2 *spec, float2 *other, int
     for (int i = p->st.nf - 1; i >= 0; --i) {
         const int Nj = (int)p->st.fac[i];
         R /= Nj;
-        if (!launch_stage_reg(true, src, dst, p->st.w32, M, Nj, S, R, nrows, 1, s))
+        if (!launch_stage_reg<float2>(true, src, dst, p->st.w32, M, Nj, S, R, nrows, 1, s))
             hipLaunchKernelGGL(k_stage_inv<float2>, dim3(grid_for(nrows * M, bs)), dim3(bs), 0, s, src, dst, p->st.w32, M,
                                Nj, S, R, nrows);
         FC_HIP(hipGetLastError());
