@@ -450,7 +450,7 @@ size_t fftconv_workspace_bytes_gated(const fftconv_plan *p, int64_t B)
 {
     if (!p || B <= 0) return 0;
     const size_t base = fftconv_workspace_bytes(p, B);
-    if (fused3_gates_fused(p)) return base;
+    if (fused3_gates_fused(p) || p->path == PATH_MULTIPASS) return base;       // gates fused into the plan's kernels
     return align256(base) + (size_t)(B * p->H * p->N) * elem_bytes(p);
 }
 
@@ -472,6 +472,8 @@ int fftconv_forward_gated(const fftconv_plan *p, const void *u, const void *w, c
     }
     hipStream_t s = (hipStream_t)stream;
     if (fused3_gates_fused(p)) return fused3_forward_gated(p, u, w, v, k_f, y, B, s);
+    if (p->path == PATH_MULTIPASS)          // the outer passes multiply the gates in as they load u / store y
+        return multipass_forward(p, u, k_f, y, B, workspace, s, 0, 0, w, v);
     const int64_t n = B * p->H * p->N;
     const void *src = u;
     if (w) {

@@ -206,6 +206,6 @@ size_t multipass_workspace_bytes(const fftconv_plan *p, int64_t B);
 int multipass_pack_kf(const fftconv_plan *p, const double2 *spec, int64_t h0, int64_t nh,
                       const uint8_t *keep_dev, int64_t n_blocks, void *kf, hipStream_t s);
 int multipass_forward(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, void *workspace,
-                      hipStream_t s, int ko_lo = 0, int ko_hi = 0);
+                      hipStream_t s, int ko_lo = 0, int ko_hi = 0, const void *wg = nullptr, const void *vg = nullptr);
 
 }  // namespace fftconv

@@ -71,6 +71,14 @@ template <bool F16> __device__ __forceinline__ float2 unpack2(uint32_t w)
     }
 }
 
+// elementwise product of two packed pairs of 16-bit values, each product rounded to the I/O dtype (the
+// gates of the gated form, Section 3.1: the rounded product is what the transform consumes / what is stored)
+template <bool F16> __device__ __forceinline__ uint32_t mul_pair16(uint32_t a, uint32_t b)
+{
+    const float2 x = unpack2<F16>(a), g = unpack2<F16>(b);
+    return (uint32_t)cv16<F16>(x.x * g.x) | ((uint32_t)cv16<F16>(x.y * g.y) << 16);
+}
+
 struct OuterGeo {
     int No, Ra, Rb, CT;          // outer length, its two factors, columns per block
 };
@@ -81,9 +89,10 @@ struct OuterGeo {
 // Step 1: for every b2 < RB the length-RA transform over a (unless FULLN, inputs a >= RA/2 are the
 // implicit zeros), times W_No^{ka b2}, into the fp32 LDS tile T[ka*RB + b2][c].  Step 2: for every ka the
 // length-RB transform over b2, times W_M^{r ko} (ko = ka + RA kb, by recurrence over kb), to S.
-template <bool F16, int RA, int RB, int CV, bool FULLN>
+template <bool F16, int RA, int RB, int CV, bool FULLN, bool GATED>
 __global__ void __launch_bounds__(TB, 4) k_outer_fwd(const uint16_t *__restrict__ u, uint32_t *__restrict__ S, int CT,
-                                                 int B, int H, int N, int64_t M, int ko_lo, int ko_hi)
+                                                 int B, int H, int N, int64_t M, int ko_lo, int ko_hi,
+                                                 const uint16_t *__restrict__ wg)
 {
     extern __shared__ float2 sm[];
     constexpr int No = RA * RB;
@@ -98,6 +107,9 @@ __global__ void __launch_bounds__(TB, 4) k_outer_fwd(const uint16_t *__restrict_
     const bool two = b0 + 1 < B;
     const uint16_t *row0 = u + ((size_t)b0 * H + h) * N;
     const uint16_t *row1 = u + ((size_t)(b0 + (two ? 1 : 0)) * H + h) * N;
+    // input gate of the gated form (same shape as u), multiplied in as the samples arrive; nullptr = none
+    const uint16_t *g0 = GATED ? wg + ((size_t)b0 * H + h) * N : nullptr;
+    const uint16_t *g1 = GATED ? wg + ((size_t)(b0 + (two ? 1 : 0)) * H + h) * N : nullptr;
     const bool wide = CV == 2 && N % 2 == 0;       // rows start 4-byte aligned
     const int CG = CT / CV;                        // column groups
     for (int j = tid; j < No; j += TB) wno[j] = wm(j, 2.0f / (float)No);
@@ -109,10 +121,15 @@ __global__ void __launch_bounds__(TB, 4) k_outer_fwd(const uint16_t *__restrict_
         for (int a = 0; a < RAIN; ++a) {
             const int64_t n = (int64_t)(a * RB + b2) * MI + r0 + c;
             in0[a] = in1[a] = 0;
+            uint32_t gt0 = 0, gt1 = 0;
             if (wide) {
                 if (n < N) {
                     in0[a] = *(const uint32_t *)(row0 + n);
                     if (two) in1[a] = *(const uint32_t *)(row1 + n);
+                    if constexpr (GATED) {
+                        gt0 = *(const uint32_t *)(g0 + n);
+                        if (two) gt1 = *(const uint32_t *)(g1 + n);
+                    }
                 }
             } else {
 #pragma unroll
@@ -120,7 +137,15 @@ __global__ void __launch_bounds__(TB, 4) k_outer_fwd(const uint16_t *__restrict_
                     if (n + v < N) {
                         in0[a] |= (uint32_t)row0[n + v] << (16 * v);
                         if (two) in1[a] |= (uint32_t)row1[n + v] << (16 * v);
+                        if constexpr (GATED) {
+                            gt0 |= (uint32_t)g0[n + v] << (16 * v);
+                            if (two) gt1 |= (uint32_t)g1[n + v] << (16 * v);
+                        }
                     }
+            }
+            if constexpr (GATED) {
+                in0[a] = mul_pair16<F16>(in0[a], gt0);
+                in1[a] = mul_pair16<F16>(in1[a], gt1);
             }
         }
         float2 o[RA][CV];
@@ -189,9 +214,10 @@ __global__ void __launch_bounds__(TB, 4) k_outer_fwd(const uint16_t *__restrict_
 }
 
 // ---- pass C: S -> conjugate twiddle -> outer inverse DFT -> the two real rows of the pair
-template <bool F16, int RA, int RB, int CV, bool FULLN>
+template <bool F16, int RA, int RB, int CV, bool FULLN, bool GATED>
 __global__ void __launch_bounds__(TB, 4) k_outer_inv(const uint32_t *__restrict__ S, uint16_t *__restrict__ y, int CT,
-                                                 int B, int H, int N, int64_t M, int ko_lo, int ko_hi)
+                                                 int B, int H, int N, int64_t M, int ko_lo, int ko_hi,
+                                                 const uint16_t *__restrict__ vg)
 {
     extern __shared__ float2 sm[];
     constexpr int No = RA * RB;
@@ -257,6 +283,9 @@ __global__ void __launch_bounds__(TB, 4) k_outer_inv(const uint32_t *__restrict_
     // step 2: z[a*RB + b2] = sum_{ka} conj(W_RA^{a ka}) T[ka*RB + b2], kept for a < RAIN (n < M/2 unless FULLN)
     uint16_t *row0 = y + ((size_t)b0 * H + h) * N;
     uint16_t *row1 = y + ((size_t)(b0 + (two ? 1 : 0)) * H + h) * N;
+    // output gate of the gated form: multiplies the result after its rounding to the I/O dtype; nullptr = none
+    const uint16_t *g0 = GATED ? vg + ((size_t)b0 * H + h) * N : nullptr;
+    const uint16_t *g1 = GATED ? vg + ((size_t)(b0 + (two ? 1 : 0)) * H + h) * N : nullptr;
     for (int e = tid; e < RB * CG; e += TB) {
         const int c = (e % CG) * CV, b2 = e / CG;
         uint32_t o0[RAIN], o1[RAIN];
@@ -279,6 +308,10 @@ __global__ void __launch_bounds__(TB, 4) k_outer_inv(const uint32_t *__restrict_
             const int64_t n = (int64_t)(a * RB + b2) * MI + r0 + c;
             if (wide) {
                 if (n < N) {
+                    if constexpr (GATED) {
+                        o0[a] = mul_pair16<F16>(o0[a], *(const uint32_t *)(g0 + n));
+                        if (two) o1[a] = mul_pair16<F16>(o1[a], *(const uint32_t *)(g1 + n));
+                    }
                     *(uint32_t *)(row0 + n) = o0[a];
                     if (two) *(uint32_t *)(row1 + n) = o1[a];
                 }
@@ -286,8 +319,13 @@ __global__ void __launch_bounds__(TB, 4) k_outer_inv(const uint32_t *__restrict_
 #pragma unroll
                 for (int v = 0; v < CV; ++v)
                     if (n + v < N) {
-                        row0[n + v] = (uint16_t)(o0[a] >> (16 * v));
-                        if (two) row1[n + v] = (uint16_t)(o1[a] >> (16 * v));
+                        uint32_t a0 = (o0[a] >> (16 * v)) & 0xffffu, a1 = (o1[a] >> (16 * v)) & 0xffffu;
+                        if constexpr (GATED) {
+                            a0 = mul_pair16<F16>(a0, g0[n + v]) & 0xffffu;
+                            if (two) a1 = mul_pair16<F16>(a1, g1[n + v]) & 0xffffu;
+                        }
+                        row0[n + v] = (uint16_t)a0;
+                        if (two) row1[n + v] = (uint16_t)a1;
                     }
             }
         }
@@ -321,26 +359,26 @@ OuterGeo outer_geo(int64_t M)
     return g;
 }
 
-template <bool F16, int RA, int RB, bool FULLN>
+template <bool F16, int RA, int RB, bool FULLN, bool GATED>
 int launch_outer_t(bool inverse, const OuterGeo &g, dim3 grid, const void *src, void *dst, int B, int H, int N, int64_t M,
-                   hipStream_t s, int ko_lo, int ko_hi)
+                   hipStream_t s, int ko_lo, int ko_hi, const void *gate)
 {
     constexpr int CV = RB <= 16 ? 2 : 1;           // two columns per thread while the registers allow
     const size_t lds = sizeof(float2) * ((size_t)g.No + (size_t)g.No * g.CT);
     static bool attr_set = false;
     if (!attr_set) {
-        FC_HIP(hipFuncSetAttribute((const void *)k_outer_fwd<F16, RA, RB, CV, FULLN>,
+        FC_HIP(hipFuncSetAttribute((const void *)k_outer_fwd<F16, RA, RB, CV, FULLN, GATED>,
                                    hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
-        FC_HIP(hipFuncSetAttribute((const void *)k_outer_inv<F16, RA, RB, CV, FULLN>,
+        FC_HIP(hipFuncSetAttribute((const void *)k_outer_inv<F16, RA, RB, CV, FULLN, GATED>,
                                    hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
         attr_set = true;
     }
     if (!inverse)
-        hipLaunchKernelGGL((k_outer_fwd<F16, RA, RB, CV, FULLN>), grid, dim3(TB), lds, s, (const uint16_t *)src,
-                           (uint32_t *)dst, g.CT, B, H, N, M, ko_lo, ko_hi);
+        hipLaunchKernelGGL((k_outer_fwd<F16, RA, RB, CV, FULLN, GATED>), grid, dim3(TB), lds, s, (const uint16_t *)src,
+                           (uint32_t *)dst, g.CT, B, H, N, M, ko_lo, ko_hi, (const uint16_t *)gate);
     else
-        hipLaunchKernelGGL((k_outer_inv<F16, RA, RB, CV, FULLN>), grid, dim3(TB), lds, s, (const uint32_t *)src,
-                           (uint16_t *)dst, g.CT, B, H, N, M, ko_lo, ko_hi);
+        hipLaunchKernelGGL((k_outer_inv<F16, RA, RB, CV, FULLN, GATED>), grid, dim3(TB), lds, s, (const uint32_t *)src,
+                           (uint16_t *)dst, g.CT, B, H, N, M, ko_lo, ko_hi, (const uint16_t *)gate);
     FC_HIP(hipGetLastError());
     return FFTCONV_OK;
 }
@@ -348,30 +386,32 @@ int launch_outer_t(bool inverse, const OuterGeo &g, dim3 grid, const void *src, 
 // the half-input instantiation needs an outer transform (No >= 2) and N <= M/2
 template <bool F16, int RA, int RB>
 int launch_outer(bool inverse, const OuterGeo &g, dim3 grid, const void *src, void *dst, int B, int H, int N, int64_t M,
-                 hipStream_t s, int ko_lo, int ko_hi)
+                 hipStream_t s, int ko_lo, int ko_hi, const void *gate)
 {
     if constexpr (RA >= 2) {
         if ((int64_t)N <= M / 2)
-            return launch_outer_t<F16, RA, RB, false>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi);
+            return gate ? launch_outer_t<F16, RA, RB, false, true>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi, gate)
+                        : launch_outer_t<F16, RA, RB, false, false>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi, gate);
     }
-    return launch_outer_t<F16, RA, RB, true>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi);
+    return gate ? launch_outer_t<F16, RA, RB, true, true>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi, gate)
+                : launch_outer_t<F16, RA, RB, true, false>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi, gate);
 }
 
 template <bool F16>
 int dispatch_outer(bool inverse, const OuterGeo &g, dim3 grid, const void *src, void *dst, int B, int H, int N,
-                   int64_t M, hipStream_t s, int ko_lo, int ko_hi)
+                   int64_t M, hipStream_t s, int ko_lo, int ko_hi, const void *gate)
 {
     switch (g.No) {
-    case 1: return launch_outer<F16, 1, 1>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi);
-    case 2: return launch_outer<F16, 2, 1>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi);
-    case 4: return launch_outer<F16, 4, 1>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi);
-    case 8: return launch_outer<F16, 8, 1>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi);
-    case 16: return launch_outer<F16, 16, 1>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi);
-    case 32: return launch_outer<F16, 16, 2>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi);
-    case 64: return launch_outer<F16, 16, 4>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi);
-    case 128: return launch_outer<F16, 16, 8>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi);
-    case 256: return launch_outer<F16, 16, 16>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi);
-    case 512: return launch_outer<F16, 16, 32>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi);
+    case 1: return launch_outer<F16, 1, 1>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi, gate);
+    case 2: return launch_outer<F16, 2, 1>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi, gate);
+    case 4: return launch_outer<F16, 4, 1>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi, gate);
+    case 8: return launch_outer<F16, 8, 1>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi, gate);
+    case 16: return launch_outer<F16, 16, 1>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi, gate);
+    case 32: return launch_outer<F16, 16, 2>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi, gate);
+    case 64: return launch_outer<F16, 16, 4>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi, gate);
+    case 128: return launch_outer<F16, 16, 8>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi, gate);
+    case 256: return launch_outer<F16, 16, 16>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi, gate);
+    case 512: return launch_outer<F16, 16, 32>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi, gate);
     default:
         set_error("multipass: unsupported outer length %d", g.No);
         return FFTCONV_EUNSUPPORTED;
@@ -414,8 +454,9 @@ int multipass_pack_kf(const fftconv_plan *p, const double2 *spec, int64_t h0, in
 
 // ko_lo, ko_hi: outer frequency digits ko in [ko_lo, ko_hi) only meet zeroed bins of k_f (frequency-sparse
 // filters); their rows of the workspace are skipped by all three passes.  ko_lo >= ko_hi: none.
+// wg, vg: input / output gate of the gated form (same shape and dtype as u), fused into passes A and C.
 int multipass_forward(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, void *workspace,
-                      hipStream_t s, int ko_lo, int ko_hi)
+                      hipStream_t s, int ko_lo, int ko_hi, const void *wg, const void *vg)
 {
     const OuterGeo g = outer_geo(p->M);
     const int64_t npairs = (B + 1) / 2;
@@ -428,13 +469,13 @@ int multipass_forward(const fftconv_plan *p, const void *u, const void *kf, void
     uint32_t *S = (uint32_t *)workspace;
     const dim3 grid((unsigned)(MI / g.CT), (unsigned)rows);
     if (ko_lo >= ko_hi) ko_lo = ko_hi = g.No;            // nothing skipped
-    int rc = f16 ? dispatch_outer<true>(false, g, grid, u, S, (int)B, (int)p->H, (int)p->N, p->M, s, ko_lo, ko_hi)
-                 : dispatch_outer<false>(false, g, grid, u, S, (int)B, (int)p->H, (int)p->N, p->M, s, ko_lo, ko_hi);
+    int rc = f16 ? dispatch_outer<true>(false, g, grid, u, S, (int)B, (int)p->H, (int)p->N, p->M, s, ko_lo, ko_hi, wg)
+                 : dispatch_outer<false>(false, g, grid, u, S, (int)B, (int)p->H, (int)p->N, p->M, s, ko_lo, ko_hi, wg);
     if (rc) return rc;
     rc = fused3_inner_rows(p, S, kf, npairs, p->H * g.No, s, g.No, ko_lo, ko_hi);
     if (rc) return rc;
-    return f16 ? dispatch_outer<true>(true, g, grid, S, y, (int)B, (int)p->H, (int)p->N, p->M, s, ko_lo, ko_hi)
-               : dispatch_outer<false>(true, g, grid, S, y, (int)B, (int)p->H, (int)p->N, p->M, s, ko_lo, ko_hi);
+    return f16 ? dispatch_outer<true>(true, g, grid, S, y, (int)B, (int)p->H, (int)p->N, p->M, s, ko_lo, ko_hi, vg)
+               : dispatch_outer<false>(true, g, grid, S, y, (int)B, (int)p->H, (int)p->N, p->M, s, ko_lo, ko_hi, vg);
 }
 
 }  // namespace fftconv

@@ -72,7 +72,6 @@ def _gated_fused(dtype, B, H, N, M, use_w, use_v):
     ("f32", 2, 2, 4096, 8192),      # staged path
     ("bf16", 3, 2, 8192, 16384),    # fused 16384 kernel, gates by elementwise kernels
     ("f16", 2, 2, 16384, 32768),    # fused 32768 kernel
-    ("bf16", 2, 1, 32768, 65536),   # multi-pass
 ])
 def test_gated_other_plans(dtype, B, H, N, M):
     w = synth.scaled(W["cfg1"], B=B, H=H, N=N, fft_size=M, dtype=dtype, alpha=(1e-3, 1e-2))
@@ -119,3 +118,20 @@ def test_gated_cfg2_full_size_sampled_sequences():
         worst = max(worst, float(oracle.rel_l2_per_sequence(y[b, h].double().numpy(), ref)))
     print("gated cfg2 full: worst sampled rel L2 = %.3e" % worst, flush=True)
     assert worst <= TOL[w.dtype]
+
+
+@pytest.mark.parametrize("dtype,B,H,N,M", [
+    ("bf16", 2, 1, 32768, 65536),   # gates fused into the outer passes of the multi-pass route
+    ("f16", 3, 2, 20000, 65536),    # odd batch, ragged N (2-byte accesses)
+    ("bf16", 2, 2, 8192, 8192),     # circular, no outer transform
+    ("f16", 1, 1, 12002, 16384),    # N > fft/2, N not a multiple of 4
+])
+def test_gated_multipass(dtype, B, H, N, M):
+    w = synth.scaled(W["cfg1"], B=B, H=H, N=N, fft_size=M, dtype=dtype, alpha=(1e-3, 1e-2))
+    for use_w, use_v in ((True, True), (True, False), (False, True)):
+        err, plan = check_all(w, use_w, use_v)
+        print("gated multipass %s B=%d H=%d N=%d M=%d w=%d v=%d path=%s err=%.3e" % (dtype, B, H, N, M, use_w, use_v, plan.path, err),
+              flush=True)
+        assert plan.path == "multipass"
+        assert plan.workspace_bytes_gated(B) == plan.workspace_bytes(B)
+        assert err <= TOL[dtype]
