@@ -1012,7 +1012,7 @@ int fused3_pack_kf(const fftconv_plan *p, const double2 *spec, int64_t h0, int64
     return FFTCONV_OK;
 }
 
-bool fused3_gates_fused(const fftconv_plan *p) { return p->path == PATH_FUSED3 && p->M <= 8192; }
+bool fused3_gates_fused(const fftconv_plan *p) { return p->path == PATH_FUSED3; }
 
 int fused3_forward_gated(const fftconv_plan *p, const void *u, const void *w, const void *v, const void *kf, void *y,
                          int64_t B, hipStream_t s)
@@ -1021,6 +1021,7 @@ int fused3_forward_gated(const fftconv_plan *p, const void *u, const void *w, co
         set_error("fftconv_forward_gated: u, w, v and y must be 16-byte aligned for this plan");
         return FFTCONV_EINVAL;
     }
+    if (p->M > 8192) return fused3_big_forward_gated(p, u, w, v, kf, y, B, s);
     return fused3_ws_launch(p, p->f3.consts, u, kf, y, B, 1, 0, s, w, v);
 }
 

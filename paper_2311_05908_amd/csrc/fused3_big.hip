@@ -125,10 +125,14 @@ __host__ __device__ inline int big_sigma_inv(int d)
 
 // FULL: B even and N == fft_size / 2, every access of a work item is in range.
 // HALF3: k_f is zero wherever k3 is in tile 1 of the order above.
-template <typename TT, bool FULL, int N2, bool HALF3>
-__global__ void __launch_bounds__(NT, N2 == 16 ? 4 : 2) k_fused3_big(const uint16_t *__restrict__ u, uint16_t *__restrict__ y,
+// GATED (gated form y = v . ((u . w) * k), Section 3.1 / 4.1): wg multiplies u as its chunks go into the
+// staging area, vg multiplies y as its chunks leave it (either may be null); the gates are fetched with the
+// next pair's input, right after phase B.  One workgroup per compute unit then (the extra chunks need registers).
+template <typename TT, bool FULL, int N2, bool HALF3, bool GATED = false>
+__global__ void __launch_bounds__(NT, (N2 == 16 && !GATED) ? 4 : 2) k_fused3_big(const uint16_t *__restrict__ u, uint16_t *__restrict__ y,
                                                   const void *__restrict__ kf, const void *__restrict__ consts,
-                                                  uint32_t kf_bytes, int B, int H, int N, int probe)
+                                                  uint32_t kf_bytes, int B, int H, int N, int probe,
+                                                  const uint16_t *__restrict__ wg, const uint16_t *__restrict__ vg)
 {
     using CW = typename TT::CW;
     using BG = BigGeo<N2>;
@@ -166,6 +170,7 @@ __global__ void __launch_bounds__(NT, N2 == 16 ? 4 : 2) k_fused3_big(const uint1
     uint4 tabA[PD][R2][R2][2], tabB[PD][R2][R2][2];      // stage-2 / inverse stage-2 matrices
     CW twaR[PD][R2][2][4], twbR[PD][R2][2][4], kfR[PD][R2][2][4];
     uint4 pre[NCH];                               // next pair's input, 16-byte chunks in memory order
+    uint4 prew[GATED ? NCH : 1], prev[GATED ? NCH : 1];   // its input gate; the output gate of the current pair
     uint2 x1r[2][R2][4];                          // the same in operand order: [row of the pair][n2 tile][r], 4 n3 planes each
 
     // The tables are loop invariant but must be re-read for every work item (they do not fit in
@@ -275,12 +280,33 @@ __global__ void __launch_bounds__(NT, N2 == 16 ? 4 : 2) k_fused3_big(const uint1
             const int n = (tid + NT * (j % (NCH / 2))) * 8;
             const int b = 2 * pair + s;
             const uint16_t *row = u + ((size_t)(FULL ? b : min(b, B - 1)) * H + h) * N;
+            const bool ok = FULL || (b < B && n < N);
             if constexpr (FULL) {
                 pre[j] = *(const uint4 *)(row + n);
             } else {
                 uint4 v = make_uint4(0, 0, 0, 0);
-                if (b < B && n < N) v = *(const uint4 *)(row + n);
+                if (ok) v = *(const uint4 *)(row + n);
                 pre[j] = v;
+            }
+            if constexpr (GATED) {
+                uint4 g = make_uint4(0, 0, 0, 0);
+                if (wg && ok) g = *(const uint4 *)(wg + (row - u) + n);
+                prew[j] = g;
+            }
+        }
+    };
+    // output gate of pair t (the pair whose y is stored at the end of this iteration)
+    auto issue_gate_v = [&](int t) {
+        if constexpr (GATED) {
+            const int h = t / npairs, pair = t - h * npairs;
+#pragma unroll
+            for (int j = 0; j < NCH; ++j) {
+                const int s = j / (NCH / 2);
+                const int n = (tid + NT * (j % (NCH / 2))) * 8;
+                const int b = 2 * pair + s;
+                uint4 g = make_uint4(0, 0, 0, 0);
+                if (vg && (FULL || (b < B && n < N))) g = *(const uint4 *)(vg + ((size_t)b * H + h) * N + n);
+                prev[j] = g;
             }
         }
     };
@@ -298,8 +324,12 @@ __global__ void __launch_bounds__(NT, N2 == 16 ? 4 : 2) k_fused3_big(const uint1
 #pragma unroll
         for (int j = 0; j < NCH; ++j) {
             uint2 *dst = (uint2 *)(US + chunk_ofs(j));
-            dst[0] = make_uint2(pre[j].x, pre[j].y);
-            dst[1] = make_uint2(pre[j].z, pre[j].w);
+            uint4 v = pre[j];
+            if constexpr (GATED) {
+                if (wg) v = TT::mul8(v, prew[j]);
+            }
+            dst[0] = make_uint2(v.x, v.y);
+            dst[1] = make_uint2(v.z, v.w);
         }
     };
     auto read_x1 = [&]() {                                    // US -> operand order
@@ -427,7 +457,11 @@ __global__ void __launch_bounds__(NT, N2 == 16 ? 4 : 2) k_fused3_big(const uint1
             const int n = (tid + NT * (j % (NCH / 2))) * 8;
             const int b = 2 * pair + s;
             uint16_t *row = y + ((size_t)(FULL ? b : min(b, B - 1)) * H + h) * N;
-            if (FULL || (b < B && n < N)) *(uint4 *)(row + n) = yc[j];
+            uint4 v = yc[j];
+            if constexpr (GATED) {
+                if (vg) v = TT::mul8(v, prev[j]);
+            }
+            if (FULL || (b < B && n < N)) *(uint4 *)(row + n) = v;
         }
     };
 
@@ -550,6 +584,7 @@ __global__ void __launch_bounds__(NT, N2 == 16 ? 4 : 2) k_fused3_big(const uint1
             load_twa(i);
         }
         issue_pre(tn);
+        issue_gate_v(t);
         SCHED_FENCE();
         lds_barrier();
         BSTAMP(2);
@@ -665,11 +700,12 @@ int big_probe()
 #endif
 }
 
-template <typename TT, bool FULL, int N2, bool HALF3>
-int launch_big(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, hipStream_t s)
+template <typename TT, bool FULL, int N2, bool HALF3, bool GATED = false>
+int launch_big(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, hipStream_t s,
+               const void *wg = nullptr, const void *vg = nullptr)
 {
     using BG = BigGeo<N2>;
-    auto kern = k_fused3_big<TT, FULL, N2, HALF3>;
+    auto kern = k_fused3_big<TT, FULL, N2, HALF3, GATED>;
     static bool attr_set = false;
     if (!attr_set) {
         FC_HIP(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)BG::LDS_BYTES));
@@ -693,11 +729,12 @@ int launch_big(const fftconv_plan *p, const void *u, const void *kf, void *y, in
     }
     // persistent workgroups, as many as are resident at once (two per compute unit for the smaller
     // size: 80 KB of LDS and 128 registers each), a multiple of 8 (see the kernel's work split)
-    const int64_t resident = (int64_t)p->f3.num_cu * (N2 == 16 ? 2 : 1);
+    const int64_t resident = (int64_t)p->f3.num_cu * ((N2 == 16 && !GATED) ? 2 : 1);
     int grid = (int)(T < resident ? T : resident);
     if (grid >= 8) grid -= grid % 8;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NT), BG::LDS_BYTES, s, (const uint16_t *)u, (uint16_t *)y,
-                       kf, (const void *)p->f3.consts, (uint32_t)kf_bytes, (int)B, (int)p->H, (int)p->N, big_probe());
+                       kf, (const void *)p->f3.consts, (uint32_t)kf_bytes, (int)B, (int)p->H, (int)p->N, big_probe(),
+                       (const uint16_t *)wg, (const uint16_t *)vg);
     FC_HIP(hipGetLastError());
     return FFTCONV_OK;
 }
@@ -832,6 +869,31 @@ int fused3_big_forward(const fftconv_plan *p, const void *u, const void *kf, voi
     for (int d = 0; d < 32; ++d)
         if (((live_k3 >> d) & 1u) && big_sigma_inv(d) >= 16) half3 = false;
     return p->M == 32768 ? big_forward_t<32>(p, u, kf, y, B, half3, s) : big_forward_t<16>(p, u, kf, y, B, half3, s);
+}
+
+// Gated form: wg / vg (same shape and dtype as u; either may be null) are applied inside the kernel.
+int fused3_big_forward_gated(const fftconv_plan *p, const void *u, const void *wg, const void *vg, const void *kf, void *y,
+                             int64_t B, hipStream_t s)
+{
+    if (((uintptr_t)u | (uintptr_t)y | (uintptr_t)wg | (uintptr_t)vg) & 15) {
+        set_error("fftconv_forward_gated: u, w, v and y must be 16-byte aligned for this plan");
+        return FFTCONV_EINVAL;
+    }
+    const bool f16 = p->dtype == FFTCONV_F16;
+    if (p->M == 32768) {
+        const bool full = (B % 2 == 0) && p->N == BigGeo<32>::M / 2;
+        if (f16)
+            return full ? launch_big<H16, true, 32, false, true>(p, u, kf, y, B, s, wg, vg)
+                        : launch_big<H16, false, 32, false, true>(p, u, kf, y, B, s, wg, vg);
+        return full ? launch_big<B16, true, 32, false, true>(p, u, kf, y, B, s, wg, vg)
+                    : launch_big<B16, false, 32, false, true>(p, u, kf, y, B, s, wg, vg);
+    }
+    const bool full = (B % 2 == 0) && p->N == BigGeo<16>::M / 2;
+    if (f16)
+        return full ? launch_big<H16, true, 16, false, true>(p, u, kf, y, B, s, wg, vg)
+                    : launch_big<H16, false, 16, false, true>(p, u, kf, y, B, s, wg, vg);
+    return full ? launch_big<B16, true, 16, false, true>(p, u, kf, y, B, s, wg, vg)
+                : launch_big<B16, false, 16, false, true>(p, u, kf, y, B, s, wg, vg);
 }
 
 }  // namespace f3

@@ -340,6 +340,8 @@ int fused3_big_pack_kf(const fftconv_plan *p, const double2 *spec, int64_t h0, i
                        int64_t n_blocks, void *kf, hipStream_t s);
 int fused3_big_forward(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, uint32_t live_k3,
                        hipStream_t s);
+int fused3_big_forward_gated(const fftconv_plan *p, const void *u, const void *wg, const void *vg, const void *kf, void *y,
+                             int64_t B, hipStream_t s);
 
 }  // namespace f3
 }  // namespace fftconv

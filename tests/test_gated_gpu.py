@@ -70,8 +70,6 @@ def _gated_fused(dtype, B, H, N, M, use_w, use_v):
     ("f32", 3, 2, 300, 1024),
     ("bf16", 2, 2, 204, 512),       # 16-bit I/O with N not a multiple of 8 stays on that kernel
     ("f32", 2, 2, 4096, 8192),      # staged path
-    ("bf16", 3, 2, 8192, 16384),    # fused 16384 kernel, gates by elementwise kernels
-    ("f16", 2, 2, 16384, 32768),    # fused 32768 kernel
 ])
 def test_gated_other_plans(dtype, B, H, N, M):
     w = synth.scaled(W["cfg1"], B=B, H=H, N=N, fft_size=M, dtype=dtype, alpha=(1e-3, 1e-2))
@@ -118,6 +116,24 @@ def test_gated_cfg2_full_size_sampled_sequences():
         worst = max(worst, float(oracle.rel_l2_per_sequence(y[b, h].double().numpy(), ref)))
     print("gated cfg2 full: worst sampled rel L2 = %.3e" % worst, flush=True)
     assert worst <= TOL[w.dtype]
+
+
+@pytest.mark.parametrize("dtype,B,H,N,M", [
+    ("bf16", 3, 2, 8192, 16384),    # fused 16384 kernel, odd batch
+    ("f16", 4, 3, 8192, 16384),
+    ("bf16", 2, 2, 4000, 16384),    # ragged N
+    ("f16", 2, 2, 16384, 32768),    # fused 32768 kernel
+    ("bf16", 3, 1, 16384, 32768),
+    ("f16", 2, 1, 10000, 32768),
+])
+def test_gated_fused_16384_32768(dtype, B, H, N, M):
+    w = synth.scaled(W["cfg1"], B=B, H=H, N=N, fft_size=M, dtype=dtype, alpha=(1e-3, 1e-2))
+    for use_w, use_v in ((True, True), (True, False), (False, True)):
+        err, plan = check_all(w, use_w, use_v)
+        print("gated fused %d %s B=%d H=%d N=%d w=%d v=%d path=%s err=%.3e" % (M, dtype, B, H, N, use_w, use_v, plan.path, err),
+              flush=True)
+        assert plan.path == "fused3" and plan.workspace_bytes_gated(B) == 0
+        assert err <= TOL[dtype]
 
 
 @pytest.mark.parametrize("dtype,B,H,N,M", [
