@@ -132,6 +132,8 @@ int fused3_forward_sparse(const fftconv_plan *p, const void *u, const void *kf, 
 uint32_t fused3_live_k3(const fftconv_plan *p, const uint8_t *block_keep, int64_t n_blocks);
 // partial convolution by overlapping short segments; returns FFTCONV_EUNSUPPORTED if this plan / Nk cannot
 bool fused3_short_ok(const fftconv_plan *p, int64_t Nk);
+int fused3_init_short(fftconv_plan *p);
+size_t fused3_short_kf_bytes(const fftconv_plan *p);
 int fused3_pack_kf_short(const fftconv_plan *p, const double2 *spec, int64_t h0, int64_t nh, void *kf, hipStream_t s);
 int fused3_forward_short(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, int64_t Nk,
                          hipStream_t s);

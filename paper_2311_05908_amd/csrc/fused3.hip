@@ -831,12 +831,15 @@ int fused3_init(fftconv_plan *p)
         p->f3.N3 = 32;
         int rc = fused3_big_init(p);
         if (rc) return rc;
-        return build_tables<16, 16>(p, &p->f3.consts_short);     // for partial convolutions, see fused3_forward_short
+        return fused3_init_short(p);                             // for partial convolutions, see fused3_forward_short
     }
-    case 32768:
+    case 32768: {
         p->f3.N2 = 32;
         p->f3.N3 = 32;
-        return fused3_big_init(p);
+        int rc = fused3_big_init(p);
+        if (rc) return rc;
+        return fused3_init_short(p);
+    }
     default:
         set_error("fused3: no kernel for fft_size=%lld", (long long)p->M);
         return FFTCONV_EUNSUPPORTED;
@@ -937,11 +940,35 @@ void fused3_destroy(fftconv_plan *p)
 constexpr int64_t SHORT_M = 8192;          // transform length of the segments of a partial convolution
 constexpr int64_t SHORT_MAX_P = 2048;      // most history a segment may carry (at least half of it is output)
 
+// Plans for fft >= 16384 (the single-kernel ones and the multi-pass route) also carry the 8192-point tables:
+// a short (partial) filter runs as overlapping 8192-point segments, and k_f then holds a second,
+// 8192-point spectrum (8 bytes per bin) after the dense one.
+int fused3_init_short(fftconv_plan *p)
+{
+    if (p->M < 2 * SHORT_M || p->N > p->M / 2 || p->N % 8 != 0) return FFTCONV_OK;      // no segmented route
+    if (p->f3.num_cu == 0) {
+        hipDeviceProp_t prop;
+        FC_HIP(hipGetDeviceProperties(&prop, p->device));
+        p->f3.num_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    }
+    return build_tables<16, 16>(p, &p->f3.consts_short);
+}
+
+size_t fused3_short_kf_bytes(const fftconv_plan *p)
+{
+    return p->f3.consts_short ? (size_t)(p->H * SHORT_M) * sizeof(float2) : 0;
+}
+
+// bytes of the plan's dense spectrum, = offset of the short one
+static size_t dense_kf_bytes(const fftconv_plan *p)
+{
+    if (p->path == PATH_MULTIPASS) return multipass_kf_bytes(p) - fused3_short_kf_bytes(p);
+    return fused3_big_kf_bytes(p);
+}
+
 size_t fused3_kf_bytes(const fftconv_plan *p)
 {
-    if (p->M == 32768) return fused3_big_kf_bytes(p);
-    // fft 16384 plans: dense spectrum, then the 8192-point spectrum of a short filter (8 bytes per bin)
-    if (p->M == 16384) return fused3_big_kf_bytes(p) + (size_t)(p->H * SHORT_M) * sizeof(float2);
+    if (p->M >= 16384) return fused3_big_kf_bytes(p) + fused3_short_kf_bytes(p);
     return (size_t)(p->H * 8192) * sizeof(float2);             // fft <= 8192: the 8192 slots of the wave-specialised kernel
 }
 
@@ -949,21 +976,21 @@ static int64_t history_of(int64_t Nk) { return (Nk - 1 + 7) / 8 * 8; }
 
 bool fused3_short_ok(const fftconv_plan *p, int64_t Nk)
 {
-    return p->path == PATH_FUSED3 && p->f3.consts_short != nullptr && Nk >= 1 && history_of(Nk) <= SHORT_MAX_P;
+    return p->f3.consts_short != nullptr && Nk >= 1 && history_of(Nk) <= SHORT_MAX_P;
 }
 
 int fused3_pack_kf_short(const fftconv_plan *p, const double2 *spec, int64_t h0, int64_t nh, void *kf, hipStream_t s)
 {
     const int bs = 256;
     const unsigned grid = (unsigned)((nh * SHORT_M + bs - 1) / bs);
-    float2 *dst = (float2 *)((char *)kf + fused3_big_kf_bytes(p));
+    float2 *dst = (float2 *)((char *)kf + dense_kf_bytes(p));
     hipLaunchKernelGGL((k_pack_fused3<16, 16>), dim3(grid), dim3(bs), 0, s, spec, dst, staged_factors_for(SHORT_M), h0,
                        nh, (const uint8_t *)nullptr, (int64_t)1, p->dtype == FFTCONV_F16 ? 2 : 1, 1);
     FC_HIP(hipGetLastError());
     return FFTCONV_OK;
 }
 
-// Partial convolution (Section 3.3) of a fft-16384 plan: the filter covers Nk <= 2049 taps, so
+// Partial convolution (Section 3.3) of a plan for fft >= 16384: the filter covers Nk <= 2049 taps, so
 // every output depends on at most P = Nk - 1 (rounded up to 8) earlier inputs and the row can be cut
 // into overlapping windows that each fit the 8192-point kernel (overlap-save).  The outermost
 // factor of the decomposition is skipped altogether: 8192-point transforms instead of 16384-point
@@ -978,7 +1005,7 @@ int fused3_forward_short(const fftconv_plan *p, const void *u, const void *kf, v
     const int P = (int)history_of(Nk);
     const int Lo = (int)(SHORT_M / 2) - P;
     const int nseg = p->N <= SHORT_M / 2 ? 1 : 1 + (int)((p->N - SHORT_M / 2 + Lo - 1) / Lo);
-    const float2 *kf_short = (const float2 *)((const char *)kf + fused3_big_kf_bytes(p));
+    const float2 *kf_short = (const float2 *)((const char *)kf + dense_kf_bytes(p));
     return fused3_ws_launch(p, p->f3.consts_short, u, kf_short, y, B, nseg, P, s);
 }
 

@@ -427,9 +427,17 @@ bool multipass_supported(int64_t N, int64_t M, int dtype)
     return N >= 1 && N <= M;
 }
 
-int multipass_init(fftconv_plan *p) { return fused3_init_inner(p); }
+int multipass_init(fftconv_plan *p)
+{
+    int rc = fused3_init_inner(p);
+    if (rc) return rc;
+    return fused3_init_short(p);      // short filters run as overlapping 8192-point segments (fused3.hip)
+}
 
-size_t multipass_kf_bytes(const fftconv_plan *p) { return (size_t)(p->H * p->M) * sizeof(uint32_t); }
+size_t multipass_kf_bytes(const fftconv_plan *p)
+{
+    return (size_t)(p->H * p->M) * sizeof(uint32_t) + fused3_short_kf_bytes(p);
+}
 
 size_t multipass_workspace_bytes(const fftconv_plan *p, int64_t B)
 {

@@ -199,6 +199,24 @@ def test_cfg5_variants_reduced_batch():
             assert err <= TOL[w.dtype]
 
 
+@pytest.mark.parametrize("dtype,B,H,N,M,Nk", [
+    ("f16", 3, 2, 16384, 32768, 1024),     # single-kernel 32768 plan: 5 segments per row
+    ("bf16", 2, 2, 16384, 32768, 2049),    # the longest filter the segments take (2048 samples of history)
+    ("bf16", 2, 1, 12000, 32768, 100),     # ragged N, short filter
+    ("bf16", 3, 1, 32768, 65536, 1024),    # multi-pass plan, odd batch
+    ("f16", 1, 2, 100000, 262144, 777),    # long row, B = 1
+])
+def test_partial_convolution_as_segments_on_long_plans(dtype, B, H, N, M, Nk):
+    """Partial convolutions (Section 3.3) of plans for fft >= 16384: overlapping 8192-point segments on the
+    wave-specialised kernel, against the oracle on the zeroed filter; the dense route on the same k_f as well."""
+    w = synth.scaled(W["cfg5a"], B=B, H=H, N=N, fft_size=M, dtype=dtype, Nk=Nk)
+    for variant in ("dense", "skip"):
+        err, plan = check_all_sequences(w, variant=variant)
+        print("partial %s B=%d H=%d N=%d M=%d Nk=%d %s path=%s err=%.3e" % (dtype, B, H, N, M, Nk, variant, plan.path, err),
+              flush=True)
+        assert err <= TOL[dtype]
+
+
 # ---------------------------------------------------------------- multi-pass path (Algorithm 4)
 
 @pytest.mark.parametrize("dtype", ["bf16", "f16"])
