@@ -32,9 +32,14 @@ constexpr int PT = 256;                       // threads per role
 constexpr int PCH = G::M / 8 / PT;            // 16-byte input chunks per outer-role thread and input (4)
 
 // FULL: B even and N == fft_size/2: every load is in range and unconditional.
+// groups > 1: plans for fft 256 .. 4096, whose tables put `groups` transforms of length 8192 / groups into one
+// input (fused3.hip, build_tables): positions [g * half, (g + 1) * half) of an input's 4096-sample slot,
+// half = 2^lg_half = fft_size / 2, hold rows 2 (pair * groups + g), + 1.  The accumulator then holds one
+// spectrum per group (slots k1 = g * (32 / groups) + k1'), which the unpacking step adds up.
 template <typename TT, bool FULL>
 __global__ void __launch_bounds__(NT) k_fused3_dk(const uint16_t *__restrict__ u, const uint16_t *__restrict__ dy,
-                                                 float2 *__restrict__ dkf, Consts cs, int B, int H, int N)
+                                                 float2 *__restrict__ dkf, Consts cs, int B, int H, int N, int groups,
+                                                 int lg_half)
 {
     extern __shared__ uint32_t smem[];
     uint32_t *const XBb = smem;                                   // [2][XBW]
@@ -44,7 +49,7 @@ __global__ void __launch_bounds__(NT) k_fused3_dk(const uint16_t *__restrict__ u
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     // channels of this workgroup: h = blockIdx.x + j * gridDim.x; its input stream: index
     // s = (j * npairs + pair) * 2 + which, which = 0 for the u rows of the pair, 1 for the dy rows
-    const int npairs = (B + 1) / 2;
+    const int npairs = (B + 2 * groups - 1) / (2 * groups);
     const int nch = (H - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x;
     const int S = nch * npairs * 2;
     if (S <= 0) return;
@@ -79,8 +84,9 @@ __global__ void __launch_bounds__(NT) k_fused3_dk(const uint16_t *__restrict__ u
 #pragma unroll
             for (int c = 0; c < PCH; ++c) {
                 const int row = c / 2;
-                const int n = (ptid + PT * (c % 2)) * 8;
-                const int b = 2 * pair + row;
+                const int np = (ptid + PT * (c % 2)) * 8;             // position in the input's slot
+                const int n = np & ((1 << lg_half) - 1);             // ... in its row
+                const int b = 2 * (pair * groups + (np >> lg_half)) + row;
                 if constexpr (FULL) {
                     pre[c] = *(const uint4 *)(src + ((size_t)b * H + h) * N + n);
                 } else {
@@ -219,17 +225,29 @@ __global__ void __launch_bounds__(NT) k_fused3_dk(const uint16_t *__restrict__ u
 
 // dk_f from the kernel's order (slot of frequency f as in the fused k_f layout) to the position order of
 // the generic inverse stages.
-__global__ void k_unpack_dkf(const float2 *dkf, float2 *spec, FacList fl, int64_t nh)
+// groups > 1: bin f = k1' + N1s (k2 + 16 k3) of the length-Ms transform is the sum over the groups of the slots
+// k1 = g N1s + k1'.
+__global__ void k_unpack_dkf(const float2 *dkf, float2 *spec, FacList fl, int64_t nh, int groups)
 {
+    const int64_t Ms = G::M / groups;
+    const int N1s = N1 / groups;
     const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= nh * G::M) return;
-    const int64_t h = idx / G::M, f = idx % G::M;
-    spec[h * G::M + freq_to_pos(f, fl, G::M)] = dkf[h * G::M + fused3_kf_slot_8192(f)];
+    if (idx >= nh * Ms) return;
+    const int64_t h = idx / Ms, f = idx % Ms;
+    const int k1s = (int)(f % N1s);
+    const int64_t rest = f / N1s;                            // k2 + 16 k3
+    float2 acc = make_float2(0.f, 0.f);
+    for (int g = 0; g < groups; ++g) {
+        const float2 v = dkf[h * G::M + fused3_kf_slot_8192((int64_t)(g * N1s + k1s) + (int64_t)N1 * rest)];
+        acc.x += v.x;
+        acc.y += v.y;
+    }
+    spec[h * Ms + freq_to_pos(f, fl, Ms)] = acc;
 }
 
 }  // namespace
 
-bool fused3_dk_supported(const fftconv_plan *p) { return p->path == PATH_FUSED3 && p->M == G::M; }
+bool fused3_dk_supported(const fftconv_plan *p) { return p->path == PATH_FUSED3 && p->M <= G::M; }
 
 // dkf: H * 8192 float2 in the kernel's order.
 int fused3_dk_accumulate(const fftconv_plan *p, const void *u, const void *dy, void *dkf, int64_t B, hipStream_t s)
@@ -238,15 +256,18 @@ int fused3_dk_accumulate(const fftconv_plan *p, const void *u, const void *dy, v
         set_error("fftconv_backward_filter: u and dy must be 16-byte aligned for this plan");
         return FFTCONV_EINVAL;
     }
-    const int64_t npairs = (B + 1) / 2;
+    const int groups = (int)(G::M / p->M);
+    int lg_half = 0;
+    while ((G::M / 2 / groups) >> (lg_half + 1)) ++lg_half;
+    const int64_t npairs = (B + 2 * groups - 1) / (2 * groups);
     if (p->H * npairs >= ((int64_t)1 << 29)) {
         set_error("fftconv_backward_filter: H * ceil(B/2) = %lld exceeds the fused kernel's limit",
                   (long long)(p->H * npairs));
         return FFTCONV_EUNSUPPORTED;
     }
-    const bool full = (B % 2 == 0) && p->N == G::M / 2;
+    const bool full = (B % (2 * groups) == 0) && p->N == G::M / 2 / groups;
     const bool f16 = p->dtype == FFTCONV_F16;
-    void (*kern)(const uint16_t *, const uint16_t *, float2 *, Consts, int, int, int) =
+    void (*kern)(const uint16_t *, const uint16_t *, float2 *, Consts, int, int, int, int, int) =
         f16 ? (full ? k_fused3_dk<F16, true> : k_fused3_dk<F16, false>)
             : (full ? k_fused3_dk<BF16, true> : k_fused3_dk<BF16, false>);
     static bool attr_set[4] = {false, false, false, false};
@@ -257,7 +278,7 @@ int fused3_dk_accumulate(const fftconv_plan *p, const void *u, const void *dy, v
     }
     const int grid = (int)(p->H < p->f3.num_cu ? p->H : p->f3.num_cu);
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NT), DK_LDS_BYTES, s, (const uint16_t *)u, (const uint16_t *)dy,
-                       (float2 *)dkf, consts_at<16, 16>(p->f3.consts), (int)B, (int)p->H, (int)p->N);
+                       (float2 *)dkf, consts_at<16, 16>(p->f3.consts), (int)B, (int)p->H, (int)p->N, groups, lg_half);
     FC_HIP(hipGetLastError());
     return FFTCONV_OK;
 }
@@ -265,9 +286,9 @@ int fused3_dk_accumulate(const fftconv_plan *p, const void *u, const void *dy, v
 int fused3_dk_unpack(const fftconv_plan *p, const void *dkf, void *spec, int64_t h0, int64_t nh, hipStream_t s)
 {
     const int bs = 256;
-    const unsigned grid = (unsigned)((nh * G::M + bs - 1) / bs);
+    const unsigned grid = (unsigned)((nh * p->M + bs - 1) / bs);
     hipLaunchKernelGGL(k_unpack_dkf, dim3(grid), dim3(bs), 0, s, (const float2 *)dkf + h0 * G::M, (float2 *)spec,
-                       staged_fac_list(p), nh);
+                       staged_fac_list(p), nh, (int)(G::M / p->M));
     FC_HIP(hipGetLastError());
     return FFTCONV_OK;
 }
