@@ -94,7 +94,9 @@ int fftconv_forward(const fftconv_plan *plan, const void *u, const void *k_f, vo
 /* Partial convolution (Section 3.3): the filter is zero for taps t >= Nk.
  * k_f must come from fftconv_filter_fft(plan, k, Nk, ...) with the same Nk.
  * Same result as fftconv_forward on that k_f; the plan may skip the parts of
- * the decomposition that a short filter leaves unused. */
+ * the decomposition that a short filter leaves unused: plans with 16-bit I/O, causal shapes (N <= fft_size / 2,
+ * N a multiple of 8) and fft_size >= 16384 run filters of Nk <= 2049 taps as overlapping 8192-point segments
+ * (the outer factors of the decomposition are never executed). */
 int fftconv_forward_partial(const fftconv_plan *plan, const void *u, const void *k_f, void *y,
                             int64_t B, int64_t H, int64_t N, int64_t Nk, void *workspace, void *stream);
 
@@ -151,9 +153,10 @@ size_t fftconv_workspace_bytes_gated(const fftconv_plan *plan, int64_t B);
  *   side; both NULL is fftconv_forward).  v must not alias y.
  * Arithmetic: the product u . w is rounded to the I/O dtype (nearest even) before the transform
  * (it is what the matrix cores consume); the output gate multiplies the convolution result after
- * it has been rounded to the I/O dtype, and the product is rounded again.  Plans that run the fused
- * 8192-point kernel apply both gates inside it (u, w, v each read once, y written once); other
- * plans run one elementwise kernel per gate around fftconv_forward.
+ * it has been rounded to the I/O dtype, and the product is rounded again.  Plans whose path
+ * (fftconv_plan_path) is "fused3" or "multipass" apply both gates inside their kernels (u, w, v each read
+ * once, y written once, no extra workspace); "small" and "staged" plans run one elementwise kernel per
+ * gate around fftconv_forward.
  * workspace: at least fftconv_workspace_bytes_gated(plan, B) bytes, may be NULL when that is 0. */
 int fftconv_forward_gated(const fftconv_plan *plan, const void *u, const void *w, const void *v, const void *k_f,
                           void *y, int64_t B, int64_t H, int64_t N, void *workspace, void *stream);
