@@ -338,6 +338,8 @@ size_t fftconv_workspace_bytes_backward_filter(const fftconv_plan *p, int64_t B)
     if (f3::fused3_dk_supported(p))        // accumulated spectra of every channel (8192 slots each, whatever the plan's
                                            // fft_size) + one ping-pong pair of a chunk of them
         return (size_t)(p->H * 8192 + 2 * staged_backward_chunk(p) * p->M) * sizeof(float2);
+    if (f3::fused3_big_dk_supported(p))
+        return (size_t)((p->H + 2 * staged_backward_chunk(p)) * p->M) * sizeof(float2);
     return staged_backward_filter_bytes(p);
 }
 
@@ -368,6 +370,18 @@ int fftconv_backward_filter(const fftconv_plan *p, const void *u, const void *dy
         for (int64_t h0 = 0; !rc && h0 < p->H; h0 += chunk) {
             const int64_t nh = p->H - h0 < chunk ? p->H - h0 : chunk;
             rc = f3::fused3_dk_unpack(p, dkf, a, h0, nh, s);
+            if (!rc) rc = staged_inverse_to_dk(p, a, b, nh, dk + h0 * Nk, Nk, s);
+        }
+        return rc;
+    }
+    if (B > 0 && f3::fused3_big_dk_supported(p)) {
+        float2 *dkf = (float2 *)workspace;
+        const int64_t chunk = staged_backward_chunk(p);
+        float2 *a = dkf + p->H * p->M, *b = a + chunk * p->M;
+        rc = f3::fused3_big_dk_accumulate(p, u, dy, dkf, B, s);
+        for (int64_t h0 = 0; !rc && h0 < p->H; h0 += chunk) {
+            const int64_t nh = p->H - h0 < chunk ? p->H - h0 : chunk;
+            rc = f3::fused3_big_dk_unpack(p, dkf, a, h0, nh, s);
             if (!rc) rc = staged_inverse_to_dk(p, a, b, nh, dk + h0 * Nk, Nk, s);
         }
         return rc;

@@ -623,6 +623,231 @@ __global__ void __launch_bounds__(NT, (N2 == 16 && !GATED) ? 4 : 2) k_fused3_big
     BSPAN(1);
 }
 
+// ---- Filter gradient for fft 16384 (Section 3.1 "Kernel Fusion and Recomputation"; see fused3_dk.hip for the
+// arithmetic: dk_f[h] = sum over the pairs of conj(FFT(u pair)) . FFT(dy pair), cross terms of the pair packing
+// end up in the dropped imaginary part of the inverse transform).  The forward half of the kernel above (staging,
+// phase A, stage 3 of phase B; same tables and layouts, N2 = 16) runs on the stream u-pair, dy-pair, u-pair, ...
+// of the channels a workgroup owns: a u input leaves its spectrum in registers (fp32), the dy input that
+// follows multiplies it in and adds to the channel's accumulator (fp32, 64 registers), which is written out in
+// the kernel's k_f order after the channel's last pair.  One workgroup per compute unit.
+template <typename TT, bool FULL>
+__global__ void __launch_bounds__(NT, 2) k_fused3_big_dk(const uint16_t *__restrict__ u, const uint16_t *__restrict__ dy,
+                                                         float2 *__restrict__ dkf, const void *__restrict__ consts, int B,
+                                                         int H, int N)
+{
+    using CW = typename TT::CW;
+    using BG = BigGeo<16>;
+    constexpr int BPK1 = BG::PK1, BPN3 = BG::PN3, NCH = BG::NCH, N2 = 16;
+    extern __shared__ uint32_t XB[];
+    const int tid = threadIdx.x, l = tid & 63, q = l >> 4, c16 = l & 15;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int npairs = (B + 1) / 2;
+    const int nch = (H - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x;      // channels h = blockIdx.x + j gridDim.x
+    const int S = nch * npairs * 2;                        // inputs: index (j * npairs + pair) * 2 + (0 = u, 1 = dy)
+    if (S <= 0) return;
+    const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
+
+    uint32_t *const wrA = XB + 4 * w * BPN3 + c16 * BPK1 + 4 * q;
+    const uint32_t *const rdB0 = XB + big_sigma(4 * q) * BPN3 + 4 * w * BPK1 + c16;
+    const uint32_t *const rdB1 = XB + big_sigma(16 + 4 * q) * BPN3 + 4 * w * BPK1 + c16;
+    constexpr int SB_ROW = 72, SB_BYTES = 2 * 16 * N2 * SB_ROW;
+    char *const US = (char *)XB + SB_BYTES;
+
+    const __amdgpu_buffer_rsrc_t rc = __builtin_amdgcn_make_buffer_rsrc((void *)consts, 0, BG::CONST_BYTES, 0x00020000);
+    int vo4 = 4 * l, vo16 = 16 * l, sz = 0;
+    auto opaque = [&]() {
+        int z = 0;
+        asm volatile("" : "+v"(z));
+        vo4 = 4 * l + z;
+        vo16 = 16 * l + z;
+        asm volatile("s_mov_b32 %0, 0" : "=s"(sz));
+    };
+    auto ld16 = [&](int base, int ofs) {
+        typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+        const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rc, vo16 + (ofs & 4095), base + (ofs & ~4095), 0);
+        return make_uint4(v.x, v.y, v.z, v.w);
+    };
+    auto ld4 = [&](int base, int ofs) {
+        return (CW)__builtin_amdgcn_raw_buffer_load_b32(rc, vo4 + (ofs & 4095), base + (ofs & ~4095), 0);
+    };
+    // resident: stage-1 and stage-3 matrices; streamed one plane ahead: stage-2 matrix and twiddles of a plane
+    uint4 tab1[2][2], tab3[2][2][2], tabA[2];
+    CW twaR[2][4];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int p = 0; p < 2; ++p) tab1[a][p] = ld16(0, BG::OFF_TAB1 + (a * 2 + p) * 1024);
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int p = 0; p < 2; ++p) tab3[a][b][p] = ld16(0, BG::OFF_TAB3 + ((a * 2 + b) * 2 + p) * 1024);
+    auto load_plane = [&](int i) {
+        const int c = 4 * w + i;
+#pragma unroll
+        for (int p = 0; p < 2; ++p) tabA[p] = ld16(sz + c * BG::PLANE2, BG::OFF_TAB2 + p * 1024);
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) twaR[b][r] = ld4(sz + c * BG::PLANEW, BG::OFF_TWA + (b * 4 + r) * 256);
+    };
+
+    uint4 pre[NCH];
+    uint2 x1r[2][4];
+    auto issue_pre = [&](int s) {
+        const int item = s >> 1, which = s & 1;
+        const int j = item / npairs, pair = item - j * npairs;
+        const int h = (int)blockIdx.x + j * (int)gridDim.x;
+        const uint16_t *src = which ? dy : u;
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            const int row = c / (NCH / 2);
+            const int n = (tid + NT * (c % (NCH / 2))) * 8;
+            const int b = 2 * pair + row;
+            if constexpr (FULL) {
+                pre[c] = *(const uint4 *)(src + ((size_t)b * H + h) * N + n);
+            } else {
+                uint4 v = make_uint4(0, 0, 0, 0);
+                if (b < B && n < N) v = *(const uint4 *)(src + ((size_t)b * H + h) * N + n);
+                pre[c] = v;
+            }
+        }
+    };
+    auto chunk_ofs = [&](int c) {
+        const int row = c / (NCH / 2);
+        const int n = (tid + NT * (c % (NCH / 2))) * 8;
+        return (row * 16 * N2 + n / 32) * SB_ROW + (n % 32) * 2;
+    };
+    auto stage_in = [&]() {
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            uint2 *dst = (uint2 *)(US + chunk_ofs(c));
+            dst[0] = make_uint2(pre[c].x, pre[c].y);
+            dst[1] = make_uint2(pre[c].z, pre[c].w);
+        }
+    };
+    auto read_x1 = [&]() {
+#pragma unroll
+        for (int row = 0; row < 2; ++row)
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                x1r[row][r] = *(const uint2 *)(US + ((row * 16 + 4 * q + r) * N2 + c16) * SB_ROW + 8 * w);
+    };
+    auto phase_A = [&]() {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t sel = (i & 1) ? 0x07060302u : 0x05040100u;
+            uint32_t d[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const uint32_t lo = i < 2 ? x1r[0][r].x : x1r[0][r].y;
+                const uint32_t hi = i < 2 ? x1r[1][r].x : x1r[1][r].y;
+                d[r] = __builtin_amdgcn_perm(hi, lo, sel);
+            }
+            const uint4 x1 = make_uint4(d[0], d[1], d[2], d[3]);
+            uint4 x2[2];
+#pragma unroll
+            for (int ct = 0; ct < 2; ++ct) {
+                const f32x4 dre = TT::mfma(x1, tab1[ct][0], zero4);
+                const f32x4 dim = TT::mfma(x1, tab1[ct][1], zero4);
+                x2[ct] = TT::template ctw4<false>(dre, dim, twaR[ct]);
+            }
+            uint4 o[2];
+#pragma unroll
+            for (int ct = 0; ct < 2; ++ct) {
+                const f32x4 dre = TT::mfma(tabA[0], x2[ct], zero4);
+                const f32x4 dim = TT::mfma(tabA[1], x2[ct], zero4);
+                o[ct] = make_uint4(TT::pack(dre[0], dim[0]), TT::pack(dre[1], dim[1]), TT::pack(dre[2], dim[2]),
+                                   TT::pack(dre[3], dim[3]));
+            }
+            SCHED_FENCE();
+            if (i + 1 < 4) load_plane(i + 1);             // this plane's tables have been consumed
+            SCHED_FENCE();
+#pragma unroll
+            for (int ct = 0; ct < 2; ++ct) *(uint4 *)(wrA + i * BPN3 + 16 * ct * BPK1) = o[ct];
+        }
+    };
+
+    f32x4 z1re[4][2], z1im[4][2], accre[4][2], accim[4][2];        // [k1 plane of the wave][k3 tile]
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int t = 0; t < 2; ++t) accre[i][t] = accim[i][t] = z1re[i][t] = z1im[i][t] = zero4;
+
+    opaque();
+    issue_pre(0);
+    for (int s = 0; s < S; ++s) {
+        const int item = s >> 1, which = s & 1;
+        const int j = item / npairs, pair = item - j * npairs;
+        stage_in();
+        lds_barrier();
+        read_x1();
+        lds_barrier();                                    // staging consumed: phase A may overwrite it
+        opaque();
+        load_plane(0);
+        issue_pre(s + 1 < S ? s + 1 : s);                 // past the end: the last input again (in range, unused)
+        SCHED_FENCE();
+        phase_A();
+        lds_barrier();
+        // stage 3 of this wave's 4 k1 planes
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            uint4 x3[2];
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) {
+                const uint32_t *src = (ks ? rdB1 : rdB0) + i * BPK1;
+                x3[ks] = make_uint4(src[0], src[BPN3], src[2 * BPN3], src[3 * BPN3]);
+            }
+#pragma unroll
+            for (int ct3 = 0; ct3 < 2; ++ct3) {
+                f32x4 dre = zero4, dim = zero4;
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks) {
+                    dre = TT::mfma(tab3[ks][ct3][0], x3[ks], dre);
+                    dim = TT::mfma(tab3[ks][ct3][1], x3[ks], dim);
+                }
+                if (which == 0) {                         // wave-uniform
+                    z1re[i][ct3] = dre;
+                    z1im[i][ct3] = dim;
+                } else {                                  // acc += conj(Z1) . Z2
+                    accre[i][ct3] += z1re[i][ct3] * dre + z1im[i][ct3] * dim;
+                    accim[i][ct3] += z1re[i][ct3] * dim - z1im[i][ct3] * dre;
+                }
+            }
+        }
+        if (which == 1 && pair == npairs - 1) {           // the channel's last pair: write its accumulator, start anew
+            const int h = (int)blockIdx.x + j * (int)gridDim.x;
+            float2 *dst = dkf + (size_t)h * BG::M;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int ct3 = 0; ct3 < 2; ++ct3)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        dst[(((4 * w + i) * 2 + ct3) * 4 + r) * 64 + l] = make_float2(accre[i][ct3][r], accim[i][ct3][r]);
+                        accre[i][ct3][r] = 0.f;
+                        accim[i][ct3][r] = 0.f;
+                    }
+        }
+        lds_barrier();                                    // every wave has read its planes: the buffer is free
+    }
+}
+
+// dk_f of the kernel above ([h][k1][k3 tile][r][lane], lane = (k3 slot / 4 % 4) * 16 + k2, k3 in the order
+// big_sigma()) -> position order of the generic inverse stages.
+__global__ void k_unpack_big_dkf(const float2 *dkf, float2 *spec, FacList fl, int64_t nh)
+{
+    constexpr int64_t BM = BigGeo<16>::M;
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= nh * BM) return;
+    const int64_t h = idx / BM, f = idx % BM;
+    const int k1 = (int)(f % 32), k2 = (int)((f / 32) % 16), k3 = (int)(f / 512);
+    const int m3 = big_sigma_inv(k3);
+    const int64_t slot = (((int64_t)k1 * 2 + m3 / 16) * 4 + m3 % 4) * 64 + ((m3 % 16) / 4) * 16 + k2;
+    spec[h * BM + freq_to_pos(f, fl, BM)] = dkf[h * BM + slot];
+}
+
 // k_f in the kernel's per-lane order: [h][k1][k2 tile][k3 tile][r][lane]; the lane holds
 // k2 = 16 tile + lane%16 and k3 = big_sigma(16 tile + 4 (lane/16) + r).  Scaled by 1/M.
 template <typename TT, int N2>
@@ -894,6 +1119,50 @@ int fused3_big_forward_gated(const fftconv_plan *p, const void *u, const void *w
                     : launch_big<H16, false, 16, false, true>(p, u, kf, y, B, s, wg, vg);
     return full ? launch_big<B16, true, 16, false, true>(p, u, kf, y, B, s, wg, vg)
                 : launch_big<B16, false, 16, false, true>(p, u, kf, y, B, s, wg, vg);
+}
+
+bool fused3_big_dk_supported(const fftconv_plan *p) { return p->path == PATH_FUSED3 && p->M == 16384; }
+
+// dkf: H * 16384 float2 in the kernel's order
+int fused3_big_dk_accumulate(const fftconv_plan *p, const void *u, const void *dy, void *dkf, int64_t B, hipStream_t s)
+{
+    using BG = BigGeo<16>;
+    if (((uintptr_t)u | (uintptr_t)dy) & 15) {
+        set_error("fftconv_backward_filter: u and dy must be 16-byte aligned for this plan");
+        return FFTCONV_EINVAL;
+    }
+    const int64_t npairs = (B + 1) / 2;
+    if (p->H * npairs >= ((int64_t)1 << 29)) {
+        set_error("fftconv_backward_filter: H * ceil(B/2) = %lld exceeds the fused kernel's limit",
+                  (long long)(p->H * npairs));
+        return FFTCONV_EUNSUPPORTED;
+    }
+    const bool full = (B % 2 == 0) && p->N == BG::M / 2;
+    const bool f16 = p->dtype == FFTCONV_F16;
+    void (*kern)(const uint16_t *, const uint16_t *, float2 *, const void *, int, int, int) =
+        f16 ? (full ? k_fused3_big_dk<H16, true> : k_fused3_big_dk<H16, false>)
+            : (full ? k_fused3_big_dk<B16, true> : k_fused3_big_dk<B16, false>);
+    static bool attr_set[4] = {false, false, false, false};
+    const int slot = (f16 ? 2 : 0) + (full ? 1 : 0);
+    if (!attr_set[slot]) {
+        FC_HIP(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)BG::LDS_BYTES));
+        attr_set[slot] = true;
+    }
+    const int grid = (int)(p->H < p->f3.num_cu ? p->H : p->f3.num_cu);
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NT), BG::LDS_BYTES, s, (const uint16_t *)u, (const uint16_t *)dy,
+                       (float2 *)dkf, (const void *)p->f3.consts, (int)B, (int)p->H, (int)p->N);
+    FC_HIP(hipGetLastError());
+    return FFTCONV_OK;
+}
+
+int fused3_big_dk_unpack(const fftconv_plan *p, const void *dkf, void *spec, int64_t h0, int64_t nh, hipStream_t s)
+{
+    const int bs = 256;
+    const unsigned grid = (unsigned)((nh * p->M + bs - 1) / bs);
+    hipLaunchKernelGGL(k_unpack_big_dkf, dim3(grid), dim3(bs), 0, s, (const float2 *)dkf + h0 * p->M, (float2 *)spec,
+                       staged_fac_list(p), nh);
+    FC_HIP(hipGetLastError());
+    return FFTCONV_OK;
 }
 
 }  // namespace f3
