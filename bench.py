@@ -134,8 +134,8 @@ def main():
                          "warm-up, as the known-size reference for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE" % (COPY_BYTES >> 20))
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on ONE GPU only (sequences are independent; see DESIGN.md for how the "
-              "path would shard); --gpus %d is not supported" % args.gpus, file=sys.stderr)
+        print("bench.py: this build runs on ONE GPU only (sequences are independent: shard channels, then batch "
+              "rows, with no collective); --gpus %d is not supported" % args.gpus, file=sys.stderr)
         sys.exit(2)
 
     import torch
