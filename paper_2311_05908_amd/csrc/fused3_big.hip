@@ -623,27 +623,31 @@ __global__ void __launch_bounds__(NT, (N2 == 16 && !GATED) ? 4 : 2) k_fused3_big
     BSPAN(1);
 }
 
-// ---- Filter gradient for fft 16384 (Section 3.1 "Kernel Fusion and Recomputation"; see fused3_dk.hip for the
-// arithmetic: dk_f[h] = sum over the pairs of conj(FFT(u pair)) . FFT(dy pair), cross terms of the pair packing
-// end up in the dropped imaginary part of the inverse transform).  The forward half of the kernel above (staging,
-// phase A, stage 3 of phase B; same tables and layouts, N2 = 16) runs on the stream u-pair, dy-pair, u-pair, ...
+// ---- Filter gradient for fft 16384 and 32768 (Section 3.1 "Kernel Fusion and Recomputation"; see fused3_dk.hip
+// for the arithmetic: dk_f[h] = sum over the pairs of conj(FFT(u pair)) . FFT(dy pair), cross terms of the pair
+// packing end up in the dropped imaginary part of the inverse transform).  The forward half of the kernel above
+// (staging, phase A, stage 3 of phase B; same tables and layouts) runs on the stream u-pair, dy-pair, u-pair, ...
 // of the channels a workgroup owns: a u input leaves its spectrum in registers (fp32), the dy input that
-// follows multiplies it in and adds to the channel's accumulator (fp32, 64 registers), which is written out in
-// the kernel's k_f order after the channel's last pair.  One workgroup per compute unit.
-template <typename TT, bool FULL>
+// follows multiplies it in and adds to the channel's accumulator (fp32), which is written out in the kernel's
+// k_f order after the channel's last pair.  Spectrum and accumulator of a whole transform are 2 x 64 registers
+// at N2 = 16 and would be 2 x 128 at N2 = 32, where the kernel therefore walks through a channel's pairs four
+// times, each time keeping one (k2 tile, k3 tile) quarter of the bins (phase A is repeated, stage 3 is not).
+// One workgroup per compute unit.
+template <typename TT, bool FULL, int N2>
 __global__ void __launch_bounds__(NT, 2) k_fused3_big_dk(const uint16_t *__restrict__ u, const uint16_t *__restrict__ dy,
                                                          float2 *__restrict__ dkf, const void *__restrict__ consts, int B,
                                                          int H, int N)
 {
     using CW = typename TT::CW;
-    using BG = BigGeo<16>;
-    constexpr int BPK1 = BG::PK1, BPN3 = BG::PN3, NCH = BG::NCH, N2 = 16;
+    using BG = BigGeo<N2>;
+    constexpr int BPK1 = BG::PK1, BPN3 = BG::PN3, NCH = BG::NCH, R2 = BG::R2;
+    constexpr int NPASS = R2 * R2, TPP = 2 / R2;          // passes over a channel; k3 tiles kept per pass
     extern __shared__ uint32_t XB[];
     const int tid = threadIdx.x, l = tid & 63, q = l >> 4, c16 = l & 15;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int npairs = (B + 1) / 2;
     const int nch = (H - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x;      // channels h = blockIdx.x + j gridDim.x
-    const int S = nch * npairs * 2;                        // inputs: index (j * npairs + pair) * 2 + (0 = u, 1 = dy)
+    const int S = nch * NPASS * npairs * 2;                // inputs: ((j * NPASS + pass) * npairs + pair) * 2 + (0 = u, 1 = dy)
     if (S <= 0) return;
     const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
 
@@ -651,6 +655,7 @@ __global__ void __launch_bounds__(NT, 2) k_fused3_big_dk(const uint16_t *__restr
     const uint32_t *const rdB0 = XB + big_sigma(4 * q) * BPN3 + 4 * w * BPK1 + c16;
     const uint32_t *const rdB1 = XB + big_sigma(16 + 4 * q) * BPN3 + 4 * w * BPK1 + c16;
     constexpr int SB_ROW = 72, SB_BYTES = 2 * 16 * N2 * SB_ROW;
+    static_assert(2 * SB_BYTES <= (int)BG::LDS_BYTES, "the staging area must fit in the exchange buffer");
     char *const US = (char *)XB + SB_BYTES;
 
     const __amdgpu_buffer_rsrc_t rc = __builtin_amdgcn_make_buffer_rsrc((void *)consts, 0, BG::CONST_BYTES, 0x00020000);
@@ -670,38 +675,49 @@ __global__ void __launch_bounds__(NT, 2) k_fused3_big_dk(const uint16_t *__restr
     auto ld4 = [&](int base, int ofs) {
         return (CW)__builtin_amdgcn_raw_buffer_load_b32(rc, vo4 + (ofs & 4095), base + (ofs & ~4095), 0);
     };
-    // resident: stage-1 and stage-3 matrices; streamed one plane ahead: stage-2 matrix and twiddles of a plane
-    uint4 tab1[2][2], tab3[2][2][2], tabA[2];
-    CW twaR[2][4];
+    // resident: stage-1 matrix, the stage-3 tiles of the current pass; streamed one plane ahead: stage-2
+    // matrix and twiddles of a plane
+    uint4 tab1[2][2], tab3[2][TPP][2], tabA[R2][R2][2];
+    CW twaR[R2][2][4];
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
         for (int p = 0; p < 2; ++p) tab1[a][p] = ld16(0, BG::OFF_TAB1 + (a * 2 + p) * 1024);
+    auto load_tab3 = [&](int ct3) {                        // tiles ct3 .. ct3 + TPP - 1
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+        for (int a = 0; a < 2; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
+            for (int b = 0; b < TPP; ++b)
 #pragma unroll
-            for (int p = 0; p < 2; ++p) tab3[a][b][p] = ld16(0, BG::OFF_TAB3 + ((a * 2 + b) * 2 + p) * 1024);
+                for (int p = 0; p < 2; ++p)
+                    tab3[a][b][p] = ld16(sz + ct3 * 2048, BG::OFF_TAB3 + ((a * 2 + b) * 2 + p) * 1024);
+    };
     auto load_plane = [&](int i) {
         const int c = 4 * w + i;
 #pragma unroll
-        for (int p = 0; p < 2; ++p) tabA[p] = ld16(sz + c * BG::PLANE2, BG::OFF_TAB2 + p * 1024);
+        for (int a = 0; a < R2; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
+            for (int b = 0; b < R2; ++b)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) twaR[b][r] = ld4(sz + c * BG::PLANEW, BG::OFF_TWA + (b * 4 + r) * 256);
+                for (int p = 0; p < 2; ++p)
+                    tabA[a][b][p] = ld16(sz + c * BG::PLANE2, BG::OFF_TAB2 + ((a * R2 + b) * 2 + p) * 1024);
+#pragma unroll
+        for (int a = 0; a < R2; ++a)
+#pragma unroll
+            for (int b = 0; b < 2; ++b)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) twaR[a][b][r] = ld4(sz + c * BG::PLANEW, BG::OFF_TWA + ((a * 2 + b) * 4 + r) * 256);
     };
 
     uint4 pre[NCH];
-    uint2 x1r[2][4];
-    auto issue_pre = [&](int s) {
+    uint2 x1r[2][R2][4];
+    auto issue_pre = [&](int s, int c0, int c1) {         // chunks c0 .. c1 - 1
         const int item = s >> 1, which = s & 1;
-        const int j = item / npairs, pair = item - j * npairs;
-        const int h = (int)blockIdx.x + j * (int)gridDim.x;
+        const int jp = item / npairs, pair = item - jp * npairs;
+        const int h = (int)blockIdx.x + (jp / NPASS) * (int)gridDim.x;
         const uint16_t *src = which ? dy : u;
 #pragma unroll
-        for (int c = 0; c < NCH; ++c) {
+        for (int c = c0; c < c1; ++c) {
             const int row = c / (NCH / 2);
             const int n = (tid + NT * (c % (NCH / 2))) * 8;
             const int b = 2 * pair + row;
@@ -731,64 +747,88 @@ __global__ void __launch_bounds__(NT, 2) k_fused3_big_dk(const uint16_t *__restr
 #pragma unroll
         for (int row = 0; row < 2; ++row)
 #pragma unroll
-            for (int r = 0; r < 4; ++r)
-                x1r[row][r] = *(const uint2 *)(US + ((row * 16 + 4 * q + r) * N2 + c16) * SB_ROW + 8 * w);
+            for (int rt = 0; rt < R2; ++rt)
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    x1r[row][rt][r] = *(const uint2 *)(US + ((row * 16 + 4 * q + r) * N2 + 16 * rt + c16) * SB_ROW + 8 * w);
     };
     auto phase_A = [&]() {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const uint32_t sel = (i & 1) ? 0x07060302u : 0x05040100u;
-            uint32_t d[4];
+            uint4 x2[2][R2];
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const uint32_t lo = i < 2 ? x1r[0][r].x : x1r[0][r].y;
-                const uint32_t hi = i < 2 ? x1r[1][r].x : x1r[1][r].y;
-                d[r] = __builtin_amdgcn_perm(hi, lo, sel);
-            }
-            const uint4 x1 = make_uint4(d[0], d[1], d[2], d[3]);
-            uint4 x2[2];
+            for (int rt = 0; rt < R2; ++rt) {
+                uint32_t d[4];
 #pragma unroll
-            for (int ct = 0; ct < 2; ++ct) {
-                const f32x4 dre = TT::mfma(x1, tab1[ct][0], zero4);
-                const f32x4 dim = TT::mfma(x1, tab1[ct][1], zero4);
-                x2[ct] = TT::template ctw4<false>(dre, dim, twaR[ct]);
-            }
-            uint4 o[2];
+                for (int r = 0; r < 4; ++r) {
+                    const uint32_t lo = i < 2 ? x1r[0][rt][r].x : x1r[0][rt][r].y;
+                    const uint32_t hi = i < 2 ? x1r[1][rt][r].x : x1r[1][rt][r].y;
+                    d[r] = __builtin_amdgcn_perm(hi, lo, sel);
+                }
+                const uint4 x1 = make_uint4(d[0], d[1], d[2], d[3]);
 #pragma unroll
-            for (int ct = 0; ct < 2; ++ct) {
-                const f32x4 dre = TT::mfma(tabA[0], x2[ct], zero4);
-                const f32x4 dim = TT::mfma(tabA[1], x2[ct], zero4);
-                o[ct] = make_uint4(TT::pack(dre[0], dim[0]), TT::pack(dre[1], dim[1]), TT::pack(dre[2], dim[2]),
-                                   TT::pack(dre[3], dim[3]));
+                for (int ct = 0; ct < 2; ++ct) {
+                    const f32x4 dre = TT::mfma(x1, tab1[ct][0], zero4);
+                    const f32x4 dim = TT::mfma(x1, tab1[ct][1], zero4);
+                    x2[ct][rt] = TT::template ctw4<false>(dre, dim, twaR[rt][ct]);
+                }
             }
+            uint4 o[2][R2];
+#pragma unroll
+            for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+                for (int ct2 = 0; ct2 < R2; ++ct2) {
+                    f32x4 dre = zero4, dim = zero4;
+#pragma unroll
+                    for (int ks = 0; ks < R2; ++ks) {
+                        dre = TT::mfma(tabA[ks][ct2][0], x2[ct][ks], dre);
+                        dim = TT::mfma(tabA[ks][ct2][1], x2[ct][ks], dim);
+                    }
+                    o[ct][ct2] = make_uint4(TT::pack(dre[0], dim[0]), TT::pack(dre[1], dim[1]), TT::pack(dre[2], dim[2]),
+                                            TT::pack(dre[3], dim[3]));
+                }
             SCHED_FENCE();
             if (i + 1 < 4) load_plane(i + 1);             // this plane's tables have been consumed
             SCHED_FENCE();
 #pragma unroll
-            for (int ct = 0; ct < 2; ++ct) *(uint4 *)(wrA + i * BPN3 + 16 * ct * BPK1) = o[ct];
+            for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+                for (int ct2 = 0; ct2 < R2; ++ct2) *(uint4 *)(wrA + i * BPN3 + 16 * ct * BPK1 + 16 * ct2) = o[ct][ct2];
         }
     };
 
-    f32x4 z1re[4][2], z1im[4][2], accre[4][2], accim[4][2];        // [k1 plane of the wave][k3 tile]
+    // [k1 plane of the wave][k3 tile of the pass]; declared with two tiles also where one is used: arrays of
+    // 16 or 32 floats in all are merged into one wide vector value, whose partial updates the compiler then
+    // turns into copies of the whole
+    f32x4 z1re[4][2], z1im[4][2], accre[4][2], accim[4][2];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int t = 0; t < 2; ++t) accre[i][t] = accim[i][t] = z1re[i][t] = z1im[i][t] = zero4;
+        for (int t = 0; t < TPP; ++t) accre[i][t] = accim[i][t] = z1re[i][t] = z1im[i][t] = zero4;
 
     opaque();
-    issue_pre(0);
+    issue_pre(0, 0, NCH);
     for (int s = 0; s < S; ++s) {
         const int item = s >> 1, which = s & 1;
-        const int j = item / npairs, pair = item - j * npairs;
+        const int jp = item / npairs, pair = item - jp * npairs;
+        const int j = jp / NPASS, pass = jp - j * NPASS;
+        const int ct2p = pass / 2, ct3p = NPASS == 1 ? 0 : pass % 2;      // the pass keeps k2 tile ct2p, k3 tiles from ct3p on
         stage_in();
         lds_barrier();
         read_x1();
         lds_barrier();                                    // staging consumed: phase A may overwrite it
         opaque();
         load_plane(0);
-        issue_pre(s + 1 < S ? s + 1 : s);                 // past the end: the last input again (in range, unused)
+        // the next input (past the end: the last one again, in range and unused) is requested ahead of
+        // phase A where registers allow, after it otherwise
+        constexpr int EARLY = NCH;
+        issue_pre(s + 1 < S ? s + 1 : s, 0, EARLY);
         SCHED_FENCE();
         phase_A();
+        SCHED_FENCE();
+        issue_pre(s + 1 < S ? s + 1 : s, EARLY, NCH);
+        if (which == 0 && pair == 0 && (NPASS > 1 || s == 0)) load_tab3(ct3p);
         lds_barrier();
         // stage 3 of this wave's 4 k1 planes
 #pragma unroll
@@ -796,55 +836,59 @@ __global__ void __launch_bounds__(NT, 2) k_fused3_big_dk(const uint16_t *__restr
             uint4 x3[2];
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks) {
-                const uint32_t *src = (ks ? rdB1 : rdB0) + i * BPK1;
+                const uint32_t *src = (ks ? rdB1 : rdB0) + i * BPK1 + 16 * ct2p;
                 x3[ks] = make_uint4(src[0], src[BPN3], src[2 * BPN3], src[3 * BPN3]);
             }
 #pragma unroll
-            for (int ct3 = 0; ct3 < 2; ++ct3) {
+            for (int t = 0; t < TPP; ++t) {
                 f32x4 dre = zero4, dim = zero4;
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks) {
-                    dre = TT::mfma(tab3[ks][ct3][0], x3[ks], dre);
-                    dim = TT::mfma(tab3[ks][ct3][1], x3[ks], dim);
+                    dre = TT::mfma(tab3[ks][t][0], x3[ks], dre);
+                    dim = TT::mfma(tab3[ks][t][1], x3[ks], dim);
                 }
                 if (which == 0) {                         // wave-uniform
-                    z1re[i][ct3] = dre;
-                    z1im[i][ct3] = dim;
+                    z1re[i][t] = dre;
+                    z1im[i][t] = dim;
                 } else {                                  // acc += conj(Z1) . Z2
-                    accre[i][ct3] += z1re[i][ct3] * dre + z1im[i][ct3] * dim;
-                    accim[i][ct3] += z1re[i][ct3] * dim - z1im[i][ct3] * dre;
+                    accre[i][t] += z1re[i][t] * dre + z1im[i][t] * dim;
+                    accim[i][t] += z1re[i][t] * dim - z1im[i][t] * dre;
                 }
             }
         }
-        if (which == 1 && pair == npairs - 1) {           // the channel's last pair: write its accumulator, start anew
+        if (which == 1 && pair == npairs - 1) {           // the pass's last pair: write its accumulator, start anew
             const int h = (int)blockIdx.x + j * (int)gridDim.x;
             float2 *dst = dkf + (size_t)h * BG::M;
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
-                for (int ct3 = 0; ct3 < 2; ++ct3)
+                for (int t = 0; t < TPP; ++t) {
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        dst[(((4 * w + i) * 2 + ct3) * 4 + r) * 64 + l] = make_float2(accre[i][ct3][r], accim[i][ct3][r]);
-                        accre[i][ct3][r] = 0.f;
-                        accim[i][ct3][r] = 0.f;
-                    }
+                    for (int r = 0; r < 4; ++r)
+                        dst[((((4 * w + i) * R2 + ct2p) * 2 + ct3p + t) * 4 + r) * 64 + l] =
+                            make_float2(accre[i][t][r], accim[i][t][r]);
+                    accre[i][t] = zero4;
+                    accim[i][t] = zero4;
+                }
         }
         lds_barrier();                                    // every wave has read its planes: the buffer is free
     }
 }
 
-// dk_f of the kernel above ([h][k1][k3 tile][r][lane], lane = (k3 slot / 4 % 4) * 16 + k2, k3 in the order
-// big_sigma()) -> position order of the generic inverse stages.
+// dk_f of the kernel above ([h][k1][k2 tile][k3 tile][r][lane], lane = (k3 slot / 4 % 4) * 16 + k2 % 16, k3 in the
+// order big_sigma()) -> position order of the generic inverse stages.
+template <int N2>
 __global__ void k_unpack_big_dkf(const float2 *dkf, float2 *spec, FacList fl, int64_t nh)
 {
-    constexpr int64_t BM = BigGeo<16>::M;
+    constexpr int64_t BM = BigGeo<N2>::M;
+    constexpr int R2 = BigGeo<N2>::R2;
     const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= nh * BM) return;
     const int64_t h = idx / BM, f = idx % BM;
-    const int k1 = (int)(f % 32), k2 = (int)((f / 32) % 16), k3 = (int)(f / 512);
+    const int k1 = (int)(f % 32), k2 = (int)((f / 32) % N2), k3 = (int)(f / (32 * N2));
     const int m3 = big_sigma_inv(k3);
-    const int64_t slot = (((int64_t)k1 * 2 + m3 / 16) * 4 + m3 % 4) * 64 + ((m3 % 16) / 4) * 16 + k2;
+    const int64_t slot =
+        ((((int64_t)k1 * R2 + k2 / 16) * 2 + m3 / 16) * 4 + m3 % 4) * 64 + ((m3 % 16) / 4) * 16 + k2 % 16;
     spec[h * BM + freq_to_pos(f, fl, BM)] = dkf[h * BM + slot];
 }
 
@@ -1121,27 +1165,17 @@ int fused3_big_forward_gated(const fftconv_plan *p, const void *u, const void *w
                 : launch_big<B16, false, 16, false, true>(p, u, kf, y, B, s, wg, vg);
 }
 
-bool fused3_big_dk_supported(const fftconv_plan *p) { return p->path == PATH_FUSED3 && p->M == 16384; }
+bool fused3_big_dk_supported(const fftconv_plan *p) { return p->path == PATH_FUSED3 && (p->M == 16384 || p->M == 32768); }
 
-// dkf: H * 16384 float2 in the kernel's order
-int fused3_big_dk_accumulate(const fftconv_plan *p, const void *u, const void *dy, void *dkf, int64_t B, hipStream_t s)
+template <int N2>
+static int big_dk_accumulate_t(const fftconv_plan *p, const void *u, const void *dy, void *dkf, int64_t B, hipStream_t s)
 {
-    using BG = BigGeo<16>;
-    if (((uintptr_t)u | (uintptr_t)dy) & 15) {
-        set_error("fftconv_backward_filter: u and dy must be 16-byte aligned for this plan");
-        return FFTCONV_EINVAL;
-    }
-    const int64_t npairs = (B + 1) / 2;
-    if (p->H * npairs >= ((int64_t)1 << 29)) {
-        set_error("fftconv_backward_filter: H * ceil(B/2) = %lld exceeds the fused kernel's limit",
-                  (long long)(p->H * npairs));
-        return FFTCONV_EUNSUPPORTED;
-    }
+    using BG = BigGeo<N2>;
     const bool full = (B % 2 == 0) && p->N == BG::M / 2;
     const bool f16 = p->dtype == FFTCONV_F16;
     void (*kern)(const uint16_t *, const uint16_t *, float2 *, const void *, int, int, int) =
-        f16 ? (full ? k_fused3_big_dk<H16, true> : k_fused3_big_dk<H16, false>)
-            : (full ? k_fused3_big_dk<B16, true> : k_fused3_big_dk<B16, false>);
+        f16 ? (full ? k_fused3_big_dk<H16, true, N2> : k_fused3_big_dk<H16, false, N2>)
+            : (full ? k_fused3_big_dk<B16, true, N2> : k_fused3_big_dk<B16, false, N2>);
     static bool attr_set[4] = {false, false, false, false};
     const int slot = (f16 ? 2 : 0) + (full ? 1 : 0);
     if (!attr_set[slot]) {
@@ -1155,12 +1189,32 @@ int fused3_big_dk_accumulate(const fftconv_plan *p, const void *u, const void *d
     return FFTCONV_OK;
 }
 
+// dkf: H * fft_size float2 in the kernel's order
+int fused3_big_dk_accumulate(const fftconv_plan *p, const void *u, const void *dy, void *dkf, int64_t B, hipStream_t s)
+{
+    if (((uintptr_t)u | (uintptr_t)dy) & 15) {
+        set_error("fftconv_backward_filter: u and dy must be 16-byte aligned for this plan");
+        return FFTCONV_EINVAL;
+    }
+    const int64_t npairs = (B + 1) / 2;
+    if (p->H * npairs >= ((int64_t)1 << 27)) {
+        set_error("fftconv_backward_filter: H * ceil(B/2) = %lld exceeds the fused kernel's limit",
+                  (long long)(p->H * npairs));
+        return FFTCONV_EUNSUPPORTED;
+    }
+    return p->M == 32768 ? big_dk_accumulate_t<32>(p, u, dy, dkf, B, s) : big_dk_accumulate_t<16>(p, u, dy, dkf, B, s);
+}
+
 int fused3_big_dk_unpack(const fftconv_plan *p, const void *dkf, void *spec, int64_t h0, int64_t nh, hipStream_t s)
 {
     const int bs = 256;
     const unsigned grid = (unsigned)((nh * p->M + bs - 1) / bs);
-    hipLaunchKernelGGL(k_unpack_big_dkf, dim3(grid), dim3(bs), 0, s, (const float2 *)dkf + h0 * p->M, (float2 *)spec,
-                       staged_fac_list(p), nh);
+    if (p->M == 32768)
+        hipLaunchKernelGGL(k_unpack_big_dkf<32>, dim3(grid), dim3(bs), 0, s, (const float2 *)dkf + h0 * p->M,
+                           (float2 *)spec, staged_fac_list(p), nh);
+    else
+        hipLaunchKernelGGL(k_unpack_big_dkf<16>, dim3(grid), dim3(bs), 0, s, (const float2 *)dkf + h0 * p->M,
+                           (float2 *)spec, staged_fac_list(p), nh);
     FC_HIP(hipGetLastError());
     return FFTCONV_OK;
 }
