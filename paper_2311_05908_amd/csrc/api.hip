@@ -168,13 +168,16 @@ static int filter_fft_impl(const fftconv_plan *p, const float *k, int64_t Nk, co
         FC_HIP(hipMemcpyAsync(p->keep_dev, block_keep, (size_t)n_blocks, hipMemcpyHostToDevice, s));
         keep_dev = p->keep_dev;
     }
-    for (int64_t h0 = 0; h0 < p->H; h0 += p->filt_chunk) {
+    if (p->path == PATH_FUSED3) {
+        rc = fused3_filter(p, k, Nk, adjoint, keep_dev, n_blocks, k_f, s);
+        if (rc) return rc;
+    }
+    for (int64_t h0 = 0; p->path != PATH_FUSED3 && h0 < p->H; h0 += p->filt_chunk) {
         int64_t nh = p->H - h0 < p->filt_chunk ? p->H - h0 : p->filt_chunk;
         double2 *spec = nullptr;
         rc = staged_filter_transform(p, k, Nk, h0, nh, s, &spec, adjoint);
         if (rc) return rc;
         switch (p->path) {
-        case PATH_FUSED3: rc = fused3_pack_kf(p, spec, h0, nh, keep_dev, n_blocks, k_f, s); break;
         case PATH_MULTIPASS: rc = multipass_pack_kf(p, spec, h0, nh, keep_dev, n_blocks, k_f, s); break;
         case PATH_SMALL: rc = small_pack_kf(p, spec, h0, nh, keep_dev, n_blocks, k_f, s); break;
         default: rc = staged_pack_kf(p, spec, h0, nh, keep_dev, n_blocks, k_f, s); break;
@@ -183,16 +186,7 @@ static int filter_fft_impl(const fftconv_plan *p, const float *k, int64_t Nk, co
     }
     // a short filter of a plan that can run partial convolutions as short segments: add the
     // short transform's spectrum behind the dense one
-    if (!block_keep && !adjoint && fused3_short_ok(p, Nk)) {
-        for (int64_t h0 = 0; h0 < p->H; h0 += p->filt_chunk) {
-            int64_t nh = p->H - h0 < p->filt_chunk ? p->H - h0 : p->filt_chunk;
-            double2 *spec = nullptr;
-            rc = staged_filter_transform_sub(p, 8192, k, Nk, h0, nh, s, &spec);
-            if (rc) return rc;
-            rc = fused3_pack_kf_short(p, spec, h0, nh, k_f, s);
-            if (rc) return rc;
-        }
-    }
+    if (!block_keep && !adjoint && fused3_short_ok(p, Nk)) return fused3_filter_short(p, k, Nk, k_f, s);
     return FFTCONV_OK;
 }
 

@@ -115,16 +115,12 @@ int staged_pack_kf(const fftconv_plan *p, const double2 *spec, int64_t h0, int64
                    const uint8_t *keep_dev, int64_t n_blocks, void *kf, hipStream_t s);
 FacList staged_fac_list(const fftconv_plan *p);
 FacList staged_factors_for(int64_t M);
-int staged_filter_transform_sub(const fftconv_plan *p, int64_t Msub, const float *k, int64_t Nk, int64_t h0,
-                                int64_t nh, hipStream_t s, double2 **result);
 
 // ---- fused 3-stage path (fused3.hip)
 bool fused3_supported(int64_t N, int64_t M, int dtype);
 int fused3_init(fftconv_plan *p);
 void fused3_destroy(fftconv_plan *p);
 size_t fused3_kf_bytes(const fftconv_plan *p);
-int fused3_pack_kf(const fftconv_plan *p, const double2 *spec, int64_t h0, int64_t nh,
-                   const uint8_t *keep_dev, int64_t n_blocks, void *kf, hipStream_t s);
 int fused3_forward(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, hipStream_t s);
 // frequency-sparse forward: live = number of accumulator registers (1..4) that can hold non-zero k_f
 int fused3_forward_sparse(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, uint32_t live_k3,
@@ -134,7 +130,10 @@ uint32_t fused3_live_k3(const fftconv_plan *p, const uint8_t *block_keep, int64_
 bool fused3_short_ok(const fftconv_plan *p, int64_t Nk);
 int fused3_init_short(fftconv_plan *p);
 size_t fused3_short_kf_bytes(const fftconv_plan *p);
-int fused3_pack_kf_short(const fftconv_plan *p, const double2 *spec, int64_t h0, int64_t nh, void *kf, hipStream_t s);
+int fused3_filter_short(const fftconv_plan *p, const float *k, int64_t Nk, void *kf, hipStream_t s);
+// filter transform in one kernel, taps to k_f; adjoint: the conjugate spectrum
+int fused3_filter(const fftconv_plan *p, const float *k, int64_t Nk, bool adjoint, const uint8_t *keep_dev,
+                  int64_t n_blocks, void *kf, hipStream_t s);
 int fused3_forward_short(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, int64_t Nk,
                          hipStream_t s);
 // the 8192-point complex-row kernel used as the inner step of the multi-pass path

@@ -50,6 +50,7 @@
 #include <type_traits>
 
 #include "fused3_common.h"
+#include "lds_fft.h"
 
 // Timing probes (development builds only, -DFUSED3_PROBE): a launch-time mask switches whole
 // phases off so their cost can be read from the difference.  Results are then meaningless.
@@ -550,32 +551,36 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *u, uint16_t *y,
     store_out(cnt - 1);
 }
 
-// k_f in the fused kernel's per-lane order: [h][k1][k2 tile][k3 tile][r][lane] float2, where the
-// lane holds k2 = 16 tile + lane%16 and k3 = k3_at_index(16 tile + 4 (lane/16) + r).
-// fmt 0: fp32 pairs; fmt 1 / 2: 16-bit constant pairs for TT::ctw (bf16 dot-product / fp16 packed form)
-// groups > 1: spec holds spectra of length Ms = M / groups; slot (k1, k2, k3) of the kernel's 8192-point
-// layout takes bin k1 % N1s + N1s (k2 + N2 k3) of it (the same spectrum for every group), see build_tables().
-template <int N2, int N3>
-__global__ void k_pack_fused3(const double2 *spec, float2 *kf, FacList fl, int64_t h0, int64_t nh,
-                              const uint8_t *keep, int64_t n_blocks, int fmt, int groups)
+// Filter transform of the plans that run on the 8192-point kernel, one workgroup per channel and no
+// intermediate in HBM: taps -> LDS (zero padded, fp32), forward transform of length Ms = 8192 / groups in
+// LDS (the stages of the generic path, lds_fft.h; fp32 is ample for constants that are rounded to 16 bits),
+// then k_f[h] in the kernel's per-lane order, scaled by 1/Ms:
+//   slot d = (k1 * 4 + r) * 64 + lane holds k2 = lane % 16, k3 = k3_at_index(4 (lane / 16) + r), as 16-bit
+//   constant pairs for TT::ctw (fmt 1: bf16 dot-product form, fmt 2: fp16 packed form).
+// groups > 1: slot (k1, k2, k3) takes bin k1 % N1s + N1s (k2 + 16 k3) of the short spectrum, N1s = 32 / groups
+// (the same spectrum for every group), see build_tables().  reversed: see the adjoint filter transform.
+constexpr int FILT_THREADS = 512;
+__global__ void __launch_bounds__(FILT_THREADS) k_filter_fused3(const float *__restrict__ k, uint2 *__restrict__ kf,
+                                                               const float2 *__restrict__ w, FacList fl, int64_t Nk,
+                                                               int tws, bool reversed, const uint8_t *__restrict__ keep,
+                                                               int64_t n_blocks, int fmt, int groups)
 {
-    using G = Geo<N2, N3>;
-    constexpr int64_t M = G::M;
-    int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= nh * M) return;
-    int64_t h = idx / M, f = idx % M;
-    int k1 = (int)(f % N1), k2 = (int)((f / N1) % N2), k3 = (int)(f / (N1 * N2));
-    const int N1s = N1 / groups;
-    const int64_t Ms = M / groups;
-    const int64_t fs = (k1 % N1s) + (int64_t)N1s * (k2 + (int64_t)N2 * k3);      // bin of the (sub-)transform
-    const int slot = k3_index(k3, N3);                     // accumulator slot 16 t + 4 q + r of this k3
-    int lane = ((slot % 16) / 4) * 16 + (k2 % 16), r = slot % 4;
-    int64_t dst = ((((int64_t)k1 * G::R2 + k2 / 16) * G::R3 + slot / 16) * 4 + r) * 64 + lane;
-    double2 v = spec[h * Ms + freq_to_pos(fs, fl, Ms)];
-    double sc = mask_weight(keep, n_blocks, fs, Ms) / (double)Ms;
-    if (fmt == 0) {
-        kf[(h0 + h) * M + dst] = make_float2((float)(v.x * sc), (float)(v.y * sc));
-    } else {
+    extern __shared__ float2 XF[];
+    constexpr int M = 8192;
+    const int Ms = M / groups, N1s = N1 / groups;
+    const int64_t h = blockIdx.x;
+    for (int n = threadIdx.x; n < Ms; n += FILT_THREADS) {
+        const int t = (reversed && n != 0) ? Ms - n : n;
+        XF[lds_slot(n)] = make_float2(t < Nk ? k[h * Nk + t] : 0.f, 0.f);
+    }
+    __syncthreads();
+    lds_forward(XF, w, fl, Ms, tws);
+    for (int d = threadIdx.x; d < M; d += FILT_THREADS) {
+        const int lane = d % 64, r = (d / 64) % 4, k1 = d / 256;
+        const int k2 = lane % 16, k3 = k3_at_index(4 * (lane / 16) + r, 16);
+        const int fs = (k1 % N1s) + N1s * (k2 + 16 * k3);                      // bin of the (sub-)transform
+        const float2 v = XF[lds_slot(lds_pos(fs, fl, Ms))];
+        const double sc = (double)lds_mask_weight(keep, n_blocks, fs, Ms) / (double)Ms;
         uint2 c;
         if (fmt == 1)
             c = ctw_const(v.x * sc, v.y * sc, 1, [](double x) {
@@ -587,7 +592,7 @@ __global__ void k_pack_fused3(const double2 *spec, float2 *kf, FacList fl, int64
                 __half hv = __float2half_rn((float)x);
                 return *(uint16_t *)&hv;
             });
-        ((uint2 *)kf)[(h0 + h) * M + dst] = c;
+        kf[h * M + d] = c;
     }
 }
 
@@ -979,15 +984,29 @@ bool fused3_short_ok(const fftconv_plan *p, int64_t Nk)
     return p->f3.consts_short != nullptr && Nk >= 1 && history_of(Nk) <= SHORT_MAX_P;
 }
 
-int fused3_pack_kf_short(const fftconv_plan *p, const double2 *spec, int64_t h0, int64_t nh, void *kf, hipStream_t s)
+static int launch_filter_fused3(const float *k, int64_t Nk, int64_t H, uint2 *kf, const float2 *w, const FacList &fl,
+                                int64_t Ms, int64_t tws, bool reversed, const uint8_t *keep_dev, int64_t n_blocks, int fmt,
+                                hipStream_t s)
 {
-    const int bs = 256;
-    const unsigned grid = (unsigned)((nh * SHORT_M + bs - 1) / bs);
-    float2 *dst = (float2 *)((char *)kf + dense_kf_bytes(p));
-    hipLaunchKernelGGL((k_pack_fused3<16, 16>), dim3(grid), dim3(bs), 0, s, spec, dst, staged_factors_for(SHORT_M), h0,
-                       nh, (const uint8_t *)nullptr, (int64_t)1, p->dtype == FFTCONV_F16 ? 2 : 1, 1);
+    const size_t bytes = lds_row_bytes(Ms, sizeof(float2));
+    static bool raised = false;
+    if (!raised) {
+        FC_HIP(hipFuncSetAttribute((const void *)k_filter_fused3, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   (int)lds_row_bytes(8192, sizeof(float2))));
+        raised = true;
+    }
+    hipLaunchKernelGGL(k_filter_fused3, dim3((unsigned)H), dim3(FILT_THREADS), bytes, s, k, kf, w, fl, Nk, (int)tws, reversed,
+                       keep_dev, n_blocks, fmt, (int)(8192 / Ms));
     FC_HIP(hipGetLastError());
     return FFTCONV_OK;
+}
+
+// the 8192-point spectrum of a short filter, behind the dense one (see fused3_forward_short)
+int fused3_filter_short(const fftconv_plan *p, const float *k, int64_t Nk, void *kf, hipStream_t s)
+{
+    uint2 *dst = (uint2 *)((char *)kf + dense_kf_bytes(p));
+    return launch_filter_fused3(k, Nk, p->H, dst, p->st.w32, staged_factors_for(SHORT_M), SHORT_M, p->M / SHORT_M, false,
+                                nullptr, 1, p->dtype == FFTCONV_F16 ? 2 : 1, s);
 }
 
 // Partial convolution (Section 3.3) of a plan for fft >= 16384: the filter covers Nk <= 2049 taps, so
@@ -1009,34 +1028,15 @@ int fused3_forward_short(const fftconv_plan *p, const void *u, const void *kf, v
     return fused3_ws_launch(p, p->f3.consts_short, u, kf_short, y, B, nseg, P, s);
 }
 
-int fused3_pack_kf(const fftconv_plan *p, const double2 *spec, int64_t h0, int64_t nh, const uint8_t *keep_dev,
-                   int64_t n_blocks, void *kf, hipStream_t s)
+// The filter transform of every plan on this path is one kernel from the taps to k_f.
+int fused3_filter(const fftconv_plan *p, const float *k, int64_t Nk, bool adjoint, const uint8_t *keep_dev,
+                  int64_t n_blocks, void *kf, hipStream_t s)
 {
-    const int bs = 256;
-    switch (p->M) {
-    case 256:
-    case 512:
-    case 1024:
-    case 2048:
-    case 4096:
-    case 8192: {
-        // the wave-specialised 8192 kernel takes k_f as 16-bit constant pairs; shorter transforms fill its
-        // 8192 slots with 8192 / fft_size copies of their spectrum (see build_tables())
-        const unsigned grid = (unsigned)((nh * 8192 + bs - 1) / bs);
-        hipLaunchKernelGGL((k_pack_fused3<16, 16>), dim3(grid), dim3(bs), 0, s, spec, (float2 *)kf,
-                           staged_fac_list(p), h0, nh, keep_dev, n_blocks, p->dtype == FFTCONV_F16 ? 2 : 1,
-                           (int)(8192 / p->M));
-        break;
-    }
-    case 16384:
-    case 32768:
-        return fused3_big_pack_kf(p, spec, h0, nh, keep_dev, n_blocks, kf, s);
-    default:
-        set_error("fused3: no kernel for fft_size=%lld", (long long)p->M);
-        return FFTCONV_EUNSUPPORTED;
-    }
-    FC_HIP(hipGetLastError());
-    return FFTCONV_OK;
+    if (p->M > 8192) return fused3_big_filter(p, k, Nk, adjoint, keep_dev, n_blocks, kf, s);
+    // the 8192-point kernel takes k_f as 16-bit constant pairs; shorter transforms fill its 8192 slots with
+    // 8192 / fft_size copies of their spectrum (see build_tables())
+    return launch_filter_fused3(k, Nk, p->H, (uint2 *)kf, p->st.w32, staged_fac_list(p), p->M, 1, adjoint, keep_dev,
+                                n_blocks, p->dtype == FFTCONV_F16 ? 2 : 1, s);
 }
 
 bool fused3_gates_fused(const fftconv_plan *p) { return p->path == PATH_FUSED3; }

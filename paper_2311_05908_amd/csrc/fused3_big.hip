@@ -28,6 +28,7 @@
 #include <vector>
 
 #include "fused3_common.h"
+#include "lds_fft.h"
 
 #ifdef FUSED3_PROBE
 // development build only: time stamps of one workgroup, read back with fftconv_debug_stamps_big()
@@ -892,25 +893,52 @@ __global__ void k_unpack_big_dkf(const float2 *dkf, float2 *spec, FacList fl, in
     spec[h * BM + freq_to_pos(f, fl, BM)] = dkf[h * BM + slot];
 }
 
+// Filter transform, one workgroup per channel and nothing but the taps and k_f in HBM.  The taps are real, so
+// the row is transformed as M/2 complex points z[n] = k[2n] + i k[2n+1] in LDS (fp32, the stages of lds_fft.h;
+// 16384 complex points are what LDS holds), and the two interleaved half-length spectra are separated on the way
+// out: with Z = FFT(z), E = (Z[f] + conj Z[M/2 - f]) / 2 and O = (Z[f] - conj Z[M/2 - f]) / (2i) are the spectra
+// of the even and odd taps, K[f] = E + W_M^f O for f < M/2, K[M/2] = Re Z[0] - Im Z[0], K[M - f] = conj K[f].
 // k_f in the kernel's per-lane order: [h][k1][k2 tile][k3 tile][r][lane]; the lane holds
 // k2 = 16 tile + lane%16 and k3 = big_sigma(16 tile + 4 (lane/16) + r).  Scaled by 1/M.
+// w: W_M^t, t < M.  flh: factors of the half-length transform.  conj_out: the adjoint filter transform.
+constexpr int BIG_FILT_THREADS = 512;
 template <typename TT, int N2>
-__global__ void k_pack_big(const double2 *spec, typename TT::CW *kf, FacList fl, int64_t h0, int64_t nh,
-                           const uint8_t *keep, int64_t n_blocks)
+__global__ void __launch_bounds__(BIG_FILT_THREADS) k_filter_big(const float *__restrict__ k, typename TT::CW *__restrict__ kf,
+                                                                const float2 *__restrict__ w, FacList flh, int64_t Nk,
+                                                                bool conj_out, const uint8_t *__restrict__ keep,
+                                                                int64_t n_blocks)
 {
-    constexpr int64_t BM = BigGeo<N2>::M;
-    constexpr int R2 = BigGeo<N2>::R2;
-    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= nh * BM) return;
-    const int64_t h = idx / BM, f = idx % BM;
-    const int k1 = (int)(f % 32), k2 = (int)((f / 32) % N2), k3 = (int)(f / (32 * N2));
-    const int m3 = big_sigma_inv(k3);
-    const int lane = ((m3 % 16) / 4) * 16 + (k2 % 16), r = m3 % 4;
-    const int64_t dst = ((((int64_t)k1 * R2 + k2 / 16) * 2 + m3 / 16) * 4 + r) * 64 + lane;
-    const double2 v = spec[h * BM + freq_to_pos(f, fl, BM)];
-    const double sc = mask_weight(keep, n_blocks, f, BM) / (double)BM;
-    const uint32_t pr = TT::pack((float)(v.x * sc), (float)(v.y * sc));      // (re, im) 16-bit pair
-    kf[(h0 + h) * BM + dst] = TT::cconst(pr & 0xffffu, pr >> 16, true);       // the kernel forms conj(A3 * k_f)
+    extern __shared__ float2 ZF[];
+    constexpr int BM = BigGeo<N2>::M, MH = BM / 2, R2 = BigGeo<N2>::R2;
+    const int64_t h = blockIdx.x;
+    const float *row = k + h * Nk;
+    for (int n = threadIdx.x; n < MH; n += BIG_FILT_THREADS)
+        ZF[lds_slot(n)] = make_float2(2 * n < Nk ? row[2 * n] : 0.f, 2 * n + 1 < Nk ? row[2 * n + 1] : 0.f);
+    __syncthreads();
+    lds_forward(ZF, w, flh, MH, 2);
+    for (int d = threadIdx.x; d < BM; d += BIG_FILT_THREADS) {
+        const int lane = d % 64, r = (d / 64) % 4, t3 = (d / 256) % 2, t2 = (d / 512) % R2, k1 = d / (512 * R2);
+        const int k2 = 16 * t2 + lane % 16, k3 = big_sigma(16 * t3 + 4 * (lane / 16) + r);
+        const int f = k1 + 32 * k2 + 32 * N2 * k3;
+        const int fe = f <= MH ? f : BM - f;              // K[f] = conj K[M - f]
+        float2 v;
+        if (fe == MH) {
+            const float2 z0 = ZF[lds_slot(0)];
+            v = make_float2(z0.x - z0.y, 0.f);
+        } else {
+            const float2 za = ZF[lds_slot(lds_pos(fe, flh, MH))];
+            const float2 zc = ZF[lds_slot(lds_pos((MH - fe) % MH, flh, MH))];
+            const float2 e = make_float2(0.5f * (za.x + zc.x), 0.5f * (za.y - zc.y));
+            const float2 o = make_float2(0.5f * (za.y + zc.y), -0.5f * (za.x - zc.x));      // (za - conj zc) / (2i)
+            v = cmul(o, w[fe]);
+            v.x += e.x;
+            v.y += e.y;
+        }
+        if ((f > MH) != conj_out) v.y = -v.y;
+        const float sc = lds_mask_weight(keep, n_blocks, f, BM) / (float)BM;
+        const uint32_t pr = TT::pack(v.x * sc, v.y * sc);                       // (re, im) 16-bit pair
+        kf[h * BM + d] = TT::cconst(pr & 0xffffu, pr >> 16, true);              // the kernel forms conj(A3 * k_f)
+    }
 }
 
 // ---------------------------------------------------------------- host side
@@ -1077,18 +1105,20 @@ template <int N2> int big_init_t(fftconv_plan *p)
     return FFTCONV_OK;
 }
 
-template <int N2>
-int big_pack_t(const fftconv_plan *p, const double2 *spec, int64_t h0, int64_t nh, const uint8_t *keep_dev,
-               int64_t n_blocks, void *kf, hipStream_t s)
+template <typename TT, int N2>
+int big_filter_tt(const fftconv_plan *p, const float *k, int64_t Nk, bool adjoint, const uint8_t *keep_dev, int64_t n_blocks,
+                  void *kf, hipStream_t s)
 {
-    const int bs = 256;
-    const unsigned grid = (unsigned)((nh * BigGeo<N2>::M + bs - 1) / bs);
-    if (p->dtype == FFTCONV_F16)
-        hipLaunchKernelGGL((k_pack_big<H16, N2>), dim3(grid), dim3(bs), 0, s, spec, (uint32_t *)kf, staged_fac_list(p), h0,
-                           nh, keep_dev, n_blocks);
-    else
-        hipLaunchKernelGGL((k_pack_big<B16, N2>), dim3(grid), dim3(bs), 0, s, spec, (uint32_t *)kf, staged_fac_list(p), h0,
-                           nh, keep_dev, n_blocks);
+    constexpr int64_t MH = BigGeo<N2>::M / 2;
+    const size_t bytes = lds_row_bytes(MH, sizeof(float2));
+    static bool raised = false;
+    if (!raised) {
+        FC_HIP(hipFuncSetAttribute((const void *)k_filter_big<TT, N2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
+        raised = true;
+    }
+    hipLaunchKernelGGL((k_filter_big<TT, N2>), dim3((unsigned)p->H), dim3(BIG_FILT_THREADS), bytes, s, k,
+                       (typename TT::CW *)kf, (const float2 *)p->st.w32, staged_factors_for(MH), Nk, adjoint, keep_dev,
+                       n_blocks);
     FC_HIP(hipGetLastError());
     return FFTCONV_OK;
 }
@@ -1118,11 +1148,15 @@ size_t fused3_big_kf_bytes(const fftconv_plan *p)
     return (size_t)(p->H * p->M) * sizeof(uint32_t);
 }
 
-int fused3_big_pack_kf(const fftconv_plan *p, const double2 *spec, int64_t h0, int64_t nh, const uint8_t *keep_dev,
-                       int64_t n_blocks, void *kf, hipStream_t s)
+int fused3_big_filter(const fftconv_plan *p, const float *k, int64_t Nk, bool adjoint, const uint8_t *keep_dev,
+                      int64_t n_blocks, void *kf, hipStream_t s)
 {
-    return p->M == 32768 ? big_pack_t<32>(p, spec, h0, nh, keep_dev, n_blocks, kf, s)
-                         : big_pack_t<16>(p, spec, h0, nh, keep_dev, n_blocks, kf, s);
+    const bool f16 = p->dtype == FFTCONV_F16;
+    if (p->M == 32768)
+        return f16 ? big_filter_tt<H16, 32>(p, k, Nk, adjoint, keep_dev, n_blocks, kf, s)
+                   : big_filter_tt<B16, 32>(p, k, Nk, adjoint, keep_dev, n_blocks, kf, s);
+    return f16 ? big_filter_tt<H16, 16>(p, k, Nk, adjoint, keep_dev, n_blocks, kf, s)
+               : big_filter_tt<B16, 16>(p, k, Nk, adjoint, keep_dev, n_blocks, kf, s);
 }
 
 // live_k3: bit d set when the digit k3 = d of the frequency (the most significant one, 32 values)

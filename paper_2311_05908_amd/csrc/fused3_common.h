@@ -336,8 +336,8 @@ int fused3_ws_launch(const fftconv_plan *p, const void *consts, const void *u, c
 // fused kernel for fft_size 32768 (fused3_big.hip): own tables (in p->f3.consts) and k_f layout
 int fused3_big_init(fftconv_plan *p);
 size_t fused3_big_kf_bytes(const fftconv_plan *p);
-int fused3_big_pack_kf(const fftconv_plan *p, const double2 *spec, int64_t h0, int64_t nh, const uint8_t *keep_dev,
-                       int64_t n_blocks, void *kf, hipStream_t s);
+int fused3_big_filter(const fftconv_plan *p, const float *k, int64_t Nk, bool adjoint, const uint8_t *keep_dev,
+                      int64_t n_blocks, void *kf, hipStream_t s);
 int fused3_big_forward(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, uint32_t live_k3,
                        hipStream_t s);
 int fused3_big_forward_gated(const fftconv_plan *p, const void *u, const void *wg, const void *vg, const void *kf, void *y,

@@ -20,7 +20,7 @@
 #include <cmath>
 #include <type_traits>
 
-#include "dft_reg.h"
+#include "lds_fft.h"
 #include "fftconv_internal.h"
 
 namespace fftconv {
@@ -32,21 +32,6 @@ namespace {
 template <typename T> struct C2;
 template <> struct C2<float> { using type = float2; };
 template <> struct C2<double> { using type = double2; };
-
-template <typename V> __device__ __forceinline__ V cmul(V a, V b)
-{
-    V r;
-    r.x = a.x * b.x - a.y * b.y;
-    r.y = a.x * b.y + a.y * b.x;
-    return r;
-}
-template <typename V> __device__ __forceinline__ V cmul_conj(V a, V b)   // a * conj(b)
-{
-    V r;
-    r.x = a.x * b.x + a.y * b.y;
-    r.y = a.y * b.x - a.x * b.y;
-    return r;
-}
 
 __device__ __forceinline__ float load_real(const float *p, int64_t i) { return p[i]; }
 __device__ __forceinline__ float load_real(const __half *p, int64_t i) { return __half2float(p[i]); }
@@ -165,6 +150,38 @@ __global__ void k_stage_inv_reg(const V *in, V *out, const V *w, int64_t M, int6
     dft_reg<R, true>(x);
 #pragma unroll
     for (int n = 0; n < R; ++n) out[base + (int64_t)n * Sj] = x[n];
+}
+
+// ---- Rows resident in LDS (lds_fft.h): one workgroup per row, HBM touched once each way.
+// Forward transform of zero-padded real rows (the filter transform): src (nrows, len) fp32 -> spec
+// (nrows, M) in position order.  reversed: see k_load_padded.
+__global__ void __launch_bounds__(LDS_ROW_THREADS) k_rows_fwd_lds(const float *__restrict__ src, double2 *__restrict__ spec,
+                                                                 const double2 *__restrict__ w, FacList fl, int M,
+                                                                 int64_t len, int tws, bool reversed)
+{
+    extern __shared__ double2 XD[];
+    const int64_t row = blockIdx.x;
+    for (int n = threadIdx.x; n < M; n += LDS_ROW_THREADS) {
+        const int t = (reversed && n != 0) ? M - n : n;
+        XD[lds_slot(n)] = make_double2(t < len ? (double)src[row * len + t] : 0.0, 0.0);
+    }
+    __syncthreads();
+    lds_forward(XD, w, fl, M, tws);
+    for (int n = threadIdx.x; n < M; n += LDS_ROW_THREADS) spec[row * M + n] = XD[lds_slot(n)];
+}
+
+// Unnormalised inverse transform of position-ordered spectra, real part of the first Nk samples times scale
+// (the tail of the filter gradient).
+__global__ void __launch_bounds__(LDS_ROW_THREADS) k_rows_inv_dk_lds(const float2 *__restrict__ spec, float *__restrict__ dk,
+                                                                    const float2 *__restrict__ w, FacList fl, int M,
+                                                                    int64_t Nk, float scale)
+{
+    extern __shared__ float2 XF[];
+    const int64_t row = blockIdx.x;
+    for (int n = threadIdx.x; n < M; n += LDS_ROW_THREADS) XF[lds_slot(n)] = spec[row * M + n];
+    __syncthreads();
+    lds_inverse(XF, w, fl, M, 1);
+    for (int n = threadIdx.x; n < Nk; n += LDS_ROW_THREADS) dk[row * Nk + n] = XF[lds_slot(n)].x * scale;
 }
 
 inline unsigned grid_of(int64_t n, int bs) { return (unsigned)((n + bs - 1) / bs); }
@@ -370,9 +387,42 @@ int staged_forward(const fftconv_plan *p, const void *u, const void *kf, void *y
     }
 }
 
+// Largest row the LDS-resident kernels take: 8192 fp64 or 16384 fp32 complex points with their padding.
+constexpr size_t LDS_ROW_MAX = (8192 + 512) * sizeof(double2);
+
+static int raise_lds_limit(const void *kern, bool *done)
+{
+    if (!*done) {
+        FC_HIP(hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_ROW_MAX));
+        *done = true;
+    }
+    return FFTCONV_OK;
+}
+
+// Rows short enough for LDS take the one-kernel transform: *ran says whether this was one (otherwise the
+// caller runs the stages through HBM).
+static int rows_fwd_lds(const fftconv_plan *p, const FacList &fl, int64_t M, int64_t tws, const float *k, int64_t Nk,
+                        int64_t nh, bool reversed, hipStream_t s, double2 **result, bool *ran)
+{
+    const size_t bytes = lds_row_bytes(M, sizeof(double2));
+    *ran = bytes <= LDS_ROW_MAX && lds_factors_ok(fl);
+    if (!*ran) return FFTCONV_OK;
+    static bool raised = false;
+    const int rc = raise_lds_limit((const void *)k_rows_fwd_lds, &raised);
+    if (rc) return rc;
+    hipLaunchKernelGGL(k_rows_fwd_lds, dim3((unsigned)nh), dim3(LDS_ROW_THREADS), bytes, s, k, p->filt_a, p->st.w64, fl,
+                       (int)M, Nk, (int)tws, reversed);
+    FC_HIP(hipGetLastError());
+    *result = p->filt_a;
+    return FFTCONV_OK;
+}
+
 int staged_filter_transform(const fftconv_plan *p, const float *k, int64_t Nk, int64_t h0, int64_t nh, hipStream_t s,
                             double2 **result, bool adjoint)
 {
+    bool ran = false;
+    const int rc = rows_fwd_lds(p, fac_list(p), p->M, 1, k + h0 * Nk, Nk, nh, adjoint, s, result, &ran);
+    if (rc || ran) return rc;
     const int bs = 256;
     hipLaunchKernelGGL((k_load_padded<double2, float>), dim3(grid_for(nh * p->M, bs)), dim3(bs), 0, s, k + h0 * Nk,
                        p->filt_a, Nk, p->M, nh, adjoint);
@@ -391,19 +441,6 @@ FacList staged_factors_for(int64_t M)
     if (rem) fl.fac[nf++] = 1 << rem;
     fl.nf = nf;
     return fl;
-}
-
-// The same transform at a shorter length Msub (a divisor of the plan's fft_size), reusing the
-// plan's twiddle table with a stride and its scratch buffers.
-int staged_filter_transform_sub(const fftconv_plan *p, int64_t Msub, const float *k, int64_t Nk, int64_t h0,
-                                int64_t nh, hipStream_t s, double2 **result)
-{
-    const int bs = 256;
-    hipLaunchKernelGGL((k_load_padded<double2, float>), dim3(grid_for(nh * Msub, bs)), dim3(bs), 0, s, k + h0 * Nk,
-                       p->filt_a, Nk, Msub, nh);
-    FC_HIP(hipGetLastError());
-    return run_stages_fwd<double2>(staged_factors_for(Msub), Msub, p->M / Msub, p->filt_a, p->filt_b, p->st.w64, nh, s,
-                                   result);
 }
 
 int staged_pack_kf(const fftconv_plan *p, const double2 *spec, int64_t h0, int64_t nh, const uint8_t *keep_dev,
@@ -466,6 +503,16 @@ int staged_inverse_to_dk(const fftconv_plan *p, float2 *spec, float2 *other, int
 {
     const int bs = 256;
     const int64_t M = p->M;
+    const size_t lds_bytes = lds_row_bytes(M, sizeof(float2));
+    if (lds_bytes <= LDS_ROW_MAX && lds_factors_ok(fac_list(p))) {
+        static bool raised = false;
+        const int rc = raise_lds_limit((const void *)k_rows_inv_dk_lds, &raised);
+        if (rc) return rc;
+        hipLaunchKernelGGL(k_rows_inv_dk_lds, dim3((unsigned)nrows), dim3(LDS_ROW_THREADS), lds_bytes, s, spec, dk,
+                           p->st.w32, fac_list(p), (int)M, Nk, 1.0f / (float)M);
+        FC_HIP(hipGetLastError());
+        return FFTCONV_OK;
+    }
     float2 *src = spec, *dst = other;
     int64_t S = 1, R = M;
     for (int i = p->st.nf - 1; i >= 0; --i) {
