@@ -179,7 +179,11 @@ def main():
         dk = torch.empty((w.H, w.filter_len), dtype=torch.float32, device=dev)
         du = torch.empty_like(u)
         times = {}
-        for name, fn in (("du", lambda: plan.backward_input(dy, kfa, out=du)),
+        # the calls of a training step besides the forward pass: k changes every step, so both filter
+        # transforms are part of it
+        for name, fn in (("filter_fft", lambda: plan.filter_fft(kd)),
+                         ("filter_fft_adjoint", lambda: plan.filter_fft_adjoint(kd)),
+                         ("du", lambda: plan.backward_input(dy, kfa, out=du)),
                          ("dk", lambda: plan.backward_filter(u, dy, w.filter_len, out=dk))):
             n_it = max(3, min(args.steps, 30))
             for _ in range(3):
@@ -196,7 +200,8 @@ def main():
                           "dtype": w.dtype, "value": times["du"] + times["dk"], "higher_is_better": False,
                           "config": {"workload": "%s backward: B=%d H=%d N=%d fft_size=%d Nk=%d" %
                                      (w.name, w.B, w.H, w.N, w.fft_size, w.filter_len),
-                                     "du_ms": times["du"], "dk_ms": times["dk"], "path": plan.path}}))
+                                     "du_ms": times["du"], "dk_ms": times["dk"], "filter_fft_ms": times["filter_fft"],
+                                     "filter_fft_adjoint_ms": times["filter_fft_adjoint"], "path": plan.path}}))
         return
 
     def step():

@@ -329,11 +329,10 @@ int fftconv_backward_input(const fftconv_plan *p, const void *dy, const void *k_
 size_t fftconv_workspace_bytes_backward_filter(const fftconv_plan *p, int64_t B)
 {
     if (!p || B <= 0) return 0;
-    if (f3::fused3_dk_supported(p))        // accumulated spectra of every channel (8192 slots each, whatever the plan's
-                                           // fft_size) + one ping-pong pair of a chunk of them
-        return (size_t)(p->H * 8192 + 2 * staged_backward_chunk(p) * p->M) * sizeof(float2);
+    if (f3::fused3_dk_supported(p))        // accumulated spectra of every channel (8192 slots each, whatever the plan's fft_size)
+        return (size_t)(p->H * 8192) * sizeof(float2);
     if (f3::fused3_big_dk_supported(p))
-        return (size_t)((p->H + 2 * staged_backward_chunk(p)) * p->M) * sizeof(float2);
+        return (size_t)(2 * p->H * p->M) * sizeof(float2);
     return staged_backward_filter_bytes(p);
 }
 
@@ -357,27 +356,14 @@ int fftconv_backward_filter(const fftconv_plan *p, const void *u, const void *dy
     }
     hipStream_t s = (hipStream_t)stream;
     if (B > 0 && f3::fused3_dk_supported(p)) {
-        float2 *dkf = (float2 *)workspace;
-        const int64_t chunk = staged_backward_chunk(p);
-        float2 *a = dkf + p->H * 8192, *b = a + chunk * p->M;       // 8192 accumulator slots per channel
-        rc = f3::fused3_dk_accumulate(p, u, dy, dkf, B, s);
-        for (int64_t h0 = 0; !rc && h0 < p->H; h0 += chunk) {
-            const int64_t nh = p->H - h0 < chunk ? p->H - h0 : chunk;
-            rc = f3::fused3_dk_unpack(p, dkf, a, h0, nh, s);
-            if (!rc) rc = staged_inverse_to_dk(p, a, b, nh, dk + h0 * Nk, Nk, s);
-        }
+        rc = f3::fused3_dk_accumulate(p, u, dy, workspace, B, s);       // 8192 accumulator slots per channel
+        if (!rc) rc = f3::fused3_dk_finish(p, workspace, dk, Nk, s);
         return rc;
     }
     if (B > 0 && f3::fused3_big_dk_supported(p)) {
-        float2 *dkf = (float2 *)workspace;
-        const int64_t chunk = staged_backward_chunk(p);
-        float2 *a = dkf + p->H * p->M, *b = a + chunk * p->M;
+        float2 *dkf = (float2 *)workspace;                          // accumulated spectra, then a scratch row each
         rc = f3::fused3_big_dk_accumulate(p, u, dy, dkf, B, s);
-        for (int64_t h0 = 0; !rc && h0 < p->H; h0 += chunk) {
-            const int64_t nh = p->H - h0 < chunk ? p->H - h0 : chunk;
-            rc = f3::fused3_big_dk_unpack(p, dkf, a, h0, nh, s);
-            if (!rc) rc = staged_inverse_to_dk(p, a, b, nh, dk + h0 * Nk, Nk, s);
-        }
+        if (!rc) rc = f3::fused3_big_dk_finish(p, dkf, dkf + p->H * p->M, dk, Nk, s);
         return rc;
     }
     return staged_backward_filter(p, u, dy, dk, Nk, B, workspace, s);

@@ -188,11 +188,11 @@ int64_t staged_backward_chunk(const fftconv_plan *p);
 namespace f3 {
 bool fused3_dk_supported(const fftconv_plan *p);
 int fused3_dk_accumulate(const fftconv_plan *p, const void *u, const void *dy, void *dkf, int64_t B, hipStream_t s);
-int fused3_dk_unpack(const fftconv_plan *p, const void *dkf, void *spec, int64_t h0, int64_t nh, hipStream_t s);
+int fused3_dk_finish(const fftconv_plan *p, const void *dkf, float *dk, int64_t Nk, hipStream_t s);
 // the same for fft 16384 plans (fused3_big.hip); dkf = H * 16384 float2
 bool fused3_big_dk_supported(const fftconv_plan *p);
 int fused3_big_dk_accumulate(const fftconv_plan *p, const void *u, const void *dy, void *dkf, int64_t B, hipStream_t s);
-int fused3_big_dk_unpack(const fftconv_plan *p, const void *dkf, void *spec, int64_t h0, int64_t nh, hipStream_t s);
+int fused3_big_dk_finish(const fftconv_plan *p, const void *dkf, void *tmp, float *dk, int64_t Nk, hipStream_t s);
 }  // namespace f3
 
 // ---- short transforms, fft_size 256 .. 4096, any dtype (small.hip); radices reported in f3.N1..N3

@@ -877,20 +877,50 @@ __global__ void __launch_bounds__(NT, 2) k_fused3_big_dk(const uint16_t *__restr
 }
 
 // dk_f of the kernel above ([h][k1][k2 tile][k3 tile][r][lane], lane = (k3 slot / 4 % 4) * 16 + k2 % 16, k3 in the
-// order big_sigma()) -> position order of the generic inverse stages.
+// order big_sigma()) -> dk, in two kernels.  The inverse transform runs the factors of the generic path
+// (16, 16, 16, M / 4096) last to first; all but the first act inside contiguous blocks of M / 16 positions, and
+// block d0 (the low four bits of k1) is made of the bins of k1 = d0 and d0 + 16: two contiguous runs of dk_f.
+// Kernel 1, one workgroup per (channel, block): the two runs -> LDS at their positions, the length-M/16
+// inverse there (twiddle table of W_M with stride 16), natural order out to a scratch row.  Kernel 2: the
+// remaining factor across the 16 blocks, real part, 1/M, the first Nk samples.
+constexpr int DK_BLK_THREADS = 256;
 template <int N2>
-__global__ void k_unpack_big_dkf(const float2 *dkf, float2 *spec, FacList fl, int64_t nh)
+__global__ void __launch_bounds__(DK_BLK_THREADS) k_big_dk_blocks(const float2 *__restrict__ dkf, float2 *__restrict__ tmp,
+                                                                 const float2 *__restrict__ w, FacList fl, FacList fl_tail)
 {
-    constexpr int64_t BM = BigGeo<N2>::M;
-    constexpr int R2 = BigGeo<N2>::R2;
+    constexpr int BM = BigGeo<N2>::M, BLK = BM / 16, RUN = BLK / 2, R2 = BigGeo<N2>::R2;
+    __shared__ float2 XS[BLK + BLK / 16];
+    const int d0 = blockIdx.x;
+    const int64_t h = blockIdx.y;
+    for (int i = threadIdx.x; i < BLK; i += DK_BLK_THREADS) {
+        const int k1 = d0 + 16 * (i / RUN), j = i % RUN;                       // slot (k1, j) of dk_f[h]
+        const int lane = j % 64, r = (j / 64) % 4, t3 = (j / 256) % 2, t2 = (j / 512) % R2;
+        const int k2 = 16 * t2 + lane % 16, k3 = big_sigma(16 * t3 + 4 * (lane / 16) + r);
+        const int f = k1 + 32 * k2 + 32 * N2 * k3;
+        XS[lds_slot(lds_pos(f, fl, BM) - d0 * BLK)] = dkf[h * BM + k1 * RUN + j];
+    }
+    __syncthreads();
+    lds_inverse(XS, w, fl_tail, BLK, 16);
+    for (int i = threadIdx.x; i < BLK; i += DK_BLK_THREADS) tmp[h * BM + d0 * BLK + i] = XS[lds_slot(i)];
+}
+
+template <int N2>
+__global__ void k_big_dk_last(const float2 *__restrict__ tmp, float *__restrict__ dk, const float2 *__restrict__ w,
+                              int64_t H, int64_t Nk)
+{
+    constexpr int BM = BigGeo<N2>::M, BLK = BM / 16;
     const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= nh * BM) return;
-    const int64_t h = idx / BM, f = idx % BM;
-    const int k1 = (int)(f % 32), k2 = (int)((f / 32) % N2), k3 = (int)(f / (32 * N2));
-    const int m3 = big_sigma_inv(k3);
-    const int64_t slot =
-        ((((int64_t)k1 * R2 + k2 / 16) * 2 + m3 / 16) * 4 + m3 % 4) * 64 + ((m3 % 16) / 4) * 16 + k2 % 16;
-    spec[h * BM + freq_to_pos(f, fl, BM)] = dkf[h * BM + slot];
+    if (idx >= H * BLK) return;
+    const int64_t h = idx / BLK;
+    const int r = (int)(idx % BLK);
+    if (r >= Nk) return;
+    float2 x[16];
+#pragma unroll
+    for (int k = 0; k < 16; ++k) x[k] = cmul_conj(tmp[h * BM + k * BLK + r], w[k * r]);
+    dft_reg<16, true>(x);
+#pragma unroll
+    for (int n = 0; n < 16; ++n)
+        if (n * BLK + r < Nk) dk[h * Nk + n * BLK + r] = x[n].x * (1.0f / (float)BM);
 }
 
 // Filter transform, one workgroup per channel and nothing but the taps and k_f in HBM.  The taps are real, so
@@ -1239,18 +1269,32 @@ int fused3_big_dk_accumulate(const fftconv_plan *p, const void *u, const void *d
     return p->M == 32768 ? big_dk_accumulate_t<32>(p, u, dy, dkf, B, s) : big_dk_accumulate_t<16>(p, u, dy, dkf, B, s);
 }
 
-int fused3_big_dk_unpack(const fftconv_plan *p, const void *dkf, void *spec, int64_t h0, int64_t nh, hipStream_t s)
+template <int N2>
+static int big_dk_finish_t(const fftconv_plan *p, const void *dkf, void *tmp, float *dk, int64_t Nk, hipStream_t s)
 {
+    constexpr int BLK = BigGeo<N2>::M / 16;
+    const FacList fl = staged_fac_list(p);
+    if (fl.nf < 2 || fl.fac[0] != 16) {
+        set_error("fftconv_backward_filter: unexpected factor list for fft_size=%lld", (long long)p->M);
+        return FFTCONV_EUNSUPPORTED;
+    }
+    FacList tail;
+    tail.nf = fl.nf - 1;
+    for (int i = 0; i < MAX_FACTORS; ++i) tail.fac[i] = i + 1 < fl.nf ? fl.fac[i + 1] : 0;
+    hipLaunchKernelGGL(k_big_dk_blocks<N2>, dim3(16, (unsigned)p->H), dim3(DK_BLK_THREADS), 0, s, (const float2 *)dkf,
+                       (float2 *)tmp, (const float2 *)p->st.w32, fl, tail);
+    FC_HIP(hipGetLastError());
     const int bs = 256;
-    const unsigned grid = (unsigned)((nh * p->M + bs - 1) / bs);
-    if (p->M == 32768)
-        hipLaunchKernelGGL(k_unpack_big_dkf<32>, dim3(grid), dim3(bs), 0, s, (const float2 *)dkf + h0 * p->M,
-                           (float2 *)spec, staged_fac_list(p), nh);
-    else
-        hipLaunchKernelGGL(k_unpack_big_dkf<16>, dim3(grid), dim3(bs), 0, s, (const float2 *)dkf + h0 * p->M,
-                           (float2 *)spec, staged_fac_list(p), nh);
+    hipLaunchKernelGGL(k_big_dk_last<N2>, dim3((unsigned)((p->H * BLK + bs - 1) / bs)), dim3(bs), 0, s, (const float2 *)tmp,
+                       dk, (const float2 *)p->st.w32, p->H, Nk);
     FC_HIP(hipGetLastError());
     return FFTCONV_OK;
+}
+
+// dkf: the accumulated spectra of fused3_big_dk_accumulate; tmp: H * fft_size float2 of scratch
+int fused3_big_dk_finish(const fftconv_plan *p, const void *dkf, void *tmp, float *dk, int64_t Nk, hipStream_t s)
+{
+    return p->M == 32768 ? big_dk_finish_t<32>(p, dkf, tmp, dk, Nk, s) : big_dk_finish_t<16>(p, dkf, tmp, dk, Nk, s);
 }
 
 }  // namespace f3

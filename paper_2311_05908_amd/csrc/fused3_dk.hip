@@ -18,6 +18,7 @@
 // registers until the channel's last pair, when it is written out in the kernel's k_f order.  The
 // inverse transform of the H accumulated spectra runs afterwards on the generic fp32 stages.
 #include "fused3_common.h"
+#include "lds_fft.h"
 
 namespace fftconv {
 namespace f3 {
@@ -223,26 +224,39 @@ __global__ void __launch_bounds__(NT) k_fused3_dk(const uint16_t *__restrict__ u
     }
 }
 
-// dk_f from the kernel's order (slot of frequency f as in the fused k_f layout) to the position order of
-// the generic inverse stages.
-// groups > 1: bin f = k1' + N1s (k2 + 16 k3) of the length-Ms transform is the sum over the groups of the slots
-// k1 = g N1s + k1'.
-__global__ void k_unpack_dkf(const float2 *dkf, float2 *spec, FacList fl, int64_t nh, int groups)
+// dk_f in the kernel's order (slot (k1 * 4 + r) * 64 + lane as in the fused k_f layout) -> dk, one workgroup
+// per channel: the 8192 slots are read in order and scattered to their positions in LDS, the unnormalised
+// inverse transform of length Ms = 8192 / groups runs there (lds_fft.h), real part times 1/Ms of the first Nk
+// samples goes out.  groups > 1: bin k1' + N1s (k2 + 16 k3) of the short transform is the sum over the groups g
+// of the slots k1 = g N1s + k1'; the groups are added one after the other (a fixed order).
+constexpr int DK_FIN_THREADS = 512;
+__global__ void __launch_bounds__(DK_FIN_THREADS) k_dk_finish(const float2 *__restrict__ dkf, float *__restrict__ dk,
+                                                             const float2 *__restrict__ w, FacList fl, int64_t Nk, int groups)
 {
-    const int64_t Ms = G::M / groups;
-    const int N1s = N1 / groups;
-    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= nh * Ms) return;
-    const int64_t h = idx / Ms, f = idx % Ms;
-    const int k1s = (int)(f % N1s);
-    const int64_t rest = f / N1s;                            // k2 + 16 k3
-    float2 acc = make_float2(0.f, 0.f);
+    extern __shared__ float2 XD[];
+    const int Ms = G::M / groups, N1s = N1 / groups;
+    const int64_t h = blockIdx.x;
+    const int per_group = G::M / groups;                     // slots of one group: k1 in [g N1s, (g + 1) N1s)
     for (int g = 0; g < groups; ++g) {
-        const float2 v = dkf[h * G::M + fused3_kf_slot_8192((int64_t)(g * N1s + k1s) + (int64_t)N1 * rest)];
-        acc.x += v.x;
-        acc.y += v.y;
+        for (int i = threadIdx.x; i < per_group; i += DK_FIN_THREADS) {
+            const int d = g * per_group + i;
+            const int lane = d % 64, r = (d / 64) % 4, k1 = d / 256;
+            const int k2 = lane % 16, k3 = k3_at_index(4 * (lane / 16) + r, 16);
+            const int fs = (k1 % N1s) + N1s * (k2 + 16 * k3);
+            const int slot = lds_slot(lds_pos(fs, fl, Ms));
+            float2 v = dkf[h * G::M + d];
+            if (g > 0) {
+                const float2 o = XD[slot];
+                v.x += o.x;
+                v.y += o.y;
+            }
+            XD[slot] = v;
+        }
+        __syncthreads();
     }
-    spec[h * Ms + freq_to_pos(f, fl, Ms)] = acc;
+    lds_inverse(XD, w, fl, Ms, 1);
+    const float scale = 1.0f / (float)Ms;
+    for (int n = threadIdx.x; n < Nk; n += DK_FIN_THREADS) dk[h * Nk + n] = XD[lds_slot(n)].x * scale;
 }
 
 }  // namespace
@@ -283,12 +297,16 @@ int fused3_dk_accumulate(const fftconv_plan *p, const void *u, const void *dy, v
     return FFTCONV_OK;
 }
 
-int fused3_dk_unpack(const fftconv_plan *p, const void *dkf, void *spec, int64_t h0, int64_t nh, hipStream_t s)
+int fused3_dk_finish(const fftconv_plan *p, const void *dkf, float *dk, int64_t Nk, hipStream_t s)
 {
-    const int bs = 256;
-    const unsigned grid = (unsigned)((nh * p->M + bs - 1) / bs);
-    hipLaunchKernelGGL(k_unpack_dkf, dim3(grid), dim3(bs), 0, s, (const float2 *)dkf + h0 * G::M, (float2 *)spec,
-                       staged_fac_list(p), nh, (int)(G::M / p->M));
+    static bool raised = false;
+    if (!raised) {
+        FC_HIP(hipFuncSetAttribute((const void *)k_dk_finish, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   (int)lds_row_bytes(G::M, sizeof(float2))));
+        raised = true;
+    }
+    hipLaunchKernelGGL(k_dk_finish, dim3((unsigned)p->H), dim3(DK_FIN_THREADS), lds_row_bytes(p->M, sizeof(float2)), s,
+                       (const float2 *)dkf, dk, (const float2 *)p->st.w32, staged_fac_list(p), Nk, (int)(G::M / p->M));
     FC_HIP(hipGetLastError());
     return FFTCONV_OK;
 }

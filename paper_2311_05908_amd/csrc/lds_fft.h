@@ -37,7 +37,7 @@ inline size_t lds_row_bytes(int64_t M, size_t elem) { return (size_t)(M + M / 16
 template <int R, bool INV, typename V>
 __device__ inline void lds_stage(V *X, const V *__restrict__ w, int M, int Sj, int Rj, int tws)
 {
-    for (int t = threadIdx.x; t < M / R; t += LDS_ROW_THREADS) {
+    for (int t = threadIdx.x; t < M / R; t += blockDim.x) {
         const int r = t % Sj, prefix = t / Sj;
         const int base = prefix * (R * Sj) + r;
         V x[R];
