@@ -83,6 +83,7 @@ int fftconv_plan_create(fftconv_plan **out, int64_t N, int64_t fft_size, int64_t
     int rc = FFTCONV_OK;
     if (hipGetDevice(&p->device) != hipSuccess) rc = FFTCONV_EHIP;
     if (rc == FFTCONV_OK) rc = staged_init(p);      // tables of the filter transform; fallback forward
+    if (rc == FFTCONV_OK && long_fft_supported(p)) rc = long_fft_init(p);
     if (rc == FFTCONV_OK && hipMalloc((void **)&p->keep_dev, (size_t)(fft_size > MAX_BLOCKS ? fft_size : MAX_BLOCKS)) != hipSuccess) {
         set_error("fftconv_plan_create: hipMalloc of the block mask failed");
         rc = FFTCONV_ENOMEM;
@@ -114,6 +115,7 @@ int fftconv_plan_destroy(fftconv_plan *p)
     if (!p) return FFTCONV_OK;
     fused3_destroy(p);
     staged_destroy(p);
+    long_fft_destroy(p);
     if (p->keep_dev) (void)hipFree(p->keep_dev);
     delete p;
     return FFTCONV_OK;
@@ -172,7 +174,14 @@ static int filter_fft_impl(const fftconv_plan *p, const float *k, int64_t Nk, co
         rc = fused3_filter(p, k, Nk, adjoint, keep_dev, n_blocks, k_f, s);
         if (rc) return rc;
     }
-    for (int64_t h0 = 0; p->path != PATH_FUSED3 && h0 < p->H; h0 += p->filt_chunk) {
+    const bool long_rows = p->path == PATH_MULTIPASS && long_fft_supported(p);
+    // fp32 in two kernels per chunk; the scratch buffer is sized for fp64 spectra, so it takes twice the rows
+    for (int64_t h0 = 0; long_rows && h0 < p->H; h0 += 2 * p->filt_chunk) {
+        const int64_t nh = p->H - h0 < 2 * p->filt_chunk ? p->H - h0 : 2 * p->filt_chunk;
+        rc = long_filter_transform(p, k + h0 * Nk, Nk, h0, nh, adjoint, keep_dev, n_blocks, (float2 *)p->filt_a, k_f, s);
+        if (rc) return rc;
+    }
+    for (int64_t h0 = 0; p->path != PATH_FUSED3 && !long_rows && h0 < p->H; h0 += p->filt_chunk) {
         int64_t nh = p->H - h0 < p->filt_chunk ? p->H - h0 : p->filt_chunk;
         double2 *spec = nullptr;
         rc = staged_filter_transform(p, k, Nk, h0, nh, s, &spec, adjoint);
@@ -333,6 +342,7 @@ size_t fftconv_workspace_bytes_backward_filter(const fftconv_plan *p, int64_t B)
         return (size_t)(p->H * 8192) * sizeof(float2);
     if (f3::fused3_big_dk_supported(p))
         return (size_t)(2 * p->H * p->M) * sizeof(float2);
+    if (long_fft_supported(p)) return long_backward_filter_bytes(p);
     return staged_backward_filter_bytes(p);
 }
 
@@ -366,6 +376,7 @@ int fftconv_backward_filter(const fftconv_plan *p, const void *u, const void *dy
         if (!rc) rc = f3::fused3_big_dk_finish(p, dkf, dkf + p->H * p->M, dk, Nk, s);
         return rc;
     }
+    if (long_fft_supported(p)) return long_backward_filter(p, u, dy, dk, Nk, B, workspace, s);
     return staged_backward_filter(p, u, dy, dk, Nk, B, workspace, s);
 }
 

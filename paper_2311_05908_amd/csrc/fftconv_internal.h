@@ -94,6 +94,7 @@ struct fftconv_plan {
     int64_t filt_chunk = 0;           // channels per pass through the scratch
     int64_t fwd_chunk_cap = 0;        // staged forward: max sequences per pass
     uint8_t *keep_dev = nullptr;      // device copy of a frequency-block mask (sparse filter transform)
+    float2 *long_tw = nullptr;        // twiddle tables of the two-kernel long transforms (long_fft.hip)
 };
 
 namespace fftconv {
@@ -115,6 +116,16 @@ int staged_pack_kf(const fftconv_plan *p, const double2 *spec, int64_t h0, int64
                    const uint8_t *keep_dev, int64_t n_blocks, void *kf, hipStream_t s);
 FacList staged_fac_list(const fftconv_plan *p);
 FacList staged_factors_for(int64_t M);
+
+// ---- fp32 transforms of long rows in two kernels per direction (long_fft.hip)
+bool long_fft_supported(const fftconv_plan *p);
+int long_fft_init(fftconv_plan *p);
+void long_fft_destroy(fftconv_plan *p);
+int long_filter_transform(const fftconv_plan *p, const float *k, int64_t Nk, int64_t h0, int64_t nh, bool adjoint,
+                          const uint8_t *keep_dev, int64_t n_blocks, float2 *tmp, void *kf, hipStream_t s);
+size_t long_backward_filter_bytes(const fftconv_plan *p);
+int long_backward_filter(const fftconv_plan *p, const void *u, const void *dy, float *dk, int64_t Nk, int64_t B,
+                         void *workspace, hipStream_t s);
 
 // ---- fused 3-stage path (fused3.hip)
 bool fused3_supported(int64_t N, int64_t M, int dtype);

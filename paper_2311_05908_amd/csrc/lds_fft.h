@@ -34,22 +34,52 @@ constexpr int LDS_ROW_THREADS = 512;
 __device__ inline int lds_slot(int p) { return p + (p >> 4); }
 inline size_t lds_row_bytes(int64_t M, size_t elem) { return (size_t)(M + M / 16) * elem; }
 
+// The R twiddles W^{k e}, k < R, of one butterfly.  A gather from the table costs the vector-memory path one
+// cache-line lookup per lane (the lanes' exponents are k e apart), which is what bounded these kernels when all
+// R - 1 were gathered; so only the multiples of 4 e come from the table (tw(x) returns W^x) and the rest are
+// products with W^e, W^{2e}, W^{3e}: at most three roundings on top of the table's.
+template <int R, typename V, typename TW> __device__ __forceinline__ void stage_twiddles(V (&t)[R], const TW &tw, int64_t e)
+{
+    t[0].x = 1;
+    t[0].y = 0;
+    t[1] = tw(e);
+    if constexpr (R > 2) {
+        t[2] = cmul(t[1], t[1]);
+        t[3] = cmul(t[2], t[1]);
+    }
+    if constexpr (R > 4) {
+#pragma unroll
+        for (int k = 4; k < R; k += 4) {
+            t[k] = tw(k * e);
+            t[k + 1] = cmul(t[k], t[1]);
+            t[k + 2] = cmul(t[k], t[2]);
+            t[k + 3] = cmul(t[k], t[3]);
+        }
+    }
+}
+
+template <typename V> struct TwTable {         // W^x = w[x]
+    const V *w;
+    __device__ __forceinline__ V operator()(int64_t x) const { return w[x]; }
+};
+
 template <int R, bool INV, typename V>
 __device__ inline void lds_stage(V *X, const V *__restrict__ w, int M, int Sj, int Rj, int tws)
 {
+    const TwTable<V> tw{w};
     for (int t = threadIdx.x; t < M / R; t += blockDim.x) {
         const int r = t % Sj, prefix = t / Sj;
         const int base = prefix * (R * Sj) + r;
-        V x[R];
+        V x[R], c[R];
+        stage_twiddles<R>(c, tw, (int64_t)Rj * r * tws);
 #pragma unroll
         for (int n = 0; n < R; ++n) {
             x[n] = X[lds_slot(base + n * Sj)];
-            if (INV) x[n] = cmul_conj(x[n], w[(int64_t)n * Rj * r * tws]);
+            if (INV) x[n] = cmul_conj(x[n], c[n]);
         }
         dft_reg<R, INV>(x);
 #pragma unroll
-        for (int k = 0; k < R; ++k)
-            X[lds_slot(base + k * Sj)] = INV ? x[k] : cmul(x[k], w[(int64_t)k * Rj * r * tws]);
+        for (int k = 0; k < R; ++k) X[lds_slot(base + k * Sj)] = INV ? x[k] : cmul(x[k], c[k]);
     }
 }
 
@@ -85,6 +115,18 @@ __device__ inline int lds_pos(int f, const FacList &fl, int M)
         f >>= lg;
     }
     return pos;
+}
+// the inverse of lds_pos(): the frequency held at a position
+__device__ inline int lds_freq(int pos, const FacList &fl, int M)
+{
+    int f = 0, lg_s = __ffs(M) - 1, lg_r = 0;
+    for (int i = 0; i < fl.nf; ++i) {
+        const int lg = __ffs(fl.fac[i]) - 1;
+        lg_s -= lg;
+        f |= ((pos >> lg_s) & (fl.fac[i] - 1)) << lg_r;
+        lg_r += lg;
+    }
+    return f;
 }
 __device__ inline float lds_mask_weight(const uint8_t *keep, int64_t n_blocks, int f, int M)
 {

@@ -1,0 +1,402 @@
+// fp32 transforms of rows too long for LDS (fft_size 16384 .. 2^22), two kernels per direction instead of one
+// per factor: the decomposition of the generic path (Section 3.2, order-p Monarch form; decimation in
+// frequency, position order out) with fft_size = A * 8192.
+//   forward:  "columns" - the factors of A act at stride 8192: a workgroup takes C = 8192 / A adjacent columns
+//             of the (A, 8192) view of a row into LDS (8192 points), runs those stages there with the twiddles
+//             W_M^{k R r} of the full length and writes the tile back in place;
+//             "blocks"  - the remaining factors act inside contiguous blocks of 8192 positions: one workgroup
+//             per block, the length-8192 forward transform of lds_fft.h (its own table of W_8192).
+//   inverse:  the same two kernels mirrored (blocks first, then columns).
+// Users: the filter transform of the multi-pass plans (taps -> spectrum -> k_f, fp32 is ample for constants
+// that are rounded to 16 bits) and the filter gradient of every plan from fft_size 16384 up that has no
+// fused kernel (Section 3.1 "Kernel Fusion and Recomputation": dk = Re iFFT(sum_b conj(FFT(u_b)) FFT(dy_b))[0:Nk]).
+// Two batch rows share one complex transform there, z = x_b + i x_{b+1}: conj(Z_u) Z_dy is the wanted sum plus
+// i times a cross term that is itself the spectrum of a real sequence, so it ends up in the imaginary part of
+// the inverse transform, which is dropped.
+#include <hip/hip_runtime.h>
+#include <hip/hip_bf16.h>
+#include <hip/hip_fp16.h>
+
+#include <cmath>
+#include <vector>
+
+#include "fftconv_internal.h"
+#include "lds_fft.h"
+
+namespace fftconv {
+
+namespace {
+
+constexpr int LB = 8192;                       // block length: what one workgroup holds in LDS
+constexpr int LT = 512;                        // threads per workgroup
+constexpr size_t L_LDS = (size_t)(LB + LB / 16) * sizeof(float2);
+
+struct LongGeo {
+    int A = 0, C = 0;                          // outer length, columns per tile (A * C = 8192)
+    FacList flA, flB, fl;                      // factors of A, of 8192, and all of them (the position order)
+};
+
+LongGeo long_geo(int64_t M)
+{
+    LongGeo g;
+    g.A = (int)(M / LB);
+    g.C = LB / g.A;
+    int nf = 0, rem = g.A;
+    for (int i = 0; i < MAX_FACTORS; ++i) g.flA.fac[i] = g.flB.fac[i] = g.fl.fac[i] = 0;
+    while (rem >= 16) {
+        g.flA.fac[nf++] = 16;
+        rem /= 16;
+    }
+    if (rem > 1) g.flA.fac[nf++] = rem;
+    g.flA.nf = nf;
+    g.flB = staged_factors_for(LB);
+    g.fl.nf = g.flA.nf + g.flB.nf;
+    for (int i = 0; i < g.flA.nf; ++i) g.fl.fac[i] = g.flA.fac[i];
+    for (int i = 0; i < g.flB.nf; ++i) g.fl.fac[g.flA.nf + i] = g.flB.fac[i];
+    return g;
+}
+
+__device__ __forceinline__ float ld_real(const float *p, int64_t i) { return p[i]; }
+__device__ __forceinline__ float ld_real(const __half *p, int64_t i) { return __half2float(p[i]); }
+__device__ __forceinline__ float ld_real(const __hip_bfloat16 *p, int64_t i) { return __bfloat162float(p[i]); }
+
+// W_M^e of the full length as a product of two small tables, e = 2048 e_hi + e_lo: the exponents of the outer
+// stages are spread over the whole range, and gathers from a table of M entries (16 MB at 2^21) miss every cache
+struct LongTw {
+    const float2 *w8k;                         // W_8192^t, t < 8192: the table of the block transforms
+    const float2 *lo, *hi;                     // W_M^t, t < 2048; W_M^{2048 t}, t < M / 2048
+    __device__ __forceinline__ float2 operator()(int64_t e) const { return cmul(hi[e >> 11], lo[e & 2047]); }
+};
+
+// One stage of the outer part on a tile X[a][c] (a < A, c < C, slot a * C + c): factor R_ along a at stride
+// Sp, for every column; the twiddle exponent k Rj r uses the position r = rp * 8192 + (first column + c)
+// inside the full-length stage.
+template <int R_, bool INV>
+__device__ inline void cols_stage(float2 *X, const LongTw &w, int A, int C, int Sp, int Rj, int col0)
+{
+    const int nb = (A / R_) * C;
+    for (int t = threadIdx.x; t < nb; t += blockDim.x) {
+        const int c = t % C, q = t / C;
+        const int rp = q % Sp, prefix = q / Sp;
+        const int a0 = prefix * R_ * Sp + rp;
+        const int64_t rg = (int64_t)rp * LB + col0 + c;
+        float2 x[R_], tw[R_];
+        stage_twiddles<R_>(tw, w, (int64_t)Rj * rg);
+#pragma unroll
+        for (int n = 0; n < R_; ++n) {
+            x[n] = X[lds_slot((a0 + n * Sp) * C + c)];
+            if (INV) x[n] = cmul_conj(x[n], tw[n]);
+        }
+        dft_reg<R_, INV>(x);
+#pragma unroll
+        for (int k = 0; k < R_; ++k) X[lds_slot((a0 + k * Sp) * C + c)] = INV ? x[k] : cmul(x[k], tw[k]);
+    }
+}
+
+template <bool INV>
+__device__ inline void cols_stage_any(float2 *X, const LongTw &w, int A, int C, int Nj, int Sp, int Rj, int col0)
+{
+    switch (Nj) {
+    case 2: cols_stage<2, INV>(X, w, A, C, Sp, Rj, col0); break;
+    case 4: cols_stage<4, INV>(X, w, A, C, Sp, Rj, col0); break;
+    case 8: cols_stage<8, INV>(X, w, A, C, Sp, Rj, col0); break;
+    default: cols_stage<16, INV>(X, w, A, C, Sp, Rj, col0); break;
+    }
+}
+
+// Forward, columns: rows of real input (re from src_re, im from src_im or zero; `len` valid samples, zeros
+// beyond; reversed: position n holds sample (M - n) mod M) -> tmp (rows, M) after the factors of A.
+template <typename In>
+__global__ void __launch_bounds__(LT) k_long_fwd_cols(const In *__restrict__ src_re, const In *__restrict__ src_im,
+                                                     float2 *__restrict__ tmp, LongTw w, FacList flA, int A, int C, int64_t len,
+                                                     bool reversed)
+{
+    extern __shared__ float2 XL[];
+    const int64_t M = (int64_t)A * LB, row = blockIdx.y;
+    const int col0 = blockIdx.x * C;
+    for (int i = threadIdx.x; i < LB; i += LT) {
+        const int a = i / C, c = i % C;
+        int64_t n = (int64_t)a * LB + col0 + c;
+        if (reversed && n != 0) n = M - n;
+        float2 v = make_float2(0.f, 0.f);
+        if (n < len) {
+            v.x = ld_real(src_re, row * len + n);
+            if (src_im) v.y = ld_real(src_im, row * len + n);
+        }
+        XL[lds_slot(i)] = v;
+    }
+    __syncthreads();
+    int Sp = A, R = 1;
+    for (int i = 0; i < flA.nf; ++i) {
+        const int Nj = flA.fac[i];
+        Sp /= Nj;
+        cols_stage_any<false>(XL, w, A, C, Nj, Sp, R, col0);
+        __syncthreads();
+        R *= Nj;
+    }
+    for (int i = threadIdx.x; i < LB; i += LT) {
+        const int a = i / C, c = i % C;
+        tmp[row * M + (int64_t)a * LB + col0 + c] = XL[lds_slot(i)];
+    }
+}
+
+// Forward, blocks: tmp -> spectrum in position order.  MODE 0: store to out.  MODE 1: acc (+)= conj(other) * X
+// (other: the spectrum of the u rows, X: that of the dy rows; first: assign instead of add).
+template <int MODE>
+__global__ void __launch_bounds__(LT) k_long_fwd_blocks(const float2 *__restrict__ tmp, float2 *__restrict__ out,
+                                                       const float2 *__restrict__ other, LongTw w, FacList flB, int A,
+                                                       bool first)
+{
+    extern __shared__ float2 XL[];
+    const int64_t base = ((int64_t)blockIdx.y * A + blockIdx.x) * LB;
+    for (int i = threadIdx.x; i < LB; i += LT) XL[lds_slot(i)] = tmp[base + i];
+    __syncthreads();
+    lds_forward(XL, w.w8k, flB, LB, 1);
+    for (int i = threadIdx.x; i < LB; i += LT) {
+        const float2 x = XL[lds_slot(i)];
+        if (MODE == 0) {
+            out[base + i] = x;
+        } else {
+            const float2 a = other[base + i];
+            float2 v = make_float2(a.x * x.x + a.y * x.y, a.x * x.y - a.y * x.x);
+            if (!first) {
+                const float2 o = out[base + i];
+                v.x += o.x;
+                v.y += o.y;
+            }
+            out[base + i] = v;
+        }
+    }
+}
+
+// Forward, blocks, for the filter transform of the multi-pass plans: the block at position a' of a row holds the
+// bins f = ko + A f' of one outer frequency digit ko (the digit reversal of a'), f' < 8192 in position order; they
+// go straight to that digit's row of k_f, [h][ko][slot of f' in the 8192-point kernel's per-lane order] as 16-bit
+// (re, im) pairs, scaled by 1/M and by the frequency mask.
+template <bool F16>
+__global__ void __launch_bounds__(LT) k_long_fwd_blocks_kf(const float2 *__restrict__ tmp, uint32_t *__restrict__ kf, LongTw w,
+                                                          FacList flA, FacList flB, int A, int64_t h0,
+                                                          const uint8_t *__restrict__ keep, int64_t n_blocks)
+{
+    extern __shared__ float2 XL[];
+    const int64_t base = ((int64_t)blockIdx.y * A + blockIdx.x) * LB;
+    for (int i = threadIdx.x; i < LB; i += LT) XL[lds_slot(i)] = tmp[base + i];
+    __syncthreads();
+    lds_forward(XL, w.w8k, flB, LB, 1);
+    const int ko = lds_freq(blockIdx.x, flA, A);
+    const int M = A * LB;
+    uint32_t *dst = kf + ((h0 + blockIdx.y) * A + ko) * (int64_t)LB;
+    for (int d = threadIdx.x; d < LB; d += LT) {
+        const int lane = d % 64, r = (d / 64) % 4, k1 = d / 256;
+        const int k2 = lane % 16, k3 = k3_at_index(4 * (lane / 16) + r, 16);
+        const int fi = k1 + 32 * (k2 + 16 * k3);
+        const float2 v = XL[lds_slot(lds_pos(fi, flB, LB))];
+        const float sc = lds_mask_weight(keep, n_blocks, ko + A * fi, M) / (float)M;
+        uint16_t re, im;
+        if constexpr (F16) {
+            const __half a = __float2half_rn(v.x * sc), b = __float2half_rn(v.y * sc);
+            re = *(const uint16_t *)&a;
+            im = *(const uint16_t *)&b;
+        } else {
+            const __hip_bfloat16 a = __float2bfloat16(v.x * sc), b = __float2bfloat16(v.y * sc);
+            re = *(const uint16_t *)&a;
+            im = *(const uint16_t *)&b;
+        }
+        dst[d] = (uint32_t)re | ((uint32_t)im << 16);
+    }
+}
+
+// Inverse, blocks: spectrum in position order -> tmp after the factors of 8192 (unnormalised).
+__global__ void __launch_bounds__(LT) k_long_inv_blocks(const float2 *__restrict__ spec, float2 *__restrict__ tmp, LongTw w,
+                                                       FacList flB, int A)
+{
+    extern __shared__ float2 XL[];
+    const int64_t base = ((int64_t)blockIdx.y * A + blockIdx.x) * LB;
+    for (int i = threadIdx.x; i < LB; i += LT) XL[lds_slot(i)] = spec[base + i];
+    __syncthreads();
+    lds_inverse(XL, w.w8k, flB, LB, 1);
+    for (int i = threadIdx.x; i < LB; i += LT) tmp[base + i] = XL[lds_slot(i)];
+}
+
+// Inverse, columns: the factors of A, then real part times scale of the samples n < Nk -> dk (rows, Nk).
+__global__ void __launch_bounds__(LT) k_long_inv_cols_dk(const float2 *__restrict__ tmp, float *__restrict__ dk, LongTw w,
+                                                        FacList flA, int A, int C, int64_t Nk, float scale)
+{
+    extern __shared__ float2 XL[];
+    const int64_t M = (int64_t)A * LB, row = blockIdx.y;
+    const int col0 = blockIdx.x * C;
+    if (col0 >= Nk) return;                                 // every sample of this tile is n >= col0 >= Nk
+    for (int i = threadIdx.x; i < LB; i += LT) {
+        const int a = i / C, c = i % C;
+        XL[lds_slot(i)] = tmp[row * M + (int64_t)a * LB + col0 + c];
+    }
+    __syncthreads();
+    int Sp = 1, R = A;
+    for (int i = flA.nf - 1; i >= 0; --i) {
+        const int Nj = flA.fac[i];
+        R /= Nj;
+        cols_stage_any<true>(XL, w, A, C, Nj, Sp, R, col0);
+        __syncthreads();
+        Sp *= Nj;
+    }
+    for (int i = threadIdx.x; i < LB; i += LT) {
+        const int a = i / C, c = i % C;
+        const int64_t n = (int64_t)a * LB + col0 + c;
+        if (n < Nk) dk[row * Nk + n] = XL[lds_slot(i)].x * scale;
+    }
+}
+
+__global__ void k_zero_dk(float *x, int64_t n)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) x[i] = 0.f;
+}
+
+LongTw long_tw(const fftconv_plan *p)
+{
+    LongTw t;
+    t.w8k = p->long_tw;
+    t.lo = p->long_tw + LB;
+    t.hi = t.lo + 2048;
+    return t;
+}
+
+int raise_lds(const void *kern, bool *done)
+{
+    if (!*done) {
+        FC_HIP(hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)L_LDS));
+        *done = true;
+    }
+    return FFTCONV_OK;
+}
+
+template <typename In>
+int launch_fwd_cols(const LongGeo &g, const In *re, const In *im, float2 *tmp, const LongTw &w, int64_t rows, int64_t len,
+                    bool reversed, hipStream_t s)
+{
+    static bool raised = false;
+    const int rc = raise_lds((const void *)k_long_fwd_cols<In>, &raised);
+    if (rc) return rc;
+    hipLaunchKernelGGL(k_long_fwd_cols<In>, dim3((unsigned)g.A, (unsigned)rows), dim3(LT), L_LDS, s, re, im, tmp, w, g.flA,
+                       g.A, g.C, len, reversed);
+    FC_HIP(hipGetLastError());
+    return FFTCONV_OK;
+}
+
+template <int MODE>
+int launch_fwd_blocks(const LongGeo &g, const float2 *tmp, float2 *out, const float2 *other, const LongTw &w, int64_t rows,
+                      bool first, hipStream_t s)
+{
+    static bool raised = false;
+    const int rc = raise_lds((const void *)k_long_fwd_blocks<MODE>, &raised);
+    if (rc) return rc;
+    hipLaunchKernelGGL(k_long_fwd_blocks<MODE>, dim3((unsigned)g.A, (unsigned)rows), dim3(LT), L_LDS, s, tmp, out, other, w,
+                       g.flB, g.A, first);
+    FC_HIP(hipGetLastError());
+    return FFTCONV_OK;
+}
+
+template <typename IO>
+int long_backward_filter_t(const fftconv_plan *p, const IO *u, const IO *dy, float *dk, int64_t Nk, int64_t B,
+                           void *workspace, hipStream_t s)
+{
+    const LongGeo g = long_geo(p->M);
+    const LongTw tw = long_tw(p);
+    const int64_t M = p->M, N = p->N, H = p->H;
+    float2 *acc = (float2 *)workspace, *spec_u = acc + H * M, *tmp = spec_u + H * M;
+    if (B == 0) {
+        const int bs = 256;
+        hipLaunchKernelGGL(k_zero_dk, dim3((unsigned)((H * Nk + bs - 1) / bs)), dim3(bs), 0, s, dk, H * Nk);
+        FC_HIP(hipGetLastError());
+        return FFTCONV_OK;
+    }
+    for (int64_t b = 0; b < B; b += 2) {                      // rows b and b + 1 share a transform
+        const IO *u0 = u + b * H * N, *u1 = b + 1 < B ? u0 + H * N : nullptr;
+        const IO *d0 = dy + b * H * N, *d1 = b + 1 < B ? d0 + H * N : nullptr;
+        int rc = launch_fwd_cols<IO>(g, u0, u1, tmp, tw, H, N, false, s);
+        if (!rc) rc = launch_fwd_blocks<0>(g, tmp, spec_u, nullptr, tw, H, false, s);
+        if (!rc) rc = launch_fwd_cols<IO>(g, d0, d1, tmp, tw, H, N, false, s);
+        if (!rc) rc = launch_fwd_blocks<1>(g, tmp, acc, spec_u, tw, H, b == 0, s);
+        if (rc) return rc;
+    }
+    static bool raised_b = false, raised_c = false;
+    int rc = raise_lds((const void *)k_long_inv_blocks, &raised_b);
+    if (!rc) rc = raise_lds((const void *)k_long_inv_cols_dk, &raised_c);
+    if (rc) return rc;
+    hipLaunchKernelGGL(k_long_inv_blocks, dim3((unsigned)g.A, (unsigned)H), dim3(LT), L_LDS, s, acc, tmp, tw, g.flB,
+                       g.A);
+    FC_HIP(hipGetLastError());
+    hipLaunchKernelGGL(k_long_inv_cols_dk, dim3((unsigned)g.A, (unsigned)H), dim3(LT), L_LDS, s, tmp, dk, tw, g.flA,
+                       g.A, g.C, Nk, 1.0f / (float)M);
+    FC_HIP(hipGetLastError());
+    return FFTCONV_OK;
+}
+
+}  // namespace
+
+// rows of fft_size = A * 8192, A = 2 .. 512; a row index must fit the grid's second dimension
+bool long_fft_supported(const fftconv_plan *p) { return p->M >= 2 * LB && p->M <= 512 * (int64_t)LB && p->H <= 65535; }
+
+int long_fft_init(fftconv_plan *p)
+{
+    const int64_t M = p->M, nhi = M / 2048;
+    std::vector<float2> t((size_t)(LB + 2048 + nhi));
+    const double two_pi = 6.283185307179586476925286766559;
+    auto wpow = [&](double num, double den) {
+        const double a = two_pi * num / den;
+        return make_float2((float)std::cos(a), (float)-std::sin(a));
+    };
+    for (int64_t i = 0; i < LB; ++i) t[(size_t)i] = wpow((double)i, (double)LB);
+    for (int64_t i = 0; i < 2048; ++i) t[(size_t)(LB + i)] = wpow((double)i, (double)M);
+    for (int64_t i = 0; i < nhi; ++i) t[(size_t)(LB + 2048 + i)] = wpow((double)i, (double)nhi);
+    FC_HIP(hipMalloc((void **)&p->long_tw, t.size() * sizeof(float2)));
+    FC_HIP(hipMemcpy(p->long_tw, t.data(), t.size() * sizeof(float2), hipMemcpyHostToDevice));
+    return FFTCONV_OK;
+}
+
+void long_fft_destroy(fftconv_plan *p)
+{
+    if (p->long_tw) (void)hipFree(p->long_tw);
+    p->long_tw = nullptr;
+}
+
+// The filter transform of channels [h0, h0 + nh) of a multi-pass plan: taps (nh, Nk) -> their rows of k_f; tmp holds
+// nh * M float2.  adjoint: the spectrum of the circularly time-reversed filter (the conjugate spectrum).
+int long_filter_transform(const fftconv_plan *p, const float *k, int64_t Nk, int64_t h0, int64_t nh, bool adjoint,
+                          const uint8_t *keep_dev, int64_t n_blocks, float2 *tmp, void *kf, hipStream_t s)
+{
+    const LongGeo g = long_geo(p->M);
+    const LongTw tw = long_tw(p);
+    int rc = launch_fwd_cols<float>(g, k, nullptr, tmp, tw, nh, Nk, adjoint, s);
+    if (rc) return rc;
+    static bool raised = false;
+    rc = raise_lds((const void *)k_long_fwd_blocks_kf<true>, &raised);
+    static bool raised2 = false;
+    if (!rc) rc = raise_lds((const void *)k_long_fwd_blocks_kf<false>, &raised2);
+    if (rc) return rc;
+    if (p->dtype == FFTCONV_F16)
+        hipLaunchKernelGGL(k_long_fwd_blocks_kf<true>, dim3((unsigned)g.A, (unsigned)nh), dim3(LT), L_LDS, s, tmp,
+                           (uint32_t *)kf, tw, g.flA, g.flB, g.A, h0, keep_dev, n_blocks);
+    else
+        hipLaunchKernelGGL(k_long_fwd_blocks_kf<false>, dim3((unsigned)g.A, (unsigned)nh), dim3(LT), L_LDS, s, tmp,
+                           (uint32_t *)kf, tw, g.flA, g.flB, g.A, h0, keep_dev, n_blocks);
+    FC_HIP(hipGetLastError());
+    return FFTCONV_OK;
+}
+
+size_t long_backward_filter_bytes(const fftconv_plan *p) { return (size_t)(3 * p->H * p->M) * sizeof(float2); }
+
+int long_backward_filter(const fftconv_plan *p, const void *u, const void *dy, float *dk, int64_t Nk, int64_t B,
+                         void *workspace, hipStream_t s)
+{
+    switch (p->dtype) {
+    case FFTCONV_F32: return long_backward_filter_t<float>(p, (const float *)u, (const float *)dy, dk, Nk, B, workspace, s);
+    case FFTCONV_F16:
+        return long_backward_filter_t<__half>(p, (const __half *)u, (const __half *)dy, dk, Nk, B, workspace, s);
+    default:
+        return long_backward_filter_t<__hip_bfloat16>(p, (const __hip_bfloat16 *)u, (const __hip_bfloat16 *)dy, dk, Nk, B,
+                                                      workspace, s);
+    }
+}
+
+}  // namespace fftconv

@@ -293,11 +293,11 @@ int staged_init(fftconv_plan *p)
     FC_HIP(hipMemcpy(p->st.w64, w64.data(), sizeof(double2) * M, hipMemcpyHostToDevice));
     FC_HIP(hipMemcpy(p->st.w32, w32.data(), sizeof(float2) * M, hipMemcpyHostToDevice));
 
-    // filter-transform scratch: two ping-pong buffers of at most 64 MiB (or one channel) each
+    // filter-transform scratch: two ping-pong buffers of at most 64 MiB, or 8 channels, each
     const int64_t cap = (int64_t)64 << 20;
     int64_t per_ch = M * (int64_t)sizeof(double2);
     int64_t chunk = cap / per_ch;
-    if (chunk < 1) chunk = 1;
+    if (chunk < 8) chunk = 8;
     if (chunk > p->H) chunk = p->H;
     p->filt_chunk = chunk;
     FC_HIP(hipMalloc((void **)&p->filt_a, (size_t)(chunk * per_ch)));
