@@ -33,7 +33,10 @@ SHAPES = [
     ("f16", 2, 1, 16384, 32768, 16384), # fused 32768: four passes over a channel, a quarter of the bins each
     ("bf16", 5, 3, 16384, 32768, 16384), # odd batch, several channels per workgroup
     ("bf16", 3, 2, 9000, 32768, 9000),  # ragged N
-    ("bf16", 1, 1, 32768, 65536, 4096), # multi-pass
+    ("bf16", 1, 1, 32768, 65536, 4096), # multi-pass: fp32 transforms in two kernels per direction (A = 8)
+    ("bf16", 3, 2, 40000, 131072, 5000), # A = 16, odd batch (the last row has no partner), ragged N
+    ("f32", 3, 2, 8192, 16384, 8192),   # fp32 I/O, A = 2
+    ("f16", 2, 1, 16384, 16384, 700),   # circular (N = fft_size) multi-pass plan
 ]
 
 
