@@ -129,6 +129,9 @@ def main():
                     help="time the backward pass (du and dk) instead (not the headline metric)")
     ap.add_argument("--gated", action="store_true",
                     help="time the gated form y = v . ((u . w) * k) instead (not the headline metric)")
+    ap.add_argument("--digit-keep", default=None,
+                    help="comma-separated kept values per digit of the plan's factorisation (Appendix A.4 cut-off "
+                         "pattern): time fftconv_forward_freq_sparse_digits against the dense call on the same k_f")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch a plain elementwise copy of %d MiB (read once, written once) before the "
                          "warm-up, as the known-size reference for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE" % (COPY_BYTES >> 20))
@@ -172,6 +175,32 @@ def main():
             torch.mul(src, 1.0, out=dst)           # one elementwise kernel: COPY_BYTES read, COPY_BYTES written
         torch.cuda.synchronize()
         del src, dst
+
+    if args.digit_keep:
+        keep = [int(x) for x in args.digit_keep.split(",")]
+        kfd = plan.filter_fft_sparse_digits(kd, keep)
+        times = {}
+        # two rounds, the second one counts: the core clock is still settling during the first
+        for name, fn in 2 * (("dense", lambda: plan.forward(u, kfd, out=y)),
+                             ("skipping", lambda: plan.forward_freq_sparse_digits(u, kfd, keep, out=y))):
+            for _ in range(min(args.warmup, 20)):
+                fn()
+            torch.cuda.synchronize()
+            b0, b1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            n_it = max(3, min(args.steps, 100))
+            b0.record()
+            for _ in range(n_it):
+                fn()
+            b1.record()
+            torch.cuda.synchronize()
+            times[name] = b0.elapsed_time(b1) / n_it
+        print(json.dumps({"metric": "digit cut-off FFT-conv ms per call", "unit": "ms", "n_gpus": 1, "data": "synthetic",
+                          "dtype": w.dtype, "value": times["skipping"], "higher_is_better": False,
+                          "config": {"workload": "%s digit cut-off: B=%d H=%d N=%d fft_size=%d" %
+                                     (w.name, w.B, w.H, w.N, w.fft_size),
+                                     "factors": plan.factors, "digit_keep": keep, "dense_ms": times["dense"],
+                                     "speedup_vs_dense": times["dense"] / times["skipping"], "path": plan.path}}))
+        return
 
     if args.backward:
         dy = synth.gen_gate(w, "dy").to(dev)
