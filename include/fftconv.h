@@ -81,7 +81,10 @@ size_t fftconv_workspace_bytes(const fftconv_plan *plan, int64_t B);
 /* k_f = FFT(zero-pad(k)) / fft_size in the plan's order (Section 1: the
  * filter transform is computed once and reused over the batch).
  *   k: device, (H, Nk) fp32, 1 <= Nk <= fft_size; taps t >= Nk are zero.
- * The transform itself runs in fp64 on the device. */
+ * The transform runs on the device: in fp32 for plans whose k_f is stored as 16-bit constants (16-bit I/O
+ * from fft_size 256 up with N <= fft_size / 2 and N a multiple of 8, and every 16-bit plan from 16384 up), in
+ * fp64 otherwise.  Asynchronous on `stream`; uses scratch memory owned by the plan, so calls on one plan must
+ * not overlap. */
 int fftconv_filter_fft(const fftconv_plan *plan, const float *k, int64_t Nk, void *k_f, void *stream);
 
 /* y = conv(u, k) as defined at the top (Algorithm 1 / 3 / 4 depending on
