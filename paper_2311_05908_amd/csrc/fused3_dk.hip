@@ -16,7 +16,7 @@
 //                        dy input that follows multiplies it in and adds to the channel's accumulator.
 // A workgroup owns whole channels, so the accumulator (fp32, 64 registers per lane) never leaves the
 // registers until the channel's last pair, when it is written out in the kernel's k_f order.  The
-// inverse transform of the H accumulated spectra runs afterwards on the generic fp32 stages.
+// inverse transform of the H accumulated spectra runs afterwards, one workgroup per channel in LDS (k_dk_finish).
 #include "fused3_common.h"
 #include "lds_fft.h"
 
