@@ -82,25 +82,21 @@ int fftconv_plan_create(fftconv_plan **out, int64_t N, int64_t fft_size, int64_t
     p->dtype = dtype;
     int rc = FFTCONV_OK;
     if (hipGetDevice(&p->device) != hipSuccess) rc = FFTCONV_EHIP;
-    if (rc == FFTCONV_OK) rc = staged_init(p);      // tables of the filter transform; fallback forward
+    // the path first: the generic tables depend on it (position order of the fp32 plans' k_f)
+    if (fused3_supported(N, fft_size, dtype)) p->path = PATH_FUSED3;          // 16-bit causal shapes, fft 256 .. 32768
+    else if (small_supported(N, fft_size, dtype)) p->path = PATH_SMALL;
+    else if (multipass_supported(N, fft_size, dtype)) p->path = PATH_MULTIPASS;
+    else p->path = PATH_STAGED;
+    if (rc == FFTCONV_OK) rc = staged_init(p);      // twiddle tables, scratch of the filter transform
     if (rc == FFTCONV_OK && long_fft_supported(p)) rc = long_fft_init(p);
     if (rc == FFTCONV_OK && hipMalloc((void **)&p->keep_dev, (size_t)(fft_size > MAX_BLOCKS ? fft_size : MAX_BLOCKS)) != hipSuccess) {
         set_error("fftconv_plan_create: hipMalloc of the block mask failed");
         rc = FFTCONV_ENOMEM;
     }
     if (rc == FFTCONV_OK) {
-        if (fused3_supported(N, fft_size, dtype)) {     // 16-bit causal shapes, fft 512 .. 32768
-            p->path = PATH_FUSED3;
-            rc = fused3_init(p);
-        } else if (small_supported(N, fft_size, dtype)) {
-            p->path = PATH_SMALL;
-            rc = small_init(p);
-        } else if (multipass_supported(N, fft_size, dtype)) {
-            p->path = PATH_MULTIPASS;
-            rc = multipass_init(p);
-        } else {
-            p->path = PATH_STAGED;
-        }
+        if (p->path == PATH_FUSED3) rc = fused3_init(p);
+        else if (p->path == PATH_SMALL) rc = small_init(p);
+        else if (p->path == PATH_MULTIPASS) rc = multipass_init(p);
     }
     if (rc != FFTCONV_OK) {
         fftconv_plan_destroy(p);

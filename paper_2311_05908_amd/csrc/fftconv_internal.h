@@ -92,7 +92,6 @@ struct fftconv_plan {
     // private scratch of the filter transform (two fp64 complex ping-pong buffers)
     double2 *filt_a = nullptr, *filt_b = nullptr;
     int64_t filt_chunk = 0;           // channels per pass through the scratch
-    int64_t fwd_chunk_cap = 0;        // staged forward: max sequences per pass
     uint8_t *keep_dev = nullptr;      // device copy of a frequency-block mask (sparse filter transform)
     float2 *long_tw = nullptr;        // twiddle tables of the two-kernel long transforms (long_fft.hip)
 };
@@ -123,6 +122,9 @@ int long_fft_init(fftconv_plan *p);
 void long_fft_destroy(fftconv_plan *p);
 int long_filter_transform(const fftconv_plan *p, const float *k, int64_t Nk, int64_t h0, int64_t nh, bool adjoint,
                           const uint8_t *keep_dev, int64_t n_blocks, float2 *tmp, void *kf, hipStream_t s);
+FacList long_fft_factor_list(int64_t M);
+size_t long_forward_workspace_bytes(const fftconv_plan *p);
+int long_forward(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, void *workspace, hipStream_t s);
 size_t long_backward_filter_bytes(const fftconv_plan *p);
 int long_backward_filter(const fftconv_plan *p, const void *u, const void *dy, float *dk, int64_t Nk, int64_t B,
                          void *workspace, hipStream_t s);

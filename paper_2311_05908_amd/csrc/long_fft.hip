@@ -59,6 +59,9 @@ LongGeo long_geo(int64_t M)
 __device__ __forceinline__ float ld_real(const float *p, int64_t i) { return p[i]; }
 __device__ __forceinline__ float ld_real(const __half *p, int64_t i) { return __half2float(p[i]); }
 __device__ __forceinline__ float ld_real(const __hip_bfloat16 *p, int64_t i) { return __bfloat162float(p[i]); }
+__device__ __forceinline__ void st_real(float *p, int64_t i, float v) { p[i] = v; }
+__device__ __forceinline__ void st_real(__half *p, int64_t i, float v) { p[i] = __float2half_rn(v); }
+__device__ __forceinline__ void st_real(__hip_bfloat16 *p, int64_t i, float v) { p[i] = __float2bfloat16(v); }
 
 // W_M^e of the full length as a product of two small tables, e = 2048 e_hi + e_lo: the exponents of the outer
 // stages are spread over the whole range, and gathers from a table of M entries (16 MB at 2^21) miss every cache
@@ -246,6 +249,83 @@ __global__ void __launch_bounds__(LT) k_long_inv_cols_dk(const float2 *__restric
     }
 }
 
+// ---- The convolution itself in fp32 (plans with fp32 I/O from fft_size 8192 up): y = iFFT(FFT(pad(u)) . k_f)[0:N]
+// with k_f as fp32 pairs in position order, already scaled by 1 / fft_size.  Two batch rows share a complex
+// transform (re = row b, im = row b + 1; k is real, so the two convolutions come back as re and im).
+//
+// Rows that fit in LDS (fft_size <= 16384): one workgroup per (pair, channel) does everything.
+template <typename IO>
+__global__ void __launch_bounds__(LT) k_rows_conv_lds(const IO *__restrict__ u, const float2 *__restrict__ kf,
+                                                     IO *__restrict__ y, const float2 *__restrict__ w, FacList fl, int M,
+                                                     int64_t N, int B, int H)
+{
+    extern __shared__ float2 XL[];
+    const int h = blockIdx.x, b0 = 2 * blockIdx.y;
+    const bool two = b0 + 1 < B;
+    const int64_t r0 = ((int64_t)b0 * H + h) * N, r1 = r0 + (int64_t)H * N;
+    for (int n = threadIdx.x; n < M; n += LT)
+        XL[lds_slot(n)] = n < N ? make_float2(ld_real(u, r0 + n), two ? ld_real(u, r1 + n) : 0.f) : make_float2(0.f, 0.f);
+    __syncthreads();
+    lds_forward(XL, w, fl, M, 1);
+    for (int i = threadIdx.x; i < M; i += LT) XL[lds_slot(i)] = cmul(XL[lds_slot(i)], kf[(int64_t)h * M + i]);
+    __syncthreads();
+    lds_inverse(XL, w, fl, M, 1);
+    for (int n = threadIdx.x; n < N; n += LT) {
+        const float2 v = XL[lds_slot(n)];
+        st_real(y, r0 + n, v.x);
+        if (two) st_real(y, r1 + n, v.y);
+    }
+}
+
+// Longer rows, middle kernel: a block of 8192 positions forward, times its piece of k_f, and back, in place in tmp.
+__global__ void __launch_bounds__(LT) k_long_conv_blocks(float2 *__restrict__ tmp, const float2 *__restrict__ kf, LongTw w,
+                                                        FacList flB, int A)
+{
+    extern __shared__ float2 XL[];
+    const int64_t base = ((int64_t)blockIdx.y * A + blockIdx.x) * LB;
+    for (int i = threadIdx.x; i < LB; i += LT) XL[lds_slot(i)] = tmp[base + i];
+    __syncthreads();
+    lds_forward(XL, w.w8k, flB, LB, 1);
+    for (int i = threadIdx.x; i < LB; i += LT) XL[lds_slot(i)] = cmul(XL[lds_slot(i)], kf[base + i]);
+    __syncthreads();
+    lds_inverse(XL, w.w8k, flB, LB, 1);
+    for (int i = threadIdx.x; i < LB; i += LT) tmp[base + i] = XL[lds_slot(i)];
+}
+
+// Longer rows, last kernel: the outer factors back, real part -> row of y_re, imaginary part -> row of y_im
+// (nullptr: no second row), the first N samples.
+template <typename IO>
+__global__ void __launch_bounds__(LT) k_long_inv_cols_y(const float2 *__restrict__ tmp, IO *__restrict__ y_re,
+                                                       IO *__restrict__ y_im, LongTw w, FacList flA, int A, int C, int64_t N)
+{
+    extern __shared__ float2 XL[];
+    const int64_t M = (int64_t)A * LB, row = blockIdx.y;
+    const int col0 = blockIdx.x * C;
+    if (col0 >= N) return;
+    for (int i = threadIdx.x; i < LB; i += LT) {
+        const int a = i / C, c = i % C;
+        XL[lds_slot(i)] = tmp[row * M + (int64_t)a * LB + col0 + c];
+    }
+    __syncthreads();
+    int Sp = 1, R = A;
+    for (int i = flA.nf - 1; i >= 0; --i) {
+        const int Nj = flA.fac[i];
+        R /= Nj;
+        cols_stage_any<true>(XL, w, A, C, Nj, Sp, R, col0);
+        __syncthreads();
+        Sp *= Nj;
+    }
+    for (int i = threadIdx.x; i < LB; i += LT) {
+        const int a = i / C, c = i % C;
+        const int64_t n = (int64_t)a * LB + col0 + c;
+        if (n < N) {
+            const float2 v = XL[lds_slot(i)];
+            st_real(y_re, row * N + n, v.x);
+            if (y_im) st_real(y_im, row * N + n, v.y);
+        }
+    }
+}
+
 __global__ void k_zero_dk(float *x, int64_t n)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -332,6 +412,60 @@ int long_backward_filter_t(const fftconv_plan *p, const IO *u, const IO *dy, flo
     return FFTCONV_OK;
 }
 
+// channels per trip through the workspace of the long forward pass: at most 512 MiB of it
+int64_t conv_chunk(const fftconv_plan *p)
+{
+    int64_t c = ((int64_t)512 << 20) / (p->M * (int64_t)sizeof(float2));
+    if (c < 1) c = 1;
+    return c < p->H ? c : p->H;
+}
+
+template <typename IO>
+int long_forward_t(const fftconv_plan *p, const IO *u, const float2 *kf, IO *y, int64_t B, void *workspace, hipStream_t s)
+{
+    const int64_t M = p->M, N = p->N, H = p->H, npairs = (B + 1) / 2;
+    if (M <= 2 * LB) {                                   // the whole row in LDS
+        if (H > 2147483647 || npairs > 65535) {
+            set_error("fftconv_forward: H = %lld or ceil(B/2) = %lld exceeds the grid limits of this plan", (long long)H,
+                      (long long)npairs);
+            return FFTCONV_EUNSUPPORTED;
+        }
+        static bool raised = false;
+        if (!raised) {
+            FC_HIP(hipFuncSetAttribute((const void *)k_rows_conv_lds<IO>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)lds_row_bytes(2 * LB, sizeof(float2))));
+            raised = true;
+        }
+        hipLaunchKernelGGL(k_rows_conv_lds<IO>, dim3((unsigned)H, (unsigned)npairs), dim3(LT), lds_row_bytes(M, sizeof(float2)),
+                           s, u, kf, y, (const float2 *)p->st.w32, staged_fac_list(p), (int)M, N, (int)B, (int)H);
+        FC_HIP(hipGetLastError());
+        return FFTCONV_OK;
+    }
+    const LongGeo g = long_geo(M);
+    const LongTw tw = long_tw(p);
+    float2 *tmp = (float2 *)workspace;
+    const int64_t chunk = conv_chunk(p);
+    static bool raised_b = false, raised_c = false;
+    int rc = raise_lds((const void *)k_long_conv_blocks, &raised_b);
+    if (!rc) rc = raise_lds((const void *)k_long_inv_cols_y<IO>, &raised_c);
+    if (rc) return rc;
+    for (int64_t b = 0; b < B; b += 2)
+        for (int64_t h0 = 0; h0 < H; h0 += chunk) {
+            const int64_t nh = H - h0 < chunk ? H - h0 : chunk;
+            const int64_t o0 = (b * H + h0) * N;
+            const bool two = b + 1 < B;
+            rc = launch_fwd_cols<IO>(g, u + o0, two ? u + o0 + H * N : nullptr, tmp, tw, nh, N, false, s);
+            if (rc) return rc;
+            hipLaunchKernelGGL(k_long_conv_blocks, dim3((unsigned)g.A, (unsigned)nh), dim3(LT), L_LDS, s, tmp, kf + h0 * M, tw,
+                               g.flB, g.A);
+            FC_HIP(hipGetLastError());
+            hipLaunchKernelGGL(k_long_inv_cols_y<IO>, dim3((unsigned)g.A, (unsigned)nh), dim3(LT), L_LDS, s,
+                               (const float2 *)tmp, y + o0, two ? y + o0 + H * N : nullptr, tw, g.flA, g.A, g.C, N);
+            FC_HIP(hipGetLastError());
+        }
+    return FFTCONV_OK;
+}
+
 }  // namespace
 
 // rows of fft_size = A * 8192, A = 2 .. 512; a row index must fit the grid's second dimension
@@ -382,6 +516,27 @@ int long_filter_transform(const fftconv_plan *p, const float *k, int64_t Nk, int
                            (uint32_t *)kf, tw, g.flA, g.flB, g.A, h0, keep_dev, n_blocks);
     FC_HIP(hipGetLastError());
     return FFTCONV_OK;
+}
+
+// The position order of the spectra of these transforms (k_f of the fp32 plans from fft_size 32768 up is stored in it)
+FacList long_fft_factor_list(int64_t M) { return long_geo(M).fl; }
+
+size_t long_forward_workspace_bytes(const fftconv_plan *p)
+{
+    return p->M <= 2 * LB ? 0 : (size_t)(conv_chunk(p) * p->M) * sizeof(float2);
+}
+
+// fp32 forward pass of the plans without a 16-bit kernel (fft_size >= 8192); kf: (H, fft_size) fp32 pairs in position order
+int long_forward(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, void *workspace, hipStream_t s)
+{
+    switch (p->dtype) {
+    case FFTCONV_F32: return long_forward_t<float>(p, (const float *)u, (const float2 *)kf, (float *)y, B, workspace, s);
+    case FFTCONV_F16:
+        return long_forward_t<__half>(p, (const __half *)u, (const float2 *)kf, (__half *)y, B, workspace, s);
+    default:
+        return long_forward_t<__hip_bfloat16>(p, (const __hip_bfloat16 *)u, (const float2 *)kf, (__hip_bfloat16 *)y, B,
+                                              workspace, s);
+    }
 }
 
 size_t long_backward_filter_bytes(const fftconv_plan *p) { return (size_t)(3 * p->H * p->M) * sizeof(float2); }

@@ -1,8 +1,10 @@
-// Generic multi-kernel FFT convolution: one launch per stage of the order-p
-// decomposition (paper Section 2.1: F_M as a chain of small DFT-matrix products
-// with twiddle diagonals in between), intermediates in HBM.  This is the path
-// for fp32 I/O and for transform lengths without a fused kernel, and -- in fp64
-// -- the engine of every filter transform k -> k_f.
+// Generic transforms, one launch per stage of the order-p decomposition (paper
+// Section 2.1: F_M as a chain of small DFT-matrix products with twiddle diagonals
+// in between), intermediates in HBM; rows that fit in LDS run all stages in one
+// kernel there (lds_fft.h).  Users: the fp64 filter transform k -> k_f of the
+// plans without a fused one, the filter gradient of the plans below fft_size
+// 16384 without a fused kernel, and the k_f layout of the fp32 plans, whose
+// forward pass lives in long_fft.hip.
 //
 // Index maps.  M = N_1 * ... * N_p.  Time index n = sum_i n_i S_i with
 // S_i = prod_{j>i} N_j (n_1 most significant); frequency f = sum_i k_i R_i with
@@ -36,9 +38,6 @@ template <> struct C2<double> { using type = double2; };
 __device__ __forceinline__ float load_real(const float *p, int64_t i) { return p[i]; }
 __device__ __forceinline__ float load_real(const __half *p, int64_t i) { return __half2float(p[i]); }
 __device__ __forceinline__ float load_real(const __hip_bfloat16 *p, int64_t i) { return __bfloat162float(p[i]); }
-__device__ __forceinline__ void store_real(float *p, int64_t i, float v) { p[i] = v; }
-__device__ __forceinline__ void store_real(__half *p, int64_t i, float v) { p[i] = __float2half_rn(v); }
-__device__ __forceinline__ void store_real(__hip_bfloat16 *p, int64_t i, float v) { p[i] = __float2bfloat16(v); }
 
 // Zero-padded real input -> complex buffer (imaginary part 0, zeros for n >= len).
 template <typename V, typename In>
@@ -211,25 +210,6 @@ bool launch_stage_reg(bool inverse, const V *src, V *dst, const V *w, int64_t M,
 #undef STAGE_REG
 }
 
-// x[row, p] *= kf[(row0 + row) % H, p]
-__global__ void k_pointwise(float2 *x, const float2 *kf, int64_t M, int64_t H, int64_t row0, int64_t nrows)
-{
-    int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= nrows * M) return;
-    int64_t row = idx / M, p = idx % M;
-    int64_t h = (row0 + row) % H;
-    x[idx] = cmul(x[idx], kf[h * M + p]);
-}
-
-template <typename Out>
-__global__ void k_store_real(const float2 *x, Out *y, int64_t N, int64_t M, int64_t nrows)
-{
-    int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= nrows * N) return;
-    int64_t row = idx / N, n = idx % N;
-    store_real(y, idx, x[row * M + n].x);
-}
-
 // spectra in position order (fp64) -> staged k_f (fp32 pairs, same position order), scaled 1/M,
 // with dropped frequency blocks zeroed.
 __global__ void k_pack_staged(const double2 *spec, float2 *kf, FacList fl, int64_t M, int64_t h0, int64_t nh,
@@ -273,8 +253,9 @@ int run_stages_fwd(const FacList &fl, int64_t M, int64_t tws, V *a, V *b, const 
 
 int staged_init(fftconv_plan *p)
 {
-    // factors of 16, remainder (2, 4 or 8) last
-    const FacList fl0 = staged_factors_for(p->M);
+    // factors of 16, remainder (2, 4 or 8) last; the fp32 plans from 32768 up keep k_f in the position order of
+    // their two-kernel transforms (long_fft.hip)
+    const FacList fl0 = (p->path == PATH_STAGED && p->M >= 32768) ? long_fft_factor_list(p->M) : staged_factors_for(p->M);
     p->st.nf = fl0.nf;
     for (int i = 0; i < MAX_FACTORS; ++i) p->st.fac[i] = fl0.fac[i];
 
@@ -302,10 +283,6 @@ int staged_init(fftconv_plan *p)
     p->filt_chunk = chunk;
     FC_HIP(hipMalloc((void **)&p->filt_a, (size_t)(chunk * per_ch)));
     FC_HIP(hipMalloc((void **)&p->filt_b, (size_t)(chunk * per_ch)));
-
-    // forward workspace: two fp32 complex buffers, at most 256 MiB each
-    int64_t fcap = ((int64_t)256 << 20) / (M * (int64_t)sizeof(float2));
-    p->fwd_chunk_cap = fcap < 1 ? 1 : fcap;
     return FFTCONV_OK;
 }
 
@@ -322,69 +299,13 @@ void staged_destroy(fftconv_plan *p)
 
 size_t staged_kf_bytes(const fftconv_plan *p) { return (size_t)(p->H * p->M) * sizeof(float2); }
 
-static int64_t staged_chunk(const fftconv_plan *p, int64_t B)
-{
-    int64_t nseq = B * p->H;
-    return nseq < p->fwd_chunk_cap ? nseq : p->fwd_chunk_cap;
-}
+size_t staged_workspace_bytes(const fftconv_plan *p, int64_t) { return long_forward_workspace_bytes(p); }
 
-size_t staged_workspace_bytes(const fftconv_plan *p, int64_t B)
-{
-    return (size_t)(2 * staged_chunk(p, B) * p->M) * sizeof(float2);
-}
-
-template <typename IO>
-static int staged_forward_t(const fftconv_plan *p, const IO *u, const float2 *kf, IO *y, int64_t B, void *workspace,
-                            hipStream_t s)
-{
-    const int bs = 256;
-    int64_t M = p->M, N = p->N, H = p->H;
-    int64_t nseq = B * H;
-    if (nseq == 0) return FFTCONV_OK;
-    int64_t chunk = staged_chunk(p, B);
-    float2 *a = (float2 *)workspace;
-    float2 *b = a + chunk * M;
-    for (int64_t row0 = 0; row0 < nseq; row0 += chunk) {
-        int64_t nrows = nseq - row0 < chunk ? nseq - row0 : chunk;
-        hipLaunchKernelGGL((k_load_padded<float2, IO>), dim3(grid_for(nrows * M, bs)), dim3(bs), 0, s, u + row0 * N,
-                           a, N, M, nrows);
-        FC_HIP(hipGetLastError());
-        float2 *x = nullptr;
-        int rc = run_stages_fwd<float2>(fac_list(p), M, 1, a, b, p->st.w32, nrows, s, &x);
-        if (rc) return rc;
-        hipLaunchKernelGGL(k_pointwise, dim3(grid_for(nrows * M, bs)), dim3(bs), 0, s, x, kf, M, H, row0, nrows);
-        FC_HIP(hipGetLastError());
-        float2 *src = x, *dst = (x == a) ? b : a;
-        int64_t S = 1, R = M;
-        for (int i = p->st.nf - 1; i >= 0; --i) {
-            int Nj = (int)p->st.fac[i];
-            R /= Nj;
-            if (!launch_stage_reg<float2>(true, src, dst, p->st.w32, M, Nj, S, R, nrows, 1, s))
-                hipLaunchKernelGGL(k_stage_inv<float2>, dim3(grid_for(nrows * M, bs)), dim3(bs), 0, s, src, dst,
-                                   p->st.w32, M, Nj, S, R, nrows);
-            FC_HIP(hipGetLastError());
-            S *= Nj;
-            float2 *t = src; src = dst; dst = t;
-        }
-        hipLaunchKernelGGL((k_store_real<IO>), dim3(grid_for(nrows * N, bs)), dim3(bs), 0, s, src, y + row0 * N, N, M,
-                           nrows);
-        FC_HIP(hipGetLastError());
-    }
-    return FFTCONV_OK;
-}
-
+// fp32 I/O from fft_size 8192 up: the whole row in LDS up to 16384, three kernels above (long_fft.hip)
 int staged_forward(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, void *workspace,
                    hipStream_t s)
 {
-    switch (p->dtype) {
-    case FFTCONV_F32:
-        return staged_forward_t<float>(p, (const float *)u, (const float2 *)kf, (float *)y, B, workspace, s);
-    case FFTCONV_F16:
-        return staged_forward_t<__half>(p, (const __half *)u, (const float2 *)kf, (__half *)y, B, workspace, s);
-    default:
-        return staged_forward_t<__hip_bfloat16>(p, (const __hip_bfloat16 *)u, (const float2 *)kf,
-                                                (__hip_bfloat16 *)y, B, workspace, s);
-    }
+    return long_forward(p, u, kf, y, B, workspace, s);
 }
 
 // Largest row the LDS-resident kernels take: 8192 fp64 or 16384 fp32 complex points with their padding.
@@ -494,7 +415,13 @@ __global__ void k_store_dk(const float2 *x, float *dk, int64_t Nk, int64_t M, in
     dk[idx] = x[row * M + t].x * scale;
 }
 
-static int64_t bwd_chunk(const fftconv_plan *p) { return p->H < p->fwd_chunk_cap ? p->H : p->fwd_chunk_cap; }
+// channels per trip through the scratch of the filter gradient: buffers of at most 256 MiB
+static int64_t bwd_chunk(const fftconv_plan *p)
+{
+    int64_t cap = ((int64_t)256 << 20) / (p->M * (int64_t)sizeof(float2));
+    if (cap < 1) cap = 1;
+    return p->H < cap ? p->H : cap;
+}
 
 // dk rows from position-ordered spectra: unnormalised inverse stages (ping-pong between spec and other,
 // both nrows * M), real part of the first Nk samples, times 1/M.  spec is overwritten.

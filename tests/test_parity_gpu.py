@@ -77,9 +77,11 @@ def test_short_transforms_grouped_on_the_8192_kernel(dtype, B, H, N, M):
 
 
 @pytest.mark.parametrize("dtype,B,H,N,M", [
-    ("f32", 2, 2, 4096, 8192),       # fp32 I/O beyond the short-transform kernel
-    ("f32", 1, 2, 5000, 16384),      # ragged N
+    ("f32", 2, 2, 4096, 8192),       # fp32 I/O beyond the short-transform kernel: the whole row in LDS
+    ("f32", 1, 2, 5000, 16384),      # ragged N, a single row (no partner in the pair)
     ("f32", 2, 1, 8192, 8192),       # circular
+    ("f32", 3, 2, 16384, 32768),     # three kernels: A = 4 outer factor, odd batch
+    ("f32", 2, 3, 20000, 65536),     # A = 8, ragged N
 ])
 def test_generic_staged_path(dtype, B, H, N, M):
     w = synth.scaled(W["cfg2"], B=B, H=H, N=N, fft_size=M, dtype=dtype, alpha=(1e-2, 1e-1))
@@ -88,6 +90,18 @@ def test_generic_staged_path(dtype, B, H, N, M):
           flush=True)
     assert plan.path == "staged"
     assert err <= TOL[dtype]
+
+
+@pytest.mark.parametrize("lg,circular", [(16, True), (18, False), (20, False), (22, False)])
+def test_fp32_long_rows_sampled_positions(lg, circular):
+    """fp32 I/O on the three-kernel route: outer factors 8, 32 = 16 x 2, 128 = 16 x 8, 512 = 16 x 16 x 2."""
+    from parity_util import check_sampled_positions
+    M = 1 << lg
+    w = synth.scaled(W["cfg4"], B=3, H=2, N=M if circular else M // 2, fft_size=M, dtype="f32", alpha=(1e-4, 1e-4))
+    err, plan = check_sampled_positions(w, n_pos=16)
+    print("fp32 long fft 2^%d path=%s factors=%s err=%.3e" % (lg, plan.path, plan.factors, err), flush=True)
+    assert plan.path == "staged"
+    assert err <= TOL["f32"]
 
 
 def test_delta_filter_is_identity_and_zero_input_gives_zero():
