@@ -315,6 +315,22 @@ def test_frequency_sparse_masks_fft16384(keep_blocks):
         assert err <= TOL[w.dtype]
 
 
+@pytest.mark.parametrize("dtype,N,M,n_blocks,keep_blocks,path", [
+    ("bf16", 4096, 8192, 32, (0, 1, 2, 3, 28, 29, 30, 31), "fused3"),     # the 8192-point kernel's own filter transform
+    ("f16", 1024, 2048, 16, (0, 1, 2), "fused3"),                         # a short plan (4 groups), one-sided mask
+    ("bf16", 16384, 32768, 64, tuple(range(8)) + tuple(range(56, 64)), "fused3"),   # half-length real transform
+    ("bf16", 20000, 65536, 32, (0, 1, 30, 31), "multipass"),              # two-kernel fp32 transform, k_f by the block kernel
+    ("f16", 8192, 8192, 8, (0, 7), "multipass"),                          # circular 8192: fp64 rows in LDS
+])
+def test_block_masks_through_every_filter_transform(dtype, N, M, n_blocks, keep_blocks, path):
+    """Frequency-block masks (weights 1 / 1/2 / 0 per bin) are applied inside each plan family's own filter transform."""
+    w = synth.scaled(W["cfg5b"], B=2, H=2, N=N, fft_size=M, dtype=dtype, keep_blocks=keep_blocks, n_blocks=n_blocks)
+    err, plan = check_all_sequences(w, variant="skip")
+    print("block mask %s N=%d M=%d path=%s err=%.3e" % (dtype, N, M, plan.path, err), flush=True)
+    assert plan.path == path
+    assert err <= TOL[dtype]
+
+
 # ---------------------------------------------------------------- every transform length the plan accepts
 
 @pytest.mark.parametrize("lg", list(range(8, 23)))
