@@ -631,9 +631,9 @@ __global__ void __launch_bounds__(NT, (N2 == 16 && !GATED) ? 4 : 2) k_fused3_big
 // of the channels a workgroup owns: a u input leaves its spectrum in registers (fp32), the dy input that
 // follows multiplies it in and adds to the channel's accumulator (fp32), which is written out in the kernel's
 // k_f order after the channel's last pair.  Spectrum and accumulator of a whole transform are 2 x 64 registers
-// at N2 = 16 and would be 2 x 128 at N2 = 32, where the kernel therefore walks through a channel's pairs four
-// times, each time keeping one (k2 tile, k3 tile) quarter of the bins (phase A is repeated, stage 3 is not).
-// One workgroup per compute unit.
+// at N2 = 16 and would be 2 x 128 at N2 = 32, where the kernel therefore walks through a channel's pairs twice,
+// each time keeping one k3 tile of the bins (phase A is repeated, stage 3 is not) with the spectrum of u held as
+// 16-bit pairs (32 registers; the accumulator stays fp32).  One workgroup per compute unit.
 template <typename TT, bool FULL, int N2>
 __global__ void __launch_bounds__(NT, 2) k_fused3_big_dk(const uint16_t *__restrict__ u, const uint16_t *__restrict__ dy,
                                                          float2 *__restrict__ dkf, const void *__restrict__ consts, int B,
@@ -642,7 +642,10 @@ __global__ void __launch_bounds__(NT, 2) k_fused3_big_dk(const uint16_t *__restr
     using CW = typename TT::CW;
     using BG = BigGeo<N2>;
     constexpr int BPK1 = BG::PK1, BPN3 = BG::PN3, NCH = BG::NCH, R2 = BG::R2;
-    constexpr int NPASS = R2 * R2, TPP = 2 / R2;          // passes over a channel; k3 tiles kept per pass
+    // Passes over a channel and (k2, k3) tiles of a k1 plane kept per pass.  N2 = 16: both k3 tiles of the only k2
+    // tile.  N2 = 32: the pass's k3 tile of both k2 tiles, with the spectrum of u held as 16-bit pairs.
+    constexpr int NPASS = R2, TPP = 2;
+    constexpr bool PACKZ = N2 == 32;
     extern __shared__ uint32_t XB[];
     const int tid = threadIdx.x, l = tid & 63, q = l >> 4, c16 = l & 15;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -678,17 +681,18 @@ __global__ void __launch_bounds__(NT, 2) k_fused3_big_dk(const uint16_t *__restr
     };
     // resident: stage-1 matrix, the stage-3 tiles of the current pass; streamed one plane ahead: stage-2
     // matrix and twiddles of a plane
-    uint4 tab1[2][2], tab3[2][TPP][2], tabA[R2][R2][2];
+    constexpr int T3R = PACKZ ? 1 : 2;                    // resident k3 tiles of the stage-3 matrix
+    uint4 tab1[2][2], tab3[2][T3R][2], tabA[R2][R2][2];
     CW twaR[R2][2][4];
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
         for (int p = 0; p < 2; ++p) tab1[a][p] = ld16(0, BG::OFF_TAB1 + (a * 2 + p) * 1024);
-    auto load_tab3 = [&](int ct3) {                        // tiles ct3 .. ct3 + TPP - 1
+    auto load_tab3 = [&](int ct3) {                        // tiles ct3 .. ct3 + T3R - 1
 #pragma unroll
         for (int a = 0; a < 2; ++a)
 #pragma unroll
-            for (int b = 0; b < TPP; ++b)
+            for (int b = 0; b < T3R; ++b)
 #pragma unroll
                 for (int p = 0; p < 2; ++p)
                     tab3[a][b][p] = ld16(sz + ct3 * 2048, BG::OFF_TAB3 + ((a * 2 + b) * 2 + p) * 1024);
@@ -799,14 +803,16 @@ __global__ void __launch_bounds__(NT, 2) k_fused3_big_dk(const uint16_t *__restr
         }
     };
 
-    // [k1 plane of the wave][k3 tile of the pass]; declared with two tiles also where one is used: arrays of
-    // 16 or 32 floats in all are merged into one wide vector value, whose partial updates the compiler then
-    // turns into copies of the whole
+    // [k1 plane of the wave][tile of the pass]
     f32x4 z1re[4][2], z1im[4][2], accre[4][2], accim[4][2];
+    uint4 z1p[4][2];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int t = 0; t < TPP; ++t) accre[i][t] = accim[i][t] = z1re[i][t] = z1im[i][t] = zero4;
+        for (int t = 0; t < TPP; ++t) {
+            accre[i][t] = accim[i][t] = z1re[i][t] = z1im[i][t] = zero4;
+            z1p[i][t] = make_uint4(0, 0, 0, 0);
+        }
 
     opaque();
     issue_pre(0, 0, NCH);
@@ -814,7 +820,6 @@ __global__ void __launch_bounds__(NT, 2) k_fused3_big_dk(const uint16_t *__restr
         const int item = s >> 1, which = s & 1;
         const int jp = item / npairs, pair = item - jp * npairs;
         const int j = jp / NPASS, pass = jp - j * NPASS;
-        const int ct2p = pass / 2, ct3p = NPASS == 1 ? 0 : pass % 2;      // the pass keeps k2 tile ct2p, k3 tiles from ct3p on
         stage_in();
         lds_barrier();
         read_x1();
@@ -823,37 +828,55 @@ __global__ void __launch_bounds__(NT, 2) k_fused3_big_dk(const uint16_t *__restr
         load_plane(0);
         // the next input (past the end: the last one again, in range and unused) is requested ahead of
         // phase A where registers allow, after it otherwise
-        constexpr int EARLY = NCH;
+        constexpr int EARLY = PACKZ ? 0 : NCH;
         issue_pre(s + 1 < S ? s + 1 : s, 0, EARLY);
         SCHED_FENCE();
         phase_A();
         SCHED_FENCE();
         issue_pre(s + 1 < S ? s + 1 : s, EARLY, NCH);
-        if (which == 0 && pair == 0 && (NPASS > 1 || s == 0)) load_tab3(ct3p);
+        if (which == 0 && pair == 0 && (NPASS > 1 || s == 0)) load_tab3(PACKZ ? pass : 0);
         lds_barrier();
         // stage 3 of this wave's 4 k1 planes
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            uint4 x3[2];
-#pragma unroll
-            for (int ks = 0; ks < 2; ++ks) {
-                const uint32_t *src = (ks ? rdB1 : rdB0) + i * BPK1 + 16 * ct2p;
-                x3[ks] = make_uint4(src[0], src[BPN3], src[2 * BPN3], src[3 * BPN3]);
-            }
+            uint4 x3[2];                                  // the plane's k2 tile: one for both k3 tiles at N2 = 16
 #pragma unroll
             for (int t = 0; t < TPP; ++t) {
+                const int ct2 = PACKZ ? t : 0;
+                if (PACKZ || t == 0) {
+#pragma unroll
+                    for (int ks = 0; ks < 2; ++ks) {
+                        const uint32_t *src = (ks ? rdB1 : rdB0) + i * BPK1 + 16 * ct2;
+                        x3[ks] = make_uint4(src[0], src[BPN3], src[2 * BPN3], src[3 * BPN3]);
+                    }
+                }
                 f32x4 dre = zero4, dim = zero4;
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks) {
-                    dre = TT::mfma(tab3[ks][t][0], x3[ks], dre);
-                    dim = TT::mfma(tab3[ks][t][1], x3[ks], dim);
+                    dre = TT::mfma(tab3[ks][PACKZ ? 0 : t][0], x3[ks], dre);
+                    dim = TT::mfma(tab3[ks][PACKZ ? 0 : t][1], x3[ks], dim);
                 }
                 if (which == 0) {                         // wave-uniform
-                    z1re[i][t] = dre;
-                    z1im[i][t] = dim;
+                    if constexpr (PACKZ) {
+                        z1p[i][t] = make_uint4(TT::pack(dre[0], dim[0]), TT::pack(dre[1], dim[1]), TT::pack(dre[2], dim[2]),
+                                               TT::pack(dre[3], dim[3]));
+                    } else {
+                        z1re[i][t] = dre;
+                        z1im[i][t] = dim;
+                    }
                 } else {                                  // acc += conj(Z1) . Z2
-                    accre[i][t] += z1re[i][t] * dre + z1im[i][t] * dim;
-                    accim[i][t] += z1re[i][t] * dim - z1im[i][t] * dre;
+                    f32x4 zr, zi;
+                    if constexpr (PACKZ) {
+                        const float2 a0 = TT::widen(z1p[i][t].x), a1 = TT::widen(z1p[i][t].y), a2 = TT::widen(z1p[i][t].z),
+                                     a3 = TT::widen(z1p[i][t].w);
+                        zr = f32x4{a0.x, a1.x, a2.x, a3.x};
+                        zi = f32x4{a0.y, a1.y, a2.y, a3.y};
+                    } else {
+                        zr = z1re[i][t];
+                        zi = z1im[i][t];
+                    }
+                    accre[i][t] += zr * dre + zi * dim;
+                    accim[i][t] += zr * dim - zi * dre;
                 }
             }
         }
@@ -864,10 +887,10 @@ __global__ void __launch_bounds__(NT, 2) k_fused3_big_dk(const uint16_t *__restr
             for (int i = 0; i < 4; ++i)
 #pragma unroll
                 for (int t = 0; t < TPP; ++t) {
+                    const int ct2 = PACKZ ? t : 0, ct3 = PACKZ ? pass : t;
 #pragma unroll
                     for (int r = 0; r < 4; ++r)
-                        dst[((((4 * w + i) * R2 + ct2p) * 2 + ct3p + t) * 4 + r) * 64 + l] =
-                            make_float2(accre[i][t][r], accim[i][t][r]);
+                        dst[((((4 * w + i) * R2 + ct2) * 2 + ct3) * 4 + r) * 64 + l] = make_float2(accre[i][t][r], accim[i][t][r]);
                     accre[i][t] = zero4;
                     accim[i][t] = zero4;
                 }
