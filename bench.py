@@ -74,6 +74,36 @@ def time_oracle(w, u_cpu, k, budget_s=12.0):
     }
 
 
+def sustained_power(torch, step, ms_per_step, seconds=2.0):
+    """Package power while the step runs back to back for about two seconds (outside the timed region), with the
+    board's power cap: the hwmon files of the amdgpu driver, read-only; None where they cannot be read."""
+    import glob
+    files = glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_input") or \
+        glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_average")
+    if not files:
+        return None
+    def read(path):
+        try:
+            with open(path) as f:
+                return int(f.read()) / 1e6
+        except (OSError, ValueError):
+            return None
+    cap = read(files[0].rsplit("/", 1)[0] + "/power1_cap")
+    n = max(1, int(seconds * 1e3 / ms_per_step / 8))
+    samples = []
+    for i in range(8):                         # 8 bursts; the sensor is read while the queue is still full
+        for _ in range(n):
+            step()
+        if i >= 3:
+            v = read(files[0])
+            if v is not None:
+                samples.append(v)
+        torch.cuda.synchronize()
+    if not samples:
+        return None
+    return {"socket_W": sum(samples) / len(samples), "cap_W": cap, "samples": len(samples)}
+
+
 def sweep(torch, fftconv, synth, dev, args):
     """Forward pass, bf16, B*H*N = 2^27 elements at every size (B*H >= 1): causal (N = fft/2) or,
     with --circular, the input filling the transform (N = fft)."""
@@ -275,6 +305,7 @@ def main():
         torch.cuda.synchronize()
         dense_ms = d0.elapsed_time(d1) / args.steps
 
+    power = sustained_power(torch, step, ms_per_step)
     nseq = w.B * w.H
     abytes = algorithmic_bytes(w, args.gated)
     avg_kernel_ms = ms_per_step          # one kernel launch per step on the fused paths
@@ -297,6 +328,7 @@ def main():
                    "path": plan.path, "factors": plan.factors,
                    "achieved_TBps": achieved / 1e3, "wall_ms_per_step": t_wall / args.steps * 1e3,
                    "input_gen_s": t_gen,
+                   "power": power,
                    "dense_ms_per_step": dense_ms,
                    "speedup_vs_dense": None if dense_ms is None else dense_ms / ms_per_step},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
