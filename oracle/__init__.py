@@ -133,6 +133,7 @@ def mask_filter(kext, keep) -> np.ndarray:
 
 def round_to(x, dtype: str) -> np.ndarray:
     """Round fp64 values to the I/O dtype ("f32", "f16", "bf16"), nearest even, and return them as fp64.
+    A diagnostic helper for tests (how far one rounding moves a value); no oracle result depends on it.
 
     bf16 is the upper half of fp32: round the fp32 bit pattern to 16 bits (finite inputs only).
     """
@@ -148,16 +149,16 @@ def round_to(x, dtype: str) -> np.ndarray:
     raise ValueError("dtype must be f32, f16 or bf16")
 
 
-def fftconv_gated(u, w, v, kext, M: int | None = None, dtype: str = "f32") -> np.ndarray:
+def fftconv_gated(u, w, v, kext, M: int | None = None) -> np.ndarray:
     """Gated convolution y = v . ((u . w) * k) (Section 3.1, "Domain-Specific Optimizations"; Section 4.1).
 
-    u, w, v: (B,H,N), w and/or v may be None (no gate on that side).  The elementwise product u . w is
-    what the transform consumes, so it is rounded to the I/O dtype first (for 16-bit inputs the
-    product itself is exact in fp32); the convolution and the output gate are exact fp64.
+    u, w, v: (B,H,N), w and/or v may be None (no gate on that side).  Exact fp64 throughout: the
+    elementwise products and the convolution are evaluated as the definition states them, with no
+    intermediate rounding.
     """
     p = _f64(u)
     if w is not None:
-        p = round_to(p * _f64(w), dtype)
+        p = p * _f64(w)
     y = fftconv(p, kext, M)
     if v is not None:
         y = y * _f64(v)

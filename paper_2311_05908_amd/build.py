@@ -1,9 +1,15 @@
 """Build libfftconv.so (HIP, gfx950 only) in-tree with hipcc.
 
-    python -m paper_2311_05908_amd.build [--force]
+    python -m paper_2311_05908_amd.build [--force] [--sync-check]
+
+Every source is compiled to an object file of its own (in parallel, under _build/, which is not
+committed) and the objects are linked into the shared library next to this file.
+--sync-check builds a second library, libfftconv_synccheck.so, in which every LDS-only workgroup
+barrier of the fused kernels is the full __syncthreads(); the GPU tests compare the two bit for bit.
 """
 from __future__ import annotations
 
+import concurrent.futures
 import glob
 import os
 import subprocess
@@ -13,13 +19,14 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libfftconv.so")
+LIB_SYNC_CHECK = os.path.join(HERE, "libfftconv_synccheck.so")
+OBJ_DIR = os.path.join(HERE, "_build")
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950",
     "-O3",
     "-std=c++17",
     "-fPIC",
-    "-shared",
     "-Wall",
     "-Wno-unused-function",
     # packed-fp32 VALU forms are kept out of the generated code on the test machines
@@ -31,26 +38,59 @@ def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
 
-def up_to_date() -> bool:
-    if not os.path.exists(LIB):
+def _headers():
+    return glob.glob(os.path.join(CSRC, "*.h")) + glob.glob(os.path.join(INCLUDE, "*.h"))
+
+
+def up_to_date(lib: str = LIB) -> bool:
+    if not os.path.exists(lib):
         return False
-    t = os.path.getmtime(LIB)
-    deps = sources() + glob.glob(os.path.join(CSRC, "*.h")) + glob.glob(os.path.join(INCLUDE, "*.h"))
-    return all(os.path.getmtime(d) <= t for d in deps)
+    t = os.path.getmtime(lib)
+    return all(os.path.getmtime(d) <= t for d in sources() + _headers())
 
 
-def build(force: bool = False, verbose: bool = False) -> str:
-    if not force and up_to_date():
-        return LIB
+def _compile(hipcc, src, obj, extra, verbose):
+    cmd = [hipcc] + HIPCC_FLAGS + extra + ["-I", INCLUDE, "-I", CSRC, "-c", "-o", obj, src]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    # hipcc's host pass does not know the packed-fp32 feature and says so once per file: harmless
+    out = "\n".join(l for l in r.stdout.splitlines() if "packed-fp32-ops" not in l)
+    if out.strip():
+        print(out, flush=True)
+    if r.returncode != 0:
+        raise subprocess.CalledProcessError(r.returncode, cmd)
+    return obj
+
+
+def build(force: bool = False, verbose: bool = False, sync_check: bool = False) -> str:
+    lib = LIB_SYNC_CHECK if sync_check else LIB
+    if not force and up_to_date(lib):
+        return lib
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    tmp = LIB + ".tmp%d" % os.getpid()
-    cmd = [hipcc] + HIPCC_FLAGS + ["-I", INCLUDE, "-I", CSRC, "-o", tmp] + sources()
+    extra = ["-DFFTCONV_SYNC_CHECK"] if sync_check else []
+    odir = os.path.join(OBJ_DIR, "synccheck" if sync_check else "release")
+    os.makedirs(odir, exist_ok=True)
+    newest_header = max(os.path.getmtime(h) for h in _headers())
+    jobs = []
+    objs = []
+    for src in sources():
+        obj = os.path.join(odir, os.path.basename(src)[:-4] + ".o")
+        objs.append(obj)
+        if force or not os.path.exists(obj) or os.path.getmtime(obj) < max(os.path.getmtime(src), newest_header):
+            jobs.append((src, obj))
+    workers = max(1, min(len(jobs), int(os.environ.get("MAX_JOBS", os.cpu_count() or 4))))
+    with concurrent.futures.ThreadPoolExecutor(max_workers=workers) as ex:
+        for f in [ex.submit(_compile, hipcc, s, o, extra, verbose) for s, o in jobs]:
+            f.result()
+    tmp = lib + ".tmp%d" % os.getpid()
+    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp] + objs
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)
-    os.replace(tmp, LIB)
-    return LIB
+    os.replace(tmp, lib)
+    return lib
 
 
 if __name__ == "__main__":
-    print(build(force="--force" in sys.argv, verbose=True))
+    print(build(force="--force" in sys.argv, verbose=True, sync_check="--sync-check" in sys.argv))

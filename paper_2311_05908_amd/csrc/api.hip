@@ -3,6 +3,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include <vector>
@@ -19,6 +20,23 @@ void set_error(const char *fmt, ...)
     va_start(ap, fmt);
     vsnprintf(g_err, sizeof(g_err), fmt, ap);
     va_end(ap);
+}
+
+// (device, kernel) pairs whose limit has been raised; a fixed table, so nothing is allocated here
+int raise_dynamic_lds(const void *kernel, int bytes)
+{
+    struct Entry { int device; const void *kernel; int bytes; };
+    static std::mutex mu;
+    static Entry done[1024];
+    static int n_done = 0;
+    int dev = 0;
+    FC_HIP(hipGetDevice(&dev));
+    std::lock_guard<std::mutex> lock(mu);
+    for (int i = 0; i < n_done; ++i)
+        if (done[i].device == dev && done[i].kernel == kernel && done[i].bytes >= bytes) return FFTCONV_OK;
+    FC_HIP(hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes));
+    if (n_done < 1024) done[n_done++] = Entry{dev, kernel, bytes};
+    return FFTCONV_OK;
 }
 
 static bool is_pow2(int64_t v) { return v > 0 && (v & (v - 1)) == 0; }

@@ -23,6 +23,16 @@ void set_error(const char *fmt, ...);
         }                                                                                 \
     } while (0)
 
+#define FC_TRY(call)                     \
+    do {                                 \
+        const int rc_ = (call);          \
+        if (rc_ != FFTCONV_OK) return rc_; \
+    } while (0)
+
+// Raise a kernel's dynamic-LDS limit to `bytes` on the current device, once per (device, kernel);
+// safe to call from several threads and before every launch.
+int raise_dynamic_lds(const void *kernel, int bytes);
+
 enum Path { PATH_STAGED = 0, PATH_FUSED3 = 1, PATH_MULTIPASS = 2, PATH_SMALL = 3 };
 
 constexpr int MAX_FACTORS = 8;

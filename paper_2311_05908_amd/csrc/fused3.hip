@@ -52,14 +52,6 @@
 #include "fused3_common.h"
 #include "lds_fft.h"
 
-// Timing probes (development builds only, -DFUSED3_PROBE): a launch-time mask switches whole
-// phases off so their cost can be read from the difference.  Results are then meaningless.
-#ifdef FUSED3_PROBE
-#define PROBE_ON(bit) (!(probe & (bit)))
-#else
-#define PROBE_ON(bit) true
-#endif
-
 namespace fftconv {
 
 namespace {
@@ -79,7 +71,7 @@ using namespace f3;
 template <int N2, int N3, typename TT, bool REGC, bool CPLX, int LIVE = 4>
 __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *u, uint16_t *y,
                                               const uint32_t *__restrict__ kf, Consts cs, int B, int H, int N,
-                                              int probe, int KoN, int ko_lo, int ko_hi)
+                                              int KoN, int ko_lo, int ko_hi)
 {
     using G = Geo<N2, N3>;
     constexpr int R2 = G::R2, R3 = G::R3, C3 = G::C3, C1 = G::C1;
@@ -239,7 +231,7 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *u, uint16_t *y,
             const int b = 2 * pair + s;
             uint4 v = make_uint4(0, 0, 0, 0);
             const uint16_t *row = u + ((size_t)b * H + h) * N;
-            if (PROBE_ON(8) && k < cnt && b < B && n < N) v = *(const uint4 *)(row + n);
+            if (k < cnt && b < B && n < N) v = *(const uint4 *)(row + n);
             pre[j] = v;
         }
     };
@@ -292,7 +284,7 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *u, uint16_t *y,
             const uint32_t *src = (const uint32_t *)(YB + s * G::SU + n1 * G::PQ1 + n2 * G::PR + n3);
             const uint4 v = make_uint4(src[0], src[1], src[2], src[3]);
             uint16_t *row = y + ((size_t)b * H + h) * N;
-            if (PROBE_ON(16) && b < B && n < N) *(uint4 *)(row + n) = v;
+            if (b < B && n < N) *(uint4 *)(row + n) = v;
         }
     };
 
@@ -325,7 +317,6 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *u, uint16_t *y,
         //  traffic of one tile drains while the next tile computes)
         {
             uint4 x1[C3][R2][KS1];
-            if (PROBE_ON(1))
 #pragma unroll
             for (int i = 0; i < C3; ++i) {
                 const int c = w * C3 + i;
@@ -349,7 +340,6 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *u, uint16_t *y,
                     }
                 }
             }
-            if (PROBE_ON(1))
 #pragma unroll
             for (int i = 0; i < C3; ++i) {
                 const int c = w * C3 + i;
@@ -405,7 +395,6 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *u, uint16_t *y,
         // ================= phase B: per k1 = c: stage 3, k_f, inverse 3, twiddle, inverse 2 -> XB in place
         {
             uint4 x3[C1][R2][R3];
-            if (PROBE_ON(2))
 #pragma unroll
             for (int i = 0; i < C1; ++i) {
                 const int c = w * C1 + i;
@@ -426,7 +415,6 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *u, uint16_t *y,
             stage_in();
             issue_loads(k + 2);
             if (k > 0) store_out(k - 1);
-            if (PROBE_ON(2))
 #pragma unroll
             for (int i = 0; i < C1; ++i) {
                 const int c = w * C1 + i;
@@ -503,7 +491,6 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *u, uint16_t *y,
         // ================= phase C: per n3 = c: inverse stage 1 (n1 < 16; re -> row b, im -> row b+1) -> YB
         {
             uint4 x1i[C3][R2][2];
-            if (PROBE_ON(4))
 #pragma unroll
             for (int i = 0; i < C3; ++i) {
                 const int c = w * C3 + i;
@@ -515,7 +502,6 @@ __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *u, uint16_t *y,
                         x1i[i][cn2][ks] = make_uint4(src[0], src[G::PK1], src[2 * G::PK1], src[3 * G::PK1]);
                     }
             }
-            if (PROBE_ON(4))
 #pragma unroll
             for (int i = 0; i < C3; ++i) {
                 const int c = w * C3 + i;
@@ -759,16 +745,6 @@ int build_tables(fftconv_plan *p, void **dest, int groups = 1)
     return FFTCONV_OK;
 }
 
-int probe_mask()
-{
-#ifdef FUSED3_PROBE
-    const char *e = getenv("FUSED3_PROBE");
-    return e ? atoi(e) : 0;
-#else
-    return 0;
-#endif
-}
-
 // Rows: for the causal kernel (CPLX false) B batch rows of H channels, N samples each; for the
 // complex-row kernel B rows per k_f row, H k_f rows.
 template <int N2, int N3, typename TT, bool REGC, bool CPLX, int LIVE = 4>
@@ -778,11 +754,7 @@ int launch(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_
     using G = Geo<N2, N3>;
     auto kern = k_fused3<N2, N3, TT, REGC, CPLX, LIVE>;
     constexpr size_t lds = CPLX ? G::LDS_BYTES_C : G::LDS_BYTES;
-    static bool attr_set = false;
-    if (!attr_set) {
-        FC_HIP(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        attr_set = true;
-    }
+    FC_TRY(raise_dynamic_lds((const void *)kern, (int)lds));
     const int64_t npairs = CPLX ? B : (B + 1) / 2;
     const int64_t T = H * npairs;
     if (T >= ((int64_t)1 << 31)) {
@@ -794,7 +766,7 @@ int launch(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_
     int grid = (int)(T < p->f3.num_cu ? T : p->f3.num_cu);
     if (!REGC && grid >= 8) grid -= grid % 8;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NT), lds, s, (const uint16_t *)u, (uint16_t *)y,
-                       (const uint32_t *)kf, consts_of<N2, N3>(p), (int)B, (int)H, (int)N, probe_mask(), KoN, ko_lo, ko_hi);
+                       (const uint32_t *)kf, consts_of<N2, N3>(p), (int)B, (int)H, (int)N, KoN, ko_lo, ko_hi);
     FC_HIP(hipGetLastError());
     return FFTCONV_OK;
 }
@@ -989,12 +961,7 @@ static int launch_filter_fused3(const float *k, int64_t Nk, int64_t H, uint2 *kf
                                 hipStream_t s)
 {
     const size_t bytes = lds_row_bytes(Ms, sizeof(float2));
-    static bool raised = false;
-    if (!raised) {
-        FC_HIP(hipFuncSetAttribute((const void *)k_filter_fused3, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                   (int)lds_row_bytes(8192, sizeof(float2))));
-        raised = true;
-    }
+    FC_TRY(raise_dynamic_lds((const void *)k_filter_fused3, (int)lds_row_bytes(8192, sizeof(float2))));
     hipLaunchKernelGGL(k_filter_fused3, dim3((unsigned)H), dim3(FILT_THREADS), bytes, s, k, kf, w, fl, Nk, (int)tws, reversed,
                        keep_dev, n_blocks, fmt, (int)(8192 / Ms));
     FC_HIP(hipGetLastError());

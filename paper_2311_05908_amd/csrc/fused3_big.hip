@@ -30,34 +30,6 @@
 #include "fused3_common.h"
 #include "lds_fft.h"
 
-#ifdef FUSED3_PROBE
-// development build only: time stamps of one workgroup, read back with fftconv_debug_stamps_big()
-__device__ unsigned long long g_stamps_big[8 * 8 * 16];
-#define BSTAMP(k)                                                                                 \
-    do {                                                                                          \
-        if (blockIdx.x == 3 && l == 0 && it >= 4 && it < 12)                                      \
-            g_stamps_big[(w * 8 + (it - 4)) * 16 + (k)] = __builtin_amdgcn_s_memtime();           \
-    } while (0)
-__device__ unsigned long long g_span_big[1024 * 2];
-extern "C" int fftconv_debug_span_big(unsigned long long *dst)
-{
-    return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(g_span_big), sizeof(g_span_big));
-}
-#define BSPAN(k)                                                                                  \
-    do {                                                                                          \
-        if (threadIdx.x == 0 && blockIdx.x < 1024) g_span_big[blockIdx.x * 2 + (k)] = __builtin_amdgcn_s_memtime(); \
-    } while (0)
-extern "C" int fftconv_debug_stamps_big(unsigned long long *dst)
-{
-    return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(g_stamps_big), sizeof(g_stamps_big));
-}
-#define BPROBE(bit) (!(probe & (bit)))
-#else
-#define BSTAMP(k) do { } while (0)
-#define BSPAN(k) do { } while (0)
-#define BPROBE(bit) true
-#endif
-
 namespace fftconv {
 namespace f3 {
 
@@ -132,7 +104,7 @@ __host__ __device__ inline int big_sigma_inv(int d)
 template <typename TT, bool FULL, int N2, bool HALF3, bool GATED = false>
 __global__ void __launch_bounds__(NT, (N2 == 16 && !GATED) ? 4 : 2) k_fused3_big(const uint16_t *__restrict__ u, uint16_t *__restrict__ y,
                                                   const void *__restrict__ kf, const void *__restrict__ consts,
-                                                  uint32_t kf_bytes, int B, int H, int N, int probe,
+                                                  uint32_t kf_bytes, int B, int H, int N,
                                                   const uint16_t *__restrict__ wg, const uint16_t *__restrict__ vg)
 {
     using CW = typename TT::CW;
@@ -151,7 +123,6 @@ __global__ void __launch_bounds__(NT, (N2 == 16 && !GATED) ? 4 : 2) k_fused3_big
     const int x = blockIdx.x % nx, nb = gridDim.x / nx, jb = blockIdx.x / nx;
     const int n_local = ((H - x + nx - 1) / nx) * npairs;         // work items of this die
     if (jb >= n_local) return;
-    BSPAN(0);
     auto item = [&](int v) { return ((v / npairs) * nx + x) * npairs + v % npairs; };
     const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
 
@@ -214,7 +185,7 @@ __global__ void __launch_bounds__(NT, (N2 == 16 && !GATED) ? 4 : 2) k_fused3_big
                 for (int p = 0; p < 2; ++p) tab3[a][b][p] = ld16(rc, sz, BG::OFF_TAB3 + ((a * 2 + b) * 2 + p) * 1024);
     };
     auto load_tabA = [&](int i) {
-        const int c = BPROBE(4) ? 4 * w + i : 0, sl = i % PD;
+        const int c = 4 * w + i, sl = i % PD;
         const int base = sz + c * BG::PLANE2;
 #pragma unroll
         for (int a = 0; a < R2; ++a)
@@ -224,7 +195,7 @@ __global__ void __launch_bounds__(NT, (N2 == 16 && !GATED) ? 4 : 2) k_fused3_big
                 for (int p = 0; p < 2; ++p) tabA[sl][a][b][p] = ld16(rc, base, BG::OFF_TAB2 + ((a * R2 + b) * 2 + p) * 1024);
     };
     auto load_twa = [&](int i) {
-        const int c = BPROBE(4) ? 4 * w + i : 0, sl = i % PD;
+        const int c = 4 * w + i, sl = i % PD;
         const int base = sz + c * BG::PLANEW;
 #pragma unroll
         for (int a = 0; a < R2; ++a)
@@ -234,7 +205,7 @@ __global__ void __launch_bounds__(NT, (N2 == 16 && !GATED) ? 4 : 2) k_fused3_big
                 for (int r = 0; r < 4; ++r) twaR[sl][a][b][r] = ld4(rc, base, BG::OFF_TWA + ((a * 2 + b) * 4 + r) * 256);
     };
     auto load_tabB = [&](int i) {
-        const int c = BPROBE(4) ? 4 * w + i : 0, sl = i % PD;
+        const int c = 4 * w + i, sl = i % PD;
         const int base = sz + c * BG::PLANE2;
 #pragma unroll
         for (int a = 0; a < R2; ++a)
@@ -244,7 +215,7 @@ __global__ void __launch_bounds__(NT, (N2 == 16 && !GATED) ? 4 : 2) k_fused3_big
                 for (int p = 0; p < 2; ++p) tabB[sl][a][b][p] = ld16(rc, base, BG::OFF_TAB2I + ((a * R2 + b) * 2 + p) * 1024);
     };
     auto load_twb = [&](int i) {
-        const int c = BPROBE(4) ? 4 * w + i : 0, sl = i % PD;
+        const int c = 4 * w + i, sl = i % PD;
         const int base = sz + c * BG::PLANEW;
 #pragma unroll
         for (int a = 0; a < R2; ++a)
@@ -254,8 +225,8 @@ __global__ void __launch_bounds__(NT, (N2 == 16 && !GATED) ? 4 : 2) k_fused3_big
                 for (int r = 0; r < 4; ++r) twbR[sl][a][b][r] = ld4(rc, base, BG::OFF_TWB + ((a * 2 + b) * 4 + r) * 256);
     };
     auto load_kf = [&](int i, int h) {
-        const int c = BPROBE(4) ? 4 * w + i : 0, sl = i % PD;
-        const int base = sz + ((BPROBE(4) ? h : 0) * 32 + c) * BG::PLANEW;
+        const int c = 4 * w + i, sl = i % PD;
+        const int base = sz + (h * 32 + c) * BG::PLANEW;
 #pragma unroll
         for (int a = 0; a < R2; ++a)
 #pragma unroll
@@ -369,7 +340,7 @@ __global__ void __launch_bounds__(NT, (N2 == 16 && !GATED) ? 4 : 2) k_fused3_big
                 }
             }
             SCHED_FENCE();
-            if (i + PD < 4 && BPROBE(2)) load_twa(i + PD);
+            if (i + PD < 4) load_twa(i + PD);
             SCHED_FENCE();
 #pragma unroll
             for (int ct = 0; ct < 2; ++ct)
@@ -387,7 +358,7 @@ __global__ void __launch_bounds__(NT, (N2 == 16 && !GATED) ? 4 : 2) k_fused3_big
                                                TT::pack(dre[2], dim[2]), TT::pack(dre[3], dim[3]));
                 }
             SCHED_FENCE();
-            if (i + PD < 4 && BPROBE(2)) load_tabA(i + PD);
+            if (i + PD < 4) load_tabA(i + PD);
             SCHED_FENCE();
         }
     };
@@ -497,7 +468,7 @@ __global__ void __launch_bounds__(NT, (N2 == 16 && !GATED) ? 4 : 2) k_fused3_big
                     x3i[ct2][ct3] = TT::template ctw4<true>(dre, dim, kfR[i % PD][ct2][ct3]);
                 }
             SCHED_FENCE();
-            if (i + PD < 4 && BPROBE(1)) load_kf(i + PD, h);
+            if (i + PD < 4) load_kf(i + PD, h);
             if (i + 1 < 4) read_plane(i + 1, x3);         // its latency hides behind the rest of this plane
             SCHED_FENCE();
             uint4 x2i[2][R2];                             // [n3 tile][K step = k2 tile]
@@ -515,7 +486,7 @@ __global__ void __launch_bounds__(NT, (N2 == 16 && !GATED) ? 4 : 2) k_fused3_big
                     x2i[cn3][ct2] = TT::template ctw4<true>(dre, dim, twbR[i % PD][ct2][cn3]);
                 }
             SCHED_FENCE();
-            if (i + PD < 4 && BPROBE(1)) load_twb(i + PD);
+            if (i + PD < 4) load_twb(i + PD);
             SCHED_FENCE();
 #pragma unroll
             for (int cn3 = 0; cn3 < 2; ++cn3)
@@ -533,9 +504,8 @@ __global__ void __launch_bounds__(NT, (N2 == 16 && !GATED) ? 4 : 2) k_fused3_big
                                                TT::pack(dre[2], dim[2]), TT::pack(dre[3], dim[3]));
                 }
             SCHED_FENCE();
-            if (i + PD < 4 && BPROBE(1)) load_tabB(i + PD);
+            if (i + PD < 4) load_tabB(i + PD);
             SCHED_FENCE();
-            BSTAMP(12 + i);
         }
     };
 
@@ -569,14 +539,12 @@ __global__ void __launch_bounds__(NT, (N2 == 16 && !GATED) ? 4 : 2) k_fused3_big
     [[maybe_unused]] int it = -1;
     for (int v = jb; v < n_local; v += nb) {
         ++it;
-        BSTAMP(0);
         opaque();
         // Past the end of the range the last pair is prepared once more (in range, never used):
         // the loop body stays free of branches.
         const int t = item(v), tn = v + nb < n_local ? item(v + nb) : t;
         phase_B(t / npairs, it);
         SCHED_FENCE();
-        BSTAMP(1);
         // tables of the next phase and the next pair's input: in flight across the barrier and phase C
         load_fixed_outer();
 #pragma unroll
@@ -588,24 +556,16 @@ __global__ void __launch_bounds__(NT, (N2 == 16 && !GATED) ? 4 : 2) k_fused3_big
         issue_gate_v(t);
         SCHED_FENCE();
         lds_barrier();
-        BSTAMP(2);
         phase_C();
-        BSTAMP(3);
         lds_barrier();                                  // every wave has read its planes: the buffer is free
-        BSTAMP(4);
         stage_out();
         stage_in();
-        BSTAMP(5);
         lds_barrier();
-        BSTAMP(6);
         read_y();
         read_x1();
-        BSTAMP(7);
         lds_barrier();                                  // staging consumed: phase A may overwrite it
-        BSTAMP(8);
         phase_A();
         SCHED_FENCE();
-        BSTAMP(9);
         load_tab3();
 #pragma unroll
         for (int i = 0; i < PD; ++i) {
@@ -617,11 +577,8 @@ __global__ void __launch_bounds__(NT, (N2 == 16 && !GATED) ? 4 : 2) k_fused3_big
         // the stores go last: loads and stores retire through one counter on this target, and
         // nothing issued after them is waited for before the next barrier
         store_y(t);
-        BSTAMP(10);
         lds_barrier();
-        BSTAMP(11);
     }
-    BSPAN(1);
 }
 
 // ---- Filter gradient for fft 16384 and 32768 (Section 3.1 "Kernel Fusion and Recomputation"; see fused3_dk.hip
@@ -1040,32 +997,13 @@ template <typename Fn> void fill_op(uint16_t *dst, bool f16, int t, int ct, int 
     }
 }
 
-int big_probe()
-{
-#ifdef FUSED3_PROBE
-    const char *e = getenv("FUSED3_PROBE");
-    return e ? atoi(e) : 0;
-#else
-    return 0;
-#endif
-}
-
 template <typename TT, bool FULL, int N2, bool HALF3, bool GATED = false>
 int launch_big(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, hipStream_t s,
                const void *wg = nullptr, const void *vg = nullptr)
 {
     using BG = BigGeo<N2>;
     auto kern = k_fused3_big<TT, FULL, N2, HALF3, GATED>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        FC_HIP(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)BG::LDS_BYTES));
-        attr_set = true;
-#ifdef FUSED3_PROBE
-        int nblk = -1;
-        hipOccupancyMaxActiveBlocksPerMultiprocessor(&nblk, (const void *)kern, NT, BG::LDS_BYTES);
-        fprintf(stderr, "k_fused3_big<N2=%d>: %d resident workgroups per compute unit, LDS %zu\n", N2, nblk, BG::LDS_BYTES);
-#endif
-    }
+    FC_TRY(raise_dynamic_lds((const void *)kern, (int)BG::LDS_BYTES));
     const int64_t T = p->H * ((B + 1) / 2);
     const int64_t kf_bytes = p->H * BG::M * 4;
     if (kf_bytes >= ((int64_t)1 << 31)) {
@@ -1083,7 +1021,7 @@ int launch_big(const fftconv_plan *p, const void *u, const void *kf, void *y, in
     int grid = (int)(T < resident ? T : resident);
     if (grid >= 8) grid -= grid % 8;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NT), BG::LDS_BYTES, s, (const uint16_t *)u, (uint16_t *)y,
-                       kf, (const void *)p->f3.consts, (uint32_t)kf_bytes, (int)B, (int)p->H, (int)p->N, big_probe(),
+                       kf, (const void *)p->f3.consts, (uint32_t)kf_bytes, (int)B, (int)p->H, (int)p->N,
                        (const uint16_t *)wg, (const uint16_t *)vg);
     FC_HIP(hipGetLastError());
     return FFTCONV_OK;
@@ -1164,11 +1102,7 @@ int big_filter_tt(const fftconv_plan *p, const float *k, int64_t Nk, bool adjoin
 {
     constexpr int64_t MH = BigGeo<N2>::M / 2;
     const size_t bytes = lds_row_bytes(MH, sizeof(float2));
-    static bool raised = false;
-    if (!raised) {
-        FC_HIP(hipFuncSetAttribute((const void *)k_filter_big<TT, N2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
-        raised = true;
-    }
+    FC_TRY(raise_dynamic_lds((const void *)k_filter_big<TT, N2>, (int)bytes));
     hipLaunchKernelGGL((k_filter_big<TT, N2>), dim3((unsigned)p->H), dim3(BIG_FILT_THREADS), bytes, s, k,
                        (typename TT::CW *)kf, (const float2 *)p->st.w32, staged_factors_for(MH), Nk, adjoint, keep_dev,
                        n_blocks);
@@ -1263,12 +1197,7 @@ static int big_dk_accumulate_t(const fftconv_plan *p, const void *u, const void 
     void (*kern)(const uint16_t *, const uint16_t *, float2 *, const void *, int, int, int) =
         f16 ? (full ? k_fused3_big_dk<H16, true, N2> : k_fused3_big_dk<H16, false, N2>)
             : (full ? k_fused3_big_dk<B16, true, N2> : k_fused3_big_dk<B16, false, N2>);
-    static bool attr_set[4] = {false, false, false, false};
-    const int slot = (f16 ? 2 : 0) + (full ? 1 : 0);
-    if (!attr_set[slot]) {
-        FC_HIP(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)BG::LDS_BYTES));
-        attr_set[slot] = true;
-    }
+    FC_TRY(raise_dynamic_lds((const void *)kern, (int)BG::LDS_BYTES));
     const int grid = (int)(p->H < p->f3.num_cu ? p->H : p->f3.num_cu);
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NT), BG::LDS_BYTES, s, (const uint16_t *)u, (const uint16_t *)dy,
                        (float2 *)dkf, (const void *)p->f3.consts, (int)B, (int)p->H, (int)p->N);

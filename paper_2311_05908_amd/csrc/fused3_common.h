@@ -18,6 +18,15 @@ typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
 typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
 
+// Wait states between the dot products of a hand-written block and the first conversion that reads
+// one of them: none in the release build (the instruction order alone keeps every DOT result 3 issue
+// slots away from its reader), eight extra in the checking build.
+#ifdef FFTCONV_SYNC_CHECK
+#define DOT_SLACK "s_nop 7\n\t"
+#else
+#define DOT_SLACK ""
+#endif
+
 struct BF16 {
     static __device__ __forceinline__ f32x4 mfma(uint4 a, uint4 b, f32x4 c)
     {
@@ -51,7 +60,7 @@ struct BF16 {
             "v_dot2_f32_bf16 %5, %10, %17, 0\n\t"
             "v_dot2_f32_bf16 %6, %11, %18, 0\n\t"
             "v_dot2_f32_bf16 %7, %11, %19, 0\n\t"
-            "v_cvt_pk_bf16_f32 %0, %0, %1\n\t"
+            DOT_SLACK "v_cvt_pk_bf16_f32 %0, %0, %1\n\t"
             "v_cvt_pk_bf16_f32 %2, %2, %3\n\t"
             "v_cvt_pk_bf16_f32 %4, %4, %5\n\t"
             "v_cvt_pk_bf16_f32 %6, %6, %7"
@@ -76,7 +85,7 @@ struct BF16 {
             "v_dot2_f32_bf16 %5, %10, %17, 0\n\t"
             "v_dot2_f32_bf16 %6, %11, %18, 0\n\t"
             "v_dot2_f32_bf16 %7, %11, %19, 0\n\t"
-            "v_cvt_pk_bf16_f32 %0, %0, %1\n\t"
+            DOT_SLACK "v_cvt_pk_bf16_f32 %0, %0, %1\n\t"
             "v_cvt_pk_bf16_f32 %2, %2, %3\n\t"
             "v_cvt_pk_bf16_f32 %4, %4, %5\n\t"
             "v_cvt_pk_bf16_f32 %6, %6, %7"
@@ -161,7 +170,7 @@ struct B16 {
             "v_dot2_f32_bf16 %5, %10, %5, 0" IMNEG "\n\t"                                           \
             "v_dot2_f32_bf16 %6, %11, %15, 0 neg_hi:[0,1,0]\n\t"                                    \
             "v_dot2_f32_bf16 %7, %11, %7, 0" IMNEG "\n\t"                                           \
-            "v_cvt_pk_bf16_f32 %0, %0, %1\n\t"                                                      \
+            DOT_SLACK "v_cvt_pk_bf16_f32 %0, %0, %1\n\t"                                                      \
             "v_cvt_pk_bf16_f32 %2, %2, %3\n\t"                                                      \
             "v_cvt_pk_bf16_f32 %4, %4, %5\n\t"                                                      \
             "v_cvt_pk_bf16_f32 %6, %6, %7"                                                          \
@@ -233,9 +242,16 @@ struct H16 {
 // throw away the prefetches and stores these kernels keep in flight across barriers.  LDS
 // operations of a wave complete in order, so once its LDS counter is zero its writes are visible
 // to, and its reads are finished before, whatever the other waves do after the barrier.
+// A build with FFTCONV_SYNC_CHECK defined (tests only) uses the full __syncthreads() instead and
+// pads the hand-spaced dot-product blocks with wait states (DOT_SLACK); its results must be
+// bit-identical to the release build's.
 __device__ __forceinline__ void lds_barrier()
 {
+#ifdef FFTCONV_SYNC_CHECK
+    __syncthreads();
+#else
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+#endif
 }
 
 template <int N2, int N3> struct Geo {

@@ -284,12 +284,7 @@ int fused3_dk_accumulate(const fftconv_plan *p, const void *u, const void *dy, v
     void (*kern)(const uint16_t *, const uint16_t *, float2 *, Consts, int, int, int, int, int) =
         f16 ? (full ? k_fused3_dk<F16, true> : k_fused3_dk<F16, false>)
             : (full ? k_fused3_dk<BF16, true> : k_fused3_dk<BF16, false>);
-    static bool attr_set[4] = {false, false, false, false};
-    const int slot = (f16 ? 2 : 0) + (full ? 1 : 0);
-    if (!attr_set[slot]) {
-        FC_HIP(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)DK_LDS_BYTES));
-        attr_set[slot] = true;
-    }
+    FC_TRY(raise_dynamic_lds((const void *)kern, (int)DK_LDS_BYTES));
     const int grid = (int)(p->H < p->f3.num_cu ? p->H : p->f3.num_cu);
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NT), DK_LDS_BYTES, s, (const uint16_t *)u, (const uint16_t *)dy,
                        (float2 *)dkf, consts_at<16, 16>(p->f3.consts), (int)B, (int)p->H, (int)p->N, groups, lg_half);
@@ -299,12 +294,7 @@ int fused3_dk_accumulate(const fftconv_plan *p, const void *u, const void *dy, v
 
 int fused3_dk_finish(const fftconv_plan *p, const void *dkf, float *dk, int64_t Nk, hipStream_t s)
 {
-    static bool raised = false;
-    if (!raised) {
-        FC_HIP(hipFuncSetAttribute((const void *)k_dk_finish, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                   (int)lds_row_bytes(G::M, sizeof(float2))));
-        raised = true;
-    }
+    FC_TRY(raise_dynamic_lds((const void *)k_dk_finish, (int)lds_row_bytes(G::M, sizeof(float2))));
     hipLaunchKernelGGL(k_dk_finish, dim3((unsigned)p->H), dim3(DK_FIN_THREADS), lds_row_bytes(p->M, sizeof(float2)), s,
                        (const float2 *)dkf, dk, (const float2 *)p->st.w32, staged_fac_list(p), Nk, (int)(G::M / p->M));
     FC_HIP(hipGetLastError());

@@ -17,27 +17,8 @@
 // Each role keeps only its own constant tables in registers (outer: stage-1/2 matrices and the
 // forward twiddles of its 4 n3 planes; inner: stage-3 matrices, k_f[h], inverse twiddles and
 // per-k1 inverse matrices of its 8 k1 planes).
-#include <cstdlib>
-
 #include "fused3_common.h"
 
-#ifdef FUSED3_PROBE
-#define WPROBE(bit) (!(probe & (bit)))
-// development build only: time stamps of one workgroup, read back with fftconv_debug_stamps()
-__device__ unsigned long long g_stamps[8 * 16 * 16];
-#define STAMP(k)                                                                              \
-    do {                                                                                      \
-        if (blockIdx.x == 3 && l == 0 && s >= t0 + 40 && s < t0 + 56)                         \
-            g_stamps[(w * 16 + (s - t0 - 40)) * 16 + (k)] = __builtin_amdgcn_s_memtime();     \
-    } while (0)
-extern "C" int fftconv_debug_stamps(unsigned long long *dst)
-{
-    return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(g_stamps), sizeof(g_stamps));
-}
-#else
-#define WPROBE(bit) true
-#define STAMP(k) do { } while (0)
-#endif
 
 namespace fftconv {
 namespace f3 {
@@ -64,7 +45,7 @@ constexpr int PCH = G::M / 8 / PT;            // 16-byte input chunks per outer-
 template <typename TT, bool FULL, int GATE, bool SKIP1 = false>
 __global__ void __launch_bounds__(NT) k_fused3_ws(const uint16_t *__restrict__ u, uint16_t *__restrict__ y,
                                                  const uint2 *__restrict__ kf, Consts cs, int B, int H, int N, int nseg, int P, int Lo,
-                                                 int probe, const uint16_t *__restrict__ wg, const uint16_t *__restrict__ vg,
+                                                 const uint16_t *__restrict__ wg, const uint16_t *__restrict__ vg,
                                                  uint32_t live_k1, int groups, int lg_half)
 {
     extern __shared__ uint32_t smem[];
@@ -213,12 +194,10 @@ __global__ void __launch_bounds__(NT) k_fused3_ws(const uint16_t *__restrict__ u
         lds_barrier();
 
         for (int s = t0 - 1; s <= t1 + 1; ++s) {
-            const bool doC = WPROBE(1) && s - 1 >= t0 && s - 1 < t1;
-            const bool doA = WPROBE(2) && s + 1 < t1;
-            STAMP(0);
-            if (WPROBE(8)) issue_loads(s + 2);
+            const bool doC = s - 1 >= t0 && s - 1 < t1;
+            const bool doA = s + 1 < t1;
+            issue_loads(s + 2);
             issue_loads_v(s - 2);
-            STAMP(1);
             // ---- phase C of item s-1: inverse stage 1, n1 < 16; re -> row b, im -> row b+1 -> YB
             if (doC) {
                 const uint32_t *XB = XBb + ((s - 1) & 1) * XBW;
@@ -260,7 +239,6 @@ __global__ void __launch_bounds__(NT) k_fused3_ws(const uint16_t *__restrict__ u
                     }
                 }
             }
-            STAMP(2);
             // ---- phase A of item s+1: stage 1, twiddle, stage 2 -> XB
             if (doA) {
                 uint32_t *XB = XBb + ((s + 1) & 1) * XBW;
@@ -301,16 +279,12 @@ __global__ void __launch_bounds__(NT) k_fused3_ws(const uint16_t *__restrict__ u
                     }
                 }
             }
-            STAMP(3);
             // ---- staging: input of item s+2 (its loads were issued at the start of this step) -> UB,
             //      then output of item s-2 -> HBM.  The input goes first: it waits for the loads, and
             //      loads and stores retire through one counter on this target.
-            if (WPROBE(8) && s + 2 < t1) stage_in(UBb + ((s + 2) & 1) * UBE);
-            STAMP(4);
-            if (WPROBE(16) && s - 2 >= t0) store_out(s - 2, YBb + ((s - 2) & 1) * UBE);
-            STAMP(5);
+            if (s + 2 < t1) stage_in(UBb + ((s + 2) & 1) * UBE);
+            if (s - 2 >= t0) store_out(s - 2, YBb + ((s - 2) & 1) * UBE);
             lds_barrier();
-            STAMP(6);
         }
     } else {
         // =========================== inner role: phase B ===========================
@@ -333,8 +307,7 @@ __global__ void __launch_bounds__(NT) k_fused3_ws(const uint16_t *__restrict__ u
         lds_barrier();                                          // pairs with the outer role's prologue barrier
         int h_cur = -1;
         for (int s = t0 - 1; s <= t1 + 1; ++s) {
-            STAMP(0);
-            if (WPROBE(4) && s >= t0 && s < t1) {
+            if (s >= t0 && s < t1) {
                 const int h = s / per_h;
                 if (h != h_cur) {                                 // new channel: its k_f slice for this wave's k1 planes
                     h_cur = h;
@@ -382,24 +355,12 @@ __global__ void __launch_bounds__(NT) k_fused3_ws(const uint16_t *__restrict__ u
                                                TT::pack(dre[2], dim[2]), TT::pack(dre[3], dim[3]));
                 }
             }
-            STAMP(5);
             lds_barrier();
-            STAMP(6);
         }
     }
 }
 
 }  // namespace
-
-static int ws_probe()
-{
-#ifdef FUSED3_PROBE
-    const char *e = getenv("FUSED3_PROBE");
-    return e ? atoi(e) : 0;
-#else
-    return 0;
-#endif
-}
 
 // nseg == 1: plain causal convolution (N <= fft/2).  nseg > 1: overlap-save segments of a partial
 // convolution, P samples of history per segment, Lo = fft/2 - P outputs per later segment.
@@ -428,7 +389,7 @@ int fused3_ws_launch(const fftconv_plan *p, const void *consts, const void *u, c
     const bool full = (B % (2 * groups) == 0) && p->N == G::M / 2 / groups && nseg == 1;
     const bool f16 = p->dtype == FFTCONV_F16;
     const int gate = (wg ? 1 : 0) | (vg ? 2 : 0);
-    using Kern = void (*)(const uint16_t *, uint16_t *, const uint2 *, Consts, int, int, int, int, int, int, int,
+    using Kern = void (*)(const uint16_t *, uint16_t *, const uint2 *, Consts, int, int, int, int, int, int,
                           const uint16_t *, const uint16_t *, uint32_t, int, int);
     static const Kern table[2][2][4] = {
         {{k_fused3_ws<BF16, false, 0>, k_fused3_ws<BF16, false, 1>, k_fused3_ws<BF16, false, 2>, k_fused3_ws<BF16, false, 3>},
@@ -440,14 +401,10 @@ int fused3_ws_launch(const fftconv_plan *p, const void *consts, const void *u, c
                                           {k_fused3_ws<F16, false, 0, true>, k_fused3_ws<F16, true, 0, true>}};
     const bool skip = live_k1 != 0xffffffffu && gate == 0;
     const Kern kern = skip ? table_skip[f16 ? 1 : 0][full ? 1 : 0] : table[f16 ? 1 : 0][full ? 1 : 0][gate];
-    static bool attr_set[2][2][5] = {};
-    if (!attr_set[f16 ? 1 : 0][full ? 1 : 0][skip ? 4 : gate]) {
-        FC_HIP(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)WS_LDS_BYTES));
-        attr_set[f16 ? 1 : 0][full ? 1 : 0][skip ? 4 : gate] = true;
-    }
+    FC_TRY(raise_dynamic_lds((const void *)kern, (int)WS_LDS_BYTES));
     const int grid = (int)(T < p->f3.num_cu ? T : p->f3.num_cu);
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NT), WS_LDS_BYTES, s, (const uint16_t *)u, (uint16_t *)y,
-                       (const uint2 *)kf, consts_at<16, 16>(consts), (int)B, (int)p->H, (int)p->N, nseg, P, Lo, ws_probe(),
+                       (const uint2 *)kf, consts_at<16, 16>(consts), (int)B, (int)p->H, (int)p->N, nseg, P, Lo,
                        (const uint16_t *)wg, (const uint16_t *)vg, live_k1, groups, lg_half);
     FC_HIP(hipGetLastError());
     return FFTCONV_OK;

@@ -341,21 +341,13 @@ LongTw long_tw(const fftconv_plan *p)
     return t;
 }
 
-int raise_lds(const void *kern, bool *done)
-{
-    if (!*done) {
-        FC_HIP(hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)L_LDS));
-        *done = true;
-    }
-    return FFTCONV_OK;
-}
+int raise_lds(const void *kern) { return raise_dynamic_lds(kern, (int)L_LDS); }
 
 template <typename In>
 int launch_fwd_cols(const LongGeo &g, const In *re, const In *im, float2 *tmp, const LongTw &w, int64_t rows, int64_t len,
                     bool reversed, hipStream_t s)
 {
-    static bool raised = false;
-    const int rc = raise_lds((const void *)k_long_fwd_cols<In>, &raised);
+    const int rc = raise_lds((const void *)k_long_fwd_cols<In>);
     if (rc) return rc;
     hipLaunchKernelGGL(k_long_fwd_cols<In>, dim3((unsigned)g.A, (unsigned)rows), dim3(LT), L_LDS, s, re, im, tmp, w, g.flA,
                        g.A, g.C, len, reversed);
@@ -367,8 +359,7 @@ template <int MODE>
 int launch_fwd_blocks(const LongGeo &g, const float2 *tmp, float2 *out, const float2 *other, const LongTw &w, int64_t rows,
                       bool first, hipStream_t s)
 {
-    static bool raised = false;
-    const int rc = raise_lds((const void *)k_long_fwd_blocks<MODE>, &raised);
+    const int rc = raise_lds((const void *)k_long_fwd_blocks<MODE>);
     if (rc) return rc;
     hipLaunchKernelGGL(k_long_fwd_blocks<MODE>, dim3((unsigned)g.A, (unsigned)rows), dim3(LT), L_LDS, s, tmp, out, other, w,
                        g.flB, g.A, first);
@@ -399,9 +390,8 @@ int long_backward_filter_t(const fftconv_plan *p, const IO *u, const IO *dy, flo
         if (!rc) rc = launch_fwd_blocks<1>(g, tmp, acc, spec_u, tw, H, b == 0, s);
         if (rc) return rc;
     }
-    static bool raised_b = false, raised_c = false;
-    int rc = raise_lds((const void *)k_long_inv_blocks, &raised_b);
-    if (!rc) rc = raise_lds((const void *)k_long_inv_cols_dk, &raised_c);
+    int rc = raise_lds((const void *)k_long_inv_blocks);
+    if (!rc) rc = raise_lds((const void *)k_long_inv_cols_dk);
     if (rc) return rc;
     hipLaunchKernelGGL(k_long_inv_blocks, dim3((unsigned)g.A, (unsigned)H), dim3(LT), L_LDS, s, acc, tmp, tw, g.flB,
                        g.A);
@@ -430,12 +420,7 @@ int long_forward_t(const fftconv_plan *p, const IO *u, const float2 *kf, IO *y, 
                       (long long)npairs);
             return FFTCONV_EUNSUPPORTED;
         }
-        static bool raised = false;
-        if (!raised) {
-            FC_HIP(hipFuncSetAttribute((const void *)k_rows_conv_lds<IO>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)lds_row_bytes(2 * LB, sizeof(float2))));
-            raised = true;
-        }
+            FC_TRY(raise_dynamic_lds((const void *)k_rows_conv_lds<IO>, (int)lds_row_bytes(2 * LB, sizeof(float2))));
         hipLaunchKernelGGL(k_rows_conv_lds<IO>, dim3((unsigned)H, (unsigned)npairs), dim3(LT), lds_row_bytes(M, sizeof(float2)),
                            s, u, kf, y, (const float2 *)p->st.w32, staged_fac_list(p), (int)M, N, (int)B, (int)H);
         FC_HIP(hipGetLastError());
@@ -445,9 +430,8 @@ int long_forward_t(const fftconv_plan *p, const IO *u, const float2 *kf, IO *y, 
     const LongTw tw = long_tw(p);
     float2 *tmp = (float2 *)workspace;
     const int64_t chunk = conv_chunk(p);
-    static bool raised_b = false, raised_c = false;
-    int rc = raise_lds((const void *)k_long_conv_blocks, &raised_b);
-    if (!rc) rc = raise_lds((const void *)k_long_inv_cols_y<IO>, &raised_c);
+    int rc = raise_lds((const void *)k_long_conv_blocks);
+    if (!rc) rc = raise_lds((const void *)k_long_inv_cols_y<IO>);
     if (rc) return rc;
     for (int64_t b = 0; b < B; b += 2)
         for (int64_t h0 = 0; h0 < H; h0 += chunk) {
@@ -503,10 +487,8 @@ int long_filter_transform(const fftconv_plan *p, const float *k, int64_t Nk, int
     const LongTw tw = long_tw(p);
     int rc = launch_fwd_cols<float>(g, k, nullptr, tmp, tw, nh, Nk, adjoint, s);
     if (rc) return rc;
-    static bool raised = false;
-    rc = raise_lds((const void *)k_long_fwd_blocks_kf<true>, &raised);
-    static bool raised2 = false;
-    if (!rc) rc = raise_lds((const void *)k_long_fwd_blocks_kf<false>, &raised2);
+    rc = raise_lds((const void *)k_long_fwd_blocks_kf<true>);
+    if (!rc) rc = raise_lds((const void *)k_long_fwd_blocks_kf<false>);
     if (rc) return rc;
     if (p->dtype == FFTCONV_F16)
         hipLaunchKernelGGL(k_long_fwd_blocks_kf<true>, dim3((unsigned)g.A, (unsigned)nh), dim3(LT), L_LDS, s, tmp,

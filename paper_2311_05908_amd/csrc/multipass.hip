@@ -365,14 +365,8 @@ int launch_outer_t(bool inverse, const OuterGeo &g, dim3 grid, const void *src, 
 {
     constexpr int CV = RB <= 16 ? 2 : 1;           // two columns per thread while the registers allow
     const size_t lds = sizeof(float2) * ((size_t)g.No + (size_t)g.No * g.CT);
-    static bool attr_set = false;
-    if (!attr_set) {
-        FC_HIP(hipFuncSetAttribute((const void *)k_outer_fwd<F16, RA, RB, CV, FULLN, GATED>,
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
-        FC_HIP(hipFuncSetAttribute((const void *)k_outer_inv<F16, RA, RB, CV, FULLN, GATED>,
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
-        attr_set = true;
-    }
+    FC_TRY(raise_dynamic_lds((const void *)k_outer_fwd<F16, RA, RB, CV, FULLN, GATED>, 160 * 1024));
+    FC_TRY(raise_dynamic_lds((const void *)k_outer_inv<F16, RA, RB, CV, FULLN, GATED>, 160 * 1024));
     if (!inverse)
         hipLaunchKernelGGL((k_outer_fwd<F16, RA, RB, CV, FULLN, GATED>), grid, dim3(TB), lds, s, (const uint16_t *)src,
                            (uint32_t *)dst, g.CT, B, H, N, M, ko_lo, ko_hi, (const uint16_t *)gate);

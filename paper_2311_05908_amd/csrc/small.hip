@@ -269,12 +269,7 @@ int launch_small(const fftconv_plan *p, const void *u, const void *kf, void *y, 
     const int64_t cap = (int64_t)p->f3.num_cu * 4;
     const unsigned grid = (unsigned)(groups < cap ? groups : cap);
     constexpr size_t lds = sizeof(float2) * (PTS + PTS / 16 + M);
-    static bool attr_set = false;
-    if (!attr_set) {
-        FC_HIP(hipFuncSetAttribute((const void *)k_small<M, R0, R1, R2, IO>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                   (int)lds));
-        attr_set = true;
-    }
+    FC_TRY(raise_dynamic_lds((const void *)k_small<M, R0, R1, R2, IO>, (int)lds));
     hipLaunchKernelGGL((k_small<M, R0, R1, R2, IO>), dim3(grid), dim3(NTS), lds, s, (const IO *)u, (IO *)y,
                        (const float2 *)kf, (const float2 *)p->st.w32, (int)B, (int)p->H, (int)p->N);
     FC_HIP(hipGetLastError());

@@ -311,14 +311,7 @@ int staged_forward(const fftconv_plan *p, const void *u, const void *kf, void *y
 // Largest row the LDS-resident kernels take: 8192 fp64 or 16384 fp32 complex points with their padding.
 constexpr size_t LDS_ROW_MAX = (8192 + 512) * sizeof(double2);
 
-static int raise_lds_limit(const void *kern, bool *done)
-{
-    if (!*done) {
-        FC_HIP(hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_ROW_MAX));
-        *done = true;
-    }
-    return FFTCONV_OK;
-}
+static int raise_lds_limit(const void *kern) { return raise_dynamic_lds(kern, (int)LDS_ROW_MAX); }
 
 // Rows short enough for LDS take the one-kernel transform: *ran says whether this was one (otherwise the
 // caller runs the stages through HBM).
@@ -328,8 +321,7 @@ static int rows_fwd_lds(const fftconv_plan *p, const FacList &fl, int64_t M, int
     const size_t bytes = lds_row_bytes(M, sizeof(double2));
     *ran = bytes <= LDS_ROW_MAX && lds_factors_ok(fl);
     if (!*ran) return FFTCONV_OK;
-    static bool raised = false;
-    const int rc = raise_lds_limit((const void *)k_rows_fwd_lds, &raised);
+    const int rc = raise_lds_limit((const void *)k_rows_fwd_lds);
     if (rc) return rc;
     hipLaunchKernelGGL(k_rows_fwd_lds, dim3((unsigned)nh), dim3(LDS_ROW_THREADS), bytes, s, k, p->filt_a, p->st.w64, fl,
                        (int)M, Nk, (int)tws, reversed);
@@ -432,8 +424,7 @@ int staged_inverse_to_dk(const fftconv_plan *p, float2 *spec, float2 *other, int
     const int64_t M = p->M;
     const size_t lds_bytes = lds_row_bytes(M, sizeof(float2));
     if (lds_bytes <= LDS_ROW_MAX && lds_factors_ok(fac_list(p))) {
-        static bool raised = false;
-        const int rc = raise_lds_limit((const void *)k_rows_inv_dk_lds, &raised);
+        const int rc = raise_lds_limit((const void *)k_rows_inv_dk_lds);
         if (rc) return rc;
         hipLaunchKernelGGL(k_rows_inv_dk_lds, dim3((unsigned)nrows), dim3(LDS_ROW_THREADS), lds_bytes, s, spec, dk,
                            p->st.w32, fac_list(p), (int)M, Nk, 1.0f / (float)M);

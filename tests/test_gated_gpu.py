@@ -30,7 +30,7 @@ def run_gated(w, use_w=True, use_v=True):
 def check_all(w, use_w=True, use_v=True):
     u, gw, gv, k, y, plan = run_gated(w, use_w, use_v)
     ref = oracle.fftconv_gated(u.double().numpy(), None if gw is None else gw.double().numpy(),
-                               None if gv is None else gv.double().numpy(), k, w.fft_size, w.dtype)
+                               None if gv is None else gv.double().numpy(), k, w.fft_size)
     return float(oracle.rel_l2_per_sequence(y.double().numpy(), ref).max()), plan
 
 
@@ -112,7 +112,7 @@ def test_gated_cfg2_full_size_sampled_sequences():
     worst = 0.0
     for b, h in synth.sample_sequences(w, 28):
         ref = oracle.fftconv_gated(u[b, h].double().numpy()[None, None], gw[b, h].double().numpy()[None, None],
-                                   gv[b, h].double().numpy()[None, None], kext[h][None], None, w.dtype)[0, 0]
+                                   gv[b, h].double().numpy()[None, None], kext[h][None])[0, 0]
         worst = max(worst, float(oracle.rel_l2_per_sequence(y[b, h].double().numpy(), ref)))
     print("gated cfg2 full: worst sampled rel L2 = %.3e" % worst, flush=True)
     assert worst <= TOL[w.dtype]

@@ -250,7 +250,7 @@ def test_gated_with_unit_gates_is_the_plain_convolution():
     ones = np.ones_like(u)
     ref = oracle.fftconv(u.astype(np.float32), k, 40)
     for w, v in ((ones, ones), (None, ones), (ones, None), (None, None)):
-        assert np.allclose(oracle.fftconv_gated(u.astype(np.float32), w, v, k, 40, "f32"), ref, rtol=0, atol=1e-12)
+        assert np.allclose(oracle.fftconv_gated(u.astype(np.float32), w, v, k, 40), ref, rtol=0, atol=1e-12)
 
 
 def test_gated_integer_inputs_are_exact():
@@ -259,12 +259,11 @@ def test_gated_integer_inputs_are_exact():
     w = RNG.integers(-2, 3, (B, H, N)).astype(np.float64)
     v = RNG.integers(-3, 4, (B, H, N)).astype(np.float64)
     k = RNG.integers(-4, 5, (H, N)).astype(np.float64)
-    for dtype in ("f32", "f16", "bf16"):          # |u w| <= 8: exact in every dtype
-        y = oracle.fftconv_gated(u, w, v, k, 2 * N, dtype)
-        for b in range(B):
-            for h in range(H):
-                want = v[b, h] * np.convolve(u[b, h] * w[b, h], k[h])[:N]
-                assert np.array_equal(y[b, h], want)
+    y = oracle.fftconv_gated(u, w, v, k, 2 * N)
+    for b in range(B):
+        for h in range(H):
+            want = v[b, h] * np.convolve(u[b, h] * w[b, h], k[h])[:N]
+            assert np.array_equal(y[b, h], want)
 
 
 def test_gated_input_gate_as_a_window_and_output_gate_as_a_selector():
@@ -276,22 +275,32 @@ def test_gated_input_gate_as_a_window_and_output_gate_as_a_selector():
     ut[..., 10:] = 0.0
     v = np.zeros_like(u)
     v[..., 5] = 2.0
-    y = oracle.fftconv_gated(u, w, v, k, 64, "f32")
+    y = oracle.fftconv_gated(u, w, v, k, 64)
     ref = oracle.fftconv(ut, k, 64)
     assert np.allclose(y[..., 5], 2.0 * ref[..., 5], rtol=0, atol=1e-12)
     assert np.count_nonzero(np.delete(y, 5, axis=-1)) == 0
 
 
-def test_gated_product_is_rounded_to_the_io_dtype_before_the_transform():
-    # (1 + 2^-7)^2 = 1 + 2^-6 + 2^-14 is not a bf16 number: it rounds to 1 + 2^-6 before the convolution
+def test_gated_product_is_not_rounded_before_the_transform():
+    # Section 3.1 defines y = v . ((u . w) * k) in exact arithmetic: (1 + 2^-7)^2 = 1 + 2^-6 + 2^-14 is not a
+    # bf16 number, and the oracle must carry it unrounded into the convolution (delta filter: y = u . w);
+    # round_to alone shows what one rounding to bf16 would have made of it
     u = np.full((1, 1, 4), 1.0 + 2.0 ** -7)
     w = u.copy()
     k = np.zeros((1, 4))
-    k[0, 0] = 1.0                                  # delta: y = rounded product
-    y_b = oracle.fftconv_gated(u, w, None, k, 8, "bf16")
-    y_f = oracle.fftconv_gated(u, w, None, k, 8, "f32")
-    assert np.array_equal(y_b, np.full((1, 1, 4), 1.0 + 2.0 ** -6))
-    assert np.array_equal(y_f, np.full((1, 1, 4), (1.0 + 2.0 ** -7) ** 2))
+    k[0, 0] = 1.0
+    y = oracle.fftconv_gated(u, w, None, k, 8)
+    assert np.array_equal(y, np.full((1, 1, 4), 1.0 + 2.0 ** -6 + 2.0 ** -14))
+    assert np.array_equal(oracle.round_to(y, "bf16"), np.full((1, 1, 4), 1.0 + 2.0 ** -6))
+
+
+def test_gated_is_bilinear_in_u_and_w_and_linear_in_v():
+    u, u2, w, v = (RNG.standard_normal((2, 2, 24)) for _ in range(4))
+    k = RNG.standard_normal((2, 24))
+    f = lambda a, b, c: oracle.fftconv_gated(a, b, c, k, 48)
+    assert np.allclose(f(u + 2 * u2, w, v), f(u, w, v) + 2 * f(u2, w, v), rtol=0, atol=1e-11)
+    assert np.allclose(f(u, w, v), f(w, u, v), rtol=0, atol=1e-12)          # u . w is symmetric
+    assert np.allclose(f(u, w, 3 * v), 3 * f(u, w, v), rtol=0, atol=1e-11)
 
 
 # ---------------------------------------------------------------- backward pass
