@@ -45,6 +45,8 @@ def _load():
         lib.oracle_fftconv.restype = ctypes.c_int
         lib.oracle_fftconv_at.argtypes = [p, p, p, p, i64, i64, i64, i64]
         lib.oracle_fftconv_at.restype = ctypes.c_int
+        lib.oracle_fftconv_taps.argtypes = [p, p, p, p, i64, i64, i64, i64, i64]
+        lib.oracle_fftconv_taps.restype = ctypes.c_int
         lib.oracle_mask_filter.argtypes = [p, p, p, i64, i64]
         lib.oracle_mask_filter.restype = ctypes.c_int
         lib.oracle_backward_u.argtypes = [p, p, p, i64, i64, i64, i64]
@@ -111,6 +113,26 @@ def fftconv_at(u_rows, kext_rows, idx) -> np.ndarray:
     if rc != 0:
         raise ValueError("oracle_fftconv_at rejected its arguments")
     return out
+
+
+def fftconv_taps(u, pos, val, M: int) -> np.ndarray:
+    """The convolution of fftconv() for a filter with few non-zero taps: channel h has taps val[h,t] at
+    positions pos[h,t] in [0,M) (distinct within a channel), zero elsewhere.  O(T N) per sequence.
+
+    u: (B,H,N); pos: (H,T) int; val: (H,T).  Returns (B,H,N).
+    """
+    u = _f64(u)
+    pos = np.ascontiguousarray(np.asarray(pos, dtype=np.int64))
+    val = _f64(val)
+    B, H, N = u.shape
+    if pos.shape != val.shape or pos.ndim != 2 or pos.shape[0] != H:
+        raise ValueError("pos and val must both be (H, T)")
+    y = np.empty_like(u)
+    rc = _load().oracle_fftconv_taps(u.ctypes.data, pos.ctypes.data, val.ctypes.data, y.ctypes.data, B, H, N, int(M),
+                                     pos.shape[1])
+    if rc != 0:
+        raise ValueError("oracle_fftconv_taps rejected its arguments (sizes, or tap positions out of range / repeated)")
+    return y
 
 
 def mask_filter(kext, keep) -> np.ndarray:

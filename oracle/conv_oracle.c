@@ -87,6 +87,43 @@ int oracle_fftconv_at(const double *u, const double *kext, const int64_t *idx, d
     return 0;
 }
 
+/* The same definition for a filter with few non-zero taps, given as a list: channel h has T taps,
+ * tap t at position pos[h,t] in [0,M) with value val[h,t] (positions distinct within a channel), so
+ * kext[h,p] = val[h,t] where p = pos[h,t] and zero elsewhere.  In the sum over j only the terms with
+ * (i-j) mod M = pos[h,t] survive, i.e. j = (i - pos[h,t]) mod M, and only if that j is an input
+ * sample (j < N):
+ *     y[b,h,i] = sum_t val[h,t] * u[b,h,(i - pos[h,t]) mod M]   [(i - pos[h,t]) mod M < N].
+ * O(T N) per sequence, which makes every output of a very long row checkable.
+ * u: (B,H,N); pos, val: (H,T); y: (B,H,N).  Returns 0, or -1 on bad sizes or positions. */
+int oracle_fftconv_taps(const double *u, const int64_t *pos, const double *val, double *y,
+                        int64_t B, int64_t H, int64_t N, int64_t M, int64_t T)
+{
+    if (B < 0 || H < 0 || N < 1 || M < N || T < 0) return -1;
+    for (int64_t h = 0; h < H; ++h)
+        for (int64_t t = 0; t < T; ++t) {
+            if (pos[h * T + t] < 0 || pos[h * T + t] >= M) return -1;
+            for (int64_t t2 = 0; t2 < t; ++t2)
+                if (pos[h * T + t2] == pos[h * T + t]) return -1;
+        }
+    int64_t nseq = B * H;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t s = 0; s < nseq; ++s) {
+        int64_t h = s % H;
+        const double *us = u + s * N;
+        double *ys = y + s * N;
+        for (int64_t i = 0; i < N; ++i) {
+            double acc = 0.0;
+            for (int64_t t = 0; t < T; ++t) {
+                int64_t j = i - pos[h * T + t];
+                if (j < 0) j += M;
+                if (j < N) acc += val[h * T + t] * us[j];
+            }
+            ys[i] = acc;
+        }
+    }
+    return 0;
+}
+
 /* Frequency masking of one or more filters.
  * kext: (H,M) real; keep: (M) bytes, 1 = keep DFT bin f, 0 = set it to zero,
  * indexed by the natural frequency f of X[f] = sum_t x[t] exp(-2 pi i f t / M)

@@ -27,7 +27,7 @@ EXPORTS = [
     "fftconv_plan_order", "fftconv_filter_fft_sparse_digits", "fftconv_forward_freq_sparse_digits",
 ]
 
-_lib = None
+_libs = {}
 
 
 class Machine(ctypes.Structure):
@@ -49,13 +49,15 @@ def library_path() -> str:
     return _build.LIB
 
 
-def load():
-    """Load libfftconv.so, building it first only if no built library exists."""
-    global _lib
-    if _lib is not None:
-        return _lib
-    path = os.environ.get("FFTCONV_LIBRARY", _build.LIB)     # override: a development build of the same ABI
+def load(path: str | None = None):
+    """Load libfftconv.so (building it first only if no built library exists) and declare its entry points.
+    path: another build of the same ABI (the tests load the barrier-checking build this way)."""
+    path = os.path.abspath(path) if path else _build.LIB
+    if path in _libs:
+        return _libs[path]
     if not os.path.exists(path):
+        if path != _build.LIB:
+            raise FileNotFoundError(path)
         _build.build()
     lib = ctypes.CDLL(path)
     vp, i64, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
@@ -112,13 +114,13 @@ def load():
     lib.fftconv_strerror.restype = ctypes.c_char_p
     lib.fftconv_last_error.argtypes = []
     lib.fftconv_last_error.restype = ctypes.c_char_p
-    _lib = lib
+    _libs[path] = lib
     return lib
 
 
-def _check(rc: int):
+def _check(rc: int, lib=None):
     if rc != 0:
-        lib = load()
+        lib = lib or load()
         detail = lib.fftconv_last_error().decode() or lib.fftconv_strerror(rc).decode()
         raise FFTConvError(rc, detail)
 
@@ -178,14 +180,17 @@ def plan_order(machine: Machine, N: int):
 class Plan:
     """fftconv_plan_create / fftconv_plan_destroy and the calls that take a plan."""
 
-    def __init__(self, N: int, fft_size: int, H: int, dtype):
+    def __init__(self, N: int, fft_size: int, H: int, dtype, lib=None):
         if isinstance(dtype, str):
             dtype = _DTYPE_NAME[dtype]
         self.N, self.fft_size, self.H, self.dtype = int(N), int(fft_size), int(H), dtype
-        self._lib = load()
+        self._lib = lib or load()
         self._h = ctypes.c_void_p()
-        _check(self._lib.fftconv_plan_create(ctypes.byref(self._h), self.N, self.fft_size, self.H, _DTYPE_CODE[dtype]))
+        self._ok(self._lib.fftconv_plan_create(ctypes.byref(self._h), self.N, self.fft_size, self.H, _DTYPE_CODE[dtype]))
         self._ws = None
+
+    def _ok(self, rc: int):
+        _check(rc, self._lib)
 
     def close(self):
         if getattr(self, "_h", None) is not None and self._h:
@@ -234,10 +239,10 @@ class Plan:
         self._check_k(k)
         kf = torch.empty(self.kf_bytes(), dtype=torch.uint8, device=k.device)
         if block_keep is None:
-            _check(self._lib.fftconv_filter_fft(self._h, k.data_ptr(), k.shape[1], kf.data_ptr(), _stream_ptr()))
+            self._ok(self._lib.fftconv_filter_fft(self._h, k.data_ptr(), k.shape[1], kf.data_ptr(), _stream_ptr()))
         else:
             bk = bytes(bytearray(int(x) for x in block_keep))
-            _check(self._lib.fftconv_filter_fft_sparse(self._h, k.data_ptr(), k.shape[1], bk, len(bk), kf.data_ptr(),
+            self._ok(self._lib.fftconv_filter_fft_sparse(self._h, k.data_ptr(), k.shape[1], bk, len(bk), kf.data_ptr(),
                                                        _stream_ptr()))
         return kf
 
@@ -251,7 +256,7 @@ class Plan:
         self._check_u(u)
         y = torch.empty_like(u) if out is None else out
         ws = self._workspace(u.shape[0], u.device)
-        _check(self._lib.fftconv_forward(self._h, u.data_ptr(), kf.data_ptr(), y.data_ptr(), u.shape[0], self.H,
+        self._ok(self._lib.fftconv_forward(self._h, u.data_ptr(), kf.data_ptr(), y.data_ptr(), u.shape[0], self.H,
                                          self.N, None if ws is None else ws.data_ptr(), _stream_ptr()))
         return y
 
@@ -265,7 +270,7 @@ class Plan:
                     raise ValueError("gates must have the shape of u")
         y = torch.empty_like(u) if out is None else out
         ws = self._workspace(u.shape[0], u.device, gated=True)
-        _check(self._lib.fftconv_forward_gated(self._h, u.data_ptr(), None if w is None else w.data_ptr(),
+        self._ok(self._lib.fftconv_forward_gated(self._h, u.data_ptr(), None if w is None else w.data_ptr(),
                                                None if v is None else v.data_ptr(), kf.data_ptr(), y.data_ptr(),
                                                u.shape[0], self.H, self.N, None if ws is None else ws.data_ptr(),
                                                _stream_ptr()))
@@ -275,7 +280,7 @@ class Plan:
         """fftconv_filter_fft_adjoint: the k_f buffer fftconv_backward_input takes."""
         self._check_k(k)
         kf = torch.empty(self.kf_bytes(), dtype=torch.uint8, device=k.device)
-        _check(self._lib.fftconv_filter_fft_adjoint(self._h, k.data_ptr(), k.shape[1], kf.data_ptr(), _stream_ptr()))
+        self._ok(self._lib.fftconv_filter_fft_adjoint(self._h, k.data_ptr(), k.shape[1], kf.data_ptr(), _stream_ptr()))
         return kf
 
     def backward_input(self, dy, kf_adjoint, out=None):
@@ -283,7 +288,7 @@ class Plan:
         self._check_u(dy)
         du = torch.empty_like(dy) if out is None else out
         ws = self._workspace(dy.shape[0], dy.device)
-        _check(self._lib.fftconv_backward_input(self._h, dy.data_ptr(), kf_adjoint.data_ptr(), du.data_ptr(),
+        self._ok(self._lib.fftconv_backward_input(self._h, dy.data_ptr(), kf_adjoint.data_ptr(), du.data_ptr(),
                                                 dy.shape[0], self.H, self.N, None if ws is None else ws.data_ptr(),
                                                 _stream_ptr()))
         return du
@@ -298,7 +303,7 @@ class Plan:
         need = int(self._lib.fftconv_workspace_bytes_backward_filter(self._h, u.shape[0]))
         if getattr(self, "_ws_bk", None) is None or self._ws_bk.numel() < need or self._ws_bk.device != u.device:
             self._ws_bk = torch.empty(max(need, 1), dtype=torch.uint8, device=u.device)
-        _check(self._lib.fftconv_backward_filter(self._h, u.data_ptr(), dy.data_ptr(), dk.data_ptr(), int(Nk),
+        self._ok(self._lib.fftconv_backward_filter(self._h, u.data_ptr(), dy.data_ptr(), dk.data_ptr(), int(Nk),
                                                  u.shape[0], self.H, self.N, self._ws_bk.data_ptr(), _stream_ptr()))
         return dk
 
@@ -307,18 +312,18 @@ class Plan:
         self._check_u(u)
         y = torch.empty_like(u) if out is None else out
         ws = self._workspace(u.shape[0], u.device)
-        _check(self._lib.fftconv_forward_partial(self._h, u.data_ptr(), kf.data_ptr(), y.data_ptr(), u.shape[0],
+        self._ok(self._lib.fftconv_forward_partial(self._h, u.data_ptr(), kf.data_ptr(), y.data_ptr(), u.shape[0],
                                                  self.H, self.N, int(Nk), None if ws is None else ws.data_ptr(),
                                                  _stream_ptr()))
         return y
 
-    def filter_fft_sparse_digits(self, k, digit_keep, Nk=None):
+    def filter_fft_sparse_digits(self, k, digit_keep):
         """fftconv_filter_fft_sparse_digits: k (H, Nk) fp32 on the device -> opaque k_f."""
         self._check_k(k)
-        Nk = k.shape[1] if Nk is None else Nk
+        Nk = k.shape[1]
         kf = torch.empty(self.kf_bytes(), dtype=torch.uint8, device=k.device)
         arr = (ctypes.c_int64 * len(digit_keep))(*[int(x) for x in digit_keep])
-        _check(self._lib.fftconv_filter_fft_sparse_digits(self._h, k.data_ptr(), Nk, arr, len(digit_keep),
+        self._ok(self._lib.fftconv_filter_fft_sparse_digits(self._h, k.data_ptr(), Nk, arr, len(digit_keep),
                                                           kf.data_ptr(), _stream_ptr()))
         return kf
 
@@ -328,7 +333,7 @@ class Plan:
         y = torch.empty_like(u) if out is None else out
         ws = self._workspace(u.shape[0], u.device)
         arr = (ctypes.c_int64 * len(digit_keep))(*[int(x) for x in digit_keep])
-        _check(self._lib.fftconv_forward_freq_sparse_digits(self._h, u.data_ptr(), kf.data_ptr(), arr, len(digit_keep),
+        self._ok(self._lib.fftconv_forward_freq_sparse_digits(self._h, u.data_ptr(), kf.data_ptr(), arr, len(digit_keep),
                                                             y.data_ptr(), u.shape[0], self.H, self.N,
                                                             None if ws is None else ws.data_ptr(), _stream_ptr()))
         return y
@@ -339,7 +344,7 @@ class Plan:
         y = torch.empty_like(u) if out is None else out
         ws = self._workspace(u.shape[0], u.device)
         bk = bytes(bytearray(int(x) for x in block_keep))
-        _check(self._lib.fftconv_forward_freq_sparse(self._h, u.data_ptr(), kf.data_ptr(), bk, len(bk), y.data_ptr(),
+        self._ok(self._lib.fftconv_forward_freq_sparse(self._h, u.data_ptr(), kf.data_ptr(), bk, len(bk), y.data_ptr(),
                                                      u.shape[0], self.H, self.N,
                                                      None if ws is None else ws.data_ptr(), _stream_ptr()))
         return y

@@ -125,6 +125,45 @@ def gen_k(w: Workload) -> np.ndarray:
     return k
 
 
+TAP_KINDS = 5
+TAPS = 16
+
+
+def gen_taps(H: int, L: int, seed: int):
+    """Filters with few non-zero taps on [0, L), one kind per channel in turn (h mod 5): a unit tap at position
+    0, at 1, at L/2, at L-1, and 16 taps of value +1 or -1, one in each sixteenth of [0, L) at a random offset
+    with the last one moved to L-1.  Unlike decaying filters these weight the late taps as much as the early
+    ones.  Returns (pos, val), both (H, 16); entries with val 0 are placeholders at distinct unused positions."""
+    if L < 4 * TAPS:
+        raise ValueError("L too short for 16 separated taps")
+    g = np.random.Generator(np.random.Philox(key=[seed, L]))
+    pos = np.zeros((H, TAPS), dtype=np.int64)
+    val = np.zeros((H, TAPS), dtype=np.float64)
+    single = [0, 1, L // 2, L - 1]
+    for h in range(H):
+        kind = h % TAP_KINDS
+        if kind < 4:
+            pos[h, 0] = single[kind]
+            val[h, 0] = 1.0
+            free = [p for p in range(2, 2 + 2 * TAPS) if p not in single][: TAPS - 1]
+            pos[h, 1:] = free
+        else:
+            step = L // TAPS
+            pos[h] = np.arange(TAPS) * step + g.integers(0, step, TAPS)
+            pos[h, -1] = L - 1
+            val[h] = g.choice([-1.0, 1.0], TAPS)
+    return pos, val
+
+
+def taps_to_filter(pos, val, L: int) -> np.ndarray:
+    """The taps of gen_taps laid out as a dense fp32 filter (H, L), the form the library takes."""
+    H = pos.shape[0]
+    k = np.zeros((H, L), dtype=np.float32)
+    for h in range(H):
+        k[h, pos[h]] = val[h]
+    return k
+
+
 def block_keep(w: Workload) -> np.ndarray:
     """uint8 flag per frequency block (1 = kept); all ones when the workload is dense."""
     if not w.n_blocks:

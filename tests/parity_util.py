@@ -7,6 +7,32 @@ import oracle
 from paper_2311_05908_amd import fftconv, synth
 
 TOL = {"f32": 1e-5, "f16": 1e-2, "bf16": 1e-2}     # max per-sequence relative L2 error
+ELEM_FACTOR = 8.0                                  # element-wise bound: |y_i - ref_i| <= ELEM_FACTOR * tol * rms(ref)
+
+
+def parity_error(y, ref, tol, what=""):
+    """Compare along the last axis (one sequence per row).  Returns the largest per-sequence relative L2 error
+    (the caller asserts it against tol) and itself asserts the element-wise bound
+
+        max_i |y_i - ref_i| <= ELEM_FACTOR * tol * rms(ref)        per sequence.
+
+    The norm alone lets a single wrong element pass once N is large (one element of size rms(ref) moves the
+    relative L2 error of a 16384-point row by 1/128); the element-wise bound does not.  With rounding errors
+    only, the largest element error of a 16-bit path is about 0.03 rms(ref) (4.5 sigma of an error of relative
+    L2 size 5e-3, plus half a unit in the last place of the largest outputs), of an fp32 path about 1e-6."""
+    y = np.asarray(y, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    assert y.shape == ref.shape, (y.shape, ref.shape)
+    assert np.isfinite(y).all(), "non-finite output %s" % what
+    if y.size == 0:
+        return 0.0
+    rms = np.sqrt((ref ** 2).mean(axis=-1))
+    worst = np.abs(y - ref).max(axis=-1)
+    bound = ELEM_FACTOR * tol * np.where(rms > 0, rms, 1.0)
+    bad = worst > bound
+    assert not bad.any(), "element-wise bound exceeded %s: worst |y - ref| / rms(ref) = %.3e (limit %.3e) in sequence %s" % (
+        what, float((worst / np.where(rms > 0, rms, 1.0)).max()), ELEM_FACTOR * tol, np.argwhere(bad)[0].tolist())
+    return float(np.max(oracle.rel_l2_per_sequence(y, ref)))
 
 
 def oracle_filter(w, k):
@@ -44,14 +70,13 @@ def check_all_sequences(w, variant="dense"):
     if keep is not None:
         kext = oracle.mask_filter(kfull, keep)
     ref = oracle.fftconv(u.double().numpy(), kext)
-    assert torch.isfinite(y.float()).all()
-    err = oracle.rel_l2_per_sequence(y.double().numpy(), ref)
-    return float(err.max()), plan
+    return parity_error(y.double().numpy(), ref, TOL[w.dtype], "%s %s" % (w.name, variant)), plan
 
 
-def check_sampled_positions(w, n_pos=48, variant="dense", seed=11):
-    """Long sequences: every sequence of the workload, but only sampled output positions
-    (first and last sample always included), each evaluated by the oracle as its own sum."""
+def check_sampled_positions(w, n_pos=48, variant="dense", seed=11, edge=1):
+    """Long sequences: every sequence of the workload, but only sampled output positions (the first `edge`
+    and the last `edge` positions always included, the rest drawn at random), each evaluated by the oracle
+    as its own sum."""
     u = synth.gen_u(w)
     k = synth.gen_k(w)
     y, plan = gpu_forward(w, u, k, variant)
@@ -60,11 +85,12 @@ def check_sampled_positions(w, n_pos=48, variant="dense", seed=11):
     g = np.random.Generator(np.random.Philox(key=[seed, w.N]))
     S = w.B * w.H
     idx = g.integers(0, w.N, size=(S, n_pos))
-    idx[:, 0] = 0
-    idx[:, 1] = w.N - 1
+    assert 2 * edge <= n_pos
+    idx[:, :edge] = np.arange(edge)[None]
+    idx[:, edge:2 * edge] = (w.N - 1 - np.arange(edge))[None]
     u_rows = u.double().numpy().reshape(S, w.N)
     k_rows = np.tile(kext, (w.B, 1))
     ref = oracle.fftconv_at(u_rows, k_rows, idx)
     got = np.take_along_axis(y.double().numpy().reshape(S, w.N), idx, axis=1)
-    err = oracle.rel_l2_per_sequence(got, ref)          # relative L2 over the sampled positions
-    return float(err.max()), plan
+    # relative L2 over the sampled positions, and every sampled element on its own
+    return parity_error(got, ref, TOL[w.dtype], "%s sampled positions" % w.name), plan

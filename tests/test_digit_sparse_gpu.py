@@ -6,7 +6,7 @@ import torch
 
 import oracle
 from paper_2311_05908_amd import fftconv, synth
-from parity_util import TOL
+from parity_util import TOL, parity_error
 
 pytestmark = pytest.mark.gpu
 W = synth.WORKLOADS
@@ -27,8 +27,8 @@ def run(dtype, B, H, N, M, digit_keep):
     keep = synth.digit_keep_mask(plan.factors, digit_keep)
     kmasked = oracle.mask_filter(oracle.extend_filter(k, M), keep)
     ref = oracle.fftconv(u.double().numpy(), kmasked)
-    e_dense = float(oracle.rel_l2_per_sequence(y_dense.double().numpy(), ref).max())
-    e_skip = float(oracle.rel_l2_per_sequence(y_skip.double().numpy(), ref).max())
+    e_dense = parity_error(y_dense.double().numpy(), ref, TOL[dtype], "dense")
+    e_skip = parity_error(y_skip.double().numpy(), ref, TOL[dtype], "skip")
     print("digits %s B=%d H=%d N=%d M=%d path=%s factors=%s keep=%s kept bins %.1f%% err dense %.3e skip %.3e"
           % (dtype, B, H, N, M, plan.path, plan.factors, list(digit_keep), 100.0 * keep.mean(), e_dense, e_skip), flush=True)
     return plan, e_dense, e_skip

@@ -229,6 +229,72 @@ def test_masked_filter_spectrum_is_the_hermitian_part_of_the_masked_spectrum():
     assert (keep != mirror).sum() == 2    # the asymmetry the weight 1/2 is there for
 
 
+# ---------------------------------------------------------------- filters given as a list of taps
+
+def test_taps_single_delta_is_a_shift_with_zero_fill_or_wrap():
+    # k = delta_s: causal (M >= N + s) gives u shifted right by s with zeros in front (Section 2.1);
+    # with M = N the samples pushed out at the end come back in at the front (Eq. 1, circular form)
+    B, H, N = 2, 3, 50
+    u = RNG.standard_normal((B, H, N))
+    for s in (0, 1, 7, 49):
+        pos = np.full((H, 1), s)
+        val = np.ones((H, 1))
+        y = oracle.fftconv_taps(u, pos, val, 2 * N)
+        want = np.zeros_like(u)
+        want[..., s:] = u[..., : N - s]
+        assert np.array_equal(y, want)
+        assert np.array_equal(oracle.fftconv_taps(u, pos, val, N), np.roll(u, s, axis=-1))
+    # a tap in the padded region (N <= s < M = 2N): output i takes input i - s + M, an input sample only while i < s - N
+    s = 70
+    y = oracle.fftconv_taps(u, np.full((H, 1), s), np.ones((H, 1)), 2 * N)
+    want = np.zeros_like(u)
+    want[..., : N - (2 * N - s)] = u[..., 2 * N - s:]
+    assert np.array_equal(y, want)
+
+
+def test_taps_equal_the_dense_definition_and_the_library_convolution():
+    B, H, N, M, T = 2, 3, 40, 64, 5
+    u = RNG.standard_normal((B, H, N))
+    pos = np.stack([RNG.permutation(M)[:T] for _ in range(H)])          # anywhere in [0, M): wrapped taps too
+    val = RNG.standard_normal((H, T))
+    kext = np.zeros((H, M))
+    for h in range(H):
+        kext[h, pos[h]] = val[h]
+    assert np.allclose(oracle.fftconv_taps(u, pos, val, M), oracle.fftconv(u, kext), rtol=0, atol=1e-13)
+    # Eq. 1 written with dense DFT matrices
+    n = np.arange(M)
+    F = np.exp(-2j * np.pi * np.outer(n, n) / M)
+    upad = np.zeros((B, H, M))
+    upad[..., :N] = u
+    want = np.real(np.einsum("fn,bhf->bhn", np.conj(F) / M, np.einsum("fn,bhn->bhf", F, upad) * (kext @ F.T)[None]))[..., :N]
+    assert np.allclose(oracle.fftconv_taps(u, pos, val, M), want, rtol=0, atol=1e-11)
+    # causal taps (all below M - N + 1): the library's polynomial product, channel by channel
+    posc = np.stack([RNG.permutation(M - N + 1)[:T] for _ in range(H)])
+    yc = oracle.fftconv_taps(u, posc, val, M)
+    for b in range(B):
+        for h in range(H):
+            kk = np.zeros(M)
+            kk[posc[h]] = val[h]
+            assert np.allclose(yc[b, h], np.convolve(u[b, h], kk)[:N], rtol=0, atol=1e-13)
+
+
+def test_taps_integer_inputs_are_exact_and_bad_arguments_are_rejected():
+    u = RNG.integers(-5, 6, (1, 2, 33)).astype(np.float64)
+    pos = np.array([[0, 3, 65], [1, 2, 40]])
+    val = np.array([[2.0, -1.0, 3.0], [1.0, 1.0, -4.0]])
+    y = oracle.fftconv_taps(u, pos, val, 66)
+    kext = np.zeros((2, 66))
+    for h in range(2):
+        kext[h, pos[h]] = val[h]
+    assert np.array_equal(y, oracle.fftconv(u, kext))
+    with pytest.raises(ValueError):
+        oracle.fftconv_taps(u, np.array([[0, 0, 1], [1, 2, 3]]), val, 66)      # a repeated position
+    with pytest.raises(ValueError):
+        oracle.fftconv_taps(u, np.array([[0, 66, 1], [1, 2, 3]]), val, 66)     # position out of range
+    with pytest.raises(ValueError):
+        oracle.fftconv_taps(u, pos, val, 32)                                   # M < N
+
+
 # ---------------------------------------------------------------- gated convolution (Section 3.1 / 4.1)
 
 def test_round_to_matches_library_casts_including_ties():
