@@ -77,6 +77,12 @@ struct Fused3Tables {
     void *consts_short = nullptr;
 };
 
+// fp16 plans of the multi-pass path (fft_size = No * 8192): 1 / fft_size itself is already a subnormal
+// fp16 number from No = 8, so a filter of small norm (a unit tap: |K| = 1) would lose most of its bits in
+// k_f.  Their k_f is therefore scaled by boost / fft_size with boost = min(No, 64), a power of two, and the
+// outer inverse pass multiplies by 1 / boost in fp32.  bf16 has the exponent range of fp32: boost = 1.
+__host__ __device__ constexpr int multipass_kf_boost(bool f16, int No) { return !f16 ? 1 : No < 64 ? No : 64; }
+
 // Weight of frequency bin f under a block mask (Section 3.3, frequency-sparse filters).  The
 // output is defined as Re(IDFT(mask . K . U)) for real u; that equals IDFT(K' . U) with the
 // Hermitian part K'[f] = K[f] (mask[f] + mask[M-f]) / 2, and only a Hermitian K' (a real filter)

@@ -175,7 +175,7 @@ __global__ void __launch_bounds__(LT) k_long_fwd_blocks(const float2 *__restrict
 // Forward, blocks, for the filter transform of the multi-pass plans: the block at position a' of a row holds the
 // bins f = ko + A f' of one outer frequency digit ko (the digit reversal of a'), f' < 8192 in position order; they
 // go straight to that digit's row of k_f, [h][ko][slot of f' in the 8192-point kernel's per-lane order] as 16-bit
-// (re, im) pairs, scaled by 1/M and by the frequency mask.
+// (re, im) pairs, scaled by 1/M (times the fp16 range boost, multipass_kf_boost) and by the frequency mask.
 template <bool F16>
 __global__ void __launch_bounds__(LT) k_long_fwd_blocks_kf(const float2 *__restrict__ tmp, uint32_t *__restrict__ kf, LongTw w,
                                                           FacList flA, FacList flB, int A, int64_t h0,
@@ -194,7 +194,7 @@ __global__ void __launch_bounds__(LT) k_long_fwd_blocks_kf(const float2 *__restr
         const int k2 = lane % 16, k3 = k3_at_index(4 * (lane / 16) + r, 16);
         const int fi = k1 + 32 * (k2 + 16 * k3);
         const float2 v = XL[lds_slot(lds_pos(fi, flB, LB))];
-        const float sc = lds_mask_weight(keep, n_blocks, ko + A * fi, M) / (float)M;
+        const float sc = lds_mask_weight(keep, n_blocks, ko + A * fi, M) * (float)multipass_kf_boost(F16, A) / (float)M;
         uint16_t re, im;
         if constexpr (F16) {
             const __half a = __float2half_rn(v.x * sc), b = __float2half_rn(v.y * sc);

@@ -16,7 +16,7 @@
 //            are implicit; the listing in the paper omits the twiddle, its prose names it)
 //   pass B:  every row S[ko, :] is circularly convolved (length Mi, complex in / complex out,
 //            fused kernel) with the spectrum row k_f[ko + No*f'] / M
-//   pass C:  y[no*Mi + r] = sum_{ko} conj(W_M^{r ko} W_No^{no ko}) S[ko, r],  no < No/2;
+//   pass C:  y[no*Mi + r] = sum_{ko} conj(W_M^{r ko} W_No^{no ko}) S[ko, r] / boost,  no < No/2;
 //            real part -> row b, imaginary part -> row b+1.
 // S lives in the caller's workspace as 16-bit (re, im) pairs, M per pair of rows, and is
 // rewritten in place by pass B.  The outer DFT of length No is itself split in two
@@ -260,6 +260,9 @@ __global__ void __launch_bounds__(TB, 4) k_outer_inv(const uint32_t *__restrict_
             const int r = r0 + c + v;
             float2 w = wm((int)(((int64_t)r * ka) % M), ihm);
             const float2 step = wm((int)(((int64_t)r * RA) % M), ihm);
+            constexpr float unboost = 1.0f / (float)multipass_kf_boost(F16, No);     // exact: a power of two
+            w.x *= unboost;
+            w.y *= unboost;
             float2 x[RB];
 #pragma unroll
             for (int kb = 0; kb < RB; ++kb) {
@@ -332,7 +335,8 @@ __global__ void __launch_bounds__(TB, 4) k_outer_inv(const uint32_t *__restrict_
     }
 }
 
-// k_f for the multi-pass path: [h][ko][inner order of f'] 16-bit (re, im) pairs, f = ko + No*f', scaled 1/M.
+// k_f for the multi-pass path: [h][ko][inner order of f'] 16-bit (re, im) pairs, f = ko + No*f', scaled 1/M
+// (fp16: boost/M, see multipass_kf_boost; pass C takes the boost out again).
 template <bool F16>
 __global__ void k_pack_multipass(const double2 *spec, uint32_t *kf, FacList fl, int64_t M, int No, int64_t h0,
                                  int64_t nh, const uint8_t *keep, int64_t n_blocks)
@@ -343,7 +347,7 @@ __global__ void k_pack_multipass(const double2 *spec, uint32_t *kf, FacList fl, 
     const int ko = (int)(f % No);
     const int64_t fi = f / No;
     const double2 v = spec[h * M + freq_to_pos(f, fl, M)];
-    const double sc = mask_weight(keep, n_blocks, f, M) / (double)M;
+    const double sc = mask_weight(keep, n_blocks, f, M) * (double)multipass_kf_boost(F16, No) / (double)M;
     kf[((h0 + h) * No + ko) * (int64_t)MI + fused3_kf_slot_8192(fi)] =
         (uint32_t)cv16<F16>((float)(v.x * sc)) | ((uint32_t)cv16<F16>((float)(v.y * sc)) << 16);
 }

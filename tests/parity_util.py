@@ -10,7 +10,7 @@ TOL = {"f32": 1e-5, "f16": 1e-2, "bf16": 1e-2}     # max per-sequence relative L
 ELEM_FACTOR = 8.0                                  # element-wise bound: |y_i - ref_i| <= ELEM_FACTOR * tol * rms(ref)
 
 
-def parity_error(y, ref, tol, what=""):
+def parity_error(y, ref, tol, what="", weight=None, floor_rms=None):
     """Compare along the last axis (one sequence per row).  Returns the largest per-sequence relative L2 error
     (the caller asserts it against tol) and itself asserts the element-wise bound
 
@@ -19,7 +19,13 @@ def parity_error(y, ref, tol, what=""):
     The norm alone lets a single wrong element pass once N is large (one element of size rms(ref) moves the
     relative L2 error of a 16384-point row by 1/128); the element-wise bound does not.  With rounding errors
     only, the largest element error of a 16-bit path is about 0.03 rms(ref) (4.5 sigma of an error of relative
-    L2 size 5e-3, plus half a unit in the last place of the largest outputs), of an fp32 path about 1e-6."""
+    L2 size 5e-3, plus half a unit in the last place of the largest outputs), of an fp32 path about 1e-6.
+    weight (same shape as y, optional) multiplies the bound element by element where it exceeds 1: the output
+    gate of the gated form scales the convolution's error at position i by |v_i|, and |v_i| reaches 4.
+    floor_rms (one value per sequence, optional): rms of the UNTRUNCATED circular result, all fft_size outputs
+    of the inverse transform.  Rounding errors are spread evenly over those outputs, so when the N kept ones
+    hold almost none of the energy (a late unit tap: y = 0 except for its last sample) the error relative to
+    the kept outputs alone says nothing about the arithmetic; both measures then use max(rms(ref), floor_rms)."""
     y = np.asarray(y, dtype=np.float64)
     ref = np.asarray(ref, dtype=np.float64)
     assert y.shape == ref.shape, (y.shape, ref.shape)
@@ -27,11 +33,17 @@ def parity_error(y, ref, tol, what=""):
     if y.size == 0:
         return 0.0
     rms = np.sqrt((ref ** 2).mean(axis=-1))
+    if floor_rms is not None:
+        rms = np.maximum(rms, np.asarray(floor_rms, dtype=np.float64))
     worst = np.abs(y - ref).max(axis=-1)
     bound = ELEM_FACTOR * tol * np.where(rms > 0, rms, 1.0)
+    if weight is not None:
+        worst = (np.abs(y - ref) / np.maximum(1.0, np.abs(np.asarray(weight, dtype=np.float64)))).max(axis=-1)
     bad = worst > bound
     assert not bad.any(), "element-wise bound exceeded %s: worst |y - ref| / rms(ref) = %.3e (limit %.3e) in sequence %s" % (
         what, float((worst / np.where(rms > 0, rms, 1.0)).max()), ELEM_FACTOR * tol, np.argwhere(bad)[0].tolist())
+    if floor_rms is not None:
+        return float(np.max(np.sqrt(((y - ref) ** 2).mean(axis=-1)) / np.where(rms > 0, rms, 1.0)))
     return float(np.max(oracle.rel_l2_per_sequence(y, ref)))
 
 

@@ -31,7 +31,7 @@ def check_all(w, use_w=True, use_v=True):
     u, gw, gv, k, y, plan = run_gated(w, use_w, use_v)
     ref = oracle.fftconv_gated(u.double().numpy(), None if gw is None else gw.double().numpy(),
                                None if gv is None else gv.double().numpy(), k, w.fft_size)
-    return parity_error(y.double().numpy(), ref, TOL[w.dtype], "gated"), plan
+    return parity_error(y.double().numpy(), ref, TOL[w.dtype], "gated", None if gv is None else gv.double().numpy()), plan
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f16"])
@@ -113,7 +113,8 @@ def test_gated_cfg2_full_size_sampled_sequences():
     for b, h in synth.sample_sequences(w, 28):
         ref = oracle.fftconv_gated(u[b, h].double().numpy()[None, None], gw[b, h].double().numpy()[None, None],
                                    gv[b, h].double().numpy()[None, None], kext[h][None])[0, 0]
-        worst = max(worst, parity_error(y[b, h].double().numpy(), ref, TOL[w.dtype], "gated cfg2 b=%d h=%d" % (b, h)))
+        worst = max(worst, parity_error(y[b, h].double().numpy(), ref, TOL[w.dtype], "gated cfg2 b=%d h=%d" % (b, h),
+                                             gv[b, h].double().numpy()))
     print("gated cfg2 full: worst sampled rel L2 = %.3e" % worst, flush=True)
     assert worst <= TOL[w.dtype]
 
