@@ -94,6 +94,21 @@ int fftconv_filter_fft(const fftconv_plan *plan, const float *k, int64_t Nk, voi
 int fftconv_forward(const fftconv_plan *plan, const void *u, const void *k_f, void *y,
                     int64_t B, int64_t H, int64_t N, void *workspace, void *stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): fftconv_forward with the workspace taken from a fixed array inside
+ * the library instead of from the caller.  The array holds FFTCONV_STATIC_WORKSPACE_BYTES bytes on every
+ * GPU the library runs on, for as long as the process lives.  Same arguments, result and kernels as
+ * fftconv_forward; the call allocates and frees nothing (no hipMalloc, hipFree or allocating library
+ * routine), it only launches the plan's kernels on `stream`.
+ *   Fails with FFTCONV_EINVAL, before anything is launched, when fftconv_workspace_bytes(plan, B)
+ *   exceeds FFTCONV_STATIC_WORKSPACE_BYTES (plans that need no workspace always fit).
+ *   All calls on one GPU share that GPU's array, which keeps the previous call's contents; every kernel
+ *   writes what it later reads, so nothing has to be cleared between calls.  Calls that overlap on one
+ *   GPU (different streams or threads) race on the array: serialise them. */
+#define FFTCONV_STATIC_WORKSPACE_BYTES ((size_t)64 << 20)
+int fftconv_forward_static(const fftconv_plan *plan, const void *u, const void *k_f, void *y,
+                           int64_t B, int64_t H, int64_t N, void *stream);
+
 /* Partial convolution (Section 3.3): the filter is zero for taps t >= Nk.
  * k_f must come from fftconv_filter_fft(plan, k, Nk, ...) with the same Nk.
  * Same result as fftconv_forward on that k_f; the plan may skip the parts of

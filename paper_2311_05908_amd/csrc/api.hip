@@ -105,6 +105,7 @@ int fftconv_plan_create(fftconv_plan **out, int64_t N, int64_t fft_size, int64_t
     else if (small_supported(N, fft_size, dtype)) p->path = PATH_SMALL;
     else if (multipass_supported(N, fft_size, dtype)) p->path = PATH_MULTIPASS;
     else p->path = PATH_STAGED;
+    if (rc == FFTCONV_OK) rc = static_workspace_init(p->device);       // address of this device's static workspace
     if (rc == FFTCONV_OK) rc = staged_init(p);      // twiddle tables, scratch of the filter transform
     if (rc == FFTCONV_OK && long_fft_supported(p)) rc = long_fft_init(p);
     if (rc == FFTCONV_OK && hipMalloc((void **)&p->keep_dev, (size_t)(fft_size > MAX_BLOCKS ? fft_size : MAX_BLOCKS)) != hipSuccess) {
@@ -333,6 +334,26 @@ int fftconv_forward(const fftconv_plan *p, const void *u, const void *k_f, void 
     default:
         return staged_forward(p, u, k_f, y, B, workspace, s);
     }
+}
+
+int fftconv_forward_static(const fftconv_plan *p, const void *u, const void *k_f, void *y, int64_t B, int64_t H,
+                           int64_t N, void *stream)
+{
+    int rc = forward_check(p, u, k_f, y, B, H, N, (void *)1, "fftconv_forward_static");
+    if (rc || B == 0) return rc;
+    const size_t need = fftconv_workspace_bytes(p, B);
+    if (need > FFTCONV_STATIC_WORKSPACE_BYTES) {
+        set_error("fftconv_forward_static: this plan needs %zu bytes of workspace for B=%lld, the static workspace "
+                  "holds %zu; use fftconv_forward with a workspace of the caller's",
+                  need, (long long)B, (size_t)FFTCONV_STATIC_WORKSPACE_BYTES);
+        return FFTCONV_EINVAL;
+    }
+    void *ws = static_workspace(p->device);
+    if (need > 0 && !ws) {
+        set_error("fftconv_forward_static: the static workspace of device %d was never initialised", p->device);
+        return FFTCONV_EHIP;
+    }
+    return fftconv_forward(p, u, k_f, y, B, H, N, need ? ws : nullptr, stream);
 }
 
 int fftconv_filter_fft_adjoint(const fftconv_plan *p, const float *k, int64_t Nk, void *k_f, void *stream)

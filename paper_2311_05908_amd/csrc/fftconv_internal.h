@@ -232,6 +232,10 @@ int small_pack_kf(const fftconv_plan *p, const double2 *spec, int64_t h0, int64_
                   int64_t n_blocks, void *kf, hipStream_t s);
 int small_forward(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, hipStream_t s);
 
+// ---- the per-GPU static workspace of fftconv_forward_static (multipass.hip)
+int static_workspace_init(int device);     // once per device, with that device current (plan creation)
+void *static_workspace(int device);        // its device address, nullptr before static_workspace_init
+
 // ---- multi-pass path (multipass.hip)
 bool multipass_supported(int64_t N, int64_t M, int dtype);
 int multipass_init(fftconv_plan *p);

@@ -28,7 +28,43 @@
 #include "dft_reg.h"
 #include "fftconv_internal.h"
 
+#include <mutex>
+
 namespace fftconv {
+
+// ---- workspace for callers that cannot allocate (fftconv_forward_static): one array per GPU, part of the
+// library's device image, held until the process ends.  Host code never uses the array's name as an
+// address: static_workspace_init() asks the runtime for the array's device address once per device and
+// every later use goes through that pointer.
+static __device__ __align__(256) unsigned char scratch[FFTCONV_STATIC_WORKSPACE_BYTES];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+void *g_scratch_ptr[MAX_DEVICES] = {};          // device address of `scratch` on each device, nullptr = not asked yet
+std::mutex g_scratch_mu;
+}  // namespace
+
+// with `device` current; called from plan creation
+int static_workspace_init(int device)
+{
+    if (device < 0 || device >= MAX_DEVICES) {
+        set_error("static workspace: device index %d out of range", device);
+        return FFTCONV_EUNSUPPORTED;
+    }
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (g_scratch_ptr[device]) return FFTCONV_OK;
+    void *ptr = nullptr;
+    FC_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    g_scratch_ptr[device] = ptr;
+    return FFTCONV_OK;
+}
+
+void *static_workspace(int device)
+{
+    if (device < 0 || device >= MAX_DEVICES) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    return g_scratch_ptr[device];
+}
 
 namespace {
 

@@ -25,7 +25,10 @@ EXPORTS = [
     "fftconv_filter_fft_adjoint", "fftconv_backward_input", "fftconv_workspace_bytes_backward_filter",
     "fftconv_backward_filter", "fftconv_machine_preset", "fftconv_cost_model", "fftconv_balanced_factors",
     "fftconv_plan_order", "fftconv_filter_fft_sparse_digits", "fftconv_forward_freq_sparse_digits",
+    "fftconv_forward_static",
 ]
+
+STATIC_WORKSPACE_BYTES = 64 << 20      # FFTCONV_STATIC_WORKSPACE_BYTES
 
 _libs = {}
 
@@ -73,6 +76,8 @@ def load(path: str | None = None):
     lib.fftconv_filter_fft.restype = ci
     lib.fftconv_forward.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, vp]
     lib.fftconv_forward.restype = ci
+    lib.fftconv_forward_static.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp]
+    lib.fftconv_forward_static.restype = ci
     lib.fftconv_forward_partial.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, vp, vp]
     lib.fftconv_forward_partial.restype = ci
     lib.fftconv_filter_fft_sparse.argtypes = [vp, vp, i64, vp, i64, vp, vp]
@@ -259,6 +264,13 @@ class Plan:
         self._ok(self._lib.fftconv_forward(self._h, u.data_ptr(), kf.data_ptr(), y.data_ptr(), u.shape[0], self.H,
                                          self.N, None if ws is None else ws.data_ptr(), _stream_ptr()))
         return y
+
+    def forward_static(self, u: torch.Tensor, kf: torch.Tensor, out: torch.Tensor) -> torch.Tensor:
+        """fftconv_forward_static: the caller passes the output; nothing is allocated on the way."""
+        self._check_u(u)
+        self._ok(self._lib.fftconv_forward_static(self._h, u.data_ptr(), kf.data_ptr(), out.data_ptr(), u.shape[0],
+                                                  self.H, self.N, _stream_ptr()))
+        return out
 
     def forward_gated(self, u, w, v, kf, out=None):
         """fftconv_forward_gated: y = v . ((u . w) * k); w and/or v may be None."""
