@@ -187,6 +187,9 @@ def main():
     ap.add_argument("--digit-keep", default=None,
                     help="comma-separated kept values per digit of the plan's factorisation (Appendix A.4 cut-off "
                          "pattern): time fftconv_forward_freq_sparse_digits against the dense call on the same k_f")
+    ap.add_argument("--constants", action="store_true",
+                    help="measure the machine constants of the cost model (Section 3.2, Appendix C) with the library's "
+                         "micro-benchmark kernels and print them beside the built-in preset (not the headline metric)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch a plain elementwise copy of %d MiB (read once, written once) before the "
                          "warm-up, as the known-size reference for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE" % (COPY_BYTES >> 20))
@@ -206,6 +209,16 @@ def main():
     torch.cuda.set_device(dev)
     if args.sweep:
         sweep(torch, fftconv, synth, dev, args)
+        return
+    if args.constants:
+        names = ("sigma_H", "sigma_S", "tau_M", "tau_G")
+        runs = [fftconv.measure_machine() for _ in range(3)]
+        med = {n: sorted(getattr(r, n) for r in runs)[1] for n in names}
+        pre = fftconv.machine_preset(fftconv.MACHINE_MI355X)
+        print(json.dumps({"metric": "machine constants of the cost model (Eq. 2), median of 3 measurements",
+                          "units": {"sigma_H": "B/s", "sigma_S": "B/s", "tau_M": "FLOP/s", "tau_G": "FLOP/s"},
+                          "measured": med, "preset": {n: getattr(pre, n) for n in names},
+                          "runs": [{n: getattr(r, n) for n in names} for r in runs], "data": "synthetic", "n_gpus": 1}))
         return
     w = synth.WORKLOADS[args.workload]
 

@@ -68,6 +68,17 @@ enum {
  * Arguments are validated before any device is touched. */
 int fftconv_plan_create(fftconv_plan **out, int64_t N, int64_t fft_size, int64_t H, int dtype);
 
+/* As fftconv_plan_create, with the kernel family chosen by the caller instead of by the cost model:
+ * path is one of the names fftconv_plan_path returns ("fused3", "small", "multipass", "staged"), or NULL /
+ * "" for the model's choice.  Fails with FFTCONV_EUNSUPPORTED when that family has no kernel for the
+ * shape.  Where several families can run a shape (16-bit causal shapes: "fused3" everywhere it exists,
+ * "small" up to fft_size 4096, "multipass" from 8192), fftconv_plan_create evaluates Eq. 2 of Section 3.2
+ * (fftconv_cost_model with the FFTCONV_MACHINE_MI355X constants) on each family's own factorisation --
+ * matrix-unit rate for the families that multiply on the matrix cores, general arithmetic rate for the
+ * vector-ALU family, one trip through HBM for every step that is a kernel of its own -- and takes the
+ * cheapest. */
+int fftconv_plan_create_path(fftconv_plan **out, int64_t N, int64_t fft_size, int64_t H, int dtype, const char *path);
+
 /* Free the plan and everything it owns.  NULL is accepted. */
 int fftconv_plan_destroy(fftconv_plan *plan);
 
@@ -213,8 +224,15 @@ double fftconv_sparsity_fraction(const int64_t *dims, const int64_t *cuts, int n
  * on chip, sigma_H otherwise: the innermost three steps form one fused kernel whose first step reads
  * from HBM and whose later steps stay on chip iff the subsequence it works on (N over the outer
  * factors) is at most sram_seq; every step outside it goes through HBM.
- * fftconv_machine_preset: FFTCONV_MACHINE_MI355X = constants measured on this chip with this library's
- * kernels, FFTCONV_MACHINE_A100_PAPER = the paper's table for A100-40GB (Appendix C).
+ * fftconv_machine_preset: FFTCONV_MACHINE_MI355X = what fftconv_measure_machine returned on an MI355X
+ * (python bench.py --constants prints a fresh measurement beside the preset), FFTCONV_MACHINE_A100_PAPER =
+ * the paper's table for A100-40GB (Appendix C).
+ * fftconv_measure_machine: measures the four rates on the current device with micro-benchmark kernels
+ * inside the library, following Appendix C ("Empirical GPU Profiling"): sigma_H from a plain copy of 1 GiB
+ * (bytes read + written per second), tau_M from 16-bit matrix-core products issued back to back on every
+ * SIMD, tau_G from fp32 twiddle products applied over and over (6 operations per complex product),
+ * sigma_S from the slow-down of a chain of matrix products when each intermediate result takes a trip
+ * through LDS.  Synchronous; allocates and frees about 2 GiB of device memory; takes about a second.
  * fftconv_cost_model: C for factors[0..p) (outermost first, product N); negative on bad arguments.
  * fftconv_balanced_factors: power-of-two factors of N as equal as possible, larger first.
  * fftconv_plan_order: the order p in {2, 3, 4} with balanced factors that minimises C for B = H = 1;
@@ -230,6 +248,7 @@ typedef struct fftconv_machine {
 #define FFTCONV_MACHINE_MI355X 0
 #define FFTCONV_MACHINE_A100_PAPER 1
 void fftconv_machine_preset(int which, fftconv_machine *m);
+int fftconv_measure_machine(fftconv_machine *m);
 double fftconv_cost_model(const fftconv_machine *m, int64_t B, int64_t H, int64_t N, int p, const int64_t *factors);
 int fftconv_balanced_factors(int64_t N, int p, int64_t *factors);
 int fftconv_plan_order(const fftconv_machine *m, int64_t N, int *p, int64_t *factors, double *cost);

@@ -56,9 +56,89 @@ static int check_plan(const fftconv_plan *p, const char *who)
     return FFTCONV_OK;
 }
 
+// ---- which kernel family runs a shape (Section 3.2: the order of the decomposition is chosen with the cost
+// model).  Every family that has a kernel for the shape is priced with Eq. 2 on its own factorisation and the
+// cheapest one wins.  Families differ in what Eq. 2's terms mean for them: "small" computes on the vector
+// ALUs (gamma = tau_G whatever the factor), the others on the matrix cores; "multipass" has its outer step
+// in kernels of their own (one more trip through HBM, priced as an order-4 decomposition).
+static const char *path_name(Path path)
+{
+    switch (path) {
+    case PATH_FUSED3: return "fused3";
+    case PATH_MULTIPASS: return "multipass";
+    case PATH_SMALL: return "small";
+    default: return "staged";
+    }
+}
+
+static double path_cost(Path path, int64_t M)
+{
+    fftconv_machine m;
+    fftconv_machine_preset(FFTCONV_MACHINE_MI355X, &m);
+    int64_t f[4];
+    switch (path) {
+    case PATH_FUSED3:
+        // the 8192-point kernel runs shorter transforms with its outermost matrix block diagonal
+        f[0] = 32, f[1] = M >= 32768 ? 32 : 16, f[2] = M >= 16384 ? 32 : 16;
+        return fftconv_cost_model(&m, 1, 1, f[0] * f[1] * f[2], 3, f) * (double)M / (double)(f[0] * f[1] * f[2]);
+    case PATH_SMALL: {
+        m.mu = 1 << 30;                                  // no factor reaches the matrix unit: vector ALUs
+        const FacList fl = small_factor_list(M);
+        int64_t g[MAX_FACTORS];
+        for (int i = 0; i < fl.nf; ++i) g[i] = fl.fac[i];
+        return fftconv_cost_model(&m, 1, 1, M, fl.nf, g);
+    }
+    case PATH_MULTIPASS:
+        f[0] = M / 8192, f[1] = 32, f[2] = 16, f[3] = 16;
+        return fftconv_cost_model(&m, 1, 1, M, 4, f);
+    default: {
+        m.mu = 1 << 30;                                  // fp32 on the vector ALUs, one kernel per group of factors
+        const FacList fl = staged_factors_for(M);
+        int64_t g[MAX_FACTORS];
+        for (int i = 0; i < fl.nf; ++i) g[i] = fl.fac[i];
+        m.sram_seq = 0;                                  // every step priced at HBM bandwidth
+        return fftconv_cost_model(&m, 1, 1, M, fl.nf, g);
+    }
+    }
+}
+
+static bool path_supported(Path path, int64_t N, int64_t M, int dtype)
+{
+    switch (path) {
+    case PATH_FUSED3: return fused3_supported(N, M, dtype);
+    case PATH_SMALL: return small_supported(N, M, dtype);
+    case PATH_MULTIPASS: return multipass_supported(N, M, dtype);
+    default: return dtype == FFTCONV_F32 && M >= 8192 && N <= M;      // the generic path: fp32 I/O from 8192 up
+    }
+}
+
+// forced: a family's name, or nullptr / "" for the cheapest supported one; false if nothing fits
+static bool choose_path(int64_t N, int64_t M, int dtype, const char *forced, Path *out)
+{
+    const Path all[4] = {PATH_FUSED3, PATH_SMALL, PATH_MULTIPASS, PATH_STAGED};
+    bool found = false;
+    double best = 0.0;
+    for (Path c : all) {
+        if (forced && forced[0] && strcmp(forced, path_name(c)) != 0) continue;
+        if (!path_supported(c, N, M, dtype)) continue;
+        const double cost = path_cost(c, M);
+        if (!found || cost < best) {
+            found = true;
+            best = cost;
+            *out = c;
+        }
+    }
+    return found;
+}
+
 extern "C" {
 
 int fftconv_plan_create(fftconv_plan **out, int64_t N, int64_t fft_size, int64_t H, int dtype)
+{
+    return fftconv_plan_create_path(out, N, fft_size, H, dtype, nullptr);
+}
+
+int fftconv_plan_create_path(fftconv_plan **out, int64_t N, int64_t fft_size, int64_t H, int dtype, const char *path)
 {
     if (!out) {
         set_error("fftconv_plan_create: out is NULL");
@@ -82,6 +162,12 @@ int fftconv_plan_create(fftconv_plan **out, int64_t N, int64_t fft_size, int64_t
         set_error("fftconv_plan_create: unknown dtype %d", dtype);
         return FFTCONV_EINVAL;
     }
+    Path chosen = PATH_STAGED;
+    if (!choose_path(N, fft_size, dtype, path, &chosen)) {
+        set_error("fftconv_plan_create: no kernel of family \"%s\" for N=%lld, fft_size=%lld, dtype %d", path ? path : "",
+                  (long long)N, (long long)fft_size, dtype);
+        return FFTCONV_EUNSUPPORTED;
+    }
     int ndev = 0;
     hipError_t e = hipGetDeviceCount(&ndev);
     if (e != hipSuccess || ndev < 1) {
@@ -101,10 +187,7 @@ int fftconv_plan_create(fftconv_plan **out, int64_t N, int64_t fft_size, int64_t
     int rc = FFTCONV_OK;
     if (hipGetDevice(&p->device) != hipSuccess) rc = FFTCONV_EHIP;
     // the path first: the generic tables depend on it (position order of the fp32 plans' k_f)
-    if (fused3_supported(N, fft_size, dtype)) p->path = PATH_FUSED3;          // 16-bit causal shapes, fft 256 .. 32768
-    else if (small_supported(N, fft_size, dtype)) p->path = PATH_SMALL;
-    else if (multipass_supported(N, fft_size, dtype)) p->path = PATH_MULTIPASS;
-    else p->path = PATH_STAGED;
+    p->path = chosen;
     if (rc == FFTCONV_OK) rc = static_workspace_init(p->device);       // address of this device's static workspace
     if (rc == FFTCONV_OK) rc = staged_init(p);      // twiddle tables, scratch of the filter transform
     if (rc == FFTCONV_OK && long_fft_supported(p)) rc = long_fft_init(p);
@@ -539,16 +622,7 @@ double fftconv_sparsity_fraction(const int64_t *dims, const int64_t *cuts, int n
     return 1.0 - kept;
 }
 
-const char *fftconv_plan_path(const fftconv_plan *p)
-{
-    if (!p) return "";
-    switch (p->path) {
-    case PATH_FUSED3: return "fused3";
-    case PATH_MULTIPASS: return "multipass";
-    case PATH_SMALL: return "small";
-    default: return "staged";
-    }
-}
+const char *fftconv_plan_path(const fftconv_plan *p) { return p ? path_name(p->path) : ""; }
 
 int fftconv_plan_factors(const fftconv_plan *p, int64_t *factors, int max_factors)
 {

@@ -226,6 +226,7 @@ int fused3_big_dk_finish(const fftconv_plan *p, const void *dkf, void *tmp, floa
 
 // ---- short transforms, fft_size 256 .. 4096, any dtype (small.hip); radices reported in f3.N1..N3
 bool small_supported(int64_t N, int64_t M, int dtype);
+FacList small_factor_list(int64_t M);      // its radices, outermost first
 int small_init(fftconv_plan *p);
 size_t small_kf_bytes(const fftconv_plan *p);
 int small_pack_kf(const fftconv_plan *p, const double2 *spec, int64_t h0, int64_t nh, const uint8_t *keep_dev,

@@ -31,16 +31,16 @@ void fftconv_machine_preset(int which, fftconv_machine *m)
         m->mu = 16;
         m->sram_seq = 32768;      // Section 3.2: p = 3 runs out of on-chip memory between 32K and 64K
     } else {
-        // MI355X, measured with this library's own kernels and micro-benchmarks:
-        //   sigma_H  torch.clone of a 1 GiB tensor (the paper's own method, Appendix C): 5.12 TB/s read + write
-        //   sigma_S  LDS, 16-byte writes and 4-byte strided reads of the exchange buffer: ~100 B/clk per
-        //            compute unit, 256 units, 2.4 GHz
-        //   tau_M    v_mfma_f32_16x16x32_bf16 issued back to back on every SIMD
-        //   tau_G    fp32 multiply-adds of the twiddle products: one vector instruction per 2.9 clk and SIMD
-        m->sigma_H = 5.1e12;
-        m->sigma_S = 61e12;
-        m->tau_M = 2.47e15;
-        m->tau_G = 108e12;
+        // MI355X: what fftconv_measure_machine() (machine.hip; `python bench.py --constants`) returned on
+        // one, median of three runs, rounded to two digits:
+        //   sigma_H  plain copy of 1 GiB, bytes read + written per second                        4.79e12
+        //   sigma_S  slow-down of a chain of matrix products from a trip through LDS per link    53e12
+        //   tau_M    v_mfma_f32_16x16x32_bf16 back to back, 16 accumulators, 2 waves per SIMD     2.27e15
+        //   tau_G    fp32 twiddle products (6 operations each) applied over and over             74e12
+        m->sigma_H = 4.8e12;
+        m->sigma_S = 53e12;
+        m->tau_M = 2.27e15;
+        m->tau_G = 74e12;
         m->mu = 16;               // 16 x 16 MFMA tiles
         m->sram_seq = 32768;      // 160 KB of LDS hold 32768 16-bit (re, im) pairs
     }

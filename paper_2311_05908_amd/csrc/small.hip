@@ -292,6 +292,18 @@ template <typename IO> int dispatch_small(const fftconv_plan *p, const void *u, 
 
 }  // namespace
 
+FacList small_factor_list(int64_t M)
+{
+    const Radices r = small_radices(M);
+    FacList fl;
+    for (int i = 0; i < MAX_FACTORS; ++i) fl.fac[i] = 0;
+    fl.fac[0] = r.r0;
+    fl.fac[1] = r.r1;
+    fl.fac[2] = r.r2;
+    fl.nf = r.r2 > 1 ? 3 : 2;
+    return fl;
+}
+
 bool small_supported(int64_t N, int64_t M, int dtype)
 {
     (void)dtype;

@@ -25,7 +25,7 @@ EXPORTS = [
     "fftconv_filter_fft_adjoint", "fftconv_backward_input", "fftconv_workspace_bytes_backward_filter",
     "fftconv_backward_filter", "fftconv_machine_preset", "fftconv_cost_model", "fftconv_balanced_factors",
     "fftconv_plan_order", "fftconv_filter_fft_sparse_digits", "fftconv_forward_freq_sparse_digits",
-    "fftconv_forward_static",
+    "fftconv_forward_static", "fftconv_plan_create_path", "fftconv_measure_machine",
 ]
 
 STATIC_WORKSPACE_BYTES = 64 << 20      # FFTCONV_STATIC_WORKSPACE_BYTES
@@ -66,6 +66,8 @@ def load(path: str | None = None):
     vp, i64, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
     lib.fftconv_plan_create.argtypes = [ctypes.POINTER(vp), i64, i64, i64, ci]
     lib.fftconv_plan_create.restype = ci
+    lib.fftconv_plan_create_path.argtypes = [ctypes.POINTER(vp), i64, i64, i64, ci, ctypes.c_char_p]
+    lib.fftconv_plan_create_path.restype = ci
     lib.fftconv_plan_destroy.argtypes = [vp]
     lib.fftconv_plan_destroy.restype = ci
     lib.fftconv_kf_bytes.argtypes = [vp]
@@ -105,6 +107,8 @@ def load(path: str | None = None):
     mp = ctypes.POINTER(Machine)
     lib.fftconv_machine_preset.argtypes = [ci, mp]
     lib.fftconv_machine_preset.restype = None
+    lib.fftconv_measure_machine.argtypes = [mp]
+    lib.fftconv_measure_machine.restype = ci
     lib.fftconv_cost_model.argtypes = [mp, i64, i64, i64, ci, ctypes.POINTER(i64)]
     lib.fftconv_cost_model.restype = ctypes.c_double
     lib.fftconv_balanced_factors.argtypes = [i64, ci, ctypes.POINTER(i64)]
@@ -153,6 +157,13 @@ def machine_preset(which: int = MACHINE_MI355X) -> Machine:
     return m
 
 
+def measure_machine() -> Machine:
+    """fftconv_measure_machine: the four rates of the cost model measured on the current GPU (about a second)."""
+    m = Machine()
+    _check(load().fftconv_measure_machine(ctypes.byref(m)))
+    return m
+
+
 def cost_model(machine: Machine, B: int, H: int, N: int, factors) -> float:
     """fftconv_cost_model: Eq. 2 in seconds for the given factors (outermost first)."""
     arr = (ctypes.c_int64 * len(factors))(*factors)
@@ -185,13 +196,15 @@ def plan_order(machine: Machine, N: int):
 class Plan:
     """fftconv_plan_create / fftconv_plan_destroy and the calls that take a plan."""
 
-    def __init__(self, N: int, fft_size: int, H: int, dtype, lib=None):
+    def __init__(self, N: int, fft_size: int, H: int, dtype, lib=None, path: str | None = None):
         if isinstance(dtype, str):
             dtype = _DTYPE_NAME[dtype]
         self.N, self.fft_size, self.H, self.dtype = int(N), int(fft_size), int(H), dtype
         self._lib = lib or load()
         self._h = ctypes.c_void_p()
-        self._ok(self._lib.fftconv_plan_create(ctypes.byref(self._h), self.N, self.fft_size, self.H, _DTYPE_CODE[dtype]))
+        # path: force a kernel family (fftconv_plan_create_path); None = the cost model's choice
+        self._ok(self._lib.fftconv_plan_create_path(ctypes.byref(self._h), self.N, self.fft_size, self.H, _DTYPE_CODE[dtype],
+                                                    path.encode() if path else None))
         self._ws = None
 
     def _ok(self, rc: int):

@@ -56,8 +56,8 @@ def oracle_filter(w, k):
     return kext, None, None
 
 
-def gpu_forward(w, u_cpu, k, variant="dense"):
-    plan = fftconv.Plan(w.N, w.fft_size, w.H, w.dtype)
+def gpu_forward(w, u_cpu, k, variant="dense", path=None):
+    plan = fftconv.Plan(w.N, w.fft_size, w.H, w.dtype, path=path)
     kd = torch.from_numpy(k[:, : w.filter_len].copy()).cuda()
     if w.n_blocks:
         bk = synth.block_keep(w)
@@ -73,11 +73,12 @@ def gpu_forward(w, u_cpu, k, variant="dense"):
     return y.cpu(), plan
 
 
-def check_all_sequences(w, variant="dense"):
-    """Every sequence of a (small) workload against the oracle; returns the max error."""
+def check_all_sequences(w, variant="dense", path=None):
+    """Every sequence of a (small) workload against the oracle; returns the max error.
+    path: force a kernel family instead of the cost model's choice."""
     u = synth.gen_u(w)
     k = synth.gen_k(w)
-    y, plan = gpu_forward(w, u, k, variant)
+    y, plan = gpu_forward(w, u, k, variant, path)
     kext, keep, kfull = oracle_filter(w, k)
     if keep is not None:
         kext = oracle.mask_filter(kfull, keep)

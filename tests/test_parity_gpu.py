@@ -104,6 +104,27 @@ def test_fp32_long_rows_sampled_positions(lg, circular):
     assert err <= TOL["f32"]
 
 
+@pytest.mark.parametrize("dtype,B,H,N,M,paths", [
+    ("bf16", 4, 3, 1024, 2048, ("fused3", "small")),          # matrix cores against vector ALUs
+    ("f16", 5, 2, 128, 256, ("fused3", "small")),
+    ("f16", 3, 2, 4096, 8192, ("fused3", "multipass")),       # one kernel against outer passes through HBM
+    ("bf16", 2, 2, 16384, 32768, ("fused3", "multipass")),
+])
+def test_every_family_that_can_run_a_shape_matches_the_oracle(dtype, B, H, N, M, paths):
+    """Where several kernel families can run a shape, plan creation takes the one Eq. 2 prices lowest (the first of
+    `paths`); the others can be forced and must return the same convolution."""
+    w = synth.scaled(W["cfg2"], B=B, H=H, N=N, fft_size=M, dtype=dtype, alpha=(1e-2, 1e-1))
+    _, chosen = check_all_sequences(w)
+    assert chosen.path == paths[0]
+    for path in paths:
+        err, plan = check_all_sequences(w, path=path)
+        print("forced %s %s N=%d M=%d factors=%s err=%.3e" % (path, dtype, N, M, plan.factors, err), flush=True)
+        assert plan.path == path
+        assert err <= TOL[dtype]
+    with pytest.raises(fftconv.FFTConvError):
+        fftconv.Plan(N, M, H, dtype, path="staged")           # fp32 I/O only
+
+
 def test_delta_filter_is_identity_and_zero_input_gives_zero():
     N, M, H, B = 1024, 2048, 3, 2
     plan = fftconv.Plan(N, M, H, torch.float32)

@@ -97,3 +97,17 @@ def test_order_chosen_for_this_chip_matches_the_dispatch_rule():
         assert fftconv.plan_order(g, 1 << lg)[0] == 4
     for lg in range(8, 12):
         assert fftconv.plan_order(g, 1 << lg)[0] == 2
+
+
+def test_a_family_without_a_kernel_for_the_shape_is_refused_before_any_device_is_touched():
+    import ctypes
+    lib = fftconv.load()
+    h = ctypes.c_void_p()
+    for N, M, dtype, path in ((4096, 8192, fftconv.FFTCONV_F32, b"fused3"),      # the fused kernels are 16-bit
+                              (4096, 8192, fftconv.FFTCONV_BF16, b"small"),       # short transforms only
+                              (1024, 2048, fftconv.FFTCONV_BF16, b"multipass"),   # from 8192 up
+                              (1000, 8192, fftconv.FFTCONV_BF16, b"staged"),      # fp32 I/O only
+                              (4096, 8192, fftconv.FFTCONV_BF16, b"no such family")):
+        assert lib.fftconv_plan_create_path(ctypes.byref(h), N, M, 2, dtype, path) == -2
+        assert not h.value
+        assert b"no kernel of family" in lib.fftconv_last_error()
