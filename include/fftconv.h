@@ -28,7 +28,15 @@
  *    arguments).
  *  - All *_filter_fft* and *_forward* calls are asynchronous on `stream`
  *    (a hipStream_t passed as void*, NULL = the default stream).  They do not
- *    allocate and do not synchronise.
+ *    allocate and do not synchronise, with one exception: the calls that take
+ *    a mask or pattern in HOST memory (fftconv_filter_fft_sparse,
+ *    fftconv_filter_fft_sparse_digits) copy it to the device from pageable
+ *    memory, for which the runtime may make the calling thread wait until
+ *    earlier work on `stream` has finished.
+ *  - A plan is const in every call after its creation as far as its meaning
+ *    goes, but the filter transforms use device scratch that the plan owns:
+ *    calls of the *_filter_fft* family on ONE plan must not overlap (different
+ *    streams or threads); forward and backward calls may.
  *  - Every call returns FFTCONV_OK (0) or a negative error code; on error no
  *    kernel has been launched by that call.  fftconv_last_error() returns a
  *    thread-local description of the most recent failure on this thread.
@@ -121,11 +129,16 @@ int fftconv_forward_static(const fftconv_plan *plan, const void *u, const void *
                            int64_t B, int64_t H, int64_t N, void *stream);
 
 /* Partial convolution (Section 3.3): the filter is zero for taps t >= Nk.
- * k_f must come from fftconv_filter_fft(plan, k, Nk, ...) with the same Nk.
- * Same result as fftconv_forward on that k_f; the plan may skip the parts of
- * the decomposition that a short filter leaves unused: plans with 16-bit I/O, causal shapes (N <= fft_size / 2,
- * N a multiple of 8) and fft_size >= 16384 run filters of Nk <= 2049 taps as overlapping 8192-point segments
- * (the outer factors of the decomposition are never executed). */
+ * Same result as fftconv_forward on that k_f; the plan may skip the parts of the decomposition that a
+ * short filter leaves unused: plans with 16-bit I/O, causal shapes (N <= fft_size / 2, N a multiple of 8)
+ * and fft_size >= 16384 run filters of Nk <= 2049 taps as overlapping 8192-point segments (the outer
+ * factors of the decomposition are never executed).  That route needs the second, 8192-point spectrum
+ * which fftconv_filter_fft(plan, k, Nk, ...) stores behind the dense one when called with this same Nk,
+ * together with a tag naming the Nk.  Any other k_f of the plan (built for another Nk -- for instance
+ * from the full-length filter with its tail zeroed --, masked, or adjoint) carries another tag, and the
+ * call then runs the plan's dense kernels on it: the choice is made on the device by the kernels
+ * themselves (both routes are launched, the one whose tag test fails returns at once), so the result is
+ * always the dense result and nothing synchronises with the host. */
 int fftconv_forward_partial(const fftconv_plan *plan, const void *u, const void *k_f, void *y,
                             int64_t B, int64_t H, int64_t N, int64_t Nk, void *workspace, void *stream);
 

@@ -39,6 +39,12 @@ int raise_dynamic_lds(const void *kernel, int bytes)
     return FFTCONV_OK;
 }
 
+LaunchGate &launch_gate()
+{
+    static thread_local LaunchGate g;
+    return g;
+}
+
 static bool is_pow2(int64_t v) { return v > 0 && (v & (v - 1)) == 0; }
 
 constexpr int64_t MAX_BLOCKS = 4096;
@@ -292,8 +298,16 @@ static int filter_fft_impl(const fftconv_plan *p, const float *k, int64_t Nk, co
         if (rc) return rc;
     }
     // a short filter of a plan that can run partial convolutions as short segments: add the
-    // short transform's spectrum behind the dense one
-    if (!block_keep && !adjoint && fused3_short_ok(p, Nk)) return fused3_filter_short(p, k, Nk, k_f, s);
+    // short transform's spectrum behind the dense one, and say in the tag behind it which filter length it
+    // belongs to (0: none -- masked, adjoint or longer filters leave that region as it was)
+    if (p->f3.consts_short) {
+        const bool with_short = !block_keep && !adjoint && fused3_short_ok(p, Nk);
+        if (with_short) {
+            rc = fused3_filter_short(p, k, Nk, k_f, s);
+            if (rc) return rc;
+        }
+        return fused3_set_short_tag(p, k_f, with_short ? Nk : 0, s);
+    }
     return FFTCONV_OK;
 }
 
@@ -508,7 +522,18 @@ int fftconv_forward_partial(const fftconv_plan *p, const void *u, const void *k_
         return FFTCONV_EINVAL;
     }
     if (B == 0) return FFTCONV_OK;
-    if (fused3_short_ok(p, Nk)) return fused3_forward_short(p, u, k_f, y, B, Nk, (hipStream_t)stream);
+    if (!fused3_short_ok(p, Nk)) return fftconv_forward(p, u, k_f, y, B, H, N, workspace, stream);
+    // Both routes are launched, gated on the tag the filter transform left in k_f: the overlapping short
+    // segments run if k_f carries a short spectrum for exactly this Nk, the plan's dense kernels otherwise
+    // (a k_f from another Nk, a masked or an adjoint one); the kernels of the other route return at once.
+    struct GateScope {
+        LaunchGate saved = launch_gate();
+        ~GateScope() { launch_gate() = saved; }
+    } scope;
+    launch_gate() = LaunchGate{fused3_short_tag(p, k_f), (long long)Nk, 1};
+    rc = fused3_forward_short(p, u, k_f, y, B, Nk, (hipStream_t)stream);
+    if (rc) return rc;
+    launch_gate().run_if_equal = 0;
     return fftconv_forward(p, u, k_f, y, B, H, N, workspace, stream);
 }
 

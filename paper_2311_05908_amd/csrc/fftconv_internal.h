@@ -33,6 +33,22 @@ void set_error(const char *fmt, ...);
 // safe to call from several threads and before every launch.
 int raise_dynamic_lds(const void *kernel, int bytes);
 
+// A launch gate: when tag is not null a kernel starts by reading *tag and returns at once unless
+// (*tag == want) == run_if_equal.  fftconv_forward_partial launches both of its routes with opposite gates
+// on the tag that the filter transform left behind the short spectrum, so the choice between them is made
+// on the device, where the tag lives, without a host synchronisation.  The gate of the calling thread is
+// empty except inside that entry point; every forward kernel takes it as its last argument.
+struct LaunchGate {
+    const long long *tag = nullptr;
+    long long want = 0;
+    int run_if_equal = 0;
+};
+LaunchGate &launch_gate();          // of the calling thread
+__device__ __forceinline__ bool gate_closed(const LaunchGate &g)
+{
+    return g.tag != nullptr && ((*g.tag == g.want) != (g.run_if_equal != 0));
+}
+
 enum Path { PATH_STAGED = 0, PATH_FUSED3 = 1, PATH_MULTIPASS = 2, PATH_SMALL = 3 };
 
 constexpr int MAX_FACTORS = 8;
@@ -160,6 +176,9 @@ bool fused3_short_ok(const fftconv_plan *p, int64_t Nk);
 int fused3_init_short(fftconv_plan *p);
 size_t fused3_short_kf_bytes(const fftconv_plan *p);
 int fused3_filter_short(const fftconv_plan *p, const float *k, int64_t Nk, void *kf, hipStream_t s);
+// the tag behind the short spectrum: the Nk that spectrum was built for, 0 = none
+const long long *fused3_short_tag(const fftconv_plan *p, const void *kf);
+int fused3_set_short_tag(const fftconv_plan *p, void *kf, int64_t Nk, hipStream_t s);
 // filter transform in one kernel, taps to k_f; adjoint: the conjugate spectrum
 int fused3_filter(const fftconv_plan *p, const float *k, int64_t Nk, bool adjoint, const uint8_t *keep_dev,
                   int64_t n_blocks, void *kf, hipStream_t s);

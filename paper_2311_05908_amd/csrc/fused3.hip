@@ -71,9 +71,10 @@ using namespace f3;
 template <int N2, int N3, typename TT, bool REGC, bool CPLX, int LIVE = 4>
 __global__ void __launch_bounds__(NT) k_fused3(const uint16_t *u, uint16_t *y,
                                               const uint32_t *__restrict__ kf, Consts cs, int B, int H, int N,
-                                              int KoN, int ko_lo, int ko_hi)
+                                              int KoN, int ko_lo, int ko_hi, LaunchGate gate)
 {
     using G = Geo<N2, N3>;
+    if (gate_closed(gate)) return;
     constexpr int R2 = G::R2, R3 = G::R3, C3 = G::C3, C1 = G::C1;
     // streamed tables are requested one tile ahead of their use when two tiles' worth fits in registers
     constexpr bool AHEAD = !REGC && N2 == 16;
@@ -766,7 +767,7 @@ int launch(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_
     int grid = (int)(T < p->f3.num_cu ? T : p->f3.num_cu);
     if (!REGC && grid >= 8) grid -= grid % 8;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NT), lds, s, (const uint16_t *)u, (uint16_t *)y,
-                       (const uint32_t *)kf, consts_of<N2, N3>(p), (int)B, (int)H, (int)N, KoN, ko_lo, ko_hi);
+                       (const uint32_t *)kf, consts_of<N2, N3>(p), (int)B, (int)H, (int)N, KoN, ko_lo, ko_hi, launch_gate());
     FC_HIP(hipGetLastError());
     return FFTCONV_OK;
 }
@@ -931,9 +932,11 @@ int fused3_init_short(fftconv_plan *p)
     return build_tables<16, 16>(p, &p->f3.consts_short);
 }
 
+constexpr size_t SHORT_TAG_BYTES = 256;     // the tag word, padded so that whatever follows stays aligned
+
 size_t fused3_short_kf_bytes(const fftconv_plan *p)
 {
-    return p->f3.consts_short ? (size_t)(p->H * SHORT_M) * sizeof(float2) : 0;
+    return p->f3.consts_short ? (size_t)(p->H * SHORT_M) * sizeof(float2) + SHORT_TAG_BYTES : 0;
 }
 
 // bytes of the plan's dense spectrum, = offset of the short one
@@ -947,6 +950,20 @@ size_t fused3_kf_bytes(const fftconv_plan *p)
 {
     if (p->M >= 16384) return fused3_big_kf_bytes(p) + fused3_short_kf_bytes(p);
     return (size_t)(p->H * 8192) * sizeof(float2);             // fft <= 8192: the 8192 slots of the wave-specialised kernel
+}
+
+const long long *fused3_short_tag(const fftconv_plan *p, const void *kf)
+{
+    return (const long long *)((const char *)kf + dense_kf_bytes(p) + (size_t)(p->H * SHORT_M) * sizeof(float2));
+}
+
+__global__ void k_set_tag(long long *tag, long long value) { *tag = value; }
+
+int fused3_set_short_tag(const fftconv_plan *p, void *kf, int64_t Nk, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_set_tag, dim3(1), dim3(1), 0, s, (long long *)fused3_short_tag(p, kf), (long long)Nk);
+    FC_HIP(hipGetLastError());
+    return FFTCONV_OK;
 }
 
 static int64_t history_of(int64_t Nk) { return (Nk - 1 + 7) / 8 * 8; }

@@ -105,13 +105,15 @@ template <typename TT, bool FULL, int N2, bool HALF3, bool GATED = false>
 __global__ void __launch_bounds__(NT, (N2 == 16 && !GATED) ? 4 : 2) k_fused3_big(const uint16_t *__restrict__ u, uint16_t *__restrict__ y,
                                                   const void *__restrict__ kf, const void *__restrict__ consts,
                                                   uint32_t kf_bytes, int B, int H, int N,
-                                                  const uint16_t *__restrict__ wg, const uint16_t *__restrict__ vg)
+                                                  const uint16_t *__restrict__ wg, const uint16_t *__restrict__ vg,
+                                                  LaunchGate gate)
 {
     using CW = typename TT::CW;
     using BG = BigGeo<N2>;
     constexpr int BPK1 = BG::PK1, BPN3 = BG::PN3, R2 = BG::R2, NCH = BG::NCH;
     constexpr int T3 = HALF3 ? 1 : 2;                             // live k3 tiles
     extern __shared__ uint32_t XB[];
+    if (gate_closed(gate)) return;
     const int tid = threadIdx.x, l = tid & 63, q = l >> 4, c16 = l & 15;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     // Persistent workgroup; a work item t = h * npairs + pair.  Workgroups are dealt to the 8
@@ -1022,7 +1024,7 @@ int launch_big(const fftconv_plan *p, const void *u, const void *kf, void *y, in
     if (grid >= 8) grid -= grid % 8;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NT), BG::LDS_BYTES, s, (const uint16_t *)u, (uint16_t *)y,
                        kf, (const void *)p->f3.consts, (uint32_t)kf_bytes, (int)B, (int)p->H, (int)p->N,
-                       (const uint16_t *)wg, (const uint16_t *)vg);
+                       (const uint16_t *)wg, (const uint16_t *)vg, launch_gate());
     FC_HIP(hipGetLastError());
     return FFTCONV_OK;
 }

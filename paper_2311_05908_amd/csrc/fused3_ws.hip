@@ -46,9 +46,10 @@ template <typename TT, bool FULL, int GATE, bool SKIP1 = false>
 __global__ void __launch_bounds__(NT) k_fused3_ws(const uint16_t *__restrict__ u, uint16_t *__restrict__ y,
                                                  const uint2 *__restrict__ kf, Consts cs, int B, int H, int N, int nseg, int P, int Lo,
                                                  const uint16_t *__restrict__ wg, const uint16_t *__restrict__ vg,
-                                                 uint32_t live_k1, int groups, int lg_half)
+                                                 uint32_t live_k1, int groups, int lg_half, LaunchGate gate)
 {
     extern __shared__ uint32_t smem[];
+    if (gate_closed(gate)) return;
     uint32_t *const XBb = smem;                                   // [2][XBW]
     uint16_t *const UBb = (uint16_t *)(smem + 2 * XBW);           // [2][UBE]
     uint16_t *const YBb = UBb + 2 * UBE;                          // [2][UBE]
@@ -390,7 +391,7 @@ int fused3_ws_launch(const fftconv_plan *p, const void *consts, const void *u, c
     const bool f16 = p->dtype == FFTCONV_F16;
     const int gate = (wg ? 1 : 0) | (vg ? 2 : 0);
     using Kern = void (*)(const uint16_t *, uint16_t *, const uint2 *, Consts, int, int, int, int, int, int,
-                          const uint16_t *, const uint16_t *, uint32_t, int, int);
+                          const uint16_t *, const uint16_t *, uint32_t, int, int, LaunchGate);
     static const Kern table[2][2][4] = {
         {{k_fused3_ws<BF16, false, 0>, k_fused3_ws<BF16, false, 1>, k_fused3_ws<BF16, false, 2>, k_fused3_ws<BF16, false, 3>},
          {k_fused3_ws<BF16, true, 0>, k_fused3_ws<BF16, true, 1>, k_fused3_ws<BF16, true, 2>, k_fused3_ws<BF16, true, 3>}},
@@ -405,7 +406,7 @@ int fused3_ws_launch(const fftconv_plan *p, const void *consts, const void *u, c
     const int grid = (int)(T < p->f3.num_cu ? T : p->f3.num_cu);
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NT), WS_LDS_BYTES, s, (const uint16_t *)u, (uint16_t *)y,
                        (const uint2 *)kf, consts_at<16, 16>(consts), (int)B, (int)p->H, (int)p->N, nseg, P, Lo,
-                       (const uint16_t *)wg, (const uint16_t *)vg, live_k1, groups, lg_half);
+                       (const uint16_t *)wg, (const uint16_t *)vg, live_k1, groups, lg_half, launch_gate());
     FC_HIP(hipGetLastError());
     return FFTCONV_OK;
 }

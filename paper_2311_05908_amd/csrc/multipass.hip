@@ -128,9 +128,10 @@ struct OuterGeo {
 template <bool F16, int RA, int RB, int CV, bool FULLN, bool GATED>
 __global__ void __launch_bounds__(TB, 4) k_outer_fwd(const uint16_t *__restrict__ u, uint32_t *__restrict__ S, int CT,
                                                  int B, int H, int N, int64_t M, int ko_lo, int ko_hi,
-                                                 const uint16_t *__restrict__ wg)
+                                                 const uint16_t *__restrict__ wg, LaunchGate gate)
 {
     extern __shared__ float2 sm[];
+    if (gate_closed(gate)) return;
     constexpr int No = RA * RB;
     constexpr int RAIN = FULLN ? RA : RA / 2;      // outer rows that can hold input
     float2 *wno = sm;                              // W_No^j, j < No
@@ -253,9 +254,10 @@ __global__ void __launch_bounds__(TB, 4) k_outer_fwd(const uint16_t *__restrict_
 template <bool F16, int RA, int RB, int CV, bool FULLN, bool GATED>
 __global__ void __launch_bounds__(TB, 4) k_outer_inv(const uint32_t *__restrict__ S, uint16_t *__restrict__ y, int CT,
                                                  int B, int H, int N, int64_t M, int ko_lo, int ko_hi,
-                                                 const uint16_t *__restrict__ vg)
+                                                 const uint16_t *__restrict__ vg, LaunchGate gate)
 {
     extern __shared__ float2 sm[];
+    if (gate_closed(gate)) return;
     constexpr int No = RA * RB;
     constexpr int RAIN = FULLN ? RA : RA / 2;      // outer rows that are kept
     float2 *wno = sm;
@@ -409,10 +411,10 @@ int launch_outer_t(bool inverse, const OuterGeo &g, dim3 grid, const void *src, 
     FC_TRY(raise_dynamic_lds((const void *)k_outer_inv<F16, RA, RB, CV, FULLN, GATED>, 160 * 1024));
     if (!inverse)
         hipLaunchKernelGGL((k_outer_fwd<F16, RA, RB, CV, FULLN, GATED>), grid, dim3(TB), lds, s, (const uint16_t *)src,
-                           (uint32_t *)dst, g.CT, B, H, N, M, ko_lo, ko_hi, (const uint16_t *)gate);
+                           (uint32_t *)dst, g.CT, B, H, N, M, ko_lo, ko_hi, (const uint16_t *)gate, launch_gate());
     else
         hipLaunchKernelGGL((k_outer_inv<F16, RA, RB, CV, FULLN, GATED>), grid, dim3(TB), lds, s, (const uint32_t *)src,
-                           (uint16_t *)dst, g.CT, B, H, N, M, ko_lo, ko_hi, (const uint16_t *)gate);
+                           (uint16_t *)dst, g.CT, B, H, N, M, ko_lo, ko_hi, (const uint16_t *)gate, launch_gate());
     FC_HIP(hipGetLastError());
     return FFTCONV_OK;
 }

@@ -321,6 +321,49 @@ def test_partial_convolution_segment_path(B, H, N, Nk):
     assert err_dense <= TOL[w.dtype] and err_skip <= TOL[w.dtype]
 
 
+@pytest.mark.parametrize("dtype,B,H,N,M", [
+    ("bf16", 3, 2, 8192, 16384),      # single-kernel plan
+    ("f16", 2, 2, 16384, 32768),
+    ("bf16", 2, 1, 32768, 65536),     # multi-pass plan: all three of its kernels are gated
+])
+def test_partial_entry_point_on_a_spectrum_built_for_another_filter_length(dtype, B, H, N, M):
+    """fftconv_forward_partial takes the segment route only when k_f carries the short spectrum of exactly that Nk
+    (a tag on the device says so); on any other k_f of the plan it must return what fftconv_forward returns."""
+    Nk = 1024
+    w = synth.scaled(W["cfg5a"], B=B, H=H, N=N, fft_size=M, dtype=dtype, Nk=Nk)
+    u = synth.gen_u(w)
+    k = synth.gen_k(w)                                    # (H, N), taps >= Nk are zero
+    ref = oracle.fftconv(u.double().numpy(), k, M)
+    plan = fftconv.Plan(N, M, H, dtype)
+    ud = u.cuda()
+    kfull = torch.from_numpy(k).cuda()
+    kshort = torch.from_numpy(k[:, :Nk].copy()).cuda()
+    stale = torch.from_numpy(synth.gen_k(synth.scaled(w, seed_k=999))[:, :Nk].copy()).cuda()
+    from parity_util import parity_error
+    # 1. the full-length filter with its tail zeroed (no short spectrum is built for Nk = N); the buffer first
+    #    holds the short spectrum of ANOTHER filter, which a route that ignored the tag would use
+    kf = plan.filter_fft(stale)
+    lib = fftconv.load()
+    assert lib.fftconv_filter_fft(plan._h, kfull.data_ptr(), N, kf.data_ptr(), None) == 0
+    y = plan.forward_partial(ud, kf, Nk)
+    assert torch.equal(y, plan.forward(ud, kf))
+    assert parity_error(y.cpu().double().numpy(), ref, TOL[dtype], "zeroed tail") <= TOL[dtype]
+    # 2. a short spectrum built for a different Nk (more taps, the extra ones zero): still the dense result
+    assert lib.fftconv_filter_fft(plan._h, kfull.data_ptr(), Nk + 8, kf.data_ptr(), None) == 0
+    y = plan.forward_partial(ud, kf, Nk)
+    assert torch.equal(y, plan.forward(ud, kf))
+    # 3. the matching one: the segment route runs (a different kernel, so not bit-identical to the dense one)
+    kf = plan.filter_fft(kshort)
+    y = plan.forward_partial(ud, kf, Nk)
+    assert parity_error(y.cpu().double().numpy(), ref, TOL[dtype], "segments") <= TOL[dtype]
+    assert not torch.equal(y, plan.forward(ud, kf))
+    # 4. a masked and an adjoint spectrum in the same buffer reset the tag
+    assert lib.fftconv_filter_fft_adjoint(plan._h, kshort.data_ptr(), Nk, kf.data_ptr(), None) == 0
+    assert torch.equal(plan.forward_partial(ud, kf, Nk), plan.forward(ud, kf))
+    kf = plan.filter_fft(kshort, block_keep=[1, 1, 0, 0, 0, 0, 1, 1])
+    assert torch.equal(plan.forward_partial(ud, kf, Nk), plan.forward(ud, kf))
+
+
 @pytest.mark.parametrize("keep_blocks", [
     (0, 1, 2, 3, 28, 29, 30, 31),                     # the low-pass of config 5b: one live accumulator slot
     tuple(range(8)) + tuple(range(24, 32)),           # half of the spectrum: two live slots
