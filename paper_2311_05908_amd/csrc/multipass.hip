@@ -251,9 +251,9 @@ __global__ void __launch_bounds__(TB, 4) k_outer_fwd(const uint16_t *__restrict_
 }
 
 // ---- pass C: S -> conjugate twiddle -> outer inverse DFT -> the two real rows of the pair
-template <bool F16, int RA, int RB, int CV, bool FULLN, bool GATED>
+template <bool F16, int RA, int RB, int CV, bool FULLN, bool GATED, bool MIRROR>
 __global__ void __launch_bounds__(TB, 4) k_outer_inv(const uint32_t *__restrict__ S, uint16_t *__restrict__ y, int CT,
-                                                 int B, int H, int N, int64_t M, int ko_lo, int ko_hi,
+                                                 int B, int H, int N, int64_t M, int ko_lo, int ko_hi, int mirror_from,
                                                  const uint16_t *__restrict__ vg, LaunchGate gate)
 {
     extern __shared__ float2 sm[];
@@ -274,13 +274,21 @@ __global__ void __launch_bounds__(TB, 4) k_outer_inv(const uint32_t *__restrict_
     __syncthreads();
     const float ihm = 2.0f / (float)M;
     // step 1: T[ka*RB + b2] = conj(W_No^{ka b2}) * sum_{kb} conj(W_RB^{b2 kb}) conj(W_M^{r ko}) S[ko], ko = ka + RA kb
+    // MIRROR (mirror_from == No/2 + 1): rows ko > No/2 were never computed (a lone real row, see multipass_forward): before the
+    // twiddle row ko is the complex conjugate of row ko' = No - ko, i.e.
+    //   conj(W_M^{r ko}) S[ko] = conj(conj(W_M^{r ko'}) S[ko']),   W_M^{r ko'} = W_Mi^{r} conj(W_M^{r ko}),
+    // so the value that enters the inverse is conj(S[ko']) conj(conj(W_Mi^{r}) W_M^{r ko}): the mirror row is
+    // read and conjugated (a sign flip on the packed word), and from the first mirrored row on the twiddle of the
+    // recurrence carries the extra factor conj(W_Mi^{r}).
     for (int e = tid; e < RA * CG; e += TB) {
         const int c = (e % CG) * CV, ka = e / CG;
         uint32_t in[RB][CV];
 #pragma unroll
         for (int kb = 0; kb < RB; ++kb) {
             const int ko = ka + RA * kb;
-            const uint32_t *src = &S[((size_t)ph * No + ko) * MI + r0 + c];
+            // ko = ka + RA kb > No/2 = RA RB/2, written so that only kb == RB/2 depends on the thread
+            const bool mir = MIRROR && (RB == 1 ? ka > RA / 2 : (kb > RB / 2 || (kb == RB / 2 && ka > 0)));
+            const uint32_t *src = &S[((size_t)ph * No + (mir ? No - ko : ko)) * MI + r0 + c];
             if (ko >= ko_lo && ko < ko_hi) {                  // zeroed part of the spectrum: the row is zero
 #pragma unroll
                 for (int v = 0; v < CV; ++v) in[kb][v] = 0;
@@ -290,6 +298,10 @@ __global__ void __launch_bounds__(TB, 4) k_outer_inv(const uint32_t *__restrict_
                 in[kb][1] = t.y;
             } else {
                 in[kb][0] = *src;
+            }
+            if (mir) {                                        // conjugate: the imaginary part is the upper half
+#pragma unroll
+                for (int v = 0; v < CV; ++v) in[kb][v] ^= 0x80000000u;
             }
         }
         float2 o[RB][CV];
@@ -304,6 +316,11 @@ __global__ void __launch_bounds__(TB, 4) k_outer_inv(const uint32_t *__restrict_
             float2 x[RB];
 #pragma unroll
             for (int kb = 0; kb < RB; ++kb) {
+                // the first mirrored row of this thread: kb = RB/2 (ka > 0) or RB/2 + 1 (ka == 0)
+                const bool first_mirrored = RB == 1 ? ka > RA / 2
+                                                    : ((kb == RB / 2 && ka > 0) || (kb == RB / 2 + 1 && ka == 0));
+                if (MIRROR && first_mirrored)
+                    w = cmulcf(w, wm((int)(((int64_t)r * No) % M), ihm));        // times conj(W_Mi^{r}), once
                 x[kb] = cmulcf(unpack2<F16>(in[kb][v]), w);
                 w = cmulf(w, step);
             }
@@ -403,18 +420,25 @@ OuterGeo outer_geo(int64_t M)
 
 template <bool F16, int RA, int RB, bool FULLN, bool GATED>
 int launch_outer_t(bool inverse, const OuterGeo &g, dim3 grid, const void *src, void *dst, int B, int H, int N, int64_t M,
-                   hipStream_t s, int ko_lo, int ko_hi, const void *gate)
+                   hipStream_t s, int ko_lo, int ko_hi, int mirror_from, const void *gate)
 {
-    constexpr int CV = RB <= 16 ? 2 : 1;           // two columns per thread while the registers allow
+    // two columns per thread while the registers allow and while that still leaves an entry for every thread
+    // (at No = 256 a block has 32 columns: 16 x 32 / 2 entries would keep half of its 512 threads idle)
+    constexpr int CTC = MI / (RA * RB) < 32 ? 32 : MI / (RA * RB);
+    constexpr int CV = (RB <= 16 && RA * CTC / 2 >= TB) ? 2 : 1;
     const size_t lds = sizeof(float2) * ((size_t)g.No + (size_t)g.No * g.CT);
     FC_TRY(raise_dynamic_lds((const void *)k_outer_fwd<F16, RA, RB, CV, FULLN, GATED>, 160 * 1024));
-    FC_TRY(raise_dynamic_lds((const void *)k_outer_inv<F16, RA, RB, CV, FULLN, GATED>, 160 * 1024));
+    FC_TRY(raise_dynamic_lds((const void *)k_outer_inv<F16, RA, RB, CV, FULLN, GATED, false>, 160 * 1024));
+    FC_TRY(raise_dynamic_lds((const void *)k_outer_inv<F16, RA, RB, CV, FULLN, GATED, true>, 160 * 1024));
     if (!inverse)
         hipLaunchKernelGGL((k_outer_fwd<F16, RA, RB, CV, FULLN, GATED>), grid, dim3(TB), lds, s, (const uint16_t *)src,
                            (uint32_t *)dst, g.CT, B, H, N, M, ko_lo, ko_hi, (const uint16_t *)gate, launch_gate());
+    else if (mirror_from < g.No)
+        hipLaunchKernelGGL((k_outer_inv<F16, RA, RB, CV, FULLN, GATED, true>), grid, dim3(TB), lds, s, (const uint32_t *)src,
+                           (uint16_t *)dst, g.CT, B, H, N, M, ko_lo, ko_hi, mirror_from, (const uint16_t *)gate, launch_gate());
     else
-        hipLaunchKernelGGL((k_outer_inv<F16, RA, RB, CV, FULLN, GATED>), grid, dim3(TB), lds, s, (const uint32_t *)src,
-                           (uint16_t *)dst, g.CT, B, H, N, M, ko_lo, ko_hi, (const uint16_t *)gate, launch_gate());
+        hipLaunchKernelGGL((k_outer_inv<F16, RA, RB, CV, FULLN, GATED, false>), grid, dim3(TB), lds, s, (const uint32_t *)src,
+                           (uint16_t *)dst, g.CT, B, H, N, M, ko_lo, ko_hi, mirror_from, (const uint16_t *)gate, launch_gate());
     FC_HIP(hipGetLastError());
     return FFTCONV_OK;
 }
@@ -422,32 +446,32 @@ int launch_outer_t(bool inverse, const OuterGeo &g, dim3 grid, const void *src, 
 // the half-input instantiation needs an outer transform (No >= 2) and N <= M/2
 template <bool F16, int RA, int RB>
 int launch_outer(bool inverse, const OuterGeo &g, dim3 grid, const void *src, void *dst, int B, int H, int N, int64_t M,
-                 hipStream_t s, int ko_lo, int ko_hi, const void *gate)
+                 hipStream_t s, int ko_lo, int ko_hi, int mirror_from, const void *gate)
 {
     if constexpr (RA >= 2) {
         if ((int64_t)N <= M / 2)
-            return gate ? launch_outer_t<F16, RA, RB, false, true>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi, gate)
-                        : launch_outer_t<F16, RA, RB, false, false>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi, gate);
+            return gate ? launch_outer_t<F16, RA, RB, false, true>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi, mirror_from, gate)
+                        : launch_outer_t<F16, RA, RB, false, false>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi, mirror_from, gate);
     }
-    return gate ? launch_outer_t<F16, RA, RB, true, true>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi, gate)
-                : launch_outer_t<F16, RA, RB, true, false>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi, gate);
+    return gate ? launch_outer_t<F16, RA, RB, true, true>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi, mirror_from, gate)
+                : launch_outer_t<F16, RA, RB, true, false>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi, mirror_from, gate);
 }
 
 template <bool F16>
 int dispatch_outer(bool inverse, const OuterGeo &g, dim3 grid, const void *src, void *dst, int B, int H, int N,
-                   int64_t M, hipStream_t s, int ko_lo, int ko_hi, const void *gate)
+                   int64_t M, hipStream_t s, int ko_lo, int ko_hi, int mirror_from, const void *gate)
 {
     switch (g.No) {
-    case 1: return launch_outer<F16, 1, 1>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi, gate);
-    case 2: return launch_outer<F16, 2, 1>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi, gate);
-    case 4: return launch_outer<F16, 4, 1>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi, gate);
-    case 8: return launch_outer<F16, 8, 1>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi, gate);
-    case 16: return launch_outer<F16, 16, 1>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi, gate);
-    case 32: return launch_outer<F16, 16, 2>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi, gate);
-    case 64: return launch_outer<F16, 16, 4>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi, gate);
-    case 128: return launch_outer<F16, 16, 8>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi, gate);
-    case 256: return launch_outer<F16, 16, 16>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi, gate);
-    case 512: return launch_outer<F16, 16, 32>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi, gate);
+    case 1: return launch_outer<F16, 1, 1>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi, mirror_from, gate);
+    case 2: return launch_outer<F16, 2, 1>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi, mirror_from, gate);
+    case 4: return launch_outer<F16, 4, 1>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi, mirror_from, gate);
+    case 8: return launch_outer<F16, 8, 1>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi, mirror_from, gate);
+    case 16: return launch_outer<F16, 16, 1>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi, mirror_from, gate);
+    case 32: return launch_outer<F16, 16, 2>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi, mirror_from, gate);
+    case 64: return launch_outer<F16, 16, 4>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi, mirror_from, gate);
+    case 128: return launch_outer<F16, 16, 8>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi, mirror_from, gate);
+    case 256: return launch_outer<F16, 16, 16>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi, mirror_from, gate);
+    case 512: return launch_outer<F16, 16, 32>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi, mirror_from, gate);
     default:
         set_error("multipass: unsupported outer length %d", g.No);
         return FFTCONV_EUNSUPPORTED;
@@ -496,11 +520,17 @@ int multipass_pack_kf(const fftconv_plan *p, const double2 *spec, int64_t h0, in
     return FFTCONV_OK;
 }
 
-// ko_lo, ko_hi: outer frequency digits ko in [ko_lo, ko_hi) only meet zeroed bins of k_f (frequency-sparse
-// filters); their rows of the workspace are skipped by all three passes.  ko_lo >= ko_hi: none.
-// wg, vg: input / output gate of the gated form (same shape and dtype as u), fused into passes A and C.
-int multipass_forward(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, void *workspace,
-                      hipStream_t s, int ko_lo, int ko_hi, const void *wg, const void *vg)
+// One set of the three passes over rows [0, B) of u.  ko_lo, ko_hi: outer frequency digits ko in [ko_lo, ko_hi)
+// only meet zeroed bins of k_f (frequency-sparse filters); their rows of the workspace are skipped by all three
+// passes.  ko_lo >= ko_hi: none.  wg, vg: input / output gate of the gated form, fused into passes A and C.
+// lone: B == 1 and the row is transformed as a REAL sequence (Appendix A.1's point -- a real input needs half
+// of a complex transform -- taken at the outer factor): before the twiddle, row No - ko of the outer transform
+// of a real sequence is the conjugate of row ko, its spectrum is the mirror image of row ko's, and since the
+// filter is real the same holds after the inner convolutions.  So only the rows ko <= No/2 are written by pass A,
+// convolved by pass B (which then reads only those rows of k_f) and read by pass C, which forms the others as
+// conjugates: half of the workspace traffic, of the k_f traffic and of the inner transforms.
+static int multipass_passes(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, uint32_t *S,
+                            hipStream_t s, int ko_lo, int ko_hi, const void *wg, const void *vg, bool lone)
 {
     const OuterGeo g = outer_geo(p->M);
     const int64_t npairs = (B + 1) / 2;
@@ -510,16 +540,39 @@ int multipass_forward(const fftconv_plan *p, const void *u, const void *kf, void
         return FFTCONV_EUNSUPPORTED;
     }
     const bool f16 = p->dtype == FFTCONV_F16;
-    uint32_t *S = (uint32_t *)workspace;
     const dim3 grid((unsigned)(MI / g.CT), (unsigned)rows);
     if (ko_lo >= ko_hi) ko_lo = ko_hi = g.No;            // nothing skipped
-    int rc = f16 ? dispatch_outer<true>(false, g, grid, u, S, (int)B, (int)p->H, (int)p->N, p->M, s, ko_lo, ko_hi, wg)
-                 : dispatch_outer<false>(false, g, grid, u, S, (int)B, (int)p->H, (int)p->N, p->M, s, ko_lo, ko_hi, wg);
+    // rows that passes A and B leave out, rows that pass C takes as zero, rows that pass C mirrors
+    int ab_lo = ko_lo, ab_hi = ko_hi, c_lo = ko_lo, c_hi = ko_hi, mirror_from = g.No;
+    if (lone && g.No >= 4 && ko_lo >= ko_hi) {            // (with a sparse filter the lone row runs as a pair without partner)
+        mirror_from = ab_lo = g.No / 2 + 1;
+        ab_hi = g.No;
+    }
+    int rc = f16 ? dispatch_outer<true>(false, g, grid, u, S, (int)B, (int)p->H, (int)p->N, p->M, s, ab_lo, ab_hi, g.No, wg)
+                 : dispatch_outer<false>(false, g, grid, u, S, (int)B, (int)p->H, (int)p->N, p->M, s, ab_lo, ab_hi, g.No, wg);
     if (rc) return rc;
-    rc = fused3_inner_rows(p, S, kf, npairs, p->H * g.No, s, g.No, ko_lo, ko_hi);
+    rc = fused3_inner_rows(p, S, kf, npairs, p->H * g.No, s, g.No, ab_lo, ab_hi);
     if (rc) return rc;
-    return f16 ? dispatch_outer<true>(true, g, grid, S, y, (int)B, (int)p->H, (int)p->N, p->M, s, ko_lo, ko_hi, vg)
-               : dispatch_outer<false>(true, g, grid, S, y, (int)B, (int)p->H, (int)p->N, p->M, s, ko_lo, ko_hi, vg);
+    return f16 ? dispatch_outer<true>(true, g, grid, S, y, (int)B, (int)p->H, (int)p->N, p->M, s, c_lo, c_hi, mirror_from, vg)
+               : dispatch_outer<false>(true, g, grid, S, y, (int)B, (int)p->H, (int)p->N, p->M, s, c_lo, c_hi, mirror_from, vg);
+}
+
+// Batch rows are transformed two at a time (one complex transform per pair, the filter being real); a row left
+// over (odd B, B = 1) goes through a set of passes of its own as a real sequence (see above).
+int multipass_forward(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, void *workspace,
+                      hipStream_t s, int ko_lo, int ko_hi, const void *wg, const void *vg)
+{
+    uint32_t *S = (uint32_t *)workspace;
+    const int64_t Be = B - B % 2;                        // rows in pairs
+    if (Be > 0) {
+        const int rc = multipass_passes(p, u, kf, y, Be, S, s, ko_lo, ko_hi, wg, vg, false);
+        if (rc) return rc;
+    }
+    if (B % 2 == 0) return FFTCONV_OK;
+    const size_t ofs = (size_t)Be * (size_t)p->H * (size_t)p->N;             // elements before the last row
+    auto at = [&](const void *base) { return base ? (const void *)((const uint16_t *)base + ofs) : nullptr; };
+    return multipass_passes(p, at(u), kf, (uint16_t *)y + ofs, 1, S + (size_t)(Be / 2) * p->H * p->M, s, ko_lo, ko_hi,
+                            at(wg), at(vg), true);
 }
 
 }  // namespace fftconv
