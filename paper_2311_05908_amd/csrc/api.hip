@@ -577,7 +577,7 @@ int fftconv_forward_freq_sparse_digits(const fftconv_plan *p, const void *u, con
         return m;
     };
     if (p->path == PATH_FUSED3)          // digits (k1, k2, k3)
-        return fused3_forward_sparse(p, u, k_f, y, B, live_mask(2), (hipStream_t)stream, live_mask(0));
+        return fused3_forward_sparse(p, u, k_f, y, B, live_mask(2), (hipStream_t)stream, live_mask(0), live_mask(1));
     if (p->path == PATH_MULTIPASS) {
         // digit 0 is the outer frequency ko; kept: ko < lo or ko >= hi, whose mirror images (No - ko) mod No
         // are ko <= lo - 1 and ko >= No - (lo - 1)

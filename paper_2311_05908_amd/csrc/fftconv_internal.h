@@ -169,7 +169,7 @@ size_t fused3_kf_bytes(const fftconv_plan *p);
 int fused3_forward(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, hipStream_t s);
 // frequency-sparse forward: live = number of accumulator registers (1..4) that can hold non-zero k_f
 int fused3_forward_sparse(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, uint32_t live_k3,
-                          hipStream_t s, uint32_t live_k1 = 0xffffffffu);
+                          hipStream_t s, uint32_t live_k1 = 0xffffffffu, uint32_t live_k2 = 0xffffffffu);
 uint32_t fused3_live_k3(const fftconv_plan *p, const uint8_t *block_keep, int64_t n_blocks);
 // partial convolution by overlapping short segments; returns FFTCONV_EUNSUPPORTED if this plan / Nk cannot
 bool fused3_short_ok(const fftconv_plan *p, int64_t Nk);

@@ -825,18 +825,18 @@ int fused3_init(fftconv_plan *p)
 }
 
 // Frequency-sparse filter (Appendix A.4): live_k3 / live_k1 have a bit set for every value of the digit that
-// can meet a non-zero bin of k_f.  The kernels for 16384 and 32768 skip the half of the innermost stage
-// that only meets zeroed bins when live_k3 allows; the 8192 kernel skips the k1 planes that are not live
-// (the trip count of its per-plane loop).
+// can meet a non-zero bin of k_f.  The kernels for 16384 and 32768 skip the tile of the innermost digit k3, and
+// (32768) of the middle digit k2, that only meets zeroed bins, and the k1 planes that are not live; the 8192
+// kernel skips the k1 planes that are not live (the trip count of its per-plane loop).
 int fused3_forward_sparse(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, uint32_t live_k3,
-                          hipStream_t s, uint32_t live_k1)
+                          hipStream_t s, uint32_t live_k1, uint32_t live_k2)
 {
     if (p->M == 16384 || p->M == 32768) {
         if (((uintptr_t)u | (uintptr_t)y) & 15) {
             set_error("fftconv_forward_freq_sparse: u and y must be 16-byte aligned for this plan");
             return FFTCONV_EINVAL;
         }
-        return fused3_big_forward(p, u, kf, y, B, live_k3, s);
+        return fused3_big_forward(p, u, kf, y, B, live_k3, s, live_k2, live_k1);
     }
     if (p->M == 8192 && live_k1 != 0xffffffffu) {
         if (((uintptr_t)u | (uintptr_t)y) & 15) {

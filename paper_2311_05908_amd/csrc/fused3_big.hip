@@ -78,13 +78,20 @@ __host__ __device__ inline int big_sigma_inv(int d)
     if (d >= 24) return d - 16;
     return 16 + (d - 8);
 }
+// Order of the middle frequency digit k2: slot m (16 tile + position in the tile) of a stage-2 result, of the
+// exchange buffer, of k_f and of the twiddle tables holds digit big_tau<N2>(m).  With 32 values (fft 32768) it is
+// the order above, so that the low-pass set of the digit -- the values nearest the two ends of its range, see
+// fftconv_filter_fft_sparse_digits -- falls into tile 0 and the HALF2 kernels can leave tile 1 out: its stage-2
+// rows, its columns of stage 3 and of the inverse stage 3, its share of the inverse stage-2 contraction, its k_f
+// and twiddles (Appendix A.4: sparsity in the second dimension of k_f).  With 16 values there is one tile.
+template <int N2> __host__ __device__ inline int big_tau(int m) { return N2 == 32 ? big_sigma(m) : m; }
 
 // The constant block of a plan, one allocation (byte offsets in BigGeo):
 //   tab1   [ct][part][lane] uint4                  W_32^{n1 k1}, n1 < 16
 //   tab1i  [K step][part][lane]                    conj(W_32^{k1 n1}), n1 < 16
 //   tab3   [K step][tile][part][lane]              W_32^{n3 k3}, both digits in the order big_sigma()
-//   tab2   [n3][K step][tile][part][lane]          W_N2^{n2 k2} W_{32 N2}^{k2 n3}
-//   tab2i  [k1][K step][tile][part][lane]          conj(W_N2^{k2 n2} W_{32 N2}^{k1 n2})
+//   tab2   [n3][K step][tile][part][lane]          W_N2^{n2 k2} W_{32 N2}^{k2 n3}, k2 in the order big_tau()
+//   tab2i  [k1][K step][tile][part][lane]          conj(W_N2^{k2 n2} W_{32 N2}^{k1 n2}), likewise
 //   twa    [n3][rt][ct][r][lane] 4-byte constants  W_M^{k1 (32 n2 + n3)}
 //   twb    [k1][ct2][ct3][r][lane]                 W_M^{(k1 + 32 k2) n3}, used as conj(z * w)
 // The kernel reads it, and k_f, through buffer descriptors: a load is then "descriptor + scalar
@@ -97,21 +104,28 @@ __host__ __device__ inline int big_sigma_inv(int d)
 #define SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
 
 // FULL: B even and N == fft_size / 2, every access of a work item is in range.
-// HALF3: k_f is zero wherever k3 is in tile 1 of the order above.
+// SP (frequency-sparse filters, Appendix A.4), a set of bits:
+//   1 (HALF3): k_f is zero wherever k3 is in tile 1 of the order big_sigma();
+//   2 (HALF2, N2 = 32): k_f is zero wherever k2 is in tile 1 of the order big_tau();
+//   4 (SKIP1): bit k1 of live_k1 clear = k_f is zero on the whole plane k1: phase B writes zeros for it and
+//      neither loads its tables nor computes (the trip count of the per-plane loop).
 // GATED (gated form y = v . ((u . w) * k), Section 3.1 / 4.1): wg multiplies u as its chunks go into the
 // staging area, vg multiplies y as its chunks leave it (either may be null); the gates are fetched with the
 // next pair's input, right after phase B.  One workgroup per compute unit then (the extra chunks need registers).
-template <typename TT, bool FULL, int N2, bool HALF3, bool GATED = false>
+template <typename TT, bool FULL, int N2, int SP, bool GATED = false>
 __global__ void __launch_bounds__(NT, (N2 == 16 && !GATED) ? 4 : 2) k_fused3_big(const uint16_t *__restrict__ u, uint16_t *__restrict__ y,
                                                   const void *__restrict__ kf, const void *__restrict__ consts,
                                                   uint32_t kf_bytes, int B, int H, int N,
                                                   const uint16_t *__restrict__ wg, const uint16_t *__restrict__ vg,
-                                                  LaunchGate gate)
+                                                  uint32_t live_k1, LaunchGate gate)
 {
     using CW = typename TT::CW;
     using BG = BigGeo<N2>;
     constexpr int BPK1 = BG::PK1, BPN3 = BG::PN3, R2 = BG::R2, NCH = BG::NCH;
+    constexpr bool HALF3 = (SP & 1) != 0, HALF2 = (SP & 2) != 0, SKIP1 = (SP & 4) != 0;
+    static_assert(!HALF2 || N2 == 32, "the middle digit has a second tile only at N2 = 32");
     constexpr int T3 = HALF3 ? 1 : 2;                             // live k3 tiles
+    constexpr int T2 = HALF2 ? 1 : R2;                            // live k2 tiles
     extern __shared__ uint32_t XB[];
     if (gate_closed(gate)) return;
     const int tid = threadIdx.x, l = tid & 63, q = l >> 4, c16 = l & 15;
@@ -131,11 +145,13 @@ __global__ void __launch_bounds__(NT, (N2 == 16 && !GATED) ? 4 : 2) k_fused3_big
     // LDS base addresses of this lane, chosen so that every access below is base + a small constant
     uint32_t *const wrA = XB + 4 * w * BPN3 + c16 * BPK1 + 4 * q;         // + i*BPN3 + 16 ct*BPK1 + 16 ct2
     const uint32_t *const rdC = XB + 4 * w * BPN3 + 4 * q * BPK1 + c16;   // + i*BPN3 + (16 ks + r)*BPK1 + 16 cn2
-    // phase B addresses n3 in the order big_sigma(): slots 4q .. 4q+3 of a tile are adjacent rows
-    const uint32_t *const rdB0 = XB + big_sigma(4 * q) * BPN3 + 4 * w * BPK1 + c16;       // + r*BPN3 + i*BPK1 + 16 ct2
-    const uint32_t *const rdB1 = XB + big_sigma(16 + 4 * q) * BPN3 + 4 * w * BPK1 + c16;  // K step 1
-    uint32_t *const wrB0 = XB + big_sigma(c16) * BPN3 + 4 * w * BPK1 + 4 * q;             // + i*BPK1 + 16 cn2
-    uint32_t *const wrB1 = XB + big_sigma(16 + c16) * BPN3 + 4 * w * BPK1 + 4 * q;        // n3 tile 1
+    // phase B: wave w owns the planes k1 = w + 8 i, i < 4 (interleaved, so that a low-pass set of k1 -- its values
+    // nearest zero on the circle -- spreads over all waves when dead planes are skipped); it addresses n3 in the
+    // order big_sigma(): slots 4q .. 4q+3 of a tile are adjacent rows
+    const uint32_t *const rdB0 = XB + big_sigma(4 * q) * BPN3 + w * BPK1 + c16;       // + r*BPN3 + 8 i*BPK1 + 16 ct2
+    const uint32_t *const rdB1 = XB + big_sigma(16 + 4 * q) * BPN3 + w * BPK1 + c16;  // K step 1
+    uint32_t *const wrB0 = XB + big_sigma(c16) * BPN3 + w * BPK1 + 4 * q;             // + 8 i*BPK1 + 16 cn2
+    uint32_t *const wrB1 = XB + big_sigma(16 + c16) * BPN3 + w * BPK1 + 4 * q;        // n3 tile 1
 
     uint4 tab1[2][2], tab1i[2][2], tab3[2][2][2];
     // streamed per-plane tables, PD planes in flight (plane i lives in slot i % PD): the smaller transform
@@ -192,7 +208,7 @@ __global__ void __launch_bounds__(NT, (N2 == 16 && !GATED) ? 4 : 2) k_fused3_big
 #pragma unroll
         for (int a = 0; a < R2; ++a)
 #pragma unroll
-            for (int b = 0; b < R2; ++b)
+            for (int b = 0; b < T2; ++b)
 #pragma unroll
                 for (int p = 0; p < 2; ++p) tabA[sl][a][b][p] = ld16(rc, base, BG::OFF_TAB2 + ((a * R2 + b) * 2 + p) * 1024);
     };
@@ -207,30 +223,30 @@ __global__ void __launch_bounds__(NT, (N2 == 16 && !GATED) ? 4 : 2) k_fused3_big
                 for (int r = 0; r < 4; ++r) twaR[sl][a][b][r] = ld4(rc, base, BG::OFF_TWA + ((a * 2 + b) * 4 + r) * 256);
     };
     auto load_tabB = [&](int i) {
-        const int c = 4 * w + i, sl = i % PD;
+        const int c = w + 8 * i, sl = i % PD;
         const int base = sz + c * BG::PLANE2;
 #pragma unroll
-        for (int a = 0; a < R2; ++a)
+        for (int a = 0; a < T2; ++a)
 #pragma unroll
             for (int b = 0; b < R2; ++b)
 #pragma unroll
                 for (int p = 0; p < 2; ++p) tabB[sl][a][b][p] = ld16(rc, base, BG::OFF_TAB2I + ((a * R2 + b) * 2 + p) * 1024);
     };
     auto load_twb = [&](int i) {
-        const int c = 4 * w + i, sl = i % PD;
+        const int c = w + 8 * i, sl = i % PD;
         const int base = sz + c * BG::PLANEW;
 #pragma unroll
-        for (int a = 0; a < R2; ++a)
+        for (int a = 0; a < T2; ++a)
 #pragma unroll
             for (int b = 0; b < 2; ++b)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) twbR[sl][a][b][r] = ld4(rc, base, BG::OFF_TWB + ((a * 2 + b) * 4 + r) * 256);
     };
     auto load_kf = [&](int i, int h) {
-        const int c = 4 * w + i, sl = i % PD;
+        const int c = w + 8 * i, sl = i % PD;
         const int base = sz + (h * 32 + c) * BG::PLANEW;
 #pragma unroll
-        for (int a = 0; a < R2; ++a)
+        for (int a = 0; a < T2; ++a)
 #pragma unroll
             for (int b = 0; b < T3; ++b)
 #pragma unroll
@@ -347,7 +363,7 @@ __global__ void __launch_bounds__(NT, (N2 == 16 && !GATED) ? 4 : 2) k_fused3_big
 #pragma unroll
             for (int ct = 0; ct < 2; ++ct)
 #pragma unroll
-                for (int ct2 = 0; ct2 < R2; ++ct2) {
+                for (int ct2 = 0; ct2 < T2; ++ct2) {      // (a dead k2 tile is neither computed nor written: nobody reads it)
                     f32x4 dre = zero4, dim = zero4;
 #pragma unroll
                     for (int ks = 0; ks < R2; ++ks) {     // matrix as the A operand: rows k2, data columns k1
@@ -439,25 +455,42 @@ __global__ void __launch_bounds__(NT, (N2 == 16 && !GATED) ? 4 : 2) k_fused3_big
         }
     };
 
-    // ---- phase B of one pair: per k1 plane (4 per wave): stage 3, k_f, inverse 3, twiddle,
-    // inverse 2, in place.  On entry tab3, kfR, twbR, tabB hold plane 0's tables.
-    auto phase_B = [&](int h, [[maybe_unused]] int it) {
+    // ---- phase B of one pair: per k1 plane (4 per wave: k1 = w + 8 i): stage 3, k_f, inverse 3, twiddle,
+    // inverse 2, in place.  On entry tab3 and, if plane 0 is live, kfR, twbR, tabB of plane 0 are loaded.
+    auto plane_live = [&](int i) { return !SKIP1 || ((live_k1 >> (w + 8 * i)) & 1u) != 0; };      // wave-uniform
+    auto phase_B = [&](int h) {
         auto read_plane = [&](int i, uint4 (&x)[R2][2]) {
 #pragma unroll
-            for (int ct2 = 0; ct2 < R2; ++ct2)
+            for (int ct2 = 0; ct2 < T2; ++ct2)
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks) {
-                    const uint32_t *src = (ks ? rdB1 : rdB0) + i * BPK1 + 16 * ct2;
+                    const uint32_t *src = (ks ? rdB1 : rdB0) + 8 * i * BPK1 + 16 * ct2;
                     x[ct2][ks] = make_uint4(src[0], src[BPN3], src[2 * BPN3], src[3 * BPN3]);
                 }
         };
         uint4 x3[R2][2];                                  // [k2 tile][K step = n3 tile]
-        read_plane(0, x3);
+        if (plane_live(0)) read_plane(0, x3);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
+            const bool next = i + PD < 4 && plane_live(i + PD);
+            if (!plane_live(i)) {
+                // k_f is zero on this plane: so is the plane's result; the next live plane's tables are requested here
+#pragma unroll
+                for (int cn3 = 0; cn3 < 2; ++cn3)
+#pragma unroll
+                    for (int cn2 = 0; cn2 < R2; ++cn2)
+                        *(uint4 *)((cn3 ? wrB1 : wrB0) + 8 * i * BPK1 + 16 * cn2) = make_uint4(0, 0, 0, 0);
+                if (next) {
+                    load_kf(i + PD, h);
+                    load_twb(i + PD);
+                    load_tabB(i + PD);
+                    read_plane(i + 1, x3);
+                }
+                continue;
+            }
             uint4 x3i[R2][2];                             // [k2 tile][K step = k3 tile], holds conj(A3 k_f)
 #pragma unroll
-            for (int ct2 = 0; ct2 < R2; ++ct2)
+            for (int ct2 = 0; ct2 < T2; ++ct2)
 #pragma unroll
                 for (int ct3 = 0; ct3 < T3; ++ct3) {
                     f32x4 dre = zero4, dim = zero4;
@@ -466,16 +499,16 @@ __global__ void __launch_bounds__(NT, (N2 == 16 && !GATED) ? 4 : 2) k_fused3_big
                         dre = TT::mfma(tab3[ks][ct3][0], x3[ct2][ks], dre);
                         dim = TT::mfma(tab3[ks][ct3][1], x3[ct2][ks], dim);
                     }
-                    // lane: k2 = 16 ct2 + c16; reg r: k3 = big_sigma(16 ct3 + 4q + r)
+                    // lane: k2 = big_tau(16 ct2 + c16); reg r: k3 = big_sigma(16 ct3 + 4q + r)
                     x3i[ct2][ct3] = TT::template ctw4<true>(dre, dim, kfR[i % PD][ct2][ct3]);
                 }
             SCHED_FENCE();
-            if (i + PD < 4) load_kf(i + PD, h);
-            if (i + 1 < 4) read_plane(i + 1, x3);         // its latency hides behind the rest of this plane
+            if (next) load_kf(i + PD, h);
+            if (i + 1 < 4 && plane_live(i + 1)) read_plane(i + 1, x3);   // its latency hides behind the rest of this plane
             SCHED_FENCE();
             uint4 x2i[2][R2];                             // [n3 tile][K step = k2 tile]
 #pragma unroll
-            for (int ct2 = 0; ct2 < R2; ++ct2)
+            for (int ct2 = 0; ct2 < T2; ++ct2)
 #pragma unroll
                 for (int cn3 = 0; cn3 < 2; ++cn3) {
                     f32x4 dre = zero4, dim = zero4;
@@ -484,11 +517,11 @@ __global__ void __launch_bounds__(NT, (N2 == 16 && !GATED) ? 4 : 2) k_fused3_big
                         dre = TT::mfma(x3i[ct2][ks], tab3[ks][cn3][0], dre);
                         dim = TT::mfma(x3i[ct2][ks], tab3[ks][cn3][1], dim);
                     }
-                    // = conj of the inverse transform.  lane: n3 = big_sigma(16 cn3 + c16); reg r: k2 = 16 ct2 + 4q + r
+                    // = conj of the inverse transform.  lane: n3 = big_sigma(16 cn3 + c16); reg r: k2 = big_tau(16 ct2 + 4q + r)
                     x2i[cn3][ct2] = TT::template ctw4<true>(dre, dim, twbR[i % PD][ct2][cn3]);
                 }
             SCHED_FENCE();
-            if (i + PD < 4) load_twb(i + PD);
+            if (next) load_twb(i + PD);
             SCHED_FENCE();
 #pragma unroll
             for (int cn3 = 0; cn3 < 2; ++cn3)
@@ -496,19 +529,29 @@ __global__ void __launch_bounds__(NT, (N2 == 16 && !GATED) ? 4 : 2) k_fused3_big
                 for (int cn2 = 0; cn2 < R2; ++cn2) {
                     f32x4 dre = zero4, dim = zero4;
 #pragma unroll
-                    for (int ks = 0; ks < R2; ++ks) {     // matrix as the A operand: rows n2, data columns n3
+                    for (int ks = 0; ks < T2; ++ks) {     // matrix as the A operand: rows n2, data columns n3; K = live k2 tiles
                         dre = TT::mfma(tabB[i % PD][ks][cn2][0], x2i[cn3][ks], dre);
                         dim = TT::mfma(tabB[i % PD][ks][cn2][1], x2i[cn3][ks], dim);
                     }
                     // lane: n3 = 16 cn3 + c16; reg r: n2 = 16 cn2 + 4q + r -> one 16-byte write
-                    uint32_t *dst = (cn3 ? wrB1 : wrB0) + i * BPK1 + 16 * cn2;
+                    uint32_t *dst = (cn3 ? wrB1 : wrB0) + 8 * i * BPK1 + 16 * cn2;
                     *(uint4 *)dst = make_uint4(TT::pack(dre[0], dim[0]), TT::pack(dre[1], dim[1]),
                                                TT::pack(dre[2], dim[2]), TT::pack(dre[3], dim[3]));
                 }
             SCHED_FENCE();
-            if (i + PD < 4) load_tabB(i + PD);
+            if (next) load_tabB(i + PD);
             SCHED_FENCE();
         }
+    };
+    // tables of the first plane of phase B for channel h (nothing if that plane is dead)
+    auto load_plane0 = [&](int h) {
+#pragma unroll
+        for (int i = 0; i < PD; ++i)
+            if (plane_live(i)) {
+                load_kf(i, h);
+                load_twb(i);
+                load_tabB(i);
+            }
     };
 
     // ---- prologue: phase A of the first pair
@@ -527,25 +570,18 @@ __global__ void __launch_bounds__(NT, (N2 == 16 && !GATED) ? 4 : 2) k_fused3_big
     phase_A();
     SCHED_FENCE();
     load_tab3();
-#pragma unroll
-    for (int i = 0; i < PD; ++i) {
-        load_kf(i, item(jb) / npairs);
-        load_twb(i);
-        load_tabB(i);
-    }
+    load_plane0(item(jb) / npairs);
     SCHED_FENCE();
     lds_barrier();
 
     // Per pair, 5 workgroup barriers:
     //   [B(t)] | [C(t) -> registers] | [y(t), u(t+1) -> staging] | [staging -> registers] | [A(t+1); store y(t)] |
-    [[maybe_unused]] int it = -1;
     for (int v = jb; v < n_local; v += nb) {
-        ++it;
         opaque();
         // Past the end of the range the last pair is prepared once more (in range, never used):
         // the loop body stays free of branches.
         const int t = item(v), tn = v + nb < n_local ? item(v + nb) : t;
-        phase_B(t / npairs, it);
+        phase_B(t / npairs);
         SCHED_FENCE();
         // tables of the next phase and the next pair's input: in flight across the barrier and phase C
         load_fixed_outer();
@@ -569,12 +605,7 @@ __global__ void __launch_bounds__(NT, (N2 == 16 && !GATED) ? 4 : 2) k_fused3_big
         phase_A();
         SCHED_FENCE();
         load_tab3();
-#pragma unroll
-        for (int i = 0; i < PD; ++i) {
-            load_kf(i, tn / npairs);
-            load_twb(i);
-            load_tabB(i);
-        }
+        load_plane0(tn / npairs);
         SCHED_FENCE();
         // the stores go last: loads and stores retire through one counter on this target, and
         // nothing issued after them is waited for before the next barrier
@@ -877,7 +908,7 @@ __global__ void __launch_bounds__(DK_BLK_THREADS) k_big_dk_blocks(const float2 *
     for (int i = threadIdx.x; i < BLK; i += DK_BLK_THREADS) {
         const int k1 = d0 + 16 * (i / RUN), j = i % RUN;                       // slot (k1, j) of dk_f[h]
         const int lane = j % 64, r = (j / 64) % 4, t3 = (j / 256) % 2, t2 = (j / 512) % R2;
-        const int k2 = 16 * t2 + lane % 16, k3 = big_sigma(16 * t3 + 4 * (lane / 16) + r);
+        const int k2 = big_tau<N2>(16 * t2 + lane % 16), k3 = big_sigma(16 * t3 + 4 * (lane / 16) + r);
         const int f = k1 + 32 * k2 + 32 * N2 * k3;
         XS[lds_slot(lds_pos(f, fl, BM) - d0 * BLK)] = dkf[h * BM + k1 * RUN + j];
     }
@@ -911,7 +942,7 @@ __global__ void k_big_dk_last(const float2 *__restrict__ tmp, float *__restrict_
 // out: with Z = FFT(z), E = (Z[f] + conj Z[M/2 - f]) / 2 and O = (Z[f] - conj Z[M/2 - f]) / (2i) are the spectra
 // of the even and odd taps, K[f] = E + W_M^f O for f < M/2, K[M/2] = Re Z[0] - Im Z[0], K[M - f] = conj K[f].
 // k_f in the kernel's per-lane order: [h][k1][k2 tile][k3 tile][r][lane]; the lane holds
-// k2 = 16 tile + lane%16 and k3 = big_sigma(16 tile + 4 (lane/16) + r).  Scaled by 1/M.
+// k2 = big_tau(16 tile + lane%16) and k3 = big_sigma(16 tile + 4 (lane/16) + r).  Scaled by 1/M.
 // w: W_M^t, t < M.  flh: factors of the half-length transform.  conj_out: the adjoint filter transform.
 constexpr int BIG_FILT_THREADS = 512;
 template <typename TT, int N2>
@@ -930,7 +961,7 @@ __global__ void __launch_bounds__(BIG_FILT_THREADS) k_filter_big(const float *__
     lds_forward(ZF, w, flh, MH, 2);
     for (int d = threadIdx.x; d < BM; d += BIG_FILT_THREADS) {
         const int lane = d % 64, r = (d / 64) % 4, t3 = (d / 256) % 2, t2 = (d / 512) % R2, k1 = d / (512 * R2);
-        const int k2 = 16 * t2 + lane % 16, k3 = big_sigma(16 * t3 + 4 * (lane / 16) + r);
+        const int k2 = big_tau<N2>(16 * t2 + lane % 16), k3 = big_sigma(16 * t3 + 4 * (lane / 16) + r);
         const int f = k1 + 32 * k2 + 32 * N2 * k3;
         const int fe = f <= MH ? f : BM - f;              // K[f] = conj K[M - f]
         float2 v;
@@ -999,12 +1030,12 @@ template <typename Fn> void fill_op(uint16_t *dst, bool f16, int t, int ct, int 
     }
 }
 
-template <typename TT, bool FULL, int N2, bool HALF3, bool GATED = false>
+template <typename TT, bool FULL, int N2, int SP, bool GATED = false>
 int launch_big(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, hipStream_t s,
-               const void *wg = nullptr, const void *vg = nullptr)
+               const void *wg = nullptr, const void *vg = nullptr, uint32_t live_k1 = 0xffffffffu)
 {
     using BG = BigGeo<N2>;
-    auto kern = k_fused3_big<TT, FULL, N2, HALF3, GATED>;
+    auto kern = k_fused3_big<TT, FULL, N2, SP, GATED>;
     FC_TRY(raise_dynamic_lds((const void *)kern, (int)BG::LDS_BYTES));
     const int64_t T = p->H * ((B + 1) / 2);
     const int64_t kf_bytes = p->H * BG::M * 4;
@@ -1024,7 +1055,7 @@ int launch_big(const fftconv_plan *p, const void *u, const void *kf, void *y, in
     if (grid >= 8) grid -= grid % 8;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NT), BG::LDS_BYTES, s, (const uint16_t *)u, (uint16_t *)y,
                        kf, (const void *)p->f3.consts, (uint32_t)kf_bytes, (int)B, (int)p->H, (int)p->N,
-                       (const uint16_t *)wg, (const uint16_t *)vg, launch_gate());
+                       (const uint16_t *)wg, (const uint16_t *)vg, live_k1, launch_gate());
     FC_HIP(hipGetLastError());
     return FFTCONV_OK;
 }
@@ -1053,14 +1084,16 @@ template <int N2> int big_init_t(fftconv_plan *p)
         for (int ks = 0; ks < R2; ++ks)
             for (int ct = 0; ct < R2; ++ct)
                 for (int part = 0; part < 2; ++part)
-                    fill_op(next(), f16, ks, ct, part, [&](int n2, int k2) {
+                    fill_op(next(), f16, ks, ct, part, [&](int n2, int m2) {       // row slot m2 holds digit k2
+                        const int k2 = big_tau<N2>(m2);
                         return cm(wp(N2, (int64_t)n2 * k2), wp(32 * N2, (int64_t)k2 * n3));
                     });
     for (int k1 = 0; k1 < 32; ++k1)                       // tab2i
         for (int ks = 0; ks < R2; ++ks)
             for (int ct = 0; ct < R2; ++ct)
                 for (int part = 0; part < 2; ++part)
-                    fill_op(next(), f16, ks, ct, part, [&](int k2, int n2) {
+                    fill_op(next(), f16, ks, ct, part, [&](int m2, int n2) {       // contraction slot m2 holds digit k2
+                        const int k2 = big_tau<N2>(m2);
                         return cj(cm(wp(N2, (int64_t)n2 * k2), wp(32 * N2, (int64_t)k1 * n2)));
                     });
     if (o != BG::U4) {
@@ -1087,7 +1120,7 @@ template <int N2> int big_init_t(fftconv_plan *p)
             for (int ct3 = 0; ct3 < 2; ++ct3)
                 for (int r = 0; r < 4; ++r)
                     for (int lane = 0; lane < 64; ++lane) {
-                        const int n3 = big_sigma(16 * ct3 + lane % 16), k2 = 16 * ct2 + 4 * (lane / 16) + r;
+                        const int n3 = big_sigma(16 * ct3 + lane % 16), k2 = big_tau<N2>(16 * ct2 + 4 * (lane / 16) + r);
                         put(e++, wp(M, ((int64_t)k1 + 32 * (int64_t)k2) * n3), true);
                     }
     const size_t bytes = BG::U4 * 16 + tw.size() * 4;
@@ -1112,19 +1145,35 @@ int big_filter_tt(const fftconv_plan *p, const float *k, int64_t Nk, bool adjoin
     return FFTCONV_OK;
 }
 
-template <typename TT, int N2, bool HALF3>
-int big_forward_tt(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, hipStream_t s)
+template <typename TT, int N2, int SP>
+int big_forward_tt(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, uint32_t live_k1, hipStream_t s)
 {
     const bool full = (B % 2 == 0) && p->N == BigGeo<N2>::M / 2;
-    return full ? launch_big<TT, true, N2, HALF3>(p, u, kf, y, B, s) : launch_big<TT, false, N2, HALF3>(p, u, kf, y, B, s);
+    return full ? launch_big<TT, true, N2, SP>(p, u, kf, y, B, s, nullptr, nullptr, live_k1)
+                : launch_big<TT, false, N2, SP>(p, u, kf, y, B, s, nullptr, nullptr, live_k1);
 }
 
-template <int N2>
-int big_forward_t(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, bool half3, hipStream_t s)
+// sp: bit 0 = the k3 tile 1 is empty, bit 1 = the k2 tile 1 is empty (N2 = 32), bit 2 = some k1 planes are empty
+template <typename TT, int N2>
+int big_forward_sp(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, int sp, uint32_t live_k1,
+                   hipStream_t s)
 {
-    if (p->dtype == FFTCONV_F16)
-        return half3 ? big_forward_tt<H16, N2, true>(p, u, kf, y, B, s) : big_forward_tt<H16, N2, false>(p, u, kf, y, B, s);
-    return half3 ? big_forward_tt<B16, N2, true>(p, u, kf, y, B, s) : big_forward_tt<B16, N2, false>(p, u, kf, y, B, s);
+    switch (sp) {
+    case 1: return big_forward_tt<TT, N2, 1>(p, u, kf, y, B, live_k1, s);
+    case 4: return big_forward_tt<TT, N2, 4>(p, u, kf, y, B, live_k1, s);
+    case 5: return big_forward_tt<TT, N2, 5>(p, u, kf, y, B, live_k1, s);
+    default: break;
+    }
+    if constexpr (N2 == 32) {
+        switch (sp) {
+        case 2: return big_forward_tt<TT, N2, 2>(p, u, kf, y, B, live_k1, s);
+        case 3: return big_forward_tt<TT, N2, 3>(p, u, kf, y, B, live_k1, s);
+        case 6: return big_forward_tt<TT, N2, 6>(p, u, kf, y, B, live_k1, s);
+        case 7: return big_forward_tt<TT, N2, 7>(p, u, kf, y, B, live_k1, s);
+        default: break;
+        }
+    }
+    return big_forward_tt<TT, N2, 0>(p, u, kf, y, B, live_k1, s);
 }
 
 }  // namespace
@@ -1148,19 +1197,25 @@ int fused3_big_filter(const fftconv_plan *p, const float *k, int64_t Nk, bool ad
                : big_filter_tt<B16, 16>(p, k, Nk, adjoint, keep_dev, n_blocks, kf, s);
 }
 
-// live_k3: bit d set when the digit k3 = d of the frequency (the most significant one, 32 values)
+// live_k3, live_k2, live_k1: bit d set when the value d of that digit of the frequency f = k1 + 32 k2 + 32 N2 k3
 // may meet a non-zero bin of k_f; all ones for a dense filter.
 int fused3_big_forward(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, uint32_t live_k3,
-                       hipStream_t s)
+                       hipStream_t s, uint32_t live_k2, uint32_t live_k1)
 {
     if (((uintptr_t)u | (uintptr_t)y) & 15) {
         set_error("fftconv_forward: u and y must be 16-byte aligned for this plan");
         return FFTCONV_EINVAL;
     }
-    bool half3 = true;                                    // no live digit in tile 1 of the kernel's order
-    for (int d = 0; d < 32; ++d)
-        if (((live_k3 >> d) & 1u) && big_sigma_inv(d) >= 16) half3 = false;
-    return p->M == 32768 ? big_forward_t<32>(p, u, kf, y, B, half3, s) : big_forward_t<16>(p, u, kf, y, B, half3, s);
+    int sp = 3;                                           // no live digit in tile 1 of the kernel's orders
+    for (int d = 0; d < 32; ++d) {
+        if (((live_k3 >> d) & 1u) && big_sigma_inv(d) >= 16) sp &= ~1;
+        if (p->M != 32768 || (((live_k2 >> d) & 1u) && big_sigma_inv(d) >= 16)) sp &= ~2;
+    }
+    if (live_k1 != 0xffffffffu) sp |= 4;
+    const bool f16 = p->dtype == FFTCONV_F16;
+    if (p->M == 32768)
+        return f16 ? big_forward_sp<H16, 32>(p, u, kf, y, B, sp, live_k1, s) : big_forward_sp<B16, 32>(p, u, kf, y, B, sp, live_k1, s);
+    return f16 ? big_forward_sp<H16, 16>(p, u, kf, y, B, sp, live_k1, s) : big_forward_sp<B16, 16>(p, u, kf, y, B, sp, live_k1, s);
 }
 
 // Gated form: wg / vg (same shape and dtype as u; either may be null) are applied inside the kernel.
@@ -1175,17 +1230,17 @@ int fused3_big_forward_gated(const fftconv_plan *p, const void *u, const void *w
     if (p->M == 32768) {
         const bool full = (B % 2 == 0) && p->N == BigGeo<32>::M / 2;
         if (f16)
-            return full ? launch_big<H16, true, 32, false, true>(p, u, kf, y, B, s, wg, vg)
-                        : launch_big<H16, false, 32, false, true>(p, u, kf, y, B, s, wg, vg);
-        return full ? launch_big<B16, true, 32, false, true>(p, u, kf, y, B, s, wg, vg)
-                    : launch_big<B16, false, 32, false, true>(p, u, kf, y, B, s, wg, vg);
+            return full ? launch_big<H16, true, 32, 0, true>(p, u, kf, y, B, s, wg, vg)
+                        : launch_big<H16, false, 32, 0, true>(p, u, kf, y, B, s, wg, vg);
+        return full ? launch_big<B16, true, 32, 0, true>(p, u, kf, y, B, s, wg, vg)
+                    : launch_big<B16, false, 32, 0, true>(p, u, kf, y, B, s, wg, vg);
     }
     const bool full = (B % 2 == 0) && p->N == BigGeo<16>::M / 2;
     if (f16)
-        return full ? launch_big<H16, true, 16, false, true>(p, u, kf, y, B, s, wg, vg)
-                    : launch_big<H16, false, 16, false, true>(p, u, kf, y, B, s, wg, vg);
-    return full ? launch_big<B16, true, 16, false, true>(p, u, kf, y, B, s, wg, vg)
-                : launch_big<B16, false, 16, false, true>(p, u, kf, y, B, s, wg, vg);
+        return full ? launch_big<H16, true, 16, 0, true>(p, u, kf, y, B, s, wg, vg)
+                    : launch_big<H16, false, 16, 0, true>(p, u, kf, y, B, s, wg, vg);
+    return full ? launch_big<B16, true, 16, 0, true>(p, u, kf, y, B, s, wg, vg)
+                : launch_big<B16, false, 16, 0, true>(p, u, kf, y, B, s, wg, vg);
 }
 
 bool fused3_big_dk_supported(const fftconv_plan *p) { return p->path == PATH_FUSED3 && (p->M == 16384 || p->M == 32768); }

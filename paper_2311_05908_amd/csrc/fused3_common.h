@@ -355,7 +355,7 @@ size_t fused3_big_kf_bytes(const fftconv_plan *p);
 int fused3_big_filter(const fftconv_plan *p, const float *k, int64_t Nk, bool adjoint, const uint8_t *keep_dev,
                       int64_t n_blocks, void *kf, hipStream_t s);
 int fused3_big_forward(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, uint32_t live_k3,
-                       hipStream_t s);
+                       hipStream_t s, uint32_t live_k2 = 0xffffffffu, uint32_t live_k1 = 0xffffffffu);
 int fused3_big_forward_gated(const fftconv_plan *p, const void *u, const void *wg, const void *vg, const void *kf, void *y,
                              int64_t B, hipStream_t s);
 

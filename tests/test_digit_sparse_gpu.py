@@ -43,6 +43,12 @@ def run(dtype, B, H, N, M, digit_keep):
     ("bf16", 4, 2, 8192, 16384, (32, 16, 8)),       # the empty tile of the innermost digit is skipped
     ("bf16", 2, 2, 8192, 16384, (10, 16, 16)),
     ("f16", 2, 1, 16384, 32768, (16, 16, 16)),
+    ("f16", 2, 1, 16384, 32768, (32, 15, 32)),      # middle digit: its second tile is left out of stages 2 and 3
+    ("bf16", 3, 2, 16384, 32768, (8, 15, 15)),      # all three at once: planes, k2 tile, k3 tile
+    ("bf16", 2, 2, 16384, 32768, (8, 32, 32)),      # k1 planes only: one live plane per wave
+    ("bf16", 4, 2, 8192, 16384, (8, 16, 32)),       # the same at fft 16384
+    ("f16", 3, 2, 8192, 16384, (5, 16, 10)),        # planes and the k3 tile
+    ("bf16", 2, 1, 8192, 16384, (1, 1, 1)),         # a single live plane in the whole workgroup
     ("bf16", 1, 1, 32768, 65536, (4, 32, 16, 16)),  # outer digit: rows of the inner kernel that are never touched
     ("f16", 2, 1, 32768, 65536, (3, 8, 16, 8)),
     ("bf16", 2, 2, 8192, 8192, (1, 32, 16, 4)),     # circular, multi-pass route without an outer transform
