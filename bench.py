@@ -187,6 +187,9 @@ def main():
     ap.add_argument("--digit-keep", default=None,
                     help="comma-separated kept values per digit of the plan's factorisation (Appendix A.4 cut-off "
                          "pattern): time fftconv_forward_freq_sparse_digits against the dense call on the same k_f")
+    ap.add_argument("--lean", action="store_true",
+                    help="warm-up and timed steps only (no cold figure, settle phase, per-launch events or power "
+                         "sampling): the form the counter-collecting rocprofv3 runs use")
     ap.add_argument("--constants", action="store_true",
                     help="measure the machine constants of the cost model (Section 3.2, Appendix C) with the library's "
                          "micro-benchmark kernels and print them beside the built-in preset (not the headline metric)")
@@ -323,14 +326,14 @@ def main():
 
     # The same protocol on a cold chip first (warm-up, then the timed steps): with a few steps the core
     # clock is still ramping up from idle and the figure is slower; reported as config.ms_per_step_cold.
-    for _ in range(args.warmup):
+    for _ in range(0 if args.lean else args.warmup):
         step()
-    ms_cold = timed(args.steps)
+    ms_cold = None if args.lean else timed(args.steps)
     # Clock-settle phase (untimed, disclosed as config.settle_ms): the same step back to back for at least
     # --settle-ms of GPU time, so that the timed region below measures the kernel at the clock the chip
     # sustains under this load, whatever --steps / --warmup are.
     settle_ms = 0.0
-    while settle_ms < args.settle_ms:
+    while not args.lean and settle_ms < args.settle_ms:
         n = max(8, int(25.0 / max(ms_cold, 1e-3)))
         settle_ms += timed(n) * n
     for _ in range(args.warmup):
@@ -351,7 +354,7 @@ def main():
     ms_per_step = e0.elapsed_time(e1) / args.steps
     assert torch.isfinite(y.float()).all(), "non-finite output"
     dense_ms = None
-    if (bk is not None or w.Nk) and not args.gated:
+    if (bk is not None or w.Nk) and not args.gated and not args.lean:
         # sparse workloads: the dense entry point on the same (masked / truncated) k_f, for the speed-up
         for _ in range(args.warmup):
             plan.forward(u, kf, out=y)
@@ -365,7 +368,7 @@ def main():
 
     # distribution over single launches: one event between consecutive launches (the marker packets
     # stretch a step by a few microseconds, which is why the headline figure uses the two-event bracket)
-    n_ev = max(2, min(args.steps, 200))
+    n_ev = 2 if args.lean else max(2, min(args.steps, 200))
     evs = [torch.cuda.Event(enable_timing=True) for _ in range(n_ev + 1)]
     torch.cuda.synchronize()
     evs[0].record()
@@ -375,7 +378,7 @@ def main():
     torch.cuda.synchronize()
     per = sorted(evs[i].elapsed_time(evs[i + 1]) for i in range(n_ev))
     per_launch = {"n": n_ev, "mean": sum(per) / n_ev, "median": per[n_ev // 2], "min": per[0], "max": per[-1]}
-    power = sustained_power(torch, step, ms_per_step)
+    power = None if args.lean else sustained_power(torch, step, ms_per_step)
     nseq = w.B * w.H
     abytes = algorithmic_bytes(w, args.gated)
     avg_kernel_ms = ms_per_step          # one kernel launch per step on the fused paths
@@ -403,7 +406,7 @@ def main():
                    "achieved_TBps": achieved / 1e3, "wall_ms_per_step": t_wall / args.steps * 1e3,
                    "input_gen_s": t_gen,
                    "settle_ms": settle_ms, "ms_per_step_cold": ms_cold,
-                   "sequences_per_ms_cold": nseq / ms_cold,
+                   "sequences_per_ms_cold": None if ms_cold is None else nseq / ms_cold,
                    "per_launch_ms": per_launch,
                    "power": power,
                    "dense_ms_per_step": dense_ms,

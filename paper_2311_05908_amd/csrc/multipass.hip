@@ -390,6 +390,193 @@ __global__ void __launch_bounds__(TB, 4) k_outer_inv(const uint32_t *__restrict_
     }
 }
 
+// ---- the outer passes of a LONE real row (B = 1, or the last row of an odd batch): two adjacent columns of
+// the real row share one complex outer transform, z[no] = x[no, c] + i x[no, c+1] (Appendix A.1's point that a
+// real transform costs half a complex one, taken on the column pairs of the outer factor), and only the
+// outer frequencies ko <= No/2 are kept (the others are their conjugates, see multipass_forward).
+//   pass A:  Z = DFT_No(z);  X_c[ko] = (Z[ko] + conj Z[No-ko]) / 2,  X_{c+1}[ko] = (Z[ko] - conj Z[No-ko]) / (2i);
+//            S[ko, r] = W_M^{r ko} X_r[ko] for ko <= No/2.
+//   pass C:  U_r[ko] = conj(W_M^{r ko}) S[ko, r] (ko <= No/2), U_r[ko] = conj(U_r[No-ko]) (ko > No/2);
+//            z = IDFT_No(U_c + i U_{c+1}): its real part is column c of y, its imaginary part column c+1.
+// One block = 2 CG consecutive columns of one channel, T[No][CG] in LDS; a 16-bit pair of adjacent samples
+// is one 32-bit word, so a wave moves whole 128-byte lines of u and y.
+template <bool F16, int RA, int RB, bool FULLN, bool GATED>
+__global__ void __launch_bounds__(TB, 4) k_outer_fwd_real(const uint16_t *__restrict__ u, uint32_t *__restrict__ S, int CG,
+                                                      int H, int N, int64_t M, const uint16_t *__restrict__ wg,
+                                                      LaunchGate gate)
+{
+    extern __shared__ float2 sm[];
+    if (gate_closed(gate)) return;
+    constexpr int No = RA * RB;
+    constexpr int RAIN = FULLN ? RA : RA / 2;      // outer rows that can hold input
+    float2 *wno = sm;                              // W_No^j, j < No
+    float2 *T = sm + No;                           // [No][CG]
+    const int tid = threadIdx.x;
+    const int r0 = blockIdx.x * 2 * CG;
+    const int h = blockIdx.y;
+    const uint16_t *row0 = u + (size_t)h * N;
+    const uint16_t *g0 = GATED ? wg + (size_t)h * N : nullptr;
+    const bool wide = N % 2 == 0;                  // rows start 4-byte aligned
+    for (int j = tid; j < No; j += TB) wno[j] = wm(j, 2.0f / (float)No);
+    __syncthreads();
+    // step 1: length-RA transforms over a, times W_No^{ka b2}
+    for (int e = tid; e < RB * CG; e += TB) {
+        const int cg = e % CG, b2 = e / CG;
+        float2 x[RA];
+#pragma unroll
+        for (int a = 0; a < RA; ++a) {
+            x[a] = make_float2(0.f, 0.f);
+            if (a < RAIN) {
+                const int64_t n = (int64_t)(a * RB + b2) * MI + r0 + 2 * cg;
+                uint32_t wd = 0, gt = 0;
+                if (wide) {
+                    if (n < N) {
+                        wd = *(const uint32_t *)(row0 + n);
+                        if constexpr (GATED) gt = *(const uint32_t *)(g0 + n);
+                    }
+                } else {
+#pragma unroll
+                    for (int v = 0; v < 2; ++v)
+                        if (n + v < N) {
+                            wd |= (uint32_t)row0[n + v] << (16 * v);
+                            if constexpr (GATED) gt |= (uint32_t)g0[n + v] << (16 * v);
+                        }
+                }
+                if constexpr (GATED) wd = mul_pair16<F16>(wd, gt);
+                x[a] = unpack2<F16>(wd);           // (column c, column c+1) = (re, im)
+            }
+        }
+        dft_reg<RA, false>(x);
+#pragma unroll
+        for (int ka = 0; ka < RA; ++ka) T[(ka * RB + b2) * CG + cg] = cmulf(x[ka], wno[ka * b2]);
+    }
+    __syncthreads();
+    // step 2: length-RB transforms over b2, in place: slot ka*RB + kb then holds Z[ko], ko = ka + RA kb
+    for (int e = tid; e < RA * CG; e += TB) {
+        const int cg = e % CG, ka = e / CG;
+        float2 x[RB];
+#pragma unroll
+        for (int b2 = 0; b2 < RB; ++b2) x[b2] = T[(ka * RB + b2) * CG + cg];
+        dft_reg<RB, false>(x);
+#pragma unroll
+        for (int kb = 0; kb < RB; ++kb) T[(ka * RB + kb) * CG + cg] = x[kb];
+    }
+    __syncthreads();
+    // step 3: split the two columns, twiddle (by recurrence over kb), store the rows ko <= No/2
+    const float ihm = 2.0f / (float)M;
+    for (int e = tid; e < RA * CG; e += TB) {
+        const int cg = e % CG, ka = e / CG;
+        const int r = r0 + 2 * cg;
+        float2 w0 = wm((int)(((int64_t)r * ka) % M), ihm), w1 = wm((int)(((int64_t)(r + 1) * ka) % M), ihm);
+        const float2 s0 = wm((int)(((int64_t)r * RA) % M), ihm), s1 = wm((int)(((int64_t)(r + 1) * RA) % M), ihm);
+#pragma unroll
+        for (int kb = 0; kb < RB; ++kb) {
+            const int ko = ka + RA * kb;
+            if (ko <= No / 2) {
+                const int km = (No - ko) % No;
+                const float2 z = T[(ka * RB + kb) * CG + cg], zm = T[((km % RA) * RB + km / RA) * CG + cg];
+                const float2 xa = make_float2(0.5f * (z.x + zm.x), 0.5f * (z.y - zm.y));      // (Z + conj Zm) / 2
+                const float2 xb = make_float2(0.5f * (z.y + zm.y), -0.5f * (z.x - zm.x));     // (Z - conj Zm) / (2i)
+                const float2 ta = cmulf(xa, w0), tb = cmulf(xb, w1);
+                *(uint2 *)&S[((size_t)h * No + ko) * MI + r] =
+                    make_uint2((uint32_t)cv16<F16>(ta.x) | ((uint32_t)cv16<F16>(ta.y) << 16),
+                               (uint32_t)cv16<F16>(tb.x) | ((uint32_t)cv16<F16>(tb.y) << 16));
+            }
+            w0 = cmulf(w0, s0);
+            w1 = cmulf(w1, s1);
+        }
+    }
+}
+
+template <bool F16, int RA, int RB, bool FULLN, bool GATED>
+__global__ void __launch_bounds__(TB, 4) k_outer_inv_real(const uint32_t *__restrict__ S, uint16_t *__restrict__ y, int CG,
+                                                      int H, int N, int64_t M, const uint16_t *__restrict__ vg,
+                                                      LaunchGate gate)
+{
+    extern __shared__ float2 sm[];
+    if (gate_closed(gate)) return;
+    constexpr int No = RA * RB;
+    constexpr int RAIN = FULLN ? RA : RA / 2;      // outer rows that are kept
+    float2 *wno = sm;
+    float2 *T = sm + No;                           // [No][CG]
+    const int tid = threadIdx.x;
+    const int r0 = blockIdx.x * 2 * CG;
+    const int h = blockIdx.y;
+    const bool wide = N % 2 == 0;
+    for (int j = tid; j < No; j += TB) wno[j] = wm(j, 2.0f / (float)No);
+    __syncthreads();
+    const float ihm = 2.0f / (float)M;
+    constexpr float unboost = 1.0f / (float)multipass_kf_boost(F16, No);     // exact: a power of two
+    // step 1: untwiddle both columns, complete the rows ko > No/2 from their mirror rows, combine the columns
+    // into one complex sequence, length-RB inverse over kb, times conj(W_No^{ka b2})
+    for (int e = tid; e < RA * CG; e += TB) {
+        const int cg = e % CG, ka = e / CG;
+        const int r = r0 + 2 * cg;
+        uint2 in[RB];
+#pragma unroll
+        for (int kb = 0; kb < RB; ++kb) {
+            const int ko = ka + RA * kb;
+            // ko > No/2, written so that only kb == RB/2 depends on the thread
+            const bool mir = RB == 1 ? ka > RA / 2 : (kb > RB / 2 || (kb == RB / 2 && ka > 0));
+            in[kb] = *(const uint2 *)&S[((size_t)h * No + (mir ? No - ko : ko)) * MI + r];
+            if (mir) {                                        // conjugate: the imaginary part is the upper half
+                in[kb].x ^= 0x80000000u;
+                in[kb].y ^= 0x80000000u;
+            }
+        }
+        float2 w0 = wm((int)(((int64_t)r * ka) % M), ihm), w1 = wm((int)(((int64_t)(r + 1) * ka) % M), ihm);
+        const float2 s0 = wm((int)(((int64_t)r * RA) % M), ihm), s1 = wm((int)(((int64_t)(r + 1) * RA) % M), ihm);
+        w0.x *= unboost, w0.y *= unboost, w1.x *= unboost, w1.y *= unboost;
+        float2 x[RB];
+#pragma unroll
+        for (int kb = 0; kb < RB; ++kb) {
+            // from the first mirrored row on the twiddle carries the extra factor conj(W_Mi^{r}) (see k_outer_inv)
+            const bool first_mirrored = RB == 1 ? ka > RA / 2 : ((kb == RB / 2 && ka > 0) || (kb == RB / 2 + 1 && ka == 0));
+            if (first_mirrored) {
+                w0 = cmulcf(w0, wm((int)(((int64_t)r * No) % M), ihm));
+                w1 = cmulcf(w1, wm((int)(((int64_t)(r + 1) * No) % M), ihm));
+            }
+            const float2 ua = cmulcf(unpack2<F16>(in[kb].x), w0), ub = cmulcf(unpack2<F16>(in[kb].y), w1);
+            x[kb] = make_float2(ua.x - ub.y, ua.y + ub.x);               // U_c + i U_{c+1}
+            w0 = cmulf(w0, s0);
+            w1 = cmulf(w1, s1);
+        }
+        dft_reg<RB, true>(x);
+#pragma unroll
+        for (int b2 = 0; b2 < RB; ++b2) T[(ka * RB + b2) * CG + cg] = cmulcf(x[b2], wno[ka * b2]);
+    }
+    __syncthreads();
+    // step 2: length-RA inverse over ka; real part -> column c, imaginary part -> column c+1
+    uint16_t *row0 = y + (size_t)h * N;
+    const uint16_t *g0 = GATED ? vg + (size_t)h * N : nullptr;
+    for (int e = tid; e < RB * CG; e += TB) {
+        const int cg = e % CG, b2 = e / CG;
+        float2 x[RA];
+#pragma unroll
+        for (int ka = 0; ka < RA; ++ka) x[ka] = T[(ka * RB + b2) * CG + cg];
+        dft_reg<RA, true>(x);
+#pragma unroll
+        for (int a = 0; a < RAIN; ++a) {
+            const int64_t n = (int64_t)(a * RB + b2) * MI + r0 + 2 * cg;
+            uint32_t o = (uint32_t)cv16<F16>(x[a].x) | ((uint32_t)cv16<F16>(x[a].y) << 16);
+            if (wide) {
+                if (n < N) {
+                    if constexpr (GATED) o = mul_pair16<F16>(o, *(const uint32_t *)(g0 + n));
+                    *(uint32_t *)(row0 + n) = o;
+                }
+            } else {
+#pragma unroll
+                for (int v = 0; v < 2; ++v)
+                    if (n + v < N) {
+                        uint32_t a0 = (o >> (16 * v)) & 0xffffu;
+                        if constexpr (GATED) a0 = mul_pair16<F16>(a0, g0[n + v]) & 0xffffu;
+                        row0[n + v] = (uint16_t)a0;
+                    }
+            }
+        }
+    }
+}
+
 // k_f for the multi-pass path: [h][ko][inner order of f'] 16-bit (re, im) pairs, f = ko + No*f', scaled 1/M
 // (fp16: boost/M, see multipass_kf_boost; pass C takes the boost out again).
 template <bool F16>
@@ -478,6 +665,59 @@ int dispatch_outer(bool inverse, const OuterGeo &g, dim3 grid, const void *src, 
     }
 }
 
+template <bool F16, int RA, int RB>
+int launch_outer_real(bool inverse, const OuterGeo &g, const void *src, void *dst, int H, int N, int64_t M, hipStream_t s,
+                      const void *gate)
+{
+    // a block takes 2 g.CT columns as g.CT pairs: the same tile T[No][g.CT] as the paired passes
+    const size_t lds = sizeof(float2) * ((size_t)g.No + (size_t)g.No * g.CT);
+    const dim3 grid((unsigned)(MI / (2 * g.CT)), (unsigned)H);
+    const bool fulln = (int64_t)N > M / 2;
+#define FFTCONV_REAL_LAUNCH(FULLN, GATED)                                                                                   \
+    do {                                                                                                                    \
+        if (!inverse) {                                                                                                     \
+            FC_TRY(raise_dynamic_lds((const void *)k_outer_fwd_real<F16, RA, RB, FULLN, GATED>, 160 * 1024));               \
+            hipLaunchKernelGGL((k_outer_fwd_real<F16, RA, RB, FULLN, GATED>), grid, dim3(TB), lds, s, (const uint16_t *)src, \
+                               (uint32_t *)dst, g.CT, H, N, M, (const uint16_t *)gate, launch_gate());                      \
+        } else {                                                                                                            \
+            FC_TRY(raise_dynamic_lds((const void *)k_outer_inv_real<F16, RA, RB, FULLN, GATED>, 160 * 1024));               \
+            hipLaunchKernelGGL((k_outer_inv_real<F16, RA, RB, FULLN, GATED>), grid, dim3(TB), lds, s, (const uint32_t *)src, \
+                               (uint16_t *)dst, g.CT, H, N, M, (const uint16_t *)gate, launch_gate());                      \
+        }                                                                                                                   \
+    } while (0)
+    if (fulln) {
+        if (gate) FFTCONV_REAL_LAUNCH(true, true);
+        else FFTCONV_REAL_LAUNCH(true, false);
+    } else {
+        if (gate) FFTCONV_REAL_LAUNCH(false, true);
+        else FFTCONV_REAL_LAUNCH(false, false);
+    }
+#undef FFTCONV_REAL_LAUNCH
+    FC_HIP(hipGetLastError());
+    return FFTCONV_OK;
+}
+
+// outer lengths the packed real-row passes exist for
+bool outer_real_ok(int No) { return No >= 4 && No <= 256; }
+
+template <bool F16>
+int dispatch_outer_real(bool inverse, const OuterGeo &g, const void *src, void *dst, int H, int N, int64_t M, hipStream_t s,
+                        const void *gate)
+{
+    switch (g.No) {
+    case 4: return launch_outer_real<F16, 4, 1>(inverse, g, src, dst, H, N, M, s, gate);
+    case 8: return launch_outer_real<F16, 8, 1>(inverse, g, src, dst, H, N, M, s, gate);
+    case 16: return launch_outer_real<F16, 16, 1>(inverse, g, src, dst, H, N, M, s, gate);
+    case 32: return launch_outer_real<F16, 16, 2>(inverse, g, src, dst, H, N, M, s, gate);
+    case 64: return launch_outer_real<F16, 16, 4>(inverse, g, src, dst, H, N, M, s, gate);
+    case 128: return launch_outer_real<F16, 16, 8>(inverse, g, src, dst, H, N, M, s, gate);
+    case 256: return launch_outer_real<F16, 16, 16>(inverse, g, src, dst, H, N, M, s, gate);
+    default:
+        set_error("multipass: no real-row outer pass for outer length %d", g.No);
+        return FFTCONV_EUNSUPPORTED;
+    }
+}
+
 }  // namespace
 
 bool multipass_supported(int64_t N, int64_t M, int dtype)
@@ -548,11 +788,22 @@ static int multipass_passes(const fftconv_plan *p, const void *u, const void *kf
         mirror_from = ab_lo = g.No / 2 + 1;
         ab_hi = g.No;
     }
-    int rc = f16 ? dispatch_outer<true>(false, g, grid, u, S, (int)B, (int)p->H, (int)p->N, p->M, s, ab_lo, ab_hi, g.No, wg)
+    // the lone row's outer passes pack two columns into one complex transform where such kernels exist
+    // (outer lengths 4 .. 256); at 512 the paired kernels run with the missing partner and pass C mirrors the rows
+    const bool packed = mirror_from < g.No && outer_real_ok(g.No);
+    int rc;
+    if (packed)
+        rc = f16 ? dispatch_outer_real<true>(false, g, u, S, (int)p->H, (int)p->N, p->M, s, wg)
+                 : dispatch_outer_real<false>(false, g, u, S, (int)p->H, (int)p->N, p->M, s, wg);
+    else
+        rc = f16 ? dispatch_outer<true>(false, g, grid, u, S, (int)B, (int)p->H, (int)p->N, p->M, s, ab_lo, ab_hi, g.No, wg)
                  : dispatch_outer<false>(false, g, grid, u, S, (int)B, (int)p->H, (int)p->N, p->M, s, ab_lo, ab_hi, g.No, wg);
     if (rc) return rc;
     rc = fused3_inner_rows(p, S, kf, npairs, p->H * g.No, s, g.No, ab_lo, ab_hi);
     if (rc) return rc;
+    if (packed)
+        return f16 ? dispatch_outer_real<true>(true, g, S, y, (int)p->H, (int)p->N, p->M, s, vg)
+                   : dispatch_outer_real<false>(true, g, S, y, (int)p->H, (int)p->N, p->M, s, vg);
     return f16 ? dispatch_outer<true>(true, g, grid, S, y, (int)B, (int)p->H, (int)p->N, p->M, s, c_lo, c_hi, mirror_from, vg)
                : dispatch_outer<false>(true, g, grid, S, y, (int)B, (int)p->H, (int)p->N, p->M, s, c_lo, c_hi, mirror_from, vg);
 }
