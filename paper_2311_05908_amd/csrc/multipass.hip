@@ -402,7 +402,7 @@ __global__ void __launch_bounds__(TB, 4) k_outer_inv(const uint32_t *__restrict_
 // is one 32-bit word, so a wave moves whole 128-byte lines of u and y.
 template <bool F16, int RA, int RB, bool FULLN, bool GATED>
 __global__ void __launch_bounds__(TB, 4) k_outer_fwd_real(const uint16_t *__restrict__ u, uint32_t *__restrict__ S, int CG,
-                                                      int H, int N, int64_t M, const uint16_t *__restrict__ wg,
+                                                      int H, int N, int64_t M, int ko_lo, const uint16_t *__restrict__ wg,
                                                       LaunchGate gate)
 {
     extern __shared__ float2 sm[];
@@ -472,7 +472,7 @@ __global__ void __launch_bounds__(TB, 4) k_outer_fwd_real(const uint16_t *__rest
 #pragma unroll
         for (int kb = 0; kb < RB; ++kb) {
             const int ko = ka + RA * kb;
-            if (ko <= No / 2) {
+            if (ko <= No / 2 && ko < ko_lo) {         // (rows from ko_lo on only meet zeroed bins of a sparse filter)
                 const int km = (No - ko) % No;
                 const float2 z = T[(ka * RB + kb) * CG + cg], zm = T[((km % RA) * RB + km / RA) * CG + cg];
                 const float2 xa = make_float2(0.5f * (z.x + zm.x), 0.5f * (z.y - zm.y));      // (Z + conj Zm) / 2
@@ -490,7 +490,7 @@ __global__ void __launch_bounds__(TB, 4) k_outer_fwd_real(const uint16_t *__rest
 
 template <bool F16, int RA, int RB, bool FULLN, bool GATED>
 __global__ void __launch_bounds__(TB, 4) k_outer_inv_real(const uint32_t *__restrict__ S, uint16_t *__restrict__ y, int CG,
-                                                      int H, int N, int64_t M, const uint16_t *__restrict__ vg,
+                                                      int H, int N, int64_t M, int ko_lo, const uint16_t *__restrict__ vg,
                                                       LaunchGate gate)
 {
     extern __shared__ float2 sm[];
@@ -518,7 +518,9 @@ __global__ void __launch_bounds__(TB, 4) k_outer_inv_real(const uint32_t *__rest
             const int ko = ka + RA * kb;
             // ko > No/2, written so that only kb == RB/2 depends on the thread
             const bool mir = RB == 1 ? ka > RA / 2 : (kb > RB / 2 || (kb == RB / 2 && ka > 0));
-            in[kb] = *(const uint2 *)&S[((size_t)h * No + (mir ? No - ko : ko)) * MI + r];
+            const int kr = mir ? No - ko : ko;                // the row that holds it, <= No/2
+            in[kb] = make_uint2(0, 0);                        // rows from ko_lo on: zeroed bins of a sparse filter, never written
+            if (kr < ko_lo) in[kb] = *(const uint2 *)&S[((size_t)h * No + kr) * MI + r];
             if (mir) {                                        // conjugate: the imaginary part is the upper half
                 in[kb].x ^= 0x80000000u;
                 in[kb].y ^= 0x80000000u;
@@ -667,7 +669,7 @@ int dispatch_outer(bool inverse, const OuterGeo &g, dim3 grid, const void *src, 
 
 template <bool F16, int RA, int RB>
 int launch_outer_real(bool inverse, const OuterGeo &g, const void *src, void *dst, int H, int N, int64_t M, hipStream_t s,
-                      const void *gate)
+                      int ko_lo, const void *gate)
 {
     // a block takes 2 g.CT columns as g.CT pairs: the same tile T[No][g.CT] as the paired passes
     const size_t lds = sizeof(float2) * ((size_t)g.No + (size_t)g.No * g.CT);
@@ -678,11 +680,11 @@ int launch_outer_real(bool inverse, const OuterGeo &g, const void *src, void *ds
         if (!inverse) {                                                                                                     \
             FC_TRY(raise_dynamic_lds((const void *)k_outer_fwd_real<F16, RA, RB, FULLN, GATED>, 160 * 1024));               \
             hipLaunchKernelGGL((k_outer_fwd_real<F16, RA, RB, FULLN, GATED>), grid, dim3(TB), lds, s, (const uint16_t *)src, \
-                               (uint32_t *)dst, g.CT, H, N, M, (const uint16_t *)gate, launch_gate());                      \
+                               (uint32_t *)dst, g.CT, H, N, M, ko_lo, (const uint16_t *)gate, launch_gate());               \
         } else {                                                                                                            \
             FC_TRY(raise_dynamic_lds((const void *)k_outer_inv_real<F16, RA, RB, FULLN, GATED>, 160 * 1024));               \
             hipLaunchKernelGGL((k_outer_inv_real<F16, RA, RB, FULLN, GATED>), grid, dim3(TB), lds, s, (const uint32_t *)src, \
-                               (uint16_t *)dst, g.CT, H, N, M, (const uint16_t *)gate, launch_gate());                      \
+                               (uint16_t *)dst, g.CT, H, N, M, ko_lo, (const uint16_t *)gate, launch_gate());               \
         }                                                                                                                   \
     } while (0)
     if (fulln) {
@@ -702,16 +704,16 @@ bool outer_real_ok(int No) { return No >= 4 && No <= 256; }
 
 template <bool F16>
 int dispatch_outer_real(bool inverse, const OuterGeo &g, const void *src, void *dst, int H, int N, int64_t M, hipStream_t s,
-                        const void *gate)
+                        int ko_lo, const void *gate)
 {
     switch (g.No) {
-    case 4: return launch_outer_real<F16, 4, 1>(inverse, g, src, dst, H, N, M, s, gate);
-    case 8: return launch_outer_real<F16, 8, 1>(inverse, g, src, dst, H, N, M, s, gate);
-    case 16: return launch_outer_real<F16, 16, 1>(inverse, g, src, dst, H, N, M, s, gate);
-    case 32: return launch_outer_real<F16, 16, 2>(inverse, g, src, dst, H, N, M, s, gate);
-    case 64: return launch_outer_real<F16, 16, 4>(inverse, g, src, dst, H, N, M, s, gate);
-    case 128: return launch_outer_real<F16, 16, 8>(inverse, g, src, dst, H, N, M, s, gate);
-    case 256: return launch_outer_real<F16, 16, 16>(inverse, g, src, dst, H, N, M, s, gate);
+    case 4: return launch_outer_real<F16, 4, 1>(inverse, g, src, dst, H, N, M, s, ko_lo, gate);
+    case 8: return launch_outer_real<F16, 8, 1>(inverse, g, src, dst, H, N, M, s, ko_lo, gate);
+    case 16: return launch_outer_real<F16, 16, 1>(inverse, g, src, dst, H, N, M, s, ko_lo, gate);
+    case 32: return launch_outer_real<F16, 16, 2>(inverse, g, src, dst, H, N, M, s, ko_lo, gate);
+    case 64: return launch_outer_real<F16, 16, 4>(inverse, g, src, dst, H, N, M, s, ko_lo, gate);
+    case 128: return launch_outer_real<F16, 16, 8>(inverse, g, src, dst, H, N, M, s, ko_lo, gate);
+    case 256: return launch_outer_real<F16, 16, 16>(inverse, g, src, dst, H, N, M, s, ko_lo, gate);
     default:
         set_error("multipass: no real-row outer pass for outer length %d", g.No);
         return FFTCONV_EUNSUPPORTED;
@@ -784,17 +786,22 @@ static int multipass_passes(const fftconv_plan *p, const void *u, const void *kf
     if (ko_lo >= ko_hi) ko_lo = ko_hi = g.No;            // nothing skipped
     // rows that passes A and B leave out, rows that pass C takes as zero, rows that pass C mirrors
     int ab_lo = ko_lo, ab_hi = ko_hi, c_lo = ko_lo, c_hi = ko_hi, mirror_from = g.No;
-    if (lone && g.No >= 4 && ko_lo >= ko_hi) {            // (with a sparse filter the lone row runs as a pair without partner)
+    const bool packed = lone && outer_real_ok(g.No);
+    if (packed) {
+        // a sparse filter keeps ko < ko_lo and ko >= ko_hi = No - (ko_lo - 1), mirror images of each other: of the rows
+        // ko <= No/2 those below ko_lo are live
+        ab_lo = ko_lo < g.No / 2 + 1 ? ko_lo : g.No / 2 + 1;
+        ab_hi = g.No;
+    } else if (lone && g.No >= 4 && ko_lo >= ko_hi) {     // outer length 512: paired kernels, pass C mirrors the rows
         mirror_from = ab_lo = g.No / 2 + 1;
         ab_hi = g.No;
     }
     // the lone row's outer passes pack two columns into one complex transform where such kernels exist
     // (outer lengths 4 .. 256); at 512 the paired kernels run with the missing partner and pass C mirrors the rows
-    const bool packed = mirror_from < g.No && outer_real_ok(g.No);
     int rc;
     if (packed)
-        rc = f16 ? dispatch_outer_real<true>(false, g, u, S, (int)p->H, (int)p->N, p->M, s, wg)
-                 : dispatch_outer_real<false>(false, g, u, S, (int)p->H, (int)p->N, p->M, s, wg);
+        rc = f16 ? dispatch_outer_real<true>(false, g, u, S, (int)p->H, (int)p->N, p->M, s, ab_lo, wg)
+                 : dispatch_outer_real<false>(false, g, u, S, (int)p->H, (int)p->N, p->M, s, ab_lo, wg);
     else
         rc = f16 ? dispatch_outer<true>(false, g, grid, u, S, (int)B, (int)p->H, (int)p->N, p->M, s, ab_lo, ab_hi, g.No, wg)
                  : dispatch_outer<false>(false, g, grid, u, S, (int)B, (int)p->H, (int)p->N, p->M, s, ab_lo, ab_hi, g.No, wg);
@@ -802,8 +809,8 @@ static int multipass_passes(const fftconv_plan *p, const void *u, const void *kf
     rc = fused3_inner_rows(p, S, kf, npairs, p->H * g.No, s, g.No, ab_lo, ab_hi);
     if (rc) return rc;
     if (packed)
-        return f16 ? dispatch_outer_real<true>(true, g, S, y, (int)p->H, (int)p->N, p->M, s, vg)
-                   : dispatch_outer_real<false>(true, g, S, y, (int)p->H, (int)p->N, p->M, s, vg);
+        return f16 ? dispatch_outer_real<true>(true, g, S, y, (int)p->H, (int)p->N, p->M, s, ab_lo, vg)
+                   : dispatch_outer_real<false>(true, g, S, y, (int)p->H, (int)p->N, p->M, s, ab_lo, vg);
     return f16 ? dispatch_outer<true>(true, g, grid, S, y, (int)B, (int)p->H, (int)p->N, p->M, s, c_lo, c_hi, mirror_from, vg)
                : dispatch_outer<false>(true, g, grid, S, y, (int)B, (int)p->H, (int)p->N, p->M, s, c_lo, c_hi, mirror_from, vg);
 }

@@ -51,6 +51,8 @@ def run(dtype, B, H, N, M, digit_keep):
     ("bf16", 2, 1, 8192, 16384, (1, 1, 1)),         # a single live plane in the whole workgroup
     ("bf16", 1, 1, 32768, 65536, (4, 32, 16, 16)),  # outer digit: rows of the inner kernel that are never touched
     ("f16", 2, 1, 32768, 65536, (3, 8, 16, 8)),
+    ("bf16", 3, 2, 1 << 17, 1 << 18, (9, 32, 16, 16)),   # odd batch: the last row goes through the real-row passes, sparse
+    ("f16", 1, 2, 1 << 16, 1 << 17, (16, 32, 16, 16)),   # a single row, half of the outer digit kept
     ("bf16", 2, 2, 8192, 8192, (1, 32, 16, 4)),     # circular, multi-pass route without an outer transform
     ("f32", 2, 2, 512, 1024, (16, 8)),              # short-transform kernel
     ("f32", 1, 2, 4096, 8192, (16, 16, 4, 2)),      # generic per-stage path
