@@ -142,9 +142,16 @@ def sweep(torch, fftconv, synth, dev, args):
         u = torch.randn(B, H, N, generator=g).to(torch.bfloat16).to(dev)
         y = torch.empty_like(u)
         steps = max(3, min(args.steps, 20))
-        for _ in range(3):
-            plan.forward(u, kf, out=y)
-        torch.cuda.synchronize()
+        # settle: the step back to back for about 60 ms (the core clock of an idle chip takes that long to come up)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        spun = 0.0
+        while spun < 60.0:
+            e0.record()
+            for _ in range(8):
+                plan.forward(u, kf, out=y)
+            e1.record()
+            torch.cuda.synchronize()
+            spun += e0.elapsed_time(e1)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
         for _ in range(steps):

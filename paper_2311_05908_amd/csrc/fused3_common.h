@@ -69,30 +69,19 @@ struct BF16 {
               "v"(c[2].x), "v"(c[2].y), "v"(c[3].x), "v"(c[3].y));
         return make_uint4(t0, t2, t4, t6);
     }
-    // Elementwise product of 8 bf16 values (a 16-byte chunk) with 8 others, rounded to bf16: each
-    // fp32 product comes from a dot product against the other operand with one half zeroed (exact
-    // for bf16 inputs), two of them are rounded into one word.  Same hazard rule as ctw4.
+    // Elementwise product of 8 bf16 values (a 16-byte chunk) with 8 others, rounded to bf16 (the gates of
+    // the gated form).  Each element is widened to fp32 (a shift or a mask: bf16 is the upper half of fp32),
+    // multiplied in fp32 -- exact for bf16 inputs -- and two products are rounded into one word: one rounding
+    // per element, and a NaN or an infinity stays in its own element (a dot product against a half-zeroed
+    // operand, four instructions cheaper per chunk, would turn 0 * inf of the neighbour into a NaN).
     static __device__ __forceinline__ uint4 mul8(uint4 a, uint4 b)
     {
-        const uint32_t l0 = b.x & 0xffffu, h0 = b.x & 0xffff0000u, l1 = b.y & 0xffffu, h1 = b.y & 0xffff0000u;
-        const uint32_t l2 = b.z & 0xffffu, h2 = b.z & 0xffff0000u, l3 = b.w & 0xffffu, h3 = b.w & 0xffff0000u;
-        uint32_t t0, t1, t2, t3, t4, t5, t6, t7;
-        asm("v_dot2_f32_bf16 %0, %8, %12, 0\n\t"
-            "v_dot2_f32_bf16 %1, %8, %13, 0\n\t"
-            "v_dot2_f32_bf16 %2, %9, %14, 0\n\t"
-            "v_dot2_f32_bf16 %3, %9, %15, 0\n\t"
-            "v_dot2_f32_bf16 %4, %10, %16, 0\n\t"
-            "v_dot2_f32_bf16 %5, %10, %17, 0\n\t"
-            "v_dot2_f32_bf16 %6, %11, %18, 0\n\t"
-            "v_dot2_f32_bf16 %7, %11, %19, 0\n\t"
-            DOT_SLACK "v_cvt_pk_bf16_f32 %0, %0, %1\n\t"
-            "v_cvt_pk_bf16_f32 %2, %2, %3\n\t"
-            "v_cvt_pk_bf16_f32 %4, %4, %5\n\t"
-            "v_cvt_pk_bf16_f32 %6, %6, %7"
-            : "=&v"(t0), "=&v"(t1), "=&v"(t2), "=&v"(t3), "=&v"(t4), "=&v"(t5), "=&v"(t6), "=&v"(t7)
-            : "v"(a.x), "v"(a.y), "v"(a.z), "v"(a.w), "v"(l0), "v"(h0), "v"(l1), "v"(h1), "v"(l2), "v"(h2), "v"(l3),
-              "v"(h3));
-        return make_uint4(t0, t2, t4, t6);
+        auto m = [](uint32_t x, uint32_t y) {
+            const float lo = __uint_as_float(x << 16) * __uint_as_float(y << 16);
+            const float hi = __uint_as_float(x & 0xffff0000u) * __uint_as_float(y & 0xffff0000u);
+            return pack(lo, hi);
+        };
+        return make_uint4(m(a.x, b.x), m(a.y, b.y), m(a.z, b.z), m(a.w, b.w));
     }
     static constexpr int CFMT = 1;
 };

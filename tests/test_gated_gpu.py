@@ -152,3 +152,25 @@ def test_gated_multipass(dtype, B, H, N, M):
         assert plan.path == "multipass"
         assert plan.workspace_bytes_gated(B) == plan.workspace_bytes(B)
         assert err <= TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+def test_a_non_finite_gate_value_stays_in_its_own_element(dtype):
+    """An infinity in the output gate, and a NaN in the input gate of ANOTHER sequence, reach exactly the elements
+    they belong to: y is non-finite at the position of the infinite gate value and nowhere else in that sequence,
+    every output of the sequence with the NaN input is NaN (it enters the transform), all other sequences are
+    untouched."""
+    w = synth.scaled(W["cfg2"], B=4, H=2, dtype=dtype)
+    u, gw, gv = synth.gen_u(w), synth.gen_gate(w, "w"), synth.gen_gate(w, "v")
+    gv[1, 0, 1001] = float("inf")
+    gw[2, 1, 7] = float("nan")
+    plan = fftconv.Plan(w.N, w.fft_size, w.H, w.dtype)
+    kf = plan.filter_fft(torch.from_numpy(synth.gen_k(w)).cuda())
+    y = plan.forward_gated(u.cuda(), gw.cuda(), gv.cuda(), kf).cpu().float()
+    bad = ~torch.isfinite(y)
+    assert bad[1, 0, 1001] and int(bad[1, 0].sum()) == 1
+    # rows b = 2 and b = 3 share one complex transform: the NaN spreads over that pair of channel 1 and nowhere else
+    assert bool(bad[2, 1].all())
+    bad[2:4, 1] = False
+    bad[1, 0, 1001] = False
+    assert not bool(bad.any())
