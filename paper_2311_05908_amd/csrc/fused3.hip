@@ -35,10 +35,14 @@
 //            B3 *= conj(W_M^{(k1 + N1 k2) n3})
 //            B2[k1,n2,n3] = sum_{k2} B3 conj(W_N2^{k2 n2} W_{N1 N2}^{k1 n2})  (folded)
 //            y[n1,n2,n3]  = sum_{k1} B2 conj(W_N1^{k1 n1}),  n1 < N1/2
-// Work split of a 512-thread workgroup (8 waves) on one pair:
+// Work split of a 512-thread workgroup (8 waves) on one work item:
 //   phase A (per n3):  stage 1, twiddle, stage 2      -> LDS[k1,k2,n3]
 //   phase B (per k1):  stage 3, k_f, inverse 3, twiddle, inverse 2 -> LDS in place
-//   phase C (per n3):  inverse stage 1                -> LDS staging -> HBM
+//   phase C (per n3):  inverse stage 1                -> HBM
+// This file holds what the kernels of this family share on the host side: the per-lane operand tables, the
+// filter transforms, the overlap-save route of short filters and the dispatch.  The kernels themselves:
+// fused3_ws.hip (fft 8192 and the grouped shorter transforms), fused3_wsc.hip (complex rows of length 8192,
+// the inner step of the multi-pass scheme), fused3_big.hip (fft 16384 and 32768).
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
@@ -57,486 +61,6 @@ namespace fftconv {
 namespace {
 
 using namespace f3;
-
-// CPLX = false: u, y are (B, H, N) real rows; a work item is a pair of batch rows of one channel.
-// CPLX = true : u, y are (B, H, M) rows of 16-bit (re, im) pairs (u may equal y); a work item is
-//               one row, transformed in full (no implicit zeros), circular convolution of length M.
-//               This is the inner step of the multi-pass scheme (Algorithm 4).
-// LIVE: accumulator registers r < LIVE of stage 3 may meet non-zero k_f (frequency-sparse filters
-//       ordered as in k3_at_index()); for r >= LIVE the product is zero and is not formed.
-// Row skipping (CPLX, frequency-sparse filters, Appendix A.4: the trip count of the outer loop): with
-// KoN > 0 the rows come in groups of KoN (the outer frequency digit ko) of which only ko < ko_lo and
-// ko >= ko_hi can meet a non-zero bin; H then counts the live rows only and rows_of() maps a live row to its
-// place among all rows.  The other rows are neither read nor written.
-template <int N2, int N3, typename TT, bool REGC, bool CPLX, int LIVE = 4>
-__global__ void __launch_bounds__(NT) k_fused3(const uint16_t *u, uint16_t *y,
-                                              const uint32_t *__restrict__ kf, Consts cs, int B, int H, int N,
-                                              int KoN, int ko_lo, int ko_hi, LaunchGate gate)
-{
-    using G = Geo<N2, N3>;
-    if (gate_closed(gate)) return;
-    constexpr int R2 = G::R2, R3 = G::R3, C3 = G::C3, C1 = G::C1;
-    // streamed tables are requested one tile ahead of their use when two tiles' worth fits in registers
-    constexpr bool AHEAD = !REGC && N2 == 16;
-    constexpr int KS1 = CPLX ? 2 : 1;            // K steps of forward stage 1 (n1 < 16 only when zero padded)
-    constexpr int RT1 = CPLX ? 2 : 1;            // output row tiles of inverse stage 1
-    constexpr int NCH = CPLX ? G::CHUNKS_C : G::CHUNKS;
-    extern __shared__ uint32_t smem[];
-    uint32_t *XB = smem;
-    uint16_t *UB = (uint16_t *)(smem + G::XB_WORDS);
-    uint16_t *YB = UB + (CPLX ? 2 * G::UBC_WORDS : G::UB_ELEMS);
-    uint32_t *UBC = (uint32_t *)UB, *YBC = (uint32_t *)YB;
-
-    const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, q = l >> 4, c16 = l & 15;
-    // Persistent workgroup; a work item t = h * npairs + pair.
-    //  REGC (k_f and tables in registers): a contiguous range of items, so k_f[h] is loaded once per
-    //  channel the range touches.
-    //  otherwise (k_f streamed from L2 for every item): workgroups are dealt to the 8 accelerator
-    //  dies round-robin, each die has its own L2; die x = blockIdx % 8 takes the channels
-    //  h = x mod 8 and its workgroups walk through them side by side, so that at any time a die
-    //  works on a few channels only and their k_f stays in its L2.
-    const int npairs = CPLX ? B : (B + 1) / 2;
-    const long long T = (long long)H * npairs;
-    const int nx = (!REGC && gridDim.x % 8 == 0) ? 8 : 1;
-    const int x = blockIdx.x % nx, nb = gridDim.x / nx, jb = blockIdx.x / nx;
-    int first, stride, cnt;                               // local item k is v = first + k * stride
-    if constexpr (REGC) {
-        const int t0 = (int)(T * blockIdx.x / gridDim.x), t1 = (int)(T * (blockIdx.x + 1) / gridDim.x);
-        first = t0;
-        stride = 1;
-        cnt = t1 - t0;
-    } else {
-        const int n_local = ((H - x + nx - 1) / nx) * npairs;
-        first = jb;
-        stride = nb;
-        cnt = jb < n_local ? (n_local - jb + nb - 1) / nb : 0;
-    }
-    if (cnt <= 0) return;
-    auto item = [&](int k) {
-        const int v = first + k * stride;
-        return REGC ? v : ((v / npairs) * nx + x) * npairs + v % npairs;
-    };
-    const int ko_live = KoN > 0 ? ko_lo + KoN - ko_hi : 1;
-    const int Hrows = KoN > 0 ? (H / ko_live) * KoN : H;        // rows per pair in memory
-    auto row_of = [&](int h) {                                   // live row -> row among all
-        if (KoN <= 0) return h;
-        const int g = h / ko_live, j = h - g * ko_live;
-        return g * KoN + (j < ko_lo ? j : j - ko_lo + ko_hi);
-    };
-
-    // ---------------- constants (per-lane operand tables) ----------------
-    uint4 tab1[KS1][2][2], tab1i[2][RT1][2], tab3[R3][R3][2], tab3i[R3][R3][2];
-    uint4 tab2[C3][R2][R2][2], tab2i[C1][R2][R2][2];
-    float2 twa[C3][R2][2][4], twb[C1][R2][R3][4];
-    // k_f: 4-byte 16-bit (re, im) constants (it is streamed for every row: as many bytes as the row itself at 8)
-    using T4 = typename std::conditional<std::is_same<TT, F16>::value, H16, B16>::type;
-    uint32_t kfr[C1][R2][R3][4];
-
-#pragma unroll
-    for (int a = 0; a < 2; ++a)
-#pragma unroll
-        for (int p = 0; p < 2; ++p) {
-#pragma unroll
-            for (int ks = 0; ks < KS1; ++ks) tab1[ks][a][p] = cs.tab1[((ks * 2 + a) * 2 + p) * 64 + l];
-#pragma unroll
-            for (int rt = 0; rt < RT1; ++rt) tab1i[a][rt][p] = cs.tab1i[((a * 2 + rt) * 2 + p) * 64 + l];
-        }
-#pragma unroll
-    for (int t = 0; t < R3; ++t)
-#pragma unroll
-        for (int c = 0; c < R3; ++c)
-#pragma unroll
-            for (int p = 0; p < 2; ++p) {
-                tab3[t][c][p] = cs.tab3[((t * R3 + c) * 2 + p) * 64 + l];
-                tab3i[t][c][p] = cs.tab3i[((t * R3 + c) * 2 + p) * 64 + l];
-            }
-    // When the tables are streamed (REGC false) the loads must stay inside the loop over work
-    // items: an opaque zero added to the lane offset keeps the compiler from hoisting them.
-    int lz = l;
-    auto opaque = [&]() {
-        if constexpr (!REGC) {
-            int z = 0;
-            asm volatile("" : "+v"(z));
-            lz = l + z;
-        }
-    };
-    auto load_A = [&](int i) {
-        const int c = w * C3 + i;
-#pragma unroll
-        for (int t = 0; t < R2; ++t)
-#pragma unroll
-            for (int ct = 0; ct < R2; ++ct)
-#pragma unroll
-                for (int p = 0; p < 2; ++p)
-                    tab2[i][t][ct][p] = cs.tab2[(((c * R2 + t) * R2 + ct) * 2 + p) * 64 + lz];
-#pragma unroll
-        for (int rt = 0; rt < R2; ++rt)
-#pragma unroll
-            for (int ct = 0; ct < 2; ++ct)
-#pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    twa[i][rt][ct][r] = cs.twa[(((c * R2 + rt) * 2 + ct) * 4 + r) * 64 + lz];
-    };
-    auto load_B = [&](int i) {
-        const int c = w * C1 + i;
-#pragma unroll
-        for (int t = 0; t < R2; ++t)
-#pragma unroll
-            for (int ct = 0; ct < R2; ++ct)
-#pragma unroll
-                for (int p = 0; p < 2; ++p)
-                    tab2i[i][t][ct][p] = cs.tab2i[(((c * R2 + t) * R2 + ct) * 2 + p) * 64 + lz];
-#pragma unroll
-        for (int a = 0; a < R2; ++a)
-#pragma unroll
-            for (int b = 0; b < R3; ++b)
-#pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    twb[i][a][b][r] = cs.twb[(((c * R2 + a) * R3 + b) * 4 + r) * 64 + lz];
-    };
-    auto load_kf = [&](int i, int h) {
-        const int c = w * C1 + i;
-#pragma unroll
-        for (int a = 0; a < R2; ++a)
-#pragma unroll
-            for (int b = 0; b < R3; ++b)
-#pragma unroll
-                for (int r = 0; r < LIVE; ++r)
-                    kfr[i][a][b][r] = kf[(size_t)h * G::KF_PER_H + (((c * R2 + a) * R3 + b) * 4 + r) * 64 + lz];
-    };
-    if constexpr (REGC) {
-#pragma unroll
-        for (int i = 0; i < C3; ++i) load_A(i);
-#pragma unroll
-        for (int i = 0; i < C1; ++i) load_B(i);
-    }
-
-    // ---------------- input prefetch (registers) ----------------
-    uint4 pre[NCH];
-    auto issue_loads = [&](int k) {
-        const int t = item(k < cnt ? k : cnt - 1);
-        const int h = t / npairs, pair = t - h * npairs;
-        if constexpr (CPLX) {
-            const uint16_t *row = u + ((size_t)pair * Hrows + row_of(h)) * (size_t)(2 * G::M);
-#pragma unroll
-            for (int j = 0; j < NCH; ++j) {
-                uint4 v = make_uint4(0, 0, 0, 0);
-                if (k < cnt) v = *(const uint4 *)(row + (size_t)(tid + NT * j) * 8);
-                pre[j] = v;
-            }
-        } else
-#pragma unroll
-        for (int j = 0; j < G::CHUNKS; ++j) {
-            const int s = j / G::CPS;                    // which row of the pair (wave-uniform)
-            const int n = (tid + NT * (j % G::CPS)) * 8;
-            const int b = 2 * pair + s;
-            uint4 v = make_uint4(0, 0, 0, 0);
-            const uint16_t *row = u + ((size_t)b * H + h) * N;
-            if (k < cnt && b < B && n < N) v = *(const uint4 *)(row + n);
-            pre[j] = v;
-        }
-    };
-    // prefetched input -> UB (padded layout)
-    auto stage_in = [&]() {
-        if constexpr (CPLX) {
-#pragma unroll
-            for (int j = 0; j < NCH; ++j) {
-                const int n = (tid + NT * j) * 4;
-                const int n3 = n % N3, n2 = (n / N3) % N2, n1 = n / (N2 * N3);
-                uint32_t *dst = UBC + n1 * G::PQ1C + n2 * G::PRC + n3;
-                dst[0] = pre[j].x;
-                dst[1] = pre[j].y;
-                dst[2] = pre[j].z;
-                dst[3] = pre[j].w;
-            }
-        } else
-#pragma unroll
-        for (int j = 0; j < G::CHUNKS; ++j) {
-            const int s = j / G::CPS;
-            const int n = (tid + NT * (j % G::CPS)) * 8;
-            const int n3 = n % N3, n2 = (n / N3) % N2, n1 = n / (N2 * N3);
-            uint32_t *dst = (uint32_t *)(UB + s * G::SU + n1 * G::PQ1 + n2 * G::PR + n3);
-            dst[0] = pre[j].x;
-            dst[1] = pre[j].y;
-            dst[2] = pre[j].z;
-            dst[3] = pre[j].w;
-        }
-    };
-    // YB -> y, 16 bytes per lane, coalesced
-    auto store_out = [&](int k) {
-        const int t = item(k);
-        const int h = t / npairs, pair = t - h * npairs;
-        if constexpr (CPLX) {
-            uint16_t *row = y + ((size_t)pair * Hrows + row_of(h)) * (size_t)(2 * G::M);
-#pragma unroll
-            for (int j = 0; j < NCH; ++j) {
-                const int n = (tid + NT * j) * 4;
-                const int n3 = n % N3, n2 = (n / N3) % N2, n1 = n / (N2 * N3);
-                const uint32_t *src = YBC + n1 * G::PQ1C + n2 * G::PRC + n3;
-                *(uint4 *)(row + (size_t)n * 2) = make_uint4(src[0], src[1], src[2], src[3]);
-            }
-        } else
-#pragma unroll
-        for (int j = 0; j < G::CHUNKS; ++j) {
-            const int s = j / G::CPS;
-            const int n = (tid + NT * (j % G::CPS)) * 8;
-            const int b = 2 * pair + s;
-            const int n3 = n % N3, n2 = (n / N3) % N2, n1 = n / (N2 * N3);
-            const uint32_t *src = (const uint32_t *)(YB + s * G::SU + n1 * G::PQ1 + n2 * G::PR + n3);
-            const uint4 v = make_uint4(src[0], src[1], src[2], src[3]);
-            uint16_t *row = y + ((size_t)b * H + h) * N;
-            if (b < B && n < N) *(uint4 *)(row + n) = v;
-        }
-    };
-
-    // Pipeline over work items (3 barriers each):
-    //   [A(t)] | [B(t) + store(t-1) + stage_in(t+1) + issue_loads(t+2)] | [C(t)] |
-    // UB is read in A(t) and rewritten in B(t); YB is written in C(t) and read in B(t+1); XB planes
-    // change owner only across barriers.
-    issue_loads(0);
-    stage_in();
-    issue_loads(1);
-    if constexpr (AHEAD) load_A(0);
-    lds_barrier();
-
-    const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
-    int h_cur = -1;
-    for (int k = 0; k < cnt; ++k) {
-        opaque();
-        {
-            const int h = row_of(item(k) / npairs);
-            if (h != h_cur) {                             // new channel: fetch its k_f (used in phase B)
-                h_cur = h;
-                if constexpr (REGC) {
-#pragma unroll
-                    for (int i = 0; i < C1; ++i) load_kf(i, h);
-                }
-            }
-        }
-        // ================= phase A: per n3 = c: stage 1, twiddle, stage 2 -> XB
-        // (all operand reads first, then tile by tile compute -> write, so that the LDS
-        //  traffic of one tile drains while the next tile computes)
-        {
-            uint4 x1[C3][R2][KS1];
-#pragma unroll
-            for (int i = 0; i < C3; ++i) {
-                const int c = w * C3 + i;
-#pragma unroll
-                for (int rt = 0; rt < R2; ++rt) {
-                    if constexpr (CPLX) {
-                        // row n2 = 16 rt + c16, slots (2r, 2r+1) = (re, im) of x[n1 = 16 ks + 4q + r]
-#pragma unroll
-                        for (int ks = 0; ks < KS1; ++ks) {
-                            const uint32_t *p0 = UBC + (16 * ks + 4 * q) * G::PQ1C + (16 * rt + c16) * G::PRC + c;
-                            x1[i][rt][ks] = make_uint4(p0[0], p0[G::PQ1C], p0[2 * G::PQ1C], p0[3 * G::PQ1C]);
-                        }
-                    } else {
-                        // operand of stage 1: row n2 = 16 rt + c16, slots (2r+s) = u_s[n1 = 4q + r]
-                        const uint16_t *p0 = UB + (4 * q) * G::PQ1 + (16 * rt + c16) * G::PR + c;
-                        uint32_t d[4];
-#pragma unroll
-                        for (int r = 0; r < 4; ++r)
-                            d[r] = (uint32_t)p0[r * G::PQ1] | ((uint32_t)p0[G::SU + r * G::PQ1] << 16);
-                        x1[i][rt][0] = make_uint4(d[0], d[1], d[2], d[3]);
-                    }
-                }
-            }
-#pragma unroll
-            for (int i = 0; i < C3; ++i) {
-                const int c = w * C3 + i;
-                // streamed tables (L2-resident): requested one tile ahead where the registers allow
-                if constexpr (AHEAD) {
-                    if (i + 1 < C3) load_A(i + 1);
-                } else if constexpr (!REGC) {
-                    load_A(i);
-                }
-                uint4 x2[2][R2];                          // stage-2 operands [k1 tile][K step = n2 tile]
-#pragma unroll
-                for (int rt = 0; rt < R2; ++rt)
-#pragma unroll
-                    for (int ct = 0; ct < 2; ++ct) {
-                        f32x4 dre = zero4, dim = zero4;
-#pragma unroll
-                        for (int ks = 0; ks < KS1; ++ks) {
-                            dre = TT::mfma(x1[i][rt][ks], tab1[ks][ct][0], dre);
-                            dim = TT::mfma(x1[i][rt][ks], tab1[ks][ct][1], dim);
-                        }
-                        uint32_t o[4];
-#pragma unroll
-                        for (int r = 0; r < 4; ++r) {
-                            float re = dre[r], im = dim[r];
-                            cmul_ip(re, im, twa[i][rt][ct][r]);
-                            o[r] = TT::pack(re, im);
-                        }
-                        x2[ct][rt] = make_uint4(o[0], o[1], o[2], o[3]);
-                    }
-#pragma unroll
-                for (int ct = 0; ct < 2; ++ct)
-#pragma unroll
-                    for (int ct2 = 0; ct2 < R2; ++ct2) {
-                        f32x4 dre = zero4, dim = zero4;
-#pragma unroll
-                        for (int ks = 0; ks < R2; ++ks) {   // matrix as the A operand: rows k2, data columns k1
-                            dre = TT::mfma(tab2[i][ks][ct2][0], x2[ct][ks], dre);
-                            dim = TT::mfma(tab2[i][ks][ct2][1], x2[ct][ks], dim);
-                        }
-                        // lane: k1 = 16 ct + c16; reg r: k2 = 16 ct2 + 4q + r -> 4 consecutive words, one 16-byte write
-                        uint32_t *dst = XB + c * G::PN3 + (16 * ct + c16) * G::PK1 + 16 * ct2 + 4 * q;
-                        *(uint4 *)dst = make_uint4(TT::pack(dre[0], dim[0]), TT::pack(dre[1], dim[1]),
-                                                   TT::pack(dre[2], dim[2]), TT::pack(dre[3], dim[3]));
-                    }
-            }
-            if constexpr (AHEAD) {                        // phase B's first tile: in flight across the barrier
-                load_B(0);
-                load_kf(0, h_cur);
-            }
-        }
-        lds_barrier();
-
-        // ================= phase B: per k1 = c: stage 3, k_f, inverse 3, twiddle, inverse 2 -> XB in place
-        {
-            uint4 x3[C1][R2][R3];
-#pragma unroll
-            for (int i = 0; i < C1; ++i) {
-                const int c = w * C1 + i;
-#pragma unroll
-                for (int ct2 = 0; ct2 < R2; ++ct2)
-#pragma unroll
-                    for (int ks = 0; ks < R3; ++ks) {
-                        const uint32_t *src = XB + (16 * ks + 4 * q) * G::PN3 + c * G::PK1 + 16 * ct2 + c16;
-                        x3[i][ct2][ks] = make_uint4(src[0], src[G::PN3], src[2 * G::PN3], src[3 * G::PN3]);
-                    }
-            }
-            // The staging traffic rides in this compute-heavy phase: the previous pair's output
-            // (YB, complete since the last barrier) goes to HBM, the next pair's prefetched input
-            // goes to UB (its readers finished before the last barrier), and the loads of the pair
-            // after that start.
-            // (stage_in first: it waits for the prefetch, and on this target loads and stores
-            //  retire through one counter, so it must not sit behind freshly issued stores)
-            stage_in();
-            issue_loads(k + 2);
-            if (k > 0) store_out(k - 1);
-#pragma unroll
-            for (int i = 0; i < C1; ++i) {
-                const int c = w * C1 + i;
-                if constexpr (AHEAD) {
-                    if (i + 1 < C1) {
-                        load_B(i + 1);
-                        load_kf(i + 1, h_cur);
-                    }
-                } else if constexpr (!REGC) {
-                    load_B(i);
-                    load_kf(i, h_cur);
-                }
-                uint4 x3i[R2][R3];                        // [k2 tile][K step = k3 tile]
-#pragma unroll
-                for (int ct2 = 0; ct2 < R2; ++ct2)
-#pragma unroll
-                    for (int ct3 = 0; ct3 < R3; ++ct3) {
-                        f32x4 dre = zero4, dim = zero4;
-#pragma unroll
-                        for (int ks = 0; ks < R3; ++ks) {  // matrix is the A operand: rows k3, data columns k2
-                            dre = TT::mfma(tab3[ks][ct3][0], x3[i][ct2][ks], dre);
-                            dim = TT::mfma(tab3[ks][ct3][1], x3[i][ct2][ks], dim);
-                        }
-                        // the product runs in fp32 (plain multiply-adds overlap with the matrix cores of the
-                        // other wave, the 16-bit dot products do not); the constant is widened in two cheap ops
-                        uint32_t o[4];
-#pragma unroll
-                        for (int r = 0; r < 4; ++r) {
-                            float re = dre[r], im = dim[r];
-                            cmul_ip(re, im, T4::widen(kfr[i][ct2][ct3][r]));
-                            o[r] = TT::pack(re, im);
-                        }
-                        x3i[ct2][ct3] = make_uint4(o[0], o[1], o[2], o[3]);
-                    }
-                uint4 x2i[R3][R2];                        // [n3 tile][K step = k2 tile]
-#pragma unroll
-                for (int ct2 = 0; ct2 < R2; ++ct2)
-#pragma unroll
-                    for (int cn3 = 0; cn3 < R3; ++cn3) {
-                        f32x4 dre = zero4, dim = zero4;
-#pragma unroll
-                        for (int ks = 0; ks < R3; ++ks) {
-                            dre = TT::mfma(x3i[ct2][ks], tab3i[ks][cn3][0], dre);
-                            dim = TT::mfma(x3i[ct2][ks], tab3i[ks][cn3][1], dim);
-                        }
-                        uint32_t o[4];
-#pragma unroll
-                        for (int r = 0; r < 4; ++r) {
-                            float re = dre[r], im = dim[r];
-                            cmul_ip(re, im, twb[i][ct2][cn3][r]);
-                            o[r] = TT::pack(re, im);
-                        }
-                        x2i[cn3][ct2] = make_uint4(o[0], o[1], o[2], o[3]);
-                    }
-#pragma unroll
-                for (int cn3 = 0; cn3 < R3; ++cn3)
-#pragma unroll
-                    for (int cn2 = 0; cn2 < R2; ++cn2) {
-                        f32x4 dre = zero4, dim = zero4;
-#pragma unroll
-                        for (int ks = 0; ks < R2; ++ks) {   // matrix as the A operand: rows n2, data columns n3
-                            dre = TT::mfma(tab2i[i][ks][cn2][0], x2i[cn3][ks], dre);
-                            dim = TT::mfma(tab2i[i][ks][cn2][1], x2i[cn3][ks], dim);
-                        }
-                        // lane: n3 = 16 cn3 + c16; reg r: n2 = 16 cn2 + 4q + r -> one 16-byte write
-                        uint32_t *dst = XB + (16 * cn3 + c16) * G::PN3 + c * G::PK1 + 16 * cn2 + 4 * q;
-                        *(uint4 *)dst = make_uint4(TT::pack(dre[0], dim[0]), TT::pack(dre[1], dim[1]),
-                                                   TT::pack(dre[2], dim[2]), TT::pack(dre[3], dim[3]));
-                    }
-            }
-        }
-        lds_barrier();
-
-        // ================= phase C: per n3 = c: inverse stage 1 (n1 < 16; re -> row b, im -> row b+1) -> YB
-        {
-            uint4 x1i[C3][R2][2];
-#pragma unroll
-            for (int i = 0; i < C3; ++i) {
-                const int c = w * C3 + i;
-#pragma unroll
-                for (int cn2 = 0; cn2 < R2; ++cn2)
-#pragma unroll
-                    for (int ks = 0; ks < 2; ++ks) {
-                        const uint32_t *src = XB + c * G::PN3 + (16 * ks + 4 * q) * G::PK1 + 16 * cn2 + c16;
-                        x1i[i][cn2][ks] = make_uint4(src[0], src[G::PK1], src[2 * G::PK1], src[3 * G::PK1]);
-                    }
-            }
-#pragma unroll
-            for (int i = 0; i < C3; ++i) {
-                const int c = w * C3 + i;
-#pragma unroll
-                for (int cn2 = 0; cn2 < R2; ++cn2)
-#pragma unroll
-                    for (int rt = 0; rt < RT1; ++rt) {
-                        f32x4 dre = zero4, dim = zero4;
-#pragma unroll
-                        for (int ks = 0; ks < 2; ++ks) {
-                            dre = TT::mfma(tab1i[ks][rt][0], x1i[i][cn2][ks], dre);
-                            dim = TT::mfma(tab1i[ks][rt][1], x1i[i][cn2][ks], dim);
-                        }
-                        // lane: n2 = 16 cn2 + c16; reg r: n1 = 16 rt + 4q + r
-                        if constexpr (CPLX) {
-                            uint32_t *dst = YBC + (16 * rt + 4 * q) * G::PQ1C + (16 * cn2 + c16) * G::PRC + c;
-#pragma unroll
-                            for (int r = 0; r < 4; ++r) dst[r * G::PQ1C] = TT::pack(dre[r], dim[r]);
-                        } else {
-                            uint16_t *dst = YB + (4 * q) * G::PQ1 + (16 * cn2 + c16) * G::PR + c;
-#pragma unroll
-                            for (int r = 0; r < 4; ++r) {
-                                dst[r * G::PQ1] = TT::cvt(dre[r]);
-                                dst[G::SU + r * G::PQ1] = TT::cvt(dim[r]);
-                            }
-                        }
-                    }
-            }
-            if constexpr (AHEAD) load_A(0);               // the next item's first phase-A tile
-        }
-        lds_barrier();
-    }
-    store_out(cnt - 1);
-}
 
 // Filter transform of the plans that run on the 8192-point kernel, one workgroup per channel and no
 // intermediate in HBM: taps -> LDS (zero padded, fp32), forward transform of length Ms = 8192 / groups in
@@ -746,32 +270,6 @@ int build_tables(fftconv_plan *p, void **dest, int groups = 1)
     return FFTCONV_OK;
 }
 
-// Rows: for the causal kernel (CPLX false) B batch rows of H channels, N samples each; for the
-// complex-row kernel B rows per k_f row, H k_f rows.
-template <int N2, int N3, typename TT, bool REGC, bool CPLX, int LIVE = 4>
-int launch(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, int64_t H, int64_t N,
-           hipStream_t s, int KoN = 0, int ko_lo = 0, int ko_hi = 0)
-{
-    using G = Geo<N2, N3>;
-    auto kern = k_fused3<N2, N3, TT, REGC, CPLX, LIVE>;
-    constexpr size_t lds = CPLX ? G::LDS_BYTES_C : G::LDS_BYTES;
-    FC_TRY(raise_dynamic_lds((const void *)kern, (int)lds));
-    const int64_t npairs = CPLX ? B : (B + 1) / 2;
-    const int64_t T = H * npairs;
-    if (T >= ((int64_t)1 << 31)) {
-        set_error("fftconv_forward: H * ceil(B/2) = %lld work items exceed the fused kernel's 2^31 limit", (long long)T);
-        return FFTCONV_EUNSUPPORTED;
-    }
-    // one persistent workgroup per compute unit (fewer when there is less work than that); a
-    // multiple of 8 for the streamed-table kernels (see the kernel's work split)
-    int grid = (int)(T < p->f3.num_cu ? T : p->f3.num_cu);
-    if (!REGC && grid >= 8) grid -= grid % 8;
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NT), lds, s, (const uint16_t *)u, (uint16_t *)y,
-                       (const uint32_t *)kf, consts_of<N2, N3>(p), (int)B, (int)H, (int)N, KoN, ko_lo, ko_hi, launch_gate());
-    FC_HIP(hipGetLastError());
-    return FFTCONV_OK;
-}
-
 }  // namespace
 
 bool fused3_supported(int64_t N, int64_t M, int dtype)
@@ -900,11 +398,7 @@ int fused3_inner_rows(const fftconv_plan *p, void *rows, const void *kf, int64_t
         if (ko_lo >= ko_hi) ko_n = 0;                            // everything live
         else live_rows = kf_rows / ko_n * (ko_lo + ko_n - ko_hi);
     }
-    if (p->dtype == FFTCONV_F16)
-        return launch<16, 16, F16, false, true>(p, rows, kf, rows, rows_per_kf, live_rows, Geo<16, 16>::M, s, ko_n, ko_lo,
-                                                ko_hi);
-    return launch<16, 16, BF16, false, true>(p, rows, kf, rows, rows_per_kf, live_rows, Geo<16, 16>::M, s, ko_n, ko_lo,
-                                             ko_hi);
+    return fused3_wsc_launch(p, rows, kf, rows_per_kf, live_rows, s, ko_n, ko_lo, ko_hi);
 }
 
 void fused3_destroy(fftconv_plan *p)

@@ -1,4 +1,4 @@
-// Definitions shared by the fused order-3 kernels (fused3.hip, fused3_ws.hip): MFMA wrappers,
+// Definitions shared by the fused order-3 kernels (fused3_ws.hip, fused3_wsc.hip, fused3_big.hip): MFMA wrappers,
 // tile geometry / LDS layouts of fft_size = 32 * N2 * N3, and the table pointers.
 #pragma once
 
@@ -246,8 +246,6 @@ __device__ __forceinline__ void lds_barrier()
 template <int N2, int N3> struct Geo {
     static constexpr int M = N1 * N2 * N3;
     static constexpr int R2 = N2 / 16, R3 = N3 / 16;
-    static constexpr int C3 = N3 / NW;           // n3 values per wave (phases A, C)
-    static constexpr int C1 = N1 / NW;           // k1 values per wave (phase B)
     // exchange buffer, 32-bit words: X(k1,k2,n3) = n3*PN3 + k1*PK1 + k2.
     // 4*PK1 and 4*PN3 are 16 mod 32, which spreads the 4 lane groups of a wave over the banks.
     static constexpr int PK1 = N2 + 4;
@@ -258,15 +256,6 @@ template <int N2, int N3> struct Geo {
     static constexpr int PQ1 = N2 * PR + 8;
     static constexpr int SU = (N1 / 2) * PQ1;
     static constexpr int UB_ELEMS = 2 * SU;
-    static constexpr size_t LDS_BYTES = (size_t)XB_WORDS * 4 + (size_t)UB_ELEMS * 2 * 2;
-    // complex-row variant: staging of 16-bit (re, im) pairs, 32-bit words: (n1, n2, n3) -> n1*PQ1C + n2*PRC + n3
-    static constexpr int PRC = N3 + 1;
-    static constexpr int PQ1C = N2 * PRC + 4;
-    static constexpr int UBC_WORDS = N1 * PQ1C;
-    static constexpr size_t LDS_BYTES_C = (size_t)XB_WORDS * 4 + (size_t)UBC_WORDS * 4 * 2;
-    static constexpr int CHUNKS_C = M / 4 / NT;  // 16-byte chunks (4 complex points) of a row per thread
-    static constexpr int CHUNKS = M / 8 / NT;    // 16-byte chunks of a pair's input per thread
-    static constexpr int CPS = CHUNKS / 2;       // ... per row of the pair
     // table sizes (entries)
     static constexpr int TAB1 = 2 * 2 * 2 * 64;             // [K step][ct][part][lane] uint4
     static constexpr int TAB2 = N3 * R2 * R2 * 2 * 64;      // [n3][t][ct][part][lane]
@@ -337,6 +326,11 @@ inline Consts consts_of(const fftconv_plan *p) { return consts_at<N2, N3>(p->f3.
 int fused3_ws_launch(const fftconv_plan *p, const void *consts, const void *u, const void *kf, void *y, int64_t B,
                      int nseg, int P, hipStream_t s, const void *wg = nullptr, const void *vg = nullptr,
                      uint32_t live_k1 = 0xffffffffu);
+
+// wave-specialised kernel for complex rows of length 8192, in place (fused3_wsc.hip): the inner step of the
+// multi-pass scheme
+int fused3_wsc_launch(const fftconv_plan *p, void *rows, const void *kf, int64_t rows_per_kf, int64_t live_rows,
+                      hipStream_t s, int ko_n, int ko_lo, int ko_hi);
 
 // fused kernel for fft_size 32768 (fused3_big.hip): own tables (in p->f3.consts) and k_f layout
 int fused3_big_init(fftconv_plan *p);

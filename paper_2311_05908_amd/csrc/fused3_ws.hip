@@ -1,5 +1,5 @@
 // Wave-specialised fused causal FFT convolution, fft_size 8192 = 32*16*16, 16-bit I/O
-// (paper Algorithm 3; same arithmetic, tables and k_f layout as k_fused3 in fused3.hip).
+// (paper Algorithm 3; index maps, tables and k_f layout: see fused3.hip).
 //
 // Why a second schedule: with every wave running the same phase at the same time, all eight
 // waves of a workgroup meet the same LDS latencies and barriers together and the SIMDs idle

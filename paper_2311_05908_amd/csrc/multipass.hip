@@ -148,11 +148,12 @@ __global__ void __launch_bounds__(TB, 4) k_outer_fwd(const uint16_t *__restrict_
     const uint16_t *g0 = GATED ? wg + ((size_t)b0 * H + h) * N : nullptr;
     const uint16_t *g1 = GATED ? wg + ((size_t)(b0 + (two ? 1 : 0)) * H + h) * N : nullptr;
     const bool wide = CV == 2 && N % 2 == 0;       // rows start 4-byte aligned
-    const int CG = CT / CV;                        // column groups
+    const int CG = CT / CV;                        // column groups, a power of two
+    const int lgCG = 31 - __builtin_clz(CG);
     for (int j = tid; j < No; j += TB) wno[j] = wm(j, 2.0f / (float)No);
     __syncthreads();
     for (int e = tid; e < RB * CG; e += TB) {
-        const int c = (e % CG) * CV, b2 = e / CG;
+        const int c = (e & (CG - 1)) * CV, b2 = e >> lgCG;
         uint32_t in0[RAIN], in1[RAIN];             // CV 16-bit values of row b / row b+1
 #pragma unroll
         for (int a = 0; a < RAIN; ++a) {
@@ -210,8 +211,9 @@ __global__ void __launch_bounds__(TB, 4) k_outer_fwd(const uint16_t *__restrict_
     }
     __syncthreads();
     const float ihm = 2.0f / (float)M;
+    const int Mmask = (int)M - 1;                  // M is a power of two, at most 2^22, and so is every r * ko
     for (int e = tid; e < RA * CG; e += TB) {
-        const int c = (e % CG) * CV, ka = e / CG;
+        const int c = (e & (CG - 1)) * CV, ka = e >> lgCG;
         uint32_t o[RB][CV];
 #pragma unroll
         for (int v = 0; v < CV; ++v) {
@@ -220,8 +222,8 @@ __global__ void __launch_bounds__(TB, 4) k_outer_fwd(const uint16_t *__restrict_
             for (int b2 = 0; b2 < RB; ++b2) x[b2] = T[(ka * RB + b2) * CT + c + v];
             dft_reg<RB, false>(x);
             const int r = r0 + c + v;
-            float2 w = wm((int)(((int64_t)r * ka) % M), ihm);                 // W_M^{r ka}
-            const float2 step = wm((int)(((int64_t)r * RA) % M), ihm);        // W_M^{r RA}
+            float2 w = wm((r * ka) & Mmask, ihm);                 // W_M^{r ka}
+            const float2 step = wm((r * RA) & Mmask, ihm);        // W_M^{r RA}
 #pragma unroll
             for (int kb = 0; kb < RB; ++kb) {
                 const float2 t = cmulf(x[kb], w);
@@ -270,9 +272,11 @@ __global__ void __launch_bounds__(TB, 4) k_outer_inv(const uint32_t *__restrict_
     const bool two = b0 + 1 < B;
     const bool wide = CV == 2 && N % 2 == 0;
     const int CG = CT / CV;
+    const int lgCG = 31 - __builtin_clz(CG);
     for (int j = tid; j < No; j += TB) wno[j] = wm(j, 2.0f / (float)No);
     __syncthreads();
     const float ihm = 2.0f / (float)M;
+    const int Mmask = (int)M - 1;                  // M is a power of two, at most 2^22, and so is every r * ko
     // step 1: T[ka*RB + b2] = conj(W_No^{ka b2}) * sum_{kb} conj(W_RB^{b2 kb}) conj(W_M^{r ko}) S[ko], ko = ka + RA kb
     // MIRROR (mirror_from == No/2 + 1): rows ko > No/2 were never computed (a lone real row, see multipass_forward): before the
     // twiddle row ko is the complex conjugate of row ko' = No - ko, i.e.
@@ -281,7 +285,7 @@ __global__ void __launch_bounds__(TB, 4) k_outer_inv(const uint32_t *__restrict_
     // read and conjugated (a sign flip on the packed word), and from the first mirrored row on the twiddle of the
     // recurrence carries the extra factor conj(W_Mi^{r}).
     for (int e = tid; e < RA * CG; e += TB) {
-        const int c = (e % CG) * CV, ka = e / CG;
+        const int c = (e & (CG - 1)) * CV, ka = e >> lgCG;
         uint32_t in[RB][CV];
 #pragma unroll
         for (int kb = 0; kb < RB; ++kb) {
@@ -308,8 +312,8 @@ __global__ void __launch_bounds__(TB, 4) k_outer_inv(const uint32_t *__restrict_
 #pragma unroll
         for (int v = 0; v < CV; ++v) {
             const int r = r0 + c + v;
-            float2 w = wm((int)(((int64_t)r * ka) % M), ihm);
-            const float2 step = wm((int)(((int64_t)r * RA) % M), ihm);
+            float2 w = wm((r * ka) & Mmask, ihm);
+            const float2 step = wm((r * RA) & Mmask, ihm);
             constexpr float unboost = 1.0f / (float)multipass_kf_boost(F16, No);     // exact: a power of two
             w.x *= unboost;
             w.y *= unboost;
@@ -320,7 +324,7 @@ __global__ void __launch_bounds__(TB, 4) k_outer_inv(const uint32_t *__restrict_
                 const bool first_mirrored = RB == 1 ? ka > RA / 2
                                                     : ((kb == RB / 2 && ka > 0) || (kb == RB / 2 + 1 && ka == 0));
                 if (MIRROR && first_mirrored)
-                    w = cmulcf(w, wm((int)(((int64_t)r * No) % M), ihm));        // times conj(W_Mi^{r}), once
+                    w = cmulcf(w, wm((r * No) & Mmask, ihm));        // times conj(W_Mi^{r}), once
                 x[kb] = cmulcf(unpack2<F16>(in[kb][v]), w);
                 w = cmulf(w, step);
             }
@@ -345,7 +349,7 @@ __global__ void __launch_bounds__(TB, 4) k_outer_inv(const uint32_t *__restrict_
     const uint16_t *g0 = GATED ? vg + ((size_t)b0 * H + h) * N : nullptr;
     const uint16_t *g1 = GATED ? vg + ((size_t)(b0 + (two ? 1 : 0)) * H + h) * N : nullptr;
     for (int e = tid; e < RB * CG; e += TB) {
-        const int c = (e % CG) * CV, b2 = e / CG;
+        const int c = (e & (CG - 1)) * CV, b2 = e >> lgCG;
         uint32_t o0[RAIN], o1[RAIN];
 #pragma unroll
         for (int a = 0; a < RAIN; ++a) o0[a] = o1[a] = 0;
@@ -413,6 +417,7 @@ __global__ void __launch_bounds__(TB, 4) k_outer_fwd_real(const uint16_t *__rest
     float2 *T = sm + No;                           // [No][CG]
     const int tid = threadIdx.x;
     const int r0 = blockIdx.x * 2 * CG;
+    const int lgCG = 31 - __builtin_clz(CG);       // CG is a power of two
     const int h = blockIdx.y;
     const uint16_t *row0 = u + (size_t)h * N;
     const uint16_t *g0 = GATED ? wg + (size_t)h * N : nullptr;
@@ -421,7 +426,7 @@ __global__ void __launch_bounds__(TB, 4) k_outer_fwd_real(const uint16_t *__rest
     __syncthreads();
     // step 1: length-RA transforms over a, times W_No^{ka b2}
     for (int e = tid; e < RB * CG; e += TB) {
-        const int cg = e % CG, b2 = e / CG;
+        const int cg = e & (CG - 1), b2 = e >> lgCG;
         float2 x[RA];
 #pragma unroll
         for (int a = 0; a < RA; ++a) {
@@ -453,7 +458,7 @@ __global__ void __launch_bounds__(TB, 4) k_outer_fwd_real(const uint16_t *__rest
     __syncthreads();
     // step 2: length-RB transforms over b2, in place: slot ka*RB + kb then holds Z[ko], ko = ka + RA kb
     for (int e = tid; e < RA * CG; e += TB) {
-        const int cg = e % CG, ka = e / CG;
+        const int cg = e & (CG - 1), ka = e >> lgCG;
         float2 x[RB];
 #pragma unroll
         for (int b2 = 0; b2 < RB; ++b2) x[b2] = T[(ka * RB + b2) * CG + cg];
@@ -464,13 +469,14 @@ __global__ void __launch_bounds__(TB, 4) k_outer_fwd_real(const uint16_t *__rest
     __syncthreads();
     // step 3: split the two columns, twiddle (by recurrence over kb), store the rows ko <= No/2
     const float ihm = 2.0f / (float)M;
+    const int Mmask = (int)M - 1;                  // M is a power of two, at most 2^22, and so is every r * ko
     for (int e = tid; e < RA * CG; e += TB) {
-        const int cg = e % CG, ka = e / CG;
+        const int cg = e & (CG - 1), ka = e >> lgCG;
         const int r = r0 + 2 * cg;
-        float2 w0 = wm((int)(((int64_t)r * ka) % M), ihm), w1 = wm((int)(((int64_t)(r + 1) * ka) % M), ihm);
-        const float2 s0 = wm((int)(((int64_t)r * RA) % M), ihm), s1 = wm((int)(((int64_t)(r + 1) * RA) % M), ihm);
+        float2 w0 = wm((r * ka) & Mmask, ihm), w1 = wm(((r + 1) * ka) & Mmask, ihm);
+        const float2 s0 = wm((r * RA) & Mmask, ihm), s1 = wm(((r + 1) * RA) & Mmask, ihm);
 #pragma unroll
-        for (int kb = 0; kb < RB; ++kb) {
+        for (int kb = 0; kb < RB && kb <= RB / 2; ++kb) {          // ko = ka + RA kb <= No/2 needs kb <= RB/2
             const int ko = ka + RA * kb;
             if (ko <= No / 2 && ko < ko_lo) {         // (rows from ko_lo on only meet zeroed bins of a sparse filter)
                 const int km = (No - ko) % No;
@@ -501,16 +507,18 @@ __global__ void __launch_bounds__(TB, 4) k_outer_inv_real(const uint32_t *__rest
     float2 *T = sm + No;                           // [No][CG]
     const int tid = threadIdx.x;
     const int r0 = blockIdx.x * 2 * CG;
+    const int lgCG = 31 - __builtin_clz(CG);       // CG is a power of two
     const int h = blockIdx.y;
     const bool wide = N % 2 == 0;
     for (int j = tid; j < No; j += TB) wno[j] = wm(j, 2.0f / (float)No);
     __syncthreads();
     const float ihm = 2.0f / (float)M;
+    const int Mmask = (int)M - 1;                  // M is a power of two, at most 2^22, and so is every r * ko
     constexpr float unboost = 1.0f / (float)multipass_kf_boost(F16, No);     // exact: a power of two
     // step 1: untwiddle both columns, complete the rows ko > No/2 from their mirror rows, combine the columns
     // into one complex sequence, length-RB inverse over kb, times conj(W_No^{ka b2})
     for (int e = tid; e < RA * CG; e += TB) {
-        const int cg = e % CG, ka = e / CG;
+        const int cg = e & (CG - 1), ka = e >> lgCG;
         const int r = r0 + 2 * cg;
         uint2 in[RB];
 #pragma unroll
@@ -526,8 +534,8 @@ __global__ void __launch_bounds__(TB, 4) k_outer_inv_real(const uint32_t *__rest
                 in[kb].y ^= 0x80000000u;
             }
         }
-        float2 w0 = wm((int)(((int64_t)r * ka) % M), ihm), w1 = wm((int)(((int64_t)(r + 1) * ka) % M), ihm);
-        const float2 s0 = wm((int)(((int64_t)r * RA) % M), ihm), s1 = wm((int)(((int64_t)(r + 1) * RA) % M), ihm);
+        float2 w0 = wm((r * ka) & Mmask, ihm), w1 = wm(((r + 1) * ka) & Mmask, ihm);
+        const float2 s0 = wm((r * RA) & Mmask, ihm), s1 = wm(((r + 1) * RA) & Mmask, ihm);
         w0.x *= unboost, w0.y *= unboost, w1.x *= unboost, w1.y *= unboost;
         float2 x[RB];
 #pragma unroll
@@ -535,8 +543,8 @@ __global__ void __launch_bounds__(TB, 4) k_outer_inv_real(const uint32_t *__rest
             // from the first mirrored row on the twiddle carries the extra factor conj(W_Mi^{r}) (see k_outer_inv)
             const bool first_mirrored = RB == 1 ? ka > RA / 2 : ((kb == RB / 2 && ka > 0) || (kb == RB / 2 + 1 && ka == 0));
             if (first_mirrored) {
-                w0 = cmulcf(w0, wm((int)(((int64_t)r * No) % M), ihm));
-                w1 = cmulcf(w1, wm((int)(((int64_t)(r + 1) * No) % M), ihm));
+                w0 = cmulcf(w0, wm((r * No) & Mmask, ihm));
+                w1 = cmulcf(w1, wm(((r + 1) * No) & Mmask, ihm));
             }
             const float2 ua = cmulcf(unpack2<F16>(in[kb].x), w0), ub = cmulcf(unpack2<F16>(in[kb].y), w1);
             x[kb] = make_float2(ua.x - ub.y, ua.y + ub.x);               // U_c + i U_{c+1}
@@ -552,7 +560,7 @@ __global__ void __launch_bounds__(TB, 4) k_outer_inv_real(const uint32_t *__rest
     uint16_t *row0 = y + (size_t)h * N;
     const uint16_t *g0 = GATED ? vg + (size_t)h * N : nullptr;
     for (int e = tid; e < RB * CG; e += TB) {
-        const int cg = e % CG, b2 = e / CG;
+        const int cg = e & (CG - 1), b2 = e >> lgCG;
         float2 x[RA];
 #pragma unroll
         for (int ka = 0; ka < RA; ++ka) x[ka] = T[(ka * RB + b2) * CG + cg];

@@ -403,6 +403,8 @@ def test_every_power_of_two_fft_size_sampled_positions(lg):
     from parity_util import check_sampled_positions
     M = 1 << lg
     w = synth.scaled(W["cfg4"], B=2, H=2, N=M // 2, fft_size=M, dtype="bf16", alpha=(1e-4, 1e-4))
-    err, plan = check_sampled_positions(w, n_pos=16)
+    # 128 positions per sequence: the relative L2 error is a ratio of two sums over the sampled positions, and
+    # with 16 of them its scatter (about a third of its value) reaches the tolerance from a typical 5.5e-3
+    err, plan = check_sampled_positions(w, n_pos=128)
     print("fft 2^%d path=%s factors=%s err=%.3e" % (lg, plan.path, plan.factors, err), flush=True)
     assert err <= TOL["bf16"]
