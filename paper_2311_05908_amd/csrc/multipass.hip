@@ -79,12 +79,14 @@ __device__ __forceinline__ float2 cmulcf(float2 a, float2 b)      // a * conj(b)
 {
     return make_float2(a.x * b.x + a.y * b.y, a.y * b.x - a.x * b.y);
 }
-// exp(-2 pi i e / M) for 0 <= e < M <= 2^22 (e / M is exact in fp32)
+// exp(-2 pi i e / M) for 0 <= e < M <= 2^22, inv_half_m = 2 / M: e / M is exact in fp32 and goes straight to
+// the hardware sine and cosine, which take their argument in revolutions (two quarter-rate instructions
+// instead of the ~25 of the library routine).  Their absolute error over every e / 2^22 measures 1.3e-7, far
+// below the 16-bit roundings of the values these twiddles multiply.
 __device__ __forceinline__ float2 wm(int e, float inv_half_m)
 {
-    float s, c;
-    sincospif((float)e * inv_half_m, &s, &c);
-    return make_float2(c, -s);
+    const float rev = (float)e * (0.5f * inv_half_m);
+    return make_float2(__builtin_amdgcn_cosf(rev), -__builtin_amdgcn_sinf(rev));
 }
 
 template <bool F16> __device__ __forceinline__ uint16_t cv16(float v)
@@ -125,7 +127,10 @@ struct OuterGeo {
 // Step 1: for every b2 < RB the length-RA transform over a (unless FULLN, inputs a >= RA/2 are the
 // implicit zeros), times W_No^{ka b2}, into the fp32 LDS tile T[ka*RB + b2][c].  Step 2: for every ka the
 // length-RB transform over b2, times W_M^{r ko} (ko = ka + RA kb, by recurrence over kb), to S.
-template <bool F16, int RA, int RB, int CV, bool FULLN, bool GATED>
+// EXACT (all four outer kernels): N is even and equals the input length the instantiation is for (M/2, or M
+// with FULLN), so every load of u and store of y is in range, 4-byte aligned and unconditional: the compiler
+// can then issue a thread's loads back to back instead of one guarded load at a time.
+template <bool F16, int RA, int RB, int CV, bool FULLN, bool GATED, bool EXACT>
 __global__ void __launch_bounds__(TB, 4) k_outer_fwd(const uint16_t *__restrict__ u, uint32_t *__restrict__ S, int CT,
                                                  int B, int H, int N, int64_t M, int ko_lo, int ko_hi,
                                                  const uint16_t *__restrict__ wg, LaunchGate gate)
@@ -147,7 +152,7 @@ __global__ void __launch_bounds__(TB, 4) k_outer_fwd(const uint16_t *__restrict_
     // input gate of the gated form (same shape as u), multiplied in as the samples arrive; nullptr = none
     const uint16_t *g0 = GATED ? wg + ((size_t)b0 * H + h) * N : nullptr;
     const uint16_t *g1 = GATED ? wg + ((size_t)(b0 + (two ? 1 : 0)) * H + h) * N : nullptr;
-    const bool wide = CV == 2 && N % 2 == 0;       // rows start 4-byte aligned
+    const bool wide = CV == 2 && (EXACT || N % 2 == 0);       // rows start 4-byte aligned
     const int CG = CT / CV;                        // column groups, a power of two
     const int lgCG = 31 - __builtin_clz(CG);
     for (int j = tid; j < No; j += TB) wno[j] = wm(j, 2.0f / (float)No);
@@ -161,7 +166,7 @@ __global__ void __launch_bounds__(TB, 4) k_outer_fwd(const uint16_t *__restrict_
             in0[a] = in1[a] = 0;
             uint32_t gt0 = 0, gt1 = 0;
             if (wide) {
-                if (n < N) {
+                if (EXACT || n < N) {
                     in0[a] = *(const uint32_t *)(row0 + n);
                     if (two) in1[a] = *(const uint32_t *)(row1 + n);
                     if constexpr (GATED) {
@@ -172,7 +177,7 @@ __global__ void __launch_bounds__(TB, 4) k_outer_fwd(const uint16_t *__restrict_
             } else {
 #pragma unroll
                 for (int v = 0; v < CV; ++v)
-                    if (n + v < N) {
+                    if (EXACT || n + v < N) {
                         in0[a] |= (uint32_t)row0[n + v] << (16 * v);
                         if (two) in1[a] |= (uint32_t)row1[n + v] << (16 * v);
                         if constexpr (GATED) {
@@ -253,7 +258,7 @@ __global__ void __launch_bounds__(TB, 4) k_outer_fwd(const uint16_t *__restrict_
 }
 
 // ---- pass C: S -> conjugate twiddle -> outer inverse DFT -> the two real rows of the pair
-template <bool F16, int RA, int RB, int CV, bool FULLN, bool GATED, bool MIRROR>
+template <bool F16, int RA, int RB, int CV, bool FULLN, bool GATED, bool MIRROR, bool EXACT>
 __global__ void __launch_bounds__(TB, 4) k_outer_inv(const uint32_t *__restrict__ S, uint16_t *__restrict__ y, int CT,
                                                  int B, int H, int N, int64_t M, int ko_lo, int ko_hi, int mirror_from,
                                                  const uint16_t *__restrict__ vg, LaunchGate gate)
@@ -270,7 +275,7 @@ __global__ void __launch_bounds__(TB, 4) k_outer_inv(const uint32_t *__restrict_
     const int pair = ph / H, h = ph % H;
     const int b0 = 2 * pair;
     const bool two = b0 + 1 < B;
-    const bool wide = CV == 2 && N % 2 == 0;
+    const bool wide = CV == 2 && (EXACT || N % 2 == 0);
     const int CG = CT / CV;
     const int lgCG = 31 - __builtin_clz(CG);
     for (int j = tid; j < No; j += TB) wno[j] = wm(j, 2.0f / (float)No);
@@ -292,16 +297,32 @@ __global__ void __launch_bounds__(TB, 4) k_outer_inv(const uint32_t *__restrict_
             const int ko = ka + RA * kb;
             // ko = ka + RA kb > No/2 = RA RB/2, written so that only kb == RB/2 depends on the thread
             const bool mir = MIRROR && (RB == 1 ? ka > RA / 2 : (kb > RB / 2 || (kb == RB / 2 && ka > 0)));
-            const uint32_t *src = &S[((size_t)ph * No + (mir ? No - ko : ko)) * MI + r0 + c];
-            if (ko >= ko_lo && ko < ko_hi) {                  // zeroed part of the spectrum: the row is zero
-#pragma unroll
-                for (int v = 0; v < CV; ++v) in[kb][v] = 0;
-            } else if constexpr (CV == 2) {
+            // zeroed part of the spectrum: the row counts as zero and was never written.  The load stays
+            // unconditional (of row 0 instead, its value discarded), so that a thread's loads go out back to
+            // back: behind a branch each of them would be waited for before the next is issued.
+            const bool dead = ko >= ko_lo && ko < ko_hi;
+            const uint32_t *src = &S[((size_t)ph * No + (dead ? 0 : (mir ? No - ko : ko))) * MI + r0 + c];
+            if constexpr (CV == 2) {
                 const uint2 t = *(const uint2 *)src;
                 in[kb][0] = t.x;
                 in[kb][1] = t.y;
             } else {
                 in[kb][0] = *src;
+            }
+        }
+        // (an empty statement that reads the loaded words: without it the compiler moves each load back under its
+        //  condition)
+#pragma unroll
+        for (int kb = 0; kb < RB; ++kb)
+#pragma unroll
+            for (int v = 0; v < CV; ++v) asm volatile("" ::"v"(in[kb][v]));
+#pragma unroll
+        for (int kb = 0; kb < RB; ++kb) {
+            const int ko = ka + RA * kb;
+            const bool mir = MIRROR && (RB == 1 ? ka > RA / 2 : (kb > RB / 2 || (kb == RB / 2 && ka > 0)));
+            if (ko >= ko_lo && ko < ko_hi) {
+#pragma unroll
+                for (int v = 0; v < CV; ++v) in[kb][v] = 0;
             }
             if (mir) {                                        // conjugate: the imaginary part is the upper half
 #pragma unroll
@@ -369,7 +390,7 @@ __global__ void __launch_bounds__(TB, 4) k_outer_inv(const uint32_t *__restrict_
         for (int a = 0; a < RAIN; ++a) {
             const int64_t n = (int64_t)(a * RB + b2) * MI + r0 + c;
             if (wide) {
-                if (n < N) {
+                if (EXACT || n < N) {
                     if constexpr (GATED) {
                         o0[a] = mul_pair16<F16>(o0[a], *(const uint32_t *)(g0 + n));
                         if (two) o1[a] = mul_pair16<F16>(o1[a], *(const uint32_t *)(g1 + n));
@@ -380,7 +401,7 @@ __global__ void __launch_bounds__(TB, 4) k_outer_inv(const uint32_t *__restrict_
             } else {
 #pragma unroll
                 for (int v = 0; v < CV; ++v)
-                    if (n + v < N) {
+                    if (EXACT || n + v < N) {
                         uint32_t a0 = (o0[a] >> (16 * v)) & 0xffffu, a1 = (o1[a] >> (16 * v)) & 0xffffu;
                         if constexpr (GATED) {
                             a0 = mul_pair16<F16>(a0, g0[n + v]) & 0xffffu;
@@ -404,7 +425,7 @@ __global__ void __launch_bounds__(TB, 4) k_outer_inv(const uint32_t *__restrict_
 //            z = IDFT_No(U_c + i U_{c+1}): its real part is column c of y, its imaginary part column c+1.
 // One block = 2 CG consecutive columns of one channel, T[No][CG] in LDS; a 16-bit pair of adjacent samples
 // is one 32-bit word, so a wave moves whole 128-byte lines of u and y.
-template <bool F16, int RA, int RB, bool FULLN, bool GATED>
+template <bool F16, int RA, int RB, bool FULLN, bool GATED, bool EXACT>
 __global__ void __launch_bounds__(TB, 4) k_outer_fwd_real(const uint16_t *__restrict__ u, uint32_t *__restrict__ S, int CG,
                                                       int H, int N, int64_t M, int ko_lo, const uint16_t *__restrict__ wg,
                                                       LaunchGate gate)
@@ -421,7 +442,7 @@ __global__ void __launch_bounds__(TB, 4) k_outer_fwd_real(const uint16_t *__rest
     const int h = blockIdx.y;
     const uint16_t *row0 = u + (size_t)h * N;
     const uint16_t *g0 = GATED ? wg + (size_t)h * N : nullptr;
-    const bool wide = N % 2 == 0;                  // rows start 4-byte aligned
+    const bool wide = EXACT || N % 2 == 0;         // rows start 4-byte aligned
     for (int j = tid; j < No; j += TB) wno[j] = wm(j, 2.0f / (float)No);
     __syncthreads();
     // step 1: length-RA transforms over a, times W_No^{ka b2}
@@ -435,14 +456,14 @@ __global__ void __launch_bounds__(TB, 4) k_outer_fwd_real(const uint16_t *__rest
                 const int64_t n = (int64_t)(a * RB + b2) * MI + r0 + 2 * cg;
                 uint32_t wd = 0, gt = 0;
                 if (wide) {
-                    if (n < N) {
+                    if (EXACT || n < N) {
                         wd = *(const uint32_t *)(row0 + n);
                         if constexpr (GATED) gt = *(const uint32_t *)(g0 + n);
                     }
                 } else {
 #pragma unroll
                     for (int v = 0; v < 2; ++v)
-                        if (n + v < N) {
+                        if (EXACT || n + v < N) {
                             wd |= (uint32_t)row0[n + v] << (16 * v);
                             if constexpr (GATED) gt |= (uint32_t)g0[n + v] << (16 * v);
                         }
@@ -494,7 +515,7 @@ __global__ void __launch_bounds__(TB, 4) k_outer_fwd_real(const uint16_t *__rest
     }
 }
 
-template <bool F16, int RA, int RB, bool FULLN, bool GATED>
+template <bool F16, int RA, int RB, bool FULLN, bool GATED, bool EXACT>
 __global__ void __launch_bounds__(TB, 4) k_outer_inv_real(const uint32_t *__restrict__ S, uint16_t *__restrict__ y, int CG,
                                                       int H, int N, int64_t M, int ko_lo, const uint16_t *__restrict__ vg,
                                                       LaunchGate gate)
@@ -509,7 +530,7 @@ __global__ void __launch_bounds__(TB, 4) k_outer_inv_real(const uint32_t *__rest
     const int r0 = blockIdx.x * 2 * CG;
     const int lgCG = 31 - __builtin_clz(CG);       // CG is a power of two
     const int h = blockIdx.y;
-    const bool wide = N % 2 == 0;
+    const bool wide = EXACT || N % 2 == 0;
     for (int j = tid; j < No; j += TB) wno[j] = wm(j, 2.0f / (float)No);
     __syncthreads();
     const float ihm = 2.0f / (float)M;
@@ -527,8 +548,20 @@ __global__ void __launch_bounds__(TB, 4) k_outer_inv_real(const uint32_t *__rest
             // ko > No/2, written so that only kb == RB/2 depends on the thread
             const bool mir = RB == 1 ? ka > RA / 2 : (kb > RB / 2 || (kb == RB / 2 && ka > 0));
             const int kr = mir ? No - ko : ko;                // the row that holds it, <= No/2
-            in[kb] = make_uint2(0, 0);                        // rows from ko_lo on: zeroed bins of a sparse filter, never written
-            if (kr < ko_lo) in[kb] = *(const uint2 *)&S[((size_t)h * No + kr) * MI + r];
+            // rows from ko_lo on: zeroed bins of a sparse filter, never written; they count as zero (the load stays
+            // unconditional, of row 0 instead, see k_outer_inv)
+            in[kb] = *(const uint2 *)&S[((size_t)h * No + (kr < ko_lo ? kr : 0)) * MI + r];
+        }
+        // (an empty statement that reads the loaded words: without it the compiler moves each load back under its
+        //  condition)
+#pragma unroll
+        for (int kb = 0; kb < RB; ++kb) asm volatile("" ::"v"(in[kb].x), "v"(in[kb].y));
+#pragma unroll
+        for (int kb = 0; kb < RB; ++kb) {
+            const int ko = ka + RA * kb;
+            const bool mir = RB == 1 ? ka > RA / 2 : (kb > RB / 2 || (kb == RB / 2 && ka > 0));
+            const int kr = mir ? No - ko : ko;
+            if (kr >= ko_lo) in[kb] = make_uint2(0, 0);
             if (mir) {                                        // conjugate: the imaginary part is the upper half
                 in[kb].x ^= 0x80000000u;
                 in[kb].y ^= 0x80000000u;
@@ -570,14 +603,14 @@ __global__ void __launch_bounds__(TB, 4) k_outer_inv_real(const uint32_t *__rest
             const int64_t n = (int64_t)(a * RB + b2) * MI + r0 + 2 * cg;
             uint32_t o = (uint32_t)cv16<F16>(x[a].x) | ((uint32_t)cv16<F16>(x[a].y) << 16);
             if (wide) {
-                if (n < N) {
+                if (EXACT || n < N) {
                     if constexpr (GATED) o = mul_pair16<F16>(o, *(const uint32_t *)(g0 + n));
                     *(uint32_t *)(row0 + n) = o;
                 }
             } else {
 #pragma unroll
                 for (int v = 0; v < 2; ++v)
-                    if (n + v < N) {
+                    if (EXACT || n + v < N) {
                         uint32_t a0 = (o >> (16 * v)) & 0xffffu;
                         if constexpr (GATED) a0 = mul_pair16<F16>(a0, g0[n + v]) & 0xffffu;
                         row0[n + v] = (uint16_t)a0;
@@ -615,7 +648,7 @@ OuterGeo outer_geo(int64_t M)
     return g;
 }
 
-template <bool F16, int RA, int RB, bool FULLN, bool GATED>
+template <bool F16, int RA, int RB, bool FULLN, bool GATED, bool EXACT>
 int launch_outer_t(bool inverse, const OuterGeo &g, dim3 grid, const void *src, void *dst, int B, int H, int N, int64_t M,
                    hipStream_t s, int ko_lo, int ko_hi, int mirror_from, const void *gate)
 {
@@ -624,34 +657,39 @@ int launch_outer_t(bool inverse, const OuterGeo &g, dim3 grid, const void *src, 
     constexpr int CTC = MI / (RA * RB) < 32 ? 32 : MI / (RA * RB);
     constexpr int CV = (RB <= 16 && RA * CTC / 2 >= TB) ? 2 : 1;
     const size_t lds = sizeof(float2) * ((size_t)g.No + (size_t)g.No * g.CT);
-    FC_TRY(raise_dynamic_lds((const void *)k_outer_fwd<F16, RA, RB, CV, FULLN, GATED>, 160 * 1024));
-    FC_TRY(raise_dynamic_lds((const void *)k_outer_inv<F16, RA, RB, CV, FULLN, GATED, false>, 160 * 1024));
-    FC_TRY(raise_dynamic_lds((const void *)k_outer_inv<F16, RA, RB, CV, FULLN, GATED, true>, 160 * 1024));
+    FC_TRY(raise_dynamic_lds((const void *)k_outer_fwd<F16, RA, RB, CV, FULLN, GATED, EXACT>, 160 * 1024));
+    FC_TRY(raise_dynamic_lds((const void *)k_outer_inv<F16, RA, RB, CV, FULLN, GATED, false, EXACT>, 160 * 1024));
+    FC_TRY(raise_dynamic_lds((const void *)k_outer_inv<F16, RA, RB, CV, FULLN, GATED, true, EXACT>, 160 * 1024));
     if (!inverse)
-        hipLaunchKernelGGL((k_outer_fwd<F16, RA, RB, CV, FULLN, GATED>), grid, dim3(TB), lds, s, (const uint16_t *)src,
+        hipLaunchKernelGGL((k_outer_fwd<F16, RA, RB, CV, FULLN, GATED, EXACT>), grid, dim3(TB), lds, s, (const uint16_t *)src,
                            (uint32_t *)dst, g.CT, B, H, N, M, ko_lo, ko_hi, (const uint16_t *)gate, launch_gate());
     else if (mirror_from < g.No)
-        hipLaunchKernelGGL((k_outer_inv<F16, RA, RB, CV, FULLN, GATED, true>), grid, dim3(TB), lds, s, (const uint32_t *)src,
+        hipLaunchKernelGGL((k_outer_inv<F16, RA, RB, CV, FULLN, GATED, true, EXACT>), grid, dim3(TB), lds, s, (const uint32_t *)src,
                            (uint16_t *)dst, g.CT, B, H, N, M, ko_lo, ko_hi, mirror_from, (const uint16_t *)gate, launch_gate());
     else
-        hipLaunchKernelGGL((k_outer_inv<F16, RA, RB, CV, FULLN, GATED, false>), grid, dim3(TB), lds, s, (const uint32_t *)src,
+        hipLaunchKernelGGL((k_outer_inv<F16, RA, RB, CV, FULLN, GATED, false, EXACT>), grid, dim3(TB), lds, s, (const uint32_t *)src,
                            (uint16_t *)dst, g.CT, B, H, N, M, ko_lo, ko_hi, mirror_from, (const uint16_t *)gate, launch_gate());
     FC_HIP(hipGetLastError());
     return FFTCONV_OK;
 }
 
-// the half-input instantiation needs an outer transform (No >= 2) and N <= M/2
+// the half-input instantiation needs an outer transform (No >= 2) and N <= M/2; EXACT: N is even and fills its
+// half (or, FULLN, the whole transform), so that no load or store needs a range check (ungated calls only)
 template <bool F16, int RA, int RB>
 int launch_outer(bool inverse, const OuterGeo &g, dim3 grid, const void *src, void *dst, int B, int H, int N, int64_t M,
                  hipStream_t s, int ko_lo, int ko_hi, int mirror_from, const void *gate)
 {
+#define FFTCONV_OUTER(FULLN, GATED, EXACT) \
+    launch_outer_t<F16, RA, RB, FULLN, GATED, EXACT>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi, mirror_from, gate)
     if constexpr (RA >= 2) {
-        if ((int64_t)N <= M / 2)
-            return gate ? launch_outer_t<F16, RA, RB, false, true>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi, mirror_from, gate)
-                        : launch_outer_t<F16, RA, RB, false, false>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi, mirror_from, gate);
+        if ((int64_t)N <= M / 2) {
+            if (gate) return FFTCONV_OUTER(false, true, false);
+            return (int64_t)N == M / 2 && N % 2 == 0 ? FFTCONV_OUTER(false, false, true) : FFTCONV_OUTER(false, false, false);
+        }
     }
-    return gate ? launch_outer_t<F16, RA, RB, true, true>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi, mirror_from, gate)
-                : launch_outer_t<F16, RA, RB, true, false>(inverse, g, grid, src, dst, B, H, N, M, s, ko_lo, ko_hi, mirror_from, gate);
+    if (gate) return FFTCONV_OUTER(true, true, false);
+    return (int64_t)N == M && N % 2 == 0 ? FFTCONV_OUTER(true, false, true) : FFTCONV_OUTER(true, false, false);
+#undef FFTCONV_OUTER
 }
 
 template <bool F16>
@@ -683,24 +721,28 @@ int launch_outer_real(bool inverse, const OuterGeo &g, const void *src, void *ds
     const size_t lds = sizeof(float2) * ((size_t)g.No + (size_t)g.No * g.CT);
     const dim3 grid((unsigned)(MI / (2 * g.CT)), (unsigned)H);
     const bool fulln = (int64_t)N > M / 2;
-#define FFTCONV_REAL_LAUNCH(FULLN, GATED)                                                                                   \
+#define FFTCONV_REAL_LAUNCH(FULLN, GATED, EXACT)                                                                                  \
     do {                                                                                                                    \
         if (!inverse) {                                                                                                     \
-            FC_TRY(raise_dynamic_lds((const void *)k_outer_fwd_real<F16, RA, RB, FULLN, GATED>, 160 * 1024));               \
-            hipLaunchKernelGGL((k_outer_fwd_real<F16, RA, RB, FULLN, GATED>), grid, dim3(TB), lds, s, (const uint16_t *)src, \
+            FC_TRY(raise_dynamic_lds((const void *)k_outer_fwd_real<F16, RA, RB, FULLN, GATED, EXACT>, 160 * 1024));               \
+            hipLaunchKernelGGL((k_outer_fwd_real<F16, RA, RB, FULLN, GATED, EXACT>), grid, dim3(TB), lds, s, (const uint16_t *)src, \
                                (uint32_t *)dst, g.CT, H, N, M, ko_lo, (const uint16_t *)gate, launch_gate());               \
         } else {                                                                                                            \
-            FC_TRY(raise_dynamic_lds((const void *)k_outer_inv_real<F16, RA, RB, FULLN, GATED>, 160 * 1024));               \
-            hipLaunchKernelGGL((k_outer_inv_real<F16, RA, RB, FULLN, GATED>), grid, dim3(TB), lds, s, (const uint32_t *)src, \
+            FC_TRY(raise_dynamic_lds((const void *)k_outer_inv_real<F16, RA, RB, FULLN, GATED, EXACT>, 160 * 1024));               \
+            hipLaunchKernelGGL((k_outer_inv_real<F16, RA, RB, FULLN, GATED, EXACT>), grid, dim3(TB), lds, s, (const uint32_t *)src, \
                                (uint16_t *)dst, g.CT, H, N, M, ko_lo, (const uint16_t *)gate, launch_gate());               \
         }                                                                                                                   \
     } while (0)
+    // exact: N is even and fills its half (or the whole transform): no range checks (ungated calls only)
+    const bool exact = N % 2 == 0 && (int64_t)N == (fulln ? M : M / 2);
     if (fulln) {
-        if (gate) FFTCONV_REAL_LAUNCH(true, true);
-        else FFTCONV_REAL_LAUNCH(true, false);
+        if (gate) FFTCONV_REAL_LAUNCH(true, true, false);
+        else if (exact) FFTCONV_REAL_LAUNCH(true, false, true);
+        else FFTCONV_REAL_LAUNCH(true, false, false);
     } else {
-        if (gate) FFTCONV_REAL_LAUNCH(false, true);
-        else FFTCONV_REAL_LAUNCH(false, false);
+        if (gate) FFTCONV_REAL_LAUNCH(false, true, false);
+        else if (exact) FFTCONV_REAL_LAUNCH(false, false, true);
+        else FFTCONV_REAL_LAUNCH(false, false, false);
     }
 #undef FFTCONV_REAL_LAUNCH
     FC_HIP(hipGetLastError());
