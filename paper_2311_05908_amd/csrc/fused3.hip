@@ -80,9 +80,23 @@ __global__ void __launch_bounds__(FILT_THREADS) k_filter_fused3(const float *__r
     constexpr int M = 8192;
     const int Ms = M / groups, N1s = N1 / groups;
     const int64_t h = blockIdx.x;
-    for (int n = threadIdx.x; n < Ms; n += FILT_THREADS) {
+    // all taps of the thread are requested before the first is used (a tap beyond Nk reads tap 0 and is discarded:
+    // behind a branch every load would be waited for in turn)
+    constexpr int TPT = M / FILT_THREADS;
+    float tap[TPT];
+#pragma unroll
+    for (int j = 0; j < TPT; ++j) {
+        const int n = threadIdx.x + j * FILT_THREADS;
         const int t = (reversed && n != 0) ? Ms - n : n;
-        XF[lds_slot(n)] = make_float2(t < Nk ? k[h * Nk + t] : 0.f, 0.f);
+        tap[j] = k[h * Nk + ((n < Ms && t < Nk) ? t : 0)];
+    }
+#pragma unroll
+    for (int j = 0; j < TPT; ++j) asm volatile("" ::"v"(tap[j]));
+#pragma unroll
+    for (int j = 0; j < TPT; ++j) {
+        const int n = threadIdx.x + j * FILT_THREADS;
+        const int t = (reversed && n != 0) ? Ms - n : n;
+        if (n < Ms) XF[lds_slot(n)] = make_float2(t < Nk ? tap[j] : 0.f, 0.f);
     }
     __syncthreads();
     lds_forward(XF, w, fl, Ms, tws);

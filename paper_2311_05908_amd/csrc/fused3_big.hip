@@ -279,9 +279,16 @@ __global__ void __launch_bounds__(NT, (N2 == 16 && !GATED) ? 4 : 2) k_fused3_big
                 pre[j] = v;
             }
             if constexpr (GATED) {
-                uint4 g = make_uint4(0, 0, 0, 0);
-                if (wg && ok) g = *(const uint4 *)(wg + (row - u) + n);
-                prew[j] = g;
+                // a missing gate is read from u instead and never multiplied in: the load then needs no branch
+                // (behind one, every gate chunk was waited for before the next load went out)
+                const uint16_t *wsrc = wg ? wg : u;
+                if constexpr (FULL) {
+                    prew[j] = *(const uint4 *)(wsrc + (row - u) + n);
+                } else {
+                    uint4 g = make_uint4(0, 0, 0, 0);
+                    if (ok) g = *(const uint4 *)(wsrc + (row - u) + n);
+                    prew[j] = g;
+                }
             }
         }
     };
@@ -294,9 +301,14 @@ __global__ void __launch_bounds__(NT, (N2 == 16 && !GATED) ? 4 : 2) k_fused3_big
                 const int s = j / (NCH / 2);
                 const int n = (tid + NT * (j % (NCH / 2))) * 8;
                 const int b = 2 * pair + s;
-                uint4 g = make_uint4(0, 0, 0, 0);
-                if (vg && (FULL || (b < B && n < N))) g = *(const uint4 *)(vg + ((size_t)b * H + h) * N + n);
-                prev[j] = g;
+                const uint16_t *vsrc = vg ? vg : u;               // see the input gate
+                if constexpr (FULL) {
+                    prev[j] = *(const uint4 *)(vsrc + ((size_t)b * H + h) * N + n);
+                } else {
+                    uint4 g = make_uint4(0, 0, 0, 0);
+                    if (b < B && n < N) g = *(const uint4 *)(vsrc + ((size_t)b * H + h) * N + n);
+                    prev[j] = g;
+                }
             }
         }
     };
@@ -905,6 +917,7 @@ __global__ void __launch_bounds__(DK_BLK_THREADS) k_big_dk_blocks(const float2 *
     __shared__ float2 XS[BLK + BLK / 16];
     const int d0 = blockIdx.x;
     const int64_t h = blockIdx.y;
+#pragma unroll
     for (int i = threadIdx.x; i < BLK; i += DK_BLK_THREADS) {
         const int k1 = d0 + 16 * (i / RUN), j = i % RUN;                       // slot (k1, j) of dk_f[h]
         const int lane = j % 64, r = (j / 64) % 4, t3 = (j / 256) % 2, t2 = (j / 512) % R2;
@@ -955,28 +968,43 @@ __global__ void __launch_bounds__(BIG_FILT_THREADS) k_filter_big(const float *__
     constexpr int BM = BigGeo<N2>::M, MH = BM / 2, R2 = BigGeo<N2>::R2;
     const int64_t h = blockIdx.x;
     const float *row = k + h * Nk;
-    for (int n = threadIdx.x; n < MH; n += BIG_FILT_THREADS)
-        ZF[lds_slot(n)] = make_float2(2 * n < Nk ? row[2 * n] : 0.f, 2 * n + 1 < Nk ? row[2 * n + 1] : 0.f);
+    // all taps of the thread are requested before the first is used (a tap beyond Nk reads tap 0 and is discarded:
+    // behind a branch every load would be waited for in turn)
+    constexpr int TPT = MH / BIG_FILT_THREADS;
+    float ta[TPT], tb[TPT];
+#pragma unroll
+    for (int j = 0; j < TPT; ++j) {
+        const int n = threadIdx.x + j * BIG_FILT_THREADS;
+        ta[j] = row[2 * n < Nk ? 2 * n : 0];
+        tb[j] = row[2 * n + 1 < Nk ? 2 * n + 1 : 0];
+    }
+#pragma unroll
+    for (int j = 0; j < TPT; ++j) asm volatile("" ::"v"(ta[j]), "v"(tb[j]));
+#pragma unroll
+    for (int j = 0; j < TPT; ++j) {
+        const int n = threadIdx.x + j * BIG_FILT_THREADS;
+        ZF[lds_slot(n)] = make_float2(2 * n < Nk ? ta[j] : 0.f, 2 * n + 1 < Nk ? tb[j] : 0.f);
+    }
     __syncthreads();
     lds_forward(ZF, w, flh, MH, 2);
+    // (straight-line body, four entries per trip: the twiddle gathers of a trip are then in flight together)
+#pragma unroll 4
     for (int d = threadIdx.x; d < BM; d += BIG_FILT_THREADS) {
         const int lane = d % 64, r = (d / 64) % 4, t3 = (d / 256) % 2, t2 = (d / 512) % R2, k1 = d / (512 * R2);
         const int k2 = big_tau<N2>(16 * t2 + lane % 16), k3 = big_sigma(16 * t3 + 4 * (lane / 16) + r);
         const int f = k1 + 32 * k2 + 32 * N2 * k3;
         const int fe = f <= MH ? f : BM - f;              // K[f] = conj K[M - f]
-        float2 v;
-        if (fe == MH) {
-            const float2 z0 = ZF[lds_slot(0)];
-            v = make_float2(z0.x - z0.y, 0.f);
-        } else {
-            const float2 za = ZF[lds_slot(lds_pos(fe, flh, MH))];
-            const float2 zc = ZF[lds_slot(lds_pos((MH - fe) % MH, flh, MH))];
-            const float2 e = make_float2(0.5f * (za.x + zc.x), 0.5f * (za.y - zc.y));
-            const float2 o = make_float2(0.5f * (za.y + zc.y), -0.5f * (za.x - zc.x));      // (za - conj zc) / (2i)
-            v = cmul(o, w[fe]);
-            v.x += e.x;
-            v.y += e.y;
-        }
+        const bool nyq = fe == MH;                        // the bin M/2: Z[0].re - Z[0].im
+        const int fa = nyq ? 0 : fe;
+        const float2 tw = w[fa];
+        const float2 za = ZF[lds_slot(lds_pos(fa, flh, MH))];
+        const float2 zc = ZF[lds_slot(lds_pos((MH - fa) % MH, flh, MH))];
+        const float2 e = make_float2(0.5f * (za.x + zc.x), 0.5f * (za.y - zc.y));
+        const float2 o = make_float2(0.5f * (za.y + zc.y), -0.5f * (za.x - zc.x));      // (za - conj zc) / (2i)
+        float2 v = cmul(o, tw);
+        v.x += e.x;
+        v.y += e.y;
+        if (nyq) v = make_float2(za.x - za.y, 0.f);
         if ((f > MH) != conj_out) v.y = -v.y;
         const float sc = lds_mask_weight(keep, n_blocks, f, BM) / (float)BM;
         const uint32_t pr = TT::pack(v.x * sc, v.y * sc);                       // (re, im) 16-bit pair

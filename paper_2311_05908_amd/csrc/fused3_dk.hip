@@ -238,6 +238,7 @@ __global__ void __launch_bounds__(DK_FIN_THREADS) k_dk_finish(const float2 *__re
     const int64_t h = blockIdx.x;
     const int per_group = G::M / groups;                     // slots of one group: k1 in [g N1s, (g + 1) N1s)
     for (int g = 0; g < groups; ++g) {
+#pragma unroll 4
         for (int i = threadIdx.x; i < per_group; i += DK_FIN_THREADS) {
             const int d = g * per_group + i;
             const int lane = d % 64, r = (d / 64) % 4, k1 = d / 256;

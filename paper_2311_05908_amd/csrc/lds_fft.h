@@ -67,8 +67,9 @@ template <int R, bool INV, typename V>
 __device__ inline void lds_stage(V *X, const V *__restrict__ w, int M, int Sj, int Rj, int tws)
 {
     const TwTable<V> tw{w};
+    const int lgS = __ffs(Sj) - 1;                 // every length and stride here is a power of two
     for (int t = threadIdx.x; t < M / R; t += blockDim.x) {
-        const int r = t % Sj, prefix = t / Sj;
+        const int r = t & (Sj - 1), prefix = t >> lgS;
         const int base = prefix * (R * Sj) + r;
         V x[R], c[R];
         stage_twiddles<R>(c, tw, (int64_t)Rj * r * tws);

@@ -71,6 +71,38 @@ struct LongTw {
     __device__ __forceinline__ float2 operator()(int64_t e) const { return cmul(hi[e >> 11], lo[e & 2047]); }
 };
 
+// A thread's share of a tile of 8192 points: LPT points LT apart.  All loads of a thread are issued before the
+// first value is used (a loop of load -> LDS write waits for every load in turn, and the round trip to HBM was most
+// of these kernels' time); the launches use LT threads.
+constexpr int LPT = LB / LT;
+// contiguous block: src[i] -> slot i
+__device__ __forceinline__ void load_block(float2 *XL, const float2 *__restrict__ src)
+{
+    float2 v[LPT];
+#pragma unroll
+    for (int j = 0; j < LPT; ++j) v[j] = src[threadIdx.x + j * LT];
+#pragma unroll
+    for (int j = 0; j < LPT; ++j) XL[lds_slot(threadIdx.x + j * LT)] = v[j];
+}
+__device__ __forceinline__ void store_block(const float2 *XL, float2 *__restrict__ dst)
+{
+#pragma unroll
+    for (int j = 0; j < LPT; ++j) dst[threadIdx.x + j * LT] = XL[lds_slot(threadIdx.x + j * LT)];
+}
+// column tile: slot i = a * C + c <- row[a * 8192 + col0 + c] (C a power of two)
+__device__ __forceinline__ void load_cols(float2 *XL, const float2 *__restrict__ row, int C, int col0)
+{
+    const int lgC = __ffs(C) - 1;
+    float2 v[LPT];
+#pragma unroll
+    for (int j = 0; j < LPT; ++j) {
+        const int i = threadIdx.x + j * LT;
+        v[j] = row[(int64_t)(i >> lgC) * LB + col0 + (i & (C - 1))];
+    }
+#pragma unroll
+    for (int j = 0; j < LPT; ++j) XL[lds_slot(threadIdx.x + j * LT)] = v[j];
+}
+
 // One stage of the outer part on a tile X[a][c] (a < A, c < C, slot a * C + c): factor R_ along a at stride
 // Sp, for every column; the twiddle exponent k Rj r uses the position r = rp * 8192 + (first column + c)
 // inside the full-length stage.
@@ -78,9 +110,10 @@ template <int R_, bool INV>
 __device__ inline void cols_stage(float2 *X, const LongTw &w, int A, int C, int Sp, int Rj, int col0)
 {
     const int nb = (A / R_) * C;
+    const int lgC = __ffs(C) - 1, lgSp = __ffs(Sp) - 1;          // powers of two
     for (int t = threadIdx.x; t < nb; t += blockDim.x) {
-        const int c = t % C, q = t / C;
-        const int rp = q % Sp, prefix = q / Sp;
+        const int c = t & (C - 1), q = t >> lgC;
+        const int rp = q & (Sp - 1), prefix = q >> lgSp;
         const int a0 = prefix * R_ * Sp + rp;
         const int64_t rg = (int64_t)rp * LB + col0 + c;
         float2 x[R_], tw[R_];
@@ -117,16 +150,27 @@ __global__ void __launch_bounds__(LT) k_long_fwd_cols(const In *__restrict__ src
     extern __shared__ float2 XL[];
     const int64_t M = (int64_t)A * LB, row = blockIdx.y;
     const int col0 = blockIdx.x * C;
-    for (int i = threadIdx.x; i < LB; i += LT) {
-        const int a = i / C, c = i % C;
-        int64_t n = (int64_t)a * LB + col0 + c;
+    const int lgC = __ffs(C) - 1;
+    // samples beyond `len` are zeros: their loads go to sample 0 instead and are discarded, so that every load of
+    // the thread is unconditional and in flight at once (see load_block)
+    float vr[LPT], vi[LPT];
+#pragma unroll
+    for (int j = 0; j < LPT; ++j) {
+        const int i = threadIdx.x + j * LT;
+        int64_t n = (int64_t)(i >> lgC) * LB + col0 + (i & (C - 1));
         if (reversed && n != 0) n = M - n;
-        float2 v = make_float2(0.f, 0.f);
-        if (n < len) {
-            v.x = ld_real(src_re, row * len + n);
-            if (src_im) v.y = ld_real(src_im, row * len + n);
-        }
-        XL[lds_slot(i)] = v;
+        const int64_t at = row * len + (n < len ? n : 0);
+        vr[j] = ld_real(src_re, at);
+        vi[j] = src_im ? ld_real(src_im, at) : 0.f;
+    }
+#pragma unroll
+    for (int j = 0; j < LPT; ++j) asm volatile("" ::"v"(vr[j]), "v"(vi[j]));      // keeps the loads unconditional
+#pragma unroll
+    for (int j = 0; j < LPT; ++j) {
+        const int i = threadIdx.x + j * LT;
+        int64_t n = (int64_t)(i >> lgC) * LB + col0 + (i & (C - 1));
+        if (reversed && n != 0) n = M - n;
+        XL[lds_slot(i)] = n < len ? make_float2(vr[j], vi[j]) : make_float2(0.f, 0.f);
     }
     __syncthreads();
     int Sp = A, R = 1;
@@ -137,9 +181,10 @@ __global__ void __launch_bounds__(LT) k_long_fwd_cols(const In *__restrict__ src
         __syncthreads();
         R *= Nj;
     }
-    for (int i = threadIdx.x; i < LB; i += LT) {
-        const int a = i / C, c = i % C;
-        tmp[row * M + (int64_t)a * LB + col0 + c] = XL[lds_slot(i)];
+#pragma unroll
+    for (int j = 0; j < LPT; ++j) {
+        const int i = threadIdx.x + j * LT;
+        tmp[row * M + (int64_t)(i >> lgC) * LB + col0 + (i & (C - 1))] = XL[lds_slot(i)];
     }
 }
 
@@ -152,20 +197,27 @@ __global__ void __launch_bounds__(LT) k_long_fwd_blocks(const float2 *__restrict
 {
     extern __shared__ float2 XL[];
     const int64_t base = ((int64_t)blockIdx.y * A + blockIdx.x) * LB;
-    for (int i = threadIdx.x; i < LB; i += LT) XL[lds_slot(i)] = tmp[base + i];
+    load_block(XL, tmp + base);
     __syncthreads();
     lds_forward(XL, w.w8k, flB, LB, 1);
-    for (int i = threadIdx.x; i < LB; i += LT) {
-        const float2 x = XL[lds_slot(i)];
-        if (MODE == 0) {
-            out[base + i] = x;
-        } else {
-            const float2 a = other[base + i];
-            float2 v = make_float2(a.x * x.x + a.y * x.y, a.x * x.y - a.y * x.x);
+    if (MODE == 0) {
+        store_block(XL, out + base);
+    } else {
+        float2 a[LPT], o[LPT];
+#pragma unroll
+        for (int j = 0; j < LPT; ++j) a[j] = other[base + threadIdx.x + j * LT];
+        if (!first) {
+#pragma unroll
+            for (int j = 0; j < LPT; ++j) o[j] = out[base + threadIdx.x + j * LT];
+        }
+#pragma unroll
+        for (int j = 0; j < LPT; ++j) {
+            const int i = threadIdx.x + j * LT;
+            const float2 x = XL[lds_slot(i)];
+            float2 v = make_float2(a[j].x * x.x + a[j].y * x.y, a[j].x * x.y - a[j].y * x.x);
             if (!first) {
-                const float2 o = out[base + i];
-                v.x += o.x;
-                v.y += o.y;
+                v.x += o[j].x;
+                v.y += o[j].y;
             }
             out[base + i] = v;
         }
@@ -183,7 +235,7 @@ __global__ void __launch_bounds__(LT) k_long_fwd_blocks_kf(const float2 *__restr
 {
     extern __shared__ float2 XL[];
     const int64_t base = ((int64_t)blockIdx.y * A + blockIdx.x) * LB;
-    for (int i = threadIdx.x; i < LB; i += LT) XL[lds_slot(i)] = tmp[base + i];
+    load_block(XL, tmp + base);
     __syncthreads();
     lds_forward(XL, w.w8k, flB, LB, 1);
     const int ko = lds_freq(blockIdx.x, flA, A);
@@ -215,10 +267,10 @@ __global__ void __launch_bounds__(LT) k_long_inv_blocks(const float2 *__restrict
 {
     extern __shared__ float2 XL[];
     const int64_t base = ((int64_t)blockIdx.y * A + blockIdx.x) * LB;
-    for (int i = threadIdx.x; i < LB; i += LT) XL[lds_slot(i)] = spec[base + i];
+    load_block(XL, spec + base);
     __syncthreads();
     lds_inverse(XL, w.w8k, flB, LB, 1);
-    for (int i = threadIdx.x; i < LB; i += LT) tmp[base + i] = XL[lds_slot(i)];
+    store_block(XL, tmp + base);
 }
 
 // Inverse, columns: the factors of A, then real part times scale of the samples n < Nk -> dk (rows, Nk).
@@ -229,10 +281,7 @@ __global__ void __launch_bounds__(LT) k_long_inv_cols_dk(const float2 *__restric
     const int64_t M = (int64_t)A * LB, row = blockIdx.y;
     const int col0 = blockIdx.x * C;
     if (col0 >= Nk) return;                                 // every sample of this tile is n >= col0 >= Nk
-    for (int i = threadIdx.x; i < LB; i += LT) {
-        const int a = i / C, c = i % C;
-        XL[lds_slot(i)] = tmp[row * M + (int64_t)a * LB + col0 + c];
-    }
+    load_cols(XL, tmp + row * M, C, col0);
     __syncthreads();
     int Sp = 1, R = A;
     for (int i = flA.nf - 1; i >= 0; --i) {
@@ -243,7 +292,7 @@ __global__ void __launch_bounds__(LT) k_long_inv_cols_dk(const float2 *__restric
         Sp *= Nj;
     }
     for (int i = threadIdx.x; i < LB; i += LT) {
-        const int a = i / C, c = i % C;
+        const int a = i >> (__ffs(C) - 1), c = i & (C - 1);
         const int64_t n = (int64_t)a * LB + col0 + c;
         if (n < Nk) dk[row * Nk + n] = XL[lds_slot(i)].x * scale;
     }
@@ -263,10 +312,18 @@ __global__ void __launch_bounds__(LT) k_rows_conv_lds(const IO *__restrict__ u, 
     const int h = blockIdx.x, b0 = 2 * blockIdx.y;
     const bool two = b0 + 1 < B;
     const int64_t r0 = ((int64_t)b0 * H + h) * N, r1 = r0 + (int64_t)H * N;
-    for (int n = threadIdx.x; n < M; n += LT)
-        XL[lds_slot(n)] = n < N ? make_float2(ld_real(u, r0 + n), two ? ld_real(u, r1 + n) : 0.f) : make_float2(0.f, 0.f);
+    // (a sample beyond N, or of a missing second row, reads a valid one and is discarded: unconditional loads,
+    //  several in flight per thread)
+    const int64_t r1e = two ? r1 : r0;
+#pragma unroll 8
+    for (int n = threadIdx.x; n < M; n += LT) {
+        const int64_t at = n < N ? n : 0;
+        const float a = ld_real(u, r0 + at), b = ld_real(u, r1e + at);
+        XL[lds_slot(n)] = n < N ? make_float2(a, two ? b : 0.f) : make_float2(0.f, 0.f);
+    }
     __syncthreads();
     lds_forward(XL, w, fl, M, 1);
+#pragma unroll 8
     for (int i = threadIdx.x; i < M; i += LT) XL[lds_slot(i)] = cmul(XL[lds_slot(i)], kf[(int64_t)h * M + i]);
     __syncthreads();
     lds_inverse(XL, w, fl, M, 1);
@@ -283,13 +340,20 @@ __global__ void __launch_bounds__(LT) k_long_conv_blocks(float2 *__restrict__ tm
 {
     extern __shared__ float2 XL[];
     const int64_t base = ((int64_t)blockIdx.y * A + blockIdx.x) * LB;
-    for (int i = threadIdx.x; i < LB; i += LT) XL[lds_slot(i)] = tmp[base + i];
+    load_block(XL, tmp + base);
+    float2 kv[LPT];                                          // in flight during the forward transform
+#pragma unroll
+    for (int j = 0; j < LPT; ++j) kv[j] = kf[base + threadIdx.x + j * LT];
     __syncthreads();
     lds_forward(XL, w.w8k, flB, LB, 1);
-    for (int i = threadIdx.x; i < LB; i += LT) XL[lds_slot(i)] = cmul(XL[lds_slot(i)], kf[base + i]);
+#pragma unroll
+    for (int j = 0; j < LPT; ++j) {
+        const int i = threadIdx.x + j * LT;
+        XL[lds_slot(i)] = cmul(XL[lds_slot(i)], kv[j]);
+    }
     __syncthreads();
     lds_inverse(XL, w.w8k, flB, LB, 1);
-    for (int i = threadIdx.x; i < LB; i += LT) tmp[base + i] = XL[lds_slot(i)];
+    store_block(XL, tmp + base);
 }
 
 // Longer rows, last kernel: the outer factors back, real part -> row of y_re, imaginary part -> row of y_im
@@ -302,10 +366,7 @@ __global__ void __launch_bounds__(LT) k_long_inv_cols_y(const float2 *__restrict
     const int64_t M = (int64_t)A * LB, row = blockIdx.y;
     const int col0 = blockIdx.x * C;
     if (col0 >= N) return;
-    for (int i = threadIdx.x; i < LB; i += LT) {
-        const int a = i / C, c = i % C;
-        XL[lds_slot(i)] = tmp[row * M + (int64_t)a * LB + col0 + c];
-    }
+    load_cols(XL, tmp + row * M, C, col0);
     __syncthreads();
     int Sp = 1, R = A;
     for (int i = flA.nf - 1; i >= 0; --i) {
@@ -316,7 +377,7 @@ __global__ void __launch_bounds__(LT) k_long_inv_cols_y(const float2 *__restrict
         Sp *= Nj;
     }
     for (int i = threadIdx.x; i < LB; i += LT) {
-        const int a = i / C, c = i % C;
+        const int a = i >> (__ffs(C) - 1), c = i & (C - 1);
         const int64_t n = (int64_t)a * LB + col0 + c;
         if (n < N) {
             const float2 v = XL[lds_slot(i)];

@@ -160,12 +160,27 @@ __global__ void __launch_bounds__(LDS_ROW_THREADS) k_rows_fwd_lds(const float *_
 {
     extern __shared__ double2 XD[];
     const int64_t row = blockIdx.x;
-    for (int n = threadIdx.x; n < M; n += LDS_ROW_THREADS) {
-        const int t = (reversed && n != 0) ? M - n : n;
-        XD[lds_slot(n)] = make_double2(t < len ? (double)src[row * len + t] : 0.0, 0.0);
+    // (a tap beyond `len` reads tap 0 and is discarded: unconditional loads, several in flight per thread)
+    for (int n0 = threadIdx.x; n0 < M; n0 += 8 * LDS_ROW_THREADS) {
+        float v[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int n = n0 + j * LDS_ROW_THREADS;
+            const int t = (reversed && n != 0) ? M - n : n;
+            v[j] = src[row * len + ((n < M && t < len) ? t : 0)];
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) asm volatile("" ::"v"(v[j]));
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int n = n0 + j * LDS_ROW_THREADS;
+            const int t = (reversed && n != 0) ? M - n : n;
+            if (n < M) XD[lds_slot(n)] = make_double2(t < len ? (double)v[j] : 0.0, 0.0);
+        }
     }
     __syncthreads();
     lds_forward(XD, w, fl, M, tws);
+#pragma unroll 8
     for (int n = threadIdx.x; n < M; n += LDS_ROW_THREADS) spec[row * M + n] = XD[lds_slot(n)];
 }
 
@@ -177,6 +192,7 @@ __global__ void __launch_bounds__(LDS_ROW_THREADS) k_rows_inv_dk_lds(const float
 {
     extern __shared__ float2 XF[];
     const int64_t row = blockIdx.x;
+#pragma unroll 8
     for (int n = threadIdx.x; n < M; n += LDS_ROW_THREADS) XF[lds_slot(n)] = spec[row * M + n];
     __syncthreads();
     lds_inverse(XF, w, fl, M, 1);
