@@ -68,6 +68,21 @@ __device__ inline void lds_stage(V *X, const V *__restrict__ w, int M, int Sj, i
 {
     const TwTable<V> tw{w};
     const int lgS = __ffs(Sj) - 1;                 // every length and stride here is a power of two
+    if (Sj == 1) {
+        // the innermost stage: r = 0, every twiddle is 1 -- no table gathers (each is a trip to L2 that the
+        // butterfly would wait for) and no products
+#pragma unroll 4
+        for (int t = threadIdx.x; t < M / R; t += blockDim.x) {
+            const int base = t * R;
+            V x[R];
+#pragma unroll
+            for (int n = 0; n < R; ++n) x[n] = X[lds_slot(base + n)];
+            dft_reg<R, INV>(x);
+#pragma unroll
+            for (int k = 0; k < R; ++k) X[lds_slot(base + k)] = x[k];
+        }
+        return;
+    }
     for (int t = threadIdx.x; t < M / R; t += blockDim.x) {
         const int r = t & (Sj - 1), prefix = t >> lgS;
         const int base = prefix * (R * Sj) + r;

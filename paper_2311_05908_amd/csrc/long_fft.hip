@@ -142,10 +142,12 @@ __device__ inline void cols_stage_any(float2 *X, const LongTw &w, int A, int C, 
 
 // Forward, columns: rows of real input (re from src_re, im from src_im or zero; `len` valid samples, zeros
 // beyond; reversed: position n holds sample (M - n) mod M) -> tmp (rows, M) after the factors of A.
+// half_rows (real input only, src_im == nullptr): only the blocks of the outer frequency digits ko <= A/2 are
+// written; the others hold mirror images (see k_long_fwd_blocks_kf) and nobody reads them.
 template <typename In>
 __global__ void __launch_bounds__(LT) k_long_fwd_cols(const In *__restrict__ src_re, const In *__restrict__ src_im,
                                                      float2 *__restrict__ tmp, LongTw w, FacList flA, int A, int C, int64_t len,
-                                                     bool reversed)
+                                                     bool reversed, bool half_rows)
 {
     extern __shared__ float2 XL[];
     const int64_t M = (int64_t)A * LB, row = blockIdx.y;
@@ -184,7 +186,9 @@ __global__ void __launch_bounds__(LT) k_long_fwd_cols(const In *__restrict__ src
 #pragma unroll
     for (int j = 0; j < LPT; ++j) {
         const int i = threadIdx.x + j * LT;
-        tmp[row * M + (int64_t)(i >> lgC) * LB + col0 + (i & (C - 1))] = XL[lds_slot(i)];
+        const int ap = i >> lgC;                              // position of the block; its digit: lds_freq()
+        if (!half_rows || 2 * lds_freq(ap, flA, A) <= A)
+            tmp[row * M + (int64_t)ap * LB + col0 + (i & (C - 1))] = XL[lds_slot(i)];
     }
 }
 
@@ -228,36 +232,55 @@ __global__ void __launch_bounds__(LT) k_long_fwd_blocks(const float2 *__restrict
 // bins f = ko + A f' of one outer frequency digit ko (the digit reversal of a'), f' < 8192 in position order; they
 // go straight to that digit's row of k_f, [h][ko][slot of f' in the 8192-point kernel's per-lane order] as 16-bit
 // (re, im) pairs, scaled by 1/M (times the fp16 range boost, multipass_kf_boost) and by the frequency mask.
+// The taps are real, so K[M - f] = conj K[f]: with f = ko + A f', M - f = (A - ko) + A (8191 - f') for ko >= 1.  Only the
+// blocks of the digits ko <= A/2 are transformed (the column kernel wrote no others); a block with 0 < ko < A/2 also
+// writes the row of the digit A - ko, bin g of which is the conjugate of this row's bin 8191 - g.  The rows ko = 0 and
+// ko = A/2 are their own mirror images.
+// natural: tmp holds the rows ko <= A/2 only, in the order of ko (A/2 + 1 blocks per channel: the output of
+// k_filter_outer_real, multipass.hip) instead of all A blocks in position order.  conj_out: the conjugate spectrum
+// (that of the circularly time-reversed taps, which are real).
 template <bool F16>
 __global__ void __launch_bounds__(LT) k_long_fwd_blocks_kf(const float2 *__restrict__ tmp, uint32_t *__restrict__ kf, LongTw w,
                                                           FacList flA, FacList flB, int A, int64_t h0,
-                                                          const uint8_t *__restrict__ keep, int64_t n_blocks)
+                                                          const uint8_t *__restrict__ keep, int64_t n_blocks, bool natural,
+                                                          bool conj_out)
 {
     extern __shared__ float2 XL[];
-    const int64_t base = ((int64_t)blockIdx.y * A + blockIdx.x) * LB;
+    const int ko = natural ? (int)blockIdx.x : lds_freq(blockIdx.x, flA, A);
+    if (2 * ko > A) return;                                   // written by the block of A - ko
+    const int64_t base = natural ? ((int64_t)blockIdx.y * (A / 2 + 1) + ko) * LB : ((int64_t)blockIdx.y * A + blockIdx.x) * LB;
     load_block(XL, tmp + base);
     __syncthreads();
     lds_forward(XL, w.w8k, flB, LB, 1);
-    const int ko = lds_freq(blockIdx.x, flA, A);
     const int M = A * LB;
+    const float boost = (float)multipass_kf_boost(F16, A) / (float)M;
+    typedef __attribute__((ext_vector_type(2))) float f32x2;
+    typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+    typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
+    auto pair16 = [](float re, float im) {                    // round to nearest even, one conversion instruction
+        const f32x2 v = {re, im};
+        if constexpr (F16) return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));
+        else return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+    };
+    // position of inner frequency f after the block transform, for the factors 16, 16, 16, 2 of 8192 (lds_pos()
+    // with the loop over the factor list folded; the launch checks the list)
+    auto pos8k = [](int f) { return ((f & 15) << 9) | (((f >> 4) & 15) << 5) | (((f >> 8) & 15) << 1) | (f >> 12); };
     uint32_t *dst = kf + ((h0 + blockIdx.y) * A + ko) * (int64_t)LB;
+    const bool mirror = ko > 0 && 2 * ko < A;
+    uint32_t *dst_m = kf + ((h0 + blockIdx.y) * A + (mirror ? A - ko : ko)) * (int64_t)LB;
+#pragma unroll 4
     for (int d = threadIdx.x; d < LB; d += LT) {
         const int lane = d % 64, r = (d / 64) % 4, k1 = d / 256;
         const int k2 = lane % 16, k3 = k3_at_index(4 * (lane / 16) + r, 16);
-        const int fi = k1 + 32 * (k2 + 16 * k3);
-        const float2 v = XL[lds_slot(lds_pos(fi, flB, LB))];
-        const float sc = lds_mask_weight(keep, n_blocks, ko + A * fi, M) * (float)multipass_kf_boost(F16, A) / (float)M;
-        uint16_t re, im;
-        if constexpr (F16) {
-            const __half a = __float2half_rn(v.x * sc), b = __float2half_rn(v.y * sc);
-            re = *(const uint16_t *)&a;
-            im = *(const uint16_t *)&b;
-        } else {
-            const __hip_bfloat16 a = __float2bfloat16(v.x * sc), b = __float2bfloat16(v.y * sc);
-            re = *(const uint16_t *)&a;
-            im = *(const uint16_t *)&b;
+        const int fi = k1 + 32 * (k2 + 16 * k3);              // the inner frequency of slot d
+        const float2 v = XL[lds_slot(pos8k(fi))];
+        const float sc = keep ? lds_mask_weight(keep, n_blocks, ko + A * fi, M) * boost : boost;
+        dst[d] = pair16(v.x * sc, conj_out ? -v.y * sc : v.y * sc);
+        if (mirror) {
+            const float2 vm = XL[lds_slot(pos8k(LB - 1 - fi))];
+            const float scm = keep ? lds_mask_weight(keep, n_blocks, (A - ko) + A * fi, M) * boost : boost;
+            dst_m[d] = pair16(vm.x * scm, conj_out ? vm.y * scm : -vm.y * scm);
         }
-        dst[d] = (uint32_t)re | ((uint32_t)im << 16);
     }
 }
 
@@ -406,12 +429,12 @@ int raise_lds(const void *kern) { return raise_dynamic_lds(kern, (int)L_LDS); }
 
 template <typename In>
 int launch_fwd_cols(const LongGeo &g, const In *re, const In *im, float2 *tmp, const LongTw &w, int64_t rows, int64_t len,
-                    bool reversed, hipStream_t s)
+                    bool reversed, hipStream_t s, bool half_rows = false)
 {
     const int rc = raise_lds((const void *)k_long_fwd_cols<In>);
     if (rc) return rc;
     hipLaunchKernelGGL(k_long_fwd_cols<In>, dim3((unsigned)g.A, (unsigned)rows), dim3(LT), L_LDS, s, re, im, tmp, w, g.flA,
-                       g.A, g.C, len, reversed);
+                       g.A, g.C, len, reversed, half_rows && im == nullptr);
     FC_HIP(hipGetLastError());
     return FFTCONV_OK;
 }
@@ -546,17 +569,26 @@ int long_filter_transform(const fftconv_plan *p, const float *k, int64_t Nk, int
 {
     const LongGeo g = long_geo(p->M);
     const LongTw tw = long_tw(p);
-    int rc = launch_fwd_cols<float>(g, k, nullptr, tmp, tw, nh, Nk, adjoint, s);
+    if (g.flB.nf != 4 || g.flB.fac[0] != 16 || g.flB.fac[1] != 16 || g.flB.fac[2] != 16 || g.flB.fac[3] != 2) {
+        set_error("multi-pass filter transform: the block transform's factors are not 16, 16, 16, 2");
+        return FFTCONV_EUNSUPPORTED;
+    }
+    // outer factor: the register kernel of the multi-pass route where it exists for this outer length (rows ko <= A/2
+    // in natural order; the adjoint spectrum is then the conjugate, taken on the way out), else the generic column kernel
+    const bool natural = multipass_filter_outer_ok(p);
+    int rc = natural ? multipass_filter_outer(p, k, Nk, nh, tmp, s)
+                     : launch_fwd_cols<float>(g, k, nullptr, tmp, tw, nh, Nk, adjoint, s, true);
     if (rc) return rc;
     rc = raise_lds((const void *)k_long_fwd_blocks_kf<true>);
     if (!rc) rc = raise_lds((const void *)k_long_fwd_blocks_kf<false>);
     if (rc) return rc;
+    const dim3 grid((unsigned)(natural ? g.A / 2 + 1 : g.A), (unsigned)nh);
     if (p->dtype == FFTCONV_F16)
-        hipLaunchKernelGGL(k_long_fwd_blocks_kf<true>, dim3((unsigned)g.A, (unsigned)nh), dim3(LT), L_LDS, s, tmp,
-                           (uint32_t *)kf, tw, g.flA, g.flB, g.A, h0, keep_dev, n_blocks);
+        hipLaunchKernelGGL(k_long_fwd_blocks_kf<true>, grid, dim3(LT), L_LDS, s, tmp, (uint32_t *)kf, tw, g.flA, g.flB, g.A, h0,
+                           keep_dev, n_blocks, natural, natural && adjoint);
     else
-        hipLaunchKernelGGL(k_long_fwd_blocks_kf<false>, dim3((unsigned)g.A, (unsigned)nh), dim3(LT), L_LDS, s, tmp,
-                           (uint32_t *)kf, tw, g.flA, g.flB, g.A, h0, keep_dev, n_blocks);
+        hipLaunchKernelGGL(k_long_fwd_blocks_kf<false>, grid, dim3(LT), L_LDS, s, tmp, (uint32_t *)kf, tw, g.flA, g.flB, g.A, h0,
+                           keep_dev, n_blocks, natural, natural && adjoint);
     FC_HIP(hipGetLastError());
     return FFTCONV_OK;
 }

@@ -620,6 +620,110 @@ __global__ void __launch_bounds__(TB, 4) k_outer_inv_real(const uint32_t *__rest
     }
 }
 
+// ---- the outer pass of the FILTER transform of a multi-pass plan (fftconv_filter_fft: taps -> k_f): pass A of a
+// lone real row (k_outer_fwd_real above) with fp32 taps in and fp32 rows out.  k_f holds 16-bit constants, so
+// its transform runs in fp32 throughout: this kernel, then the 8192-point transform of every row in LDS
+// (k_long_fwd_blocks_kf, long_fft.hip).  Rows ko <= No/2 only, T2[h][ko][r] (No/2 + 1 rows of 8192 fp32 pairs per
+// channel): the taps are real, the other rows are mirror images that the second kernel writes from these.
+// Taps at and beyond Nk are zeros (their loads read tap 0 and are discarded: no load sits behind a branch).
+template <int RA, int RB, bool FULLN>
+__global__ void __launch_bounds__(TB, 4) k_filter_outer_real(const float *__restrict__ k, float2 *__restrict__ T2, int CG,
+                                                         int64_t Nk, int64_t M, bool wide)
+{
+    extern __shared__ float2 sm[];
+    constexpr int No = RA * RB, NR = No / 2 + 1;
+    constexpr int RAIN = FULLN ? RA : RA / 2;      // outer rows that can hold taps
+    float2 *wno = sm;                              // W_No^j, j < No
+    float2 *T = sm + No;                           // [No][CG]
+    const int tid = threadIdx.x;
+    const int r0 = blockIdx.x * 2 * CG;
+    const int lgCG = 31 - __builtin_clz(CG);       // CG is a power of two
+    const int64_t h = blockIdx.y;
+    const float *row0 = k + h * Nk;
+    for (int j = tid; j < No; j += TB) wno[j] = wm(j, 2.0f / (float)No);
+    __syncthreads();
+    // step 1: length-RA transforms over a, times W_No^{ka b2}; (column c, column c+1) = (re, im)
+    for (int e = tid; e < RB * CG; e += TB) {
+        const int cg = e & (CG - 1), b2 = e >> lgCG;
+        float2 x[RA];
+#pragma unroll
+        for (int a = 0; a < RA; ++a) x[a] = make_float2(0.f, 0.f);
+#pragma unroll
+        for (int a = 0; a < RAIN; ++a) {
+            const int64_t n = (int64_t)(a * RB + b2) * MI + r0 + 2 * cg;
+            if (wide) {                            // Nk even, rows 8-byte aligned: a pair is inside or outside as a whole
+                x[a] = *(const float2 *)(row0 + (n < Nk ? n : 0));
+            } else {
+                x[a].x = row0[n < Nk ? n : 0];
+                x[a].y = row0[n + 1 < Nk ? n + 1 : 0];
+            }
+        }
+#pragma unroll
+        for (int a = 0; a < RAIN; ++a) asm volatile("" ::"v"(x[a].x), "v"(x[a].y));      // keeps the loads unconditional
+#pragma unroll
+        for (int a = 0; a < RAIN; ++a) {
+            const int64_t n = (int64_t)(a * RB + b2) * MI + r0 + 2 * cg;
+            if (n >= Nk) x[a].x = 0.f;
+            if (n + 1 >= Nk) x[a].y = 0.f;
+        }
+        dft_reg<RA, false>(x);
+#pragma unroll
+        for (int ka = 0; ka < RA; ++ka) T[(ka * RB + b2) * CG + cg] = cmulf(x[ka], wno[ka * b2]);
+    }
+    __syncthreads();
+    // step 2: length-RB transforms over b2, in place: slot ka*RB + kb then holds Z[ko], ko = ka + RA kb
+    for (int e = tid; e < RA * CG; e += TB) {
+        const int cg = e & (CG - 1), ka = e >> lgCG;
+        float2 x[RB];
+#pragma unroll
+        for (int b2 = 0; b2 < RB; ++b2) x[b2] = T[(ka * RB + b2) * CG + cg];
+        dft_reg<RB, false>(x);
+#pragma unroll
+        for (int kb = 0; kb < RB; ++kb) T[(ka * RB + kb) * CG + cg] = x[kb];
+    }
+    __syncthreads();
+    // step 3: split the two columns, twiddle (by recurrence over kb), store the rows ko <= No/2
+    const float ihm = 2.0f / (float)M;
+    const int Mmask = (int)M - 1;                  // M is a power of two, at most 2^22, and so is every r * ko
+    for (int e = tid; e < RA * CG; e += TB) {
+        const int cg = e & (CG - 1), ka = e >> lgCG;
+        const int r = r0 + 2 * cg;
+        float2 w0 = wm((r * ka) & Mmask, ihm), w1 = wm(((r + 1) * ka) & Mmask, ihm);
+        const float2 s0 = wm((r * RA) & Mmask, ihm), s1 = wm(((r + 1) * RA) & Mmask, ihm);
+#pragma unroll
+        for (int kb = 0; kb < RB && kb <= RB / 2; ++kb) {          // ko = ka + RA kb <= No/2 needs kb <= RB/2
+            const int ko = ka + RA * kb;
+            if (ko <= No / 2) {
+                const int km = (No - ko) % No;
+                const float2 z = T[(ka * RB + kb) * CG + cg], zm = T[((km % RA) * RB + km / RA) * CG + cg];
+                const float2 xa = make_float2(0.5f * (z.x + zm.x), 0.5f * (z.y - zm.y));      // (Z + conj Zm) / 2
+                const float2 xb = make_float2(0.5f * (z.y + zm.y), -0.5f * (z.x - zm.x));     // (Z - conj Zm) / (2i)
+                const float2 ta = cmulf(xa, w0), tb = cmulf(xb, w1);
+                *(float4 *)&T2[((size_t)h * NR + ko) * MI + r] = make_float4(ta.x, ta.y, tb.x, tb.y);
+            }
+            w0 = cmulf(w0, s0);
+            w1 = cmulf(w1, s1);
+        }
+    }
+}
+
+template <int RA, int RB>
+int launch_filter_outer(const OuterGeo &g, const float *k, float2 *T2, int64_t Nk, int64_t M, int64_t nh, hipStream_t s)
+{
+    const size_t lds = sizeof(float2) * ((size_t)g.No + (size_t)g.No * g.CT);
+    const dim3 grid((unsigned)(MI / (2 * g.CT)), (unsigned)nh);
+    const bool wide = Nk % 2 == 0 && ((uintptr_t)k & 7) == 0;
+    if (Nk > M / 2) {
+        FC_TRY(raise_dynamic_lds((const void *)k_filter_outer_real<RA, RB, true>, 160 * 1024));
+        hipLaunchKernelGGL((k_filter_outer_real<RA, RB, true>), grid, dim3(TB), lds, s, k, T2, g.CT, Nk, M, wide);
+    } else {
+        FC_TRY(raise_dynamic_lds((const void *)k_filter_outer_real<RA, RB, false>, 160 * 1024));
+        hipLaunchKernelGGL((k_filter_outer_real<RA, RB, false>), grid, dim3(TB), lds, s, k, T2, g.CT, Nk, M, wide);
+    }
+    FC_HIP(hipGetLastError());
+    return FFTCONV_OK;
+}
+
 // k_f for the multi-pass path: [h][ko][inner order of f'] 16-bit (re, im) pairs, f = ko + No*f', scaled 1/M
 // (fp16: boost/M, see multipass_kf_boost; pass C takes the boost out again).
 template <bool F16>
@@ -810,6 +914,33 @@ int multipass_pack_kf(const fftconv_plan *p, const double2 *spec, int64_t h0, in
                            p->M, (int)(p->M / MI), h0, nh, keep_dev, n_blocks);
     FC_HIP(hipGetLastError());
     return FFTCONV_OK;
+}
+
+// Outer pass of the filter transform (see k_filter_outer_real) for channels whose taps start at k, nh of them;
+// T2 takes nh * (No/2 + 1) * 8192 fp32 pairs.  false: no such kernel for this outer length (the caller takes the
+// generic column kernel instead).
+bool multipass_filter_outer_ok(const fftconv_plan *p) { return outer_real_ok((int)(p->M / MI)); }
+
+int multipass_filter_outer(const fftconv_plan *p, const float *k, int64_t Nk, int64_t nh, void *T2, hipStream_t s)
+{
+    const OuterGeo g = outer_geo(p->M);
+    if (nh > 65535) {
+        set_error("fftconv_filter_fft: %lld channels per launch exceed the grid limit", (long long)nh);
+        return FFTCONV_EUNSUPPORTED;
+    }
+    float2 *t = (float2 *)T2;
+    switch (g.No) {
+    case 4: return launch_filter_outer<4, 1>(g, k, t, Nk, p->M, nh, s);
+    case 8: return launch_filter_outer<8, 1>(g, k, t, Nk, p->M, nh, s);
+    case 16: return launch_filter_outer<16, 1>(g, k, t, Nk, p->M, nh, s);
+    case 32: return launch_filter_outer<16, 2>(g, k, t, Nk, p->M, nh, s);
+    case 64: return launch_filter_outer<16, 4>(g, k, t, Nk, p->M, nh, s);
+    case 128: return launch_filter_outer<16, 8>(g, k, t, Nk, p->M, nh, s);
+    case 256: return launch_filter_outer<16, 16>(g, k, t, Nk, p->M, nh, s);
+    default:
+        set_error("multipass: no filter outer pass for outer length %d", g.No);
+        return FFTCONV_EUNSUPPORTED;
+    }
 }
 
 // One set of the three passes over rows [0, B) of u.  ko_lo, ko_hi: outer frequency digits ko in [ko_lo, ko_hi)
