@@ -279,9 +279,15 @@ static int filter_fft_impl(const fftconv_plan *p, const float *k, int64_t Nk, co
         if (rc) return rc;
     }
     const bool long_rows = p->path == PATH_MULTIPASS && long_fft_supported(p);
-    // fp32 in two kernels per chunk; the scratch buffer is sized for fp64 spectra, so it takes twice the rows
-    for (int64_t h0 = 0; long_rows && h0 < p->H; h0 += 2 * p->filt_chunk) {
-        const int64_t nh = p->H - h0 < 2 * p->filt_chunk ? p->H - h0 : 2 * p->filt_chunk;
+    // fp32 in two kernels per chunk; the scratch buffer is sized for fp64 spectra, so it takes twice the rows, and
+    // where only the outer rows ko <= No/2 pass through it (multipass_filter_outer) nearly twice as many again
+    int64_t long_chunk = 2 * p->filt_chunk;
+    if (long_rows && multipass_filter_outer_ok(p)) {
+        const int64_t No = p->M / 8192;
+        long_chunk = long_chunk * No / (No / 2 + 1);
+    }
+    for (int64_t h0 = 0; long_rows && h0 < p->H; h0 += long_chunk) {
+        const int64_t nh = p->H - h0 < long_chunk ? p->H - h0 : long_chunk;
         rc = long_filter_transform(p, k + h0 * Nk, Nk, h0, nh, adjoint, keep_dev, n_blocks, (float2 *)p->filt_a, k_f, s);
         if (rc) return rc;
     }
