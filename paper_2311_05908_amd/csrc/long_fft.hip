@@ -465,6 +465,34 @@ int long_backward_filter_t(const fftconv_plan *p, const IO *u, const IO *dy, flo
         FC_HIP(hipGetLastError());
         return FFTCONV_OK;
     }
+    if (multipass_filter_outer_ok(p)) {
+        // Outer lengths with a register kernel for real rows (multipass.hip): every row of u and dy is transformed
+        // as a real sequence -- outer pass on the rows ko <= A/2 only, 8192-point block transforms of those rows,
+        // acc (+)= conj(U) DY on them -- and the sum, the spectrum of a real sequence again, goes back through the
+        // inverse block transforms and the real inverse outer pass: half the intermediate traffic of the complex
+        // pipeline below, and a row without a partner costs no more than half a pair.
+        const int NR = g.A / 2 + 1;
+        const int64_t RW = (int64_t)NR * LB;
+        float2 *acc2 = (float2 *)workspace, *spec2 = acc2 + H * RW, *tmp2 = spec2 + H * RW;
+        const dim3 grid((unsigned)NR, (unsigned)H);
+        int rc = raise_lds((const void *)k_long_fwd_blocks<0>);
+        if (!rc) rc = raise_lds((const void *)k_long_fwd_blocks<1>);
+        if (!rc) rc = raise_lds((const void *)k_long_inv_blocks);
+        if (rc) return rc;
+        for (int64_t b = 0; b < B; ++b) {
+            rc = multipass_filter_outer(p, u + b * H * N, p->dtype, N, H, tmp2, s);
+            if (rc) return rc;
+            hipLaunchKernelGGL(k_long_fwd_blocks<0>, grid, dim3(LT), L_LDS, s, tmp2, spec2, nullptr, tw, g.flB, NR, false);
+            FC_HIP(hipGetLastError());
+            rc = multipass_filter_outer(p, dy + b * H * N, p->dtype, N, H, tmp2, s);
+            if (rc) return rc;
+            hipLaunchKernelGGL(k_long_fwd_blocks<1>, grid, dim3(LT), L_LDS, s, tmp2, acc2, spec2, tw, g.flB, NR, b == 0);
+            FC_HIP(hipGetLastError());
+        }
+        hipLaunchKernelGGL(k_long_inv_blocks, grid, dim3(LT), L_LDS, s, acc2, tmp2, tw, g.flB, NR);
+        FC_HIP(hipGetLastError());
+        return multipass_dk_outer_inv(p, tmp2, dk, Nk, H, s);
+    }
     for (int64_t b = 0; b < B; b += 2) {                      // rows b and b + 1 share a transform
         const IO *u0 = u + b * H * N, *u1 = b + 1 < B ? u0 + H * N : nullptr;
         const IO *d0 = dy + b * H * N, *d1 = b + 1 < B ? d0 + H * N : nullptr;
@@ -576,7 +604,7 @@ int long_filter_transform(const fftconv_plan *p, const float *k, int64_t Nk, int
     // outer factor: the register kernel of the multi-pass route where it exists for this outer length (rows ko <= A/2
     // in natural order; the adjoint spectrum is then the conjugate, taken on the way out), else the generic column kernel
     const bool natural = multipass_filter_outer_ok(p);
-    int rc = natural ? multipass_filter_outer(p, k, Nk, nh, tmp, s)
+    int rc = natural ? multipass_filter_outer(p, k, FFTCONV_F32, Nk, nh, tmp, s)
                      : launch_fwd_cols<float>(g, k, nullptr, tmp, tw, nh, Nk, adjoint, s, true);
     if (rc) return rc;
     rc = raise_lds((const void *)k_long_fwd_blocks_kf<true>);

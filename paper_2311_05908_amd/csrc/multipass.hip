@@ -626,8 +626,10 @@ __global__ void __launch_bounds__(TB, 4) k_outer_inv_real(const uint32_t *__rest
 // (k_long_fwd_blocks_kf, long_fft.hip).  Rows ko <= No/2 only, T2[h][ko][r] (No/2 + 1 rows of 8192 fp32 pairs per
 // channel): the taps are real, the other rows are mirror images that the second kernel writes from these.
 // Taps at and beyond Nk are zeros (their loads read tap 0 and are discarded: no load sits behind a branch).
-template <int RA, int RB, bool FULLN>
-__global__ void __launch_bounds__(TB, 4) k_filter_outer_real(const float *__restrict__ k, float2 *__restrict__ T2, int CG,
+// The filter gradient of these plans (long_fft.hip) transforms its rows of u and dy the same way: IN = 0: fp32
+// rows, 1: fp16, 2: bf16; row h starts at element h * Nk.
+template <int IN, int RA, int RB, bool FULLN>
+__global__ void __launch_bounds__(TB, 4) k_filter_outer_real(const void *__restrict__ src, float2 *__restrict__ T2, int CG,
                                                          int64_t Nk, int64_t M, bool wide)
 {
     extern __shared__ float2 sm[];
@@ -639,7 +641,8 @@ __global__ void __launch_bounds__(TB, 4) k_filter_outer_real(const float *__rest
     const int r0 = blockIdx.x * 2 * CG;
     const int lgCG = 31 - __builtin_clz(CG);       // CG is a power of two
     const int64_t h = blockIdx.y;
-    const float *row0 = k + h * Nk;
+    const float *row0 = (const float *)src + h * Nk;               // IN == 0
+    const uint16_t *row16 = (const uint16_t *)src + h * Nk;        // IN != 0
     for (int j = tid; j < No; j += TB) wno[j] = wm(j, 2.0f / (float)No);
     __syncthreads();
     // step 1: length-RA transforms over a, times W_No^{ka b2}; (column c, column c+1) = (re, im)
@@ -651,11 +654,20 @@ __global__ void __launch_bounds__(TB, 4) k_filter_outer_real(const float *__rest
 #pragma unroll
         for (int a = 0; a < RAIN; ++a) {
             const int64_t n = (int64_t)(a * RB + b2) * MI + r0 + 2 * cg;
-            if (wide) {                            // Nk even, rows 8-byte aligned: a pair is inside or outside as a whole
-                x[a] = *(const float2 *)(row0 + (n < Nk ? n : 0));
+            if constexpr (IN == 0) {
+                if (wide) {                        // Nk even, rows 8-byte aligned: a pair is inside or outside as a whole
+                    x[a] = *(const float2 *)(row0 + (n < Nk ? n : 0));
+                } else {
+                    x[a].x = row0[n < Nk ? n : 0];
+                    x[a].y = row0[n + 1 < Nk ? n + 1 : 0];
+                }
             } else {
-                x[a].x = row0[n < Nk ? n : 0];
-                x[a].y = row0[n + 1 < Nk ? n + 1 : 0];
+                uint32_t wd;
+                if (wide)                          // Nk even, rows 4-byte aligned: one word holds the pair
+                    wd = *(const uint32_t *)(row16 + (n < Nk ? n : 0));
+                else
+                    wd = (uint32_t)row16[n < Nk ? n : 0] | ((uint32_t)row16[n + 1 < Nk ? n + 1 : 0] << 16);
+                x[a] = unpack2<IN == 1>(wd);
             }
         }
 #pragma unroll
@@ -707,21 +719,134 @@ __global__ void __launch_bounds__(TB, 4) k_filter_outer_real(const float *__rest
     }
 }
 
+// ---- the last pass of the filter gradient of a multi-pass plan: pass C of a lone real row (k_outer_inv_real)
+// with fp32 rows in and fp32 samples out.  T2[h][ko][r], ko <= No/2, holds the rows of sum_b conj(FFT u_b) FFT dy_b
+// after their inverse 8192-point transforms (unnormalised); the spectrum is that of a real sequence, so the rows
+// ko > No/2 are the mirror images described at k_outer_inv.  dk[h][n] = scale * (the inverse outer transform),
+// n < Nk.
+template <int RA, int RB, bool FULLN>
+__global__ void __launch_bounds__(TB, 4) k_dk_outer_inv_real(const float2 *__restrict__ T2, float *__restrict__ dk, int CG,
+                                                         int64_t Nk, int64_t M, float scale)
+{
+    extern __shared__ float2 sm[];
+    constexpr int No = RA * RB, NR = No / 2 + 1;
+    constexpr int RAIN = FULLN ? RA : RA / 2;      // outer rows that are kept
+    constexpr int KBC = RB < 8 ? RB : 8;           // rows loaded at a time (16 bytes each per thread)
+    float2 *wno = sm;
+    float2 *T = sm + No;                           // [No][CG]
+    const int tid = threadIdx.x;
+    const int r0 = blockIdx.x * 2 * CG;
+    const int lgCG = 31 - __builtin_clz(CG);       // CG is a power of two
+    const int64_t h = blockIdx.y;
+    for (int j = tid; j < No; j += TB) wno[j] = wm(j, 2.0f / (float)No);
+    __syncthreads();
+    const float ihm = 2.0f / (float)M;
+    const int Mmask = (int)M - 1;                  // M is a power of two, at most 2^22, and so is every r * ko
+    // step 1: untwiddle both columns, complete the rows ko > No/2 from their mirror rows, combine the columns
+    // into one complex sequence, length-RB inverse over kb, times conj(W_No^{ka b2})
+    for (int e = tid; e < RA * CG; e += TB) {
+        const int cg = e & (CG - 1), ka = e >> lgCG;
+        const int r = r0 + 2 * cg;
+        float2 w0 = wm((r * ka) & Mmask, ihm), w1 = wm(((r + 1) * ka) & Mmask, ihm);
+        const float2 s0 = wm((r * RA) & Mmask, ihm), s1 = wm(((r + 1) * RA) & Mmask, ihm);
+        w0.x *= scale, w0.y *= scale, w1.x *= scale, w1.y *= scale;
+        float2 x[RB];
+#pragma unroll
+        for (int kb0 = 0; kb0 < RB; kb0 += KBC) {
+            float4 in[KBC];
+#pragma unroll
+            for (int kk = 0; kk < KBC; ++kk) {
+                const int kb = kb0 + kk, ko = ka + RA * kb;
+                // ko > No/2, written so that only kb == RB/2 depends on the thread
+                const bool mir = RB == 1 ? ka > RA / 2 : (kb > RB / 2 || (kb == RB / 2 && ka > 0));
+                const int kr = mir ? No - ko : ko;            // the row that holds it, <= No/2
+                in[kk] = *(const float4 *)&T2[((size_t)h * NR + kr) * MI + r];
+            }
+#pragma unroll
+            for (int kk = 0; kk < KBC; ++kk) {
+                const int kb = kb0 + kk;
+                const bool mir = RB == 1 ? ka > RA / 2 : (kb > RB / 2 || (kb == RB / 2 && ka > 0));
+                // from the first mirrored row on the twiddle carries the extra factor conj(W_Mi^{r}) (see k_outer_inv)
+                const bool first_mirrored = RB == 1 ? ka > RA / 2 : ((kb == RB / 2 && ka > 0) || (kb == RB / 2 + 1 && ka == 0));
+                if (first_mirrored) {
+                    w0 = cmulcf(w0, wm((r * No) & Mmask, ihm));
+                    w1 = cmulcf(w1, wm(((r + 1) * No) & Mmask, ihm));
+                }
+                const float2 sa = make_float2(in[kk].x, mir ? -in[kk].y : in[kk].y);
+                const float2 sb = make_float2(in[kk].z, mir ? -in[kk].w : in[kk].w);
+                const float2 ua = cmulcf(sa, w0), ub = cmulcf(sb, w1);
+                x[kb] = make_float2(ua.x - ub.y, ua.y + ub.x);               // U_c + i U_{c+1}
+                w0 = cmulf(w0, s0);
+                w1 = cmulf(w1, s1);
+            }
+        }
+        dft_reg<RB, true>(x);
+#pragma unroll
+        for (int b2 = 0; b2 < RB; ++b2) T[(ka * RB + b2) * CG + cg] = cmulcf(x[b2], wno[ka * b2]);
+    }
+    __syncthreads();
+    // step 2: length-RA inverse over ka; real part -> column c, imaginary part -> column c+1
+    float *row0 = dk + h * Nk;
+    const bool wide = Nk % 2 == 0 && ((uintptr_t)dk & 7) == 0;
+    for (int e = tid; e < RB * CG; e += TB) {
+        const int cg = e & (CG - 1), b2 = e >> lgCG;
+        float2 x[RA];
+#pragma unroll
+        for (int ka = 0; ka < RA; ++ka) x[ka] = T[(ka * RB + b2) * CG + cg];
+        dft_reg<RA, true>(x);
+#pragma unroll
+        for (int a = 0; a < RAIN; ++a) {
+            const int64_t n = (int64_t)(a * RB + b2) * MI + r0 + 2 * cg;
+            if (wide) {
+                if (n < Nk) *(float2 *)(row0 + n) = x[a];
+            } else {
+                if (n < Nk) row0[n] = x[a].x;
+                if (n + 1 < Nk) row0[n + 1] = x[a].y;
+            }
+        }
+    }
+}
+
 template <int RA, int RB>
-int launch_filter_outer(const OuterGeo &g, const float *k, float2 *T2, int64_t Nk, int64_t M, int64_t nh, hipStream_t s)
+int launch_dk_outer_inv(const OuterGeo &g, const float2 *T2, float *dk, int64_t Nk, int64_t M, int64_t nh, hipStream_t s)
 {
     const size_t lds = sizeof(float2) * ((size_t)g.No + (size_t)g.No * g.CT);
     const dim3 grid((unsigned)(MI / (2 * g.CT)), (unsigned)nh);
-    const bool wide = Nk % 2 == 0 && ((uintptr_t)k & 7) == 0;
+    const float scale = 1.0f / (float)M;
     if (Nk > M / 2) {
-        FC_TRY(raise_dynamic_lds((const void *)k_filter_outer_real<RA, RB, true>, 160 * 1024));
-        hipLaunchKernelGGL((k_filter_outer_real<RA, RB, true>), grid, dim3(TB), lds, s, k, T2, g.CT, Nk, M, wide);
+        FC_TRY(raise_dynamic_lds((const void *)k_dk_outer_inv_real<RA, RB, true>, 160 * 1024));
+        hipLaunchKernelGGL((k_dk_outer_inv_real<RA, RB, true>), grid, dim3(TB), lds, s, T2, dk, g.CT, Nk, M, scale);
     } else {
-        FC_TRY(raise_dynamic_lds((const void *)k_filter_outer_real<RA, RB, false>, 160 * 1024));
-        hipLaunchKernelGGL((k_filter_outer_real<RA, RB, false>), grid, dim3(TB), lds, s, k, T2, g.CT, Nk, M, wide);
+        FC_TRY(raise_dynamic_lds((const void *)k_dk_outer_inv_real<RA, RB, false>, 160 * 1024));
+        hipLaunchKernelGGL((k_dk_outer_inv_real<RA, RB, false>), grid, dim3(TB), lds, s, T2, dk, g.CT, Nk, M, scale);
     }
     FC_HIP(hipGetLastError());
     return FFTCONV_OK;
+}
+
+template <int IN, int RA, int RB>
+int launch_filter_outer_in(const OuterGeo &g, const void *k, float2 *T2, int64_t Nk, int64_t M, int64_t nh, hipStream_t s)
+{
+    const size_t lds = sizeof(float2) * ((size_t)g.No + (size_t)g.No * g.CT);
+    const dim3 grid((unsigned)(MI / (2 * g.CT)), (unsigned)nh);
+    const bool wide = Nk % 2 == 0 && ((uintptr_t)k & (IN == 0 ? 7 : 3)) == 0;
+    if (Nk > M / 2) {
+        FC_TRY(raise_dynamic_lds((const void *)k_filter_outer_real<IN, RA, RB, true>, 160 * 1024));
+        hipLaunchKernelGGL((k_filter_outer_real<IN, RA, RB, true>), grid, dim3(TB), lds, s, k, T2, g.CT, Nk, M, wide);
+    } else {
+        FC_TRY(raise_dynamic_lds((const void *)k_filter_outer_real<IN, RA, RB, false>, 160 * 1024));
+        hipLaunchKernelGGL((k_filter_outer_real<IN, RA, RB, false>), grid, dim3(TB), lds, s, k, T2, g.CT, Nk, M, wide);
+    }
+    FC_HIP(hipGetLastError());
+    return FFTCONV_OK;
+}
+// dtype: FFTCONV_F32 / F16 / BF16 of the rows
+template <int RA, int RB>
+int launch_filter_outer(const OuterGeo &g, const void *k, int dtype, float2 *T2, int64_t Nk, int64_t M, int64_t nh, hipStream_t s)
+{
+    if (dtype == FFTCONV_F32) return launch_filter_outer_in<0, RA, RB>(g, k, T2, Nk, M, nh, s);
+    if (dtype == FFTCONV_F16) return launch_filter_outer_in<1, RA, RB>(g, k, T2, Nk, M, nh, s);
+    return launch_filter_outer_in<2, RA, RB>(g, k, T2, Nk, M, nh, s);
 }
 
 // k_f for the multi-pass path: [h][ko][inner order of f'] 16-bit (re, im) pairs, f = ko + No*f', scaled 1/M
@@ -916,29 +1041,52 @@ int multipass_pack_kf(const fftconv_plan *p, const double2 *spec, int64_t h0, in
     return FFTCONV_OK;
 }
 
-// Outer pass of the filter transform (see k_filter_outer_real) for channels whose taps start at k, nh of them;
-// T2 takes nh * (No/2 + 1) * 8192 fp32 pairs.  false: no such kernel for this outer length (the caller takes the
-// generic column kernel instead).
+// Outer pass of the transform of nh real rows of Nk samples each (see k_filter_outer_real; dtype: FFTCONV_F32 / F16 /
+// BF16 of the rows); T2 takes nh * (No/2 + 1) * 8192 fp32 pairs.  multipass_filter_outer_ok(): false = no such kernel
+// for this outer length (the caller takes the generic column kernel instead).
 bool multipass_filter_outer_ok(const fftconv_plan *p) { return outer_real_ok((int)(p->M / MI)); }
 
-int multipass_filter_outer(const fftconv_plan *p, const float *k, int64_t Nk, int64_t nh, void *T2, hipStream_t s)
+int multipass_filter_outer(const fftconv_plan *p, const void *rows, int dtype, int64_t Nk, int64_t nh, void *T2, hipStream_t s)
 {
     const OuterGeo g = outer_geo(p->M);
     if (nh > 65535) {
-        set_error("fftconv_filter_fft: %lld channels per launch exceed the grid limit", (long long)nh);
+        set_error("multipass: %lld rows per launch of the real outer pass exceed the grid limit", (long long)nh);
         return FFTCONV_EUNSUPPORTED;
     }
     float2 *t = (float2 *)T2;
     switch (g.No) {
-    case 4: return launch_filter_outer<4, 1>(g, k, t, Nk, p->M, nh, s);
-    case 8: return launch_filter_outer<8, 1>(g, k, t, Nk, p->M, nh, s);
-    case 16: return launch_filter_outer<16, 1>(g, k, t, Nk, p->M, nh, s);
-    case 32: return launch_filter_outer<16, 2>(g, k, t, Nk, p->M, nh, s);
-    case 64: return launch_filter_outer<16, 4>(g, k, t, Nk, p->M, nh, s);
-    case 128: return launch_filter_outer<16, 8>(g, k, t, Nk, p->M, nh, s);
-    case 256: return launch_filter_outer<16, 16>(g, k, t, Nk, p->M, nh, s);
+    case 4: return launch_filter_outer<4, 1>(g, rows, dtype, t, Nk, p->M, nh, s);
+    case 8: return launch_filter_outer<8, 1>(g, rows, dtype, t, Nk, p->M, nh, s);
+    case 16: return launch_filter_outer<16, 1>(g, rows, dtype, t, Nk, p->M, nh, s);
+    case 32: return launch_filter_outer<16, 2>(g, rows, dtype, t, Nk, p->M, nh, s);
+    case 64: return launch_filter_outer<16, 4>(g, rows, dtype, t, Nk, p->M, nh, s);
+    case 128: return launch_filter_outer<16, 8>(g, rows, dtype, t, Nk, p->M, nh, s);
+    case 256: return launch_filter_outer<16, 16>(g, rows, dtype, t, Nk, p->M, nh, s);
     default:
-        set_error("multipass: no filter outer pass for outer length %d", g.No);
+        set_error("multipass: no real outer pass for outer length %d", g.No);
+        return FFTCONV_EUNSUPPORTED;
+    }
+}
+
+// Last pass of the filter gradient (see k_dk_outer_inv_real): T2 holds nh * (No/2 + 1) rows, dk (nh, Nk).
+int multipass_dk_outer_inv(const fftconv_plan *p, const void *T2, float *dk, int64_t Nk, int64_t nh, hipStream_t s)
+{
+    const OuterGeo g = outer_geo(p->M);
+    if (nh > 65535) {
+        set_error("multipass: %lld rows per launch of the real outer pass exceed the grid limit", (long long)nh);
+        return FFTCONV_EUNSUPPORTED;
+    }
+    const float2 *t = (const float2 *)T2;
+    switch (g.No) {
+    case 4: return launch_dk_outer_inv<4, 1>(g, t, dk, Nk, p->M, nh, s);
+    case 8: return launch_dk_outer_inv<8, 1>(g, t, dk, Nk, p->M, nh, s);
+    case 16: return launch_dk_outer_inv<16, 1>(g, t, dk, Nk, p->M, nh, s);
+    case 32: return launch_dk_outer_inv<16, 2>(g, t, dk, Nk, p->M, nh, s);
+    case 64: return launch_dk_outer_inv<16, 4>(g, t, dk, Nk, p->M, nh, s);
+    case 128: return launch_dk_outer_inv<16, 8>(g, t, dk, Nk, p->M, nh, s);
+    case 256: return launch_dk_outer_inv<16, 16>(g, t, dk, Nk, p->M, nh, s);
+    default:
+        set_error("multipass: no real outer pass for outer length %d", g.No);
         return FFTCONV_EUNSUPPORTED;
     }
 }

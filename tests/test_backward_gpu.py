@@ -33,7 +33,7 @@ SHAPES = [
     ("f16", 2, 1, 16384, 32768, 16384), # fused 32768: four passes over a channel, a quarter of the bins each
     ("bf16", 5, 3, 16384, 32768, 16384), # odd batch, several channels per workgroup
     ("bf16", 3, 2, 9000, 32768, 9000),  # ragged N
-    ("bf16", 1, 1, 32768, 65536, 4096), # multi-pass: fp32 transforms in two kernels per direction (A = 8)
+    ("bf16", 1, 1, 32768, 65536, 4096), # multi-pass: fp32 transforms of real rows, outer rows ko <= A/2 only (A = 8)
     ("bf16", 3, 2, 40000, 131072, 5000), # A = 16, odd batch (the last row has no partner), ragged N
     ("f32", 3, 2, 8192, 16384, 8192),   # fp32 I/O, A = 2
     ("f16", 2, 1, 16384, 16384, 700),   # circular (N = fft_size) multi-pass plan
@@ -67,6 +67,27 @@ def test_backward_input_and_filter(dtype, B, H, N, M, Nk):
     y = plan.forward(u.cuda(), plan.filter_fft(kd))
     y_ref = oracle.fftconv(u.double().numpy(), k, M)
     assert parity_error(y.cpu().double().numpy(), y_ref, TOL[dtype], "y") <= TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype,B,H,N,M,Nk", [
+    ("bf16", 2, 1, 1 << 18, 1 << 19, 2000),     # A = 64: both levels of the register outer passes
+    ("f16", 1, 2, 1 << 20, 1 << 21, 1000),      # A = 256, config 4's transform, a single row
+    ("bf16", 3, 1, 100000, 1 << 18, 300),       # A = 32, ragged N, odd batch
+    ("f16", 2, 1, 1 << 17, 1 << 17, 500),       # A = 16, the input fills the transform (circular form)
+])
+def test_backward_filter_long_rows(dtype, B, H, N, M, Nk):
+    """dk of multi-pass plans at lengths where only the filter gradient's oracle (O(N Nk) per row) is affordable."""
+    w = synth.scaled(W["cfg1"], B=B, H=H, N=N, fft_size=M, dtype=dtype, alpha=(1e-3, 1e-2))
+    u = synth.gen_u(w)
+    dy = synth.gen_gate(w, "dy")
+    plan = fftconv.Plan(N, M, H, dtype)
+    dk = plan.backward_filter(u.cuda(), dy.cuda(), Nk)
+    torch.cuda.synchronize()
+    dk_ref = oracle.backward_k(u.double().numpy(), dy.double().numpy(), M, Nk)
+    e_k = parity_error(dk.cpu().double().numpy(), dk_ref, TOL["f32"], "dk")
+    print("backward_filter %s B=%d H=%d N=%d M=%d Nk=%d path=%s dk err=%.3e" % (dtype, B, H, N, M, Nk, plan.path, e_k), flush=True)
+    assert plan.path == "multipass"
+    assert e_k <= TOL["f32"]
 
 
 def test_backward_empty_batch_and_errors():
