@@ -957,7 +957,7 @@ __global__ void k_big_dk_last(const float2 *__restrict__ tmp, float *__restrict_
 // k_f in the kernel's per-lane order: [h][k1][k2 tile][k3 tile][r][lane]; the lane holds
 // k2 = big_tau(16 tile + lane%16) and k3 = big_sigma(16 tile + 4 (lane/16) + r).  Scaled by 1/M.
 // w: W_M^t, t < M.  flh: factors of the half-length transform.  conj_out: the adjoint filter transform.
-constexpr int BIG_FILT_THREADS = 512;
+constexpr int BIG_FILT_THREADS = 1024;
 template <typename TT, int N2>
 __global__ void __launch_bounds__(BIG_FILT_THREADS) k_filter_big(const float *__restrict__ k, typename TT::CW *__restrict__ kf,
                                                                 const float2 *__restrict__ w, FacList flh, int64_t Nk,
