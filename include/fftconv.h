@@ -21,7 +21,9 @@
  *    device that was current when the plan was created; the caller owns and
  *    frees it.  block_keep is HOST memory.
  *  - u and y are contiguous row-major (B, H, N) in the plan's I/O dtype;
- *    k is contiguous row-major (H, Nk) fp32.
+ *    k is contiguous row-major (H, Nk) fp32.  u, y, the gates, k_f and the
+ *    workspace must start on a 16-byte boundary (any device allocation does);
+ *    k and dk on a 4-byte one.
  *  - k_f is an opaque buffer of fftconv_kf_bytes() bytes: spectrum in the
  *    plan's internal (permuted) order, pre-scaled by 1/fft_size.  It is only
  *    valid with the plan that produced it (or a plan created with identical

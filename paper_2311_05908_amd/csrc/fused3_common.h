@@ -124,7 +124,7 @@ struct F16 {
 };
 
 // ---- complex products with 4-byte constants: the traits of the kernels that stream their tables
-//      or keep them in registers by the plane (fused3_big.hip, fused3_ws.hip)
+//      or reload them by the plane (fused3_big.hip, fused3_wsc.hip)
 
 // bf16: dot-product form.  Constant of a factor: the pair (wr, wi), 4 bytes (every constant is
 // streamed from L2 once per use by the kernels for the larger sizes, whose bound is the load
@@ -173,8 +173,6 @@ struct B16 {
         return make_uint4(t0, t2, t4, t6);
     }
     static __host__ __device__ inline CW cconst(uint32_t re, uint32_t im, bool) { return re | (im << 16); }   // 16-bit patterns
-    // from the 8-byte table form of BF16::ctw4, { (wr, -wi), (wi, wr) }
-    static __device__ __forceinline__ CW from_table(uint2 c) { return c.x ^ 0x80000000u; }
     // the constant as an fp32 pair
     static __device__ __forceinline__ float2 widen(CW c)
     {
@@ -192,8 +190,6 @@ struct H16 {
     static __device__ __forceinline__ f32x4 mfma(uint4 a, uint4 b, f32x4 c) { return F16::mfma(a, b, c); }
     static __device__ __forceinline__ uint32_t pack(float lo, float hi) { return F16::pack(lo, hi); }
     static __host__ __device__ inline CW cconst(uint32_t re, uint32_t im, bool) { return re | (im << 16); }
-    // from the 8-byte table form of F16::ctw4, { (wr, wr), (-wi, wi) }
-    static __device__ __forceinline__ CW from_table(uint2 c) { return (c.x & 0xffffu) | (c.y & 0xffff0000u); }
     // the constant as an fp32 pair
     static __device__ __forceinline__ float2 widen(CW c)
     {
