@@ -259,6 +259,7 @@ def test_partial_convolution_as_segments_on_long_plans(dtype, B, H, N, M, Nk):
     (3, 2, 32768, 65536),      # outer length 8, odd batch
     (2, 1, 65536, 131072),     # outer length 16
     (1, 1, 20000, 65536),      # ragged N, B = 1
+    (3, 1, 20001, 65536),      # odd N: rows start on 2-byte boundaries, element-wise loads and stores; odd batch
 ])
 def test_multipass_all_outputs(dtype, B, H, N, M):
     w = synth.scaled(W["cfg3"], B=B, H=H, N=N, fft_size=M, dtype=dtype)
