@@ -279,10 +279,12 @@ static int filter_fft_impl(const fftconv_plan *p, const float *k, int64_t Nk, co
         if (rc) return rc;
     }
     const bool long_rows = p->path == PATH_MULTIPASS && long_fft_supported(p);
+    // fp32 k_f in the position order of the long transforms (staged plans from fft 32768 up) with a real outer pass
+    const bool long_rows_f32 = p->path == PATH_STAGED && p->M >= 32768 && long_fft_supported(p) && multipass_filter_outer_ok(p);
     // fp32 in two kernels per chunk; the scratch buffer is sized for fp64 spectra, so it takes twice the rows, and
     // where only the outer rows ko <= No/2 pass through it (multipass_filter_outer) nearly twice as many again
     int64_t long_chunk = 2 * p->filt_chunk;
-    if (long_rows && multipass_filter_outer_ok(p)) {
+    if ((long_rows || long_rows_f32) && multipass_filter_outer_ok(p)) {
         const int64_t No = p->M / 8192;
         long_chunk = long_chunk * No / (No / 2 + 1);
     }
@@ -291,7 +293,12 @@ static int filter_fft_impl(const fftconv_plan *p, const float *k, int64_t Nk, co
         rc = long_filter_transform(p, k + h0 * Nk, Nk, h0, nh, adjoint, keep_dev, n_blocks, (float2 *)p->filt_a, k_f, s);
         if (rc) return rc;
     }
-    for (int64_t h0 = 0; p->path != PATH_FUSED3 && !long_rows && h0 < p->H; h0 += p->filt_chunk) {
+    for (int64_t h0 = 0; long_rows_f32 && h0 < p->H; h0 += long_chunk) {
+        const int64_t nh = p->H - h0 < long_chunk ? p->H - h0 : long_chunk;
+        rc = long_filter_transform_f32(p, k + h0 * Nk, Nk, h0, nh, adjoint, keep_dev, n_blocks, (float2 *)p->filt_a, k_f, s);
+        if (rc) return rc;
+    }
+    for (int64_t h0 = 0; p->path != PATH_FUSED3 && !long_rows && !long_rows_f32 && h0 < p->H; h0 += p->filt_chunk) {
         int64_t nh = p->H - h0 < p->filt_chunk ? p->H - h0 : p->filt_chunk;
         double2 *spec = nullptr;
         rc = staged_filter_transform(p, k, Nk, h0, nh, s, &spec, adjoint);

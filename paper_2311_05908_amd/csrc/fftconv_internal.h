@@ -154,6 +154,8 @@ int long_fft_init(fftconv_plan *p);
 void long_fft_destroy(fftconv_plan *p);
 int long_filter_transform(const fftconv_plan *p, const float *k, int64_t Nk, int64_t h0, int64_t nh, bool adjoint,
                           const uint8_t *keep_dev, int64_t n_blocks, float2 *tmp, void *kf, hipStream_t s);
+int long_filter_transform_f32(const fftconv_plan *p, const float *k, int64_t Nk, int64_t h0, int64_t nh, bool adjoint,
+                          const uint8_t *keep_dev, int64_t n_blocks, float2 *tmp, void *kf, hipStream_t s);
 FacList long_fft_factor_list(int64_t M);
 size_t long_forward_workspace_bytes(const fftconv_plan *p);
 int long_forward(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, void *workspace, hipStream_t s);

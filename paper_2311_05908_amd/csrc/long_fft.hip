@@ -284,6 +284,43 @@ __global__ void __launch_bounds__(LT) k_long_fwd_blocks_kf(const float2 *__restr
     }
 }
 
+// The same for the plans that keep k_f as fp32 pairs in position order (fp32 I/O from fft_size 32768 up): tmp
+// holds the rows ko <= A/2 in the order of ko (k_filter_outer_real); row ko goes to the block at the position of
+// digit ko, bins in the block transform's own order, scaled by 1/M and by the frequency mask; the mirror row
+// A - ko likewise, bin g = conj of this row's bin 8191 - g.
+__global__ void __launch_bounds__(LT) k_long_fwd_blocks_kf32(const float2 *__restrict__ tmp, float2 *__restrict__ kf, LongTw w,
+                                                            FacList flA, FacList flB, int A, int64_t h0,
+                                                            const uint8_t *__restrict__ keep, int64_t n_blocks, bool conj_out)
+{
+    extern __shared__ float2 XL[];
+    const int ko = blockIdx.x;                                // <= A/2
+    const int64_t base = ((int64_t)blockIdx.y * (A / 2 + 1) + ko) * LB;
+    load_block(XL, tmp + base);
+    __syncthreads();
+    lds_forward(XL, w.w8k, flB, LB, 1);
+    const int M = A * LB;
+    const float inv = 1.0f / (float)M;
+    // the factors 16, 16, 16, 2 of 8192 folded (the launch checks the list): position of a frequency and back
+    auto pos8k = [](int f) { return ((f & 15) << 9) | (((f >> 4) & 15) << 5) | (((f >> 8) & 15) << 1) | (f >> 12); };
+    auto freq8k = [](int i) { return (i >> 9) | (((i >> 5) & 15) << 4) | (((i >> 1) & 15) << 8) | ((i & 1) << 12); };
+    const bool mirror = ko > 0 && 2 * ko < A;
+    float2 *dst = kf + ((h0 + blockIdx.y) * A + lds_pos(ko, flA, A)) * (int64_t)LB;
+    float2 *dst_m = kf + ((h0 + blockIdx.y) * A + lds_pos(mirror ? A - ko : ko, flA, A)) * (int64_t)LB;
+    const float sgn = conj_out ? -1.f : 1.f;
+#pragma unroll 4
+    for (int i = threadIdx.x; i < LB; i += LT) {
+        const int fi = freq8k(i);
+        const float2 v = XL[lds_slot(i)];
+        const float sc = keep ? lds_mask_weight(keep, n_blocks, ko + A * fi, M) * inv : inv;
+        dst[i] = make_float2(v.x * sc, sgn * v.y * sc);
+        if (mirror) {
+            const float2 vm = XL[lds_slot(pos8k(LB - 1 - fi))];
+            const float scm = keep ? lds_mask_weight(keep, n_blocks, (A - ko) + A * fi, M) * inv : inv;
+            dst_m[i] = make_float2(vm.x * scm, -sgn * vm.y * scm);
+        }
+    }
+}
+
 // Inverse, blocks: spectrum in position order -> tmp after the factors of 8192 (unnormalised).
 __global__ void __launch_bounds__(LT) k_long_inv_blocks(const float2 *__restrict__ spec, float2 *__restrict__ tmp, LongTw w,
                                                        FacList flB, int A)
@@ -617,6 +654,28 @@ int long_filter_transform(const fftconv_plan *p, const float *k, int64_t Nk, int
     else
         hipLaunchKernelGGL(k_long_fwd_blocks_kf<false>, grid, dim3(LT), L_LDS, s, tmp, (uint32_t *)kf, tw, g.flA, g.flB, g.A, h0,
                            keep_dev, n_blocks, natural, natural && adjoint);
+    FC_HIP(hipGetLastError());
+    return FFTCONV_OK;
+}
+
+// The filter transform of channels [h0, h0 + nh) of a plan that keeps k_f as fp32 pairs in the position order of
+// long_fft_factor_list() (fp32 I/O, fft_size 32768 .. 2^21): the real outer pass and the block transforms of the
+// rows ko <= A/2, as above.  tmp holds nh * (A/2 + 1) * 8192 float2.  Needs multipass_filter_outer_ok(p).
+int long_filter_transform_f32(const fftconv_plan *p, const float *k, int64_t Nk, int64_t h0, int64_t nh, bool adjoint,
+                              const uint8_t *keep_dev, int64_t n_blocks, float2 *tmp, void *kf, hipStream_t s)
+{
+    const LongGeo g = long_geo(p->M);
+    const LongTw tw = long_tw(p);
+    if (g.flB.nf != 4 || g.flB.fac[0] != 16 || g.flB.fac[1] != 16 || g.flB.fac[2] != 16 || g.flB.fac[3] != 2) {
+        set_error("long filter transform: the block transform's factors are not 16, 16, 16, 2");
+        return FFTCONV_EUNSUPPORTED;
+    }
+    int rc = multipass_filter_outer(p, k, FFTCONV_F32, Nk, nh, tmp, s);
+    if (rc) return rc;
+    rc = raise_lds((const void *)k_long_fwd_blocks_kf32);
+    if (rc) return rc;
+    hipLaunchKernelGGL(k_long_fwd_blocks_kf32, dim3((unsigned)(g.A / 2 + 1), (unsigned)nh), dim3(LT), L_LDS, s, tmp,
+                       (float2 *)kf, tw, g.flA, g.flB, g.A, h0, keep_dev, n_blocks, adjoint);
     FC_HIP(hipGetLastError());
     return FFTCONV_OK;
 }
