@@ -266,7 +266,7 @@ size_t multipass_workspace_bytes(const fftconv_plan *p, int64_t B);
 // outer pass of the filter transform of a multi-pass plan (multipass.hip), where a kernel for the plan's outer length exists
 bool multipass_filter_outer_ok(const fftconv_plan *p);
 int multipass_filter_outer(const fftconv_plan *p, const void *rows, int dtype, int64_t Nk, int64_t nh, void *T2, hipStream_t s);
-int multipass_dk_outer_inv(const fftconv_plan *p, const void *T2, float *dk, int64_t Nk, int64_t nh, hipStream_t s);
+int multipass_dk_outer_inv(const fftconv_plan *p, const void *T2, float *dk, int64_t Nk, int64_t nh, float scale, hipStream_t s);
 int multipass_pack_kf(const fftconv_plan *p, const double2 *spec, int64_t h0, int64_t nh,
                       const uint8_t *keep_dev, int64_t n_blocks, void *kf, hipStream_t s);
 int multipass_forward(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, void *workspace,

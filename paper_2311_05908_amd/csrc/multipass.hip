@@ -808,11 +808,11 @@ __global__ void __launch_bounds__(TB, 4) k_dk_outer_inv_real(const float2 *__res
 }
 
 template <int RA, int RB>
-int launch_dk_outer_inv(const OuterGeo &g, const float2 *T2, float *dk, int64_t Nk, int64_t M, int64_t nh, hipStream_t s)
+int launch_dk_outer_inv(const OuterGeo &g, const float2 *T2, float *dk, int64_t Nk, int64_t M, int64_t nh, float scale,
+                        hipStream_t s)
 {
     const size_t lds = sizeof(float2) * ((size_t)g.No + (size_t)g.No * g.CT);
     const dim3 grid((unsigned)(MI / (2 * g.CT)), (unsigned)nh);
-    const float scale = 1.0f / (float)M;
     if (Nk > M / 2) {
         FC_TRY(raise_dynamic_lds((const void *)k_dk_outer_inv_real<RA, RB, true>, 160 * 1024));
         hipLaunchKernelGGL((k_dk_outer_inv_real<RA, RB, true>), grid, dim3(TB), lds, s, T2, dk, g.CT, Nk, M, scale);
@@ -1068,8 +1068,9 @@ int multipass_filter_outer(const fftconv_plan *p, const void *rows, int dtype, i
     }
 }
 
-// Last pass of the filter gradient (see k_dk_outer_inv_real): T2 holds nh * (No/2 + 1) rows, dk (nh, Nk).
-int multipass_dk_outer_inv(const fftconv_plan *p, const void *T2, float *dk, int64_t Nk, int64_t nh, hipStream_t s)
+// Last pass of the filter gradient, and of the fp32 forward pass of long plans (see k_dk_outer_inv_real): T2 holds
+// nh * (No/2 + 1) rows; dk (nh, Nk) = scale * the real inverse outer transform.
+int multipass_dk_outer_inv(const fftconv_plan *p, const void *T2, float *dk, int64_t Nk, int64_t nh, float scale, hipStream_t s)
 {
     const OuterGeo g = outer_geo(p->M);
     if (nh > 65535) {
@@ -1078,13 +1079,13 @@ int multipass_dk_outer_inv(const fftconv_plan *p, const void *T2, float *dk, int
     }
     const float2 *t = (const float2 *)T2;
     switch (g.No) {
-    case 4: return launch_dk_outer_inv<4, 1>(g, t, dk, Nk, p->M, nh, s);
-    case 8: return launch_dk_outer_inv<8, 1>(g, t, dk, Nk, p->M, nh, s);
-    case 16: return launch_dk_outer_inv<16, 1>(g, t, dk, Nk, p->M, nh, s);
-    case 32: return launch_dk_outer_inv<16, 2>(g, t, dk, Nk, p->M, nh, s);
-    case 64: return launch_dk_outer_inv<16, 4>(g, t, dk, Nk, p->M, nh, s);
-    case 128: return launch_dk_outer_inv<16, 8>(g, t, dk, Nk, p->M, nh, s);
-    case 256: return launch_dk_outer_inv<16, 16>(g, t, dk, Nk, p->M, nh, s);
+    case 4: return launch_dk_outer_inv<4, 1>(g, t, dk, Nk, p->M, nh, scale, s);
+    case 8: return launch_dk_outer_inv<8, 1>(g, t, dk, Nk, p->M, nh, scale, s);
+    case 16: return launch_dk_outer_inv<16, 1>(g, t, dk, Nk, p->M, nh, scale, s);
+    case 32: return launch_dk_outer_inv<16, 2>(g, t, dk, Nk, p->M, nh, scale, s);
+    case 64: return launch_dk_outer_inv<16, 4>(g, t, dk, Nk, p->M, nh, scale, s);
+    case 128: return launch_dk_outer_inv<16, 8>(g, t, dk, Nk, p->M, nh, scale, s);
+    case 256: return launch_dk_outer_inv<16, 16>(g, t, dk, Nk, p->M, nh, scale, s);
     default:
         set_error("multipass: no real outer pass for outer length %d", g.No);
         return FFTCONV_EUNSUPPORTED;
