@@ -160,19 +160,21 @@ __global__ void __launch_bounds__(TB, 4) k_outer_fwd(const uint16_t *__restrict_
     for (int e = tid; e < RB * CG; e += TB) {
         const int c = (e & (CG - 1)) * CV, b2 = e >> lgCG;
         uint32_t in0[RAIN], in1[RAIN];             // CV 16-bit values of row b / row b+1
+        uint32_t gt0[GATED ? RAIN : 1], gt1[GATED ? RAIN : 1];
 #pragma unroll
         for (int a = 0; a < RAIN; ++a) {
             const int64_t n = (int64_t)(a * RB + b2) * MI + r0 + c;
             in0[a] = in1[a] = 0;
-            uint32_t gt0 = 0, gt1 = 0;
+            if constexpr (GATED) gt0[a] = gt1[a] = 0;
             if (wide) {
-                if (EXACT || n < N) {
-                    in0[a] = *(const uint32_t *)(row0 + n);
-                    if (two) in1[a] = *(const uint32_t *)(row1 + n);
-                    if constexpr (GATED) {
-                        gt0 = *(const uint32_t *)(g0 + n);
-                        if (two) gt1 = *(const uint32_t *)(g1 + n);
-                    }
+                // a pair beyond N (n and N are even: in or out as a whole) reads sample 0 and is discarded below, a
+                // missing row b+1 reads row b: the loads need no branch and go out back to back
+                const int64_t at = (EXACT || n < N) ? n : 0;
+                in0[a] = *(const uint32_t *)(row0 + at);
+                in1[a] = *(const uint32_t *)(row1 + at);
+                if constexpr (GATED) {
+                    gt0[a] = *(const uint32_t *)(g0 + at);
+                    gt1[a] = *(const uint32_t *)(g1 + at);
                 }
             } else {
 #pragma unroll
@@ -181,14 +183,35 @@ __global__ void __launch_bounds__(TB, 4) k_outer_fwd(const uint16_t *__restrict_
                         in0[a] |= (uint32_t)row0[n + v] << (16 * v);
                         if (two) in1[a] |= (uint32_t)row1[n + v] << (16 * v);
                         if constexpr (GATED) {
-                            gt0 |= (uint32_t)g0[n + v] << (16 * v);
-                            if (two) gt1 |= (uint32_t)g1[n + v] << (16 * v);
+                            gt0[a] |= (uint32_t)g0[n + v] << (16 * v);
+                            if (two) gt1[a] |= (uint32_t)g1[n + v] << (16 * v);
                         }
                     }
             }
-            if constexpr (GATED) {
-                in0[a] = mul_pair16<F16>(in0[a], gt0);
-                in1[a] = mul_pair16<F16>(in1[a], gt1);
+        }
+        if (wide) {
+#pragma unroll
+            for (int a = 0; a < RAIN; ++a) {
+                asm volatile("" ::"v"(in0[a]), "v"(in1[a]));             // keeps the loads unconditional
+                if constexpr (GATED) asm volatile("" ::"v"(gt0[a]), "v"(gt1[a]));
+            }
+#pragma unroll
+            for (int a = 0; a < RAIN; ++a) {
+                const int64_t n = (int64_t)(a * RB + b2) * MI + r0 + c;
+                const bool in = EXACT || n < N;
+                if (!in) in0[a] = 0;
+                if (!in || !two) in1[a] = 0;
+                if constexpr (GATED) {                                    // (0 times a discarded gate must stay 0)
+                    if (!in) gt0[a] = 0;
+                    if (!in || !two) gt1[a] = 0;
+                }
+            }
+        }
+        if constexpr (GATED) {
+#pragma unroll
+            for (int a = 0; a < RAIN; ++a) {
+                in0[a] = mul_pair16<F16>(in0[a], gt0[a]);
+                in1[a] = mul_pair16<F16>(in1[a], gt1[a]);
             }
         }
         float2 o[RA][CV];
@@ -449,27 +472,48 @@ __global__ void __launch_bounds__(TB, 4) k_outer_fwd_real(const uint16_t *__rest
     for (int e = tid; e < RB * CG; e += TB) {
         const int cg = e & (CG - 1), b2 = e >> lgCG;
         float2 x[RA];
+        uint32_t wd[RAIN], gt[GATED ? RAIN : 1];
+#pragma unroll
+        for (int a = 0; a < RAIN; ++a) {
+            const int64_t n = (int64_t)(a * RB + b2) * MI + r0 + 2 * cg;
+            wd[a] = 0;
+            if constexpr (GATED) gt[a] = 0;
+            if (wide) {
+                // a pair beyond N (n and N are even: in or out as a whole) reads sample 0 and is discarded below: the
+                // loads need no branch and go out back to back
+                const int64_t at = (EXACT || n < N) ? n : 0;
+                wd[a] = *(const uint32_t *)(row0 + at);
+                if constexpr (GATED) gt[a] = *(const uint32_t *)(g0 + at);
+            } else {
+#pragma unroll
+                for (int v = 0; v < 2; ++v)
+                    if (EXACT || n + v < N) {
+                        wd[a] |= (uint32_t)row0[n + v] << (16 * v);
+                        if constexpr (GATED) gt[a] |= (uint32_t)g0[n + v] << (16 * v);
+                    }
+            }
+        }
+        if (wide && !EXACT) {
+#pragma unroll
+            for (int a = 0; a < RAIN; ++a) {
+                asm volatile("" ::"v"(wd[a]));                           // keeps the loads unconditional
+                if constexpr (GATED) asm volatile("" ::"v"(gt[a]));
+            }
+#pragma unroll
+            for (int a = 0; a < RAIN; ++a) {
+                const int64_t n = (int64_t)(a * RB + b2) * MI + r0 + 2 * cg;
+                if (n >= N) {
+                    wd[a] = 0;
+                    if constexpr (GATED) gt[a] = 0;                      // (0 times a discarded gate must stay 0)
+                }
+            }
+        }
 #pragma unroll
         for (int a = 0; a < RA; ++a) {
             x[a] = make_float2(0.f, 0.f);
             if (a < RAIN) {
-                const int64_t n = (int64_t)(a * RB + b2) * MI + r0 + 2 * cg;
-                uint32_t wd = 0, gt = 0;
-                if (wide) {
-                    if (EXACT || n < N) {
-                        wd = *(const uint32_t *)(row0 + n);
-                        if constexpr (GATED) gt = *(const uint32_t *)(g0 + n);
-                    }
-                } else {
-#pragma unroll
-                    for (int v = 0; v < 2; ++v)
-                        if (EXACT || n + v < N) {
-                            wd |= (uint32_t)row0[n + v] << (16 * v);
-                            if constexpr (GATED) gt |= (uint32_t)g0[n + v] << (16 * v);
-                        }
-                }
-                if constexpr (GATED) wd = mul_pair16<F16>(wd, gt);
-                x[a] = unpack2<F16>(wd);           // (column c, column c+1) = (re, im)
+                if constexpr (GATED) wd[a] = mul_pair16<F16>(wd[a], gt[a]);
+                x[a] = unpack2<F16>(wd[a]);        // (column c, column c+1) = (re, im)
             }
         }
         dft_reg<RA, false>(x);
