@@ -189,7 +189,7 @@ int fused3_forward_short(const fftconv_plan *p, const void *u, const void *kf, v
 // the 8192-point complex-row kernel used as the inner step of the multi-pass path
 int fused3_init_inner(fftconv_plan *p);
 int fused3_inner_rows(const fftconv_plan *p, void *rows, const void *kf, int64_t rows_per_kf, int64_t kf_rows,
-                      hipStream_t s, int ko_n = 0, int ko_lo = 0, int ko_hi = 0);
+                      hipStream_t s, int ko_n = 0, int ko_lo = 0, int ko_hi = 0, bool quarter_rows = false);
 // Order of the innermost frequency digit k3 (N3 values) inside the fused kernels.  Stage 3 leaves
 // k3 in an accumulator slot (tile t, lane group q, register r) = index 16 t + 4 q + r.  The digits are
 // ranked by closeness to DC (0, N3-1, 1, N3-2, ...: k3 is the most significant digit of the
@@ -207,6 +207,21 @@ __host__ __device__ inline int k3_index(int k3, int N3)
     const int j = k3 < N3 / 2 ? 2 * k3 : 2 * (N3 - 1 - k3) + 1;
     const int t = j / 16, jj = j % 16;
     return 16 * t + 4 * (jj % 4) + jj / 4;
+}
+
+// Place of column r (< 8192) inside a row of the multi-pass workspace.  r = n1*256 + n2*16 + n3 in the inner
+// kernel's digits.  Outer lengths up to 64 store a row as four quarter rows, one per group of four n3 planes -- the
+// planes of one outer wave of the inner kernel (fused3_wsc.hip), which then reads and writes whole contiguous
+// lines instead of a quarter of each:
+//   slot = (n3 / 4) * 2048 + n1 * 64 + n2 * 4 + n3 % 4        (columns r and r + 1, r even, stay adjacent).
+// A block of the outer passes holds 8192 / No consecutive columns: from 128 columns (No <= 64) up its share of a
+// quarter row is still 128 bytes or more and the sweep gains 5-11 %; at No = 128 it makes no difference, and at 256
+// (64- and 32-byte pieces) the outer passes lose more than the inner kernel gains (0.21 -> 0.175 ms against
+// 0.095 -> 0.11 and 0.115 -> 0.15 ms on config 4).  Longer outer transforms keep the natural order.
+constexpr bool multipass_quarter_rows(int No) { return No <= 64; }
+__host__ __device__ inline int multipass_row_slot(int r, bool quarter)
+{
+    return quarter ? ((r & 12) << 9) | ((r >> 8) << 6) | (((r >> 4) & 15) << 2) | (r & 3) : r;
 }
 
 // slot of inner frequency fi (< 8192) in the 8192-point kernel's per-lane k_f order

@@ -405,14 +405,14 @@ int fused3_init_inner(fftconv_plan *p)
 // ko_n > 0: the k_f rows come in groups of ko_n (outer frequency digit ko); only ko < ko_lo and ko >= ko_hi
 // are processed (the others hold zero spectra and their rows are never touched).  ko_n = 0: every row.
 int fused3_inner_rows(const fftconv_plan *p, void *rows, const void *kf, int64_t rows_per_kf, int64_t kf_rows,
-                      hipStream_t s, int ko_n, int ko_lo, int ko_hi)
+                      hipStream_t s, int ko_n, int ko_lo, int ko_hi, bool quarter_rows)
 {
     int64_t live_rows = kf_rows;
     if (ko_n > 0) {
         if (ko_lo >= ko_hi) ko_n = 0;                            // everything live
         else live_rows = kf_rows / ko_n * (ko_lo + ko_n - ko_hi);
     }
-    return fused3_wsc_launch(p, rows, kf, rows_per_kf, live_rows, s, ko_n, ko_lo, ko_hi);
+    return fused3_wsc_launch(p, rows, kf, rows_per_kf, live_rows, s, ko_n, ko_lo, ko_hi, quarter_rows);
 }
 
 void fused3_destroy(fftconv_plan *p)

@@ -326,7 +326,7 @@ int fused3_ws_launch(const fftconv_plan *p, const void *consts, const void *u, c
 // wave-specialised kernel for complex rows of length 8192, in place (fused3_wsc.hip): the inner step of the
 // multi-pass scheme
 int fused3_wsc_launch(const fftconv_plan *p, void *rows, const void *kf, int64_t rows_per_kf, int64_t live_rows,
-                      hipStream_t s, int ko_n, int ko_lo, int ko_hi);
+                      hipStream_t s, int ko_n, int ko_lo, int ko_hi, bool quarter_rows);
 
 // fused kernel for fft_size 32768 (fused3_big.hip): own tables (in p->f3.consts) and k_f layout
 int fused3_big_init(fftconv_plan *p);

@@ -13,8 +13,10 @@
 //                        has used them.
 // A row needs no staging through LDS: the operand of stage 1 for the planes n3 = 4w .. 4w+3 of wave w,
 // row n2 and four consecutive n1 is four 16-byte pieces of the row (position n1*256 + n2*16 + n3), and
-// the result of the inverse of stage 1 has the same shape.  LDS holds only the exchange buffer XB, double
-// buffered by item parity:
+// the result of the inverse of stage 1 has the same shape.  With the row in natural order a wave takes a
+// quarter of every line; QUARTER says the row is stored as four quarter rows, one per outer wave
+// (multipass_row_slot(): outer lengths up to 64), and the pieces of a wave are then contiguous.  LDS holds
+// only the exchange buffer XB, double buffered by item parity:
 //   XB[t&1]: written by A(t) in step t-1, rewritten in place by B(t) in step t, read by C(t) in step t+1;
 //            A(t+2) reuses it in step t+1, and every outer wave reads (C) and rewrites (A) only its own planes.
 #include <type_traits>
@@ -58,7 +60,7 @@ __device__ __forceinline__ uint32_t tw_f16(float2 w) { return F16::pack(w.x, w.y
 // Row skipping (frequency-sparse filters, Appendix A.4: the trip count of the outer loop): with KoN > 0 the
 // rows come in groups of KoN (the outer frequency digit ko) of which only ko < ko_lo and ko >= ko_hi can
 // meet a non-zero bin; Hlive counts the live rows only.  The other rows are neither read nor written.
-template <typename TT>
+template <typename TT, bool QUARTER>
 __global__ void __launch_bounds__(NT) k_fused3_wsc(uint32_t *rows, const uint32_t *__restrict__ kf, Consts cs, int npairs,
                                                   int Hlive, int KoN, int ko_lo, int ko_hi, LaunchGate gate)
 {
@@ -107,7 +109,9 @@ __global__ void __launch_bounds__(NT) k_fused3_wsc(uint32_t *rows, const uint32_
                 for (int r = 0; r < 4; ++r) twa[i][ct][r] = tw_f16(cs.twa[((c * 2 + ct) * 4 + r) * 64 + l]);
         }
         // this lane's piece (tile k, register r) of a row: n1 = 16k + 4q + r, n2 = c16, n3 = 4w .. 4w+3
-        const int lane_ofs = (4 * q) * 256 + c16 * 16 + 4 * w;
+        // (words: multipass_row_slot() of (n1 = 4q, n2 = c16, n3 = 4w), and the distance between consecutive n1)
+        const int lane_ofs = QUARTER ? w * 2048 + (4 * q) * 64 + c16 * 4 : (4 * q) * 256 + c16 * 16 + 4 * w;
+        constexpr int n1_stride = QUARTER ? 64 : 256;
         auto row_ptr = [&](int t) {
             const int h = t / npairs, pair = t - h * npairs;
             return rows + ((size_t)pair * Hrows + row_of(h)) * (size_t)G::M + lane_ofs;
@@ -118,7 +122,7 @@ __global__ void __launch_bounds__(NT) k_fused3_wsc(uint32_t *rows, const uint32_
 #pragma unroll
             for (int k = 0; k < 2; ++k)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) L[k][r] = *(const uint4 *)(src + (16 * k + r) * 256);
+                for (int r = 0; r < 4; ++r) L[k][r] = *(const uint4 *)(src + (16 * k + r) * n1_stride);
         };
 
         issue_loads(t0);
@@ -158,7 +162,7 @@ __global__ void __launch_bounds__(NT) k_fused3_wsc(uint32_t *rows, const uint32_
                 for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
                     for (int r = 0; r < 4; ++r)
-                        *(uint4 *)(dst + (16 * rt + r) * 256) = make_uint4(ow[rt][r][0], ow[rt][r][1], ow[rt][r][2], ow[rt][r][3]);
+                        *(uint4 *)(dst + (16 * rt + r) * n1_stride) = make_uint4(ow[rt][r][0], ow[rt][r][1], ow[rt][r][2], ow[rt][r][3]);
             }
             // ---- phase A of item s+1: stage 1, twiddle, stage 2 -> XB
             if (doA) {
@@ -274,7 +278,7 @@ __global__ void __launch_bounds__(NT) k_fused3_wsc(uint32_t *rows, const uint32_
 
 // rows_per_kf rows per k_f row, `live_rows` live k_f rows (see the kernel for ko_n, ko_lo, ko_hi)
 int fused3_wsc_launch(const fftconv_plan *p, void *rows, const void *kf, int64_t rows_per_kf, int64_t live_rows,
-                      hipStream_t s, int ko_n, int ko_lo, int ko_hi)
+                      hipStream_t s, int ko_n, int ko_lo, int ko_hi, bool quarter_rows)
 {
     const int64_t T = live_rows * rows_per_kf;
     if (T >= ((int64_t)1 << 31) - 8) {
@@ -283,7 +287,8 @@ int fused3_wsc_launch(const fftconv_plan *p, void *rows, const void *kf, int64_t
     }
     if (T <= 0) return FFTCONV_OK;
     const bool f16 = p->dtype == FFTCONV_F16;
-    auto kern = f16 ? k_fused3_wsc<H16> : k_fused3_wsc<B16>;
+    auto kern = f16 ? (quarter_rows ? k_fused3_wsc<H16, true> : k_fused3_wsc<H16, false>)
+                    : (quarter_rows ? k_fused3_wsc<B16, true> : k_fused3_wsc<B16, false>);
     FC_TRY(raise_dynamic_lds((const void *)kern, (int)WSC_LDS_BYTES));
     const int grid = (int)(T < p->f3.num_cu ? T : p->f3.num_cu);
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NT), WSC_LDS_BYTES, s, (uint32_t *)rows, (const uint32_t *)kf,

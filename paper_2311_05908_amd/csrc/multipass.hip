@@ -260,7 +260,7 @@ __global__ void __launch_bounds__(TB, 4) k_outer_fwd(const uint16_t *__restrict_
             }
         }
         auto put = [&](int kb) {
-            uint32_t *dst = &S[((size_t)ph * No + ka + RA * kb) * MI + r0 + c];
+            uint32_t *dst = &S[((size_t)ph * No + ka + RA * kb) * MI + multipass_row_slot(r0 + c, multipass_quarter_rows(No))];
             if constexpr (CV == 2)
                 *(uint2 *)dst = make_uint2(o[kb][0], o[kb][1]);
             else
@@ -324,7 +324,7 @@ __global__ void __launch_bounds__(TB, 4) k_outer_inv(const uint32_t *__restrict_
             // unconditional (of row 0 instead, its value discarded), so that a thread's loads go out back to
             // back: behind a branch each of them would be waited for before the next is issued.
             const bool dead = ko >= ko_lo && ko < ko_hi;
-            const uint32_t *src = &S[((size_t)ph * No + (dead ? 0 : (mir ? No - ko : ko))) * MI + r0 + c];
+            const uint32_t *src = &S[((size_t)ph * No + (dead ? 0 : (mir ? No - ko : ko))) * MI + multipass_row_slot(r0 + c, multipass_quarter_rows(No))];
             if constexpr (CV == 2) {
                 const uint2 t = *(const uint2 *)src;
                 in[kb][0] = t.x;
@@ -549,7 +549,7 @@ __global__ void __launch_bounds__(TB, 4) k_outer_fwd_real(const uint16_t *__rest
                 const float2 xa = make_float2(0.5f * (z.x + zm.x), 0.5f * (z.y - zm.y));      // (Z + conj Zm) / 2
                 const float2 xb = make_float2(0.5f * (z.y + zm.y), -0.5f * (z.x - zm.x));     // (Z - conj Zm) / (2i)
                 const float2 ta = cmulf(xa, w0), tb = cmulf(xb, w1);
-                *(uint2 *)&S[((size_t)h * No + ko) * MI + r] =
+                *(uint2 *)&S[((size_t)h * No + ko) * MI + multipass_row_slot(r, multipass_quarter_rows(No))] =
                     make_uint2((uint32_t)cv16<F16>(ta.x) | ((uint32_t)cv16<F16>(ta.y) << 16),
                                (uint32_t)cv16<F16>(tb.x) | ((uint32_t)cv16<F16>(tb.y) << 16));
             }
@@ -594,7 +594,7 @@ __global__ void __launch_bounds__(TB, 4) k_outer_inv_real(const uint32_t *__rest
             const int kr = mir ? No - ko : ko;                // the row that holds it, <= No/2
             // rows from ko_lo on: zeroed bins of a sparse filter, never written; they count as zero (the load stays
             // unconditional, of row 0 instead, see k_outer_inv)
-            in[kb] = *(const uint2 *)&S[((size_t)h * No + (kr < ko_lo ? kr : 0)) * MI + r];
+            in[kb] = *(const uint2 *)&S[((size_t)h * No + (kr < ko_lo ? kr : 0)) * MI + multipass_row_slot(r, multipass_quarter_rows(No))];
         }
         // (an empty statement that reads the loaded words: without it the compiler moves each load back under its
         //  condition)
@@ -1180,7 +1180,7 @@ static int multipass_passes(const fftconv_plan *p, const void *u, const void *kf
         rc = f16 ? dispatch_outer<true>(false, g, grid, u, S, (int)B, (int)p->H, (int)p->N, p->M, s, ab_lo, ab_hi, g.No, wg)
                  : dispatch_outer<false>(false, g, grid, u, S, (int)B, (int)p->H, (int)p->N, p->M, s, ab_lo, ab_hi, g.No, wg);
     if (rc) return rc;
-    rc = fused3_inner_rows(p, S, kf, npairs, p->H * g.No, s, g.No, ab_lo, ab_hi);
+    rc = fused3_inner_rows(p, S, kf, npairs, p->H * g.No, s, g.No, ab_lo, ab_hi, multipass_quarter_rows(g.No));
     if (rc) return rc;
     if (packed)
         return f16 ? dispatch_outer_real<true>(true, g, S, y, (int)p->H, (int)p->N, p->M, s, ab_lo, vg)
