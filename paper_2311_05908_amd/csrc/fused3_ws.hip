@@ -69,6 +69,29 @@ __global__ void __launch_bounds__(NT) k_fused3_ws(const uint16_t *__restrict__ u
     const int t1 = (int)(T * (blockIdx.x + 1) / gridDim.x);
     if (t0 >= t1) return;
     const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
+    // (channel, pair, segment) of a work item, t = (h * npairs + pair) * nseg + seg.  Every loop below walks its
+    // items one by one, so the three digits are counted up (a few scalar adds and compares per step) instead of
+    // divided out of t at every use.
+    struct Item {
+        int h, pair, seg;
+    };
+    auto item_at = [&](int t) {
+        Item it;
+        it.h = t / per_h;
+        const int rem = t - it.h * per_h;
+        it.pair = rem / nseg;
+        it.seg = rem - it.pair * nseg;
+        return it;
+    };
+    auto item_next = [&](Item &it) {
+        if (++it.seg == nseg) {
+            it.seg = 0;
+            if (++it.pair == npairs) {
+                it.pair = 0;
+                ++it.h;
+            }
+        }
+    };
 
     if (w < 4) {
         // =========================== outer role: phases A and C, staging ===========================
@@ -103,17 +126,16 @@ __global__ void __launch_bounds__(NT) k_fused3_ws(const uint16_t *__restrict__ u
         // input prefetch: the loads of item s+2 are issued at the start of step s and staged at its end
         uint4 pre[PCH];
         uint4 prew[(GATE & 1) ? PCH : 1], prev[(GATE & 2) ? PCH : 1];
-        auto issue_loads = [&](int t) {
-            const int h = t / per_h, rem = t - h * per_h;
-            const int pair = rem / nseg, seg = rem - pair * nseg;
+        // it: the item min(t, t1 - 1)
+        auto issue_loads = [&](int t, const Item &it) {
+            const int h = it.h, pair = it.pair, seg = it.seg;
 #pragma unroll
             for (int j = 0; j < PCH; ++j) {
                 const int s = j / 2;
                 const int n = co[j % 2];
                 if constexpr (FULL) {
                     // (nseg == 1) past the end of the range the last item is fetched again (in range, unused)
-                    const int tc = t < t1 ? t : t1 - 1;
-                    const int hc = tc / npairs, pc = tc - hc * npairs;
+                    const int hc = it.h, pc = it.pair;
                     const size_t ofs = ((size_t)(2 * (pc * groups + cg[j % 2]) + s) * H + hc) * N + n;
                     pre[j] = *(const uint4 *)(u + ofs);
                     if constexpr (GATE & 1) prew[j] = *(const uint4 *)(wg + ofs);
@@ -134,10 +156,10 @@ __global__ void __launch_bounds__(NT) k_fused3_ws(const uint16_t *__restrict__ u
             }
         };
         // output gate of item t (the item stored at the end of this step)
-        auto issue_loads_v = [&](int t) {
+        // it: the item max(t, t0)
+        auto issue_loads_v = [&](const Item &it) {
             if constexpr (GATE & 2) {
-                const int tc = t < t0 ? t0 : t;
-                const int h = tc / per_h, pair = tc - h * per_h;
+                const int h = it.h, pair = it.pair;
 #pragma unroll
                 for (int j = 0; j < PCH; ++j) {
                     const int s = j / 2;
@@ -164,9 +186,8 @@ __global__ void __launch_bounds__(NT) k_fused3_ws(const uint16_t *__restrict__ u
                 dst[3] = v.w;
             }
         };
-        auto store_out = [&](int t, const uint16_t *YB) {
-            const int h = t / per_h, rem = t - h * per_h;
-            const int pair = rem / nseg, seg = rem - pair * nseg;
+        auto store_out = [&](const Item &it, const uint16_t *YB) {
+            const int h = it.h, pair = it.pair, seg = it.seg;
             const int skip = seg == 0 ? 0 : P;                    // outputs before `skip` lack history: dropped
             const int out_ofs = seg == 0 ? 0 : G::M / 2 + (seg - 1) * Lo;
             const int out_len = min(seg == 0 ? G::M / 2 : Lo, N - out_ofs);
@@ -190,15 +211,18 @@ __global__ void __launch_bounds__(NT) k_fused3_ws(const uint16_t *__restrict__ u
         };
 
         // prologue: item t0 staged; item t0+1 is fetched at the start of the first step
-        issue_loads(t0);
+        Item it_st = item_at(t0);                                 // the item stored in this step: max(s - 2, t0)
+        Item it_ld = it_st;                                       // the item loaded in this step: min(s + 2, t1 - 1)
+        issue_loads(t0, it_ld);
         stage_in(UBb + (t0 & 1) * UBE);
         lds_barrier();
+        if (t0 + 1 < t1) item_next(it_ld);                        // the first step (s = t0 - 1) loads item t0 + 1
 
         for (int s = t0 - 1; s <= t1 + 1; ++s) {
             const bool doC = s - 1 >= t0 && s - 1 < t1;
             const bool doA = s + 1 < t1;
-            issue_loads(s + 2);
-            issue_loads_v(s - 2);
+            issue_loads(s + 2, it_ld);
+            issue_loads_v(it_st);
             // ---- phase C of item s-1: inverse stage 1, n1 < 16; re -> row b, im -> row b+1 -> YB
             if (doC) {
                 const uint32_t *XB = XBb + ((s - 1) & 1) * XBW;
@@ -284,7 +308,11 @@ __global__ void __launch_bounds__(NT) k_fused3_ws(const uint16_t *__restrict__ u
             //      then output of item s-2 -> HBM.  The input goes first: it waits for the loads, and
             //      loads and stores retire through one counter on this target.
             if (s + 2 < t1) stage_in(UBb + ((s + 2) & 1) * UBE);
-            if (s - 2 >= t0) store_out(s - 2, YBb + ((s - 2) & 1) * UBE);
+            if (s - 2 >= t0) {
+                store_out(it_st, YBb + ((s - 2) & 1) * UBE);
+                item_next(it_st);
+            }
+            if (s + 3 < t1) item_next(it_ld);
             lds_barrier();
         }
     } else {
@@ -307,9 +335,11 @@ __global__ void __launch_bounds__(NT) k_fused3_ws(const uint16_t *__restrict__ u
         }
         lds_barrier();                                          // pairs with the outer role's prologue barrier
         int h_cur = -1;
+        Item it_b = item_at(t0);                                  // the item of phase B in this step
         for (int s = t0 - 1; s <= t1 + 1; ++s) {
             if (s >= t0 && s < t1) {
-                const int h = s / per_h;
+                const int h = it_b.h;
+                item_next(it_b);
                 if (h != h_cur) {                                 // new channel: its k_f slice for this wave's k1 planes
                     h_cur = h;
 #pragma unroll
