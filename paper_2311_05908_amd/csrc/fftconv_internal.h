@@ -190,6 +190,8 @@ int fused3_forward_short(const fftconv_plan *p, const void *u, const void *kf, v
 int fused3_init_inner(fftconv_plan *p);
 int fused3_inner_rows(const fftconv_plan *p, void *rows, const void *kf, int64_t rows_per_kf, int64_t kf_rows,
                       hipStream_t s, int ko_n = 0, int ko_lo = 0, int ko_hi = 0, bool quarter_rows = false);
+// the same kernel running the whole convolution of an 8192-point plan, u (B, H, N) -> y with N a multiple of 4
+int fused3_inner_whole(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, hipStream_t s);
 // Order of the innermost frequency digit k3 (N3 values) inside the fused kernels.  Stage 3 leaves
 // k3 in an accumulator slot (tile t, lane group q, register r) = index 16 t + 4 q + r.  The digits are
 // ranked by closeness to DC (0, N3-1, 1, N3-2, ...: k3 is the most significant digit of the

@@ -415,6 +415,11 @@ int fused3_inner_rows(const fftconv_plan *p, void *rows, const void *kf, int64_t
     return fused3_wsc_launch(p, rows, kf, rows_per_kf, live_rows, s, ko_n, ko_lo, ko_hi, quarter_rows);
 }
 
+int fused3_inner_whole(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, hipStream_t s)
+{
+    return fused3_wsc_real_launch(p, u, kf, y, B, s);
+}
+
 void fused3_destroy(fftconv_plan *p)
 {
     if (p->f3.consts) (void)hipFree(p->f3.consts);

@@ -239,6 +239,22 @@ __device__ __forceinline__ void lds_barrier()
 #endif
 }
 
+// Waits until every vector-memory operation of the wave has completed, as an instruction the compiler knows.
+// Placed after the loads of a persistent kernel's prologue (register-resident tables, the first work item) and
+// before its loop.  Without it the compiler's wait-count bookkeeping treats those registers as possibly still
+// in flight at the head of every iteration (it merges the state before the loop with the state at the back edge)
+// and re-issues the prologue's waits there, where they then wait for the loads that the previous iteration
+// has just put in flight for a later work item.
+// (The empty statements and scheduling barriers keep the compiler from moving loads across the wait.)
+__device__ __forceinline__ void vmem_settled()
+{
+    asm volatile("" ::: "memory");                                // no load is moved below this point
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_waitcnt(0x0F70);                           // vmcnt(0)
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("" ::: "memory");
+}
+
 template <int N2, int N3> struct Geo {
     static constexpr int M = N1 * N2 * N3;
     static constexpr int R2 = N2 / 16, R3 = N3 / 16;
@@ -327,6 +343,8 @@ int fused3_ws_launch(const fftconv_plan *p, const void *consts, const void *u, c
 // multi-pass scheme
 int fused3_wsc_launch(const fftconv_plan *p, void *rows, const void *kf, int64_t rows_per_kf, int64_t live_rows,
                       hipStream_t s, int ko_n, int ko_lo, int ko_hi, bool quarter_rows);
+// the same kernel running a whole 8192-point convolution (u and y in place of the rows; N a multiple of 4)
+int fused3_wsc_real_launch(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, hipStream_t s);
 
 // fused kernel for fft_size 32768 (fused3_big.hip): own tables (in p->f3.consts) and k_f layout
 int fused3_big_init(fftconv_plan *p);

@@ -32,7 +32,7 @@ using G = Geo<16, 16>;
 constexpr int XBW = G::XB_WORDS;
 constexpr size_t WSC_LDS_BYTES = (size_t)2 * XBW * 4;
 
-__device__ __forceinline__ uint32_t comp(const uint4 &v, int i) { return i == 0 ? v.x : i == 1 ? v.y : i == 2 ? v.z : v.w; }
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));        // a 16-byte piece as one register tuple
 
 // Four complex products (re[r] + i im[r]) * c[r] in fp32, each rounded once into a 16-bit (re, im) pair of
 // the I/O type; CT is the type of the 4-byte constant.  The 16-bit forms TT::ctw4 round the operand before the
@@ -55,15 +55,27 @@ template <typename TT, typename CT> __device__ __forceinline__ uint4 cmul4(f32x4
     return make_uint4(o[0], o[1], o[2], o[3]);
 }
 __device__ __forceinline__ uint32_t tw_f16(float2 w) { return F16::pack(w.x, w.y); }
+// Re-defines a register-resident constant in place (no instruction).  The bf16 products widen their fp16
+// twiddles to fp32 at every use; seen as loop invariant, the widened values would be computed once before the
+// loop and kept: twice the registers of the table, which the role does not have (they ended up in scratch
+// memory, reloaded inside the loop).
+__device__ __forceinline__ void redefine(uint32_t &c) { asm volatile("" : "+v"(c)); }
 
 // Rows: `npairs` rows per k_f row, Hlive live k_f rows; row (pair, h) starts at word (pair * Hrows + row_of(h)) * 8192.
 // Row skipping (frequency-sparse filters, Appendix A.4: the trip count of the outer loop): with KoN > 0 the
 // rows come in groups of KoN (the outer frequency digit ko) of which only ko < ko_lo and ko >= ko_hi can
 // meet a non-zero bin; Hlive counts the live rows only.  The other rows are neither read nor written.
-template <typename TT, bool QUARTER>
+//
+// MODE: 0 = rows in natural order, 1 = quarter rows, 2 = no rows at all: the transform is 8192 points long (outer
+// length 1), an item is a pair of batch rows of u (row 2*pair as the real, row 2*pair+1 as the imaginary part; samples
+// from N on are zero and are not read) and the real / imaginary parts of the result are the first N samples of the two
+// rows of y.  A lane's piece is then 4 consecutive samples (8 bytes) of either row; N is a multiple of 4, Hlive = H.
+template <typename TT, int MODE>
 __global__ void __launch_bounds__(NT) k_fused3_wsc(uint32_t *rows, const uint32_t *__restrict__ kf, Consts cs, int npairs,
-                                                  int Hlive, int KoN, int ko_lo, int ko_hi, LaunchGate gate)
+                                                  int Hlive, int KoN, int ko_lo, int ko_hi, const uint16_t *__restrict__ u,
+                                                  uint16_t *__restrict__ y, int B, int N, LaunchGate gate)
 {
+    constexpr bool QUARTER = MODE == 1, REAL = MODE == 2;
     extern __shared__ uint32_t smem[];
     if (gate_closed(gate)) return;
     uint32_t *const XBb = smem;                                   // [2][XBW]
@@ -116,19 +128,64 @@ __global__ void __launch_bounds__(NT) k_fused3_wsc(uint32_t *rows, const uint32_
             const int h = t / npairs, pair = t - h * npairs;
             return rows + ((size_t)pair * Hrows + row_of(h)) * (size_t)G::M + lane_ofs;
         };
-        uint4 L[2][4];                                            // the row being loaded / consumed by phase A
-        auto issue_loads = [&](int t) {
-            const uint32_t *src = row_ptr(t);
+        // MODE 2: first sample of this lane's piece (tile k, register r) is real_ofs + (16k + r) * 256; bit 4k + r
+        // of in_range says that it lies below N (the piece then does entirely)
+        const int real_ofs = (4 * q) * 256 + c16 * 16 + 4 * w;
+        uint32_t in_range = 0;
+        if constexpr (REAL) {
 #pragma unroll
             for (int k = 0; k < 2; ++k)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) L[k][r] = *(const uint4 *)(src + (16 * k + r) * n1_stride);
+                for (int r = 0; r < 4; ++r) in_range |= (real_ofs + (16 * k + r) * 256 < N ? 1u : 0u) << (4 * k + r);
+        }
+        auto real_rows = [&](int t, size_t &e0, size_t &e1, bool &has1) {   // first elements of the two rows of item t
+            const int h = t / npairs, pair = t - h * npairs;
+            has1 = 2 * pair + 1 < B;
+            e0 = ((size_t)(2 * pair) * Hlive + h) * (size_t)N;
+            e1 = ((size_t)(has1 ? 2 * pair + 1 : 2 * pair) * Hlive + h) * (size_t)N;
+        };
+        u32x4 L[2][4];                                            // the row being loaded / consumed by phase A
+        bool L_has1 = true;                                       // MODE 2: the item in L has a second row
+        auto issue_loads = [&](int t) {
+            if constexpr (REAL) {
+                // every load unconditional (a piece beyond N reads the row's first samples and is dropped in
+                // phase A): behind a condition each would be waited for before the next one is issued
+                size_t e0, e1;
+                real_rows(t, e0, e1, L_has1);
+#pragma unroll
+                for (int k = 0; k < 2; ++k)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const int n = (in_range >> (4 * k + r)) & 1u ? real_ofs + (16 * k + r) * 256 : 0;
+                        const uint2 a = *(const uint2 *)(u + e0 + n), b = *(const uint2 *)(u + e1 + n);
+                        L[k][r] = u32x4{a.x, a.y, b.x, b.y};
+                    }
+            } else {
+                const uint32_t *src = row_ptr(t);
+#pragma unroll
+                for (int k = 0; k < 2; ++k)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) L[k][r] = *(const u32x4 *)(src + (16 * k + r) * n1_stride);
+            }
         };
 
         issue_loads(t0);
-        for (int s = t0 - 1; s <= t1; ++s) {
-            const bool doC = s - 1 >= t0 && s - 1 < t1;
-            const bool doA = s + 1 < t1;
+        vmem_settled();
+        // One step s: phase C of item s-1 (doC), phase A of item s+1 (doA), the loads of item s+2 (doL: only with
+        // doA).  The steps in the middle of a workgroup's range have all three and are a loop of their own with
+        // the flags as constants: the compiler's wait counts are exact only in straight-line code.  With the
+        // three parts behind conditions it assumes at every join that the shorter path was taken -- no stores
+        // issued in phase C, the row registers not yet consumed by phase A -- and then waits for the row loads
+        // with a count that also drains the stores issued after them, and for everything before the next loads.
+        auto step = [&](const int s, const bool doC, const bool doA, const bool doL) __attribute__((always_inline)) {
+            if constexpr (!std::is_same<TT, H16>::value) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) redefine(twa[i][ct][r]);
+            }
             // ---- phase C of item s-1: inverse stage 1 -> the row, in place
             if (doC) {
                 const uint32_t *XB = XBb + ((s - 1) & 1) * XBW;
@@ -139,41 +196,85 @@ __global__ void __launch_bounds__(NT) k_fused3_wsc(uint32_t *rows, const uint32_
                         x[ks] = make_uint4(src[0], src[G::PK1], src[2 * G::PK1], src[3 * G::PK1]);
                     }
                 };
-                uint4 xc[4][2];                                   // [plane][K step]
-#pragma unroll
-                for (int i = 0; i < 4; ++i) read_c(i, xc[i]);
+                uint4 xc[2][2];                                   // [plane parity][K step], read one plane ahead
+                read_c(0, xc[0]);
                 uint32_t ow[2][4][4];                             // [n1 tile][r][plane]
 #pragma unroll
-                for (int i = 0; i < 4; ++i)
+                for (int i = 0; i < 4; ++i) {
+                    if (i + 1 < 4) read_c(i + 1, xc[(i + 1) & 1]);
 #pragma unroll
                     for (int rt = 0; rt < 2; ++rt) {
                         f32x4 dre = zero4, dim = zero4;
 #pragma unroll
                         for (int ks = 0; ks < 2; ++ks) {
-                            dre = TT::mfma(tab1i[ks][rt][0], xc[i][ks], dre);
-                            dim = TT::mfma(tab1i[ks][rt][1], xc[i][ks], dim);
+                            dre = TT::mfma(tab1i[ks][rt][0], xc[i & 1][ks], dre);
+                            dim = TT::mfma(tab1i[ks][rt][1], xc[i & 1][ks], dim);
                         }
                         // lane: n2 = c16; reg r: n1 = 16 rt + 4q + r
 #pragma unroll
                         for (int r = 0; r < 4; ++r) ow[rt][r][i] = TT::pack(dre[r], dim[r]);
                     }
-                uint32_t *dst = row_ptr(s - 1);
+                }
+                if constexpr (REAL) {
+                    size_t e0, e1;
+                    bool has1;
+                    real_rows(s - 1, e0, e1, has1);
 #pragma unroll
-                for (int rt = 0; rt < 2; ++rt)
+                    for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
-                    for (int r = 0; r < 4; ++r)
-                        *(uint4 *)(dst + (16 * rt + r) * n1_stride) = make_uint4(ow[rt][r][0], ow[rt][r][1], ow[rt][r][2], ow[rt][r][3]);
+                        for (int r = 0; r < 4; ++r) {
+                            if (!((in_range >> (4 * rt + r)) & 1u)) continue;
+                            const int n = real_ofs + (16 * rt + r) * 256;
+                            const uint32_t(&o)[4] = ow[rt][r];
+                            // low halves = real parts = row 2*pair, high halves = row 2*pair + 1
+                            *(uint2 *)(y + e0 + n) = make_uint2(__builtin_amdgcn_perm(o[1], o[0], 0x05040100u),
+                                                                __builtin_amdgcn_perm(o[3], o[2], 0x05040100u));
+                            if (has1)
+                                *(uint2 *)(y + e1 + n) = make_uint2(__builtin_amdgcn_perm(o[1], o[0], 0x07060302u),
+                                                                    __builtin_amdgcn_perm(o[3], o[2], 0x07060302u));
+                        }
+                } else {
+                    uint32_t *dst = row_ptr(s - 1);
+#pragma unroll
+                    for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r)
+                            *(uint4 *)(dst + (16 * rt + r) * n1_stride) =
+                                make_uint4(ow[rt][r][0], ow[rt][r][1], ow[rt][r][2], ow[rt][r][3]);
+                }
             }
             // ---- phase A of item s+1: stage 1, twiddle, stage 2 -> XB
             if (doA) {
                 uint32_t *XB = XBb + ((s + 1) & 1) * XBW;
+                // the row registers are consumed from here on, not earlier: without this the compiler gathers
+                // the operands (register moves) at the top of the step and waits there for the loads, which
+                // were issued just before the barrier
+#pragma unroll
+                for (int k = 0; k < 2; ++k)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        asm volatile("" : "+v"(L[k][r])::"memory");       // as a tuple: it stays where the load put it
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const int c = 4 * w + i;
                     uint4 x1[2];
 #pragma unroll
-                    for (int ks = 0; ks < 2; ++ks)
-                        x1[ks] = make_uint4(comp(L[ks][0], i), comp(L[ks][1], i), comp(L[ks][2], i), comp(L[ks][3], i));
+                    for (int ks = 0; ks < 2; ++ks) {
+                        if constexpr (REAL) {
+                            // sample i of the piece from either row -> one (re, im) word; zero beyond N
+                            uint32_t d[4];
+#pragma unroll
+                            for (int r = 0; r < 4; ++r) {
+                                const u32x4 v = L[ks][r];
+                                const uint32_t lo = i < 2 ? v.x : v.y, hi = L_has1 ? (i < 2 ? v.z : v.w) : 0u;
+                                const uint32_t word = __builtin_amdgcn_perm(hi, lo, (i & 1) ? 0x07060302u : 0x05040100u);
+                                d[r] = (in_range >> (4 * ks + r)) & 1u ? word : 0u;
+                            }
+                            x1[ks] = make_uint4(d[0], d[1], d[2], d[3]);
+                        } else {
+                            x1[ks] = make_uint4(L[ks][0][i], L[ks][1][i], L[ks][2][i], L[ks][3][i]);
+                        }
+                    }
                     uint4 x2[2];
 #pragma unroll
                     for (int ct = 0; ct < 2; ++ct) {
@@ -195,11 +296,15 @@ __global__ void __launch_bounds__(NT) k_fused3_wsc(uint32_t *rows, const uint32_
                                                    TT::pack(dre[2], dim[2]), TT::pack(dre[3], dim[3]));
                     }
                 }
+                // ---- the row of item s+2: in flight during the barrier and phase C of the next step
+                if (doL) issue_loads(s + 2);
             }
-            // ---- the row of item s+2: in flight during the barrier and phase C of the next step
-            if (s + 2 < t1) issue_loads(s + 2);
             lds_barrier();
-        }
+        };
+        int s = t0 - 1;
+        for (; s <= t0 && s <= t1; ++s) step(s, false, s + 1 < t1, s + 2 < t1);          // nothing to finish yet
+        for (; s + 2 < t1; ++s) step(s, true, true, true);
+        for (; s <= t1; ++s) step(s, true, s + 1 < t1, false);                           // nothing left to load
     } else {
         // =========================== inner role: phase B ===========================
         const int wq = w - 4;
@@ -229,8 +334,16 @@ __global__ void __launch_bounds__(NT) k_fused3_wsc(uint32_t *rows, const uint32_
 #pragma unroll
                 for (int r = 0; r < 4; ++r) kfr[i][r] = src[(i * 4 + r) * 64];
         }
-        for (int s = t0 - 1; s <= t1; ++s) {
-            if (s >= t0 && s < t1) {
+        vmem_settled();
+        lds_barrier();                                            // step t0 - 1: nothing to do yet
+        for (int s = t0; s < t1; ++s) {
+            if constexpr (!std::is_same<TT, H16>::value) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) redefine(twb[i][r]);
+            }
+            {
                 uint32_t *XB = XBb + (s & 1) * XBW;
                 const bool more = s + 1 < t1;
                 const uint32_t *kf_next = kf_ptr(more ? s + 1 : s);
@@ -254,8 +367,7 @@ __global__ void __launch_bounds__(NT) k_fused3_wsc(uint32_t *rows, const uint32_
                     const uint4 x3i = cmul4<TT, TT>(dre, dim, kfr[i]);
                     // this plane's constants of the next item (the same row again while the item's k_f row stays)
 #pragma unroll
-                    for (int r = 0; r < 4; ++r)
-                        if (more) kfr[i][r] = kf_next[(i * 4 + r) * 64];
+                    for (int r = 0; r < 4; ++r) kfr[i][r] = kf_next[(i * 4 + r) * 64];
                     // inverse stage 3: rows k2, contraction over k3
                     dre = TT::mfma(x3i, tab3i[0], zero4);
                     dim = TT::mfma(x3i, tab3i[1], zero4);
@@ -271,6 +383,7 @@ __global__ void __launch_bounds__(NT) k_fused3_wsc(uint32_t *rows, const uint32_
             }
             lds_barrier();
         }
+        lds_barrier();                                            // step t1: the outer role finishes the last item
     }
 }
 
@@ -287,12 +400,36 @@ int fused3_wsc_launch(const fftconv_plan *p, void *rows, const void *kf, int64_t
     }
     if (T <= 0) return FFTCONV_OK;
     const bool f16 = p->dtype == FFTCONV_F16;
-    auto kern = f16 ? (quarter_rows ? k_fused3_wsc<H16, true> : k_fused3_wsc<H16, false>)
-                    : (quarter_rows ? k_fused3_wsc<B16, true> : k_fused3_wsc<B16, false>);
+    auto kern = f16 ? (quarter_rows ? k_fused3_wsc<H16, 1> : k_fused3_wsc<H16, 0>)
+                    : (quarter_rows ? k_fused3_wsc<B16, 1> : k_fused3_wsc<B16, 0>);
     FC_TRY(raise_dynamic_lds((const void *)kern, (int)WSC_LDS_BYTES));
     const int grid = (int)(T < p->f3.num_cu ? T : p->f3.num_cu);
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NT), WSC_LDS_BYTES, s, (uint32_t *)rows, (const uint32_t *)kf,
-                       consts_at<16, 16>(p->f3.consts), (int)rows_per_kf, (int)live_rows, ko_n, ko_lo, ko_hi, launch_gate());
+                       consts_at<16, 16>(p->f3.consts), (int)rows_per_kf, (int)live_rows, ko_n, ko_lo, ko_hi,
+                       (const uint16_t *)nullptr, (uint16_t *)nullptr, 0, 0, launch_gate());
+    FC_HIP(hipGetLastError());
+    return FFTCONV_OK;
+}
+
+// The whole convolution of an 8192-point plan in this kernel (MODE 2): u (B, H, N) -> y, N <= 8192 a multiple of 4.
+int fused3_wsc_real_launch(const fftconv_plan *p, const void *u, const void *kf, void *y, int64_t B, hipStream_t s)
+{
+    const int64_t npairs = (B + 1) / 2, T = npairs * p->H;
+    if (p->M != G::M || p->N % 4 != 0 || p->N > G::M) {
+        set_error("fftconv_forward: the single-kernel 8192-point route needs fft_size 8192 and N a multiple of 4");
+        return FFTCONV_EINVAL;
+    }
+    if (T >= ((int64_t)1 << 31) - 8) {
+        set_error("fftconv_forward: %lld row pairs exceed the fused kernel's limit", (long long)T);
+        return FFTCONV_EUNSUPPORTED;
+    }
+    if (T <= 0) return FFTCONV_OK;
+    auto kern = p->dtype == FFTCONV_F16 ? k_fused3_wsc<H16, 2> : k_fused3_wsc<B16, 2>;
+    FC_TRY(raise_dynamic_lds((const void *)kern, (int)WSC_LDS_BYTES));
+    const int grid = (int)(T < p->f3.num_cu ? T : p->f3.num_cu);
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NT), WSC_LDS_BYTES, s, (uint32_t *)nullptr, (const uint32_t *)kf,
+                       consts_at<16, 16>(p->f3.consts), (int)npairs, (int)p->H, 0, 0, 0, (const uint16_t *)u, (uint16_t *)y,
+                       (int)B, (int)p->N, launch_gate());
     FC_HIP(hipGetLastError());
     return FFTCONV_OK;
 }

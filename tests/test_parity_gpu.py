@@ -271,8 +271,11 @@ def test_multipass_all_outputs(dtype, B, H, N, M):
 
 
 @pytest.mark.parametrize("dtype,B,H,N,M", [
-    ("bf16", 2, 2, 8192, 8192),      # circular, no outer transform (a pair of rows is packed, convolved, unpacked)
-    ("f16", 3, 1, 4100, 8192),       # causal, N not a multiple of 8: the same route
+    ("bf16", 2, 2, 8192, 8192),      # circular, no outer transform: the inner kernel reads u and writes y itself
+    ("f16", 3, 1, 4100, 8192),       # causal, N a multiple of 4 but not of 8: the same single kernel, odd batch
+    ("bf16", 5, 3, 6000, 8192),      # N > fft/2 (wrap-around taps), ragged tail inside a lane's range, odd batch
+    ("f16", 1, 2, 8192, 8192),       # a lone row: its partner is taken as zero and never stored
+    ("f16", 2, 2, 4102, 8192),       # N not a multiple of 4: pack, convolve, unpack as three passes
     ("bf16", 3, 2, 16384, 16384),    # circular, outer length 2
     ("f16", 2, 1, 9000, 16384),      # N > fft/2, ragged
     ("bf16", 1, 2, 8190, 16384),     # causal, N not a multiple of 8, outer length 2 with the implicit zero half
@@ -287,6 +290,21 @@ def test_multipass_circular_and_ragged(dtype, B, H, N, M):
     err, plan = check_all_sequences(w)
     print("multipass %s B=%d H=%d N=%d M=%d path=%s factors=%s err=%.3e" % (dtype, B, H, N, M, plan.path, plan.factors, err),
           flush=True)
+    assert plan.path == "multipass"
+    assert err <= TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype,B,H,N", [
+    ("bf16", 6, 300, 8192),        # 900 work items: three or four per workgroup, the software pipeline at full depth
+    ("f16", 3, 171, 5004),         # one or two items per workgroup, ragged, every channel's last pair without partner
+])
+def test_circular_8192_single_kernel_many_items(dtype, B, H, N):
+    """fft 8192 with N > fft/2 (Section 2.1: circular convolution): one kernel, several work items per workgroup;
+    sampled output positions of every sequence, the first and last ones always."""
+    from parity_util import check_sampled_positions
+    w = synth.scaled(W["cfg2"], B=B, H=H, N=N, fft_size=8192, dtype=dtype)
+    err, plan = check_sampled_positions(w, n_pos=128, edge=2)     # fewer positions: the norm estimate is too noisy
+    print("circular 8192 %s B=%d H=%d N=%d path=%s err=%.3e" % (dtype, B, H, N, plan.path, err), flush=True)
     assert plan.path == "multipass"
     assert err <= TOL[dtype]
 
