@@ -818,6 +818,7 @@ __global__ void __launch_bounds__(NT, 2) k_fused3_big_dk(const uint16_t *__restr
 
     opaque();
     issue_pre(0, 0, NCH);
+    if constexpr (!PACKZ) load_tab3(0);                   // one pass: the stage-3 matrices stay in registers
     for (int s = 0; s < S; ++s) {
         const int item = s >> 1, which = s & 1;
         const int jp = item / npairs, pair = item - jp * npairs;
@@ -835,8 +836,13 @@ __global__ void __launch_bounds__(NT, 2) k_fused3_big_dk(const uint16_t *__restr
         SCHED_FENCE();
         phase_A();
         SCHED_FENCE();
+        // Two passes: the pass's stage-3 matrices take the place of phase A's tables, in every step and ahead of
+        // the input loads.  (Loaded only in a pass's first step they sat behind a condition; the compiler then has to
+        // take them as possibly in flight in every step, and as they came after the input loads, the wait before
+        // stage 3 waited for the whole next input as well.)
+        if constexpr (PACKZ) load_tab3(pass);
+        SCHED_FENCE();
         issue_pre(s + 1 < S ? s + 1 : s, EARLY, NCH);
-        if (which == 0 && pair == 0 && (NPASS > 1 || s == 0)) load_tab3(PACKZ ? pass : 0);
         lds_barrier();
         // stage 3 of this wave's 4 k1 planes
 #pragma unroll

@@ -116,10 +116,13 @@ __global__ void __launch_bounds__(NT) k_fused3_dk(const uint16_t *__restrict__ u
         stage_in(UBb);
         lds_barrier();
 
-        for (int s = -1; s < S; ++s) {
+        // One step; all but the last two have both parts and run as a loop of their own with constant flags, so that
+        // a step is straight-line code: with the parts behind conditions the compiler moves the loads from the top
+        // of the step down into the conditional block that consumes them, where they are waited for at once.
+        auto step = [&](const int s, const bool doA, const bool doIn) __attribute__((always_inline)) {
             issue_loads(s + 2);
             // ---- stage 1, twiddle, stage 2 of input s+1 -> XB
-            if (s + 1 < S) {
+            if (doA) {
                 uint32_t *XB = XBb + ((s + 1) & 1) * XBW;
                 const uint32_t *UB32 = (const uint32_t *)(UBb + ((s + 1) & 1) * UBE);
                 uint32_t w0[2][4], w1[2][4];
@@ -157,9 +160,12 @@ __global__ void __launch_bounds__(NT) k_fused3_dk(const uint16_t *__restrict__ u
                     }
                 }
             }
-            if (s + 2 < S) stage_in(UBb + ((s + 2) & 1) * UBE);
+            if (doIn) stage_in(UBb + ((s + 2) & 1) * UBE);
             lds_barrier();
-        }
+        };
+        int s = -1;
+        for (; s + 2 < S; ++s) step(s, true, true);
+        for (; s < S; ++s) step(s, s + 1 < S, false);
     } else {
         // =========================== inner role: stage 3, product, accumulation ===========================
         const int wq = w - 4;
@@ -175,8 +181,9 @@ __global__ void __launch_bounds__(NT) k_fused3_dk(const uint16_t *__restrict__ u
             accim[i] = zero4;
         }
         lds_barrier();                                            // pairs with the outer role's prologue barrier
-        for (int s = -1; s < S; ++s) {
-            if (s >= 0) {
+        lds_barrier();                                            // step -1: nothing to do yet
+        for (int s = 0; s < S; ++s) {
+            {
                 const int which = s & 1, item = s >> 1;
                 const uint32_t *XB = XBb + (s & 1) * XBW;
                 // operand of stage 3 for plane k1: columns k2 = c16, slots = (re, im) of n3 = 4q + r
