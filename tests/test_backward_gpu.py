@@ -37,6 +37,7 @@ SHAPES = [
     ("bf16", 3, 2, 40000, 131072, 5000), # A = 16, odd batch (the last row has no partner), ragged N
     ("f32", 3, 2, 8192, 16384, 8192),   # fp32 I/O, A = 2
     ("f16", 2, 1, 16384, 16384, 700),   # circular (N = fft_size) multi-pass plan
+    ("bf16", 3, 2, 8192, 8192, 600),    # circular fft 8192: du through the single-kernel route of the multi-pass family
 ]
 
 

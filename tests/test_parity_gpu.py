@@ -275,6 +275,8 @@ def test_multipass_all_outputs(dtype, B, H, N, M):
     ("f16", 3, 1, 4100, 8192),       # causal, N a multiple of 4 but not of 8: the same single kernel, odd batch
     ("bf16", 5, 3, 6000, 8192),      # N > fft/2 (wrap-around taps), ragged tail inside a lane's range, odd batch
     ("f16", 1, 2, 8192, 8192),       # a lone row: its partner is taken as zero and never stored
+    ("bf16", 2, 1, 4, 8192),         # the shortest row the single kernel takes: one 8-byte piece
+    ("bf16", 3, 1, 8188, 8192),      # the last piece of a row missing
     ("f16", 2, 2, 4102, 8192),       # N not a multiple of 4: pack, convolve, unpack as three passes
     ("bf16", 3, 2, 16384, 16384),    # circular, outer length 2
     ("f16", 2, 1, 9000, 16384),      # N > fft/2, ragged
