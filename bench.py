@@ -426,7 +426,7 @@ def main():
                      "mfma_frac": mfma_frac, "mfma_achieved": mfma_tflops, "mfma_peak": MFMA_PEAK_TFLOPS,
                      "mfma_unit": "TFLOP/s", "mfma_flops": flops,
                      "limiter": ("HBM traffic of the workspace (three passes, measured traffic about 2 x the algorithmic bytes, "
-                                 "moved at 3.5-4.3 TB/s; profiles/multipass_cfg4.md)" if plan.path == "multipass" else
+                                 "moved at 3.4-4.7 TB/s; profiles/multipass_cfg4.md)" if plan.path == "multipass" else
                                  "vector-instruction issue (SQ_INSTS_VALU against SQ_BUSY_CYCLES in profiles/)"),
                      "kernel": ("k_fused3_ws" if w.fft_size == 8192 else "k_fused3_big") if plan.path == "fused3" else plan.path,
                      "algorithmic_bytes": abytes},
