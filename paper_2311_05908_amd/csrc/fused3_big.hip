@@ -208,9 +208,7 @@ __global__ void __launch_bounds__(NT, (N2 == 16 && !GATED) ? 4 : 2) k_fused3_big
 #pragma unroll
         for (int a = 0; a < R2; ++a)
 #pragma unroll
-            for (int b = 0; b < T2; ++b)
-#pragma unroll
-                for (int p = 0; p < 2; ++p) tabA[sl][a][b][p] = ld16(rc, base, BG::OFF_TAB2 + ((a * R2 + b) * 2 + p) * 1024);
+            for (int b = 0; b < T2; ++b) tabA[sl][a][b][0] = ld16(rc, base, BG::OFF_TAB2 + ((a * R2 + b) * 2 + 0) * 1024);
     };
     auto load_twa = [&](int i) {
         const int c = 4 * w + i, sl = i % PD;
@@ -228,9 +226,7 @@ __global__ void __launch_bounds__(NT, (N2 == 16 && !GATED) ? 4 : 2) k_fused3_big
 #pragma unroll
         for (int a = 0; a < T2; ++a)
 #pragma unroll
-            for (int b = 0; b < R2; ++b)
-#pragma unroll
-                for (int p = 0; p < 2; ++p) tabB[sl][a][b][p] = ld16(rc, base, BG::OFF_TAB2I + ((a * R2 + b) * 2 + p) * 1024);
+            for (int b = 0; b < R2; ++b) tabB[sl][a][b][0] = ld16(rc, base, BG::OFF_TAB2I + ((a * R2 + b) * 2 + 0) * 1024);
     };
     auto load_twb = [&](int i) {
         const int c = w + 8 * i, sl = i % PD;
@@ -372,6 +368,14 @@ __global__ void __launch_bounds__(NT, (N2 == 16 && !GATED) ? 4 : 2) k_fused3_big
             SCHED_FENCE();
             if (i + PD < 4) load_twa(i + PD);
             SCHED_FENCE();
+            // Of the streamed per-plane matrices only the operand of the real part is fetched; the operand of the
+            // imaginary part holds the same numbers in another arrangement and is made from it here: one or two vector
+            // operations per word instead of four more bytes per lane through the load path, which is the kernel's
+            // scarcest resource.
+#pragma unroll
+            for (int ks = 0; ks < R2; ++ks)
+#pragma unroll
+                for (int ct2 = 0; ct2 < T2; ++ct2) tabA[i % PD][ks][ct2][1] = TT::imag_operand(tabA[i % PD][ks][ct2][0]);
 #pragma unroll
             for (int ct = 0; ct < 2; ++ct)
 #pragma unroll
@@ -536,6 +540,10 @@ __global__ void __launch_bounds__(NT, (N2 == 16 && !GATED) ? 4 : 2) k_fused3_big
             if (next) load_twb(i + PD);
             SCHED_FENCE();
 #pragma unroll
+            for (int ks = 0; ks < T2; ++ks)                // (see phase A)
+#pragma unroll
+                for (int cn2 = 0; cn2 < R2; ++cn2) tabB[i % PD][ks][cn2][1] = TT::imag_operand(tabB[i % PD][ks][cn2][0]);
+#pragma unroll
             for (int cn3 = 0; cn3 < 2; ++cn3)
 #pragma unroll
                 for (int cn2 = 0; cn2 < R2; ++cn2) {
@@ -566,6 +574,10 @@ __global__ void __launch_bounds__(NT, (N2 == 16 && !GATED) ? 4 : 2) k_fused3_big
             }
     };
 
+    // The matrices that do not depend on the plane (stage 1, its inverse, stage 3: 64 registers) stay in registers for
+    // the whole launch where the kernel has them to spare; otherwise each set is fetched again before the phase
+    // that uses it.
+    constexpr bool RESIDENT = FULL && !GATED && N2 == 32 && SP == 0;
     // ---- prologue: phase A of the first pair
     opaque();
     issue_pre(item(jb));
@@ -586,6 +598,7 @@ __global__ void __launch_bounds__(NT, (N2 == 16 && !GATED) ? 4 : 2) k_fused3_big
     SCHED_FENCE();
     lds_barrier();
 
+    vmem_settled();                                     // nothing of the prologue is still in flight inside the loop
     // Per pair, 5 workgroup barriers:
     //   [B(t)] | [C(t) -> registers] | [y(t), u(t+1) -> staging] | [staging -> registers] | [A(t+1); store y(t)] |
     for (int v = jb; v < n_local; v += nb) {
@@ -596,7 +609,7 @@ __global__ void __launch_bounds__(NT, (N2 == 16 && !GATED) ? 4 : 2) k_fused3_big
         phase_B(t / npairs);
         SCHED_FENCE();
         // tables of the next phase and the next pair's input: in flight across the barrier and phase C
-        load_fixed_outer();
+        if constexpr (!RESIDENT) load_fixed_outer();
 #pragma unroll
         for (int i = 0; i < PD; ++i) {
             load_tabA(i);
@@ -616,7 +629,7 @@ __global__ void __launch_bounds__(NT, (N2 == 16 && !GATED) ? 4 : 2) k_fused3_big
         lds_barrier();                                  // staging consumed: phase A may overwrite it
         phase_A();
         SCHED_FENCE();
-        load_tab3();
+        if constexpr (!RESIDENT) load_tab3();
         load_plane0(tn / npairs);
         SCHED_FENCE();
         // the stores go last: loads and stores retire through one counter on this target, and
@@ -704,10 +717,8 @@ __global__ void __launch_bounds__(NT, 2) k_fused3_big_dk(const uint16_t *__restr
 #pragma unroll
         for (int a = 0; a < R2; ++a)
 #pragma unroll
-            for (int b = 0; b < R2; ++b)
-#pragma unroll
-                for (int p = 0; p < 2; ++p)
-                    tabA[a][b][p] = ld16(sz + c * BG::PLANE2, BG::OFF_TAB2 + ((a * R2 + b) * 2 + p) * 1024);
+            for (int b = 0; b < R2; ++b)               // the operand of the real part only (see k_fused3_big)
+                tabA[a][b][0] = ld16(sz + c * BG::PLANE2, BG::OFF_TAB2 + ((a * R2 + b) * 2 + 0) * 1024);
 #pragma unroll
         for (int a = 0; a < R2; ++a)
 #pragma unroll
@@ -782,6 +793,10 @@ __global__ void __launch_bounds__(NT, 2) k_fused3_big_dk(const uint16_t *__restr
                 }
             }
             uint4 o[2][R2];
+#pragma unroll
+            for (int ks = 0; ks < R2; ++ks)
+#pragma unroll
+                for (int ct2 = 0; ct2 < R2; ++ct2) tabA[ks][ct2][1] = TT::imag_operand(tabA[ks][ct2][0]);
 #pragma unroll
             for (int ct = 0; ct < 2; ++ct)
 #pragma unroll

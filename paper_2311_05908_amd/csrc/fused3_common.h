@@ -141,6 +141,13 @@ struct B16 {
     using CW = uint32_t;
     static __device__ __forceinline__ f32x4 mfma(uint4 a, uint4 b, f32x4 c) { return BF16::mfma(a, b, c); }
     static __device__ __forceinline__ uint32_t pack(float lo, float hi) { return BF16::pack(lo, hi); }
+    // The matrix operand that yields the imaginary part of a complex product, from the one that yields the real
+    // part: every 32-bit word (g.re, -g.im) becomes (g.im, g.re): halves swapped, sign of the new lower half flipped.
+    static __device__ __forceinline__ uint4 imag_operand(uint4 a)
+    {
+        auto f = [](uint32_t x) { return __builtin_amdgcn_perm(x, x, 0x01000302u) ^ 0x00008000u; };
+        return make_uint4(f(a.x), f(a.y), f(a.z), f(a.w));
+    }
     template <bool CONJ> static __device__ __forceinline__ uint4 ctw4(f32x4 re, f32x4 im, const CW (&c)[4])
     {
         const uint32_t p0 = pack(re[0], im[0]), p1 = pack(re[1], im[1]);
@@ -189,6 +196,20 @@ struct H16 {
     using CW = uint32_t;
     static __device__ __forceinline__ f32x4 mfma(uint4 a, uint4 b, f32x4 c) { return F16::mfma(a, b, c); }
     static __device__ __forceinline__ uint32_t pack(float lo, float hi) { return F16::pack(lo, hi); }
+    // The matrix operand that yields the imaginary part of a complex product, from the one that yields the real
+    // part: every 32-bit word (g.re, -g.im) becomes (g.im, g.re).  One packed multiplication by (-1, 1) with the
+    // halves of the source swapped: exact.
+    static __device__ __forceinline__ uint4 imag_operand(uint4 a)
+    {
+        uint4 d;
+        asm("v_pk_mul_f16 %0, %4, %8 op_sel:[1,0] op_sel_hi:[0,1]\n\t"
+            "v_pk_mul_f16 %1, %5, %8 op_sel:[1,0] op_sel_hi:[0,1]\n\t"
+            "v_pk_mul_f16 %2, %6, %8 op_sel:[1,0] op_sel_hi:[0,1]\n\t"
+            "v_pk_mul_f16 %3, %7, %8 op_sel:[1,0] op_sel_hi:[0,1]"
+            : "=&v"(d.x), "=&v"(d.y), "=&v"(d.z), "=&v"(d.w)
+            : "v"(a.x), "v"(a.y), "v"(a.z), "v"(a.w), "s"(0x3C00BC00u));
+        return d;
+    }
     static __host__ __device__ inline CW cconst(uint32_t re, uint32_t im, bool) { return re | (im << 16); }
     // the constant as an fp32 pair
     static __device__ __forceinline__ float2 widen(CW c)

@@ -99,7 +99,7 @@ __global__ void __launch_bounds__(NT) k_fused3_wsc(uint32_t *rows, const uint32_
 
     if (w < 4) {
         // =========================== outer role: phases C and A, all row traffic ===========================
-        uint4 tab1[2][2][2], tab1i[2][2][2], tab2[4][2];
+        uint4 tab1[2][2][2], tab1i[2][2][2], tab2[4];             // tab2: the operand of the real part only
         uint32_t twa[4][2][4];                                    // fp16 pairs
 #pragma unroll
         for (int a = 0; a < 2; ++a)
@@ -113,8 +113,7 @@ __global__ void __launch_bounds__(NT) k_fused3_wsc(uint32_t *rows, const uint32_
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int c = 4 * w + i;
-#pragma unroll
-            for (int p = 0; p < 2; ++p) tab2[i][p] = cs.tab2[(c * 2 + p) * 64 + l];
+            tab2[i] = cs.tab2[(c * 2 + 0) * 64 + l];
 #pragma unroll
             for (int ct = 0; ct < 2; ++ct)
 #pragma unroll
@@ -286,10 +285,13 @@ __global__ void __launch_bounds__(NT) k_fused3_wsc(uint32_t *rows, const uint32_
                         }
                         x2[ct] = cmul4<TT, H16>(dre, dim, twa[i][ct]);
                     }
+                    // the operand of the imaginary part is made from the other one (the same numbers in another
+                    // arrangement) instead of being kept: 16 registers for a few vector operations per plane
+                    const uint4 tab2_im = TT::imag_operand(tab2[i]);
 #pragma unroll
                     for (int ct = 0; ct < 2; ++ct) {
-                        const f32x4 dre = TT::mfma(tab2[i][0], x2[ct], zero4);
-                        const f32x4 dim = TT::mfma(tab2[i][1], x2[ct], zero4);
+                        const f32x4 dre = TT::mfma(tab2[i], x2[ct], zero4);
+                        const f32x4 dim = TT::mfma(tab2_im, x2[ct], zero4);
                         // lane: k1 = 16 ct + c16; reg r: k2 = 4q + r
                         uint32_t *dst = XB + c * G::PN3 + (16 * ct + c16) * G::PK1 + 4 * q;
                         *(uint4 *)dst = make_uint4(TT::pack(dre[0], dim[0]), TT::pack(dre[1], dim[1]),
